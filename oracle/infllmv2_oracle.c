@@ -1,0 +1,307 @@
+/*
+ * CPU oracle for InfLLM v2 block-sparse attention (MiniCPM4 report, section 2.1).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * HIP library is checked against.  It shares no code with the HIP path, and the
+ * product never calls it: only the tests, the smoke check and the cpu_baseline
+ * leg of the benchmark may load it.
+ *
+ * Everything is fp64 computed from bf16-valued inputs (bf16 bit patterns in
+ * uint16 arrays).  One sequence per call; rows are independent, so the only
+ * parallelism is an OpenMP `parallel for` over query rows.  There is no tiling,
+ * fusion or reordering: each function is the formula written out.
+ *
+ * Notation follows section 2.1: l sequence length, m block size, p / s semantic
+ * kernel size / stride, k number of selected blocks, G = Hq / Hkv query heads per
+ * key-value head, d head dimension.  Positions, blocks and kernels are 0-based.
+ *
+ * Readings taken where the text is silent (each is a definition shared with the
+ * HIP path, none can be pinned to a printed example -- "parity unpinned" for the
+ * readings themselves; the arithmetic of every function below IS pinned by the
+ * CPU tests):
+ *   - only complete semantic kernels exist:  n_c(l) = floor((l-p)/s)+1  (0 if l<p);
+ *   - query i sees kernel jh iff the kernel lies wholly at or before i:
+ *     jh*s + p - 1 <= i, i.e. n_vis(i) = n_c(i+1);
+ *   - the softmax over kernels uses the attention scale;
+ *   - group score = mean over the G heads of the per-head softmax;
+ *   - scores are floored at 2^-100 so that underflow gives deterministic ties;
+ *   - ties go to the lower block index;
+ *   - query i ranks blocks 0..floor(i/m); the last one may be partial;
+ *   - forced blocks: the first n_init blocks and the last n_local blocks up to
+ *     and including the query's own.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_SCORE_FLOOR 7.888609052210118e-31 /* 2^-100 */
+
+/* ---- bf16 helpers -------------------------------------------------------- */
+
+static double bf16_to_f64(uint16_t b) {
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+/* Round an fp64 value straight to bf16 (8 significant bits), ties to even.
+ * Rounding goes directly from fp64 so there is no double rounding through fp32. */
+static uint16_t f64_to_bf16(double x) {
+    float f;
+    uint32_t u;
+    if (isnan(x)) return 0x7fc0;
+    if (x == 0.0 || isinf(x)) {
+        f = (float)x;
+    } else {
+        int e = ilogb(x);
+        if (e < -126) e = -126;              /* subnormal range: fixed quantum   */
+        double q = ldexp(1.0, e - 7);        /* value of the last kept bit        */
+        double r = rint(x / q) * q;          /* rint: round-half-even by default  */
+        f = (float)r;                        /* exact, or overflows to +-inf      */
+    }
+    memcpy(&u, &f, sizeof u);
+    return (uint16_t)(u >> 16);
+}
+
+/* ---- counts -------------------------------------------------------------- */
+
+/* Number of complete semantic kernels in a sequence of l tokens (section 2.1.2,
+ * "Semantic Kernels": windows K[jh*s : jh*s+p]). */
+int32_t oracle_num_kernels(int32_t l, int32_t p, int32_t s) {
+    if (l < p) return 0;
+    return (l - p) / s + 1;
+}
+
+/* ---- O1: mean-pool compression ------------------------------------------- */
+
+/* CK[h, jh, :] = Mean(K[h, jh*s : jh*s+p, :])   (section 2.1.2, the Mean(.) in the
+ * definition of r_kernel).
+ *   k_bits   [Hkv, l, d]  bf16 bit patterns
+ *   ck_f64   [Hkv, n_c, d] unrounded means (may be NULL)
+ *   ck_bits  [Hkv, n_c, d] means rounded to bf16, ties to even (may be NULL)
+ * Returns n_c. */
+int32_t oracle_compress_keys(const uint16_t *k_bits, int32_t Hkv, int32_t l, int32_t d,
+                             int32_t p, int32_t s, double *ck_f64, uint16_t *ck_bits) {
+    int32_t n_c = oracle_num_kernels(l, p, s);
+    for (int32_t h = 0; h < Hkv; ++h)
+        for (int32_t jh = 0; jh < n_c; ++jh)
+            for (int32_t c = 0; c < d; ++c) {
+                double sum = 0.0;
+                for (int32_t t = jh * s; t < jh * s + p; ++t)
+                    sum += bf16_to_f64(k_bits[((size_t)h * l + t) * d + c]);
+                double mean = sum / (double)p;
+                size_t o = ((size_t)h * n_c + jh) * d + c;
+                if (ck_f64) ck_f64[o] = mean;
+                if (ck_bits) ck_bits[o] = f64_to_bf16(mean);
+            }
+    return n_c;
+}
+
+/* ---- O2: kernel relevance for one query row ------------------------------- */
+
+/* r[jh] = (1/G) sum_g softmax_jh(scale * <q_g, CK[jh]>), jh < n_vis, then floored.
+ * (section 2.1.2: r_kernel; "Top-K Blocks Sharing": mean over the group;
+ * "Efficient Top-K Implementation": softmax first, then aggregate.)
+ *   q_row   G consecutive heads of one token, [G, d] bf16 bits
+ *   ck_h    [n_c, d] bf16 bits of this key-value head
+ *   r       [n_vis] out
+ *   z, e    scratch of n_vis doubles each */
+static void kernel_scores_row(const uint16_t *q_row, const uint16_t *ck_h, int32_t G, int32_t d,
+                              int32_t n_vis, double scale, double *r, double *z) {
+    for (int32_t jh = 0; jh < n_vis; ++jh) r[jh] = 0.0;
+    for (int32_t g = 0; g < G; ++g) {
+        double zmax = -INFINITY;
+        for (int32_t jh = 0; jh < n_vis; ++jh) {
+            double dot = 0.0;
+            for (int32_t c = 0; c < d; ++c)
+                dot += bf16_to_f64(q_row[(size_t)g * d + c]) * bf16_to_f64(ck_h[(size_t)jh * d + c]);
+            z[jh] = scale * dot;
+            if (z[jh] > zmax) zmax = z[jh];
+        }
+        double denom = 0.0;
+        for (int32_t jh = 0; jh < n_vis; ++jh) denom += exp(z[jh] - zmax);
+        for (int32_t jh = 0; jh < n_vis; ++jh) r[jh] += exp(z[jh] - zmax) / denom;
+    }
+    for (int32_t jh = 0; jh < n_vis; ++jh) {
+        r[jh] /= (double)G;
+        if (r[jh] < ORACLE_SCORE_FLOOR) r[jh] = ORACLE_SCORE_FLOOR;
+    }
+}
+
+/* Group-mean kernel scores for a list of query rows (for tests and small cases).
+ *   q_bits    [Tq, Hq, d]; row t is the query at position pos[t]
+ *   ck_bits   [Hkv, n_c, d]
+ *   r_out     [Hkv, Tq, n_c] fp64; entries jh >= n_vis(pos[t]) are set to 0 */
+void oracle_kernel_scores(const uint16_t *q_bits, const uint16_t *ck_bits, const int32_t *pos,
+                          int32_t Tq, int32_t Hq, int32_t Hkv, int32_t d, int32_t n_c,
+                          int32_t p, int32_t s, double scale, double *r_out) {
+    int32_t G = Hq / Hkv;
+#pragma omp parallel
+    {
+        double *z = (double *)malloc(sizeof(double) * (size_t)(n_c > 0 ? n_c : 1));
+#pragma omp for schedule(dynamic, 16)
+        for (int32_t t = 0; t < Tq; ++t)
+            for (int32_t h = 0; h < Hkv; ++h) {
+                int32_t n_vis = oracle_num_kernels(pos[t] + 1, p, s);
+                if (n_vis > n_c) n_vis = n_c;
+                double *r = r_out + ((size_t)h * Tq + t) * n_c;
+                for (int32_t jh = 0; jh < n_c; ++jh) r[jh] = 0.0;
+                kernel_scores_row(q_bits + ((size_t)t * Hq + (size_t)h * G) * d,
+                                  ck_bits + (size_t)h * n_c * d, G, d, n_vis, scale, r, z);
+            }
+        free(z);
+    }
+}
+
+/* ---- O3: block relevance and selection ------------------------------------ */
+
+/* Eq. (1): R[j] = max over visible kernels jh whose token span [jh*s, jh*s+p)
+ * intersects the block's span [j*m, (j+1)*m); -inf when no visible kernel does.
+ * The test is the literal interval intersection, not a closed-form window. */
+static void block_scores_row(const double *r, int32_t n_vis, int32_t n_blk, int32_t m, int32_t p,
+                             int32_t s, double *R) {
+    for (int32_t j = 0; j < n_blk; ++j) {
+        double best = -INFINITY;
+        int64_t b_lo = (int64_t)j * m, b_hi = (int64_t)(j + 1) * m;      /* [b_lo, b_hi) */
+        for (int32_t jh = 0; jh < n_vis; ++jh) {
+            int64_t k_lo = (int64_t)jh * s, k_hi = k_lo + p;             /* [k_lo, k_hi) */
+            int intersects = (k_lo < b_hi) && (b_lo < k_hi);
+            if (intersects && r[jh] > best) best = r[jh];
+        }
+        R[j] = best;
+    }
+}
+
+/* Select blocks for a list of query rows of one sequence.
+ *   q_bits     [Tq, Hq, d]; row t is the query at position pos[t]
+ *   ck_bits    [Hkv, n_c, d] compressed keys (bf16) of the sequence
+ *   block_idx  [Hkv, Tq, topk] out: selected block indices ascending, -1 padded
+ *   margins    [Hkv, Tq, 2] out (may be NULL): smallest selected non-forced score and
+ *              largest unselected score (NaN when there is none)
+ *   R_out      [Hkv, Tq, nb_cap] out (may be NULL): block scores after forcing
+ *              (+inf forced, -inf no visible kernel, NaN beyond the query's own block)
+ * Section 2.1.2: "selects the k blocks with the highest relevance"; the initial and the
+ * local-window blocks get score infinity; with at most k blocks everything is selected. */
+void oracle_select_blocks(const uint16_t *q_bits, const uint16_t *ck_bits, const int32_t *pos,
+                          int32_t Tq, int32_t Hq, int32_t Hkv, int32_t d, int32_t n_c,
+                          int32_t m, int32_t p, int32_t s, int32_t topk, int32_t n_init,
+                          int32_t n_local, double scale, int32_t *block_idx, double *margins,
+                          double *R_out, int32_t nb_cap) {
+    int32_t G = Hq / Hkv;
+#pragma omp parallel
+    {
+        int32_t max_blk = 1;
+        for (int32_t t = 0; t < Tq; ++t)
+            if (pos[t] / m + 1 > max_blk) max_blk = pos[t] / m + 1;
+        double *z = (double *)malloc(sizeof(double) * (size_t)(n_c > 0 ? n_c : 1));
+        double *r = (double *)malloc(sizeof(double) * (size_t)(n_c > 0 ? n_c : 1));
+        double *R = (double *)malloc(sizeof(double) * (size_t)max_blk);
+        char *taken = (char *)malloc((size_t)max_blk);
+#pragma omp for schedule(dynamic, 4)
+        for (int32_t t = 0; t < Tq; ++t)
+            for (int32_t h = 0; h < Hkv; ++h) {
+                int32_t i = pos[t];
+                int32_t b_i = i / m;               /* the query's own block          */
+                int32_t n_blk = b_i + 1;           /* candidate blocks 0..b_i        */
+                int32_t n_vis = oracle_num_kernels(i + 1, p, s);
+                if (n_vis > n_c) n_vis = n_c;
+                kernel_scores_row(q_bits + ((size_t)t * Hq + (size_t)h * G) * d,
+                                  ck_bits + (size_t)h * n_c * d, G, d, n_vis, scale, r, z);
+                block_scores_row(r, n_vis, n_blk, m, p, s, R);
+                for (int32_t j = 0; j < n_blk; ++j) {
+                    int forced = (j < n_init) || (j > b_i - n_local);
+                    if (forced) R[j] = INFINITY;
+                    taken[j] = 0;
+                }
+                int32_t n_sel = topk < n_blk ? topk : n_blk;
+                double kth = NAN;                  /* smallest selected unforced score */
+                for (int32_t c = 0; c < n_sel; ++c) {
+                    int32_t best = -1;
+                    for (int32_t j = 0; j < n_blk; ++j)   /* strict > : lower index wins ties */
+                        if (!taken[j] && (best < 0 || R[j] > R[best])) best = j;
+                    taken[best] = 1;
+                    if (R[best] != INFINITY) kth = R[best];
+                }
+                double next = NAN;                 /* largest score left out         */
+                for (int32_t j = 0; j < n_blk; ++j)
+                    if (!taken[j] && (isnan(next) || R[j] > next)) next = R[j];
+                int32_t *out = block_idx + ((size_t)h * Tq + t) * topk;
+                int32_t w = 0;
+                for (int32_t j = 0; j < n_blk; ++j)
+                    if (taken[j]) out[w++] = j;
+                for (; w < topk; ++w) out[w] = -1;
+                if (margins) {
+                    margins[((size_t)h * Tq + t) * 2 + 0] = kth;
+                    margins[((size_t)h * Tq + t) * 2 + 1] = next;
+                }
+                if (R_out) {
+                    double *Ro = R_out + ((size_t)h * Tq + t) * nb_cap;
+                    for (int32_t j = 0; j < nb_cap; ++j) Ro[j] = j < n_blk ? R[j] : NAN;
+                }
+            }
+        free(z); free(r); free(R); free(taken);
+    }
+}
+
+/* ---- O4: attention over the selected blocks -------------------------------- */
+
+/* o_i = sum_{t in T_i} softmax_t(scale * <q_i, k_t>) v_t,  T_i = { t <= i : floor(t/m) in Sel(i) },
+ * LSE_i = log sum_{t in T_i} exp(scale * <q_i, k_t>)      (section 2.1.1, second stage).
+ *   q_bits     [Tq, Hq, d]; row t is the query at position pos[t]
+ *   k_bits, v_bits [Hkv, l, d]
+ *   block_idx  [Hkv, Tq, topk], -1 entries ignored
+ *   out        [Tq, Hq, d] fp64,  lse [Tq, Hq] fp64 (natural log)
+ *   probs_sum  [Tq, Hq] fp64 (may be NULL): sum of the softmax weights, for the row-sum pin */
+void oracle_sparse_attn(const uint16_t *q_bits, const uint16_t *k_bits, const uint16_t *v_bits,
+                        const int32_t *pos, const int32_t *block_idx, int32_t Tq, int32_t Hq,
+                        int32_t Hkv, int32_t d, int32_t l, int32_t m, int32_t topk, double scale,
+                        double *out, double *lse, double *probs_sum) {
+    int32_t G = Hq / Hkv;
+#pragma omp parallel
+    {
+        double *z = (double *)malloc(sizeof(double) * (size_t)topk * m);
+        int32_t *tok = (int32_t *)malloc(sizeof(int32_t) * (size_t)topk * m);
+#pragma omp for schedule(dynamic, 4)
+        for (int32_t t = 0; t < Tq; ++t)
+            for (int32_t hq = 0; hq < Hq; ++hq) {
+                int32_t h = hq / G;
+                int32_t i = pos[t];
+                const uint16_t *q = q_bits + ((size_t)t * Hq + hq) * d;
+                const int32_t *sel = block_idx + ((size_t)h * Tq + t) * topk;
+                int32_t n = 0;
+                for (int32_t c = 0; c < topk; ++c) {
+                    if (sel[c] < 0) continue;
+                    for (int32_t u = sel[c] * m; u < (sel[c] + 1) * m; ++u)
+                        if (u <= i && u < l) tok[n++] = u;      /* causal, inside the cache */
+                }
+                double zmax = -INFINITY;
+                for (int32_t a = 0; a < n; ++a) {
+                    const uint16_t *kr = k_bits + ((size_t)h * l + tok[a]) * d;
+                    double dot = 0.0;
+                    for (int32_t c = 0; c < d; ++c) dot += bf16_to_f64(q[c]) * bf16_to_f64(kr[c]);
+                    z[a] = scale * dot;
+                    if (z[a] > zmax) zmax = z[a];
+                }
+                double denom = 0.0;
+                for (int32_t a = 0; a < n; ++a) denom += exp(z[a] - zmax);
+                double *o = out + ((size_t)t * Hq + hq) * d;
+                for (int32_t c = 0; c < d; ++c) o[c] = 0.0;
+                double wsum = 0.0;
+                for (int32_t a = 0; a < n; ++a) {
+                    double w = exp(z[a] - zmax) / denom;
+                    wsum += w;
+                    const uint16_t *vr = v_bits + ((size_t)h * l + tok[a]) * d;
+                    for (int32_t c = 0; c < d; ++c) o[c] += w * bf16_to_f64(vr[c]);
+                }
+                lse[(size_t)t * Hq + hq] = n > 0 ? zmax + log(denom) : -INFINITY;
+                if (probs_sum) probs_sum[(size_t)t * Hq + hq] = wsum;
+            }
+        free(z); free(tok);
+    }
+}
+
+/* Rounding helper exported for tests of the bf16 conversion itself. */
+uint16_t oracle_f64_to_bf16(double x) { return f64_to_bf16(x); }
+double oracle_bf16_to_f64(uint16_t b) { return bf16_to_f64(b); }

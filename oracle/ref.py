@@ -1,0 +1,171 @@
+"""ctypes wrapper around the C oracle (`infllmv2_oracle.c`).
+
+TEST INFRASTRUCTURE ONLY.  Marshals numpy arrays to the C functions; holds no
+arithmetic of the method.  bf16 tensors are numpy uint16 arrays of bit patterns.
+One sequence per call.
+
+Layouts (C-contiguous):
+  q      [Tq, Hq, d]    row t is the query token at position pos[t]
+  k, v   [Hkv, l, d]
+  ck     [Hkv, n_c, d]
+  block_idx [Hkv, Tq, topk] int32, ascending, -1 padded
+"""
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "infllmv2_oracle.c")
+_LIB = os.path.join(_HERE, "libinfllmv2_oracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile the C oracle with gcc (CPU only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+                               "-ffp-contract=off", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i32, f64, vp = ctypes.c_int32, ctypes.c_double, ctypes.c_void_p
+        lib.oracle_num_kernels.restype = i32
+        lib.oracle_num_kernels.argtypes = [i32, i32, i32]
+        lib.oracle_compress_keys.restype = i32
+        lib.oracle_compress_keys.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
+        lib.oracle_kernel_scores.restype = None
+        lib.oracle_kernel_scores.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, f64, vp]
+        lib.oracle_select_blocks.restype = None
+        lib.oracle_select_blocks.argtypes = [vp, vp, vp] + [i32] * 11 + [f64, vp, vp, vp, i32]
+        lib.oracle_sparse_attn.restype = None
+        lib.oracle_sparse_attn.argtypes = [vp, vp, vp, vp, vp] + [i32] * 7 + [f64, vp, vp, vp]
+        lib.oracle_f64_to_bf16.restype = ctypes.c_uint16
+        lib.oracle_f64_to_bf16.argtypes = [f64]
+        lib.oracle_bf16_to_f64.restype = f64
+        lib.oracle_bf16_to_f64.argtypes = [ctypes.c_uint16]
+        _lib = lib
+    return _lib
+
+
+@dataclass
+class Params:
+    """Hyper-parameters of section 2.1 (names follow the paper: m, p, s, k)."""
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int = 128
+    block_size: int = 64        # m
+    kernel_size: int = 32       # p
+    kernel_stride: int = 16     # s
+    topk: int = 16              # k, total blocks per query including the forced ones
+    n_init_blocks: int = 1
+    n_local_blocks: int = 2
+    softmax_scale: float = None
+
+    def __post_init__(self):
+        if self.softmax_scale is None:
+            self.softmax_scale = float(self.head_dim) ** -0.5
+
+
+def _u16(a, shape=None):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16, a.dtype
+    if shape is not None:
+        assert a.shape == tuple(shape), (a.shape, shape)
+    return a
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def num_kernels(l, p, s):
+    return int(_load().oracle_num_kernels(int(l), int(p), int(s)))
+
+
+def f64_to_bf16(x):
+    return int(_load().oracle_f64_to_bf16(float(x)))
+
+
+def bf16_to_f64(b):
+    return float(_load().oracle_bf16_to_f64(int(b)))
+
+
+def compress_keys(k, prm):
+    """k uint16 [Hkv, l, d] -> (ck_f64 [Hkv, n_c, d], ck_bf16 uint16 [Hkv, n_c, d])."""
+    lib = _load()
+    k = _u16(k)
+    Hkv, l, d = k.shape
+    n_c = num_kernels(l, prm.kernel_size, prm.kernel_stride)
+    ck64 = np.zeros((Hkv, n_c, d), np.float64)
+    ckb = np.zeros((Hkv, n_c, d), np.uint16)
+    got = lib.oracle_compress_keys(_ptr(k), Hkv, l, d, prm.kernel_size, prm.kernel_stride,
+                                   _ptr(ck64), _ptr(ckb))
+    assert got == n_c
+    return ck64, ckb
+
+
+def kernel_scores(q, ck, pos, prm):
+    """Group-mean kernel scores r [Hkv, Tq, n_c] (0 beyond the visible kernels)."""
+    lib = _load()
+    q = _u16(q)
+    ck = _u16(ck)
+    pos = np.ascontiguousarray(pos, np.int32)
+    Tq, Hq, d = q.shape
+    Hkv, n_c, _ = ck.shape
+    assert Hq == prm.n_q_heads and Hkv == prm.n_kv_heads and pos.shape == (Tq,)
+    r = np.zeros((Hkv, Tq, n_c), np.float64)
+    lib.oracle_kernel_scores(_ptr(q), _ptr(ck), _ptr(pos), Tq, Hq, Hkv, d, n_c,
+                             prm.kernel_size, prm.kernel_stride, float(prm.softmax_scale), _ptr(r))
+    return r
+
+
+def select_blocks(q, ck, pos, prm, want_scores=False):
+    """-> block_idx int32 [Hkv, Tq, topk], margins fp64 [Hkv, Tq, 2] (, R [Hkv, Tq, nb])."""
+    lib = _load()
+    q = _u16(q)
+    ck = _u16(ck)
+    pos = np.ascontiguousarray(pos, np.int32)
+    Tq, Hq, d = q.shape
+    Hkv, n_c, _ = ck.shape
+    assert Hq == prm.n_q_heads and Hkv == prm.n_kv_heads and pos.shape == (Tq,)
+    idx = np.full((Hkv, Tq, prm.topk), -1, np.int32)
+    margins = np.zeros((Hkv, Tq, 2), np.float64)
+    nb_cap = int(pos.max()) // prm.block_size + 1 if Tq else 1
+    R = np.zeros((Hkv, Tq, nb_cap), np.float64) if want_scores else None
+    lib.oracle_select_blocks(_ptr(q), _ptr(ck), _ptr(pos), Tq, Hq, Hkv, d, n_c,
+                             prm.block_size, prm.kernel_size, prm.kernel_stride, prm.topk,
+                             prm.n_init_blocks, prm.n_local_blocks, float(prm.softmax_scale),
+                             _ptr(idx), _ptr(margins), _ptr(R), nb_cap)
+    return (idx, margins, R) if want_scores else (idx, margins)
+
+
+def sparse_attn(q, k, v, pos, block_idx, prm, want_probs_sum=False):
+    """-> out fp64 [Tq, Hq, d], lse fp64 [Tq, Hq] (, probs_sum [Tq, Hq])."""
+    lib = _load()
+    q = _u16(q)
+    k = _u16(k)
+    v = _u16(v)
+    pos = np.ascontiguousarray(pos, np.int32)
+    block_idx = np.ascontiguousarray(block_idx, np.int32)
+    Tq, Hq, d = q.shape
+    Hkv, l, _ = k.shape
+    assert v.shape == k.shape and pos.shape == (Tq,)
+    topk = block_idx.shape[-1]
+    assert block_idx.shape == (Hkv, Tq, topk)
+    out = np.zeros((Tq, Hq, d), np.float64)
+    lse = np.zeros((Tq, Hq), np.float64)
+    ps = np.zeros((Tq, Hq), np.float64) if want_probs_sum else None
+    lib.oracle_sparse_attn(_ptr(q), _ptr(k), _ptr(v), _ptr(pos), _ptr(block_idx), Tq, Hq, Hkv, d,
+                           l, prm.block_size, topk, float(prm.softmax_scale),
+                           _ptr(out), _ptr(lse), _ptr(ps))
+    return (out, lse, ps) if want_probs_sum else (out, lse)

@@ -1,0 +1,193 @@
+/*
+ * infllmv2.h -- C ABI of the MI355X (gfx950) implementation of InfLLM v2
+ * trainable block-sparse attention (MiniCPM4 report, section 2.1).
+ *
+ * The path has three stages (section 2.1.1, "two stages" plus the compression the
+ * first one needs):
+ *   1. infllmv2_compress_keys       mean-pool the keys into overlapping semantic kernels
+ *   2. infllmv2_select_blocks       relevance of every key-value block to each query token,
+ *                                   shared by the query heads of a group; top-k blocks plus
+ *                                   the always-selected initial and local-window blocks
+ *   3. infllmv2_sparse_attn_prefill / infllmv2_sparse_attn_decode
+ *                                   exact softmax attention over the selected blocks only
+ * plus infllmv2_append_kv, the cache append that opens a decode step.
+ *
+ * Conventions for every entry point
+ *   - Returns 0 (INFLLMV2_OK) or a negative INFLLMV2_ERR_* code; never throws, never
+ *     allocates or frees device memory, never synchronises the stream.  Arguments are
+ *     validated on the host before the first HIP call; on a validation error nothing
+ *     is launched.
+ *   - Every data pointer is a DEVICE pointer owned by the caller; `prm` and the tensor
+ *     descriptors are HOST structs read during the call only.  `stream` is a hipStream_t
+ *     passed as void* (NULL = the default stream).  Work is enqueued on that stream.
+ *   - bf16 tensors are described by infllmv2_tensor: strides are in ELEMENTS, the
+ *     head_dim axis is contiguous (stride 1) and every row must be 16-byte aligned
+ *     (pointer and strides multiples of 8 elements).
+ *       key / value cache, compressed keys:  element (b, h, t, c) at
+ *           ptr + b*stride_b + h*stride_h + t*stride_t + c        h = key-value head
+ *       queries, outputs:                    element (b, t, hq, c) at
+ *           ptr + b*stride_b + t*stride_t + hq*stride_h + c       hq = query head
+ *     Query head hq belongs to key-value head hq / G, G = n_q_heads / n_kv_heads.
+ *   - `seqlens` is a device int32 [batch] array: the number of valid cache rows of each
+ *     sequence.  `max_seqlen` is a host upper bound on its entries, used to size
+ *     launches and buffers; entries above it are clamped to it.
+ *   - Positions, blocks and semantic kernels are 0-based.  With m = block_size,
+ *     p = kernel_size, s = kernel_stride:
+ *       a sequence of l tokens has n_c(l) = floor((l-p)/s)+1 complete kernels (0 if l<p);
+ *       query position i ranks blocks 0..floor(i/m) and sees kernels jh < n_c(i+1).
+ *   - Supported shapes: head_dim 128, block_size 64, kernel_size 32, kernel_stride 16,
+ *     G in {1,2,4,8,16}, topk in [max(1, n_init_blocks + n_local_blocks), 64].  Anything
+ *     else returns INFLLMV2_ERR_UNSUPPORTED.
+ *   - Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef INFLLMV2_H
+#define INFLLMV2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define INFLLMV2_OK 0
+#define INFLLMV2_ERR_INVALID_ARGUMENT (-1) /* null pointer, bad size, bad stride or alignment  */
+#define INFLLMV2_ERR_UNSUPPORTED (-2)      /* a shape outside the supported set above           */
+#define INFLLMV2_ERR_WORKSPACE (-3)        /* workspace missing or smaller than the size query */
+#define INFLLMV2_ERR_HIP (-4)              /* a HIP launch reported an error                   */
+
+/* Stage selector for infllmv2_workspace_bytes. */
+#define INFLLMV2_OP_SELECT_PREFILL 1
+#define INFLLMV2_OP_SELECT_DECODE 2
+#define INFLLMV2_OP_ATTN_PREFILL 3
+#define INFLLMV2_OP_ATTN_DECODE 4
+
+/* Query layout selector for infllmv2_select_blocks. */
+#define INFLLMV2_MODE_PREFILL 0 /* one query per cached token: query t sits at position t        */
+#define INFLLMV2_MODE_DECODE 1  /* one query per sequence, at position seqlens[b]-1              */
+
+/* Hyper-parameters of section 2.1 ("Hyper-Parameter Recommendation": p = 32, s = 16). */
+typedef struct infllmv2_params {
+    int32_t head_dim;        /* d, 128                                                         */
+    int32_t n_q_heads;       /* Hq                                                             */
+    int32_t n_kv_heads;      /* Hkv                                                            */
+    int32_t block_size;      /* m, tokens per key-value block, 64                              */
+    int32_t kernel_size;     /* p, tokens per semantic kernel, 32                              */
+    int32_t kernel_stride;   /* s, stride between semantic kernels, 16                         */
+    int32_t topk;            /* k, blocks attended per query token INCLUDING the forced ones   */
+    int32_t n_init_blocks;   /* leading blocks whose relevance is set to infinity              */
+    int32_t n_local_blocks;  /* trailing blocks (the query's own and the ones before it) forced */
+    float softmax_scale;     /* multiplies q.k in both the relevance softmax and the attention */
+} infllmv2_params;
+
+/* A bf16 device tensor with a contiguous head_dim axis; strides in elements (see above). */
+typedef struct infllmv2_tensor {
+    void *ptr;
+    int64_t stride_b;
+    int64_t stride_h;
+    int64_t stride_t;
+} infllmv2_tensor;
+
+/* Human-readable name of a status code (static storage). */
+const char *infllmv2_status_string(int32_t status);
+
+/* Bytes of device scratch the given stage needs for `batch` sequences of at most `max_seqlen`
+ * cached tokens (0 if the stage needs none, or if the arguments are invalid). */
+size_t infllmv2_workspace_bytes(int32_t op, const infllmv2_params *prm, int32_t batch,
+                                int32_t max_seqlen);
+
+/*
+ * Stage 1 -- semantic-kernel representations (section 2.1.2, "Semantic Kernels"):
+ *     ck[b, h, jh, :] = Mean(k[b, h, jh*s : jh*s+p, :]),   jh < n_c(seqlens[b]),
+ * accumulated in fp64 in token order and rounded once to bf16 (ties to even).
+ *   k             in   bf16 cache [batch, Hkv, >=max_seqlen, d]
+ *   ck            out  bf16 [batch, Hkv, >=n_c(max_seqlen), d]; stride_t is the kernel stride
+ *   n_new_tokens  <= 0: write every kernel of every sequence.
+ *                 >  0: incremental update -- write only the kernels completed by the last
+ *                       n_new_tokens tokens, i.e. jh in [n_c(seqlens[b]-n_new_tokens), n_c(seqlens[b]));
+ *                       rows written earlier are left untouched, so after any sequence of
+ *                       appends ck equals the from-scratch result bit for bit.
+ * Rows jh >= n_c(seqlens[b]) are never written.
+ */
+int32_t infllmv2_compress_keys(const infllmv2_params *prm, const infllmv2_tensor *k,
+                               const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
+                               int32_t n_new_tokens, const infllmv2_tensor *ck, void *stream);
+
+/*
+ * Stage 2 -- block selection (section 2.1.2, "Dynamic Contextual Block Selection", Eq. 1,
+ * "Top-K Blocks Sharing", "Efficient Top-K Implementation").  For every key-value head h and
+ * query token at position i:
+ *     z_g[jh] = softmax_scale * <q_g, ck[h, jh]>              g in the group of h, jh < n_c(i+1)
+ *     r[jh]   = max( mean_g softmax_jh(z_g)[jh], 2^-100 )     (softmax first, then the group mean)
+ *     R[j]    = max of r[jh] over kernels whose tokens intersect block j,   j <= floor(i/m)
+ *     R[j]    = +inf for j < n_init_blocks and for j > floor(i/m) - n_local_blocks
+ *     select the min(topk, floor(i/m)+1) blocks of largest R, ties to the lower index.
+ * The softmax is computed exactly in two passes (log-sum-exp first, scores second).
+ *   mode       INFLLMV2_MODE_PREFILL: q is [batch, max_seqlen, Hq, d], row t = position t,
+ *              rows t >= seqlens[b] are ignored; n_q = max_seqlen rows per sequence.
+ *              INFLLMV2_MODE_DECODE: q is [batch, 1, Hq, d], position seqlens[b]-1; n_q = 1.
+ *   ck         in   compressed keys with at least n_c(seqlens[b]) valid rows per sequence
+ *   block_idx  out  int32 [batch, Hkv, n_q, topk] contiguous: selected block indices in
+ *              ascending order, padded with -1.  Prefill rows t >= seqlens[b] are not written.
+ *   workspace  device scratch of infllmv2_workspace_bytes(INFLLMV2_OP_SELECT_*, ...) bytes,
+ *              256-byte aligned; contents are undefined before and after the call.
+ */
+int32_t infllmv2_select_blocks(const infllmv2_params *prm, int32_t mode, const infllmv2_tensor *q,
+                               const infllmv2_tensor *ck, const int32_t *seqlens, int32_t batch,
+                               int32_t max_seqlen, int32_t *block_idx, void *workspace,
+                               size_t workspace_bytes, void *stream);
+
+/*
+ * Stage 3, prefill -- attention over the selected blocks (section 2.1.1, second stage):
+ *     T_i = { t <= i : floor(t/m) in block_idx[b, h, i, :] }
+ *     out[b, i, hq, :] = sum_{t in T_i} softmax_t(softmax_scale * <q_i, k_t>) v_t
+ *     lse[b, i, hq]    = log sum_{t in T_i} exp(softmax_scale * <q_i, k_t>)      (natural log)
+ * bf16 products accumulated in fp32; probabilities are rounded to bf16 before the value
+ * product, their fp32 sum is taken before rounding.
+ *   q, out     [batch, max_seqlen, Hq, d] bf16 (rows t >= seqlens[b] ignored / not written)
+ *   k, v       bf16 caches [batch, Hkv, >=max_seqlen, d]
+ *   block_idx  in   int32 [batch, Hkv, max_seqlen, topk]; entries < 0 or > floor(i/m) are skipped;
+ *              each row must be duplicate-free
+ *   lse        out  fp32 [batch, max_seqlen, Hq] contiguous
+ *   workspace  may be NULL when infllmv2_workspace_bytes(INFLLMV2_OP_ATTN_PREFILL, ...) is 0
+ */
+int32_t infllmv2_sparse_attn_prefill(const infllmv2_params *prm, const infllmv2_tensor *q,
+                                     const infllmv2_tensor *k, const infllmv2_tensor *v,
+                                     const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
+                                     const int32_t *block_idx, const infllmv2_tensor *out,
+                                     float *lse, void *workspace, size_t workspace_bytes,
+                                     void *stream);
+
+/*
+ * Stage 3, decode -- the same attention for the single query at position seqlens[b]-1
+ * (section 2.1.3, "Different Granularity for Query and Key-Value Tokens": token-level
+ * queries are what makes the method usable in decoding).
+ *   q, out     [batch, 1, Hq, d] bf16
+ *   k, v       bf16 caches [batch, Hkv, >=max_seqlen, d]
+ *   block_idx  in   int32 [batch, Hkv, 1, topk]
+ *   lse        out  fp32 [batch, Hq]
+ *   workspace  device scratch of infllmv2_workspace_bytes(INFLLMV2_OP_ATTN_DECODE, ...) bytes
+ */
+int32_t infllmv2_sparse_attn_decode(const infllmv2_params *prm, const infllmv2_tensor *q,
+                                    const infllmv2_tensor *k, const infllmv2_tensor *v,
+                                    const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
+                                    const int32_t *block_idx, const infllmv2_tensor *out,
+                                    float *lse, void *workspace, size_t workspace_bytes,
+                                    void *stream);
+
+/*
+ * Decode-step cache append: writes the new token's key and value rows at position
+ * seqlens[b]-1 of each sequence's cache (seqlens already counts the new token).
+ *   k_new, v_new  in   bf16 [batch, Hkv, 1, d]  (stride_t unused)
+ *   k, v          out  bf16 caches [batch, Hkv, >=max_seqlen, d]
+ * Sequences with seqlens[b] < 1 are skipped.
+ */
+int32_t infllmv2_append_kv(const infllmv2_params *prm, const infllmv2_tensor *k_new,
+                           const infllmv2_tensor *v_new, const infllmv2_tensor *k,
+                           const infllmv2_tensor *v, const int32_t *seqlens, int32_t batch,
+                           int32_t max_seqlen, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INFLLMV2_H */

@@ -1,0 +1,231 @@
+"""Thin Python binding over the C ABI declared in include/infllmv2.h.
+
+Argument marshalling only: every function here has the name of the C entry point it calls
+(minus the `infllmv2_` prefix), turns torch tensors into pointers + element strides, and
+passes the current torch stream.  torch is used for device memory and streams, nothing else.
+A missing library is an error: there is no fallback path.
+
+Tensor layouts (bf16, CUDA/HIP device, head_dim contiguous):
+  caches k, v, ck   [B, Hkv, T, d]
+  queries, outputs  [B, T, Hq, d]   (decode: T = 1)
+  seqlens           int32 [B]
+  block_idx         int32 [B, Hkv, Tq, topk]
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libinfllmv2.so")
+
+OK = 0
+OP_SELECT_PREFILL, OP_SELECT_DECODE, OP_ATTN_PREFILL, OP_ATTN_DECODE = 1, 2, 3, 4
+MODE_PREFILL, MODE_DECODE = 0, 1
+
+EXPORTS = ["infllmv2_status_string", "infllmv2_workspace_bytes", "infllmv2_compress_keys",
+           "infllmv2_select_blocks", "infllmv2_sparse_attn_prefill", "infllmv2_sparse_attn_decode",
+           "infllmv2_append_kv"]
+
+
+class CParams(ctypes.Structure):
+    _fields_ = [("head_dim", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("block_size", ctypes.c_int32),
+                ("kernel_size", ctypes.c_int32), ("kernel_stride", ctypes.c_int32),
+                ("topk", ctypes.c_int32), ("n_init_blocks", ctypes.c_int32),
+                ("n_local_blocks", ctypes.c_int32), ("softmax_scale", ctypes.c_float)]
+
+
+class CTensor(ctypes.Structure):
+    _fields_ = [("ptr", ctypes.c_void_p), ("stride_b", ctypes.c_int64),
+                ("stride_h", ctypes.c_int64), ("stride_t", ctypes.c_int64)]
+
+
+@dataclass
+class Params:
+    """Hyper-parameters of section 2.1 (m = block_size, p = kernel_size, s = kernel_stride, k = topk)."""
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int = 128
+    block_size: int = 64
+    kernel_size: int = 32
+    kernel_stride: int = 16
+    topk: int = 16
+    n_init_blocks: int = 1
+    n_local_blocks: int = 2
+    softmax_scale: float = None
+
+    def __post_init__(self):
+        if self.softmax_scale is None:
+            self.softmax_scale = float(self.head_dim) ** -0.5
+
+    def c(self):
+        return CParams(self.head_dim, self.n_q_heads, self.n_kv_heads, self.block_size,
+                       self.kernel_size, self.kernel_stride, self.topk, self.n_init_blocks,
+                       self.n_local_blocks, self.softmax_scale)
+
+
+class InfLLMv2Error(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def load_library(path=None):
+    """Load libinfllmv2.so (built by paper_2506_07900_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise InfLLMv2Error("HIP library not built: %s is missing (run python -m paper_2506_07900_amd.build)" % path)
+    lib = ctypes.CDLL(path)
+    i32, vp, sz = ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
+    P, T = ctypes.POINTER(CParams), ctypes.POINTER(CTensor)
+    lib.infllmv2_status_string.restype = ctypes.c_char_p
+    lib.infllmv2_status_string.argtypes = [i32]
+    lib.infllmv2_workspace_bytes.restype = sz
+    lib.infllmv2_workspace_bytes.argtypes = [i32, P, i32, i32]
+    lib.infllmv2_compress_keys.restype = i32
+    lib.infllmv2_compress_keys.argtypes = [P, T, vp, i32, i32, i32, T, vp]
+    lib.infllmv2_select_blocks.restype = i32
+    lib.infllmv2_select_blocks.argtypes = [P, i32, T, T, vp, i32, i32, vp, vp, sz, vp]
+    lib.infllmv2_sparse_attn_prefill.restype = i32
+    lib.infllmv2_sparse_attn_prefill.argtypes = [P, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
+    lib.infllmv2_sparse_attn_decode.restype = i32
+    lib.infllmv2_sparse_attn_decode.argtypes = [P, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
+    lib.infllmv2_append_kv.restype = i32
+    lib.infllmv2_append_kv.argtypes = [P, T, T, T, T, vp, i32, i32, vp]
+    _lib = lib
+    return lib
+
+
+def status_string(status):
+    return load_library().infllmv2_status_string(int(status)).decode()
+
+
+def _check(status, what):
+    if status != OK:
+        raise InfLLMv2Error("%s failed: %s (%d)" % (what, status_string(status), status))
+
+
+def _bf16(t, ndim, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.bfloat16 and t.dim() == ndim):
+        raise InfLLMv2Error("%s must be a %d-d bf16 device tensor" % (name, ndim))
+    if t.stride(-1) != 1:
+        raise InfLLMv2Error("%s: head_dim axis must be contiguous" % name)
+    return t
+
+
+def _cache_desc(t, name):       # [B, Hkv, T, d]
+    _bf16(t, 4, name)
+    return CTensor(t.data_ptr(), t.stride(0), t.stride(1), t.stride(2))
+
+
+def _query_desc(t, name):       # [B, T, Hq, d]
+    _bf16(t, 4, name)
+    return CTensor(t.data_ptr(), t.stride(0), t.stride(2), t.stride(1))
+
+
+def _i32(t, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+        raise InfLLMv2Error("%s must be a contiguous int32 device tensor" % name)
+    return t
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def num_kernels(seqlen, prm):
+    """n_c(l): complete semantic kernels of a sequence of l tokens."""
+    return 0 if seqlen < prm.kernel_size else (seqlen - prm.kernel_size) // prm.kernel_stride + 1
+
+
+def workspace_bytes(op, prm, batch, max_seqlen):
+    return int(load_library().infllmv2_workspace_bytes(op, ctypes.byref(prm.c()), batch, max_seqlen))
+
+
+def _workspace(op, prm, batch, max_seqlen, workspace, device):
+    need = workspace_bytes(op, prm, batch, max_seqlen)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def compress_keys(prm, k, seqlens, max_seqlen, ck=None, n_new_tokens=0):
+    """k [B, Hkv, T, d] -> ck [B, Hkv, n_c(max_seqlen) (or more), d] (allocated if not given)."""
+    lib = load_library()
+    B, Hkv = k.shape[0], k.shape[1]
+    if ck is None:
+        ck = torch.zeros((B, Hkv, max(num_kernels(max_seqlen, prm), 1), k.shape[3]),
+                         dtype=torch.bfloat16, device=k.device)
+    kd, cd = _cache_desc(k, "k"), _cache_desc(ck, "ck")
+    _check(lib.infllmv2_compress_keys(ctypes.byref(prm.c()), ctypes.byref(kd), _i32(seqlens, "seqlens").data_ptr(),
+                                      B, max_seqlen, n_new_tokens, ctypes.byref(cd), _stream()),
+           "infllmv2_compress_keys")
+    return ck
+
+
+def append_kv(prm, k_new, v_new, k, v, seqlens, max_seqlen):
+    """k_new, v_new [B, Hkv, 1, d] are written at cache position seqlens[b]-1."""
+    lib = load_library()
+    d = [_cache_desc(k_new, "k_new"), _cache_desc(v_new, "v_new"), _cache_desc(k, "k"), _cache_desc(v, "v")]
+    _check(lib.infllmv2_append_kv(ctypes.byref(prm.c()), ctypes.byref(d[0]), ctypes.byref(d[1]),
+                                  ctypes.byref(d[2]), ctypes.byref(d[3]), _i32(seqlens, "seqlens").data_ptr(),
+                                  k.shape[0], max_seqlen, _stream()), "infllmv2_append_kv")
+
+
+def select_blocks(prm, mode, q, ck, seqlens, max_seqlen, block_idx=None, workspace=None):
+    """-> block_idx int32 [B, Hkv, Tq, topk] (Tq = max_seqlen in prefill, 1 in decode)."""
+    lib = load_library()
+    B = q.shape[0]
+    n_q = max_seqlen if mode == MODE_PREFILL else 1
+    if block_idx is None:
+        block_idx = torch.full((B, prm.n_kv_heads, n_q, prm.topk), -1, dtype=torch.int32, device=q.device)
+    op = OP_SELECT_PREFILL if mode == MODE_PREFILL else OP_SELECT_DECODE
+    workspace, ws_bytes = _workspace(op, prm, B, max_seqlen, workspace, q.device)
+    qd, cd = _query_desc(q, "q"), _cache_desc(ck, "ck")
+    _check(lib.infllmv2_select_blocks(ctypes.byref(prm.c()), mode, ctypes.byref(qd), ctypes.byref(cd),
+                                      _i32(seqlens, "seqlens").data_ptr(), B, max_seqlen,
+                                      _i32(block_idx, "block_idx").data_ptr(), workspace.data_ptr(),
+                                      ws_bytes, _stream()), "infllmv2_select_blocks")
+    return block_idx
+
+
+def sparse_attn_prefill(prm, q, k, v, seqlens, max_seqlen, block_idx, out=None, lse=None, workspace=None):
+    """-> out bf16 [B, T, Hq, d], lse fp32 [B, T, Hq]."""
+    lib = load_library()
+    B = q.shape[0]
+    if out is None:
+        out = torch.zeros_like(q)
+    if lse is None:
+        lse = torch.zeros((B, max_seqlen, prm.n_q_heads), dtype=torch.float32, device=q.device)
+    workspace, ws_bytes = _workspace(OP_ATTN_PREFILL, prm, B, max_seqlen, workspace, q.device)
+    d = [_query_desc(q, "q"), _cache_desc(k, "k"), _cache_desc(v, "v"), _query_desc(out, "out")]
+    _check(lib.infllmv2_sparse_attn_prefill(ctypes.byref(prm.c()), ctypes.byref(d[0]), ctypes.byref(d[1]),
+                                            ctypes.byref(d[2]), _i32(seqlens, "seqlens").data_ptr(), B,
+                                            max_seqlen, _i32(block_idx, "block_idx").data_ptr(),
+                                            ctypes.byref(d[3]), lse.data_ptr(), workspace.data_ptr(),
+                                            ws_bytes, _stream()), "infllmv2_sparse_attn_prefill")
+    return out, lse
+
+
+def sparse_attn_decode(prm, q, k, v, seqlens, max_seqlen, block_idx, out=None, lse=None, workspace=None):
+    """q [B, 1, Hq, d] -> out bf16 [B, 1, Hq, d], lse fp32 [B, Hq]."""
+    lib = load_library()
+    B = q.shape[0]
+    if out is None:
+        out = torch.zeros_like(q)
+    if lse is None:
+        lse = torch.zeros((B, prm.n_q_heads), dtype=torch.float32, device=q.device)
+    workspace, ws_bytes = _workspace(OP_ATTN_DECODE, prm, B, max_seqlen, workspace, q.device)
+    d = [_query_desc(q, "q"), _cache_desc(k, "k"), _cache_desc(v, "v"), _query_desc(out, "out")]
+    _check(lib.infllmv2_sparse_attn_decode(ctypes.byref(prm.c()), ctypes.byref(d[0]), ctypes.byref(d[1]),
+                                           ctypes.byref(d[2]), _i32(seqlens, "seqlens").data_ptr(), B,
+                                           max_seqlen, _i32(block_idx, "block_idx").data_ptr(),
+                                           ctypes.byref(d[3]), lse.data_ptr(), workspace.data_ptr(),
+                                           ws_bytes, _stream()), "infllmv2_sparse_attn_decode")
+    return out, lse

@@ -1,0 +1,92 @@
+// Device-side helpers shared by the HIP kernels (gfx950 / CDNA4 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/infllmv2.h"
+
+namespace infllmv2 {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Geometry the kernels are specialised for ("Hyper-Parameter Recommendation": p=32, s=16; m=64).
+constexpr int kHeadDim = 128;
+constexpr int kBlock = 64;    // m
+constexpr int kKernel = 32;   // p
+constexpr int kStride = 16;   // s
+constexpr int kMaxTopk = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kScoreFloor = 7.888609052210118e-31f;  // 2^-100, floor of a relevance score
+
+// Host+device view of the call: everything a kernel needs besides its own buffers.
+struct Dims {
+    int32_t Hq, Hkv, G;
+    int32_t topk, n_init, n_local;
+    int32_t batch, max_seqlen;
+    float scale_log2;   // softmax_scale * log2(e)
+};
+
+struct Tensor {          // strides in elements
+    __bf16 *ptr;
+    int64_t sb, sh, st;
+};
+
+// Number of complete semantic kernels of a sequence of l tokens (p=32, s=16).
+__host__ __device__ inline int32_t num_kernels(int32_t l) {
+    return l < kKernel ? 0 : (l - kKernel) / kStride + 1;
+}
+
+// 16x16x32 bf16 MFMA, D = A*B + C.
+//   A is 16(M) x 32(K): lane l holds row l%16, k = 8*(l/16) .. 8*(l/16)+7
+//   B is 32(K) x 16(N): lane l holds column l%16, same k range
+//   C/D is 16 x 16:     lane l holds column l%16, rows 4*(l/16) .. 4*(l/16)+3
+__device__ inline f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ inline bf16x8 load8(const __bf16 *p) {
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(p));
+}
+
+__device__ inline bf16x8 zero8() {
+    uint4 z = {0u, 0u, 0u, 0u};
+    return __builtin_bit_cast(bf16x8, z);
+}
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ inline float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// Reduce over the four 16-lane groups of a wavefront (lanes l, l^16, l^32, l^48).
+__device__ inline float xgroup_max(float v) {
+    v = fmaxf(v, __shfl_xor(v, 16));
+    v = fmaxf(v, __shfl_xor(v, 32));
+    return v;
+}
+__device__ inline float xgroup_sum(float v) {
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+
+// Launchers implemented in the .hip files; each returns a hipError_t as int.
+int launch_compress_keys(const Dims &dm, Tensor k, Tensor ck, const int32_t *seqlens,
+                         int32_t n_new_tokens, hipStream_t stream);
+int launch_append_kv(const Dims &dm, Tensor k_new, Tensor v_new, Tensor k, Tensor v,
+                     const int32_t *seqlens, hipStream_t stream);
+int launch_select_prefill(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
+                          int32_t *block_idx, void *ws, hipStream_t stream);
+size_t select_prefill_ws_bytes(const Dims &dm);
+int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
+                         int32_t *block_idx, void *ws, hipStream_t stream);
+size_t select_decode_ws_bytes(const Dims &dm);
+int launch_attn_prefill(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32_t *seqlens,
+                        const int32_t *block_idx, Tensor out, float *lse, hipStream_t stream);
+int launch_attn_decode(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32_t *seqlens,
+                       const int32_t *block_idx, Tensor out, float *lse, void *ws,
+                       hipStream_t stream);
+size_t attn_decode_ws_bytes(const Dims &dm);
+
+}  // namespace infllmv2

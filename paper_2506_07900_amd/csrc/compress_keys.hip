@@ -1,0 +1,100 @@
+// Stage 1: mean-pool compression of the key cache into semantic-kernel representations
+// (section 2.1.2, "Semantic Kernels": S_jh = K[jh*s : jh*s+p], representation Mean(S_jh)),
+// and the decode-step cache append.  Both are pure HBM traffic: 16-byte coalesced rows.
+#include "common.h"
+
+namespace infllmv2 {
+
+// fp64 -> bf16, round to nearest even with a single rounding: first round-to-odd to fp32
+// (24 bits keep a sticky bit), then nearest-even to 8 bits.
+__device__ inline uint16_t f64_to_bf16_rne(double x) {
+    float f = (float)x;
+    uint32_t u = __float_as_uint(f);
+    double fd = (double)f;
+    if (fd != x) {
+        if (fabs(fd) > fabs(x)) u -= 1u;   // back to the truncated magnitude
+        u |= 1u;                           // inexact: make the last bit odd
+    }
+    uint32_t r = u + 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(r >> 16);
+}
+
+// One thread = 8 channels of one semantic kernel; 16 threads cover a 128-wide row, so a
+// 256-thread workgroup produces 16 kernels.  The sum runs in fp64 in token order: for bf16
+// inputs it is exact, so the result is the correctly rounded mean.
+__global__ __launch_bounds__(256) void compress_keys_kernel(Dims dm, Tensor k, Tensor ck,
+                                                             const int32_t *__restrict__ seqlens,
+                                                             int32_t n_new_tokens) {
+    const int b = blockIdx.z, h = blockIdx.y;
+    int32_t L = seqlens[b];
+    L = L < 0 ? 0 : (L > dm.max_seqlen ? dm.max_seqlen : L);
+    const int32_t n_c = num_kernels(L);
+    int32_t first = 0;
+    if (n_new_tokens > 0) first = num_kernels(L - n_new_tokens > 0 ? L - n_new_tokens : 0);
+    const int c = (threadIdx.x & 15) * 8;
+    const __bf16 *kb = k.ptr + b * k.sb + h * k.sh + c;
+    __bf16 *ob = ck.ptr + b * ck.sb + h * ck.sh + c;
+    for (int32_t jh = first + blockIdx.x * 16 + (threadIdx.x >> 4); jh < n_c; jh += gridDim.x * 16) {
+        double acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.0;
+        const __bf16 *row = kb + (int64_t)jh * kStride * k.st;
+#pragma unroll 8
+        for (int t = 0; t < kKernel; ++t) {
+            bf16x8 x = load8(row + (int64_t)t * k.st);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += (double)(float)x[e];
+        }
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint32_t lo = f64_to_bf16_rne(acc[2 * e] / (double)kKernel);
+            uint32_t hi = f64_to_bf16_rne(acc[2 * e + 1] / (double)kKernel);
+            w[e] = lo | (hi << 16);
+        }
+        uint4 o = {w[0], w[1], w[2], w[3]};
+        *reinterpret_cast<uint4 *>(ob + (int64_t)jh * ck.st) = o;
+    }
+}
+
+int launch_compress_keys(const Dims &dm, Tensor k, Tensor ck, const int32_t *seqlens,
+                         int32_t n_new_tokens, hipStream_t stream) {
+    int32_t per_seq = num_kernels(dm.max_seqlen);
+    if (n_new_tokens > 0) {
+        int32_t inc = n_new_tokens / kStride + 1;
+        if (inc < per_seq) per_seq = inc;
+    }
+    if (per_seq <= 0 || dm.batch <= 0) return 0;
+    dim3 grid((per_seq + 15) / 16, dm.Hkv, dm.batch);
+    hipLaunchKernelGGL(compress_keys_kernel, grid, dim3(256), 0, stream, dm, k, ck, seqlens,
+                       n_new_tokens);
+    return (int)hipGetLastError();
+}
+
+// Decode-step append: copy the new key / value row of every (sequence, key-value head) to
+// cache position seqlens[b]-1.  One 16-lane group per row.
+__global__ __launch_bounds__(256) void append_kv_kernel(Dims dm, Tensor k_new, Tensor v_new, Tensor k,
+                                                         Tensor v, const int32_t *__restrict__ seqlens) {
+    const int row = blockIdx.x * 16 + (threadIdx.x >> 4);   // (b, h) pair
+    if (row >= dm.batch * dm.Hkv) return;
+    const int b = row / dm.Hkv, h = row % dm.Hkv;
+    const int32_t L = seqlens[b];
+    if (L < 1 || L > dm.max_seqlen) return;
+    const int c = (threadIdx.x & 15) * 8;
+    const int64_t dst = (int64_t)(L - 1);
+    *reinterpret_cast<uint4 *>(k.ptr + b * k.sb + h * k.sh + dst * k.st + c) =
+        *reinterpret_cast<const uint4 *>(k_new.ptr + b * k_new.sb + h * k_new.sh + c);
+    *reinterpret_cast<uint4 *>(v.ptr + b * v.sb + h * v.sh + dst * v.st + c) =
+        *reinterpret_cast<const uint4 *>(v_new.ptr + b * v_new.sb + h * v_new.sh + c);
+}
+
+int launch_append_kv(const Dims &dm, Tensor k_new, Tensor v_new, Tensor k, Tensor v,
+                     const int32_t *seqlens, hipStream_t stream) {
+    int rows = dm.batch * dm.Hkv;
+    if (rows <= 0) return 0;
+    hipLaunchKernelGGL(append_kv_kernel, dim3((rows + 15) / 16), dim3(256), 0, stream, dm, k_new,
+                       v_new, k, v, seqlens);
+    return (int)hipGetLastError();
+}
+
+}  // namespace infllmv2

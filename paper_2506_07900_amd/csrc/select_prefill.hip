@@ -1,0 +1,351 @@
+// Stage 2, prefill: block selection for every query token (section 2.1.2, "Dynamic Contextual
+// Block Selection", Eq. 1, "Top-K Blocks Sharing", "Efficient Top-K Implementation").
+//
+// The relevance softmax runs over all visible semantic kernels and the group mean is taken
+// AFTER it, so the scores cannot be produced by an online softmax: two passes over the
+// compressed keys are needed ("Efficient Top-K Implementation").
+//   pass 1  lse[token, head] = log2 sum_jh 2^(z)          z = scale*log2(e) * <q, ck_jh>
+//   pass 2  r[token, jh] = (1/G) sum_head 2^(z - lse), floored at 2^-100;
+//           R[token, j]  = max of r over the kernels {4j-1 .. 4j+3} that intersect block j
+//   top-k   forced blocks to +inf, pick the largest, ties to the lower index.
+// Both passes are causal GEMMs Q (tokens*heads x 128) . CK^T on 16x16x32 bf16 MFMA with the
+// 64-kernel CK chunk staged in LDS; a wavefront keeps its query fragments in registers.
+// Row tiles: 16 consecutive (token, head) rows of one key-value head, i.e. 16/G tokens.
+#include "common.h"
+
+namespace infllmv2 {
+
+constexpr int kChunk = 64;        // semantic kernels per LDS stage (= 16 key-value blocks)
+constexpr int kCkPitch = 136;     // bf16 elements per CK row in LDS (272 B)
+
+template <int G> struct SelCfg {
+    static constexpr int kTokPerTile = 16 / G;                     // tokens in one 16-row MFMA tile
+    static constexpr int kTiles = (G == 1) ? 1 : (G / 2);           // row tiles per wavefront
+    static constexpr int kTokPerWave = kTiles * kTokPerTile;        // 8 (16 when G == 1)
+    static constexpr int kTokPerWg = 4 * kTokPerWave;
+};
+
+// Kernels visible to the query at position i: those lying wholly at or before i.
+__device__ inline int n_visible(int i) { return num_kernels(i + 1); }
+
+__device__ inline void stage_ck_chunk(__bf16 *lds, const __bf16 *ckb, int64_t st, int jh0, int n_valid,
+                                      int tid) {
+    const int sc = tid & 15, sr = tid >> 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = sr + 16 * i;
+        uint4 x = {0u, 0u, 0u, 0u};
+        if (jh0 + r < n_valid) x = *reinterpret_cast<const uint4 *>(ckb + (int64_t)(jh0 + r) * st + 8 * sc);
+        *reinterpret_cast<uint4 *>(&lds[r * kCkPitch + 8 * sc]) = x;
+    }
+}
+
+template <int G>
+__device__ inline void load_q_tiles(bf16x8 (&qf)[SelCfg<G>::kTiles][4], const Tensor &q, int b, int h,
+                                    int tok_wave0, int L, int n, int g) {
+    using C = SelCfg<G>;
+#pragma unroll
+    for (int mt = 0; mt < C::kTiles; ++mt) {
+        const int tok = tok_wave0 + mt * C::kTokPerTile + n / G;
+        const int head = h * G + n % G;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            qf[mt][ks] = zero8();
+            if (tok < L)
+                qf[mt][ks] = load8(q.ptr + b * q.sb + (int64_t)tok * q.st + (int64_t)head * q.sh + 32 * ks + 8 * g);
+        }
+    }
+}
+
+// ---- pass 1: log-sum-exp per (token, head) over the visible kernels -------------------------
+// MFMA computes Z^T = CK . Q^T: lane = one (token, head) row, its 4 accumulator entries are 4
+// consecutive kernels, so the running (max, sum) is lane-local until the final 4-group merge.
+template <int G>
+__global__ __launch_bounds__(256) void select_lse_kernel(Dims dm, Tensor q, Tensor ck,
+                                                          const int32_t *__restrict__ seqlens,
+                                                          float *__restrict__ lse2, int32_t n_tiles) {
+    using C = SelCfg<G>;
+    __shared__ __align__(16) __bf16 cks[kChunk * kCkPitch];
+    const int tile = blockIdx.x % n_tiles;
+    const int h = (blockIdx.x / n_tiles) % dm.Hkv;
+    const int b = blockIdx.x / (n_tiles * dm.Hkv);
+    int32_t L = seqlens[b];
+    L = L < 0 ? 0 : (L > dm.max_seqlen ? dm.max_seqlen : L);
+    const int t0 = tile * C::kTokPerWg;
+    if (t0 >= L) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, g = lane >> 4;
+    const int tok_wave0 = t0 + wave * C::kTokPerWave;
+
+    bf16x8 qf[C::kTiles][4];
+    load_q_tiles<G>(qf, q, b, h, tok_wave0, L, n, g);
+    float m_run[C::kTiles], s_run[C::kTiles];
+    int nvis[C::kTiles];
+#pragma unroll
+    for (int mt = 0; mt < C::kTiles; ++mt) {
+        m_run[mt] = -INFINITY;
+        s_run[mt] = 0.f;
+        nvis[mt] = n_visible(tok_wave0 + mt * C::kTokPerTile + n / G);
+    }
+    const int last_tok = min(t0 + C::kTokPerWg, (int)L) - 1;
+    const int nvis_wg = n_visible(last_tok);
+    const int nvis_wave_min = n_visible(tok_wave0);
+    const int n_valid = num_kernels(L);
+    const __bf16 *ckb = ck.ptr + b * ck.sb + h * ck.sh;
+
+    for (int jh0 = 0; jh0 < nvis_wg; jh0 += kChunk) {
+        __syncthreads();
+        stage_ck_chunk(cks, ckb, ck.st, jh0, n_valid, tid);
+        __syncthreads();
+        f32x4 z[C::kTiles][4];
+#pragma unroll
+        for (int mt = 0; mt < C::kTiles; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) z[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+                bf16x8 a = load8(&cks[(16 * nt + n) * kCkPitch + 32 * ks + 8 * g]);
+#pragma unroll
+                for (int mt = 0; mt < C::kTiles; ++mt) z[mt][nt] = mfma16(a, qf[mt][ks], z[mt][nt]);
+            }
+        const bool edge = jh0 + kChunk > nvis_wave_min;     // some entry of this wave may be masked
+#pragma unroll
+        for (int mt = 0; mt < C::kTiles; ++mt) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float x = z[mt][nt][j] * dm.scale_log2;
+                    if (edge && jh0 + 16 * nt + 4 * g + j >= nvis[mt]) x = -INFINITY;
+                    z[mt][nt][j] = x;
+                    mx = fmaxf(mx, x);
+                }
+            const float m_new = fmaxf(m_run[mt], mx);
+            const float m_use = m_new == -INFINITY ? 0.f : m_new;
+            float acc = s_run[mt] * fast_exp2(m_run[mt] - m_use);
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc += fast_exp2(z[mt][nt][j] - m_use);
+            s_run[mt] = acc;
+            m_run[mt] = m_new;
+        }
+    }
+#pragma unroll
+    for (int mt = 0; mt < C::kTiles; ++mt) {
+        const float M = xgroup_max(m_run[mt]);
+        const float m_use = M == -INFINITY ? 0.f : M;
+        const float S = xgroup_sum(s_run[mt] * fast_exp2(m_run[mt] - m_use));
+        const int tok = tok_wave0 + mt * C::kTokPerTile + n / G;
+        if (g == 0 && tok < L)
+            lse2[((int64_t)b * dm.max_seqlen + tok) * dm.Hq + h * G + n % G] = M + fast_log2(S);
+    }
+}
+
+// ---- pass 2: group-mean kernel scores, 5-wide / stride-4 max over kernels -> block scores ----
+// MFMA computes Z = Q . CK^T: lane = one kernel, its 4 accumulator entries are 4 consecutive
+// (token, head) rows, so the sum over a token's heads is 3 adds plus at most 2 cross-group adds.
+template <int G>
+__global__ __launch_bounds__(256) void select_score_kernel(Dims dm, Tensor q, Tensor ck,
+                                                            const int32_t *__restrict__ seqlens,
+                                                            const float *__restrict__ lse2,
+                                                            float *__restrict__ R, int32_t nb_cap,
+                                                            int32_t n_tiles) {
+    using C = SelCfg<G>;
+    constexpr int TL = (G >= 4) ? 1 : 4 / G;     // tokens held by one lane of a row tile
+    constexpr int RL = (G >= 4) ? 4 : G;         // rows of one token held by one lane
+    __shared__ __align__(16) __bf16 cks[kChunk * kCkPitch];
+    __shared__ float rs[C::kTokPerWg][kChunk + 2];   // slot 0: kernel jh0-1 (halo), slot 1+x: jh0+x
+    const int tile = blockIdx.x % n_tiles;
+    const int h = (blockIdx.x / n_tiles) % dm.Hkv;
+    const int b = blockIdx.x / (n_tiles * dm.Hkv);
+    int32_t L = seqlens[b];
+    L = L < 0 ? 0 : (L > dm.max_seqlen ? dm.max_seqlen : L);
+    const int t0 = tile * C::kTokPerWg;
+    if (t0 >= L) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, g = lane >> 4;
+    const int tok_wave0 = t0 + wave * C::kTokPerWave;
+
+    bf16x8 qf[C::kTiles][4];
+    load_q_tiles<G>(qf, q, b, h, tok_wave0, L, n, g);
+    // lane holds rows 4g+j of each row tile: their log-sum-exps
+    float lse_r[C::kTiles][4];
+#pragma unroll
+    for (int mt = 0; mt < C::kTiles; ++mt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = 4 * g + j;
+            const int tok = tok_wave0 + mt * C::kTokPerTile + r / G;
+            lse_r[mt][j] = tok < L ? lse2[((int64_t)b * dm.max_seqlen + tok) * dm.Hq + h * G + r % G] : 0.f;
+        }
+    const int last_tok = min(t0 + C::kTokPerWg, (int)L) - 1;
+    const int nvis_wg = n_visible(last_tok);
+    const int n_valid = num_kernels(L);
+    const __bf16 *ckb = ck.ptr + b * ck.sb + h * ck.sh;
+    for (int i = tid; i < C::kTokPerWg; i += 256) rs[i][0] = -INFINITY;
+
+    for (int jh0 = 0; jh0 < nvis_wg; jh0 += kChunk) {
+        __syncthreads();
+        stage_ck_chunk(cks, ckb, ck.st, jh0, n_valid, tid);
+        __syncthreads();
+        f32x4 z[C::kTiles][4];
+#pragma unroll
+        for (int mt = 0; mt < C::kTiles; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) z[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+                bf16x8 bq = load8(&cks[(16 * nt + n) * kCkPitch + 32 * ks + 8 * g]);
+#pragma unroll
+                for (int mt = 0; mt < C::kTiles; ++mt) z[mt][nt] = mfma16(qf[mt][ks], bq, z[mt][nt]);
+            }
+#pragma unroll
+        for (int mt = 0; mt < C::kTiles; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+                float e[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) e[j] = fast_exp2(z[mt][nt][j] * dm.scale_log2 - lse_r[mt][j]);
+                const int jh = jh0 + 16 * nt + n;
+#pragma unroll
+                for (int tl = 0; tl < TL; ++tl) {
+                    float vsum = 0.f;
+#pragma unroll
+                    for (int jj = 0; jj < RL; ++jj) vsum += e[tl * RL + jj];
+                    if (G >= 8) vsum += __shfl_xor(vsum, 16);
+                    if (G >= 16) vsum += __shfl_xor(vsum, 32);
+                    // token of rows 4g + tl*RL ..: local index inside the workgroup's tile
+                    const int tloc = wave * C::kTokPerWave + mt * C::kTokPerTile + (4 * g + tl * RL) / G;
+                    const bool writer = ((4 * g + tl * RL) % G) == 0;
+                    if (writer) {
+                        float r = fmaxf(vsum * (1.f / G), kScoreFloor);
+                        if (jh >= n_visible(t0 + tloc)) r = -INFINITY;
+                        rs[tloc][1 + 16 * nt + n] = r;
+                    }
+                }
+            }
+        __syncthreads();
+        // block scores of blocks jh0/4 .. jh0/4+15: kernels 4j-1 .. 4j+3 -> slots 4jb .. 4jb+4
+        for (int i = tid; i < C::kTokPerWg * 16; i += 256) {
+            const int tloc = i >> 4, jb = i & 15;
+            const int tok = t0 + tloc, j = (jh0 >> 2) + jb;
+            if (tok < L && j <= tok / kBlock) {
+                float r = rs[tloc][4 * jb];
+#pragma unroll
+                for (int x = 1; x < 5; ++x) r = fmaxf(r, rs[tloc][4 * jb + x]);
+                R[(((int64_t)b * dm.Hkv + h) * dm.max_seqlen + tok) * nb_cap + j] = r;
+            }
+        }
+        __syncthreads();
+        for (int i = tid; i < C::kTokPerWg; i += 256) rs[i][0] = rs[i][kChunk];
+    }
+    // blocks past the last scored chunk (only the local ones can be): no visible kernel
+    const int j_done = ((nvis_wg + kChunk - 1) / kChunk) * 16;
+    for (int i = tid; i < C::kTokPerWg * 4; i += 256) {
+        const int tloc = i >> 2, tok = t0 + tloc, j = j_done + (i & 3);
+        if (tok < L && j <= tok / kBlock) R[(((int64_t)b * dm.Hkv + h) * dm.max_seqlen + tok) * nb_cap + j] = -INFINITY;
+    }
+}
+
+// ---- top-k: one wavefront per (sequence, key-value head, token) row of block scores ------------
+// Picks follow the total order (score descending, index ascending); pick c is the largest entry
+// strictly after pick c-1 in that order, so no "taken" flags are needed.
+__global__ __launch_bounds__(256) void select_topk_kernel(Dims dm, const int32_t *__restrict__ seqlens,
+                                                           const float *__restrict__ R, int32_t nb_cap,
+                                                           int32_t *__restrict__ block_idx) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t rows = (int64_t)dm.batch * dm.Hkv * dm.max_seqlen;
+    if (row >= rows) return;
+    const int tok = row % dm.max_seqlen;
+    const int b = row / ((int64_t)dm.max_seqlen * dm.Hkv);
+    int32_t L = seqlens[b];
+    L = L < 0 ? 0 : (L > dm.max_seqlen ? dm.max_seqlen : L);
+    if (tok >= L) return;
+    const int b_own = tok / kBlock, n_blk = b_own + 1;
+    const int n_sel = dm.topk < n_blk ? dm.topk : n_blk;
+    const float *Rr = R + row * nb_cap;
+    float last_s = INFINITY;
+    int last_j = -1;
+    int mine = 0x7fffffff;                  // lane c keeps pick c
+    for (int c = 0; c < n_sel; ++c) {
+        float best_s = -INFINITY;
+        int best_j = 0x7fffffff;
+        for (int j = lane; j < n_blk; j += 64) {
+            float sc = (j < dm.n_init || j > b_own - dm.n_local) ? INFINITY : Rr[j];
+            const bool after = sc < last_s || (sc == last_s && j > last_j);
+            if (after && (sc > best_s || (sc == best_s && j < best_j))) {
+                best_s = sc;
+                best_j = j;
+            }
+        }
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const float os = __shfl_xor(best_s, o);
+            const int oj = __shfl_xor(best_j, o);
+            if (os > best_s || (os == best_s && oj < best_j)) {
+                best_s = os;
+                best_j = oj;
+            }
+        }
+        last_s = best_s;
+        last_j = best_j;
+        if (lane == c) mine = best_j;
+    }
+    // ascending order: rank = number of picks below mine
+    int rank = 0;
+    for (int c = 0; c < n_sel; ++c) rank += __shfl(mine, c) < mine ? 1 : 0;
+    int32_t *o = block_idx + row * dm.topk;
+    if (lane < n_sel) o[rank] = mine;
+    else if (lane < dm.topk) o[lane] = -1;
+}
+
+size_t select_prefill_ws_bytes(const Dims &dm) {
+    const size_t nb_cap = ((size_t)(dm.max_seqlen + kBlock - 1) / kBlock + 15) / 16 * 16;
+    size_t lse = (size_t)dm.batch * dm.max_seqlen * dm.Hq * sizeof(float);
+    lse = (lse + 255) / 256 * 256;
+    const size_t r = (size_t)dm.batch * dm.Hkv * dm.max_seqlen * nb_cap * sizeof(float);
+    return lse + r;
+}
+
+template <int G>
+static int launch_select_prefill_g(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
+                                   int32_t *block_idx, void *ws, hipStream_t stream) {
+    using C = SelCfg<G>;
+    const int32_t nb_cap = (int32_t)(((size_t)(dm.max_seqlen + kBlock - 1) / kBlock + 15) / 16 * 16);
+    size_t lse_bytes = (size_t)dm.batch * dm.max_seqlen * dm.Hq * sizeof(float);
+    lse_bytes = (lse_bytes + 255) / 256 * 256;
+    float *lse2 = reinterpret_cast<float *>(ws);
+    float *R = reinterpret_cast<float *>(reinterpret_cast<char *>(ws) + lse_bytes);
+    const int32_t n_tiles = (dm.max_seqlen + C::kTokPerWg - 1) / C::kTokPerWg;
+    const int64_t n_wg = (int64_t)n_tiles * dm.Hkv * dm.batch;
+    if (n_wg <= 0) return 0;
+    hipLaunchKernelGGL(select_lse_kernel<G>, dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, ck,
+                       seqlens, lse2, n_tiles);
+    hipLaunchKernelGGL(select_score_kernel<G>, dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, ck,
+                       seqlens, lse2, R, nb_cap, n_tiles);
+    const int64_t rows = (int64_t)dm.batch * dm.Hkv * dm.max_seqlen;
+    hipLaunchKernelGGL(select_topk_kernel, dim3((uint32_t)((rows + 3) / 4)), dim3(256), 0, stream, dm,
+                       seqlens, R, nb_cap, block_idx);
+    return (int)hipGetLastError();
+}
+
+int launch_select_prefill(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
+                          int32_t *block_idx, void *ws, hipStream_t stream) {
+    switch (dm.G) {
+        case 1: return launch_select_prefill_g<1>(dm, q, ck, seqlens, block_idx, ws, stream);
+        case 2: return launch_select_prefill_g<2>(dm, q, ck, seqlens, block_idx, ws, stream);
+        case 4: return launch_select_prefill_g<4>(dm, q, ck, seqlens, block_idx, ws, stream);
+        case 8: return launch_select_prefill_g<8>(dm, q, ck, seqlens, block_idx, ws, stream);
+        case 16: return launch_select_prefill_g<16>(dm, q, ck, seqlens, block_idx, ws, stream);
+    }
+    return (int)hipErrorInvalidValue;
+}
+
+}  // namespace infllmv2

@@ -1,0 +1,108 @@
+"""CPU checks of the C ABI: the library loads, exports every symbol the header declares, and
+rejects bad arguments with a status code before any HIP call (so this runs without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2506_07900_amd import binding
+from paper_2506_07900_amd.binding import CParams, CTensor
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+INVALID, UNSUPPORTED, WORKSPACE = -1, -2, -3
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2506_07900_amd import build
+        build.build()
+    return binding.load_library()
+
+
+def test_header_symbols_are_exported(lib):
+    text = open(os.path.join(ROOT, "include", "infllmv2.h")).read()
+    declared = sorted(set(re.findall(r"\b(infllmv2_[a-z_]+)\s*\(", text)))
+    assert set(declared) == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(CParams) == 40 and ctypes.sizeof(CTensor) == 32
+
+
+def good_params(**kw):
+    p = dict(head_dim=128, n_q_heads=32, n_kv_heads=2, block_size=64, kernel_size=32, kernel_stride=16,
+             topk=16, n_init_blocks=1, n_local_blocks=2, softmax_scale=128 ** -0.5)
+    p.update(kw)
+    return CParams(**p)
+
+
+FAKE = 0x10000   # non-null, 256-byte aligned; never dereferenced because validation fails first
+
+
+def tensor(ptr=FAKE, sb=1 << 20, sh=1 << 16, st=128):
+    return CTensor(ptr, sb, sh, st)
+
+
+def call_compress(lib, prm, k=None, ck=None, seqlens=FAKE, batch=1, max_seqlen=1024):
+    k = k or tensor()
+    ck = ck or tensor()
+    return lib.infllmv2_compress_keys(ctypes.byref(prm) if prm else None, ctypes.byref(k), seqlens, batch,
+                                      max_seqlen, 0, ctypes.byref(ck), None)
+
+
+def test_status_strings(lib):
+    assert lib.infllmv2_status_string(0) == b"ok"
+    for s in (-1, -2, -3, -4):
+        assert lib.infllmv2_status_string(s) not in (b"ok", b"unknown status")
+    assert lib.infllmv2_status_string(-99) == b"unknown status"
+
+
+def test_parameter_validation(lib):
+    assert call_compress(lib, None) == INVALID
+    assert call_compress(lib, good_params(n_q_heads=30, n_kv_heads=4)) == INVALID      # ragged head ratio
+    assert call_compress(lib, good_params(topk=2)) == INVALID                           # fewer than forced
+    assert call_compress(lib, good_params(softmax_scale=0.0)) == INVALID
+    assert call_compress(lib, good_params(head_dim=64)) == UNSUPPORTED
+    assert call_compress(lib, good_params(block_size=128)) == UNSUPPORTED
+    assert call_compress(lib, good_params(kernel_size=16)) == UNSUPPORTED
+    assert call_compress(lib, good_params(n_q_heads=64, n_kv_heads=2)) == UNSUPPORTED  # G = 32
+    assert call_compress(lib, good_params(topk=65)) == UNSUPPORTED
+    assert call_compress(lib, good_params(), seqlens=None) == INVALID
+    assert call_compress(lib, good_params(), k=tensor(ptr=None)) == INVALID
+    assert call_compress(lib, good_params(), k=tensor(ptr=FAKE + 2)) == INVALID        # misaligned
+    assert call_compress(lib, good_params(), ck=tensor(st=100)) == INVALID             # stride not /8
+    assert call_compress(lib, good_params(), batch=-1) == INVALID
+    assert call_compress(lib, good_params(), max_seqlen=-5) == INVALID
+
+
+def test_workspace_validation(lib):
+    prm = good_params()
+    need = lib.infllmv2_workspace_bytes(binding.OP_SELECT_PREFILL, ctypes.byref(prm), 1, 4096)
+    # fp32 log-sum-exp per (token, head) + fp32 block scores per (token, kv head, block)
+    assert need == 4096 * 32 * 4 + 2 * 4096 * 64 * 4
+    assert lib.infllmv2_workspace_bytes(binding.OP_ATTN_PREFILL, ctypes.byref(prm), 1, 4096) == 0
+    assert lib.infllmv2_workspace_bytes(binding.OP_ATTN_DECODE, ctypes.byref(prm), 2, 4096) > 0
+    assert lib.infllmv2_workspace_bytes(99, ctypes.byref(prm), 1, 4096) == 0
+    q, ck = tensor(), tensor()
+    args = (ctypes.byref(prm), 0, ctypes.byref(q), ctypes.byref(ck), FAKE, 1, 4096, FAKE)
+    assert lib.infllmv2_select_blocks(*args, None, 0, None) == WORKSPACE
+    assert lib.infllmv2_select_blocks(*args, FAKE, need - 1, None) == WORKSPACE
+    assert lib.infllmv2_select_blocks(*args, FAKE + 16, need, None) == WORKSPACE        # not 256-aligned
+    bad_mode = (ctypes.byref(prm), 7, ctypes.byref(q), ctypes.byref(ck), FAKE, 1, 4096, FAKE)
+    assert lib.infllmv2_select_blocks(*bad_mode, FAKE, need, None) == INVALID
+    dec = (ctypes.byref(prm), 1, ctypes.byref(q), ctypes.byref(ck), FAKE, 1, 1 << 20, FAKE)
+    assert lib.infllmv2_select_blocks(*dec, FAKE, 1 << 40, None) == UNSUPPORTED         # decode context cap
+    o = tensor()
+    assert lib.infllmv2_sparse_attn_decode(ctypes.byref(prm), ctypes.byref(q), ctypes.byref(q), ctypes.byref(q),
+                                           FAKE, 1, 4096, FAKE, ctypes.byref(o), FAKE, None, 0, None) == WORKSPACE
+    assert lib.infllmv2_sparse_attn_prefill(ctypes.byref(prm), ctypes.byref(q), ctypes.byref(q), ctypes.byref(q),
+                                            FAKE, 1, 4096, None, ctypes.byref(o), FAKE, None, 0, None) == INVALID
+
+
+def test_binding_fails_loudly_without_library(tmp_path):
+    with pytest.raises(binding.InfLLMv2Error):
+        binding.load_library(str(tmp_path / "missing.so"))

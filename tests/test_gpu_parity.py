@@ -1,0 +1,245 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle element by
+element on the same seeded inputs.  Sizes span several tiles and ragged tails; the largest
+stated workloads are checked on sampled rows."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2506_07900_amd import binding, synth
+from util import LSE_TOL, OUT_TOL, compare_selection, oracle_params, to_bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def dev_i32(a):
+    return torch.tensor(np.asarray(a, np.int32), dtype=torch.int32, device="cuda")
+
+
+def make_batch(seed, seqlens, Hq, Hkv, n_planted=0, heavy=()):
+    """Padded batch of independent sequences -> numpy bits q [B,T,Hq,d], k/v [B,Hkv,T,d]."""
+    T = max(int(max(seqlens)), 1)
+    B = len(seqlens)
+    q = np.zeros((B, T, Hq, 128), np.uint16)
+    k = np.zeros((B, Hkv, T, 128), np.uint16)
+    v = np.zeros((B, Hkv, T, 128), np.uint16)
+    for b, l in enumerate(seqlens):
+        if l == 0:
+            continue
+        s = synth.make_sequence(seed * 100 + b, l, Hq, Hkv, n_planted=n_planted, heavy_tail=b in heavy)
+        q[b, :l], k[b, :, :l], v[b, :, :l] = s.q, s.k, s.v
+    return q, k, v, T
+
+
+# ------------------------------------------------------------------ stage 1
+
+@pytest.mark.parametrize("seqlens,Hkv", [([2048], 1), ([1077, 31, 32, 0, 47, 48], 2), ([5000, 4999], 2)])
+def test_compress_keys_bit_exact(seqlens, Hkv):
+    print("case compress", seqlens, Hkv, flush=True)
+    prm = binding.Params(Hkv * 4, Hkv)
+    q, k, v, T = make_batch(11, seqlens, Hkv * 4, Hkv, heavy=(1,))
+    kd = to_dev(k)
+    n_cap = binding.num_kernels(T, prm) + 3
+    ck = torch.full((len(seqlens), Hkv, n_cap, 128), 7.0, dtype=torch.bfloat16, device="cuda")
+    binding.compress_keys(prm, kd, dev_i32(seqlens), T, ck=ck)
+    torch.cuda.synchronize()
+    got = to_bits(ck)
+    sentinel = to_bits(torch.full((1,), 7.0, dtype=torch.bfloat16))[0]
+    for b, l in enumerate(seqlens):
+        _, want = ref.compress_keys(k[b, :, :l], oracle_params(prm))
+        n_c = want.shape[1]
+        assert np.array_equal(got[b, :, :n_c], want), (b, l)
+        assert np.all(got[b, :, n_c:] == sentinel)          # rows past n_c(l) are never written
+
+
+def test_compress_keys_incremental_equals_from_scratch():
+    print("case compress incremental", flush=True)
+    Hkv, L0, steps = 2, 1000, 70
+    prm = binding.Params(32, Hkv)
+    q, k, v, T = make_batch(12, [L0 + steps, L0 + steps - 13], 32, Hkv)
+    kd = to_dev(k)
+    lens = np.array([L0, L0 - 13], np.int32)
+    ck = binding.compress_keys(prm, kd, dev_i32(lens), T)
+    for _ in range(steps):
+        lens = lens + 1
+        binding.compress_keys(prm, kd, dev_i32(lens), T, ck=ck, n_new_tokens=1)
+    full = binding.compress_keys(prm, kd, dev_i32(lens), T)
+    torch.cuda.synchronize()
+    assert torch.equal(ck.view(torch.int16), full.view(torch.int16))
+    for b in range(2):
+        _, want = ref.compress_keys(k[b, :, :lens[b]], oracle_params(prm))
+        assert np.array_equal(to_bits(ck)[b, :, :want.shape[1]], want)
+
+
+# ------------------------------------------------------------------ stages 2 + 3, prefill
+
+PREFILL_CASES = [
+    # seqlens, Hq, Hkv, topk, planted
+    ([2048], 4, 1, 8, 4),            # the smallest stated workload (G = 4)
+    ([1077, 333], 32, 2, 16, 6),     # G = 16, ragged tails, two sequences
+    ([700], 16, 2, 6, 3),            # G = 8
+    ([300, 64, 63, 1], 4, 2, 4, 0),  # G = 2, tiny sequences
+    ([450], 2, 2, 5, 2),             # G = 1
+    ([1500], 16, 1, 32, 5),          # everything selected up to 2048 tokens: dense degrade
+]
+
+
+def run_prefill(seqlens, Hq, Hkv, topk, planted, seed=21):
+    prm = binding.Params(Hq, Hkv, topk=topk)
+    q, k, v, T = make_batch(seed, seqlens, Hq, Hkv, n_planted=planted)
+    qd, kd, vd, sl = to_dev(q), to_dev(k), to_dev(v), dev_i32(seqlens)
+    ck = binding.compress_keys(prm, kd, sl, T)
+    idx = binding.select_blocks(prm, binding.MODE_PREFILL, qd, ck, sl, T)
+    torch.cuda.synchronize()
+    return prm, (q, k, v, T), (qd, kd, vd, sl), ck, idx
+
+
+@pytest.mark.parametrize("seqlens,Hq,Hkv,topk,planted", PREFILL_CASES)
+def test_select_blocks_prefill(seqlens, Hq, Hkv, topk, planted):
+    print("case select prefill", seqlens, Hq, Hkv, topk, flush=True)
+    prm, (q, k, v, T), dev, ck, idx = run_prefill(seqlens, Hq, Hkv, topk, planted)
+    oprm = oracle_params(prm)
+    idx = idx.cpu().numpy()
+    ckb = to_bits(ck)
+    tot = exact = near = 0
+    for b, l in enumerate(seqlens):
+        if l == 0:
+            continue
+        n_c = ref.num_kernels(l, 32, 16)
+        pos = np.arange(l, dtype=np.int32)
+        want, margins, R = ref.select_blocks(q[b, :l], ckb[b, :, :n_c], pos, oprm, want_scores=True)
+        n, e, nt, hard = compare_selection(idx[b, :, :l], want, margins, R)
+        assert not hard, hard[:3]
+        tot, exact, near = tot + n, exact + e, near + nt
+    print("rows %d exact %d near-tie %d" % (tot, exact, near), flush=True)
+    assert near <= max(2, tot // 200)
+
+
+@pytest.mark.parametrize("seqlens,Hq,Hkv,topk,planted", PREFILL_CASES)
+def test_sparse_attn_prefill(seqlens, Hq, Hkv, topk, planted):
+    print("case attn prefill", seqlens, Hq, Hkv, topk, flush=True)
+    prm = binding.Params(Hq, Hkv, topk=topk)
+    oprm = oracle_params(prm)
+    q, k, v, T = make_batch(21, seqlens, Hq, Hkv, n_planted=planted)
+    # attention is checked in isolation: both sides consume the oracle's block sets
+    idx_ref = np.full((len(seqlens), Hkv, T, topk), -1, np.int32)
+    outs = []
+    for b, l in enumerate(seqlens):
+        if l == 0:
+            outs.append(None)
+            continue
+        _, ckb = ref.compress_keys(k[b, :, :l], oprm)
+        pos = np.arange(l, dtype=np.int32)
+        idx_b, _ = ref.select_blocks(q[b, :l], ckb, pos, oprm)
+        idx_ref[b, :, :l] = idx_b
+        outs.append(ref.sparse_attn(q[b, :l], k[b, :, :l], v[b, :, :l], pos, idx_b, oprm))
+    qd, kd, vd, sl = to_dev(q), to_dev(k), to_dev(v), dev_i32(seqlens)
+    out = torch.full_like(qd, 3.0)
+    lse = torch.full((len(seqlens), T, Hq), 5.0, dtype=torch.float32, device="cuda")
+    binding.sparse_attn_prefill(prm, qd, kd, vd, sl, T, torch.from_numpy(idx_ref).cuda(), out=out, lse=lse)
+    torch.cuda.synchronize()
+    o = out.float().cpu().numpy().astype(np.float64)
+    ls = lse.cpu().numpy().astype(np.float64)
+    for b, l in enumerate(seqlens):
+        if l:
+            want_o, want_l = outs[b]
+            eo = np.abs(o[b, :l] - want_o).max()
+            el = np.abs(ls[b, :l] - want_l).max()
+            print("seq %d len %d: max|dO| %.3e max|dLSE| %.3e" % (b, l, eo, el), flush=True)
+            assert eo <= OUT_TOL and el <= LSE_TOL
+        assert np.all(o[b, l:] == 3.0) and np.all(ls[b, l:] == 5.0)     # padding rows untouched
+
+
+def test_prefill_end_to_end_dense_degrade():
+    # top-k covering every block: the whole path equals dense causal attention
+    print("case dense degrade", flush=True)
+    l, Hq, Hkv = 900, 32, 2
+    prm, (q, k, v, T), (qd, kd, vd, sl), ck, idx = run_prefill([l], Hq, Hkv, 16, 0)
+    out, lse = binding.sparse_attn_prefill(prm, qd, kd, vd, sl, T, idx)
+    torch.cuda.synchronize()
+    G = Hq // Hkv
+    qt = torch.from_numpy(synth.bf16_bits_to_f32(q[0]).astype(np.float64)).permute(1, 0, 2)
+    kt = torch.from_numpy(synth.bf16_bits_to_f32(k[0]).astype(np.float64)).repeat_interleave(G, 0)
+    vt = torch.from_numpy(synth.bf16_bits_to_f32(v[0]).astype(np.float64)).repeat_interleave(G, 0)
+    want = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, is_causal=True).permute(1, 0, 2)
+    assert (out[0].double().cpu() - want).abs().max().item() <= OUT_TOL
+
+
+# ------------------------------------------------------------------ decode
+
+@pytest.mark.parametrize("seqlens,Hq,Hkv,topk", [([3000, 1077, 64, 33, 31, 1], 32, 2, 16),
+                                                 ([2048, 129], 4, 1, 8), ([777], 16, 2, 6)])
+def test_decode_select_and_attn(seqlens, Hq, Hkv, topk):
+    print("case decode", seqlens, Hq, Hkv, topk, flush=True)
+    prm = binding.Params(Hq, Hkv, topk=topk)
+    oprm = oracle_params(prm)
+    q, k, v, T = make_batch(31, seqlens, Hq, Hkv, n_planted=4, heavy=(1,))
+    B = len(seqlens)
+    last = np.array([l - 1 for l in seqlens])
+    q1 = np.stack([q[b, last[b]] for b in range(B)])[:, None]            # [B,1,Hq,d]
+    qd, kd, vd, sl = to_dev(q1), to_dev(k), to_dev(v), dev_i32(seqlens)
+    ck = binding.compress_keys(prm, kd, sl, T)
+    idx = binding.select_blocks(prm, binding.MODE_DECODE, qd, ck, sl, T)
+    torch.cuda.synchronize()
+    idx_np = idx.cpu().numpy()
+    ckb = to_bits(ck)
+    idx_ref = np.full((B, Hkv, 1, topk), -1, np.int32)
+    want = []
+    for b, l in enumerate(seqlens):
+        pos = np.array([l - 1], np.int32)
+        n_c = ref.num_kernels(l, 32, 16)
+        ib, margins, R = ref.select_blocks(q1[b], ckb[b, :, :n_c], pos, oprm, want_scores=True)
+        n, e, nt, hard = compare_selection(idx_np[b], ib, margins, R)
+        assert not hard, (b, hard)
+        idx_ref[b] = ib
+        want.append(ref.sparse_attn(q1[b], k[b, :, :l], v[b, :, :l], pos, ib, oprm))
+    out, lse = binding.sparse_attn_decode(prm, qd, kd, vd, sl, T, torch.from_numpy(idx_ref).cuda())
+    torch.cuda.synchronize()
+    for b in range(B):
+        eo = np.abs(out[b].double().cpu().numpy() - want[b][0]).max()
+        el = np.abs(lse[b].double().cpu().numpy() - want[b][1][0]).max()
+        print("seq %d len %d: max|dO| %.3e max|dLSE| %.3e" % (b, seqlens[b], eo, el), flush=True)
+        assert eo <= OUT_TOL and el <= LSE_TOL
+
+
+def test_decode_steps_with_append_and_incremental_compress():
+    # a short run of real decode steps: append, incremental compression, select, attend;
+    # every step equals the oracle evaluated on the cache as it stands
+    print("case decode steps", flush=True)
+    cfg = synth.CONFIGS[3]
+    steps, L0 = 40, 1500
+    x = synth.make_decode(cfg, steps=steps, seqlen=L0)
+    prm = binding.Params(cfg.n_q_heads, cfg.n_kv_heads, topk=cfg.topk)
+    oprm = oracle_params(prm)
+    cap = x.capacity
+    kd, vd = to_dev(x.k_cache), to_dev(x.v_cache)
+    lens = x.seqlens0.copy()
+    sl = dev_i32(lens)
+    ck = binding.compress_keys(prm, kd, sl, cap)
+    k_np, v_np = x.k_cache.copy(), x.v_cache.copy()
+    for s in range(steps):
+        lens = lens + 1
+        sl = dev_i32(lens)
+        kn = to_dev(x.k_steps[s][:, :, None])
+        vn = to_dev(x.v_steps[s][:, :, None])
+        qd = to_dev(x.q_steps[s][:, None])
+        binding.append_kv(prm, kn, vn, kd, vd, sl, cap)
+        binding.compress_keys(prm, kd, sl, cap, ck=ck, n_new_tokens=1)
+        idx = binding.select_blocks(prm, binding.MODE_DECODE, qd, ck, sl, cap)
+        out, lse = binding.sparse_attn_decode(prm, qd, kd, vd, sl, cap, idx)
+        torch.cuda.synchronize()
+        l = int(lens[0])
+        k_np[0, :, l - 1] = x.k_steps[s][0]
+        v_np[0, :, l - 1] = x.v_steps[s][0]
+        if s % 8 == 0 or s == steps - 1:
+            pos = np.array([l - 1], np.int32)
+            _, ckb = ref.compress_keys(k_np[0, :, :l], oprm)
+            assert np.array_equal(to_bits(ck)[0, :, :ckb.shape[1]], ckb)
+            ib, margins, R = ref.select_blocks(x.q_steps[s][0][None], ckb, pos, oprm, want_scores=True)
+            n, e, nt, hard = compare_selection(idx.cpu().numpy()[0], ib, margins, R)
+            assert not hard, (s, hard)
+            if nt == 0:
+                wo, wl = ref.sparse_attn(x.q_steps[s][0][None], k_np[0, :, :l], v_np[0, :, :l], pos, ib, oprm)
+                assert np.abs(out[0].double().cpu().numpy() - wo).max() <= OUT_TOL
+                assert np.abs(lse[0].double().cpu().numpy() - wl[0]).max() <= LSE_TOL
+    assert torch.equal(kd.view(torch.int16).cpu(), torch.from_numpy(k_np.view(np.int16)))

@@ -1,0 +1,60 @@
+"""Helpers shared by the GPU parity tests: tensor marshalling and the comparison rules.
+
+Tolerances (from the stated target): outputs max abs error <= 2e-2, fp32 log-sum-exp abs
+error <= 1e-5, block-index sets bit-exact except near-ties (relative score gap < 1e-3),
+which are counted."""
+import numpy as np
+import torch
+
+from oracle import ref
+
+OUT_TOL = 2e-2
+LSE_TOL = 1e-5
+NEAR_TIE = 1e-3
+
+
+def to_dev(bits):
+    """uint16 bf16 bit patterns (numpy) -> bf16 tensor on cuda:0."""
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def to_bits(t):
+    """bf16 tensor -> uint16 numpy bit patterns."""
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def oracle_params(prm):
+    return ref.Params(prm.n_q_heads, prm.n_kv_heads, prm.head_dim, prm.block_size, prm.kernel_size,
+                      prm.kernel_stride, prm.topk, prm.n_init_blocks, prm.n_local_blocks,
+                      prm.softmax_scale)
+
+
+def compare_selection(idx_gpu, idx_ref, margins, R):
+    """idx_* [Hkv, Tq, topk]; margins [Hkv, Tq, 2]; R [Hkv, Tq, nb] oracle block scores.
+    Returns (n_rows, n_exact, n_near_tie, hard) where hard lists rows that differ outside a
+    near-tie.  A differing row is a near-tie when every block in the symmetric difference has
+    an oracle score within NEAR_TIE (relative) of the smallest selected score."""
+    Hkv, Tq, _ = idx_ref.shape
+    exact = near = 0
+    hard = []
+    for h in range(Hkv):
+        for t in range(Tq):
+            a, b = idx_gpu[h, t], idx_ref[h, t]
+            if np.array_equal(a, b):
+                exact += 1
+                continue
+            sa, sb = set(a[a >= 0].tolist()), set(b[b >= 0].tolist())
+            kth = margins[h, t, 0]
+            ok = len(sa) == len(sb) and sorted(sa) == [x for x in a.tolist() if x >= 0]
+            for j in sa ^ sb:
+                if not ok:
+                    break
+                if j < 0 or j >= R.shape[2] or not np.isfinite(R[h, t, j]) or not np.isfinite(kth):
+                    ok = False
+                elif abs(R[h, t, j] - kth) > NEAR_TIE * abs(kth):
+                    ok = False
+            if ok:
+                near += 1
+            else:
+                hard.append((h, t, a.tolist(), b.tolist()))
+    return Hkv * Tq, exact, near, hard

@@ -1,0 +1,263 @@
+#!/usr/bin/env python3
+"""Benchmark of the InfLLM v2 hot path on one MI355X.
+
+A step is one pass of the whole prefill path -- compress_keys -> select_blocks ->
+sparse_attn_prefill -- over the 32K-token workload (batch 1, 32 query heads : 2 key-value
+heads, head_dim 128, block 64, kernel 32 / stride 16, top-k 16; seeded synthetic bf16 inputs
+with planted key blocks), inputs resident in HBM.  The headline value is attended TFLOP/s
+(sum over heads and query tokens of |T_i| * 4d, divided by the time of the WHOLE step).  The
+line also carries the per-kernel times, the roofline of the dominant kernel, the decode leg of
+the metric (128K context, microseconds per token and bytes moved per second) and the fp64 CPU
+oracle timed on a bounded sample of the same workload.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--decode-steps N] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def attended_pairs_per_head(idx, l, m):
+    """Sum over query tokens of |T_i| for one key-value head's block lists (torch, on device)."""
+    import torch
+    t = torch.arange(l, device=idx.device, dtype=torch.int64)[:, None]
+    j = idx.to(torch.int64)
+    n = torch.clamp(t + 1 - j * m, min=0, max=m)
+    n = torch.where(j >= 0, n, torch.zeros_like(n))
+    return int(n.sum().item())
+
+
+def visible_pairs(l, p=32, s=16):
+    """Sum over query positions i of the number of visible semantic kernels n_c(i+1)."""
+    i = np.arange(l, dtype=np.int64)
+    return int(np.where(i + 1 >= p, (i + 1 - p) // s + 1, 0).sum())
+
+
+def bench_prefill(args):
+    import torch
+    from paper_2506_07900_amd import binding, synth
+
+    cfg = synth.CONFIGS[1]
+    log("[bench] generating %s inputs" % cfg.name)
+    x = synth.make_prefill(cfg)
+    l, Hq, Hkv, d, m = cfg.seqlen, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.block_size
+    prm = binding.Params(Hq, Hkv, topk=cfg.topk)
+
+    def dev(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+    q, k, v = dev(x.q)[None], dev(x.k)[None], dev(x.v)[None]
+    sl = torch.tensor([l], dtype=torch.int32, device="cuda")
+    ck = torch.zeros((1, Hkv, binding.num_kernels(l, prm), d), dtype=torch.bfloat16, device="cuda")
+    idx = torch.full((1, Hkv, l, cfg.topk), -1, dtype=torch.int32, device="cuda")
+    out = torch.zeros_like(q)
+    lse = torch.zeros((1, l, Hq), dtype=torch.float32, device="cuda")
+    ws_bytes = binding.workspace_bytes(binding.OP_SELECT_PREFILL, prm, 1, l)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+
+    def step():
+        binding.compress_keys(prm, k, sl, l, ck=ck)
+        binding.select_blocks(prm, binding.MODE_PREFILL, q, ck, sl, l, block_idx=idx, workspace=ws)
+        binding.sparse_attn_prefill(prm, q, k, v, sl, l, idx, out=out, lse=lse)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.timing_enable(True)
+    per_kernel = {}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    done = 0
+    while done < args.steps:                      # the event log holds 256 launches: read it in chunks
+        n = min(32, args.steps - done)
+        for _ in range(n):
+            step()
+        for name, ms in binding.timing_read():
+            per_kernel.setdefault(name, []).append(ms)
+        done += n
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    binding.timing_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kern_ms = {n: float(np.mean(v)) for n, v in per_kernel.items()}
+
+    pairs = sum(attended_pairs_per_head(idx[0, h], l, m) for h in range(Hkv)) * (Hq // Hkv)
+    attended_flops = pairs * 4 * d
+    score_flops = visible_pairs(l) * 2 * d * Hq          # one scoring pass
+    value = attended_flops / (ms_per_step * 1e-3) / 1e12
+
+    flops_of = {"attn_prefill_kernel": attended_flops, "select_lse_kernel": score_flops,
+                "select_score_kernel": score_flops}
+    dominant = max(kern_ms, key=kern_ms.get)
+    if dominant in flops_of:
+        ach = flops_of[dominant] / (kern_ms[dominant] * 1e-3) / 1e12
+        roofline = {"kernel": dominant, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                    "flops_per_launch": flops_of[dominant], "avg_launch_ms": kern_ms[dominant]}
+    else:
+        roofline = {"kernel": dominant, "bound": "hbm", "achieved": None, "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": None, "traffic": None, "avg_launch_ms": kern_ms[dominant]}
+    res = {
+        "ms_per_step": ms_per_step, "value": value, "roofline": roofline,
+        "kernels_ms": kern_ms, "attended_flops": attended_flops, "scoring_flops_per_pass": score_flops,
+        "attn_only_tflops": attended_flops / (kern_ms["attn_prefill_kernel"] * 1e-3) / 1e12,
+    }
+    return res, (x, idx, out, lse, prm, cfg)
+
+
+def bench_decode(args):
+    """128K-context decode: append -> incremental compress -> select -> attend, per token."""
+    import torch
+    from paper_2506_07900_amd import binding, synth
+
+    cfg = synth.CONFIGS[3]
+    steps = args.decode_steps
+    log("[bench] generating %s inputs (%d steps)" % (cfg.name, steps))
+    x = synth.make_decode(cfg, steps=steps)
+    prm = binding.Params(cfg.n_q_heads, cfg.n_kv_heads, topk=cfg.topk)
+    Hq, Hkv, d, m = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.block_size
+
+    def dev(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+    cap = x.capacity
+    kc, vc = dev(x.k_cache), dev(x.v_cache)
+    qs = dev(x.q_steps)[:, :, None].contiguous()         # [steps, B, 1, Hq, d]
+    ks = dev(x.k_steps)[:, :, :, None].contiguous()      # [steps, B, Hkv, 1, d]
+    vs = dev(x.v_steps)[:, :, :, None].contiguous()
+    B = 1
+    sl = torch.tensor(x.seqlens0, dtype=torch.int32, device="cuda")
+    ck = torch.zeros((B, Hkv, binding.num_kernels(cap, prm), d), dtype=torch.bfloat16, device="cuda")
+    binding.compress_keys(prm, kc, sl, cap, ck=ck)
+    idx = torch.full((B, Hkv, 1, cfg.topk), -1, dtype=torch.int32, device="cuda")
+    out = torch.zeros((B, 1, Hq, d), dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros((B, Hq), dtype=torch.float32, device="cuda")
+    ws_sel = torch.empty(binding.workspace_bytes(binding.OP_SELECT_DECODE, prm, B, cap), dtype=torch.uint8, device="cuda")
+    ws_att = torch.empty(binding.workspace_bytes(binding.OP_ATTN_DECODE, prm, B, cap), dtype=torch.uint8, device="cuda")
+
+    def step(s):
+        sl.add_(1)
+        binding.append_kv(prm, ks[s], vs[s], kc, vc, sl, cap)
+        binding.compress_keys(prm, kc, sl, cap, ck=ck, n_new_tokens=1)
+        binding.select_blocks(prm, binding.MODE_DECODE, qs[s], ck, sl, cap, block_idx=idx, workspace=ws_sel)
+        binding.sparse_attn_decode(prm, qs[s], kc, vc, sl, cap, idx, out=out, lse=lse, workspace=ws_att)
+
+    n_warm = min(20, steps // 10)
+    for s in range(n_warm):
+        step(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(n_warm, steps):
+        step(s)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    us = (t1 - t0) * 1e6 / (steps - n_warm)
+    L = int(x.seqlens0[0]) + steps // 2
+    n_c = (L - 32) // 16 + 1
+    gathered = Hkv * cfg.topk * m * d * 2 * 2
+    algorithmic = gathered + n_c * Hkv * d * 2 + 2 * Hq * d * 2 + Hkv * cfg.topk * 4
+    return {"workload": cfg.name, "steps": steps - n_warm, "us_per_token": us,
+            "bytes_gathered": gathered, "bytes_algorithmic": algorithmic,
+            "gathered_GBs": gathered / us / 1e3, "algorithmic_GBs": algorithmic / us / 1e3,
+            "frac_hbm_gathered": gathered / us / 1e3 / PEAK_HBM_GBS,
+            "frac_hbm_algorithmic": algorithmic / us / 1e3 / PEAK_HBM_GBS,
+            "launch": "eager, 6 kernels per step"}
+
+
+def cpu_baseline(x, cfg, n_rows):
+    """The fp64 oracle, as it stands, on a stratified sample of query rows of the same workload."""
+    from oracle import ref
+    oprm = ref.Params(cfg.n_q_heads, cfg.n_kv_heads, topk=cfg.topk)
+    l = cfg.seqlen
+    stride = max(1, l // n_rows)
+    pos = np.arange(stride - 1, l, stride, dtype=np.int32)[:n_rows]
+    t0 = time.perf_counter()
+    _, ckb = ref.compress_keys(x.k, oprm)
+    t_comp = time.perf_counter() - t0
+    qs = np.ascontiguousarray(x.q[pos])
+    t0 = time.perf_counter()
+    idx, _ = ref.select_blocks(qs, ckb, pos, oprm)
+    t_sel = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    ref.sparse_attn(qs, x.k, x.v, pos, idx, oprm)
+    t_att = time.perf_counter() - t0
+    m = cfg.block_size
+    pairs = 0
+    for h in range(cfg.n_kv_heads):
+        for a, i in enumerate(pos):
+            for j in idx[h, a]:
+                if j >= 0:
+                    pairs += min(m, int(i) + 1 - int(j) * m)
+    flops = pairs * (cfg.n_q_heads // cfg.n_kv_heads) * 4 * cfg.head_dim
+    secs = t_sel + t_att + t_comp * len(pos) / l
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": "%d of %d query rows (every %dth), all heads: select %.2fs + attend %.2fs + compress %.2fs x %d/%d"
+                      % (len(pos), l, stride, t_sel, t_att, t_comp, len(pos), l)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--decode-steps", type=int, default=1000)
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=4096)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (multi-GPU sharding is design only)",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    from paper_2506_07900_amd import binding
+    binding.load_library()          # fails loudly when the HIP library is missing
+
+    res, (x, idx, out, lse, prm, cfg) = bench_prefill(args)
+    line = {
+        "metric": "sparse-attn prefill TFLOP/s (% bf16 MFMA peak); 128K decode us/token (% HBM BW)",
+        "value": res["value"], "unit": "TFLOP/s (attended flops / whole-step time)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "prefill_32k: batch 1, seq 32768, 32 q heads : 2 kv heads, d 128, block 64, "
+                               "kernel 32/16, top-k 16 (1 init + 2 local + 13 scored), 32 planted blocks/head",
+                   "step": "compress_keys + select_blocks + sparse_attn_prefill"},
+        "frac_bf16_peak_whole_step": res["value"] / PEAK_BF16_TFLOPS,
+        "attn_only_tflops": res["attn_only_tflops"],
+        "frac_bf16_peak_attn_only": res["attn_only_tflops"] / PEAK_BF16_TFLOPS,
+        "kernels_ms": res["kernels_ms"],
+        "attended_flops": res["attended_flops"],
+        "scoring_flops_per_pass": res["scoring_flops_per_pass"],
+        "roofline": res["roofline"],
+    }
+    if not args.no_decode:
+        del out, lse
+        line["decode"] = bench_decode(args)
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on a sample")
+        line["cpu_baseline"] = cpu_baseline(x, cfg, args.cpu_rows)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

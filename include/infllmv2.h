@@ -187,6 +187,21 @@ int32_t infllmv2_append_kv(const infllmv2_params *prm, const infllmv2_tensor *k_
                            const infllmv2_tensor *v, const int32_t *seqlens, int32_t batch,
                            int32_t max_seqlen, void *stream);
 
+/*
+ * Per-kernel timing for benchmarks (the measurement the roofline figures are built on).
+ * While enabled, every kernel launched by the entry points above is bracketed by HIP events
+ * recorded on the call's stream; at most 256 launches are kept between reads.  Process-wide
+ * state, not thread-safe; leave it off in production (each launch costs two event records).
+ *   infllmv2_timing_enable  enable != 0 creates the events on the current device on first use
+ *                           and clears the log; 0 switches recording off.
+ *   infllmv2_timing_read    waits for the recorded launches to finish, writes up to max_entries
+ *                           (kernel name, milliseconds) pairs in launch order into the HOST
+ *                           arrays names / ms, clears the log, and returns the count (>= 0) or
+ *                           a negative status.
+ */
+int32_t infllmv2_timing_enable(int32_t enable);
+int32_t infllmv2_timing_read(int32_t max_entries, const char **names, float *ms);
+
 #ifdef __cplusplus
 }
 #endif

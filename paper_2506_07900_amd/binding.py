@@ -26,7 +26,7 @@ MODE_PREFILL, MODE_DECODE = 0, 1
 
 EXPORTS = ["infllmv2_status_string", "infllmv2_workspace_bytes", "infllmv2_compress_keys",
            "infllmv2_select_blocks", "infllmv2_sparse_attn_prefill", "infllmv2_sparse_attn_decode",
-           "infllmv2_append_kv"]
+           "infllmv2_append_kv", "infllmv2_timing_enable", "infllmv2_timing_read"]
 
 
 class CParams(ctypes.Structure):
@@ -98,6 +98,10 @@ def load_library(path=None):
     lib.infllmv2_sparse_attn_decode.argtypes = [P, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
     lib.infllmv2_append_kv.restype = i32
     lib.infllmv2_append_kv.argtypes = [P, T, T, T, T, vp, i32, i32, vp]
+    lib.infllmv2_timing_enable.restype = i32
+    lib.infllmv2_timing_enable.argtypes = [i32]
+    lib.infllmv2_timing_read.restype = i32
+    lib.infllmv2_timing_read.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float)]
     _lib = lib
     return lib
 
@@ -137,6 +141,20 @@ def _i32(t, name):
 
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def timing_enable(enable):
+    _check(load_library().infllmv2_timing_enable(1 if enable else 0), "infllmv2_timing_enable")
+
+
+def timing_read(max_entries=256):
+    """-> list of (kernel name, milliseconds) for the launches recorded since the last read."""
+    names = (ctypes.c_char_p * max_entries)()
+    ms = (ctypes.c_float * max_entries)()
+    n = load_library().infllmv2_timing_read(max_entries, names, ms)
+    if n < 0:
+        _check(n, "infllmv2_timing_read")
+    return [(names[i].decode(), float(ms[i])) for i in range(n)]
 
 
 def num_kernels(seqlen, prm):

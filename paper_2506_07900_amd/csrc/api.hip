@@ -73,7 +73,53 @@ int32_t hip_status(int e) { return e == 0 ? INFLLMV2_OK : INFLLMV2_ERR_HIP; }
 
 }  // namespace
 
+// ---- per-kernel timing ---------------------------------------------------------------------------
+namespace {
+constexpr int kMaxTimed = 256;
+bool g_timing = false;
+int g_timed = 0;
+hipEvent_t g_ev[2 * kMaxTimed];
+bool g_ev_made = false;
+const char *g_names[kMaxTimed];
+}  // namespace
+
+namespace infllmv2 {
+void timing_begin(const char *kernel_name, hipStream_t stream) {
+    if (!g_timing || g_timed >= kMaxTimed) return;
+    g_names[g_timed] = kernel_name;
+    (void)hipEventRecord(g_ev[2 * g_timed], stream);
+}
+void timing_end(hipStream_t stream) {
+    if (!g_timing || g_timed >= kMaxTimed) return;
+    (void)hipEventRecord(g_ev[2 * g_timed + 1], stream);
+    ++g_timed;
+}
+}  // namespace infllmv2
+
 extern "C" {
+
+int32_t infllmv2_timing_enable(int32_t enable) {
+    if (enable && !g_ev_made) {
+        for (int i = 0; i < 2 * kMaxTimed; ++i)
+            if (hipEventCreate(&g_ev[i]) != hipSuccess) return INFLLMV2_ERR_HIP;
+        g_ev_made = true;
+    }
+    g_timing = enable != 0;
+    g_timed = 0;
+    return INFLLMV2_OK;
+}
+
+int32_t infllmv2_timing_read(int32_t max_entries, const char **names, float *ms) {
+    if (max_entries < 0 || (max_entries > 0 && (!names || !ms))) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    const int n = g_timed < max_entries ? g_timed : max_entries;
+    for (int i = 0; i < n; ++i) {
+        if (hipEventSynchronize(g_ev[2 * i + 1]) != hipSuccess) return INFLLMV2_ERR_HIP;
+        if (hipEventElapsedTime(&ms[i], g_ev[2 * i], g_ev[2 * i + 1]) != hipSuccess) return INFLLMV2_ERR_HIP;
+        names[i] = g_names[i];
+    }
+    g_timed = 0;
+    return n;
+}
 
 const char *infllmv2_status_string(int32_t status) {
     switch (status) {

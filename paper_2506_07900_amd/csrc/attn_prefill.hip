@@ -261,8 +261,10 @@ int launch_attn_prefill(const Dims &dm, Tensor q, Tensor k, Tensor v, const int3
     const int32_t n_tiles = (dm.max_seqlen + kQT - 1) / kQT;
     const int64_t n_wg = (int64_t)n_tiles * dm.Hkv * dm.batch;
     if (n_wg <= 0) return 0;
+    timing_begin("attn_prefill_kernel", stream);
     hipLaunchKernelGGL(attn_prefill_kernel, dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, k, v,
                        seqlens, block_idx, out, lse, n_tiles);
+    timing_end(stream);
     return (int)hipGetLastError();
 }
 

@@ -71,6 +71,11 @@ __device__ inline float xgroup_sum(float v) {
     return v;
 }
 
+// Optional per-kernel timing (infllmv2_timing_enable): when on, every launch is bracketed by HIP
+// events on the launch stream.  No-ops when off.
+void timing_begin(const char *kernel_name, hipStream_t stream);
+void timing_end(hipStream_t stream);
+
 // Launchers implemented in the .hip files; each returns a hipError_t as int.
 int launch_compress_keys(const Dims &dm, Tensor k, Tensor ck, const int32_t *seqlens,
                          int32_t n_new_tokens, hipStream_t stream);

@@ -66,8 +66,10 @@ int launch_compress_keys(const Dims &dm, Tensor k, Tensor ck, const int32_t *seq
     }
     if (per_seq <= 0 || dm.batch <= 0) return 0;
     dim3 grid((per_seq + 15) / 16, dm.Hkv, dm.batch);
+    timing_begin("compress_keys_kernel", stream);
     hipLaunchKernelGGL(compress_keys_kernel, grid, dim3(256), 0, stream, dm, k, ck, seqlens,
                        n_new_tokens);
+    timing_end(stream);
     return (int)hipGetLastError();
 }
 
@@ -92,8 +94,10 @@ int launch_append_kv(const Dims &dm, Tensor k_new, Tensor v_new, Tensor k, Tenso
                      const int32_t *seqlens, hipStream_t stream) {
     int rows = dm.batch * dm.Hkv;
     if (rows <= 0) return 0;
+    timing_begin("append_kv_kernel", stream);
     hipLaunchKernelGGL(append_kv_kernel, dim3((rows + 15) / 16), dim3(256), 0, stream, dm, k_new,
                        v_new, k, v, seqlens);
+    timing_end(stream);
     return (int)hipGetLastError();
 }
 

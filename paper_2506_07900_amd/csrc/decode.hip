@@ -323,11 +323,15 @@ int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seq
     DecodeSelLayout l = decode_sel_layout(dm);
     float *zbuf = reinterpret_cast<float *>(ws);
     float2 *part = reinterpret_cast<float2 *>(reinterpret_cast<char *>(ws) + l.z_bytes);
+    timing_begin("decode_logits_kernel", stream);
     hipLaunchKernelGGL(decode_logits_kernel, dim3(l.n_c_cap / 64, dm.Hkv, dm.batch), dim3(256), 0,
                        stream, dm, q, ck, seqlens, zbuf, part, l.n_c_cap, l.n_part);
+    timing_end(stream);
     const size_t lds = select_decode_lds_bytes(dm);
+    timing_begin("decode_topk_kernel", stream);
     hipLaunchKernelGGL(decode_topk_kernel, dim3(dm.Hkv, dm.batch), dim3(1024), lds, stream, dm, seqlens,
                        zbuf, part, l.n_c_cap, l.n_part, l.nb_cap, block_idx);
+    timing_end(stream);
     return (int)hipGetLastError();
 }
 
@@ -343,10 +347,14 @@ int launch_attn_decode(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32
     const size_t o_bytes = align256((size_t)dm.batch * dm.Hq * dm.topk * kHeadDim * sizeof(float));
     float *o_part = reinterpret_cast<float *>(ws);
     float2 *ml_part = reinterpret_cast<float2 *>(reinterpret_cast<char *>(ws) + o_bytes);
+    timing_begin("decode_attn_partial_kernel", stream);
     hipLaunchKernelGGL(decode_attn_partial_kernel, dim3(dm.topk, dm.Hkv, dm.batch), dim3(256), 0, stream,
                        dm, q, k, v, seqlens, block_idx, o_part, ml_part);
+    timing_end(stream);
+    timing_begin("decode_merge_kernel", stream);
     hipLaunchKernelGGL(decode_merge_kernel, dim3(dm.Hq, dm.batch), dim3(128), 0, stream, dm, o_part,
                        ml_part, out, lse);
+    timing_end(stream);
     return (int)hipGetLastError();
 }
 

@@ -326,13 +326,19 @@ static int launch_select_prefill_g(const Dims &dm, Tensor q, Tensor ck, const in
     const int32_t n_tiles = (dm.max_seqlen + C::kTokPerWg - 1) / C::kTokPerWg;
     const int64_t n_wg = (int64_t)n_tiles * dm.Hkv * dm.batch;
     if (n_wg <= 0) return 0;
+    timing_begin("select_lse_kernel", stream);
     hipLaunchKernelGGL(select_lse_kernel<G>, dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, ck,
                        seqlens, lse2, n_tiles);
+    timing_end(stream);
+    timing_begin("select_score_kernel", stream);
     hipLaunchKernelGGL(select_score_kernel<G>, dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, ck,
                        seqlens, lse2, R, nb_cap, n_tiles);
+    timing_end(stream);
     const int64_t rows = (int64_t)dm.batch * dm.Hkv * dm.max_seqlen;
+    timing_begin("select_topk_kernel", stream);
     hipLaunchKernelGGL(select_topk_kernel, dim3((uint32_t)((rows + 3) / 4)), dim3(256), 0, stream, dm,
                        seqlens, R, nb_cap, block_idx);
+    timing_end(stream);
     return (int)hipGetLastError();
 }
 

@@ -149,7 +149,8 @@ int32_t infllmv2_select_blocks(const infllmv2_params *prm, int32_t mode, const i
  *   block_idx  in   int32 [batch, Hkv, max_seqlen, topk]; entries < 0 or > floor(i/m) are skipped;
  *              each row must be duplicate-free
  *   lse        out  fp32 [batch, max_seqlen, Hq] contiguous
- *   workspace  may be NULL when infllmv2_workspace_bytes(INFLLMV2_OP_ATTN_PREFILL, ...) is 0
+ *   workspace  device scratch of infllmv2_workspace_bytes(INFLLMV2_OP_ATTN_PREFILL, ...) bytes
+ *              (a re-laid-out copy of the K and V blocks: 32 KiB per block and key-value head)
  */
 int32_t infllmv2_sparse_attn_prefill(const infllmv2_params *prm, const infllmv2_tensor *q,
                                      const infllmv2_tensor *k, const infllmv2_tensor *v,

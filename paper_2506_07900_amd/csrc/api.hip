@@ -139,7 +139,7 @@ size_t infllmv2_workspace_bytes(int32_t op, const infllmv2_params *prm, int32_t 
     switch (op) {
         case INFLLMV2_OP_SELECT_PREFILL: return select_prefill_ws_bytes(dm);
         case INFLLMV2_OP_SELECT_DECODE: return max_seqlen > kMaxDecodeSeqlen ? 0 : select_decode_ws_bytes(dm);
-        case INFLLMV2_OP_ATTN_PREFILL: return 0;
+        case INFLLMV2_OP_ATTN_PREFILL: return attn_prefill_ws_bytes(dm);
         case INFLLMV2_OP_ATTN_DECODE: return attn_decode_ws_bytes(dm);
     }
     return 0;
@@ -203,8 +203,6 @@ int32_t infllmv2_sparse_attn_prefill(const infllmv2_params *prm, const infllmv2_
                                      const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
                                      const int32_t *block_idx, const infllmv2_tensor *out, float *lse,
                                      void *workspace, size_t workspace_bytes, void *stream) {
-    (void)workspace;
-    (void)workspace_bytes;
     RETURN_IF_ERR(check_params(prm));
     RETURN_IF_ERR(check_sizes(batch, max_seqlen));
     RETURN_IF_ERR(check_tensor(q));
@@ -213,8 +211,12 @@ int32_t infllmv2_sparse_attn_prefill(const infllmv2_params *prm, const infllmv2_
     RETURN_IF_ERR(check_tensor(out));
     if (!seqlens || !block_idx || !lse) return INFLLMV2_ERR_INVALID_ARGUMENT;
     const Dims dm = make_dims(prm, batch, max_seqlen);
+    const size_t need = attn_prefill_ws_bytes(dm);
+    if (need > 0 && (!workspace || workspace_bytes < need ||
+                     (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0))
+        return INFLLMV2_ERR_WORKSPACE;
     return hip_status(launch_attn_prefill(dm, make_tensor(q), make_tensor(k), make_tensor(v), seqlens,
-                                          block_idx, make_tensor(out), lse,
+                                          block_idx, make_tensor(out), lse, workspace,
                                           reinterpret_cast<hipStream_t>(stream)));
 }
 

@@ -88,7 +88,8 @@ int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seq
                          int32_t *block_idx, void *ws, hipStream_t stream);
 size_t select_decode_ws_bytes(const Dims &dm);
 int launch_attn_prefill(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32_t *seqlens,
-                        const int32_t *block_idx, Tensor out, float *lse, hipStream_t stream);
+                        const int32_t *block_idx, Tensor out, float *lse, void *ws, hipStream_t stream);
+size_t attn_prefill_ws_bytes(const Dims &dm);
 int launch_attn_decode(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32_t *seqlens,
                        const int32_t *block_idx, Tensor out, float *lse, void *ws,
                        hipStream_t stream);

@@ -84,7 +84,7 @@ def test_workspace_validation(lib):
     need = lib.infllmv2_workspace_bytes(binding.OP_SELECT_PREFILL, ctypes.byref(prm), 1, 4096)
     # fp32 log-sum-exp per (token, head) + fp32 block scores per (token, kv head, block)
     assert need == 4096 * 32 * 4 + 2 * 4096 * 64 * 4
-    assert lib.infllmv2_workspace_bytes(binding.OP_ATTN_PREFILL, ctypes.byref(prm), 1, 4096) == 0
+    assert lib.infllmv2_workspace_bytes(binding.OP_ATTN_PREFILL, ctypes.byref(prm), 1, 4096) == 2 * 64 * 32768
     assert lib.infllmv2_workspace_bytes(binding.OP_ATTN_DECODE, ctypes.byref(prm), 2, 4096) > 0
     assert lib.infllmv2_workspace_bytes(99, ctypes.byref(prm), 1, 4096) == 0
     q, ck = tensor(), tensor()
@@ -101,6 +101,8 @@ def test_workspace_validation(lib):
                                            FAKE, 1, 4096, FAKE, ctypes.byref(o), FAKE, None, 0, None) == WORKSPACE
     assert lib.infllmv2_sparse_attn_prefill(ctypes.byref(prm), ctypes.byref(q), ctypes.byref(q), ctypes.byref(q),
                                             FAKE, 1, 4096, None, ctypes.byref(o), FAKE, None, 0, None) == INVALID
+    assert lib.infllmv2_sparse_attn_prefill(ctypes.byref(prm), ctypes.byref(q), ctypes.byref(q), ctypes.byref(q),
+                                            FAKE, 1, 4096, FAKE, ctypes.byref(o), FAKE, None, 0, None) == WORKSPACE
 
 
 def test_binding_fails_loudly_without_library(tmp_path):

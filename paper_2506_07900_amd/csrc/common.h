@@ -84,6 +84,9 @@ int launch_append_kv(const Dims &dm, Tensor k_new, Tensor v_new, Tensor k, Tenso
 int launch_select_prefill(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
                           int32_t *block_idx, void *ws, hipStream_t stream);
 size_t select_prefill_ws_bytes(const Dims &dm);
+int launch_select_prefill16(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
+                            int32_t *block_idx, void *ws, hipStream_t stream);
+size_t select_prefill16_ws_bytes(const Dims &dm);
 int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
                          int32_t *block_idx, void *ws, hipStream_t stream);
 size_t select_decode_ws_bytes(const Dims &dm);

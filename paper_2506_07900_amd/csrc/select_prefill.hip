@@ -307,6 +307,7 @@ __global__ __launch_bounds__(256) void select_topk_kernel(Dims dm, const int32_t
 }
 
 size_t select_prefill_ws_bytes(const Dims &dm) {
+    if (dm.G == 16) return select_prefill16_ws_bytes(dm);
     const size_t nb_cap = ((size_t)(dm.max_seqlen + kBlock - 1) / kBlock + 15) / 16 * 16;
     size_t lse = (size_t)dm.batch * dm.max_seqlen * dm.Hq * sizeof(float);
     lse = (lse + 255) / 256 * 256;
@@ -349,7 +350,7 @@ int launch_select_prefill(const Dims &dm, Tensor q, Tensor ck, const int32_t *se
         case 2: return launch_select_prefill_g<2>(dm, q, ck, seqlens, block_idx, ws, stream);
         case 4: return launch_select_prefill_g<4>(dm, q, ck, seqlens, block_idx, ws, stream);
         case 8: return launch_select_prefill_g<8>(dm, q, ck, seqlens, block_idx, ws, stream);
-        case 16: return launch_select_prefill_g<16>(dm, q, ck, seqlens, block_idx, ws, stream);
+        case 16: return launch_select_prefill16(dm, q, ck, seqlens, block_idx, ws, stream);
     }
     return (int)hipErrorInvalidValue;
 }

@@ -103,7 +103,7 @@ def bench_prefill(args):
 
     flops_of = {"attn_prefill_kernel": attended_flops, "select_lse_kernel": score_flops,
                 "select_score_kernel": score_flops, "select_lse16_kernel": score_flops,
-                "select_topk16_kernel": score_flops}
+                "select_score16_kernel": score_flops}
     dominant = max(kern_ms, key=kern_ms.get)
     if dominant in flops_of:
         ach = flops_of[dominant] / (kern_ms[dominant] * 1e-3) / 1e12

@@ -254,11 +254,103 @@ __global__ __launch_bounds__(256) void select_score_kernel(Dims dm, Tensor q, Te
 }
 
 // ---- top-k: one wavefront per (sequence, key-value head, token) row of block scores ------------
-// Picks follow the total order (score descending, index ascending); pick c is the largest entry
-// strictly after pick c-1 in that order, so no "taken" flags are needed.
-__global__ __launch_bounds__(256) void select_topk_kernel(Dims dm, const int32_t *__restrict__ seqlens,
+// Candidates are the blocks n_init .. b_own - n_local; the forced ones are added afterwards.
+// Scores are positive floats, so their bit patterns order like unsigned integers: key = bits of
+// the score, 1 for a block without visible kernel (-inf), 0 for "not a candidate / taken".
+// Lane l keeps blocks l, l+64, ... in registers and its best (key, slot); each of the n_pick
+// rounds takes the wave-wide best (ties: lowest block index) and retires it.
+template <int VPL>
+__global__ __launch_bounds__(256) void select_pick_kernel(Dims dm, const int32_t *__restrict__ seqlens,
                                                            const float *__restrict__ R, int32_t nb_cap,
                                                            int32_t *__restrict__ block_idx) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t rows = (int64_t)dm.batch * dm.Hkv * dm.max_seqlen;
+    if (row >= rows) return;
+    const int tok = row % dm.max_seqlen;
+    const int b = row / ((int64_t)dm.max_seqlen * dm.Hkv);
+    int32_t L = seqlens[b];
+    L = L < 0 ? 0 : (L > dm.max_seqlen ? dm.max_seqlen : L);
+    if (tok >= L) return;
+    const int b_own = tok / kBlock, n_blk = b_own + 1;
+    const int n_sel = dm.topk < n_blk ? dm.topk : n_blk;
+    const int n_init = dm.n_init < n_blk ? dm.n_init : n_blk;                 // forced leading blocks
+    const int lo_local = max(n_init, b_own - dm.n_local + 1);                 // forced trailing: lo_local..b_own
+    const int jc_max = lo_local - 1;                                          // candidates: n_init..jc_max
+    const int n_pick = n_sel - (n_init + (b_own - lo_local + 1));
+    int mine = 0x7fffffff;                                                    // lane c keeps pick c
+    if (n_pick > 0) {
+        const float *Rr = R + row * nb_cap;
+        uint32_t key[VPL];
+#pragma unroll
+        for (int s = 0; s < VPL; ++s) {
+            const int j = lane + 64 * s;
+            key[s] = 0u;
+            if (j >= n_init && j <= jc_max) {
+                const float r = Rr[j];
+                key[s] = r == -INFINITY ? 1u : __float_as_uint(r);
+            }
+        }
+        uint32_t lb_key = 0u;
+        int lb_slot = 0;
+#pragma unroll
+        for (int s = VPL - 1; s >= 0; --s)
+            if (key[s] >= lb_key) {
+                lb_key = key[s];
+                lb_slot = s;
+            }
+        for (int c = 0; c < n_pick; ++c) {
+            // wave-wide maximum key: row maxima by DPP shifts, then the four rows through scalars
+            uint32_t m = lb_key;
+            m = max(m, (uint32_t)__builtin_amdgcn_update_dpp((int)m, (int)m, 0x111, 0xf, 0xf, false));
+            m = max(m, (uint32_t)__builtin_amdgcn_update_dpp((int)m, (int)m, 0x112, 0xf, 0xf, false));
+            m = max(m, (uint32_t)__builtin_amdgcn_update_dpp((int)m, (int)m, 0x114, 0xf, 0xf, false));
+            m = max(m, (uint32_t)__builtin_amdgcn_update_dpp((int)m, (int)m, 0x118, 0xf, 0xf, false));
+            const uint32_t k0 = __builtin_amdgcn_readlane(m, 15), k1 = __builtin_amdgcn_readlane(m, 31);
+            const uint32_t k2 = __builtin_amdgcn_readlane(m, 47), k3 = __builtin_amdgcn_readlane(m, 63);
+            const uint32_t kmax = max(max(k0, k1), max(k2, k3));
+            uint64_t who = __ballot(lb_key == kmax);
+            int wl = __builtin_ctzll(who);
+            int wslot = __builtin_amdgcn_readlane(lb_slot, wl);
+            who &= who - 1;
+            while (who) {                                                     // exact ties: lowest block index
+                const int l2 = __builtin_ctzll(who);
+                who &= who - 1;
+                const int s2 = __builtin_amdgcn_readlane(lb_slot, l2);
+                if (l2 + 64 * s2 < wl + 64 * wslot) {
+                    wl = l2;
+                    wslot = s2;
+                }
+            }
+            if (lane == c) mine = wl + 64 * wslot;
+            const bool me = lane == wl;
+            lb_key = me ? 0u : lb_key;
+#pragma unroll
+            for (int s = VPL - 1; s >= 0; --s) {
+                if (me && s == wslot) key[s] = 0u;
+                if (me && key[s] >= lb_key) {
+                    lb_key = key[s];
+                    lb_slot = s;
+                }
+            }
+        }
+    }
+    if (lane >= n_pick && lane < n_sel) {
+        const int f = lane - n_pick;
+        mine = f < n_init ? f : lo_local + (f - n_init);
+    }
+    // ascending order: rank = number of selected blocks below mine
+    int rank = 0;
+    for (int e = 0; e < n_sel; ++e) rank += __builtin_amdgcn_readlane(mine, e) < mine ? 1 : 0;
+    int32_t *o = block_idx + row * dm.topk;
+    if (lane < n_sel) o[rank] = mine;
+    else if (lane < dm.topk) o[lane] = -1;
+}
+
+// Fallback for rows longer than 64*32 blocks: scans the row in memory once per pick.
+__global__ __launch_bounds__(256) void select_pick_scan_kernel(Dims dm, const int32_t *__restrict__ seqlens,
+                                                                const float *__restrict__ R, int32_t nb_cap,
+                                                                int32_t *__restrict__ block_idx) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t rows = (int64_t)dm.batch * dm.Hkv * dm.max_seqlen;
@@ -273,7 +365,7 @@ __global__ __launch_bounds__(256) void select_topk_kernel(Dims dm, const int32_t
     const float *Rr = R + row * nb_cap;
     float last_s = INFINITY;
     int last_j = -1;
-    int mine = 0x7fffffff;                  // lane c keeps pick c
+    int mine = 0x7fffffff;
     for (int c = 0; c < n_sel; ++c) {
         float best_s = -INFINITY;
         int best_j = 0x7fffffff;
@@ -298,7 +390,6 @@ __global__ __launch_bounds__(256) void select_topk_kernel(Dims dm, const int32_t
         last_j = best_j;
         if (lane == c) mine = best_j;
     }
-    // ascending order: rank = number of picks below mine
     int rank = 0;
     for (int c = 0; c < n_sel; ++c) rank += __shfl(mine, c) < mine ? 1 : 0;
     int32_t *o = block_idx + row * dm.topk;
@@ -306,20 +397,46 @@ __global__ __launch_bounds__(256) void select_topk_kernel(Dims dm, const int32_t
     else if (lane < dm.topk) o[lane] = -1;
 }
 
+int32_t select_scores_pitch(const Dims &dm) {
+    return (int32_t)(((size_t)(dm.max_seqlen + kBlock - 1) / kBlock + 15) / 16 * 16);
+}
+size_t select_scores_bytes(const Dims &dm) {
+    return (size_t)dm.batch * dm.Hkv * dm.max_seqlen * select_scores_pitch(dm) * sizeof(float);
+}
+
+int launch_select_pick(const Dims &dm, const int32_t *seqlens, const float *R, int32_t nb_cap,
+                       int32_t *block_idx, hipStream_t stream) {
+    const int64_t rows = (int64_t)dm.batch * dm.Hkv * dm.max_seqlen;
+    if (rows <= 0) return 0;
+    const dim3 grid((uint32_t)((rows + 3) / 4));
+    const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
+    timing_begin("select_pick_kernel", stream);
+    if (n_blocks <= 64 * 4)
+        hipLaunchKernelGGL(select_pick_kernel<4>, grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+    else if (n_blocks <= 64 * 8)
+        hipLaunchKernelGGL(select_pick_kernel<8>, grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+    else if (n_blocks <= 64 * 16)
+        hipLaunchKernelGGL(select_pick_kernel<16>, grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+    else if (n_blocks <= 64 * 32)
+        hipLaunchKernelGGL(select_pick_kernel<32>, grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+    else
+        hipLaunchKernelGGL(select_pick_scan_kernel, grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+    timing_end(stream);
+    return (int)hipGetLastError();
+}
+
 size_t select_prefill_ws_bytes(const Dims &dm) {
     if (dm.G == 16) return select_prefill16_ws_bytes(dm);
-    const size_t nb_cap = ((size_t)(dm.max_seqlen + kBlock - 1) / kBlock + 15) / 16 * 16;
     size_t lse = (size_t)dm.batch * dm.max_seqlen * dm.Hq * sizeof(float);
     lse = (lse + 255) / 256 * 256;
-    const size_t r = (size_t)dm.batch * dm.Hkv * dm.max_seqlen * nb_cap * sizeof(float);
-    return lse + r;
+    return lse + select_scores_bytes(dm);
 }
 
 template <int G>
 static int launch_select_prefill_g(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
                                    int32_t *block_idx, void *ws, hipStream_t stream) {
     using C = SelCfg<G>;
-    const int32_t nb_cap = (int32_t)(((size_t)(dm.max_seqlen + kBlock - 1) / kBlock + 15) / 16 * 16);
+    const int32_t nb_cap = select_scores_pitch(dm);
     size_t lse_bytes = (size_t)dm.batch * dm.max_seqlen * dm.Hq * sizeof(float);
     lse_bytes = (lse_bytes + 255) / 256 * 256;
     float *lse2 = reinterpret_cast<float *>(ws);
@@ -335,12 +452,7 @@ static int launch_select_prefill_g(const Dims &dm, Tensor q, Tensor ck, const in
     hipLaunchKernelGGL(select_score_kernel<G>, dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, ck,
                        seqlens, lse2, R, nb_cap, n_tiles);
     timing_end(stream);
-    const int64_t rows = (int64_t)dm.batch * dm.Hkv * dm.max_seqlen;
-    timing_begin("select_topk_kernel", stream);
-    hipLaunchKernelGGL(select_topk_kernel, dim3((uint32_t)((rows + 3) / 4)), dim3(256), 0, stream, dm,
-                       seqlens, R, nb_cap, block_idx);
-    timing_end(stream);
-    return (int)hipGetLastError();
+    return launch_select_pick(dm, seqlens, R, nb_cap, block_idx, stream);
 }
 
 int launch_select_prefill(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,

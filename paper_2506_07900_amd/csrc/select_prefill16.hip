@@ -5,9 +5,9 @@
 //   pack_ck_kernel        compressed keys -> fragment-major copy (a wavefront reads the operand
 //                         of one 16-kernel tile as four coalesced 1 KiB loads, no LDS)
 //   select_lse16_kernel   pass 1: log-sum-exp of every (token, head) row over its visible kernels
-//   select_topk16_kernel  pass 2: scores 2^(z - lse), mean over the 16 heads, 5-wide / stride-4
-//                         max over kernels -> block scores, and a streaming top-k kept in
-//                         registers (one list entry per lane), then forced blocks and the sort
+//   select_score16_kernel pass 2: scores 2^(z - lse), mean over the 16 heads, 5-wide / stride-4
+//                         max over kernels -> block scores of the candidate blocks
+// followed by select_pick_kernel (select_prefill.hip), the row-parallel top-k.
 //
 // A wavefront owns 8 consecutive tokens and works alone (no LDS, no barriers).  MFMA and plain
 // VALU work only overlap on this hardware when they alternate inside one instruction stream, so
@@ -188,14 +188,15 @@ __global__ __launch_bounds__(256) void select_lse16_kernel(Dims dm, Tensor q, co
     }
 }
 
-// ---- pass 2 + top-k --------------------------------------------------------------------------------
+// ---- pass 2 ----------------------------------------------------------------------------------------
 // Z = Q . CK^T: lane = kernel n of the tile, accumulator entries = heads 4g..4g+3 of the token.
-// Candidate keys: a block score (>= 2^-100), -1 for a block with no visible kernel, -2 for an
-// empty list slot.  List entry e of a token lives in lane e.
-__global__ __launch_bounds__(256) void select_topk16_kernel(Dims dm, Tensor q, const uint4 *__restrict__ ckp,
-                                                             int32_t nt_cap, const int32_t *__restrict__ seqlens,
-                                                             const float *__restrict__ lse2,
-                                                             int32_t *__restrict__ block_idx, int32_t n_tiles) {
+// Writes the block scores R[token, j] of the candidate blocks j in [n_init, b_own - n_local]
+// (-inf when no visible kernel intersects the block); select_pick_kernel ranks them.
+__global__ __launch_bounds__(256) void select_score16_kernel(Dims dm, Tensor q, const uint4 *__restrict__ ckp,
+                                                              int32_t nt_cap, const int32_t *__restrict__ seqlens,
+                                                              const float *__restrict__ lse2,
+                                                              float *__restrict__ R, int32_t nb_cap,
+                                                              int32_t n_tiles) {
     const int tile = n_tiles - 1 - (int)(blockIdx.x % n_tiles);
     const int h = (blockIdx.x / n_tiles) % dm.Hkv;
     const int b = blockIdx.x / (n_tiles * dm.Hkv);
@@ -207,201 +208,114 @@ __global__ __launch_bounds__(256) void select_topk16_kernel(Dims dm, Tensor q, c
     const int n = lane & 15, g = lane >> 4;
     const float c = dm.scale_log2;
 
-    // the 8 tokens share their own block (8 divides 64), hence the forced set and the pick count
+    // the 8 tokens share their own block (8 divides 64), hence the candidate range
     const int b_own = t0 / kBlock, n_blk = b_own + 1;
+    const int n_init = dm.n_init < n_blk ? dm.n_init : n_blk;
+    const int jc_max = max(n_init, b_own - dm.n_local + 1) - 1;               // candidates: n_init..jc_max
     const int n_sel = dm.topk < n_blk ? dm.topk : n_blk;
-    const int n_init = dm.n_init < n_blk ? dm.n_init : n_blk;                 // forced leading blocks
-    const int lo_local = max(n_init, b_own - dm.n_local + 1);                 // forced trailing: lo_local..b_own
-    const int n_forced = n_init + (b_own - lo_local + 1);
-    const int n_pick = n_sel - n_forced;                                      // scored picks, >= 0
-    const int jc_max = lo_local - 1;                                          // candidates: n_init..jc_max
+    const int n_pick = n_sel - (n_init + (b_own - jc_max));
+    if (n_pick <= 0 || jc_max < n_init) return;                               // forced blocks only
 
-    float list_s[kMT];
-    int list_i[kMT];
+    bf16x8 qf[kMT][4];
+    load_q16(qf, q, b, h, t0, L, n, g);
+    float lse_r[kMT][4];                                                      // heads 4g+j of token mt
 #pragma unroll
-    for (int mt = 0; mt < kMT; ++mt) {
-        list_s[mt] = -2.f;
-        list_i[mt] = 0x7fffffff;
+    for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            lse_r[mt][j] = (t0 + mt < L) ? -lse2[((int64_t)b * dm.max_seqlen + t0 + mt) * dm.Hq + h * 16 + 4 * g + j]
+                                          : 0.f;
+    const int nvis_lo = n_visible16(t0);
+    const int nt_full = nvis_lo >> 4;                                         // tiles needing no mask
+    const int nt_all = min((4 * jc_max + 4 + 15) >> 4, nt_cap);               // tiles that hold candidate kernels
+    if (nt_all <= 0) return;
+    const uint4 *ckp_head = ckp + ((int64_t)b * dm.Hkv + h) * nt_cap * 256;
+    // packed per-token values: 16-lane group g of register [i] belongs to token 4i+g
+    float prev_v[2] = {-INFINITY, -INFINITY};
+    float *Rrow[2];
+    bool wr[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int tok = t0 + 4 * i + g;
+        Rrow[i] = R + (((int64_t)b * dm.Hkv + h) * dm.max_seqlen + tok) * nb_cap + (n >> 2);
+        wr[i] = ((n & 3) == 0) && tok < L;
     }
 
-    if (n_pick > 0) {
-        bf16x8 qf[kMT][4];
-        load_q16(qf, q, b, h, t0, L, n, g);
-        float lse_r[kMT][4];                                                  // heads 4g+j of token mt
+    auto mfma_tile = [&](const Frag4 &fr, f32x4 (&z)[kMT]) {
 #pragma unroll
-        for (int mt = 0; mt < kMT; ++mt)
+        for (int mt = 0; mt < kMT; ++mt) z[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                lse_r[mt][j] = (t0 + mt < L) ? lse2[((int64_t)b * dm.max_seqlen + t0 + mt) * dm.Hq + h * 16 + 4 * g + j]
-                                              : 0.f;
-        const int nvis_lo = n_visible16(t0);
-        const int nt_full = nvis_lo >> 4;                                     // tiles needing no mask
-        const int nt_all = min((4 * jc_max + 4 + 15) >> 4, nt_cap);           // tiles that hold candidate kernels
-        const uint4 *ckp_head = ckp + ((int64_t)b * dm.Hkv + h) * nt_cap * 256;
-        // packed per-token state: 16-lane group g of register [i] belongs to token 4i+g
-        float tau[2] = {-2.f, -2.f};
-        float prev_v[2] = {-INFINITY, -INFINITY};
-
-        auto mfma_tile = [&](const Frag4 &fr, f32x4 (&z)[kMT]) {
+        for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-            for (int mt = 0; mt < kMT; ++mt) z[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int mt = 0; mt < kMT; ++mt)
+                z[mt] = mfma16(qf[mt][ks], __builtin_bit_cast(bf16x8, fr.f[ks]), z[mt]);
+    };
+    // scores of tile t: mean over heads, floor, causal mask, 5-wide / stride-4 max -> lanes
+    // n = 0,4,8,12 hold blocks 4t + n/4, which are written out
+    auto finish_tile = [&](const f32x4 (&z)[kMT], int t, bool masked) {
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
+        for (int i = 0; i < 2; ++i) {
+            float v = 0.f;
 #pragma unroll
-                for (int mt = 0; mt < kMT; ++mt)
-                    z[mt] = mfma16(qf[mt][ks], __builtin_bit_cast(bf16x8, fr.f[ks]), z[mt]);
-        };
-        // scores of tile t for the 8 tokens -> packed kernel scores v[i] (group g = token 4i+g)
-        auto scores = [&](const f32x4 (&z)[kMT], int t, bool masked, float (&v)[2]) {
+            for (int gg = 0; gg < 4; ++gg) {
+                const int mt = 4 * i + gg;
+                float e = 0.f;
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                float acc = 0.f;
-#pragma unroll
-                for (int gg = 0; gg < 4; ++gg) {
-                    const int mt = 4 * i + gg;
-                    float e = 0.f;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) e += fast_exp2(__builtin_fmaf(z[mt][j], c, -lse_r[mt][j]));
-                    e = xgroup_sum(e);                                        // all 16 heads, every group
-                    e = fmaxf(e * (1.f / 16.f), kScoreFloor);
-                    if (masked && 16 * t + n >= n_visible16(t0 + mt)) e = -INFINITY;
-                    acc = (g == gg) ? e : acc;
-                }
-                v[i] = acc;
+                for (int j = 0; j < 4; ++j) e += fast_exp2(__builtin_fmaf(z[mt][j], c, lse_r[mt][j]));
+                e = xgroup_sum(e);                                            // all 16 heads, in every group
+                v = (g == gg) ? e : v;
             }
-        };
-        // 5-wide / stride-4 max over kernels -> lanes n = 0,4,8,12 hold blocks 4t + n/4; insert
-        // into the lists whatever beats the current k-th best
-        auto pool_and_insert = [&](float (&v)[2], int t) {
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const float a = fmaxf(v[i], dpp_f32<kRowShl1>(v[i], v[i]));
-                const float bq = fmaxf(a, dpp_f32<kRowShl2>(a, a));
-                const float halo0 = dpp_f32<kRowRor1>(prev_v[i], prev_v[i]);  // lane 0 <- previous tile's lane 15
-                const float halo = dpp_f32<kRowShr1>(halo0, v[i]);            // lane n <- v[n-1]
-                float w = fmaxf(bq, halo);
-                prev_v[i] = v[i];
-                const int j = 4 * t + (n >> 2);
-                w = (w == -INFINITY) ? -1.f : w;
-                const bool cand = ((n & 3) == 0) && j >= n_init && j <= jc_max && (t0 + 4 * i + g) < L;
-                uint64_t todo = __ballot(cand && w > tau[i]);
-                while (todo) {                                                // rare after warm-up
-                    const int src = __builtin_ctzll(todo);
-                    todo &= todo - 1;
-                    const int tk = 4 * i + (src >> 4);
-                    const float cs = __shfl(w, src);
-                    const int cj = 4 * t + ((src & 15) >> 2);
-#pragma unroll
-                    for (int u = 0; u < kMT; ++u) {
-                        if (tk != u) continue;
-                        const float kth = __shfl(list_s[u], n_pick - 1);
-                        if (cs > kth) {
-                            const int pos = __popcll(__ballot(list_s[u] >= cs));
-                            const float up_s = __shfl_up(list_s[u], 1);
-                            const int up_i = __shfl_up(list_i[u], 1);
-                            if (lane == pos) {
-                                list_s[u] = cs;
-                                list_i[u] = cj;
-                            } else if (lane > pos) {
-                                list_s[u] = up_s;
-                                list_i[u] = up_i;
-                            }
-                        }
-                    }
-                }
-            }
-            // refresh the packed thresholds (cheap, and only the inserting path changes them)
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                float tv = tau[i];
-#pragma unroll
-                for (int gg = 0; gg < 4; ++gg) {
-                    const float kth = __shfl(list_s[4 * i + gg], n_pick - 1);
-                    tv = (g == gg) ? kth : tv;
-                }
-                tau[i] = tv;
-            }
-        };
-        auto pool_only = [&](float (&v)[2], int t) {                          // fast path check, no refresh
-            bool hit = false;
-            float w2[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const float a = fmaxf(v[i], dpp_f32<kRowShl1>(v[i], v[i]));
-                const float bq = fmaxf(a, dpp_f32<kRowShl2>(a, a));
-                const float halo0 = dpp_f32<kRowRor1>(prev_v[i], prev_v[i]);
-                const float halo = dpp_f32<kRowShr1>(halo0, v[i]);
-                float w = fmaxf(bq, halo);
-                w = (w == -INFINITY) ? -1.f : w;
-                w2[i] = w;
-                const int j = 4 * t + (n >> 2);
-                const bool cand = ((n & 3) == 0) && j >= n_init && j <= jc_max && (t0 + 4 * i + g) < L;
-                hit |= cand && w > tau[i];
-            }
-            return __any(hit);
-        };
-
-        if (nt_all > 0) {
-            const int nt_pipe = min(nt_full, nt_all);
-            Frag4 fr = load_ck_tile(ckp_head, 0, lane);
-            Frag4 fr_next = fr;
-            if (nt_all > 1) fr_next = load_ck_tile(ckp_head, 1, lane);
-            f32x4 z_prev[kMT];
-            mfma_tile(fr, z_prev);
-            for (int t = 1; t < nt_all; ++t) {
-                fr = fr_next;
-                if (t + 1 < nt_all) fr_next = load_ck_tile(ckp_head, t + 1, lane);
-                f32x4 z[kMT];
-                float v[2];
-                mfma_tile(fr, z);                     // matrix work of tile t ...
-                scores(z_prev, t - 1, t - 1 >= nt_pipe, v);   // ... alternates with the scores of tile t-1
-                if (pool_only(v, t - 1)) pool_and_insert(v, t - 1);
-                else {
-                    prev_v[0] = v[0];
-                    prev_v[1] = v[1];
-                }
-#pragma unroll
-                for (int mt = 0; mt < kMT; ++mt) z_prev[mt] = z[mt];
-            }
-            float v[2];
-            scores(z_prev, nt_all - 1, nt_all - 1 >= nt_pipe, v);
-            pool_and_insert(v, nt_all - 1);
+            v = fmaxf(v * (1.f / 16.f), kScoreFloor);
+            if (masked && 16 * t + n >= n_visible16(t0 + 4 * i + g)) v = -INFINITY;   // kernel not visible
+            const float a = fmaxf(v, dpp_f32<kRowShl1>(v, v));
+            const float bq = fmaxf(a, dpp_f32<kRowShl2>(a, a));
+            const float halo0 = dpp_f32<kRowRor1>(prev_v[i], prev_v[i]);      // lane 0 <- previous tile's lane 15
+            const float halo = dpp_f32<kRowShr1>(halo0, v);                   // lane n <- v[n-1]
+            const float w = fmaxf(bq, halo);
+            prev_v[i] = v;
+            const int j = 4 * t + (n >> 2);
+            if (wr[i] && j >= n_init && j <= jc_max) Rrow[i][4 * t] = w;
         }
-    }
+    };
 
-    // ---- forced blocks, ascending order, -1 padding ----------------------------------------------------
+    const int nt_pipe = min(nt_full, nt_all);
+    Frag4 fr = load_ck_tile(ckp_head, 0, lane);
+    Frag4 fr_next = fr;
+    if (nt_all > 1) fr_next = load_ck_tile(ckp_head, 1, lane);
+    f32x4 z_prev[kMT];
+    mfma_tile(fr, z_prev);
+    for (int t = 1; t < nt_all; ++t) {
+        fr = fr_next;
+        if (t + 1 < nt_all) fr_next = load_ck_tile(ckp_head, t + 1, lane);
+        f32x4 z[kMT];
+        mfma_tile(fr, z);                              // matrix work of tile t ...
+        finish_tile(z_prev, t - 1, t - 1 >= nt_pipe);  // ... alternates with the epilogue of tile t-1
 #pragma unroll
-    for (int mt = 0; mt < kMT; ++mt) {
-        const int tok = t0 + mt;
-        if (tok >= L) continue;
-        int mine = 0x7fffffff;
-        if (lane < n_pick) mine = list_i[mt];
-        else if (lane < n_sel) {
-            const int f = lane - n_pick;
-            mine = f < n_init ? f : lo_local + (f - n_init);
-        }
-        int rank = 0;
-        for (int e = 0; e < n_sel; ++e) rank += __shfl(mine, e) < mine ? 1 : 0;
-        int32_t *o = block_idx + (((int64_t)b * dm.Hkv + h) * dm.max_seqlen + tok) * dm.topk;
-        if (lane < n_sel) o[rank] = mine;
-        else if (lane < dm.topk) o[lane] = -1;
+        for (int mt = 0; mt < kMT; ++mt) z_prev[mt] = z[mt];
     }
+    finish_tile(z_prev, nt_all - 1, nt_all - 1 >= nt_pipe);
 }
 
 size_t select_prefill16_ws_bytes(const Dims &dm) {
     size_t lse = (size_t)dm.batch * dm.max_seqlen * dm.Hq * sizeof(float);
     lse = (lse + 255) / 256 * 256;
     const size_t nt_cap = ((size_t)num_kernels(dm.max_seqlen) + 15) / 16;
-    return lse + (size_t)dm.batch * dm.Hkv * nt_cap * 256 * sizeof(uint4);
+    size_t ckp = (size_t)dm.batch * dm.Hkv * nt_cap * 256 * sizeof(uint4);
+    ckp = (ckp + 255) / 256 * 256;
+    return lse + ckp + select_scores_bytes(dm);
 }
 
 int launch_select_prefill16(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens, int32_t *block_idx,
                             void *ws, hipStream_t stream) {
     size_t lse_bytes = (size_t)dm.batch * dm.max_seqlen * dm.Hq * sizeof(float);
     lse_bytes = (lse_bytes + 255) / 256 * 256;
+    const int32_t nt_cap = (num_kernels(dm.max_seqlen) + 15) / 16;
+    size_t ckp_bytes = (size_t)dm.batch * dm.Hkv * nt_cap * 256 * sizeof(uint4);
+    ckp_bytes = (ckp_bytes + 255) / 256 * 256;
     float *lse2 = reinterpret_cast<float *>(ws);
     uint4 *ckp = reinterpret_cast<uint4 *>(reinterpret_cast<char *>(ws) + lse_bytes);
-    const int32_t nt_cap = (num_kernels(dm.max_seqlen) + 15) / 16;
+    float *R = reinterpret_cast<float *>(reinterpret_cast<char *>(ws) + lse_bytes + ckp_bytes);
+    const int32_t nb_cap = select_scores_pitch(dm);
     const int32_t n_tiles = (dm.max_seqlen + kTokPerWg16 - 1) / kTokPerWg16;
     const int64_t n_wg = (int64_t)n_tiles * dm.Hkv * dm.batch;
     if (n_wg <= 0) return 0;
@@ -414,12 +328,12 @@ int launch_select_prefill16(const Dims &dm, Tensor q, Tensor ck, const int32_t *
         hipLaunchKernelGGL(select_lse16_kernel, dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, ckp, nt_cap,
                            seqlens, lse2, n_tiles);
         timing_end(stream);
+        timing_begin("select_score16_kernel", stream);
+        hipLaunchKernelGGL(select_score16_kernel, dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, ckp, nt_cap,
+                           seqlens, lse2, R, nb_cap, n_tiles);
+        timing_end(stream);
     }
-    timing_begin("select_topk16_kernel", stream);
-    hipLaunchKernelGGL(select_topk16_kernel, dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, ckp, nt_cap,
-                       seqlens, lse2, block_idx, n_tiles);
-    timing_end(stream);
-    return (int)hipGetLastError();
+    return launch_select_pick(dm, seqlens, R, nb_cap, block_idx, stream);
 }
 
 }  // namespace infllmv2

@@ -75,9 +75,33 @@ __device__ inline void load_q16(bf16x8 (&qf)[kMT][4], const Tensor &q, int b, in
     }
 }
 
+// ---- shared pieces of the two passes -------------------------------------------------------------------
+// The 8 tokens of a wavefront are handled as two halves of 4 (A: tokens 0..3, B: 4..7) that
+// ping-pong: while the matrix cores work on one half of kernel tile t, the vector ALU finishes the
+// other half's previous results, inside one basic block.
+constexpr int kHalf = 4;
+
+// 16 MFMAs: logits of one 16-kernel tile against 4 tokens.  kKeysAreRows picks the orientation:
+//   true   Z^T = CK . Q^T   lane = (head n), accumulator entries = kernels 4g..4g+3
+//   false  Z   = Q . CK^T   lane = (kernel n), accumulator entries = heads 4g..4g+3
+template <bool kKeysAreRows>
+__device__ inline void mfma_half(const Frag4 &fr, const bf16x8 (&qf)[kMT][4], int base, f32x4 (&z)[kHalf]) {
+#pragma unroll
+    for (int u = 0; u < kHalf; ++u) z[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int u = 0; u < kHalf; ++u) {
+            const bf16x8 ckf = __builtin_bit_cast(bf16x8, fr.f[ks]);
+            z[u] = kKeysAreRows ? mfma16(ckf, qf[base + u][ks], z[u]) : mfma16(qf[base + u][ks], ckf, z[u]);
+        }
+}
+
 // ---- pass 1 ------------------------------------------------------------------------------------------
-// Z^T = CK . Q^T: lane = (token mt, head n) row, its 4 accumulator entries are kernels 4g..4g+3 of
-// the tile, so the running sum is lane-local until the final merge of the four 16-lane groups.
+// Lane = one (token, head) row; it sums 2^(z*c - m_ref) over its own kernels (4 per tile) and the
+// four 16-lane groups are merged at the end.  m_ref is a logit of the row itself, re-based only
+// when a partial sum leaves the safe range, so the common path has no max tracking at all:
+// neg_m = -m_ref starts as NaN, which sends the first tile through the re-basing path.
 __global__ __launch_bounds__(256) void select_lse16_kernel(Dims dm, Tensor q, const uint4 *__restrict__ ckp,
                                                             int32_t nt_cap, const int32_t *__restrict__ seqlens,
                                                             float *__restrict__ lse2, int32_t n_tiles) {
@@ -94,11 +118,10 @@ __global__ __launch_bounds__(256) void select_lse16_kernel(Dims dm, Tensor q, co
 
     bf16x8 qf[kMT][4];
     load_q16(qf, q, b, h, t0, L, n, g);
-    float m_ref[kMT], neg_m[kMT], s_run[kMT];     // neg_m = -m_ref, or 0 while the row has seen nothing
+    float neg_m[kMT], s_run[kMT];
 #pragma unroll
     for (int mt = 0; mt < kMT; ++mt) {
-        m_ref[mt] = -INFINITY;
-        neg_m[mt] = 0.f;
+        neg_m[mt] = __builtin_nanf("");
         s_run[mt] = 0.f;
     }
     const int last_tok = min(t0 + kMT, (int)L) - 1;
@@ -107,91 +130,87 @@ __global__ __launch_bounds__(256) void select_lse16_kernel(Dims dm, Tensor q, co
     const int nt_all = (nvis_hi + 15) >> 4;
     const uint4 *ckp_head = ckp + ((int64_t)b * dm.Hkv + h) * nt_cap * 256;
 
-    auto mfma_tile = [&](const Frag4 &fr, f32x4 (&z)[kMT]) {
+    auto finish = [&](const f32x4 (&z)[kHalf], int base) {
+        float acc[kHalf];
+        bool bad = false;
 #pragma unroll
-        for (int mt = 0; mt < kMT; ++mt) z[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int u = 0; u < kHalf; ++u) {
+            float a = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int mt = 0; mt < kMT; ++mt)
-                z[mt] = mfma16(__builtin_bit_cast(bf16x8, fr.f[ks]), qf[mt][ks], z[mt]);
-    };
-    // re-base the exponent reference of any row whose new logits exceed it by the slack (rare)
-    auto check_rescale = [&](const f32x4 (&z)[kMT]) {
-        bool any = false;
-        float tmax[kMT];
-#pragma unroll
-        for (int mt = 0; mt < kMT; ++mt) {
-            tmax[mt] = fmaxf(fmaxf(z[mt][0], z[mt][1]), fmaxf(z[mt][2], z[mt][3])) * c;
-            any |= tmax[mt] > m_ref[mt] + kRescaleSlack;
+            for (int j = 0; j < 4; ++j) a += fast_exp2(__builtin_fmaf(z[u][j], c, neg_m[base + u]));
+            acc[u] = a;
+            bad |= !(a <= 0x1p60f);                      // too large, inf, or NaN (no reference yet)
         }
-        if (__any(any)) {
+        if (__any(bad)) {                                // rare: re-base on this tile's own maximum
 #pragma unroll
-            for (int mt = 0; mt < kMT; ++mt)
-                if (tmax[mt] > m_ref[mt] + kRescaleSlack) {
-                    s_run[mt] *= fast_exp2(m_ref[mt] - tmax[mt]);   // 0 * 2^-inf = 0 on the first tile
-                    m_ref[mt] = tmax[mt];
-                    neg_m[mt] = -tmax[mt];
+            for (int u = 0; u < kHalf; ++u)
+                if (!(acc[u] <= 0x1p60f)) {
+                    const float tmax = fmaxf(fmaxf(z[u][0], z[u][1]), fmaxf(z[u][2], z[u][3])) * c;
+                    if (tmax > -INFINITY) {
+                        const float old = neg_m[base + u];
+                        s_run[base + u] = (old != old) ? 0.f : s_run[base + u] * fast_exp2(-old - tmax);
+                        neg_m[base + u] = -tmax;
+                        float a = 0.f;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) a += fast_exp2(__builtin_fmaf(z[u][j], c, -tmax));
+                        acc[u] = a;
+                    } else {
+                        acc[u] = 0.f;                    // every kernel of this lane masked so far
+                    }
                 }
         }
-    };
-    auto accumulate = [&](const f32x4 (&z)[kMT]) {
 #pragma unroll
-        for (int mt = 0; mt < kMT; ++mt) {
-            float acc = 0.f;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc += fast_exp2(__builtin_fmaf(z[mt][j], c, neg_m[mt]));
-            s_run[mt] += acc;
-        }
+        for (int u = 0; u < kHalf; ++u) s_run[base + u] += acc[u];
     };
 
+    f32x4 zA[kHalf], zB[kHalf];
     if (nt_full > 0) {
         Frag4 fr = load_ck_tile(ckp_head, 0, lane);
         Frag4 fr_next = fr;
         if (nt_full > 1) fr_next = load_ck_tile(ckp_head, 1, lane);
-        f32x4 z_prev[kMT];
-        mfma_tile(fr, z_prev);
-        check_rescale(z_prev);
+        mfma_half<true>(fr, qf, 0, zA);
+        mfma_half<true>(fr, qf, kHalf, zB);
+        finish(zA, 0);
         for (int t = 1; t < nt_full; ++t) {
             fr = fr_next;
             if (t + 1 < nt_full) fr_next = load_ck_tile(ckp_head, t + 1, lane);
-            f32x4 z[kMT];
-            mfma_tile(fr, z);          // matrix work of tile t ...
-            accumulate(z_prev);        // ... alternates with the exponentials of tile t-1
-            check_rescale(z);
-#pragma unroll
-            for (int mt = 0; mt < kMT; ++mt) z_prev[mt] = z[mt];
+            mfma_half<true>(fr, qf, 0, zA);              // matrix work on half A of tile t ...
+            finish(zB, kHalf);                           // ... alternates with half B of tile t-1
+            mfma_half<true>(fr, qf, kHalf, zB);
+            finish(zA, 0);
         }
-        accumulate(z_prev);
+        finish(zB, kHalf);
     }
     for (int t = nt_full; t < nt_all; ++t) {             // causal edge: at most two masked tiles
-        Frag4 fr = load_ck_tile(ckp_head, t, lane);
-        f32x4 z[kMT];
-        mfma_tile(fr, z);
+        const Frag4 fr = load_ck_tile(ckp_head, t, lane);
 #pragma unroll
-        for (int mt = 0; mt < kMT; ++mt) {
-            const int nv = n_visible16(t0 + mt);
+        for (int half = 0; half < 2; ++half) {
+            mfma_half<true>(fr, qf, half * kHalf, zA);
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (16 * t + 4 * g + j >= nv) z[mt][j] = -INFINITY;
+            for (int u = 0; u < kHalf; ++u) {
+                const int nv = n_visible16(t0 + half * kHalf + u);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (16 * t + 4 * g + j >= nv) zA[u][j] = -INFINITY;
+            }
+            finish(zA, half * kHalf);
         }
-        check_rescale(z);
-        accumulate(z);
     }
 #pragma unroll
     for (int mt = 0; mt < kMT; ++mt) {
-        const float M = xgroup_max(m_ref[mt]);
+        const float m_lane = (neg_m[mt] != neg_m[mt]) ? -INFINITY : -neg_m[mt];
+        const float M = xgroup_max(m_lane);
         const float m_use = M == -INFINITY ? 0.f : M;
-        const float S = xgroup_sum(s_run[mt] * fast_exp2(m_ref[mt] - m_use));
+        const float S = xgroup_sum(s_run[mt] * fast_exp2(m_lane - m_use));
         const int tok = t0 + mt;
         if (g == 0 && tok < L) lse2[((int64_t)b * dm.max_seqlen + tok) * dm.Hq + h * 16 + n] = M + fast_log2(S);
     }
 }
 
 // ---- pass 2 ----------------------------------------------------------------------------------------
-// Z = Q . CK^T: lane = kernel n of the tile, accumulator entries = heads 4g..4g+3 of the token.
-// Writes the block scores R[token, j] of the candidate blocks j in [n_init, b_own - n_local]
-// (-inf when no visible kernel intersects the block); select_pick_kernel ranks them.
+// Lane = kernel n of the tile, accumulator entries = heads 4g..4g+3 of the token.  Writes the
+// block scores R[token, j] of the candidate blocks j in [n_init, b_own - n_local] (-inf when no
+// visible kernel intersects the block); select_pick_kernel ranks them.
 __global__ __launch_bounds__(256) void select_score16_kernel(Dims dm, Tensor q, const uint4 *__restrict__ ckp,
                                                               int32_t nt_cap, const int32_t *__restrict__ seqlens,
                                                               const float *__restrict__ lse2,
@@ -218,82 +237,78 @@ __global__ __launch_bounds__(256) void select_score16_kernel(Dims dm, Tensor q, 
 
     bf16x8 qf[kMT][4];
     load_q16(qf, q, b, h, t0, L, n, g);
-    float lse_r[kMT][4];                                                      // heads 4g+j of token mt
+    float nlse[kMT][4];                                                       // -lse of heads 4g+j of token mt
 #pragma unroll
     for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            lse_r[mt][j] = (t0 + mt < L) ? -lse2[((int64_t)b * dm.max_seqlen + t0 + mt) * dm.Hq + h * 16 + 4 * g + j]
-                                          : 0.f;
-    const int nvis_lo = n_visible16(t0);
-    const int nt_full = nvis_lo >> 4;                                         // tiles needing no mask
+            nlse[mt][j] = (t0 + mt < L) ? -lse2[((int64_t)b * dm.max_seqlen + t0 + mt) * dm.Hq + h * 16 + 4 * g + j]
+                                         : 0.f;
+    const int nt_full = n_visible16(t0) >> 4;                                 // tiles needing no mask
     const int nt_all = min((4 * jc_max + 4 + 15) >> 4, nt_cap);               // tiles that hold candidate kernels
     if (nt_all <= 0) return;
+    const int nt_pipe = min(nt_full, nt_all);
     const uint4 *ckp_head = ckp + ((int64_t)b * dm.Hkv + h) * nt_cap * 256;
-    // packed per-token values: 16-lane group g of register [i] belongs to token 4i+g
+    // packed per-token values: 16-lane group g of half i belongs to token 4i+g
     float prev_v[2] = {-INFINITY, -INFINITY};
     float *Rrow[2];
     bool wr[2];
+    int nvis_tok[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int tok = t0 + 4 * i + g;
         Rrow[i] = R + (((int64_t)b * dm.Hkv + h) * dm.max_seqlen + tok) * nb_cap + (n >> 2);
         wr[i] = ((n & 3) == 0) && tok < L;
+        nvis_tok[i] = n_visible16(tok);
     }
 
-    auto mfma_tile = [&](const Frag4 &fr, f32x4 (&z)[kMT]) {
+    // epilogue of tile t for half i: 2^(z*c - lse), sum over the 16 heads, mean, floor, causal mask,
+    // 5-wide / stride-4 max over kernels -> lanes n = 0,4,8,12 hold blocks 4t + n/4
+    auto finish = [&](const f32x4 (&z)[kHalf], int i, int t) {
+        float e[kHalf];
 #pragma unroll
-        for (int mt = 0; mt < kMT; ++mt) z[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int u = 0; u < kHalf; ++u) {
+            float a = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int mt = 0; mt < kMT; ++mt)
-                z[mt] = mfma16(qf[mt][ks], __builtin_bit_cast(bf16x8, fr.f[ks]), z[mt]);
-    };
-    // scores of tile t: mean over heads, floor, causal mask, 5-wide / stride-4 max -> lanes
-    // n = 0,4,8,12 hold blocks 4t + n/4, which are written out
-    auto finish_tile = [&](const f32x4 (&z)[kMT], int t, bool masked) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            float v = 0.f;
-#pragma unroll
-            for (int gg = 0; gg < 4; ++gg) {
-                const int mt = 4 * i + gg;
-                float e = 0.f;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) e += fast_exp2(__builtin_fmaf(z[mt][j], c, lse_r[mt][j]));
-                e = xgroup_sum(e);                                            // all 16 heads, in every group
-                v = (g == gg) ? e : v;
-            }
-            v = fmaxf(v * (1.f / 16.f), kScoreFloor);
-            if (masked && 16 * t + n >= n_visible16(t0 + 4 * i + g)) v = -INFINITY;   // kernel not visible
-            const float a = fmaxf(v, dpp_f32<kRowShl1>(v, v));
-            const float bq = fmaxf(a, dpp_f32<kRowShl2>(a, a));
-            const float halo0 = dpp_f32<kRowRor1>(prev_v[i], prev_v[i]);      // lane 0 <- previous tile's lane 15
-            const float halo = dpp_f32<kRowShr1>(halo0, v);                   // lane n <- v[n-1]
-            const float w = fmaxf(bq, halo);
-            prev_v[i] = v;
-            const int j = 4 * t + (n >> 2);
-            if (wr[i] && j >= n_init && j <= jc_max) Rrow[i][4 * t] = w;
+            for (int j = 0; j < 4; ++j) a += fast_exp2(__builtin_fmaf(z[u][j], c, nlse[kHalf * i + u][j]));
+            e[u] = a;
         }
+        // sum over the four 16-lane groups, leaving token u's total in group u (3 lane swaps)
+        typedef unsigned v2u __attribute__((ext_vector_type(2)));
+        const v2u p01 = __builtin_amdgcn_permlane16_swap(__float_as_uint(e[0]), __float_as_uint(e[1]), false, false);
+        const v2u p23 = __builtin_amdgcn_permlane16_swap(__float_as_uint(e[2]), __float_as_uint(e[3]), false, false);
+        const float s01 = __uint_as_float(p01[0]) + __uint_as_float(p01[1]);
+        const float s23 = __uint_as_float(p23[0]) + __uint_as_float(p23[1]);
+        const v2u pq = __builtin_amdgcn_permlane32_swap(__float_as_uint(s01), __float_as_uint(s23), false, false);
+        float v = __uint_as_float(pq[0]) + __uint_as_float(pq[1]);
+        v = fmaxf(v * (1.f / 16.f), kScoreFloor);
+        if (t >= nt_pipe && 16 * t + n >= nvis_tok[i]) v = -INFINITY;         // kernel not visible to this token
+        const float a = fmaxf(v, dpp_f32<kRowShl1>(v, v));
+        const float bq = fmaxf(a, dpp_f32<kRowShl2>(a, a));
+        const float halo0 = dpp_f32<kRowRor1>(prev_v[i], prev_v[i]);          // lane 0 <- previous tile's lane 15
+        const float halo = dpp_f32<kRowShr1>(halo0, v);                       // lane n <- v[n-1]
+        const float w = fmaxf(bq, halo);
+        prev_v[i] = v;
+        const int j = 4 * t + (n >> 2);
+        if (wr[i] && j >= n_init && j <= jc_max) Rrow[i][4 * t] = w;
     };
 
-    const int nt_pipe = min(nt_full, nt_all);
+    f32x4 zA[kHalf], zB[kHalf];
     Frag4 fr = load_ck_tile(ckp_head, 0, lane);
     Frag4 fr_next = fr;
     if (nt_all > 1) fr_next = load_ck_tile(ckp_head, 1, lane);
-    f32x4 z_prev[kMT];
-    mfma_tile(fr, z_prev);
+    mfma_half<false>(fr, qf, 0, zA);
+    mfma_half<false>(fr, qf, kHalf, zB);
+    finish(zA, 0, 0);
     for (int t = 1; t < nt_all; ++t) {
         fr = fr_next;
         if (t + 1 < nt_all) fr_next = load_ck_tile(ckp_head, t + 1, lane);
-        f32x4 z[kMT];
-        mfma_tile(fr, z);                              // matrix work of tile t ...
-        finish_tile(z_prev, t - 1, t - 1 >= nt_pipe);  // ... alternates with the epilogue of tile t-1
-#pragma unroll
-        for (int mt = 0; mt < kMT; ++mt) z_prev[mt] = z[mt];
+        mfma_half<false>(fr, qf, 0, zA);                 // matrix work on half A of tile t ...
+        finish(zB, 1, t - 1);                            // ... alternates with the epilogue of half B, tile t-1
+        mfma_half<false>(fr, qf, kHalf, zB);
+        finish(zA, 0, t);
     }
-    finish_tile(z_prev, nt_all - 1, nt_all - 1 >= nt_pipe);
+    finish(zB, 1, nt_all - 1);
 }
 
 size_t select_prefill16_ws_bytes(const Dims &dm) {

@@ -6,7 +6,7 @@ using namespace infllmv2;
 
 namespace {
 
-constexpr int32_t kMaxDecodeSeqlen = 196608;   // keeps the decode top-k's LDS arrays under 64 KiB
+constexpr int32_t kMaxDecodeSeqlen = 262144;   // decode selection: at most 256 log-sum-exp partials per head
 
 int32_t check_params(const infllmv2_params *p) {
     if (!p) return INFLLMV2_ERR_INVALID_ARGUMENT;

@@ -3,13 +3,16 @@
 // keep the method usable in decoding; section 5.4: per step the attended blocks stay constant
 // and only the semantic-kernel representations grow).
 //
-// Selection: G x n_c logits per key-value head.  The softmax needs the log-sum-exp over ALL
-// visible kernels before any score can be ranked, so the scan is split:
-//   decode_logits_kernel   every CU takes 64 kernels: MFMA logits -> scratch, per-16-kernel
-//                          partial (max, sum) per head
-//   decode_topk_kernel     one workgroup per (sequence, key-value head): merges the partials
-//                          into the log-sum-exp, forms group-mean scores, 5/4 max-pool to
-//                          blocks, forces initial/local blocks, ordered top-k
+// A decode step moves a few megabytes, so it is bound by launch and memory latency, not by
+// bandwidth: every kernel below spreads its reads over many workgroups and issues all the loads
+// of a thread before using any of them.
+//
+// Selection (the softmax needs the log-sum-exp over ALL visible kernels before any score exists):
+//   decode_logits_kernel   64 kernels per workgroup: MFMA logits -> scratch, one partial
+//                          (max, sum) per head and workgroup
+//   decode_scores_kernel   256 kernels (64 blocks) per workgroup: merges the partials into the
+//                          log-sum-exp, group-mean scores, 5/4 max-pool -> block scores
+//   select_pick_kernel     (select_prefill.hip) register top-k of the block-score row
 // Attention: one workgroup per selected block (split-KV) writes an unnormalised partial
 // (o, max, sum); decode_merge_kernel combines the k partials per query head.
 #include "common.h"
@@ -19,31 +22,35 @@ namespace infllmv2 {
 __device__ inline int clamp_len(int32_t L, int32_t cap) { return L < 0 ? 0 : (L > cap ? cap : L); }
 
 // ---- selection, part 1 ------------------------------------------------------------------------
-// grid (ceil(n_c_cap/64), Hkv, B); wave w of a workgroup owns kernels 64*bx + 16*w .. +15.
+// grid (n_c_cap/64, Hkv, B); wave w of a workgroup owns kernels 64*bx + 16*w .. +15.
 // Z^T = CK . Q^T: lane = query head, 4 accumulator entries = 4 consecutive kernels.
 __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, Tensor ck,
                                                              const int32_t *__restrict__ seqlens,
                                                              float *__restrict__ zbuf,
                                                              float2 *__restrict__ part, int32_t n_c_cap,
                                                              int32_t n_part) {
+    __shared__ float2 wpart[4][16];
     const int b = blockIdx.z, h = blockIdx.y;
     const int L = clamp_len(seqlens[b], dm.max_seqlen);
     const int n_vis = num_kernels(L);                 // the query sits at L-1: n_c((L-1)+1)
+    if ((int)blockIdx.x * 64 >= n_vis) return;        // uniform over the workgroup
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, g = lane >> 4;
     const int jh0 = blockIdx.x * 64 + wave * 16;
-    if (jh0 >= n_vis) return;
     const int G = dm.G;
     f32x4 z = {0.f, 0.f, 0.f, 0.f};
     const __bf16 *ckr = ck.ptr + b * ck.sb + h * ck.sh + (int64_t)(jh0 + n) * ck.st + 8 * g;
     const __bf16 *qr = q.ptr + b * q.sb + (int64_t)(h * G + n) * q.sh + 8 * g;
+    bf16x8 a[4], bq[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-        bf16x8 a = zero8(), bq = zero8();
-        if (jh0 + n < n_vis) a = load8(ckr + 32 * ks);
-        if (n < G) bq = load8(qr + 32 * ks);
-        z = mfma16(a, bq, z);
+        a[ks] = zero8();
+        bq[ks] = zero8();
+        if (jh0 + n < n_vis) a[ks] = load8(ckr + 32 * ks);
+        if (n < G) bq[ks] = load8(qr + 32 * ks);
     }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) z = mfma16(a[ks], bq[ks], z);
     float mx = -INFINITY;
     float x[4];
 #pragma unroll
@@ -52,166 +59,125 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, T
         if (jh0 + 4 * g + j >= n_vis) x[j] = -INFINITY;
         mx = fmaxf(mx, x[j]);
     }
-    mx = xgroup_max(mx);                              // finite: kernel jh0 is visible
+    mx = xgroup_max(mx);
+    const float m_use = mx == -INFINITY ? 0.f : mx;
     float s = 0.f;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) s += fast_exp2(x[j] - mx);
+    for (int j = 0; j < 4; ++j) s += fast_exp2(x[j] - m_use);
     s = xgroup_sum(s);
-    if (n < G) {
+    if (n < G && jh0 < n_vis) {
         float *zr = zbuf + (((int64_t)b * dm.Hkv + h) * G + n) * n_c_cap + jh0 + 4 * g;
         *reinterpret_cast<float4 *>(zr) = float4{x[0], x[1], x[2], x[3]};
-        if (g == 0) part[(((int64_t)b * dm.Hkv + h) * G + n) * n_part + (jh0 >> 4)] = float2{mx, s};
     }
-}
-
-// Ordered argmax over a workgroup: (score descending, index ascending).
-__device__ inline void wave_best(float &s, int &j) {
+    if (g == 0) wpart[wave][n] = float2{mx, s};
+    __syncthreads();
+    if (threadIdx.x < 16 && (int)threadIdx.x < G) {   // merge the four waves: one partial per head
+        float M = -INFINITY;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const float os = __shfl_xor(s, o);
-        const int oj = __shfl_xor(j, o);
-        if (os > s || (os == s && oj < j)) {
-            s = os;
-            j = oj;
-        }
+        for (int w = 0; w < 4; ++w) M = fmaxf(M, wpart[w][threadIdx.x].x);
+        const float mu = M == -INFINITY ? 0.f : M;
+        float S = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) S += wpart[w][threadIdx.x].y * fast_exp2(wpart[w][threadIdx.x].x - mu);
+        part[(((int64_t)b * dm.Hkv + h) * G + threadIdx.x) * n_part + blockIdx.x] = float2{M, S};
     }
 }
 
 // ---- selection, part 2 ------------------------------------------------------------------------
-// grid (Hkv, B), 1024 threads.  Dynamic LDS: r[n_c_cap + 1] kernel scores (slot 0 = kernel -1),
-// R[nb_cap] block scores.
-__global__ __launch_bounds__(1024) void decode_topk_kernel(Dims dm, const int32_t *__restrict__ seqlens,
-                                                            const float *__restrict__ zbuf,
-                                                            const float2 *__restrict__ part,
-                                                            int32_t n_c_cap, int32_t n_part, int32_t nb_cap,
-                                                            int32_t *__restrict__ block_idx) {
-    extern __shared__ float smem[];
-    float *r = smem;                        // [n_c_cap + 1]
-    float *R = smem + n_c_cap + 1;          // [nb_cap]
+// grid (ceil(n_c_cap/256), Hkv, B), 320 threads.  Thread t <= 256 scores kernel 256*bx - 1 + t
+// (one halo kernel to the left); threads 0..63 then pool blocks 64*bx + t.
+constexpr int kMaxParts = 256;                        // partials per head: contexts up to 262144 tokens
+__global__ __launch_bounds__(320) void decode_scores_kernel(Dims dm, const int32_t *__restrict__ seqlens,
+                                                             const float *__restrict__ zbuf,
+                                                             const float2 *__restrict__ part,
+                                                             int32_t n_c_cap, int32_t n_part,
+                                                             float *__restrict__ R, int32_t nb_cap) {
     __shared__ float lse_h[16];
-    __shared__ float best_s[16];
-    __shared__ int best_j[16];
-    __shared__ int picks[kMaxTopk];
-    const int h = blockIdx.x, b = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ float rs[260];
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x;
     const int G = dm.G;
     const int L = clamp_len(seqlens[b], dm.max_seqlen);
-    int32_t *out = block_idx + ((int64_t)b * dm.Hkv + h) * dm.topk;
-    if (L < 1) {
-        if (tid < dm.topk) out[tid] = -1;
-        return;
-    }
     const int n_vis = num_kernels(L);
-    const int np = (n_vis + 15) >> 4;       // valid partials
-    const int b_own = (L - 1) / kBlock, n_blk = b_own + 1;
-
-    // log-sum-exp per head: wave w reduces head w (16 waves, up to 16 heads)
-    if (wave < G) {
-        const float2 *pp = part + (((int64_t)b * dm.Hkv + h) * G + wave) * n_part;
+    const int base = blockIdx.x * 256;
+    if (L < 1 || (int)blockIdx.x * 64 > (L - 1) / kBlock) return;            // no block of this chunk exists
+    const int np = (n_vis + 63) >> 6;                 // valid partials
+    // log-sum-exp per head: 16 lanes per head, all loads of a lane issued together
+    if (tid < 256) {
+        const int head = tid >> 4, sub = tid & 15;
+        float2 v[kMaxParts / 16];
+#pragma unroll
+        for (int i = 0; i < kMaxParts / 16; ++i) {
+            const int p = sub + 16 * i;
+            v[i] = float2{-INFINITY, 0.f};
+            if (head < G && p < np) v[i] = part[(((int64_t)b * dm.Hkv + h) * G + head) * n_part + p];
+        }
         float m = -INFINITY;
-        for (int i = lane; i < np; i += 64) m = fmaxf(m, pp[i].x);
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
+        for (int i = 0; i < kMaxParts / 16; ++i) m = fmaxf(m, v[i].x);
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
+        const float mu = m == -INFINITY ? 0.f : m;
         float s = 0.f;
-        for (int i = lane; i < np; i += 64) {
-            float2 v = pp[i];
-            s += v.y * fast_exp2(v.x - m);
-        }
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) s += __shfl_xor(s, o);
-        if (lane == 0) lse_h[wave] = np > 0 ? m + fast_log2(s) : 0.f;
+        for (int i = 0; i < kMaxParts / 16; ++i) s += v[i].y * fast_exp2(v[i].x - mu);
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) s += __shfl_xor(s, o);
+        if (sub == 0) lse_h[head] = m + fast_log2(s);
+    }
+    // logits of this thread's kernel, all heads (independent loads, in flight during the reduction)
+    const int jh = base - 1 + tid;
+    const bool have = tid <= 256 && jh >= 0 && jh < n_vis;
+    float zz[16];
+#pragma unroll
+    for (int gq = 0; gq < 16; ++gq) {
+        zz[gq] = -INFINITY;
+        if (have && gq < G) zz[gq] = zbuf[(((int64_t)b * dm.Hkv + h) * G + gq) * n_c_cap + jh];
     }
     __syncthreads();
-    // group-mean kernel scores
-    const float *zb = zbuf + ((int64_t)b * dm.Hkv + h) * G * n_c_cap;
-    const float inv_g = 1.f / G;
-    for (int jh = tid; jh < n_vis; jh += 1024) {
+    if (tid <= 256) {
         float acc = 0.f;
-        for (int gq = 0; gq < G; ++gq) acc += fast_exp2(zb[(int64_t)gq * n_c_cap + jh] - lse_h[gq]);
-        r[jh + 1] = fmaxf(acc * inv_g, kScoreFloor);
-    }
-    if (tid == 0) r[0] = -INFINITY;
-    __syncthreads();
-    // block scores: kernels 4j-1 .. 4j+3 that are visible; forced blocks to +inf
-    for (int j = tid; j < n_blk; j += 1024) {
-        float v = -INFINITY;
 #pragma unroll
-        for (int x = 0; x < 5; ++x) {
-            const int jh = 4 * j - 1 + x;
-            if (jh < n_vis) v = fmaxf(v, r[jh + 1]);
-        }
-        if (j < dm.n_init || j > b_own - dm.n_local) v = INFINITY;
-        R[j] = v;
+        for (int gq = 0; gq < 16; ++gq)
+            if (gq < G) acc += fast_exp2(zz[gq] - lse_h[gq]);
+        rs[tid] = have ? fmaxf(acc * (1.f / G), kScoreFloor) : -INFINITY;
     }
     __syncthreads();
-    const int n_sel = dm.topk < n_blk ? dm.topk : n_blk;
-    float last_s = INFINITY;
-    int last_j = -1;
-    for (int c = 0; c < n_sel; ++c) {
-        float bs = -INFINITY;
-        int bj = 0x7fffffff;
-        for (int j = tid; j < n_blk; j += 1024) {
-            const float sc = R[j];
-            const bool after = sc < last_s || (sc == last_s && j > last_j);
-            if (after && (sc > bs || (sc == bs && j < bj))) {
-                bs = sc;
-                bj = j;
-            }
-        }
-        wave_best(bs, bj);
-        if (lane == 0) {
-            best_s[wave] = bs;
-            best_j[wave] = bj;
-        }
-        __syncthreads();
-        bs = best_s[0];
-        bj = best_j[0];
+    if (tid < 64) {
+        const int j = blockIdx.x * 64 + tid;          // kernels 4j-1 .. 4j+3 = rs[4*tid .. 4*tid+4]
+        if (j <= (L - 1) / kBlock) {
+            float v = rs[4 * tid];
 #pragma unroll
-        for (int w = 1; w < 16; ++w) {
-            const float os = best_s[w];
-            const int oj = best_j[w];
-            if (os > bs || (os == bs && oj < bj)) {
-                bs = os;
-                bj = oj;
-            }
-        }
-        last_s = bs;
-        last_j = bj;
-        if (tid == 0) picks[c] = bj;
-        __syncthreads();
-    }
-    if (tid < dm.topk) {
-        if (tid < n_sel) {
-            const int mine = picks[tid];
-            int rank = 0;
-            for (int c = 0; c < n_sel; ++c) rank += picks[c] < mine ? 1 : 0;
-            out[rank] = mine;
-        } else {
-            out[tid] = -1;
+            for (int x = 1; x < 5; ++x) v = fmaxf(v, rs[4 * tid + x]);
+            R[((int64_t)b * dm.Hkv + h) * nb_cap + j] = v;
         }
     }
 }
 
 // ---- attention, part 1: one workgroup per selected block --------------------------------------
-// grid (topk, Hkv, B).  Wave w: keys 16w..16w+15 of the block, S^T = K . Q^T on MFMA; then
-// thread (head, 8-channel chunk) accumulates p*v over the 64 keys in fp32.
+// grid (topk, Hkv, B), 256 threads.  Wave w: keys 16w..16w+15 of the block, S^T = K . Q^T on MFMA.
+// Then thread = (8-channel chunk c, key quarter kq, head quad hq): it issues its 16 value loads at
+// once, accumulates p*v for 4 heads over 16 keys in fp32, and the four key quarters are summed
+// through LDS.
 __global__ __launch_bounds__(256) void decode_attn_partial_kernel(Dims dm, Tensor q, Tensor k, Tensor v,
                                                                    const int32_t *__restrict__ seqlens,
                                                                    const int32_t *__restrict__ block_idx,
                                                                    float *__restrict__ o_part,
                                                                    float2 *__restrict__ ml_part) {
     __shared__ float S[kBlock][17];
-    const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    __shared__ float mrow[16];
+    __shared__ float red[3][16][kHeadDim + 4];       // partial outputs of key quarters 1..3
+    const int cidx = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, g = lane >> 4;
     const int G = dm.G;
     const int L = clamp_len(seqlens[b], dm.max_seqlen);
-    const int blk = block_idx[((int64_t)b * dm.Hkv + h) * dm.topk + c];
-    const int head = tid & 15, chunk = tid >> 4;
-    const int64_t pbase = (((int64_t)b * dm.Hq + h * G + head) * dm.topk + c);
+    const int blk = block_idx[((int64_t)b * dm.Hkv + h) * dm.topk + cidx];
     const bool valid = L >= 1 && blk >= 0 && (int64_t)blk * kBlock < L;
     if (!valid) {                                        // uniform over the workgroup
+        const int head = tid & 15, chunk = tid >> 4;
         if (head < G) {
+            const int64_t pbase = (((int64_t)b * dm.Hq + h * G + head) * dm.topk + cidx);
             if (chunk == 0) ml_part[pbase] = float2{-INFINITY, 0.f};
             float4 zf = {0.f, 0.f, 0.f, 0.f};
             float4 *op = reinterpret_cast<float4 *>(o_part + pbase * kHeadDim + 8 * chunk);
@@ -222,18 +188,32 @@ __global__ __launch_bounds__(256) void decode_attn_partial_kernel(Dims dm, Tenso
     }
     const int key0 = blk * kBlock;
     const int pos = L - 1;
+    // value rows of this thread: keys 16*kq .. 16*kq+15, channels 8c .. 8c+7 (issued before the scores)
+    const int c8 = tid & 15, kq = (tid >> 4) & 3, hq = tid >> 6;
+    bf16x8 vv[16];
+    {
+        const __bf16 *vr = v.ptr + b * v.sb + h * v.sh + (int64_t)(key0 + 16 * kq) * v.st + 8 * c8;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            vv[i] = zero8();
+            if (key0 + 16 * kq + i <= pos) vv[i] = load8(vr + (int64_t)i * v.st);
+        }
+    }
     {
         f32x4 s = {0.f, 0.f, 0.f, 0.f};
         const int key = key0 + 16 * wave + n;
         const __bf16 *kr = k.ptr + b * k.sb + h * k.sh + (int64_t)key * k.st + 8 * g;
         const __bf16 *qr = q.ptr + b * q.sb + (int64_t)(h * G + n) * q.sh + 8 * g;
+        bf16x8 a[4], bq[4];
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 a = zero8(), bq = zero8();
-            if (key <= pos) a = load8(kr + 32 * ks);
-            if (n < G) bq = load8(qr + 32 * ks);
-            s = mfma16(a, bq, s);
+            a[ks] = zero8();
+            bq[ks] = zero8();
+            if (key <= pos) a[ks] = load8(kr + 32 * ks);
+            if (n < G) bq[ks] = load8(qr + 32 * ks);
         }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) s = mfma16(a[ks], bq[ks], s);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int kk = 16 * wave + 4 * g + j;
@@ -241,46 +221,90 @@ __global__ __launch_bounds__(256) void decode_attn_partial_kernel(Dims dm, Tenso
         }
     }
     __syncthreads();
-    if (head >= G) return;
-    float m = -INFINITY;
+    if (tid < 16) {
+        float m = -INFINITY;
 #pragma unroll 8
-    for (int kk = 0; kk < kBlock; ++kk) m = fmaxf(m, S[kk][head]);     // key0 <= pos: finite
-    float acc[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    float l = 0.f;
-    const int n_keys = min(kBlock, pos - key0 + 1);
-    const __bf16 *vr = v.ptr + b * v.sb + h * v.sh + (int64_t)key0 * v.st + 8 * chunk;
-#pragma unroll 4
-    for (int kk = 0; kk < n_keys; ++kk) {
-        const float p = fast_exp2(S[kk][head] - m);
-        l += p;
-        bf16x8 x = load8(vr + (int64_t)kk * v.st);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] += p * (float)x[e];
+        for (int kk = 0; kk < kBlock; ++kk) m = fmaxf(m, S[kk][tid]);   // key0 <= pos: finite
+        mrow[tid] = m;
     }
-    if (chunk == 0) ml_part[pbase] = float2{m, l};
-    float4 *op = reinterpret_cast<float4 *>(o_part + pbase * kHeadDim + 8 * chunk);
-    op[0] = float4{acc[0], acc[1], acc[2], acc[3]};
-    op[1] = float4{acc[4], acc[5], acc[6], acc[7]};
+    __syncthreads();
+    float acc[4][8];
+    float lsum[4];
+#pragma unroll
+    for (int hh = 0; hh < 4; ++hh) {
+        lsum[hh] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[hh][e] = 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+#pragma unroll
+        for (int hh = 0; hh < 4; ++hh) {
+            const float p = fast_exp2(S[16 * kq + i][4 * hq + hh] - mrow[4 * hq + hh]);
+            lsum[hh] += p;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[hh][e] += p * (float)vv[i][e];
+        }
+    }
+    // sum the four key quarters: quarters 1..3 park their partials in LDS, quarter 0 adds and writes
+    if (kq > 0) {
+#pragma unroll
+        for (int hh = 0; hh < 4; ++hh) {
+            float *r = &red[kq - 1][4 * hq + hh][8 * c8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) r[e] = acc[hh][e];
+            if (c8 == 0) red[kq - 1][4 * hq + hh][kHeadDim] = lsum[hh];
+        }
+    }
+    __syncthreads();
+    if (kq == 0) {
+#pragma unroll
+        for (int hh = 0; hh < 4; ++hh) {
+            const int head = 4 * hq + hh;
+            if (head >= G) continue;
+#pragma unroll
+            for (int qq = 0; qq < 3; ++qq) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[hh][e] += red[qq][head][8 * c8 + e];
+                lsum[hh] += red[qq][head][kHeadDim];
+            }
+            const int64_t pbase = (((int64_t)b * dm.Hq + h * G + head) * dm.topk + cidx);
+            if (c8 == 0) ml_part[pbase] = float2{mrow[head], lsum[hh]};
+            float4 *op = reinterpret_cast<float4 *>(o_part + pbase * kHeadDim + 8 * c8);
+            op[0] = float4{acc[hh][0], acc[hh][1], acc[hh][2], acc[hh][3]};
+            op[1] = float4{acc[hh][4], acc[hh][5], acc[hh][6], acc[hh][7]};
+        }
+    }
 }
 
 // ---- attention, part 2: merge the k partials of every query head ---------------------------------
-// grid (Hq, B), 128 threads: thread = channel.
+// grid (Hq, B), 128 threads: thread = channel.  All partial loads are issued before the merge.
 __global__ __launch_bounds__(128) void decode_merge_kernel(Dims dm, const float *__restrict__ o_part,
                                                             const float2 *__restrict__ ml_part, Tensor out,
                                                             float *__restrict__ lse) {
     const int hq = blockIdx.x, b = blockIdx.y, cch = threadIdx.x;
     const int64_t pbase = ((int64_t)b * dm.Hq + hq) * dm.topk;
+    float2 ml[kMaxTopk];
+    float ov[kMaxTopk];
+#pragma unroll
+    for (int c = 0; c < kMaxTopk; ++c) {
+        ml[c] = float2{-INFINITY, 0.f};
+        ov[c] = 0.f;
+        if (c < dm.topk) {
+            ml[c] = ml_part[pbase + c];
+            ov[c] = o_part[(pbase + c) * kHeadDim + cch];
+        }
+    }
     float M = -INFINITY;
-    for (int c = 0; c < dm.topk; ++c) M = fmaxf(M, ml_part[pbase + c].x);
+#pragma unroll
+    for (int c = 0; c < kMaxTopk; ++c) M = fmaxf(M, ml[c].x);
     float num = 0.f, den = 0.f;
     if (M > -INFINITY) {
-        for (int c = 0; c < dm.topk; ++c) {
-            const float2 ml = ml_part[pbase + c];
-            const float w = fast_exp2(ml.x - M);
-            den += w * ml.y;
-            num += w * o_part[(pbase + c) * kHeadDim + cch];
+#pragma unroll
+        for (int c = 0; c < kMaxTopk; ++c) {
+            const float w = fast_exp2(ml[c].x - M);
+            den += w * ml[c].y;
+            num += w * ov[c];
         }
     }
     const float o = den > 0.f ? num / den : 0.f;
@@ -293,46 +317,43 @@ static inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct DecodeSelLayout {
     int32_t n_c_cap, n_part, nb_cap;
-    size_t z_bytes, part_bytes;
+    size_t z_bytes, part_bytes, r_bytes;
 };
 static DecodeSelLayout decode_sel_layout(const Dims &dm) {
     DecodeSelLayout l;
     int32_t n_c = num_kernels(dm.max_seqlen);
-    l.n_c_cap = (n_c + 63) / 64 * 64;
-    if (l.n_c_cap < 64) l.n_c_cap = 64;
-    l.n_part = l.n_c_cap / 16;
-    l.nb_cap = (dm.max_seqlen + kBlock - 1) / kBlock + 1;
+    l.n_c_cap = (n_c + 255) / 256 * 256;
+    if (l.n_c_cap < 256) l.n_c_cap = 256;
+    l.n_part = l.n_c_cap / 64;
+    l.nb_cap = ((dm.max_seqlen + kBlock - 1) / kBlock + 63) / 64 * 64;
     l.z_bytes = align256((size_t)dm.batch * dm.Hq * l.n_c_cap * sizeof(float));
     l.part_bytes = align256((size_t)dm.batch * dm.Hq * l.n_part * sizeof(float2));
+    l.r_bytes = align256((size_t)dm.batch * dm.Hkv * l.nb_cap * sizeof(float));
     return l;
 }
 
 size_t select_decode_ws_bytes(const Dims &dm) {
     DecodeSelLayout l = decode_sel_layout(dm);
-    return l.z_bytes + l.part_bytes;
-}
-
-size_t select_decode_lds_bytes(const Dims &dm) {
-    DecodeSelLayout l = decode_sel_layout(dm);
-    return ((size_t)l.n_c_cap + 1 + l.nb_cap) * sizeof(float);
+    return l.z_bytes + l.part_bytes + l.r_bytes;
 }
 
 int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
                          int32_t *block_idx, void *ws, hipStream_t stream) {
     if (dm.batch <= 0) return 0;
     DecodeSelLayout l = decode_sel_layout(dm);
+    if (l.n_part > kMaxParts) return (int)hipErrorInvalidValue;      // rejected earlier by the C ABI
     float *zbuf = reinterpret_cast<float *>(ws);
     float2 *part = reinterpret_cast<float2 *>(reinterpret_cast<char *>(ws) + l.z_bytes);
+    float *R = reinterpret_cast<float *>(reinterpret_cast<char *>(ws) + l.z_bytes + l.part_bytes);
     timing_begin("decode_logits_kernel", stream);
     hipLaunchKernelGGL(decode_logits_kernel, dim3(l.n_c_cap / 64, dm.Hkv, dm.batch), dim3(256), 0,
                        stream, dm, q, ck, seqlens, zbuf, part, l.n_c_cap, l.n_part);
     timing_end(stream);
-    const size_t lds = select_decode_lds_bytes(dm);
-    timing_begin("decode_topk_kernel", stream);
-    hipLaunchKernelGGL(decode_topk_kernel, dim3(dm.Hkv, dm.batch), dim3(1024), lds, stream, dm, seqlens,
-                       zbuf, part, l.n_c_cap, l.n_part, l.nb_cap, block_idx);
+    timing_begin("decode_scores_kernel", stream);
+    hipLaunchKernelGGL(decode_scores_kernel, dim3(l.n_c_cap / 256, dm.Hkv, dm.batch), dim3(320), 0, stream,
+                       dm, seqlens, zbuf, part, l.n_c_cap, l.n_part, R, l.nb_cap);
     timing_end(stream);
-    return (int)hipGetLastError();
+    return launch_select_pick_decode(dm, seqlens, R, l.nb_cap, block_idx, stream);
 }
 
 size_t attn_decode_ws_bytes(const Dims &dm) {

@@ -259,18 +259,25 @@ __global__ __launch_bounds__(256) void select_score_kernel(Dims dm, Tensor q, Te
 // the score, 1 for a block without visible kernel (-inf), 0 for "not a candidate / taken".
 // Lane l keeps blocks l, l+64, ... in registers and its best (key, slot); each of the n_pick
 // rounds takes the wave-wide best (ties: lowest block index) and retires it.
-template <int VPL>
+// Slots are kept in groups of 8 with a cached best per group, so retiring a pick recomputes one
+// group only.  kDecode: one row per (sequence, key-value head), the query sits at seqlens[b]-1.
+template <int VPL, bool kDecode>
 __global__ __launch_bounds__(256) void select_pick_kernel(Dims dm, const int32_t *__restrict__ seqlens,
                                                            const float *__restrict__ R, int32_t nb_cap,
                                                            int32_t *__restrict__ block_idx) {
+    constexpr int GS = VPL < 8 ? VPL : 8, NG = VPL / GS;
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int64_t rows = (int64_t)dm.batch * dm.Hkv * dm.max_seqlen;
+    const int64_t rows = (int64_t)dm.batch * dm.Hkv * (kDecode ? 1 : dm.max_seqlen);
     if (row >= rows) return;
-    const int tok = row % dm.max_seqlen;
-    const int b = row / ((int64_t)dm.max_seqlen * dm.Hkv);
+    const int b = kDecode ? row / dm.Hkv : row / ((int64_t)dm.max_seqlen * dm.Hkv);
     int32_t L = seqlens[b];
     L = L < 0 ? 0 : (L > dm.max_seqlen ? dm.max_seqlen : L);
+    const int tok = kDecode ? L - 1 : row % dm.max_seqlen;
+    if (kDecode && L < 1) {
+        if (lane < dm.topk) block_idx[row * dm.topk + lane] = -1;
+        return;
+    }
     if (tok >= L) return;
     const int b_own = tok / kBlock, n_blk = b_own + 1;
     const int n_sel = dm.topk < n_blk ? dm.topk : n_blk;
@@ -291,15 +298,29 @@ __global__ __launch_bounds__(256) void select_pick_kernel(Dims dm, const int32_t
                 key[s] = r == -INFINITY ? 1u : __float_as_uint(r);
             }
         }
-        uint32_t lb_key = 0u;
-        int lb_slot = 0;
+        uint32_t gkey[NG];
+        int gslot[NG];
+        auto regroup = [&](int gi) {                                          // gi is a compile-time index
+            gkey[gi] = 0u;
+            gslot[gi] = gi * GS;
 #pragma unroll
-        for (int s = VPL - 1; s >= 0; --s)
-            if (key[s] >= lb_key) {
-                lb_key = key[s];
-                lb_slot = s;
-            }
+            for (int s = gi * GS + GS - 1; s >= gi * GS; --s)
+                if (key[s] >= gkey[gi]) {
+                    gkey[gi] = key[s];
+                    gslot[gi] = s;
+                }
+        };
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) regroup(gi);
         for (int c = 0; c < n_pick; ++c) {
+            uint32_t lb_key = 0u;
+            int lb_slot = 0;
+#pragma unroll
+            for (int gi = NG - 1; gi >= 0; --gi)
+                if (gkey[gi] >= lb_key) {
+                    lb_key = gkey[gi];
+                    lb_slot = gslot[gi];
+                }
             // wave-wide maximum key: row maxima by DPP shifts, then the four rows through scalars
             uint32_t m = lb_key;
             m = max(m, (uint32_t)__builtin_amdgcn_update_dpp((int)m, (int)m, 0x111, 0xf, 0xf, false));
@@ -324,14 +345,13 @@ __global__ __launch_bounds__(256) void select_pick_kernel(Dims dm, const int32_t
             }
             if (lane == c) mine = wl + 64 * wslot;
             const bool me = lane == wl;
-            lb_key = me ? 0u : lb_key;
 #pragma unroll
-            for (int s = VPL - 1; s >= 0; --s) {
-                if (me && s == wslot) key[s] = 0u;
-                if (me && key[s] >= lb_key) {
-                    lb_key = key[s];
-                    lb_slot = s;
-                }
+            for (int gi = 0; gi < NG; ++gi) {
+                if (wslot / GS != gi) continue;                               // uniform: one group is touched
+#pragma unroll
+                for (int s = gi * GS; s < gi * GS + GS; ++s)
+                    if (me && s == wslot) key[s] = 0u;
+                regroup(gi);
             }
         }
     }
@@ -412,13 +432,13 @@ int launch_select_pick(const Dims &dm, const int32_t *seqlens, const float *R, i
     const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
     timing_begin("select_pick_kernel", stream);
     if (n_blocks <= 64 * 4)
-        hipLaunchKernelGGL(select_pick_kernel<4>, grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+        hipLaunchKernelGGL((select_pick_kernel<4, false>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
     else if (n_blocks <= 64 * 8)
-        hipLaunchKernelGGL(select_pick_kernel<8>, grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+        hipLaunchKernelGGL((select_pick_kernel<8, false>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
     else if (n_blocks <= 64 * 16)
-        hipLaunchKernelGGL(select_pick_kernel<16>, grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+        hipLaunchKernelGGL((select_pick_kernel<16, false>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
     else if (n_blocks <= 64 * 32)
-        hipLaunchKernelGGL(select_pick_kernel<32>, grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+        hipLaunchKernelGGL((select_pick_kernel<32, false>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
     else
         hipLaunchKernelGGL(select_pick_scan_kernel, grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
     timing_end(stream);
@@ -453,6 +473,25 @@ static int launch_select_prefill_g(const Dims &dm, Tensor q, Tensor ck, const in
                        seqlens, lse2, R, nb_cap, n_tiles);
     timing_end(stream);
     return launch_select_pick(dm, seqlens, R, nb_cap, block_idx, stream);
+}
+
+// Decode: one row per (sequence, key-value head); contexts up to 64*64 blocks.
+int launch_select_pick_decode(const Dims &dm, const int32_t *seqlens, const float *R, int32_t nb_cap,
+                              int32_t *block_idx, hipStream_t stream) {
+    const int64_t rows = (int64_t)dm.batch * dm.Hkv;
+    if (rows <= 0) return 0;
+    const dim3 grid((uint32_t)((rows + 3) / 4));
+    const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
+    if (n_blocks > 64 * 64) return (int)hipErrorInvalidValue;         // rejected earlier by the C ABI
+    timing_begin("select_pick_kernel", stream);
+    if (n_blocks <= 64 * 8)
+        hipLaunchKernelGGL((select_pick_kernel<8, true>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+    else if (n_blocks <= 64 * 32)
+        hipLaunchKernelGGL((select_pick_kernel<32, true>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+    else
+        hipLaunchKernelGGL((select_pick_kernel<64, true>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+    timing_end(stream);
+    return (int)hipGetLastError();
 }
 
 int launch_select_prefill(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,

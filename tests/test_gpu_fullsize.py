@@ -1,0 +1,198 @@
+"""GPU parity at the stated workload sizes, in the launch configuration bench.py times.
+The whole path runs on the GPU; the fp64 oracle is evaluated on sampled query rows (rows are
+independent, so a sampled row is checked exactly), and properties that hold at any size are
+checked on every row."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2506_07900_amd import binding, synth
+from util import OUT_TOL, compare_selection, lse_err, oracle_params, to_bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_rows(l, n_random, seed):
+    rng = np.random.default_rng(seed)
+    fixed = [0, 1, 30, 31, 46, 47, 63, 64, 127, 128, 191, 192, 1023, 1024, l - 65, l - 64, l - 2, l - 1]
+    rows = set(int(x) for x in fixed if 0 <= x < l)
+    rows.update(int(x) for x in rng.integers(0, l, n_random))
+    return np.array(sorted(rows), np.int32)
+
+
+def run_prefill_config(cfg_index, n_random):
+    cfg = synth.CONFIGS[cfg_index]
+    print("workload", cfg.name, flush=True)
+    x = synth.make_prefill(cfg)
+    l, Hq, Hkv = cfg.seqlen, cfg.n_q_heads, cfg.n_kv_heads
+    prm = binding.Params(Hq, Hkv, topk=cfg.topk)
+    oprm = oracle_params(prm)
+    q, k, v = to_dev(x.q)[None], to_dev(x.k)[None], to_dev(x.v)[None]
+    sl = torch.tensor([l], dtype=torch.int32, device="cuda")
+    ck = binding.compress_keys(prm, k, sl, l)
+    idx = binding.select_blocks(prm, binding.MODE_PREFILL, q, ck, sl, l)
+    out, lse = binding.sparse_attn_prefill(prm, q, k, v, sl, l, idx)
+    torch.cuda.synchronize()
+    print("gpu path done", flush=True)
+
+    # stage 1: bit-exact against the oracle, whole tensor
+    _, ck_ref = ref.compress_keys(x.k, oprm)
+    assert np.array_equal(to_bits(ck)[0], ck_ref)
+
+    # properties of every row of the selection
+    idx_all = idx[0]                                              # [Hkv, l, topk] on device
+    t = torch.arange(l, device="cuda")
+    b_own = (t // cfg.block_size)[None, :, None]
+    valid = idx_all >= 0
+    n_sel = valid.sum(-1)
+    assert torch.equal(n_sel, torch.minimum(b_own[..., 0] + 1, torch.tensor(cfg.topk, device="cuda")).expand_as(n_sel))
+    assert bool(((idx_all <= b_own) | ~valid).all())
+    srt = torch.where(valid, idx_all, torch.full_like(idx_all, 1 << 30))
+    assert bool((srt[..., 1:] > srt[..., :-1]).logical_or(~valid[..., 1:]).all())      # ascending, no duplicates
+    assert bool((idx_all[..., 0] == 0).all())                                            # initial block
+    has = lambda blk: ((idx_all == blk) & valid).any(-1)
+    assert bool(has(b_own).all()) and bool((has(b_own - 1) | (b_own[..., 0] < 1)).all())  # local blocks
+    assert bool(torch.isfinite(lse).all()) and bool(torch.isfinite(out.float()).all())
+
+    # sampled rows against the oracle
+    rows = sample_rows(l, n_random, 1000 + cfg_index)
+    qs = np.ascontiguousarray(x.q[rows])
+    want_idx, margins, R = ref.select_blocks(qs, ck_ref, rows, oprm, want_scores=True)
+    got_idx = idx_all[:, torch.from_numpy(rows).long().cuda()].cpu().numpy()
+    n, exact, near, hard = compare_selection(got_idx, want_idx, margins, R)
+    print("selection: %d rows, %d exact, %d near-tie, %d hard" % (n, exact, near, len(hard)), flush=True)
+    assert not hard, hard[:3]
+    assert near <= max(2, n // 50)
+    # attention in isolation: the oracle consumes the block sets the GPU attended
+    want_o, want_l = ref.sparse_attn(qs, x.k, x.v, rows, got_idx, oprm)
+    ri = torch.from_numpy(rows).long().cuda()
+    eo = np.abs(out[0, ri].double().cpu().numpy() - want_o).max()
+    el = lse_err(lse[0, ri].double().cpu().numpy(), want_l)
+    print("attention: max|dO| %.3e LSE err/tol %.3f" % (eo, el), flush=True)
+    assert eo <= OUT_TOL and el <= 1.0
+    # planted blocks that are visible and unforced dominate the scored picks (reported, weak bound)
+    hits = []
+    for a, i in enumerate(rows):
+        if i // 64 >= 64:
+            for h in range(Hkv):
+                pl = set(int(p) for p in x.planted[h] if p <= i // 64 - 2)
+                hits.append(len(pl & set(got_idx[h, a].tolist())) / max(1, min(len(pl), cfg.topk - 3)))
+    print("planted hit ratio %.2f" % float(np.mean(hits)), flush=True)
+    assert np.mean(hits) > 0.5
+
+
+@pytest.mark.timeout(300)
+def test_prefill_32k_sampled_rows():
+    run_prefill_config(1, 150)
+
+
+@pytest.mark.timeout(600)
+def test_prefill_128k_sampled_rows():
+    run_prefill_config(2, 60)
+
+
+@pytest.mark.timeout(600)
+def test_decode_ragged_batch8_steps():
+    # the ragged decode workload: 8 sequences of different cached lengths, four with heavy-tailed
+    # key norms; a few real decode steps, every sequence checked against the oracle
+    cfg = synth.CONFIGS[4]
+    steps = 6
+    print("workload", cfg.name, flush=True)
+    x = synth.make_decode(cfg, steps=steps)
+    B, Hq, Hkv = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads
+    prm = binding.Params(Hq, Hkv, topk=cfg.topk)
+    oprm = oracle_params(prm)
+    cap = x.capacity
+    kd, vd = to_dev(x.k_cache), to_dev(x.v_cache)
+    lens = x.seqlens0.copy()
+    print("contexts", lens.tolist(), flush=True)
+    sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    ck = binding.compress_keys(prm, kd, sl, cap)
+    k_np, v_np = x.k_cache, x.v_cache
+    tot = exact = near = 0
+    for s in range(steps):
+        lens = lens + 1
+        sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+        qd = to_dev(x.q_steps[s][:, None])
+        binding.append_kv(prm, to_dev(x.k_steps[s][:, :, None]), to_dev(x.v_steps[s][:, :, None]), kd, vd, sl, cap)
+        binding.compress_keys(prm, kd, sl, cap, ck=ck, n_new_tokens=1)
+        idx = binding.select_blocks(prm, binding.MODE_DECODE, qd, ck, sl, cap)
+        out, lse = binding.sparse_attn_decode(prm, qd, kd, vd, sl, cap, idx)
+        torch.cuda.synchronize()
+        for b in range(B):
+            k_np[b, :, lens[b] - 1] = x.k_steps[s][b]
+            v_np[b, :, lens[b] - 1] = x.v_steps[s][b]
+        if s in (0, steps - 1):
+            ckb = to_bits(ck)
+            idx_np = idx.cpu().numpy()
+            for b in range(B):
+                l = int(lens[b])
+                pos = np.array([l - 1], np.int32)
+                _, ck_ref = ref.compress_keys(k_np[b, :, :l], oprm)
+                assert np.array_equal(ckb[b, :, :ck_ref.shape[1]], ck_ref), (s, b)
+                q1 = x.q_steps[s][b][None]
+                ib, margins, R = ref.select_blocks(q1, ck_ref, pos, oprm, want_scores=True)
+                n, e, nt, hard = compare_selection(idx_np[b], ib, margins, R)
+                assert not hard, (s, b, hard)
+                tot, exact, near = tot + n, exact + e, near + nt
+                wo, wl = ref.sparse_attn(q1, k_np[b, :, :l], v_np[b, :, :l], pos, idx_np[b], oprm)
+                eo = np.abs(out[b].double().cpu().numpy() - wo).max()
+                el = lse_err(lse[b].double().cpu().numpy(), wl[0])
+                assert eo <= OUT_TOL and el <= 1.0, (s, b, eo, el, float(np.abs(wl).max()))
+    print("ragged decode: %d rows, %d exact, %d near-tie" % (tot, exact, near), flush=True)
+
+
+def test_decode_graph_replays_match_eager():
+    # a captured decode step must give the eager result on every replay, with eager work and
+    # synchronisations in between
+    cfg = synth.CONFIGS[3]
+    chunk, reps, L0 = 4, 3, 3000
+    x = synth.make_decode(cfg, steps=chunk * reps + 2, seqlen=L0)
+    Hq, Hkv, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    prm = binding.Params(Hq, Hkv, topk=cfg.topk)
+    cap = x.capacity
+    qs = to_dev(x.q_steps)[:, :, None].contiguous()
+    ks = to_dev(x.k_steps)[:, :, :, None].contiguous()
+    vs = to_dev(x.v_steps)[:, :, :, None].contiguous()
+
+    def make_state():
+        st = dict(kc=to_dev(x.k_cache), vc=to_dev(x.v_cache),
+                  sl=torch.tensor(x.seqlens0, dtype=torch.int32, device="cuda"),
+                  idx=torch.full((1, Hkv, 1, cfg.topk), -1, dtype=torch.int32, device="cuda"),
+                  out=torch.zeros((1, 1, Hq, d), dtype=torch.bfloat16, device="cuda"),
+                  lse=torch.zeros((1, Hq), dtype=torch.float32, device="cuda"),
+                  ws1=torch.empty(binding.workspace_bytes(binding.OP_SELECT_DECODE, prm, 1, cap), dtype=torch.uint8, device="cuda"),
+                  ws2=torch.empty(binding.workspace_bytes(binding.OP_ATTN_DECODE, prm, 1, cap), dtype=torch.uint8, device="cuda"))
+        st["ck"] = binding.compress_keys(prm, st["kc"], st["sl"], cap)
+        return st
+
+    def step(st, s):
+        st["sl"].add_(1)
+        binding.append_kv(prm, ks[s], vs[s], st["kc"], st["vc"], st["sl"], cap)
+        binding.compress_keys(prm, st["kc"], st["sl"], cap, ck=st["ck"], n_new_tokens=1)
+        binding.select_blocks(prm, binding.MODE_DECODE, qs[s], st["ck"], st["sl"], cap, block_idx=st["idx"], workspace=st["ws1"])
+        binding.sparse_attn_decode(prm, qs[s], st["kc"], st["vc"], st["sl"], cap, st["idx"], out=st["out"], lse=st["lse"], workspace=st["ws2"])
+
+    g_st, e_st = make_state(), make_state()
+    for st in (g_st, e_st):
+        step(st, 0)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for s in range(1, 1 + chunk):
+                step(g_st, s)
+    torch.cuda.synchronize()
+    for r in range(reps):
+        graph.replay()
+        for s in range(1, 1 + chunk):            # eager twin: same inputs, its own buffers
+            step(e_st, s)
+        torch.cuda.synchronize()
+        assert torch.equal(g_st["sl"], e_st["sl"]), r
+        assert torch.equal(g_st["idx"], e_st["idx"]), r
+        assert torch.equal(g_st["out"].view(torch.int16), e_st["out"].view(torch.int16)), r
+        assert torch.equal(g_st["lse"], e_st["lse"]), r
+        assert torch.equal(g_st["ck"].view(torch.int16), e_st["ck"].view(torch.int16)), r

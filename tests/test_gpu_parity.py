@@ -7,7 +7,7 @@ import torch
 
 from oracle import ref
 from paper_2506_07900_amd import binding, synth
-from util import LSE_TOL, OUT_TOL, compare_selection, oracle_params, to_bits, to_dev
+from util import OUT_TOL, compare_selection, lse_err, oracle_params, to_bits, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -144,9 +144,9 @@ def test_sparse_attn_prefill(seqlens, Hq, Hkv, topk, planted):
         if l:
             want_o, want_l = outs[b]
             eo = np.abs(o[b, :l] - want_o).max()
-            el = np.abs(ls[b, :l] - want_l).max()
-            print("seq %d len %d: max|dO| %.3e max|dLSE| %.3e" % (b, l, eo, el), flush=True)
-            assert eo <= OUT_TOL and el <= LSE_TOL
+            el = lse_err(ls[b, :l], want_l)
+            print("seq %d len %d: max|dO| %.3e LSE err/tol %.3f" % (b, l, eo, el), flush=True)
+            assert eo <= OUT_TOL and el <= 1.0
         assert np.all(o[b, l:] == 3.0) and np.all(ls[b, l:] == 5.0)     # padding rows untouched
 
 
@@ -197,9 +197,9 @@ def test_decode_select_and_attn(seqlens, Hq, Hkv, topk):
     torch.cuda.synchronize()
     for b in range(B):
         eo = np.abs(out[b].double().cpu().numpy() - want[b][0]).max()
-        el = np.abs(lse[b].double().cpu().numpy() - want[b][1][0]).max()
-        print("seq %d len %d: max|dO| %.3e max|dLSE| %.3e" % (b, seqlens[b], eo, el), flush=True)
-        assert eo <= OUT_TOL and el <= LSE_TOL
+        el = lse_err(lse[b].double().cpu().numpy(), want[b][1][0])
+        print("seq %d len %d: max|dO| %.3e LSE err/tol %.3f" % (b, seqlens[b], eo, el), flush=True)
+        assert eo <= OUT_TOL and el <= 1.0
 
 
 def test_decode_steps_with_append_and_incremental_compress():
@@ -241,5 +241,5 @@ def test_decode_steps_with_append_and_incremental_compress():
             if nt == 0:
                 wo, wl = ref.sparse_attn(x.q_steps[s][0][None], k_np[0, :, :l], v_np[0, :, :l], pos, ib, oprm)
                 assert np.abs(out[0].double().cpu().numpy() - wo).max() <= OUT_TOL
-                assert np.abs(lse[0].double().cpu().numpy() - wl[0]).max() <= LSE_TOL
+                assert lse_err(lse[0].double().cpu().numpy(), wl[0]) <= 1.0
     assert torch.equal(kd.view(torch.int16).cpu(), torch.from_numpy(k_np.view(np.int16)))

@@ -13,6 +13,17 @@ LSE_TOL = 1e-5
 NEAR_TIE = 1e-3
 
 
+def lse_err(got, want):
+    """Largest log-sum-exp error in units of its tolerance (<= 1 passes).  The tolerance is the
+    stated 1e-5 absolute, widened to 2^-20 * |LSE| (16 fp32 ulps) where |LSE| is so large that
+    fp32 cannot hold 1e-5: heavy-tailed keys give |LSE| in the hundreds, whose ulp alone is
+    1.5e-5, and the dominant logit is a 128-term fp32 sum (rounding grows like sqrt(128) ulps)."""
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    tol = np.maximum(LSE_TOL, 2.0 ** -20 * np.abs(want))
+    return float(np.max(np.abs(got - want) / tol)) if want.size else 0.0
+
+
 def to_dev(bits):
     """uint16 bf16 bit patterns (numpy) -> bf16 tensor on cuda:0."""
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)

@@ -48,6 +48,20 @@ def visible_pairs(l, p=32, s=16):
     return int(np.where(i + 1 >= p, (i + 1 - p) // s + 1, 0).sum())
 
 
+def measured_hbm_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary (scaled
+    FETCH_SIZE + WRITE_SIZE), or None when the summary has no row for it."""
+    path = os.path.join(ROOT, "profiles", "prefill_32k_hbm_traffic.md")
+    try:
+        for line in open(path):
+            cells = [c.strip() for c in line.split("|")]
+            if len(cells) >= 7 and cells[1].strip("`").startswith(kernel):
+                return (float(cells[4]) + float(cells[5])) * 1e6
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def bench_prefill(args):
     import torch
     from paper_2506_07900_amd import binding, synth
@@ -108,7 +122,7 @@ def bench_prefill(args):
     if dominant in flops_of:
         ach = flops_of[dominant] / (kern_ms[dominant] * 1e-3) / 1e12
         roofline = {"kernel": dominant, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                    "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": measured_hbm_traffic(dominant),
                     "flops_per_launch": flops_of[dominant], "avg_launch_ms": kern_ms[dominant]}
     else:
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": None, "peak": PEAK_HBM_GBS,
@@ -129,7 +143,7 @@ def bench_decode(args):
     cfg = synth.CONFIGS[3]
     steps = args.decode_steps
     log("[bench] generating %s inputs (%d steps)" % (cfg.name, steps))
-    x = synth.make_decode(cfg, steps=steps)
+    x = synth.make_decode(cfg, steps=steps + 128)      # head-room: the graph is replayed once untimed
     prm = binding.Params(cfg.n_q_heads, cfg.n_kv_heads, topk=cfg.topk)
     Hq, Hkv, d, m = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.block_size
 
@@ -250,6 +264,9 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=4096)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain 1 GiB read + 1 GiB write elementwise kernel, the known-size "
+                         "reference the rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (multi-GPU sharding is design only)",
@@ -262,6 +279,13 @@ def main():
     from paper_2506_07900_amd import binding
     binding.load_library()          # fails loudly when the HIP library is missing
 
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     res, (x, idx, out, lse, prm, cfg) = bench_prefill(args)
     line = {
         "metric": "sparse-attn prefill TFLOP/s (% bf16 MFMA peak); 128K decode us/token (% HBM BW)",

@@ -78,7 +78,7 @@ def load_library(path=None):
     global _lib
     if _lib is not None and path is None:
         return _lib
-    path = path or LIB_PATH
+    path = path or os.environ.get("INFLLMV2_LIB") or LIB_PATH     # INFLLMV2_LIB: use another build of the library
     if not os.path.exists(path):
         raise InfLLMv2Error("HIP library not built: %s is missing (run python -m paper_2506_07900_amd.build)" % path)
     lib = ctypes.CDLL(path)

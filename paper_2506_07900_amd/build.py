@@ -11,7 +11,10 @@ LIB = os.path.join(HERE, "libinfllmv2.so")
 SOURCES = ["api.hip", "compress_keys.hip", "select_prefill.hip", "select_prefill16.hip", "attn_prefill.hip", "decode.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed fp32 VALU forms are kept out of the generated code on the test machines
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # MFMA results go to ordinary vector registers: the softmax arithmetic consumes them
+         # directly, with no copies out of the accumulation registers
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1"]
 
 
 def build(verbose=False):

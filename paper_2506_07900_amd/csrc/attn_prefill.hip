@@ -21,6 +21,7 @@
 // from the accumulator layout of S^T (lane = head column, 4 consecutive keys per 16-lane group),
 // with the key order inside the packed V^T rows permuted to match.
 #include "common.h"
+#include <cstdlib>
 
 namespace infllmv2 {
 
@@ -99,15 +100,46 @@ __global__ __launch_bounds__(256) void pack_kv_kernel(Dims dm, Tensor k, Tensor 
 }
 
 // ---- attention ---------------------------------------------------------------------------------------
-// kPrefetch: keep the next operand's 16 fragments in flight while computing on the current one
-// (K during the value phase, V during the score phase); costs 64 more registers per lane.
-template <int kTok, bool kPrefetch, int kWavesPerSimd>
+// A block is processed as two halves of 32 keys.  The operand fragments of a block are fetched in
+// 8 units of 4 fragments (4 KiB per wavefront), in the order they are consumed:
+//   half hs:  K rows of key tile 2hs (all four 32-channel k-steps), K rows of key tile 2hs+1,
+//             V^T of the half's 32 keys for channel tiles 0..3, then for channel tiles 4..7
+// They rotate through a ring of kNU register buffers: as soon as the matrix cores have consumed
+// a unit, the load of the unit kNU places further down the stream (same block, or the next block
+// of the wavefront's list) is issued into the same registers, so loads stay in flight under the
+// wavefront's own arithmetic.
+//
+// The softmax keeps a per-head reference exponent taken from the data and re-bases it only when
+// a partial sum leaves the safe range (or on first use, when it is still NaN): the common path is
+// one fma, one exp2 and one add per probability, with no running maximum.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+constexpr float kPsumLimit = 0x1p40f;
+constexpr int kNone = 0x7fffffff;
+constexpr int kBlkBits = 27, kBlkMask = (1 << kBlkBits) - 1;
+
+// probabilities 2^(s*c + ne) of 32 keys (two key tiles) of one token in MFMA B layout, and their sum
+__device__ __forceinline__ float half_probs(const f32x4 (&s)[2], float c, float ne, bf16x8 &p8) {
+    float sum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float p = fast_exp2(__builtin_fmaf(s[t][j], c, ne));
+            sum += p;
+            p8[4 * t + j] = (__bf16)p;
+        }
+    return sum;
+}
+
+template <int kTok, int kNU, int kWavesPerSimd>
 __global__ __launch_bounds__(256, kWavesPerSimd) void attn_prefill_kernel(Dims dm, Tensor q, const uint4 *__restrict__ kvp,
                                                             int32_t nb_cap,
                                                             const int32_t *__restrict__ seqlens,
                                                             const int32_t *__restrict__ block_idx,
                                                             Tensor out, float *__restrict__ lse,
                                                             int32_t n_tiles) {
+    static_assert(kNU == 4 || kNU == 8, "ring of 4 or 8 units");
+    static_assert(kTok <= 4 && 64 % kTok == 0, "membership bits / one own block per wavefront");
     // a workgroup is 4 independent wavefronts covering 4*kTok consecutive tokens
     const uint32_t vid = xcd_contiguous_id(blockIdx.x, gridDim.x);
     const int tile = vid % n_tiles;
@@ -121,10 +153,11 @@ __global__ __launch_bounds__(256, kWavesPerSimd) void attn_prefill_kernel(Dims d
     const int b_own = t0 / kBlock;                       // kTok divides 64: one own block per wavefront
     const int n = lane & 15, g = lane >> 4;              // MFMA column (query head) and 16-lane group
     const int G = dm.G;
+    const float c = dm.scale_log2;
 
     bf16x8 qf[kTok][4];
     f32x4 o[kTok][8];
-    float m_run[kTok], l_run[kTok];
+    float neg_m[kTok], l_run[kTok];
     int own[kTok];                                       // lane e < topk holds entry e of the block list
 #pragma unroll
     for (int u = 0; u < kTok; ++u) {
@@ -139,128 +172,172 @@ __global__ __launch_bounds__(256, kWavesPerSimd) void attn_prefill_kernel(Dims d
         }
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) o[u][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        m_run[u] = -INFINITY;
+        neg_m[u] = __builtin_nanf("");
         l_run[u] = 0.f;
-        int e = 0x7fffffff;
+        int e = kNone;
         if (live && lane < dm.topk) {
             int x = block_idx[(((int64_t)b * dm.Hkv + h) * dm.max_seqlen + tok) * dm.topk + lane];
             if (x >= 0 && x <= b_own) e = x;
         }
         own[u] = e;
     }
-    const uint4 *kv_head = kvp + ((int64_t)b * dm.Hkv + h) * nb_cap * kPackedBlockU4;   // uniform
 
-    auto next_block = [&](int cur) {
-        int cand = 0x7fffffff;
+    // Ascending union of the tokens' block lists, by counting instead of sorting: an entry's place
+    // is the number of distinct smaller entries.  A token's own list holds no duplicates, so an
+    // entry is a duplicate exactly when a lower-numbered token of the wavefront lists the same
+    // block.  Entry i of the union ends up in lane i%64 of ul[i/64] as block | member bits << 27.
+    int w[kTok];                                         // own[u] with duplicates removed
+    w[0] = own[0];
 #pragma unroll
-        for (int u = 0; u < kTok; ++u) {
-            int e = own[u] > cur ? own[u] : 0x7fffffff;
-            cand = e < cand ? e : cand;
+    for (int u = 1; u < kTok; ++u) {
+        bool dup = false;
+#pragma unroll
+        for (int u2 = 0; u2 < u; ++u2)
+            for (int j = 0; j < dm.topk; ++j) dup |= __builtin_amdgcn_readlane(own[u2], j) == own[u];
+        w[u] = dup ? kNone : own[u];
+    }
+    int rank[kTok], bits[kTok];
+#pragma unroll
+    for (int u = 0; u < kTok; ++u) rank[u] = bits[u] = 0;
+#pragma unroll
+    for (int u2 = 0; u2 < kTok; ++u2)
+        for (int j = 0; j < dm.topk; ++j) {
+            const int wj = __builtin_amdgcn_readlane(w[u2], j), xj = __builtin_amdgcn_readlane(own[u2], j);
+#pragma unroll
+            for (int u = 0; u < kTok; ++u) {
+                rank[u] += wj < w[u] ? 1 : 0;            // kNone (absent or duplicate) is never smaller
+                bits[u] |= xj == w[u] ? 1 << u2 : 0;
+            }
         }
-        return __builtin_amdgcn_readfirstlane(wave_min_i32(cand));   // wave-uniform: scalar addressing
+    __shared__ int ulist[4][64 * kTok];
+    int cnt = 0;
+#pragma unroll
+    for (int u = 0; u < kTok; ++u) {
+        const bool have = w[u] != kNone;
+        if (have) ulist[wave][rank[u]] = w[u] | (bits[u] << kBlkBits);
+        cnt += __popcll(__ballot(have));
+    }
+    int ul[kTok];
+#pragma unroll
+    for (int r = 0; r < kTok; ++r) ul[r] = ulist[wave][64 * r + lane];   // same wavefront: LDS keeps the order
+    auto union_entry = [&](int i) __attribute__((always_inline)) {
+        int e = __builtin_amdgcn_readlane(ul[0], i & 63);
+#pragma unroll
+        for (int r = 1; r < kTok; ++r)
+            if ((i >> 6) == r) e = __builtin_amdgcn_readlane(ul[r], i & 63);
+        return e;
     };
 
-    int blk = next_block(-1);
-    uint4 kf[16];
-    if (kPrefetch && blk != 0x7fffffff) {
-        const uint4 *p = kv_head + (int64_t)blk * kPackedBlockU4;
+    const u32x4 *kv_lane = reinterpret_cast<const u32x4 *>(kvp) +
+                           ((int64_t)b * dm.Hkv + h) * nb_cap * kPackedBlockU4 + lane;
+    u32x4 ring[kNU][4];
+    auto issue = [&](int unit, const u32x4 *bp) __attribute__((always_inline)) {
+        const int hs = unit >> 2, r = unit & 3;
+        if (r < 2) {
 #pragma unroll
-        for (int f = 0; f < 16; ++f) kf[f] = p[f * 64 + lane];
-    }
-    while (blk != 0x7fffffff) {
-        uint4 vf[16];
-        if (kPrefetch) {           // value fragments of this block: in flight during the score phase
-            const uint4 *p = kv_head + (int64_t)blk * kPackedBlockU4 + kFragsPerOperand * 64;
-#pragma unroll
-            for (int f = 0; f < 16; ++f) vf[f] = p[f * 64 + lane];
+            for (int ks = 0; ks < 4; ++ks) ring[unit % kNU][ks] = bp[(ks * 4 + 2 * hs + r) * 64];
         } else {
-            const uint4 *p = kv_head + (int64_t)blk * kPackedBlockU4;
 #pragma unroll
-            for (int f = 0; f < 16; ++f) kf[f] = p[f * 64 + lane];
+            for (int i = 0; i < 4; ++i)
+                ring[unit % kNU][i] = bp[(kFragsPerOperand + (4 * (r - 2) + i) * 2 + hs) * 64];
         }
-        bool member[kTok];
+    };
+
+    // softmax of one member token on 32 keys: pf = P^T in bf16; re-bases the reference when needed
+    auto softmax = [&](f32x4 (&s)[2], int u, bf16x8 &pf) __attribute__((always_inline)) {
+        float ps = half_probs(s, c, neg_m[u], pf);
+        if (__any(!(ps <= kPsumLimit))) {                 // rare: too large, inf, or NaN (no reference yet)
+            float tmax = -INFINITY;
 #pragma unroll
-        for (int u = 0; u < kTok; ++u) member[u] = __ballot(own[u] == blk) != 0ull;
-        const int nxt = next_block(blk);
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) tmax = fmaxf(tmax, s[t][j]);
+            tmax = xgroup_max(tmax) * c;                  // per head, same in the four lane groups
+            const float old = neg_m[u];                   // NaN = no reference yet
+            const float m_new = (old != old) ? tmax : fmaxf(-old, tmax);
+            if (m_new > -INFINITY) {
+                const float f = (old != old) ? 0.f : fast_exp2(-old - m_new);
+                l_run[u] *= f;
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) o[u][dt] *= f;
+                neg_m[u] = -m_new;
+                ps = half_probs(s, c, -m_new, pf);
+            } else {                                      // every key of this head masked so far
+                ps = 0.f;
+                pf = zero8();
+            }
+        }
+        l_run[u] += ps;
+    };
+
+    // Everything loaded so far (queries, block lists) has to land before the ring starts: the
+    // compiler's wait-count bookkeeping otherwise merges those pending loads into the loop and
+    // waits for ALL outstanding loads at the top of every iteration, which defeats the ring.
+    __builtin_amdgcn_s_waitcnt(0);
+    if (cnt > 0) {
+        const u32x4 *bp = kv_lane + (int64_t)(union_entry(0) & kBlkMask) * kPackedBlockU4;
+#pragma unroll
+        for (int unit = 0; unit < kNU; ++unit) issue(unit, bp);
+    }
+    for (int ci = 0; ci < cnt; ++ci) {
+        const int e = union_entry(ci);
+        const int blk = e & kBlkMask, bits = e >> kBlkBits;
+        const bool has_next = ci + 1 < cnt;
+        const int en = union_entry(has_next ? ci + 1 : ci);
+        const u32x4 *bp = kv_lane + (int64_t)blk * kPackedBlockU4;
+        const u32x4 *bn = kv_lane + (int64_t)(en & kBlkMask) * kPackedBlockU4;
         const int key0 = blk * kBlock;
         const bool edge = (blk == b_own) || (key0 + kBlock > L);
-
-        // ---- S^T = K . Q^T, online softmax, P^T packed to bf16 in MFMA B layout -----------------
-        bf16x8 pf[kTok][2];
 #pragma unroll
-        for (int u = 0; u < kTok; ++u) {
-            if (!member[u]) continue;
-            f32x4 s[4];
+        for (int hs = 0; hs < 2; ++hs) {
+            // ---- S^T = K . Q^T for 32 keys, one key tile per unit ------------------------------
+            f32x4 s[kTok][2];
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) s[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int r = 0; r < 2; ++r) {
+                const int unit = 4 * hs + r;
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
+                for (int u = 0; u < kTok; ++u) {
+                    if (!((bits >> u) & 1)) continue;
+                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-                    s[mt] = mfma16(__builtin_bit_cast(bf16x8, kf[ks * 4 + mt]), qf[u][ks], s[mt]);
-            const int tok = t0 + u;
-            float mx = -INFINITY;
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    float x = s[mt][j] * dm.scale_log2;
-                    if (edge && key0 + 16 * mt + 4 * g + j > tok) x = -INFINITY;
-                    s[mt][j] = x;
-                    mx = fmaxf(mx, x);
+                    for (int ks = 0; ks < 4; ++ks)
+                        acc = mfma16(__builtin_bit_cast(bf16x8, ring[unit % kNU][ks]), qf[u][ks], acc);
+                    s[u][r] = acc;
                 }
-            mx = xgroup_max(mx);
-            const float m_new = fmaxf(m_run[u], mx);
-            const float m_use = m_new == -INFINITY ? 0.f : m_new;
-            const float alpha = fast_exp2(m_run[u] - m_use);
-            float psum = 0.f;
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    float p = fast_exp2(s[mt][j] - m_use);
-                    s[mt][j] = p;
-                    psum += p;
-                }
-            l_run[u] = l_run[u] * alpha + psum;
-            m_run[u] = m_new;
-            if (__any(alpha != 1.f)) {
-#pragma unroll
-                for (int dt = 0; dt < 8; ++dt) o[u][dt] *= alpha;
+                if (unit + kNU < 8) issue(unit + kNU, bp);
+                else issue(unit + kNU - 8, bn);      // (a harmless re-read of this block at the tail)
             }
+            // ---- probabilities, P^T packed to bf16 in MFMA B layout ---------------------------
+            bf16x8 pf[kTok];
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                bf16x8 p8;
+            for (int u = 0; u < kTok; ++u) {
+                if (!((bits >> u) & 1)) continue;
+                if (edge) {
+                    const int tok = t0 + u;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    p8[j] = (__bf16)s[2 * kk][j];
-                    p8[4 + j] = (__bf16)s[2 * kk + 1][j];
+                    for (int t = 0; t < 2; ++t)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (key0 + 32 * hs + 16 * t + 4 * g + j > tok) s[u][t][j] = -INFINITY;
                 }
-                pf[u][kk] = p8;
+                softmax(s[u], u, pf[u]);
+            }
+            // ---- O^T += V^T . P^T, four channel tiles per unit --------------------------------
+#pragma unroll
+            for (int r = 2; r < 4; ++r) {
+                const int unit = 4 * hs + r, dh = r - 2;
+#pragma unroll
+                for (int u = 0; u < kTok; ++u) {
+                    if (!((bits >> u) & 1)) continue;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        o[u][4 * dh + i] =
+                            mfma16(__builtin_bit_cast(bf16x8, ring[unit % kNU][i]), pf[u], o[u][4 * dh + i]);
+                }
+                if (unit + kNU < 8) issue(unit + kNU, bp);
+                else issue(unit + kNU - 8, bn);      // (a harmless re-read of this block at the tail)
             }
         }
-        if (kPrefetch) {           // key fragments of the next block: in flight during the value phase
-            if (nxt != 0x7fffffff) {
-                const uint4 *p = kv_head + (int64_t)nxt * kPackedBlockU4;
-#pragma unroll
-                for (int f = 0; f < 16; ++f) kf[f] = p[f * 64 + lane];
-            }
-        } else {
-            const uint4 *p = kv_head + (int64_t)blk * kPackedBlockU4 + kFragsPerOperand * 64;
-#pragma unroll
-            for (int f = 0; f < 16; ++f) vf[f] = p[f * 64 + lane];
-        }
-        // ---- O^T += V^T . P^T ----------------------------------------------------------------------
-#pragma unroll
-        for (int u = 0; u < kTok; ++u) {
-            if (!member[u]) continue;
-#pragma unroll
-            for (int dt = 0; dt < 8; ++dt)
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk)
-                    o[u][dt] = mfma16(__builtin_bit_cast(bf16x8, vf[dt * 2 + kk]), pf[u][kk], o[u][dt]);
-        }
-        blk = nxt;
     }
 
     // ---- normalise and write: lane holds channels 16*dt + 4*g .. +3 of head n ------------------
@@ -269,7 +346,7 @@ __global__ __launch_bounds__(256, kWavesPerSimd) void attn_prefill_kernel(Dims d
         const int tok = t0 + u;
         if (tok >= L || n >= G) continue;
         const float l_tot = xgroup_sum(l_run[u]);
-        const float inv = 1.f / l_tot;
+        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
         __bf16 *op = out.ptr + b * out.sb + (int64_t)tok * out.st + (int64_t)(h * G + n) * out.sh + 4 * g;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
@@ -279,7 +356,8 @@ __global__ __launch_bounds__(256, kWavesPerSimd) void attn_prefill_kernel(Dims d
             *reinterpret_cast<uint2 *>(op + 16 * dt) = __builtin_bit_cast(uint2, r);
         }
         if (g == 0)
-            lse[((int64_t)b * dm.max_seqlen + tok) * dm.Hq + h * G + n] = (m_run[u] + fast_log2(l_tot)) * kLn2;
+            lse[((int64_t)b * dm.max_seqlen + tok) * dm.Hq + h * G + n] =
+                l_tot > 0.f ? (fast_log2(l_tot) - neg_m[u]) * kLn2 : -INFINITY;
     }
 }
 
@@ -288,9 +366,17 @@ size_t attn_prefill_ws_bytes(const Dims &dm) {
     return (size_t)dm.batch * dm.Hkv * nb_cap * kPackedBlockU4 * sizeof(uint4);
 }
 
+template <int kTok, int kNU, int kWavesPerSimd>
+static void launch_attn_variant(const Dims &dm, Tensor q, const uint4 *kvp, int32_t nb_cap, const int32_t *seqlens,
+                                const int32_t *block_idx, Tensor out, float *lse, hipStream_t stream) {
+    const int32_t n_tiles = (dm.max_seqlen + 4 * kTok - 1) / (4 * kTok);
+    const int64_t n_wg = (int64_t)n_tiles * dm.Hkv * dm.batch;
+    hipLaunchKernelGGL((attn_prefill_kernel<kTok, kNU, kWavesPerSimd>), dim3((uint32_t)n_wg), dim3(256), 0, stream,
+                       dm, q, kvp, nb_cap, seqlens, block_idx, out, lse, n_tiles);
+}
+
 int launch_attn_prefill(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32_t *seqlens,
                         const int32_t *block_idx, Tensor out, float *lse, void *ws, hipStream_t stream) {
-    constexpr int kTok = 2;
     const int32_t nb_cap = (dm.max_seqlen + kBlock - 1) / kBlock;
     if (nb_cap <= 0 || dm.batch <= 0) return 0;
     uint4 *kvp = reinterpret_cast<uint4 *>(ws);
@@ -298,11 +384,14 @@ int launch_attn_prefill(const Dims &dm, Tensor q, Tensor k, Tensor v, const int3
     hipLaunchKernelGGL(pack_kv_kernel, dim3(nb_cap, dm.Hkv, dm.batch), dim3(256), 0, stream, dm, k, v,
                        seqlens, kvp, nb_cap);
     timing_end(stream);
-    const int32_t n_tiles = (dm.max_seqlen + 4 * kTok - 1) / (4 * kTok);
-    const int64_t n_wg = (int64_t)n_tiles * dm.Hkv * dm.batch;
+    static const int variant = [] {
+        const char *e = getenv("INFLLMV2_ATTN_VARIANT");
+        return e ? atoi(e) : 0;
+    }();
     timing_begin("attn_prefill_kernel", stream);
-    hipLaunchKernelGGL((attn_prefill_kernel<kTok, false, 2>), dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, kvp,
-                       nb_cap, seqlens, block_idx, out, lse, n_tiles);
+    if (variant == 1) launch_attn_variant<4, 8, 1>(dm, q, kvp, nb_cap, seqlens, block_idx, out, lse, stream);
+    else if (variant == 2) launch_attn_variant<2, 8, 1>(dm, q, kvp, nb_cap, seqlens, block_idx, out, lse, stream);
+    else launch_attn_variant<2, 4, 2>(dm, q, kvp, nb_cap, seqlens, block_idx, out, lse, stream);
     timing_end(stream);
     return (int)hipGetLastError();
 }

@@ -102,7 +102,7 @@ __device__ inline void mfma_half(const Frag4 &fr, const bf16x8 (&qf)[kMT][4], in
 // four 16-lane groups are merged at the end.  m_ref is a logit of the row itself, re-based only
 // when a partial sum leaves the safe range, so the common path has no max tracking at all:
 // neg_m = -m_ref starts as NaN, which sends the first tile through the re-basing path.
-__global__ __launch_bounds__(256) void select_lse16_kernel(Dims dm, Tensor q, const uint4 *__restrict__ ckp,
+__global__ __launch_bounds__(256, 2) void select_lse16_kernel(Dims dm, Tensor q, const uint4 *__restrict__ ckp,
                                                             int32_t nt_cap, const int32_t *__restrict__ seqlens,
                                                             float *__restrict__ lse2, int32_t n_tiles) {
     const int tile = n_tiles - 1 - (int)(blockIdx.x % n_tiles);       // longest rows first
@@ -165,20 +165,28 @@ __global__ __launch_bounds__(256) void select_lse16_kernel(Dims dm, Tensor q, co
 
     f32x4 zA[kHalf], zB[kHalf];
     if (nt_full > 0) {
-        Frag4 fr = load_ck_tile(ckp_head, 0, lane);
-        Frag4 fr_next = fr;
-        if (nt_full > 1) fr_next = load_ck_tile(ckp_head, 1, lane);
-        mfma_half<true>(fr, qf, 0, zA);
-        mfma_half<true>(fr, qf, kHalf, zB);
+        // two fragment buffers that swap roles each tile (the loop is unrolled by two so that no
+        // register copies are needed): one feeds the matrix cores, the other receives the next tile
+        Frag4 f0 = load_ck_tile(ckp_head, 0, lane);
+        Frag4 f1 = f0;
+        if (nt_full > 1) f1 = load_ck_tile(ckp_head, 1, lane);
+        mfma_half<true>(f0, qf, 0, zA);
+        mfma_half<true>(f0, qf, kHalf, zB);
         finish(zA, 0);
-        for (int t = 1; t < nt_full; ++t) {
-            fr = fr_next;
-            if (t + 1 < nt_full) fr_next = load_ck_tile(ckp_head, t + 1, lane);
-            mfma_half<true>(fr, qf, 0, zA);              // matrix work on half A of tile t ...
-            finish(zB, kHalf);                           // ... alternates with half B of tile t-1
-            mfma_half<true>(fr, qf, kHalf, zB);
+        auto tile_step = [&](const Frag4 &f) {
+            mfma_half<true>(f, qf, 0, zA);               // matrix work on half A of this tile ...
+            finish(zB, kHalf);                           // ... alternates with half B of the previous tile
+            mfma_half<true>(f, qf, kHalf, zB);
             finish(zA, 0);
+        };
+        int t = 1;
+        for (; t + 1 < nt_full; t += 2) {
+            f0 = load_ck_tile(ckp_head, t + 1, lane);
+            tile_step(f1);
+            if (t + 2 < nt_full) f1 = load_ck_tile(ckp_head, t + 2, lane);
+            tile_step(f0);
         }
+        if (t < nt_full) tile_step(f1);
         finish(zB, kHalf);
     }
     for (int t = nt_full; t < nt_all; ++t) {             // causal edge: at most two masked tiles
@@ -211,7 +219,7 @@ __global__ __launch_bounds__(256) void select_lse16_kernel(Dims dm, Tensor q, co
 // Lane = kernel n of the tile, accumulator entries = heads 4g..4g+3 of the token.  Writes the
 // block scores R[token, j] of the candidate blocks j in [n_init, b_own - n_local] (-inf when no
 // visible kernel intersects the block); select_pick_kernel ranks them.
-__global__ __launch_bounds__(256) void select_score16_kernel(Dims dm, Tensor q, const uint4 *__restrict__ ckp,
+__global__ __launch_bounds__(256, 2) void select_score16_kernel(Dims dm, Tensor q, const uint4 *__restrict__ ckp,
                                                               int32_t nt_cap, const int32_t *__restrict__ seqlens,
                                                               const float *__restrict__ lse2,
                                                               float *__restrict__ R, int32_t nb_cap,
@@ -294,20 +302,27 @@ __global__ __launch_bounds__(256) void select_score16_kernel(Dims dm, Tensor q, 
     };
 
     f32x4 zA[kHalf], zB[kHalf];
-    Frag4 fr = load_ck_tile(ckp_head, 0, lane);
-    Frag4 fr_next = fr;
-    if (nt_all > 1) fr_next = load_ck_tile(ckp_head, 1, lane);
-    mfma_half<false>(fr, qf, 0, zA);
-    mfma_half<false>(fr, qf, kHalf, zB);
+    // two fragment buffers that swap roles each tile (loop unrolled by two: no register copies)
+    Frag4 f0 = load_ck_tile(ckp_head, 0, lane);
+    Frag4 f1 = f0;
+    if (nt_all > 1) f1 = load_ck_tile(ckp_head, 1, lane);
+    mfma_half<false>(f0, qf, 0, zA);
+    mfma_half<false>(f0, qf, kHalf, zB);
     finish(zA, 0, 0);
-    for (int t = 1; t < nt_all; ++t) {
-        fr = fr_next;
-        if (t + 1 < nt_all) fr_next = load_ck_tile(ckp_head, t + 1, lane);
-        mfma_half<false>(fr, qf, 0, zA);                 // matrix work on half A of tile t ...
+    auto tile_step = [&](const Frag4 &f, int t) {
+        mfma_half<false>(f, qf, 0, zA);                  // matrix work on half A of tile t ...
         finish(zB, 1, t - 1);                            // ... alternates with the epilogue of half B, tile t-1
-        mfma_half<false>(fr, qf, kHalf, zB);
+        mfma_half<false>(f, qf, kHalf, zB);
         finish(zA, 0, t);
+    };
+    int t = 1;
+    for (; t + 1 < nt_all; t += 2) {
+        f0 = load_ck_tile(ckp_head, t + 1, lane);
+        tile_step(f1, t);
+        if (t + 2 < nt_all) f1 = load_ck_tile(ckp_head, t + 2, lane);
+        tile_step(f0, t + 1);
     }
+    if (t < nt_all) tile_step(f1, t);
     finish(zB, 1, nt_all - 1);
 }
 

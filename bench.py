@@ -165,8 +165,8 @@ def bench_decode(args):
     ws_sel = torch.empty(binding.workspace_bytes(binding.OP_SELECT_DECODE, prm, B, cap), dtype=torch.uint8, device="cuda")
     ws_att = torch.empty(binding.workspace_bytes(binding.OP_ATTN_DECODE, prm, B, cap), dtype=torch.uint8, device="cuda")
 
-    def step(s):
-        sl.add_(1)
+    def step(s, sl):
+        """One decoded token; sl holds the sequence lengths INCLUDING the new token."""
         binding.append_kv(prm, ks[s], vs[s], kc, vc, sl, cap)
         binding.compress_keys(prm, kc, sl, cap, ck=ck, n_new_tokens=1)
         binding.select_blocks(prm, binding.MODE_DECODE, qs[s], ck, sl, cap, block_idx=idx, workspace=ws_sel)
@@ -174,10 +174,11 @@ def bench_decode(args):
 
     n_warm = min(20, max(1, steps // 10))
     for s in range(n_warm):
-        step(s)
+        sl.add_(1)
+        step(s, sl)
     torch.cuda.synchronize()
     timed = steps - n_warm
-    launch = "eager, 7 kernels per step"
+    launch = "eager launches"
     chunk = min(100, timed)
     graph = None
     if chunk >= 10:
@@ -185,10 +186,14 @@ def bench_decode(args):
             side = torch.cuda.Stream()
             side.wait_stream(torch.cuda.current_stream())
             graph = torch.cuda.CUDAGraph()
+            # the serving loop knows every length in advance: one row of lengths per captured step,
+            # advanced by `chunk` at the end of the graph so that each replay continues the context
+            sl_tab = (sl[None, :] + torch.arange(1, chunk + 1, dtype=torch.int32, device="cuda")[:, None]).contiguous()
             with torch.cuda.stream(side):
                 with torch.cuda.graph(graph, stream=side):
-                    for s in range(n_warm, n_warm + chunk):
-                        step(s)
+                    for i in range(chunk):
+                        step(n_warm + i, sl_tab[i])
+                    sl_tab.add_(chunk)
             torch.cuda.synchronize()
         except Exception as exc:              # capture unsupported: time the eager loop instead
             log("[bench] graph capture failed (%r); timing eager launches" % (exc,))
@@ -207,10 +212,13 @@ def bench_decode(args):
     else:
         t0 = time.perf_counter()
         for s in range(n_warm, steps):
-            step(s)
+            sl.add_(1)
+            step(s, sl)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
     us = (t1 - t0) * 1e6 / timed
+    if graph is not None:
+        sl = sl_tab[0] - 1                     # lengths reached after the last replay
     L = int(sl[0].item()) - timed // 2
     n_c = (L - 32) // 16 + 1
     gathered = Hkv * cfg.topk * m * d * 2 * 2

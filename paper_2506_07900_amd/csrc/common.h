@@ -91,8 +91,6 @@ int32_t select_scores_pitch(const Dims &dm);
 size_t select_scores_bytes(const Dims &dm);
 int launch_select_pick(const Dims &dm, const int32_t *seqlens, const float *R, int32_t nb_cap,
                        int32_t *block_idx, hipStream_t stream);
-int launch_select_pick_decode(const Dims &dm, const int32_t *seqlens, const float *R, int32_t nb_cap,
-                              int32_t *block_idx, hipStream_t stream);
 int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
                          int32_t *block_idx, void *ws, hipStream_t stream);
 size_t select_decode_ws_bytes(const Dims &dm);

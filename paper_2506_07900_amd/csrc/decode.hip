@@ -12,7 +12,7 @@
 //                          (max, sum) per head and workgroup
 //   decode_scores_kernel   256 kernels (64 blocks) per workgroup: merges the partials into the
 //                          log-sum-exp, group-mean scores, 5/4 max-pool -> block scores
-//   select_pick_kernel     (select_prefill.hip) register top-k of the block-score row
+//   decode_pick_kernel     two-level top-k of the block-score row
 // Attention: one workgroup per selected block (split-KV) writes an unnormalised partial
 // (o, max, sum); decode_merge_kernel combines the k partials per query head.
 #include "common.h"
@@ -151,6 +151,136 @@ __global__ __launch_bounds__(320) void decode_scores_kernel(Dims dm, const int32
             for (int x = 1; x < 5; ++x) v = fmaxf(v, rs[4 * tid + x]);
             R[((int64_t)b * dm.Hkv + h) * nb_cap + j] = v;
         }
+    }
+}
+
+// ---- selection, part 3: top-k of one row of block scores ----------------------------------------
+// grid (B*Hkv), 256 threads.  Candidates are the blocks n_init .. b_own - n_local; the forced ones
+// are added afterwards (section 2.1.2 "Top-K Blocks Sharing": initial and local blocks are always
+// attended).  Scores are positive floats, so their bit patterns order like unsigned integers.
+// An element is the 64-bit word  key << 32 | ~block  with key = bits of the score (1 for a block
+// without visible kernel, -inf): larger word = better element, ties go to the lower block index,
+// and no two elements are equal.  Words below 2^32 (key 0) are "not a candidate".
+//
+// No serial rounds (a dependent chain per pick is what makes a small top-k slow on this machine);
+// filters by counting instead, every comparison independent of the others.  Thread t keeps blocks
+// t, t+256, ... in registers and `best`, the largest of them.  An element of the final top-k can
+// only sit in a thread whose best is among the n_pick largest thread maxima (every better thread
+// holds an element that beats it), and it is at least tau, the n_pick-th largest thread maximum
+// (the n_pick largest thread maxima are n_pick distinct elements).
+//   1a. rank of `best` inside its wavefront; the n_pick best of each wavefront survive
+//   1b. rank of the survivors among all survivors = rank among all thread maxima; gives tau
+//   2.  the n_pick best threads publish their elements >= tau; rank by counting among those
+constexpr int kPickThreads = 256, kPickWaves = kPickThreads / 64, kPickMaxVPT = 16;
+constexpr int kPickMaxCand = kMaxTopk * kPickMaxVPT;
+constexpr uint64_t kPickValid = 1ull << 32;               // smallest word of a real candidate
+
+// number of words in w[0..n) (n a multiple of 4, 16-byte aligned) that are larger than x
+__device__ inline int count_larger(const uint64_t *w, int n, uint64_t x) {
+    int c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+    for (int j = 0; j < n; j += 4) {
+        const ulonglong2 a = *reinterpret_cast<const ulonglong2 *>(w + j);
+        const ulonglong2 bq = *reinterpret_cast<const ulonglong2 *>(w + j + 2);
+        c0 += a.x > x ? 1 : 0;
+        c1 += a.y > x ? 1 : 0;
+        c2 += bq.x > x ? 1 : 0;
+        c3 += bq.y > x ? 1 : 0;
+    }
+    return (c0 + c1) + (c2 + c3);
+}
+
+template <int kVPT>
+__global__ __launch_bounds__(kPickThreads) void decode_pick_kernel(Dims dm, const int32_t *__restrict__ seqlens,
+                                                                    const float *__restrict__ R, int32_t nb_cap,
+                                                                    int32_t *__restrict__ block_idx) {
+    __shared__ __align__(16) uint64_t tmax[kPickThreads];
+    __shared__ __align__(16) uint64_t surv[kPickWaves * kMaxTopk];
+    __shared__ __align__(16) uint64_t cand[kPickMaxCand];
+    __shared__ uint64_t tau_s;
+    __shared__ int n_cand_s;
+    __shared__ int picked[kMaxTopk];
+    const int row = blockIdx.x, b = row / dm.Hkv;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float *Rr = R + (int64_t)row * nb_cap;
+    float r[kVPT];                                        // every load issued before any use
+#pragma unroll
+    for (int s = 0; s < kVPT; ++s) r[s] = Rr[min(tid + kPickThreads * s, nb_cap - 1)];
+    const int L = clamp_len(seqlens[b], dm.max_seqlen);
+    int32_t *o = block_idx + (int64_t)row * dm.topk;
+    if (L < 1) {
+        if (tid < dm.topk) o[tid] = -1;
+        return;
+    }
+    const int b_own = (L - 1) / kBlock, n_blk = b_own + 1;
+    const int n_sel = dm.topk < n_blk ? dm.topk : n_blk;
+    const int n_init = dm.n_init < n_blk ? dm.n_init : n_blk;                 // forced leading blocks
+    const int lo_local = max(n_init, b_own - dm.n_local + 1);                 // forced trailing: lo_local..b_own
+    const int jc_max = lo_local - 1;                                          // candidates: n_init..jc_max
+    const int n_pick = n_sel - (n_init + (b_own - lo_local + 1));
+    if (n_pick > 0) {                                                         // uniform over the workgroup
+        const int n_surv = (kPickWaves * n_pick + 3) & ~3;
+        const int cand_cap = n_pick * kVPT;
+        for (int i = tid; i < n_surv; i += kPickThreads) surv[i] = 0ull;
+        for (int i = tid; i < cand_cap + 4; i += kPickThreads)
+            if (i < kPickMaxCand) cand[i] = 0ull;
+        if (tid == 0) {
+            tau_s = kPickValid;
+            n_cand_s = 0;
+        }
+        uint64_t el[kVPT], best = 0ull;
+#pragma unroll
+        for (int s = 0; s < kVPT; ++s) {
+            const int j = tid + kPickThreads * s;
+            const uint32_t kj = r[s] == -INFINITY ? 1u : __float_as_uint(r[s]);
+            const uint32_t key = (j >= n_init && j <= jc_max) ? kj : 0u;
+            el[s] = ((uint64_t)key << 32) | (uint32_t)~j;
+            best = el[s] > best ? el[s] : best;
+        }
+        const bool real = best >= kPickValid;
+        tmax[tid] = best;
+        __syncthreads();
+        // 1a. rank inside the wavefront
+        const int wrank = count_larger(tmax + 64 * wave, 64, best);
+        const bool survivor = real && wrank < n_pick;
+        if (survivor) surv[wave * n_pick + wrank] = best;
+        __syncthreads();
+        // 1b. rank among all thread maxima (a thread that did not survive has n_pick better ones)
+        int trank = n_pick;
+        if (survivor) trank = count_larger(surv, n_surv, best);
+        if (trank == n_pick - 1) tau_s = best;
+        __syncthreads();
+        // 2. publish the elements that can still make it, then rank them by counting
+        if (trank < n_pick) {
+            const uint64_t tau = tau_s;
+#pragma unroll
+            for (int s = 0; s < kVPT; ++s)
+                if (el[s] >= tau) cand[atomicAdd(&n_cand_s, 1)] = el[s];
+        }
+        __syncthreads();
+        const int n_cand = n_cand_s;                                          // n_pick <= n_cand <= cand_cap
+        for (int i = tid; i < n_cand; i += kPickThreads) {
+            const uint64_t e = cand[i];
+            const int beaten = count_larger(cand, (n_cand + 3) & ~3, e);
+            if (beaten < n_pick) picked[beaten] = (int)~(uint32_t)e;
+        }
+        __syncthreads();
+    }
+    if (wave == 0) {
+        int mine = 0x7fffffff;
+        if (lane < n_pick) mine = picked[lane];
+        else if (lane < n_sel) {
+            const int f = lane - n_pick;
+            mine = f < n_init ? f : lo_local + (f - n_init);
+        }
+        // ascending order: rank = number of selected blocks below mine
+        int rank = 0;
+#pragma unroll
+        for (int e = 0; e < kMaxTopk; ++e) {
+            if (e >= n_sel) break;                                            // uniform
+            rank += __builtin_amdgcn_readlane(mine, e) < mine ? 1 : 0;
+        }
+        if (lane < n_sel) o[rank] = mine;
+        else if (lane < dm.topk) o[lane] = -1;
     }
 }
 
@@ -353,7 +483,20 @@ int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seq
     hipLaunchKernelGGL(decode_scores_kernel, dim3(l.n_c_cap / 256, dm.Hkv, dm.batch), dim3(320), 0, stream,
                        dm, seqlens, zbuf, part, l.n_c_cap, l.n_part, R, l.nb_cap);
     timing_end(stream);
-    return launch_select_pick_decode(dm, seqlens, R, l.nb_cap, block_idx, stream);
+    const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
+    if (n_blocks > kPickThreads * kPickMaxVPT) return (int)hipErrorInvalidValue;   // rejected earlier by the C ABI
+    const dim3 grid(dm.batch * dm.Hkv), block(kPickThreads);
+    timing_begin("decode_pick_kernel", stream);
+    if (n_blocks <= kPickThreads * 4)
+        hipLaunchKernelGGL(decode_pick_kernel<4>, grid, block, 0, stream, dm, seqlens, R, l.nb_cap, block_idx);
+    else if (n_blocks <= kPickThreads * 8)
+        hipLaunchKernelGGL(decode_pick_kernel<8>, grid, block, 0, stream, dm, seqlens, R, l.nb_cap, block_idx);
+    else if (n_blocks <= kPickThreads * 12)
+        hipLaunchKernelGGL(decode_pick_kernel<12>, grid, block, 0, stream, dm, seqlens, R, l.nb_cap, block_idx);
+    else
+        hipLaunchKernelGGL(decode_pick_kernel<16>, grid, block, 0, stream, dm, seqlens, R, l.nb_cap, block_idx);
+    timing_end(stream);
+    return (int)hipGetLastError();
 }
 
 size_t attn_decode_ws_bytes(const Dims &dm) {

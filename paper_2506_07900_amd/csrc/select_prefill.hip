@@ -260,24 +260,20 @@ __global__ __launch_bounds__(256) void select_score_kernel(Dims dm, Tensor q, Te
 // Lane l keeps blocks l, l+64, ... in registers and its best (key, slot); each of the n_pick
 // rounds takes the wave-wide best (ties: lowest block index) and retires it.
 // Slots are kept in groups of 8 with a cached best per group, so retiring a pick recomputes one
-// group only.  kDecode: one row per (sequence, key-value head), the query sits at seqlens[b]-1.
-template <int VPL, bool kDecode>
+// group only.
+template <int VPL>
 __global__ __launch_bounds__(256) void select_pick_kernel(Dims dm, const int32_t *__restrict__ seqlens,
                                                            const float *__restrict__ R, int32_t nb_cap,
                                                            int32_t *__restrict__ block_idx) {
     constexpr int GS = VPL < 8 ? VPL : 8, NG = VPL / GS;
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int64_t rows = (int64_t)dm.batch * dm.Hkv * (kDecode ? 1 : dm.max_seqlen);
+    const int64_t rows = (int64_t)dm.batch * dm.Hkv * dm.max_seqlen;
     if (row >= rows) return;
-    const int b = kDecode ? row / dm.Hkv : row / ((int64_t)dm.max_seqlen * dm.Hkv);
+    const int b = row / ((int64_t)dm.max_seqlen * dm.Hkv);
     int32_t L = seqlens[b];
     L = L < 0 ? 0 : (L > dm.max_seqlen ? dm.max_seqlen : L);
-    const int tok = kDecode ? L - 1 : row % dm.max_seqlen;
-    if (kDecode && L < 1) {
-        if (lane < dm.topk) block_idx[row * dm.topk + lane] = -1;
-        return;
-    }
+    const int tok = row % dm.max_seqlen;
     if (tok >= L) return;
     const int b_own = tok / kBlock, n_blk = b_own + 1;
     const int n_sel = dm.topk < n_blk ? dm.topk : n_blk;
@@ -288,15 +284,15 @@ __global__ __launch_bounds__(256) void select_pick_kernel(Dims dm, const int32_t
     int mine = 0x7fffffff;                                                    // lane c keeps pick c
     if (n_pick > 0) {
         const float *Rr = R + row * nb_cap;
+        float r[VPL];                                                         // every load issued before any use
+#pragma unroll
+        for (int s = 0; s < VPL; ++s) r[s] = Rr[min(lane + 64 * s, nb_cap - 1)];
         uint32_t key[VPL];
 #pragma unroll
         for (int s = 0; s < VPL; ++s) {
             const int j = lane + 64 * s;
-            key[s] = 0u;
-            if (j >= n_init && j <= jc_max) {
-                const float r = Rr[j];
-                key[s] = r == -INFINITY ? 1u : __float_as_uint(r);
-            }
+            const uint32_t kj = r[s] == -INFINITY ? 1u : __float_as_uint(r[s]);
+            key[s] = (j >= n_init && j <= jc_max) ? kj : 0u;
         }
         uint32_t gkey[NG];
         int gslot[NG];
@@ -432,13 +428,13 @@ int launch_select_pick(const Dims &dm, const int32_t *seqlens, const float *R, i
     const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
     timing_begin("select_pick_kernel", stream);
     if (n_blocks <= 64 * 4)
-        hipLaunchKernelGGL((select_pick_kernel<4, false>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+        hipLaunchKernelGGL((select_pick_kernel<4>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
     else if (n_blocks <= 64 * 8)
-        hipLaunchKernelGGL((select_pick_kernel<8, false>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+        hipLaunchKernelGGL((select_pick_kernel<8>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
     else if (n_blocks <= 64 * 16)
-        hipLaunchKernelGGL((select_pick_kernel<16, false>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+        hipLaunchKernelGGL((select_pick_kernel<16>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
     else if (n_blocks <= 64 * 32)
-        hipLaunchKernelGGL((select_pick_kernel<32, false>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+        hipLaunchKernelGGL((select_pick_kernel<32>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
     else
         hipLaunchKernelGGL(select_pick_scan_kernel, grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
     timing_end(stream);
@@ -473,25 +469,6 @@ static int launch_select_prefill_g(const Dims &dm, Tensor q, Tensor ck, const in
                        seqlens, lse2, R, nb_cap, n_tiles);
     timing_end(stream);
     return launch_select_pick(dm, seqlens, R, nb_cap, block_idx, stream);
-}
-
-// Decode: one row per (sequence, key-value head); contexts up to 64*64 blocks.
-int launch_select_pick_decode(const Dims &dm, const int32_t *seqlens, const float *R, int32_t nb_cap,
-                              int32_t *block_idx, hipStream_t stream) {
-    const int64_t rows = (int64_t)dm.batch * dm.Hkv;
-    if (rows <= 0) return 0;
-    const dim3 grid((uint32_t)((rows + 3) / 4));
-    const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
-    if (n_blocks > 64 * 64) return (int)hipErrorInvalidValue;         // rejected earlier by the C ABI
-    timing_begin("select_pick_kernel", stream);
-    if (n_blocks <= 64 * 8)
-        hipLaunchKernelGGL((select_pick_kernel<8, true>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
-    else if (n_blocks <= 64 * 32)
-        hipLaunchKernelGGL((select_pick_kernel<32, true>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
-    else
-        hipLaunchKernelGGL((select_pick_kernel<64, true>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
-    timing_end(stream);
-    return (int)hipGetLastError();
 }
 
 int launch_select_prefill(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,

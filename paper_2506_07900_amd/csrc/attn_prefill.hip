@@ -21,7 +21,6 @@
 // from the accumulator layout of S^T (lane = head column, 4 consecutive keys per 16-lane group),
 // with the key order inside the packed V^T rows permuted to match.
 #include "common.h"
-#include <cstdlib>
 
 namespace infllmv2 {
 
@@ -384,14 +383,10 @@ int launch_attn_prefill(const Dims &dm, Tensor q, Tensor k, Tensor v, const int3
     hipLaunchKernelGGL(pack_kv_kernel, dim3(nb_cap, dm.Hkv, dm.batch), dim3(256), 0, stream, dm, k, v,
                        seqlens, kvp, nb_cap);
     timing_end(stream);
-    static const int variant = [] {
-        const char *e = getenv("INFLLMV2_ATTN_VARIANT");
-        return e ? atoi(e) : 0;
-    }();
+    // 2 tokens per wavefront, ring of 4 units, 2 wavefronts per SIMD: the configuration that keeps
+    // the most loads in flight per compute unit within 256 registers per lane
     timing_begin("attn_prefill_kernel", stream);
-    if (variant == 1) launch_attn_variant<4, 8, 1>(dm, q, kvp, nb_cap, seqlens, block_idx, out, lse, stream);
-    else if (variant == 2) launch_attn_variant<2, 8, 1>(dm, q, kvp, nb_cap, seqlens, block_idx, out, lse, stream);
-    else launch_attn_variant<2, 4, 2>(dm, q, kvp, nb_cap, seqlens, block_idx, out, lse, stream);
+    launch_attn_variant<2, 4, 2>(dm, q, kvp, nb_cap, seqlens, block_idx, out, lse, stream);
     timing_end(stream);
     return (int)hipGetLastError();
 }

@@ -274,11 +274,7 @@ __global__ __launch_bounds__(kPickThreads) void decode_pick_kernel(Dims dm, cons
         }
         // ascending order: rank = number of selected blocks below mine
         int rank = 0;
-#pragma unroll
-        for (int e = 0; e < kMaxTopk; ++e) {
-            if (e >= n_sel) break;                                            // uniform
-            rank += __builtin_amdgcn_readlane(mine, e) < mine ? 1 : 0;
-        }
+        for (int e = 0; e < n_sel; ++e) rank += __builtin_amdgcn_readlane(mine, e) < mine ? 1 : 0;
         if (lane < n_sel) o[rank] = mine;
         else if (lane < dm.topk) o[lane] = -1;
     }

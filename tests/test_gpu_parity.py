@@ -81,6 +81,7 @@ PREFILL_CASES = [
     ([300, 64, 63, 1], 4, 2, 4, 0),  # G = 2, tiny sequences
     ([450], 2, 2, 5, 2),             # G = 1
     ([1500], 16, 1, 32, 5),          # everything selected up to 2048 tokens: dense degrade
+    ([5200], 32, 2, 48, 6),          # wide top-k: two neighbouring tokens list more than 64 distinct blocks
 ]
 
 
@@ -150,6 +151,49 @@ def test_sparse_attn_prefill(seqlens, Hq, Hkv, topk, planted):
         assert np.all(o[b, l:] == 3.0) and np.all(ls[b, l:] == 5.0)     # padding rows untouched
 
 
+def test_exact_ties_go_to_the_lower_block_index():
+    # zero queries: every visible kernel gets the same probability, so every block score of a
+    # row is the same number on both sides; the selection is decided by the tie rule alone
+    print("case ties", flush=True)
+    seqlens, Hq, Hkv, topk = [1300, 700], 32, 2, 8
+    prm = binding.Params(Hq, Hkv, topk=topk)
+    oprm = oracle_params(prm)
+    q, k, v, T = make_batch(41, seqlens, Hq, Hkv)
+    q[:] = 0
+    qd, kd, sl = to_dev(q), to_dev(k), dev_i32(seqlens)
+    ck = binding.compress_keys(prm, kd, sl, T)
+    idx = binding.select_blocks(prm, binding.MODE_PREFILL, qd, ck, sl, T).cpu().numpy()
+    last = [l - 1 for l in seqlens]
+    q1 = np.stack([q[b, last[b]] for b in range(len(seqlens))])[:, None]
+    idx_dec = binding.select_blocks(prm, binding.MODE_DECODE, to_dev(q1), ck, sl, T).cpu().numpy()
+    ckb = to_bits(ck)
+    for b, l in enumerate(seqlens):
+        n_c = ref.num_kernels(l, 32, 16)
+        want, _ = ref.select_blocks(q[b, :l], ckb[b, :, :n_c], np.arange(l, dtype=np.int32), oprm)
+        assert np.array_equal(idx[b, :, :l], want)
+        assert np.array_equal(idx_dec[b, :, 0], want[:, l - 1])
+        # the rule itself: the scored picks are the lowest-numbered candidates with a visible kernel
+        row = want[0, l - 1]
+        assert row.tolist() == sorted(set(row.tolist())) and row[1] == 1 and row[topk - 4] == topk - 4
+
+
+def test_sparse_attn_prefill_accepts_unsorted_block_lists():
+    # the block list of a token is a set: any order, padding anywhere
+    print("case unsorted lists", flush=True)
+    l, Hq, Hkv, topk = 1100, 32, 2, 16
+    prm, (q, k, v, T), (qd, kd, vd, sl), ck, idx = run_prefill([l], Hq, Hkv, topk, 4)
+    out0, lse0 = binding.sparse_attn_prefill(prm, qd, kd, vd, sl, T, idx)
+    rng = np.random.default_rng(5)
+    shuffled = idx.cpu().numpy().copy()
+    for h in range(Hkv):
+        for t in range(l):
+            rng.shuffle(shuffled[0, h, t])
+    out1, lse1 = binding.sparse_attn_prefill(prm, qd, kd, vd, sl, T, torch.from_numpy(shuffled).cuda())
+    torch.cuda.synchronize()
+    # same set, same ascending processing order inside the kernel: identical results
+    assert torch.equal(out0.view(torch.int16), out1.view(torch.int16)) and torch.equal(lse0, lse1)
+
+
 def test_prefill_end_to_end_dense_degrade():
     # top-k covering every block: the whole path equals dense causal attention
     print("case dense degrade", flush=True)
@@ -168,7 +212,8 @@ def test_prefill_end_to_end_dense_degrade():
 # ------------------------------------------------------------------ decode
 
 @pytest.mark.parametrize("seqlens,Hq,Hkv,topk", [([3000, 1077, 64, 33, 31, 1], 32, 2, 16),
-                                                 ([2048, 129], 4, 1, 8), ([777], 16, 2, 6)])
+                                                 ([2048, 129], 4, 1, 8), ([777], 16, 2, 6),
+                                                 ([9000, 4500, 200], 32, 2, 64)])
 def test_decode_select_and_attn(seqlens, Hq, Hkv, topk):
     print("case decode", seqlens, Hq, Hkv, topk, flush=True)
     prm = binding.Params(Hq, Hkv, topk=topk)

@@ -71,6 +71,24 @@ __device__ inline float xgroup_sum(float v) {
     return v;
 }
 
+// Top-k by counting (used by the pick kernels).  An element is the 64-bit word
+// key << 32 | ~block: larger word = better element, ties go to the lower block index.
+constexpr uint64_t kPickValid = 1ull << 32;               // smallest word of a real candidate
+
+// number of words in w[0..n) (n a multiple of 4, 16-byte aligned) that are larger than x
+__device__ inline int count_larger(const uint64_t *w, int n, uint64_t x) {
+    int c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+    for (int j = 0; j < n; j += 4) {
+        const ulonglong2 a = *reinterpret_cast<const ulonglong2 *>(w + j);
+        const ulonglong2 bq = *reinterpret_cast<const ulonglong2 *>(w + j + 2);
+        c0 += a.x > x ? 1 : 0;
+        c1 += a.y > x ? 1 : 0;
+        c2 += bq.x > x ? 1 : 0;
+        c3 += bq.y > x ? 1 : 0;
+    }
+    return (c0 + c1) + (c2 + c3);
+}
+
 // Optional per-kernel timing (infllmv2_timing_enable): when on, every launch is bracketed by HIP
 // events on the launch stream.  No-ops when off.
 void timing_begin(const char *kernel_name, hipStream_t stream);

@@ -173,22 +173,6 @@ __global__ __launch_bounds__(320) void decode_scores_kernel(Dims dm, const int32
 //   2.  the n_pick best threads publish their elements >= tau; rank by counting among those
 constexpr int kPickThreads = 256, kPickWaves = kPickThreads / 64, kPickMaxVPT = 16;
 constexpr int kPickMaxCand = kMaxTopk * kPickMaxVPT;
-constexpr uint64_t kPickValid = 1ull << 32;               // smallest word of a real candidate
-
-// number of words in w[0..n) (n a multiple of 4, 16-byte aligned) that are larger than x
-__device__ inline int count_larger(const uint64_t *w, int n, uint64_t x) {
-    int c0 = 0, c1 = 0, c2 = 0, c3 = 0;
-    for (int j = 0; j < n; j += 4) {
-        const ulonglong2 a = *reinterpret_cast<const ulonglong2 *>(w + j);
-        const ulonglong2 bq = *reinterpret_cast<const ulonglong2 *>(w + j + 2);
-        c0 += a.x > x ? 1 : 0;
-        c1 += a.y > x ? 1 : 0;
-        c2 += bq.x > x ? 1 : 0;
-        c3 += bq.y > x ? 1 : 0;
-    }
-    return (c0 + c1) + (c2 + c3);
-}
-
 template <int kVPT>
 __global__ __launch_bounds__(kPickThreads) void decode_pick_kernel(Dims dm, const int32_t *__restrict__ seqlens,
                                                                     const float *__restrict__ R, int32_t nb_cap,

@@ -255,22 +255,37 @@ __global__ __launch_bounds__(256) void select_score_kernel(Dims dm, Tensor q, Te
 
 // ---- top-k: one wavefront per (sequence, key-value head, token) row of block scores ------------
 // Candidates are the blocks n_init .. b_own - n_local; the forced ones are added afterwards.
-// Scores are positive floats, so their bit patterns order like unsigned integers: key = bits of
-// the score, 1 for a block without visible kernel (-inf), 0 for "not a candidate / taken".
-// Lane l keeps blocks l, l+64, ... in registers and its best (key, slot); each of the n_pick
-// rounds takes the wave-wide best (ties: lowest block index) and retires it.
-// Slots are kept in groups of 8 with a cached best per group, so retiring a pick recomputes one
-// group only.
+// Scores are positive floats, so their bit patterns order like unsigned integers.  An element is
+// the 64-bit word  key << 32 | ~block  with key = bits of the score (1 for a block without visible
+// kernel, -inf): larger word = better element, ties go to the lower block index, no two elements
+// are equal; words below 2^32 are "not a candidate".
+//
+// No serial rounds: lane l keeps blocks l, l+64, ... in registers and `best`, the largest of
+// them.  An element of the final top-k can only sit in a lane whose best is among the n_pick
+// largest lane maxima, and it is at least tau, the n_pick-th largest lane maximum.  So: rank the
+// 64 lane maxima by counting, let the n_pick best lanes publish their elements >= tau (a
+// handful), and rank those by counting.  All through the wavefront's own piece of LDS.
+constexpr int kPickRowsPerWg = 4;
+__host__ __device__ inline int pick_cand_cap(int topk, int vpl) { return (topk * vpl + 3) & ~3; }
+
 template <int VPL>
 __global__ __launch_bounds__(256) void select_pick_kernel(Dims dm, const int32_t *__restrict__ seqlens,
                                                            const float *__restrict__ R, int32_t nb_cap,
                                                            int32_t *__restrict__ block_idx) {
-    constexpr int GS = VPL < 8 ? VPL : 8, NG = VPL / GS;
-    const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    extern __shared__ __align__(16) unsigned char pick_smem[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cand_cap = pick_cand_cap(dm.topk, VPL);
+    uint64_t *tmax = reinterpret_cast<uint64_t *>(pick_smem) + (size_t)wave * (64 + cand_cap);
+    uint64_t *cand = tmax + 64;
+    int *picked = reinterpret_cast<int *>(tmax);                              // reused once the ranks are known
+    const int64_t row = (int64_t)blockIdx.x * kPickRowsPerWg + wave;
     const int64_t rows = (int64_t)dm.batch * dm.Hkv * dm.max_seqlen;
     if (row >= rows) return;
     const int b = row / ((int64_t)dm.max_seqlen * dm.Hkv);
+    const float *Rr = R + row * nb_cap;
+    float r[VPL];                                                             // every load issued before any use
+#pragma unroll
+    for (int s = 0; s < VPL; ++s) r[s] = Rr[min(lane + 64 * s, nb_cap - 1)];
     int32_t L = seqlens[b];
     L = L < 0 ? 0 : (L > dm.max_seqlen ? dm.max_seqlen : L);
     const int tok = row % dm.max_seqlen;
@@ -282,74 +297,48 @@ __global__ __launch_bounds__(256) void select_pick_kernel(Dims dm, const int32_t
     const int jc_max = lo_local - 1;                                          // candidates: n_init..jc_max
     const int n_pick = n_sel - (n_init + (b_own - lo_local + 1));
     int mine = 0x7fffffff;                                                    // lane c keeps pick c
-    if (n_pick > 0) {
-        const float *Rr = R + row * nb_cap;
-        float r[VPL];                                                         // every load issued before any use
-#pragma unroll
-        for (int s = 0; s < VPL; ++s) r[s] = Rr[min(lane + 64 * s, nb_cap - 1)];
-        uint32_t key[VPL];
+    if (n_pick > 0) {                                                         // uniform over the wavefront
+        uint64_t el[VPL], best = 0ull;
 #pragma unroll
         for (int s = 0; s < VPL; ++s) {
             const int j = lane + 64 * s;
             const uint32_t kj = r[s] == -INFINITY ? 1u : __float_as_uint(r[s]);
-            key[s] = (j >= n_init && j <= jc_max) ? kj : 0u;
+            const uint32_t key = (j >= n_init && j <= jc_max) ? kj : 0u;
+            el[s] = ((uint64_t)key << 32) | (uint32_t)~j;
+            best = el[s] > best ? el[s] : best;
         }
-        uint32_t gkey[NG];
-        int gslot[NG];
-        auto regroup = [&](int gi) {                                          // gi is a compile-time index
-            gkey[gi] = 0u;
-            gslot[gi] = gi * GS;
-#pragma unroll
-            for (int s = gi * GS + GS - 1; s >= gi * GS; --s)
-                if (key[s] >= gkey[gi]) {
-                    gkey[gi] = key[s];
-                    gslot[gi] = s;
-                }
-        };
-#pragma unroll
-        for (int gi = 0; gi < NG; ++gi) regroup(gi);
-        for (int c = 0; c < n_pick; ++c) {
-            uint32_t lb_key = 0u;
-            int lb_slot = 0;
-#pragma unroll
-            for (int gi = NG - 1; gi >= 0; --gi)
-                if (gkey[gi] >= lb_key) {
-                    lb_key = gkey[gi];
-                    lb_slot = gslot[gi];
-                }
-            // wave-wide maximum key: row maxima by DPP shifts, then the four rows through scalars
-            uint32_t m = lb_key;
-            m = max(m, (uint32_t)__builtin_amdgcn_update_dpp((int)m, (int)m, 0x111, 0xf, 0xf, false));
-            m = max(m, (uint32_t)__builtin_amdgcn_update_dpp((int)m, (int)m, 0x112, 0xf, 0xf, false));
-            m = max(m, (uint32_t)__builtin_amdgcn_update_dpp((int)m, (int)m, 0x114, 0xf, 0xf, false));
-            m = max(m, (uint32_t)__builtin_amdgcn_update_dpp((int)m, (int)m, 0x118, 0xf, 0xf, false));
-            const uint32_t k0 = __builtin_amdgcn_readlane(m, 15), k1 = __builtin_amdgcn_readlane(m, 31);
-            const uint32_t k2 = __builtin_amdgcn_readlane(m, 47), k3 = __builtin_amdgcn_readlane(m, 63);
-            const uint32_t kmax = max(max(k0, k1), max(k2, k3));
-            uint64_t who = __ballot(lb_key == kmax);
-            int wl = __builtin_ctzll(who);
-            int wslot = __builtin_amdgcn_readlane(lb_slot, wl);
-            who &= who - 1;
-            while (who) {                                                     // exact ties: lowest block index
-                const int l2 = __builtin_ctzll(who);
-                who &= who - 1;
-                const int s2 = __builtin_amdgcn_readlane(lb_slot, l2);
-                if (l2 + 64 * s2 < wl + 64 * wslot) {
-                    wl = l2;
-                    wslot = s2;
-                }
-            }
-            if (lane == c) mine = wl + 64 * wslot;
-            const bool me = lane == wl;
-#pragma unroll
-            for (int gi = 0; gi < NG; ++gi) {
-                if (wslot / GS != gi) continue;                               // uniform: one group is touched
-#pragma unroll
-                for (int s = gi * GS; s < gi * GS + GS; ++s)
-                    if (me && s == wslot) key[s] = 0u;
-                regroup(gi);
-            }
+        tmax[lane] = best;
+        __builtin_amdgcn_wave_barrier();
+        const bool real = best >= kPickValid;
+        const int lrank = count_larger(tmax, 64, best);
+        const bool finalist = real && lrank < n_pick;
+        // tau = the n_pick-th largest lane maximum, if there are that many real ones
+        uint64_t tau = kPickValid;
+        const uint64_t who = __ballot(real && lrank == n_pick - 1);
+        if (who) {
+            const int src = __builtin_ctzll(who);
+            tau = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(best >> 32), src) << 32) |
+                  (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)best, src);
         }
+        int n_cand = 0;
+        const uint64_t below = (1ull << lane) - 1ull;
+#pragma unroll
+        for (int s = 0; s < VPL; ++s) {
+            const bool pub = finalist && el[s] >= tau;
+            const uint64_t m = __ballot(pub);
+            if (pub) cand[n_cand + __popcll(m & below)] = el[s];
+            n_cand += __popcll(m);
+        }
+        const int n_cand4 = (n_cand + 3) & ~3;                                // <= cand_cap
+        if (lane < n_cand4 - n_cand) cand[n_cand + lane] = 0ull;
+        __builtin_amdgcn_wave_barrier();
+        for (int i = lane; i < n_cand; i += 64) {
+            const uint64_t e = cand[i];
+            const int beaten = count_larger(cand, n_cand4, e);
+            if (beaten < n_pick) picked[beaten] = (int)~(uint32_t)e;
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (lane < n_pick) mine = picked[lane];
     }
     if (lane >= n_pick && lane < n_sel) {
         const int f = lane - n_pick;
@@ -426,17 +415,19 @@ int launch_select_pick(const Dims &dm, const int32_t *seqlens, const float *R, i
     if (rows <= 0) return 0;
     const dim3 grid((uint32_t)((rows + 3) / 4));
     const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
+    const int vpl = n_blocks <= 64 * 4 ? 4 : n_blocks <= 64 * 8 ? 8 : n_blocks <= 64 * 16 ? 16 : 32;
+    const size_t lds = (size_t)kPickRowsPerWg * (64 + pick_cand_cap(dm.topk, vpl)) * sizeof(uint64_t);
     timing_begin("select_pick_kernel", stream);
-    if (n_blocks <= 64 * 4)
-        hipLaunchKernelGGL((select_pick_kernel<4>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
-    else if (n_blocks <= 64 * 8)
-        hipLaunchKernelGGL((select_pick_kernel<8>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
-    else if (n_blocks <= 64 * 16)
-        hipLaunchKernelGGL((select_pick_kernel<16>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
-    else if (n_blocks <= 64 * 32)
-        hipLaunchKernelGGL((select_pick_kernel<32>), grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
-    else
+    if (n_blocks > 64 * 32 || lds > 64 * 1024)           // very long rows or very wide top-k: generic scan
         hipLaunchKernelGGL(select_pick_scan_kernel, grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+    else if (vpl == 4)
+        hipLaunchKernelGGL((select_pick_kernel<4>), grid, dim3(256), lds, stream, dm, seqlens, R, nb_cap, block_idx);
+    else if (vpl == 8)
+        hipLaunchKernelGGL((select_pick_kernel<8>), grid, dim3(256), lds, stream, dm, seqlens, R, nb_cap, block_idx);
+    else if (vpl == 16)
+        hipLaunchKernelGGL((select_pick_kernel<16>), grid, dim3(256), lds, stream, dm, seqlens, R, nb_cap, block_idx);
+    else
+        hipLaunchKernelGGL((select_pick_kernel<32>), grid, dim3(256), lds, stream, dm, seqlens, R, nb_cap, block_idx);
     timing_end(stream);
     return (int)hipGetLastError();
 }

@@ -265,18 +265,20 @@ __global__ __launch_bounds__(kPickThreads) void decode_pick_kernel(Dims dm, cons
 }
 
 // ---- attention, part 1: one workgroup per selected block --------------------------------------
-// grid (topk, Hkv, B), 256 threads.  Wave w: keys 16w..16w+15 of the block, S^T = K . Q^T on MFMA.
-// Then thread = (8-channel chunk c, key quarter kq, head quad hq): it issues its 16 value loads at
-// once, accumulates p*v for 4 heads over 16 keys in fp32, and the four key quarters are summed
-// through LDS.
+// grid (topk, Hkv, B), 256 threads.  Every load of the block (64 key rows as MFMA operands, 64
+// value rows for LDS, the query) is issued before anything is used.  Wave w: S^T = K . Q^T for
+// keys 16w..16w+15; the probabilities go to LDS as P[key][head]; then wave w owns value channels
+// 32w..32w+31 and computes O^T = V^T . P^T on the matrix cores, gathering the V^T fragments
+// (8 keys of one channel per lane) from the row-major value tile in LDS.
+constexpr int kVsPitch = kHeadDim + 4;               // bf16 elements per LDS value row: conflict-free column reads
 __global__ __launch_bounds__(256) void decode_attn_partial_kernel(Dims dm, Tensor q, Tensor k, Tensor v,
                                                                    const int32_t *__restrict__ seqlens,
                                                                    const int32_t *__restrict__ block_idx,
                                                                    float *__restrict__ o_part,
                                                                    float2 *__restrict__ ml_part) {
-    __shared__ float S[kBlock][17];
-    __shared__ float mrow[16];
-    __shared__ float red[3][16][kHeadDim + 4];       // partial outputs of key quarters 1..3
+    __shared__ __align__(16) uint16_t Vs[kBlock * kVsPitch];
+    __shared__ float Ps[kBlock][17];
+    __shared__ float wmax[4][16], wsum[4][16];
     const int cidx = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, g = lane >> 4;
@@ -297,93 +299,88 @@ __global__ __launch_bounds__(256) void decode_attn_partial_kernel(Dims dm, Tenso
         return;
     }
     const int key0 = blk * kBlock;
-    const int pos = L - 1;
-    // value rows of this thread: keys 16*kq .. 16*kq+15, channels 8c .. 8c+7 (issued before the scores)
-    const int c8 = tid & 15, kq = (tid >> 4) & 3, hq = tid >> 6;
-    bf16x8 vv[16];
+    const int pos = L - 1;                               // key0 <= pos
+    const int last_row = dm.max_seqlen - 1;              // rows past pos are read (in bounds) and masked
+    // ---- all loads --------------------------------------------------------------------------------
+    const int c8 = tid & 15, vr = tid >> 4;
+    uint4 vrow[4];
     {
-        const __bf16 *vr = v.ptr + b * v.sb + h * v.sh + (int64_t)(key0 + 16 * kq) * v.st + 8 * c8;
+        const __bf16 *vb = v.ptr + b * v.sb + h * v.sh + 8 * c8;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            vv[i] = zero8();
-            if (key0 + 16 * kq + i <= pos) vv[i] = load8(vr + (int64_t)i * v.st);
-        }
+        for (int i = 0; i < 4; ++i)
+            vrow[i] = *reinterpret_cast<const uint4 *>(vb + (int64_t)min(key0 + vr + 16 * i, last_row) * v.st);
     }
+    bf16x8 a[4], bq[4];
     {
-        f32x4 s = {0.f, 0.f, 0.f, 0.f};
-        const int key = key0 + 16 * wave + n;
+        const int key = min(key0 + 16 * wave + n, last_row);
         const __bf16 *kr = k.ptr + b * k.sb + h * k.sh + (int64_t)key * k.st + 8 * g;
-        const __bf16 *qr = q.ptr + b * q.sb + (int64_t)(h * G + n) * q.sh + 8 * g;
-        bf16x8 a[4], bq[4];
+        const __bf16 *qr = q.ptr + b * q.sb + (int64_t)(h * G + min(n, G - 1)) * q.sh + 8 * g;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            a[ks] = zero8();
-            bq[ks] = zero8();
-            if (key <= pos) a[ks] = load8(kr + 32 * ks);
-            if (n < G) bq[ks] = load8(qr + 32 * ks);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) s = mfma16(a[ks], bq[ks], s);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int kk = 16 * wave + 4 * g + j;
-            S[kk][n] = (key0 + kk <= pos) ? s[j] * dm.scale_log2 : -INFINITY;
+            a[ks] = load8(kr + 32 * ks);
+            bq[ks] = load8(qr + 32 * ks);
         }
     }
+    // ---- value tile to LDS (rows past the query position as zeros: 0 * garbage must stay 0) -------
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = vr + 16 * i;
+        uint4 x = vrow[i];
+        if (key0 + r > pos) x = uint4{0u, 0u, 0u, 0u};
+        *reinterpret_cast<uint2 *>(&Vs[r * kVsPitch + 8 * c8]) = uint2{x.x, x.y};
+        *reinterpret_cast<uint2 *>(&Vs[r * kVsPitch + 8 * c8 + 4]) = uint2{x.z, x.w};
+    }
+    // ---- scores of this wave's 16 keys ---------------------------------------------------------------
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) s = mfma16(a[ks], bq[ks], s);
+    float x[4], mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        x[j] = (key0 + 16 * wave + 4 * g + j <= pos) ? s[j] * dm.scale_log2 : -INFINITY;
+        mx = fmaxf(mx, x[j]);
+    }
+    mx = xgroup_max(mx);
+    if (g == 0) wmax[wave][n] = mx;
     __syncthreads();
-    if (tid < 16) {
-        float m = -INFINITY;
-#pragma unroll 8
-        for (int kk = 0; kk < kBlock; ++kk) m = fmaxf(m, S[kk][tid]);   // key0 <= pos: finite
-        mrow[tid] = m;
+    const float m = fmaxf(fmaxf(wmax[0][n], wmax[1][n]), fmaxf(wmax[2][n], wmax[3][n]));   // finite: key0 <= pos
+    float ps = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float p = fast_exp2(x[j] - m);
+        ps += p;
+        Ps[16 * wave + 4 * g + j][n] = p;
     }
+    ps = xgroup_sum(ps);
+    if (g == 0) wsum[wave][n] = ps;
     __syncthreads();
-    float acc[4][8];
-    float lsum[4];
+    // ---- O^T[channel, head] for channels 32*wave .. 32*wave+31 ---------------------------------------
+    f32x4 o[2];
+    o[0] = o[1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int hh = 0; hh < 4; ++hh) {
-        lsum[hh] = 0.f;
+    for (int kk = 0; kk < 2; ++kk) {
+        bf16x8 pb;                                       // B: head n, keys 32kk + 8g .. +7
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[hh][e] = 0.f;
-    }
+        for (int e = 0; e < 8; ++e) pb[e] = (__bf16)Ps[32 * kk + 8 * g + e][n];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+        for (int ct = 0; ct < 2; ++ct) {
+            const uint16_t *vc = &Vs[(32 * kk + 8 * g) * kVsPitch + 32 * wave + 16 * ct + n];   // A: channel row n
+            uint32_t w[4];
 #pragma unroll
-        for (int hh = 0; hh < 4; ++hh) {
-            const float p = fast_exp2(S[16 * kq + i][4 * hq + hh] - mrow[4 * hq + hh]);
-            lsum[hh] += p;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[hh][e] += p * (float)vv[i][e];
+            for (int e2 = 0; e2 < 4; ++e2)
+                w[e2] = (uint32_t)vc[(2 * e2) * kVsPitch] | ((uint32_t)vc[(2 * e2 + 1) * kVsPitch] << 16);
+            const uint4 av = {w[0], w[1], w[2], w[3]};
+            o[ct] = mfma16(__builtin_bit_cast(bf16x8, av), pb, o[ct]);
         }
     }
-    // sum the four key quarters: quarters 1..3 park their partials in LDS, quarter 0 adds and writes
-    if (kq > 0) {
+    if (n < G) {                                         // lane: head n, channels 32w + 16ct + 4g .. +3
+        const int64_t pbase = (((int64_t)b * dm.Hq + h * G + n) * dm.topk + cidx);
 #pragma unroll
-        for (int hh = 0; hh < 4; ++hh) {
-            float *r = &red[kq - 1][4 * hq + hh][8 * c8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) r[e] = acc[hh][e];
-            if (c8 == 0) red[kq - 1][4 * hq + hh][kHeadDim] = lsum[hh];
-        }
-    }
-    __syncthreads();
-    if (kq == 0) {
-#pragma unroll
-        for (int hh = 0; hh < 4; ++hh) {
-            const int head = 4 * hq + hh;
-            if (head >= G) continue;
-#pragma unroll
-            for (int qq = 0; qq < 3; ++qq) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[hh][e] += red[qq][head][8 * c8 + e];
-                lsum[hh] += red[qq][head][kHeadDim];
-            }
-            const int64_t pbase = (((int64_t)b * dm.Hq + h * G + head) * dm.topk + cidx);
-            if (c8 == 0) ml_part[pbase] = float2{mrow[head], lsum[hh]};
-            float4 *op = reinterpret_cast<float4 *>(o_part + pbase * kHeadDim + 8 * c8);
-            op[0] = float4{acc[hh][0], acc[hh][1], acc[hh][2], acc[hh][3]};
-            op[1] = float4{acc[hh][4], acc[hh][5], acc[hh][6], acc[hh][7]};
-        }
+        for (int ct = 0; ct < 2; ++ct)
+            *reinterpret_cast<float4 *>(o_part + pbase * kHeadDim + 32 * wave + 16 * ct + 4 * g) =
+                float4{o[ct][0], o[ct][1], o[ct][2], o[ct][3]};
+        if (wave == 0 && g == 0)
+            ml_part[pbase] = float2{m, (wsum[0][n] + wsum[1][n]) + (wsum[2][n] + wsum[3][n])};
     }
 }
 

@@ -167,8 +167,7 @@ def bench_decode(args):
 
     def step(s, sl):
         """One decoded token; sl holds the sequence lengths INCLUDING the new token."""
-        binding.append_kv(prm, ks[s], vs[s], kc, vc, sl, cap)
-        binding.compress_keys(prm, kc, sl, cap, ck=ck, n_new_tokens=1)
+        binding.append_kv(prm, ks[s], vs[s], kc, vc, sl, cap, ck=ck)      # append + incremental compression
         binding.select_blocks(prm, binding.MODE_DECODE, qs[s], ck, sl, cap, block_idx=idx, workspace=ws_sel)
         binding.sparse_attn_decode(prm, qs[s], kc, vc, sl, cap, idx, out=out, lse=lse, workspace=ws_att)
 

@@ -181,12 +181,18 @@ int32_t infllmv2_sparse_attn_decode(const infllmv2_params *prm, const infllmv2_t
  * seqlens[b]-1 of each sequence's cache (seqlens already counts the new token).
  *   k_new, v_new  in   bf16 [batch, Hkv, 1, d]  (stride_t unused)
  *   k, v          out  bf16 caches [batch, Hkv, >=max_seqlen, d]
+ *   ck            out  optional (NULL to skip): the compressed-key cache of
+ *                      infllmv2_compress_keys.  When the new token completes a semantic kernel
+ *                      (seqlens[b] >= p and seqlens[b]-p a multiple of s) its representation is
+ *                      written in the same launch, bit-identical to what
+ *                      infllmv2_compress_keys(n_new_tokens = 1) writes after the append
+ *                      (section 5.4: per decode step only the semantic-kernel representations grow).
  * Sequences with seqlens[b] < 1 are skipped.
  */
 int32_t infllmv2_append_kv(const infllmv2_params *prm, const infllmv2_tensor *k_new,
                            const infllmv2_tensor *v_new, const infllmv2_tensor *k,
-                           const infllmv2_tensor *v, const int32_t *seqlens, int32_t batch,
-                           int32_t max_seqlen, void *stream);
+                           const infllmv2_tensor *v, const infllmv2_tensor *ck,
+                           const int32_t *seqlens, int32_t batch, int32_t max_seqlen, void *stream);
 
 /*
  * Per-kernel timing for benchmarks (the measurement the roofline figures are built on).

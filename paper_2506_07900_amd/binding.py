@@ -97,7 +97,7 @@ def load_library(path=None):
     lib.infllmv2_sparse_attn_decode.restype = i32
     lib.infllmv2_sparse_attn_decode.argtypes = [P, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
     lib.infllmv2_append_kv.restype = i32
-    lib.infllmv2_append_kv.argtypes = [P, T, T, T, T, vp, i32, i32, vp]
+    lib.infllmv2_append_kv.argtypes = [P, T, T, T, T, T, vp, i32, i32, vp]
     lib.infllmv2_timing_enable.restype = i32
     lib.infllmv2_timing_enable.argtypes = [i32]
     lib.infllmv2_timing_read.restype = i32
@@ -187,13 +187,16 @@ def compress_keys(prm, k, seqlens, max_seqlen, ck=None, n_new_tokens=0):
     return ck
 
 
-def append_kv(prm, k_new, v_new, k, v, seqlens, max_seqlen):
-    """k_new, v_new [B, Hkv, 1, d] are written at cache position seqlens[b]-1."""
+def append_kv(prm, k_new, v_new, k, v, seqlens, max_seqlen, ck=None):
+    """k_new, v_new [B, Hkv, 1, d] are written at cache position seqlens[b]-1; with ck the
+    compressed key that the new token completes (if any) is written in the same launch."""
     lib = load_library()
     d = [_cache_desc(k_new, "k_new"), _cache_desc(v_new, "v_new"), _cache_desc(k, "k"), _cache_desc(v, "v")]
+    ckd = ctypes.byref(_cache_desc(ck, "ck")) if ck is not None else None
     _check(lib.infllmv2_append_kv(ctypes.byref(prm.c()), ctypes.byref(d[0]), ctypes.byref(d[1]),
-                                  ctypes.byref(d[2]), ctypes.byref(d[3]), _i32(seqlens, "seqlens").data_ptr(),
-                                  k.shape[0], max_seqlen, _stream()), "infllmv2_append_kv")
+                                  ctypes.byref(d[2]), ctypes.byref(d[3]), ckd,
+                                  _i32(seqlens, "seqlens").data_ptr(), k.shape[0], max_seqlen, _stream()),
+           "infllmv2_append_kv")
 
 
 def select_blocks(prm, mode, q, ck, seqlens, max_seqlen, block_idx=None, workspace=None):

@@ -160,18 +160,22 @@ int32_t infllmv2_compress_keys(const infllmv2_params *prm, const infllmv2_tensor
 
 int32_t infllmv2_append_kv(const infllmv2_params *prm, const infllmv2_tensor *k_new,
                            const infllmv2_tensor *v_new, const infllmv2_tensor *k,
-                           const infllmv2_tensor *v, const int32_t *seqlens, int32_t batch,
-                           int32_t max_seqlen, void *stream) {
+                           const infllmv2_tensor *v, const infllmv2_tensor *ck, const int32_t *seqlens,
+                           int32_t batch, int32_t max_seqlen, void *stream) {
     RETURN_IF_ERR(check_params(prm));
     RETURN_IF_ERR(check_sizes(batch, max_seqlen));
     RETURN_IF_ERR(check_tensor(k_new));
     RETURN_IF_ERR(check_tensor(v_new));
     RETURN_IF_ERR(check_tensor(k));
     RETURN_IF_ERR(check_tensor(v));
+    if (ck) RETURN_IF_ERR(check_tensor(ck));
     if (!seqlens) return INFLLMV2_ERR_INVALID_ARGUMENT;
     const Dims dm = make_dims(prm, batch, max_seqlen);
+    Tensor ckt;
+    if (ck) ckt = make_tensor(ck);
     return hip_status(launch_append_kv(dm, make_tensor(k_new), make_tensor(v_new), make_tensor(k),
-                                       make_tensor(v), seqlens, reinterpret_cast<hipStream_t>(stream)));
+                                       make_tensor(v), ck ? &ckt : nullptr, seqlens,
+                                       reinterpret_cast<hipStream_t>(stream)));
 }
 
 int32_t infllmv2_select_blocks(const infllmv2_params *prm, int32_t mode, const infllmv2_tensor *q,

@@ -97,7 +97,7 @@ void timing_end(hipStream_t stream);
 // Launchers implemented in the .hip files; each returns a hipError_t as int.
 int launch_compress_keys(const Dims &dm, Tensor k, Tensor ck, const int32_t *seqlens,
                          int32_t n_new_tokens, hipStream_t stream);
-int launch_append_kv(const Dims &dm, Tensor k_new, Tensor v_new, Tensor k, Tensor v,
+int launch_append_kv(const Dims &dm, Tensor k_new, Tensor v_new, Tensor k, Tensor v, const Tensor *ck,
                      const int32_t *seqlens, hipStream_t stream);
 int launch_select_prefill(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
                           int32_t *block_idx, void *ws, hipStream_t stream);

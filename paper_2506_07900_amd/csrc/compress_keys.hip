@@ -74,9 +74,13 @@ int launch_compress_keys(const Dims &dm, Tensor k, Tensor ck, const int32_t *seq
 }
 
 // Decode-step append: copy the new key / value row of every (sequence, key-value head) to
-// cache position seqlens[b]-1.  One 16-lane group per row.
+// cache position seqlens[b]-1.  One 16-lane group per row.  With kWithCk the same launch also
+// writes the semantic-kernel representation that the new token completes (it ends kernel
+// jh = (L-32)/16 when L >= 32 and L-32 is a multiple of 16): its 31 older rows come from the
+// cache, the newest from k_new, summed in fp64 like compress_keys_kernel (exact for bf16 inputs).
+template <bool kWithCk>
 __global__ __launch_bounds__(256) void append_kv_kernel(Dims dm, Tensor k_new, Tensor v_new, Tensor k,
-                                                         Tensor v, const int32_t *__restrict__ seqlens) {
+                                                         Tensor v, Tensor ck, const int32_t *__restrict__ seqlens) {
     const int row = blockIdx.x * 16 + (threadIdx.x >> 4);   // (b, h) pair
     if (row >= dm.batch * dm.Hkv) return;
     const int b = row / dm.Hkv, h = row % dm.Hkv;
@@ -84,19 +88,50 @@ __global__ __launch_bounds__(256) void append_kv_kernel(Dims dm, Tensor k_new, T
     if (L < 1 || L > dm.max_seqlen) return;
     const int c = (threadIdx.x & 15) * 8;
     const int64_t dst = (int64_t)(L - 1);
-    *reinterpret_cast<uint4 *>(k.ptr + b * k.sb + h * k.sh + dst * k.st + c) =
-        *reinterpret_cast<const uint4 *>(k_new.ptr + b * k_new.sb + h * k_new.sh + c);
+    const uint4 kn = *reinterpret_cast<const uint4 *>(k_new.ptr + b * k_new.sb + h * k_new.sh + c);
+    const __bf16 *kb = k.ptr + b * k.sb + h * k.sh + c;
+    const bool closes = kWithCk && L >= kKernel && (L - kKernel) % kStride == 0;
+    bf16x8 old[kKernel - 1];
+    if (closes) {
+#pragma unroll
+        for (int t = 0; t < kKernel - 1; ++t) old[t] = load8(kb + (int64_t)(L - kKernel + t) * k.st);
+    }
+    *reinterpret_cast<uint4 *>(k.ptr + b * k.sb + h * k.sh + dst * k.st + c) = kn;
     *reinterpret_cast<uint4 *>(v.ptr + b * v.sb + h * v.sh + dst * v.st + c) =
         *reinterpret_cast<const uint4 *>(v_new.ptr + b * v_new.sb + h * v_new.sh + c);
+    if (closes) {
+        const bf16x8 newest = __builtin_bit_cast(bf16x8, kn);
+        double acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.0;
+#pragma unroll
+        for (int t = 0; t < kKernel - 1; ++t)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += (double)(float)old[t][e];
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t lo = f64_to_bf16_rne((acc[2 * e] + (double)(float)newest[2 * e]) / (double)kKernel);
+            const uint32_t hi = f64_to_bf16_rne((acc[2 * e + 1] + (double)(float)newest[2 * e + 1]) / (double)kKernel);
+            w[e] = lo | (hi << 16);
+        }
+        const int32_t jh = (L - kKernel) / kStride;
+        *reinterpret_cast<uint4 *>(ck.ptr + b * ck.sb + h * ck.sh + (int64_t)jh * ck.st + c) =
+            uint4{w[0], w[1], w[2], w[3]};
+    }
 }
 
-int launch_append_kv(const Dims &dm, Tensor k_new, Tensor v_new, Tensor k, Tensor v,
+int launch_append_kv(const Dims &dm, Tensor k_new, Tensor v_new, Tensor k, Tensor v, const Tensor *ck,
                      const int32_t *seqlens, hipStream_t stream) {
     int rows = dm.batch * dm.Hkv;
     if (rows <= 0) return 0;
     timing_begin("append_kv_kernel", stream);
-    hipLaunchKernelGGL(append_kv_kernel, dim3((rows + 15) / 16), dim3(256), 0, stream, dm, k_new,
-                       v_new, k, v, seqlens);
+    if (ck)
+        hipLaunchKernelGGL(append_kv_kernel<true>, dim3((rows + 15) / 16), dim3(256), 0, stream, dm, k_new,
+                           v_new, k, v, *ck, seqlens);
+    else
+        hipLaunchKernelGGL(append_kv_kernel<false>, dim3((rows + 15) / 16), dim3(256), 0, stream, dm, k_new,
+                           v_new, k, v, k, seqlens);
     timing_end(stream);
     return (int)hipGetLastError();
 }

@@ -106,6 +106,16 @@ def test_workspace_validation(lib):
                                             FAKE, 1, 4096, FAKE, ctypes.byref(o), FAKE, None, 0, None) == WORKSPACE
 
 
+def test_append_kv_validation(lib):
+    prm, t = good_params(), tensor()
+    P, T = ctypes.byref(prm), ctypes.byref(t)
+    bad = tensor(st=100)                                                                 # stride not /8
+    assert lib.infllmv2_append_kv(P, T, T, T, T, None, None, 1, 4096, None) == INVALID   # no seqlens
+    assert lib.infllmv2_append_kv(P, T, T, T, T, ctypes.byref(bad), FAKE, 1, 4096, None) == INVALID
+    assert lib.infllmv2_append_kv(P, None, T, T, T, None, FAKE, 1, 4096, None) == INVALID
+    assert lib.infllmv2_append_kv(P, T, T, T, T, None, FAKE, 0, 4096, None) == 0         # empty batch: nothing to do
+
+
 def test_binding_fails_loudly_without_library(tmp_path):
     with pytest.raises(binding.InfLLMv2Error):
         binding.load_library(str(tmp_path / "missing.so"))

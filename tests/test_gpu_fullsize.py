@@ -169,8 +169,7 @@ def test_decode_graph_replays_match_eager():
 
     def step(st, s):
         st["sl"].add_(1)
-        binding.append_kv(prm, ks[s], vs[s], st["kc"], st["vc"], st["sl"], cap)
-        binding.compress_keys(prm, st["kc"], st["sl"], cap, ck=st["ck"], n_new_tokens=1)
+        binding.append_kv(prm, ks[s], vs[s], st["kc"], st["vc"], st["sl"], cap, ck=st["ck"])
         binding.select_blocks(prm, binding.MODE_DECODE, qs[s], st["ck"], st["sl"], cap, block_idx=st["idx"], workspace=st["ws1"])
         binding.sparse_attn_decode(prm, qs[s], st["kc"], st["vc"], st["sl"], cap, st["idx"], out=st["out"], lse=st["lse"], workspace=st["ws2"])
 

@@ -247,10 +247,11 @@ def test_decode_select_and_attn(seqlens, Hq, Hkv, topk):
         assert eo <= OUT_TOL and el <= 1.0
 
 
-def test_decode_steps_with_append_and_incremental_compress():
-    # a short run of real decode steps: append, incremental compression, select, attend;
-    # every step equals the oracle evaluated on the cache as it stands
-    print("case decode steps", flush=True)
+@pytest.mark.parametrize("fused", [False, True])
+def test_decode_steps_with_append_and_incremental_compress(fused):
+    # a short run of real decode steps: append, incremental compression (its own launch, or
+    # inside the append), select, attend; every step equals the oracle on the cache as it stands
+    print("case decode steps, fused append+compress:", fused, flush=True)
     cfg = synth.CONFIGS[3]
     steps, L0 = 40, 1500
     x = synth.make_decode(cfg, steps=steps, seqlen=L0)
@@ -268,15 +269,18 @@ def test_decode_steps_with_append_and_incremental_compress():
         kn = to_dev(x.k_steps[s][:, :, None])
         vn = to_dev(x.v_steps[s][:, :, None])
         qd = to_dev(x.q_steps[s][:, None])
-        binding.append_kv(prm, kn, vn, kd, vd, sl, cap)
-        binding.compress_keys(prm, kd, sl, cap, ck=ck, n_new_tokens=1)
+        if fused:
+            binding.append_kv(prm, kn, vn, kd, vd, sl, cap, ck=ck)
+        else:
+            binding.append_kv(prm, kn, vn, kd, vd, sl, cap)
+            binding.compress_keys(prm, kd, sl, cap, ck=ck, n_new_tokens=1)
         idx = binding.select_blocks(prm, binding.MODE_DECODE, qd, ck, sl, cap)
         out, lse = binding.sparse_attn_decode(prm, qd, kd, vd, sl, cap, idx)
         torch.cuda.synchronize()
         l = int(lens[0])
         k_np[0, :, l - 1] = x.k_steps[s][0]
         v_np[0, :, l - 1] = x.v_steps[s][0]
-        if s % 8 == 0 or s == steps - 1:
+        if s % 8 == 0 or s == steps - 1 or (l - 32) % 16 == 0:
             pos = np.array([l - 1], np.int32)
             _, ckb = ref.compress_keys(k_np[0, :, :l], oprm)
             assert np.array_equal(to_bits(ck)[0, :, :ckb.shape[1]], ckb)

@@ -195,6 +195,19 @@ int32_t infllmv2_append_kv(const infllmv2_params *prm, const infllmv2_tensor *k_
                            const int32_t *seqlens, int32_t batch, int32_t max_seqlen, void *stream);
 
 /*
+ * Measured practical peaks for the benchmark's rooflines (not part of the method).  Launches two
+ * probe kernels on `stream`: a dense bf16 MFMA loop ("probe_mfma_kernel") and a read of every byte
+ * of `buf` ("probe_stream_kernel"); their durations are obtained like any other kernel's, through
+ * infllmv2_timing_enable / infllmv2_timing_read.
+ *   buf            in   DEVICE buffer, 256-byte aligned, at least 8 MiB, ZERO-FILLED by the caller
+ *                       (it is only read; a size far above the cache sizes measures HBM)
+ *   mfma_flops     out  HOST: floating-point operations the MFMA probe executes per launch
+ *   stream_bytes   out  HOST: bytes the stream probe reads per launch
+ */
+int32_t infllmv2_probe_peaks(void *buf, size_t buf_bytes, double *mfma_flops, double *stream_bytes,
+                             void *stream);
+
+/*
  * Per-kernel timing for benchmarks (the measurement the roofline figures are built on).
  * While enabled, every kernel launched by the entry points above is bracketed by HIP events
  * recorded on the call's stream; at most 256 launches are kept between reads.  Process-wide

@@ -26,7 +26,7 @@ MODE_PREFILL, MODE_DECODE = 0, 1
 
 EXPORTS = ["infllmv2_status_string", "infllmv2_workspace_bytes", "infllmv2_compress_keys",
            "infllmv2_select_blocks", "infllmv2_sparse_attn_prefill", "infllmv2_sparse_attn_decode",
-           "infllmv2_append_kv", "infllmv2_timing_enable", "infllmv2_timing_read"]
+           "infllmv2_append_kv", "infllmv2_probe_peaks", "infllmv2_timing_enable", "infllmv2_timing_read"]
 
 
 class CParams(ctypes.Structure):
@@ -98,6 +98,8 @@ def load_library(path=None):
     lib.infllmv2_sparse_attn_decode.argtypes = [P, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
     lib.infllmv2_append_kv.restype = i32
     lib.infllmv2_append_kv.argtypes = [P, T, T, T, T, T, vp, i32, i32, vp]
+    lib.infllmv2_probe_peaks.restype = i32
+    lib.infllmv2_probe_peaks.argtypes = [vp, sz, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp]
     lib.infllmv2_timing_enable.restype = i32
     lib.infllmv2_timing_enable.argtypes = [i32]
     lib.infllmv2_timing_read.restype = i32
@@ -197,6 +199,16 @@ def append_kv(prm, k_new, v_new, k, v, seqlens, max_seqlen, ck=None):
                                   ctypes.byref(d[2]), ctypes.byref(d[3]), ckd,
                                   _i32(seqlens, "seqlens").data_ptr(), k.shape[0], max_seqlen, _stream()),
            "infllmv2_append_kv")
+
+
+def probe_peaks(buf):
+    """Launch the two probe kernels over the zero-filled uint8 device buffer `buf`;
+    -> (flops of the MFMA probe, bytes of the stream probe).  Durations come from timing_read()."""
+    lib = load_library()
+    fl, by = ctypes.c_double(), ctypes.c_double()
+    _check(lib.infllmv2_probe_peaks(buf.data_ptr(), buf.numel(), ctypes.byref(fl), ctypes.byref(by), _stream()),
+           "infllmv2_probe_peaks")
+    return fl.value, by.value
 
 
 def select_blocks(prm, mode, q, ck, seqlens, max_seqlen, block_idx=None, workspace=None):

@@ -121,6 +121,13 @@ int32_t infllmv2_timing_read(int32_t max_entries, const char **names, float *ms)
     return n;
 }
 
+int32_t infllmv2_probe_peaks(void *buf, size_t buf_bytes, double *mfma_flops, double *stream_bytes, void *stream) {
+    if (!buf || !mfma_flops || !stream_bytes || buf_bytes < (size_t)(8u << 20) ||
+        (reinterpret_cast<uintptr_t>(buf) & 255u) != 0)
+        return INFLLMV2_ERR_INVALID_ARGUMENT;
+    return hip_status(launch_probes(buf, buf_bytes, mfma_flops, stream_bytes, reinterpret_cast<hipStream_t>(stream)));
+}
+
 const char *infllmv2_status_string(int32_t status) {
     switch (status) {
         case INFLLMV2_OK: return "ok";

@@ -119,5 +119,6 @@ int launch_attn_decode(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32
                        const int32_t *block_idx, Tensor out, float *lse, void *ws,
                        hipStream_t stream);
 size_t attn_decode_ws_bytes(const Dims &dm);
+int launch_probes(void *buf, size_t buf_bytes, double *mfma_flops, double *stream_bytes, hipStream_t stream);
 
 }  // namespace infllmv2

@@ -136,13 +136,12 @@ def bench_prefill(args):
     return res, (x, idx, out, lse, prm, cfg)
 
 
-def bench_decode(args):
-    """128K-context decode: append -> incremental compress -> select -> attend, per token."""
+def bench_decode(cfg_index, steps):
+    """Decode workload: append (+ incremental compression) -> select -> attend, per step."""
     import torch
     from paper_2506_07900_amd import binding, synth
 
-    cfg = synth.CONFIGS[3]
-    steps = args.decode_steps
+    cfg = synth.CONFIGS[cfg_index]
     log("[bench] generating %s inputs (%d steps)" % (cfg.name, steps))
     x = synth.make_decode(cfg, steps=steps + 128)      # head-room: the graph is replayed once untimed
     prm = binding.Params(cfg.n_q_heads, cfg.n_kv_heads, topk=cfg.topk)
@@ -156,7 +155,7 @@ def bench_decode(args):
     qs = dev(x.q_steps)[:, :, None].contiguous()         # [steps, B, 1, Hq, d]
     ks = dev(x.k_steps)[:, :, :, None].contiguous()      # [steps, B, Hkv, 1, d]
     vs = dev(x.v_steps)[:, :, :, None].contiguous()
-    B = 1
+    B = cfg.batch
     sl = torch.tensor(x.seqlens0, dtype=torch.int32, device="cuda")
     ck = torch.zeros((B, Hkv, binding.num_kernels(cap, prm), d), dtype=torch.bfloat16, device="cuda")
     binding.compress_keys(prm, kc, sl, cap, ck=ck)
@@ -219,16 +218,16 @@ def bench_decode(args):
     us = (t1 - t0) * 1e6 / timed
     if graph is not None:
         sl = sl_tab[0] - 1                     # lengths reached after the last replay
-    L = int(sl[0].item()) - timed // 2
-    n_c = (L - 32) // 16 + 1
-    gathered = Hkv * cfg.topk * m * d * 2 * 2
-    algorithmic = gathered + n_c * Hkv * d * 2 + 2 * Hq * d * 2 + Hkv * cfg.topk * 4
-    return {"workload": cfg.name, "steps": timed, "us_per_token": us,
+    Ls = sl.cpu().numpy().astype(np.int64) - timed // 2      # mid-run lengths, per sequence
+    n_c = np.maximum((Ls - 32) // 16 + 1, 0)
+    gathered = B * Hkv * cfg.topk * m * d * 2 * 2
+    algorithmic = gathered + int(n_c.sum()) * Hkv * d * 2 + B * (2 * Hq * d * 2 + Hkv * cfg.topk * 4)
+    return {"workload": cfg.name, "batch": B, "steps": timed, "us_per_step": us, "us_per_token": us / B,
             "bytes_gathered": gathered, "bytes_algorithmic": algorithmic,
             "gathered_GBs": gathered / us / 1e3, "algorithmic_GBs": algorithmic / us / 1e3,
             "frac_hbm_gathered": gathered / us / 1e3 / PEAK_HBM_GBS,
             "frac_hbm_algorithmic": algorithmic / us / 1e3 / PEAK_HBM_GBS,
-            "context_at_end": int(sl[0].item()), "launch": launch}
+            "contexts_at_end": [int(v) for v in sl.cpu().numpy()], "launch": launch}
 
 
 def measured_peaks():
@@ -291,9 +290,10 @@ def main():
     ap.add_argument("--workload", choices=["prefill_32k", "prefill_128k"], default="prefill_32k",
                     help="prefill workload of the timed step (the headline metric is quoted on prefill_32k)")
     ap.add_argument("--decode-steps", type=int, default=1000)
+    ap.add_argument("--ragged-steps", type=int, default=200)
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=4096)
+    ap.add_argument("--cpu-rows", type=int, default=32768)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 1 GiB read + 1 GiB write elementwise kernel, the known-size "
                          "reference the rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -344,11 +344,15 @@ def main():
     line["frac_measured_mfma_peak_whole_step"] = res["value"] / mp["mfma_bf16_TFLOPs"]
     if not args.no_decode:
         del out, lse
-        line["decode"] = bench_decode(args)
+        line["decode"] = bench_decode(3, args.decode_steps)
         line["decode"]["frac_measured_hbm_algorithmic"] = line["decode"]["algorithmic_GBs"] / mp["hbm_read_GBs"]
+        if args.ragged_steps > 0:
+            line["decode_ragged_b8"] = bench_decode(4, args.ragged_steps)
+            line["decode_ragged_b8"]["frac_measured_hbm_algorithmic"] = (
+                line["decode_ragged_b8"]["algorithmic_GBs"] / mp["hbm_read_GBs"])
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a sample")
-        line["cpu_baseline"] = cpu_baseline(x, cfg, args.cpu_rows)
+        line["cpu_baseline"] = cpu_baseline(x, cfg, args.cpu_rows if args.workload == "prefill_32k" else min(args.cpu_rows, 8192))
     print(json.dumps(line), flush=True)
 
 

@@ -213,7 +213,8 @@ def test_prefill_end_to_end_dense_degrade():
 
 @pytest.mark.parametrize("seqlens,Hq,Hkv,topk", [([3000, 1077, 64, 33, 31, 1], 32, 2, 16),
                                                  ([2048, 129], 4, 1, 8), ([777], 16, 2, 6),
-                                                 ([9000, 4500, 200], 32, 2, 64)])
+                                                 ([9000, 4500, 200], 32, 2, 64),
+                                                 ([4100, 4097, 20], 32, 2, 16)])      # 65 blocks, 255 kernels
 def test_decode_select_and_attn(seqlens, Hq, Hkv, topk):
     print("case decode", seqlens, Hq, Hkv, topk, flush=True)
     prm = binding.Params(Hq, Hkv, topk=topk)

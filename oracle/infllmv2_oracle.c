@@ -29,6 +29,17 @@
  *   - query i ranks blocks 0..floor(i/m); the last one may be partial;
  *   - forced blocks: the first n_init blocks and the last n_local blocks up to
  *     and including the query's own.
+ * Readings for the approximate log-sum-exp ("Efficient Top-K Implementation", last
+ * paragraph; the report gives no formula, so all of this is a definition -- parity
+ * unpinned for the reading, the arithmetic is pinned):
+ *   - a coarse semantic kernel covers s_c = rho*s tokens of stride and 2*s_c tokens of
+ *     size (the same overlap as p = 2s); it is the mean of the rho disjoint fine kernels
+ *     that tile its window, taken from the bf16 fine representations and rounded to bf16;
+ *   - a query sees a coarse kernel iff it sees all of its fine kernels;
+ *   - LSE_approx = log sum_{visible coarse} exp(scale <q, CKc>) + log(rho)   (there are
+ *     rho times fewer coarse kernels); 0 when no coarse kernel is visible (no selection
+ *     depends on it when (n_init + n_local) * m >= 2 * s_c);
+ *   - scores exp(z - LSE_approx) are no longer bounded by 1: they are clamped above at 2^100.
  */
 #include <math.h>
 #include <stdint.h>
@@ -36,6 +47,7 @@
 #include <string.h>
 
 #define ORACLE_SCORE_FLOOR 7.888609052210118e-31 /* 2^-100 */
+#define ORACLE_SCORE_CEIL 1.2676506002282294e30  /* 2^100, approximate-LSE mode only */
 
 /* ---- bf16 helpers -------------------------------------------------------- */
 
@@ -99,6 +111,37 @@ int32_t oracle_compress_keys(const uint16_t *k_bits, int32_t Hkv, int32_t l, int
     return n_c;
 }
 
+/* ---- coarse semantic kernels for the approximate log-sum-exp ------------------ */
+
+/* Number of coarse kernels whose rho fine kernels rho*c, rho*c+2, .., rho*c+2(rho-1) all lie
+ * among the first n fine kernels ("Efficient Top-K Implementation": coarse-grained semantic
+ * kernels of size s_c >> s). */
+int32_t oracle_num_coarse(int32_t n, int32_t rho) {
+    if (rho < 1 || n < 2 * rho - 1) return 0;
+    return (n - (2 * rho - 1)) / rho + 1;
+}
+
+/* CKc[h, c, :] = mean_r CK[h, rho*c + 2r, :], r = 0..rho-1, from the bf16 fine representations.
+ *   ck_bits   [Hkv, n_c, d]
+ *   ckc_f64   [Hkv, n_cc, d] unrounded (may be NULL); ckc_bits rounded to bf16 (may be NULL)
+ * Returns n_cc = oracle_num_coarse(n_c, rho). */
+int32_t oracle_coarse_kernels(const uint16_t *ck_bits, int32_t Hkv, int32_t n_c, int32_t d,
+                              int32_t rho, double *ckc_f64, uint16_t *ckc_bits) {
+    int32_t n_cc = oracle_num_coarse(n_c, rho);
+    for (int32_t h = 0; h < Hkv; ++h)
+        for (int32_t c = 0; c < n_cc; ++c)
+            for (int32_t e = 0; e < d; ++e) {
+                double sum = 0.0;
+                for (int32_t r = 0; r < rho; ++r)
+                    sum += bf16_to_f64(ck_bits[((size_t)h * n_c + (size_t)rho * c + 2 * r) * d + e]);
+                double mean = sum / (double)rho;
+                size_t o = ((size_t)h * n_cc + c) * d + e;
+                if (ckc_f64) ckc_f64[o] = mean;
+                if (ckc_bits) ckc_bits[o] = f64_to_bf16(mean);
+            }
+    return n_cc;
+}
+
 /* ---- O2: kernel relevance for one query row ------------------------------- */
 
 /* r[jh] = (1/G) sum_g softmax_jh(scale * <q_g, CK[jh]>), jh < n_vis, then floored.
@@ -130,6 +173,45 @@ static void kernel_scores_row(const uint16_t *q_row, const uint16_t *ck_h, int32
     }
 }
 
+/* The same with the approximate log-sum-exp: per head, lse = log sum over the n_vis_c visible
+ * coarse kernels of exp(scale <q_g, CKc>) + log(rho) (0 when none is visible), and
+ * r[jh] = (1/G) sum_g exp(scale <q_g, CK[jh]> - lse_g), clamped to [2^-100, 2^100].
+ *   ckc_h   [n_cc, d] bf16 bits of the coarse kernels of this key-value head
+ *   lse_out [G] (may be NULL): the approximate log-sum-exp per head */
+static void kernel_scores_row_coarse(const uint16_t *q_row, const uint16_t *ck_h, const uint16_t *ckc_h,
+                                     int32_t G, int32_t d, int32_t n_vis, int32_t n_vis_c, int32_t rho,
+                                     double scale, double *r, double *z, double *lse_out) {
+    for (int32_t jh = 0; jh < n_vis; ++jh) r[jh] = 0.0;
+    for (int32_t g = 0; g < G; ++g) {
+        double lse = 0.0;
+        if (n_vis_c > 0) {
+            double zmax = -INFINITY;
+            for (int32_t c = 0; c < n_vis_c; ++c) {
+                double dot = 0.0;
+                for (int32_t e = 0; e < d; ++e)
+                    dot += bf16_to_f64(q_row[(size_t)g * d + e]) * bf16_to_f64(ckc_h[(size_t)c * d + e]);
+                z[c] = scale * dot;
+                if (z[c] > zmax) zmax = z[c];
+            }
+            double denom = 0.0;
+            for (int32_t c = 0; c < n_vis_c; ++c) denom += exp(z[c] - zmax);
+            lse = zmax + log(denom) + log((double)rho);
+        }
+        if (lse_out) lse_out[g] = lse;
+        for (int32_t jh = 0; jh < n_vis; ++jh) {
+            double dot = 0.0;
+            for (int32_t e = 0; e < d; ++e)
+                dot += bf16_to_f64(q_row[(size_t)g * d + e]) * bf16_to_f64(ck_h[(size_t)jh * d + e]);
+            r[jh] += exp(scale * dot - lse);
+        }
+    }
+    for (int32_t jh = 0; jh < n_vis; ++jh) {
+        r[jh] /= (double)G;
+        if (r[jh] < ORACLE_SCORE_FLOOR) r[jh] = ORACLE_SCORE_FLOOR;
+        if (r[jh] > ORACLE_SCORE_CEIL) r[jh] = ORACLE_SCORE_CEIL;
+    }
+}
+
 /* Group-mean kernel scores for a list of query rows (for tests and small cases).
  *   q_bits    [Tq, Hq, d]; row t is the query at position pos[t]
  *   ck_bits   [Hkv, n_c, d]
@@ -150,6 +232,34 @@ void oracle_kernel_scores(const uint16_t *q_bits, const uint16_t *ck_bits, const
                 for (int32_t jh = 0; jh < n_c; ++jh) r[jh] = 0.0;
                 kernel_scores_row(q_bits + ((size_t)t * Hq + (size_t)h * G) * d,
                                   ck_bits + (size_t)h * n_c * d, G, d, n_vis, scale, r, z);
+            }
+        free(z);
+    }
+}
+
+/* Group-mean kernel scores with the approximate log-sum-exp, for a list of query rows.
+ *   ckc_bits  [Hkv, n_cc, d] coarse kernels (oracle_coarse_kernels)
+ *   r_out     [Hkv, Tq, n_c]; lse_out [Hkv, Tq, G] (may be NULL) */
+void oracle_kernel_scores_coarse(const uint16_t *q_bits, const uint16_t *ck_bits, const uint16_t *ckc_bits,
+                                 const int32_t *pos, int32_t Tq, int32_t Hq, int32_t Hkv, int32_t d,
+                                 int32_t n_c, int32_t n_cc, int32_t p, int32_t s, int32_t rho, double scale,
+                                 double *r_out, double *lse_out) {
+    int32_t G = Hq / Hkv;
+#pragma omp parallel
+    {
+        double *z = (double *)malloc(sizeof(double) * (size_t)(n_c > 0 ? n_c : 1));
+#pragma omp for schedule(dynamic, 16)
+        for (int32_t t = 0; t < Tq; ++t)
+            for (int32_t h = 0; h < Hkv; ++h) {
+                int32_t n_vis = oracle_num_kernels(pos[t] + 1, p, s);
+                if (n_vis > n_c) n_vis = n_c;
+                int32_t n_vis_c = oracle_num_coarse(n_vis, rho);
+                double *r = r_out + ((size_t)h * Tq + t) * n_c;
+                for (int32_t jh = 0; jh < n_c; ++jh) r[jh] = 0.0;
+                kernel_scores_row_coarse(q_bits + ((size_t)t * Hq + (size_t)h * G) * d,
+                                         ck_bits + (size_t)h * n_c * d, ckc_bits + (size_t)h * n_cc * d, G, d,
+                                         n_vis, n_vis_c, rho, scale, r, z,
+                                         lse_out ? lse_out + ((size_t)h * Tq + t) * G : NULL);
             }
         free(z);
     }
@@ -184,11 +294,11 @@ static void block_scores_row(const double *r, int32_t n_vis, int32_t n_blk, int3
  *              (+inf forced, -inf no visible kernel, NaN beyond the query's own block)
  * Section 2.1.2: "selects the k blocks with the highest relevance"; the initial and the
  * local-window blocks get score infinity; with at most k blocks everything is selected. */
-void oracle_select_blocks(const uint16_t *q_bits, const uint16_t *ck_bits, const int32_t *pos,
-                          int32_t Tq, int32_t Hq, int32_t Hkv, int32_t d, int32_t n_c,
-                          int32_t m, int32_t p, int32_t s, int32_t topk, int32_t n_init,
-                          int32_t n_local, double scale, int32_t *block_idx, double *margins,
-                          double *R_out, int32_t nb_cap) {
+static void select_rows(const uint16_t *q_bits, const uint16_t *ck_bits, const int32_t *pos,
+                        int32_t Tq, int32_t Hq, int32_t Hkv, int32_t d, int32_t n_c,
+                        int32_t m, int32_t p, int32_t s, int32_t topk, int32_t n_init,
+                        int32_t n_local, double scale, int32_t *block_idx, double *margins,
+                        double *R_out, int32_t nb_cap, int32_t rho, const uint16_t *ckc_bits, int32_t n_cc) {
     int32_t G = Hq / Hkv;
 #pragma omp parallel
     {
@@ -207,8 +317,13 @@ void oracle_select_blocks(const uint16_t *q_bits, const uint16_t *ck_bits, const
                 int32_t n_blk = b_i + 1;           /* candidate blocks 0..b_i        */
                 int32_t n_vis = oracle_num_kernels(i + 1, p, s);
                 if (n_vis > n_c) n_vis = n_c;
-                kernel_scores_row(q_bits + ((size_t)t * Hq + (size_t)h * G) * d,
-                                  ck_bits + (size_t)h * n_c * d, G, d, n_vis, scale, r, z);
+                if (ckc_bits)      /* approximate log-sum-exp from the coarse kernels */
+                    kernel_scores_row_coarse(q_bits + ((size_t)t * Hq + (size_t)h * G) * d,
+                                             ck_bits + (size_t)h * n_c * d, ckc_bits + (size_t)h * n_cc * d,
+                                             G, d, n_vis, oracle_num_coarse(n_vis, rho), rho, scale, r, z, NULL);
+                else
+                    kernel_scores_row(q_bits + ((size_t)t * Hq + (size_t)h * G) * d,
+                                      ck_bits + (size_t)h * n_c * d, G, d, n_vis, scale, r, z);
                 block_scores_row(r, n_vis, n_blk, m, p, s, R);
                 for (int32_t j = 0; j < n_blk; ++j) {
                     int forced = (j < n_init) || (j > b_i - n_local);
@@ -243,6 +358,26 @@ void oracle_select_blocks(const uint16_t *q_bits, const uint16_t *ck_bits, const
             }
         free(z); free(r); free(R); free(taken);
     }
+}
+
+void oracle_select_blocks(const uint16_t *q_bits, const uint16_t *ck_bits, const int32_t *pos,
+                          int32_t Tq, int32_t Hq, int32_t Hkv, int32_t d, int32_t n_c,
+                          int32_t m, int32_t p, int32_t s, int32_t topk, int32_t n_init,
+                          int32_t n_local, double scale, int32_t *block_idx, double *margins,
+                          double *R_out, int32_t nb_cap) {
+    select_rows(q_bits, ck_bits, pos, Tq, Hq, Hkv, d, n_c, m, p, s, topk, n_init, n_local, scale, block_idx,
+                margins, R_out, nb_cap, 1, NULL, 0);
+}
+
+/* The same selection with the approximate log-sum-exp ("Efficient Top-K Implementation"):
+ * ckc_bits [Hkv, n_cc, d] are the coarse kernels of ratio rho (oracle_coarse_kernels). */
+void oracle_select_blocks_coarse(const uint16_t *q_bits, const uint16_t *ck_bits, const uint16_t *ckc_bits,
+                                 const int32_t *pos, int32_t Tq, int32_t Hq, int32_t Hkv, int32_t d,
+                                 int32_t n_c, int32_t n_cc, int32_t m, int32_t p, int32_t s, int32_t topk,
+                                 int32_t n_init, int32_t n_local, int32_t rho, double scale,
+                                 int32_t *block_idx, double *margins, double *R_out, int32_t nb_cap) {
+    select_rows(q_bits, ck_bits, pos, Tq, Hq, Hkv, d, n_c, m, p, s, topk, n_init, n_local, scale, block_idx,
+                margins, R_out, nb_cap, rho, ckc_bits, n_cc);
 }
 
 /* ---- O4: attention over the selected blocks -------------------------------- */

@@ -47,6 +47,14 @@ def _load():
         lib.oracle_kernel_scores.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, f64, vp]
         lib.oracle_select_blocks.restype = None
         lib.oracle_select_blocks.argtypes = [vp, vp, vp] + [i32] * 11 + [f64, vp, vp, vp, i32]
+        lib.oracle_num_coarse.restype = i32
+        lib.oracle_num_coarse.argtypes = [i32, i32]
+        lib.oracle_coarse_kernels.restype = i32
+        lib.oracle_coarse_kernels.argtypes = [vp, i32, i32, i32, i32, vp, vp]
+        lib.oracle_kernel_scores_coarse.restype = None
+        lib.oracle_kernel_scores_coarse.argtypes = [vp, vp, vp, vp] + [i32] * 9 + [f64, vp, vp]
+        lib.oracle_select_blocks_coarse.restype = None
+        lib.oracle_select_blocks_coarse.argtypes = [vp, vp, vp, vp] + [i32] * 13 + [f64, vp, vp, vp, i32]
         lib.oracle_sparse_attn.restype = None
         lib.oracle_sparse_attn.argtypes = [vp, vp, vp, vp, vp] + [i32] * 7 + [f64, vp, vp, vp]
         lib.oracle_f64_to_bf16.restype = ctypes.c_uint16
@@ -70,6 +78,7 @@ class Params:
     n_init_blocks: int = 1
     n_local_blocks: int = 2
     softmax_scale: float = None
+    lse_coarse_ratio: int = 1   # rho = s_c / s of the approximate log-sum-exp; 1 = exact
 
     def __post_init__(self):
         if self.softmax_scale is None:
@@ -114,8 +123,28 @@ def compress_keys(k, prm):
     return ck64, ckb
 
 
-def kernel_scores(q, ck, pos, prm):
-    """Group-mean kernel scores r [Hkv, Tq, n_c] (0 beyond the visible kernels)."""
+def num_coarse(n, rho):
+    return int(_load().oracle_num_coarse(int(n), int(rho)))
+
+
+def coarse_kernels(ck, rho):
+    """ck uint16 [Hkv, n_c, d] -> (ckc_f64, ckc_bf16 uint16) [Hkv, n_cc, d]."""
+    lib = _load()
+    ck = _u16(ck)
+    Hkv, n_c, d = ck.shape
+    n_cc = num_coarse(n_c, rho)
+    c64 = np.zeros((Hkv, n_cc, d), np.float64)
+    cb = np.zeros((Hkv, n_cc, d), np.uint16)
+    got = lib.oracle_coarse_kernels(_ptr(ck), Hkv, n_c, d, int(rho), _ptr(c64), _ptr(cb))
+    assert got == n_cc
+    return c64, cb
+
+
+def kernel_scores(q, ck, pos, prm, want_lse=False, coarse_path=None):
+    """Group-mean kernel scores r [Hkv, Tq, n_c] (0 beyond the visible kernels); with
+    prm.lse_coarse_ratio > 1 the approximate log-sum-exp is used (want_lse: also return it,
+    [Hkv, Tq, G]).  coarse_path=True takes the approximate-LSE code path even for ratio 1 (where it
+    must reproduce the exact scores)."""
     lib = _load()
     q = _u16(q)
     ck = _u16(ck)
@@ -124,12 +153,20 @@ def kernel_scores(q, ck, pos, prm):
     Hkv, n_c, _ = ck.shape
     assert Hq == prm.n_q_heads and Hkv == prm.n_kv_heads and pos.shape == (Tq,)
     r = np.zeros((Hkv, Tq, n_c), np.float64)
+    if prm.lse_coarse_ratio > 1 if coarse_path is None else coarse_path:
+        _, ckc = coarse_kernels(ck, prm.lse_coarse_ratio)
+        lse = np.zeros((Hkv, Tq, Hq // Hkv), np.float64)
+        lib.oracle_kernel_scores_coarse(_ptr(q), _ptr(ck), _ptr(ckc), _ptr(pos), Tq, Hq, Hkv, d, n_c,
+                                        ckc.shape[1], prm.kernel_size, prm.kernel_stride,
+                                        prm.lse_coarse_ratio, float(prm.softmax_scale), _ptr(r), _ptr(lse))
+        return (r, lse) if want_lse else r
+    assert not want_lse
     lib.oracle_kernel_scores(_ptr(q), _ptr(ck), _ptr(pos), Tq, Hq, Hkv, d, n_c,
                              prm.kernel_size, prm.kernel_stride, float(prm.softmax_scale), _ptr(r))
     return r
 
 
-def select_blocks(q, ck, pos, prm, want_scores=False):
+def select_blocks(q, ck, pos, prm, want_scores=False, coarse_path=None):
     """-> block_idx int32 [Hkv, Tq, topk], margins fp64 [Hkv, Tq, 2] (, R [Hkv, Tq, nb])."""
     lib = _load()
     q = _u16(q)
@@ -142,10 +179,18 @@ def select_blocks(q, ck, pos, prm, want_scores=False):
     margins = np.zeros((Hkv, Tq, 2), np.float64)
     nb_cap = int(pos.max()) // prm.block_size + 1 if Tq else 1
     R = np.zeros((Hkv, Tq, nb_cap), np.float64) if want_scores else None
-    lib.oracle_select_blocks(_ptr(q), _ptr(ck), _ptr(pos), Tq, Hq, Hkv, d, n_c,
-                             prm.block_size, prm.kernel_size, prm.kernel_stride, prm.topk,
-                             prm.n_init_blocks, prm.n_local_blocks, float(prm.softmax_scale),
-                             _ptr(idx), _ptr(margins), _ptr(R), nb_cap)
+    if prm.lse_coarse_ratio > 1 if coarse_path is None else coarse_path:
+        _, ckc = coarse_kernels(ck, prm.lse_coarse_ratio)
+        lib.oracle_select_blocks_coarse(_ptr(q), _ptr(ck), _ptr(ckc), _ptr(pos), Tq, Hq, Hkv, d, n_c,
+                                        ckc.shape[1], prm.block_size, prm.kernel_size, prm.kernel_stride,
+                                        prm.topk, prm.n_init_blocks, prm.n_local_blocks,
+                                        prm.lse_coarse_ratio, float(prm.softmax_scale),
+                                        _ptr(idx), _ptr(margins), _ptr(R), nb_cap)
+    else:
+        lib.oracle_select_blocks(_ptr(q), _ptr(ck), _ptr(pos), Tq, Hq, Hkv, d, n_c,
+                                 prm.block_size, prm.kernel_size, prm.kernel_stride, prm.topk,
+                                 prm.n_init_blocks, prm.n_local_blocks, float(prm.softmax_scale),
+                                 _ptr(idx), _ptr(margins), _ptr(R), nb_cap)
     return (idx, margins, R) if want_scores else (idx, margins)
 
 

@@ -385,3 +385,113 @@ def test_config1_planted_blocks_are_found():
     planted = set(x.planted[0].tolist())
     hits = np.mean([len(planted & set(row.tolist())) for row in idx[0]])
     assert hits > 0.6 * len(planted)
+
+
+# ------------------------------------------------------------------ approximate log-sum-exp
+# ("Efficient Top-K Implementation", last paragraph: LSE from coarse-grained semantic kernels)
+
+def _small_case(l, Hq, Hkv, seed, d=16):
+    rng = np.random.default_rng(seed)
+    q = synth.f32_to_bf16_bits(rng.standard_normal((l, Hq, d), dtype=np.float32))
+    k = synth.f32_to_bf16_bits(rng.standard_normal((Hkv, l, d), dtype=np.float32))
+    return q, k
+
+
+@pytest.mark.parametrize("rho", [1, 2, 4])
+def test_coarse_kernel_count_by_brute_force(rho):
+    # a coarse kernel of ratio rho spans tokens [16 rho c, 16 rho c + 32 rho); query i sees it iff
+    # the whole span lies at or before i
+    for i in range(0, 700):
+        n_vis = ref.num_kernels(i + 1, 32, 16)
+        want = sum(1 for c in range(100) if 16 * rho * c + 32 * rho - 1 <= i)
+        assert ref.num_coarse(n_vis, rho) == want, (i, rho)
+
+
+@pytest.mark.parametrize("rho", [2, 4])
+def test_coarse_kernels_are_means_of_their_fine_kernels(rho):
+    q, k = _small_case(500, 4, 2, 3)
+    prm = ref.Params(4, 2, head_dim=16)
+    ck64, ckb = ref.compress_keys(k, prm)
+    c64, cb = ref.coarse_kernels(ckb, rho)
+    fine = synth.bf16_bits_to_f32(ckb).astype(np.float64)
+    n_cc = c64.shape[1]
+    assert n_cc == (ckb.shape[1] - (2 * rho - 1)) // rho + 1
+    want = np.stack([fine[:, rho * c: rho * c + 2 * rho: 2].mean(axis=1) for c in range(n_cc)], axis=1)
+    assert np.array_equal(c64, want)
+    assert np.array_equal(cb, synth.f32_to_bf16_bits(want.astype(np.float32)))      # fp32 holds the mean of <= 4 bf16 exactly here
+    # and they track the plain mean of the raw keys over the same 32*rho tokens (up to the bf16
+    # rounding of the fine kernels)
+    kf = synth.bf16_bits_to_f32(k).astype(np.float64)
+    raw = np.stack([kf[:, 16 * rho * c: 16 * rho * c + 32 * rho].mean(axis=1) for c in range(n_cc)], axis=1)
+    assert np.abs(c64 - raw).max() < 2.0 ** -8
+
+
+def test_coarse_path_with_ratio_one_is_the_exact_path():
+    q, k = _small_case(400, 8, 2, 5)
+    prm = ref.Params(8, 2, head_dim=16, topk=5)
+    _, ckb = ref.compress_keys(k, prm)
+    pos = np.arange(400, dtype=np.int32)
+    r_exact = ref.kernel_scores(q, ckb, pos, prm)
+    r_coarse, lse = ref.kernel_scores(q, ckb, pos, prm, want_lse=True, coarse_path=True)
+    assert np.abs(r_exact - r_coarse).max() < 1e-14
+    a, _ = ref.select_blocks(q, ckb, pos, prm)
+    b, _ = ref.select_blocks(q, ckb, pos, prm, coarse_path=True)
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("rho", [2, 4])
+def test_coarse_scores_against_library_logsumexp(rho):
+    from scipy.special import logsumexp
+    l, Hq, Hkv, d = 333, 6, 2, 16
+    q, k = _small_case(l, Hq, Hkv, 7, d)
+    prm = ref.Params(Hq, Hkv, head_dim=d, lse_coarse_ratio=rho)
+    _, ckb = ref.compress_keys(k, prm)
+    _, ccb = ref.coarse_kernels(ckb, rho)
+    pos = np.array([31, 47, 63, 64, 127, 128, 200, 332], np.int32)
+    r, lse = ref.kernel_scores(q[pos], ckb, pos, prm, want_lse=True)
+    G = Hq // Hkv
+    qf = synth.bf16_bits_to_f32(q).astype(np.float64)
+    cf = synth.bf16_bits_to_f32(ckb).astype(np.float64)
+    ccf = synth.bf16_bits_to_f32(ccb).astype(np.float64)
+    for a, i in enumerate(pos):
+        n_vis = ref.num_kernels(i + 1, 32, 16)
+        n_vc = ref.num_coarse(n_vis, rho)
+        for h in range(Hkv):
+            want = np.zeros(n_vis)
+            for g in range(G):
+                zc = prm.softmax_scale * ccf[h, :n_vc] @ qf[i, h * G + g]
+                L = logsumexp(zc) + np.log(rho) if n_vc else 0.0
+                assert abs(lse[h, a, g] - L) < 1e-12
+                want += np.exp(prm.softmax_scale * cf[h, :n_vis] @ qf[i, h * G + g] - L)
+            want = np.clip(want / G, 2.0 ** -100, 2.0 ** 100)
+            assert np.allclose(r[h, a, :n_vis], want, rtol=1e-12, atol=0)
+            assert np.all(r[h, a, n_vis:] == 0)
+
+
+def test_coarse_lse_closed_form_and_clamps():
+    # zero queries: every logit is 0, so LSE_approx = log(rho * n_vis_c) and every score is its inverse
+    l, Hq, Hkv, d, rho = 300, 4, 1, 16, 4
+    q, k = _small_case(l, Hq, Hkv, 9, d)
+    q[:] = 0
+    prm = ref.Params(Hq, Hkv, head_dim=d, lse_coarse_ratio=rho)
+    _, ckb = ref.compress_keys(k, prm)
+    pos = np.array([127, 191, 299], np.int32)
+    r = ref.kernel_scores(q[pos], ckb, pos, prm)
+    for a, i in enumerate(pos):
+        n_vis = ref.num_kernels(i + 1, 32, 16)
+        assert np.allclose(r[0, a, :n_vis], 1.0 / (rho * ref.num_coarse(n_vis, rho)), rtol=1e-14)
+    # a key far outside the coarse average: the score exceeds 2^100 and is clamped there;
+    # a key far below: floored at 2^-100
+    kf = synth.bf16_bits_to_f32(k)
+    kf[0, 64:96] = 0
+    kf[0, 64:96, 0] = 3000.0                  # fine kernel 4 = tokens 64..95
+    kf[0, 128:160] = 0
+    kf[0, 128:160, 0] = -3000.0               # fine kernel 8
+    k2 = synth.f32_to_bf16_bits(kf)
+    q2 = synth.f32_to_bf16_bits(np.full((1, Hq, d), 0.0, np.float32))
+    q2f = synth.bf16_bits_to_f32(q2)
+    q2f[..., 0] = 1.0
+    q2 = synth.f32_to_bf16_bits(q2f)
+    _, ckb2 = ref.compress_keys(k2, prm)
+    r2 = ref.kernel_scores(q2, ckb2, np.array([299], np.int32), prm)
+    assert r2[0, 0, 4] == 2.0 ** 100 and r2[0, 0, 8] == 2.0 ** -100

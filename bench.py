@@ -70,7 +70,7 @@ def bench_prefill(args):
     log("[bench] generating %s inputs" % cfg.name)
     x = synth.make_prefill(cfg)
     l, Hq, Hkv, d, m = cfg.seqlen, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.block_size
-    prm = binding.Params(Hq, Hkv, topk=cfg.topk)
+    prm = binding.Params(Hq, Hkv, topk=cfg.topk, lse_coarse_ratio=args.lse_ratio)
 
     def dev(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
@@ -128,7 +128,16 @@ def bench_prefill(args):
     else:
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": None, "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": None, "traffic": None, "avg_launch_ms": kern_ms[dominant]}
+    overlap = None
+    if args.lse_ratio > 1:                        # how much of the exact selection the approximation keeps
+        exact = binding.select_blocks(binding.Params(Hq, Hkv, topk=cfg.topk), binding.MODE_PREFILL, q, ck, sl, l,
+                                      workspace=ws)
+        a, e = idx[0].reshape(-1, cfg.topk), exact[0].reshape(-1, cfg.topk)
+        hit = ((a[:, :, None] == e[:, None, :]) & (a[:, :, None] >= 0)).any(-1).sum().item()
+        overlap = hit / max(1, int((a >= 0).sum().item()))
+        del exact
     res = {
+        "selection_overlap_with_exact": overlap,
         "ms_per_step": ms_per_step, "value": value, "roofline": roofline,
         "kernels_ms": kern_ms, "attended_flops": attended_flops, "scoring_flops_per_pass": score_flops,
         "attn_only_tflops": attended_flops / (kern_ms["attn_prefill_kernel"] * 1e-3) / 1e12,
@@ -250,10 +259,10 @@ def measured_peaks():
                    "probe_stream_kernel: one coalesced read of a 2 GiB buffer"}
 
 
-def cpu_baseline(x, cfg, n_rows):
+def cpu_baseline(x, cfg, n_rows, lse_ratio=1):
     """The fp64 oracle, as it stands, on a stratified sample of query rows of the same workload."""
     from oracle import ref
-    oprm = ref.Params(cfg.n_q_heads, cfg.n_kv_heads, topk=cfg.topk)
+    oprm = ref.Params(cfg.n_q_heads, cfg.n_kv_heads, topk=cfg.topk, lse_coarse_ratio=lse_ratio)
     l = cfg.seqlen
     stride = max(1, l // n_rows)
     pos = np.arange(stride - 1, l, stride, dtype=np.int32)[:n_rows]
@@ -289,6 +298,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", choices=["prefill_32k", "prefill_128k"], default="prefill_32k",
                     help="prefill workload of the timed step (the headline metric is quoted on prefill_32k)")
+    ap.add_argument("--lse-ratio", type=int, default=1, choices=[1, 2, 4],
+                    help="prefill selection with the approximate log-sum-exp from coarse semantic kernels "
+                         "(ratio s_c/s); 1 = the exact two-pass selection the headline metric is quoted on")
     ap.add_argument("--decode-steps", type=int, default=1000)
     ap.add_argument("--ragged-steps", type=int, default=200)
     ap.add_argument("--no-decode", action="store_true")
@@ -327,7 +339,9 @@ def main():
                                "kernel 32/16, top-k %d (1 init + 2 local + %d scored), %d planted blocks/head"
                                % (cfg.name, cfg.seqlen, cfg.n_q_heads, cfg.n_kv_heads, cfg.topk, cfg.topk - 3,
                                   cfg.n_planted),
-                   "step": "compress_keys + select_blocks + sparse_attn_prefill"},
+                   "step": "compress_keys + select_blocks + sparse_attn_prefill",
+                   "lse": "exact" if args.lse_ratio <= 1 else "approximate, coarse kernels of ratio %d" % args.lse_ratio},
+        "selection_overlap_with_exact": res["selection_overlap_with_exact"],
         "frac_bf16_peak_whole_step": res["value"] / PEAK_BF16_TFLOPS,
         "attn_only_tflops": res["attn_only_tflops"],
         "frac_bf16_peak_attn_only": res["attn_only_tflops"] / PEAK_BF16_TFLOPS,
@@ -352,7 +366,8 @@ def main():
                 line["decode_ragged_b8"]["algorithmic_GBs"] / mp["hbm_read_GBs"])
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a sample")
-        line["cpu_baseline"] = cpu_baseline(x, cfg, args.cpu_rows if args.workload == "prefill_32k" else min(args.cpu_rows, 8192))
+        line["cpu_baseline"] = cpu_baseline(x, cfg, args.cpu_rows if args.workload == "prefill_32k" else min(args.cpu_rows, 8192),
+                                            args.lse_ratio)
     print(json.dumps(line), flush=True)
 
 

@@ -78,6 +78,15 @@ typedef struct infllmv2_params {
     int32_t n_init_blocks;   /* leading blocks whose relevance is set to infinity              */
     int32_t n_local_blocks;  /* trailing blocks (the query's own and the ones before it) forced */
     float softmax_scale;     /* multiplies q.k in both the relevance softmax and the attention */
+    int32_t lse_coarse_ratio; /* rho = s_c / s of the approximate log-sum-exp of the relevance softmax
+                                ("Efficient Top-K Implementation", last paragraph); 0 or 1 = exact.
+                                rho = 2 or 4: prefill selection only, G = 16, and
+                                (n_init_blocks + n_local_blocks) * m >= 2 * rho * s.  A coarse kernel is
+                                the bf16-rounded mean of the rho disjoint semantic kernels
+                                rho*c, rho*c+2, .., that tile tokens [rho*s*c, rho*s*(c+2)); the
+                                softmax denominator of a query head becomes
+                                rho * sum over visible coarse kernels of exp(scale q.CKc), and relevance
+                                scores are clamped to [2^-100, 2^100].  It changes which blocks win. */
 } infllmv2_params;
 
 /* A bf16 device tensor with a contiguous head_dim axis; strides in elements (see above). */

@@ -34,7 +34,8 @@ class CParams(ctypes.Structure):
                 ("n_kv_heads", ctypes.c_int32), ("block_size", ctypes.c_int32),
                 ("kernel_size", ctypes.c_int32), ("kernel_stride", ctypes.c_int32),
                 ("topk", ctypes.c_int32), ("n_init_blocks", ctypes.c_int32),
-                ("n_local_blocks", ctypes.c_int32), ("softmax_scale", ctypes.c_float)]
+                ("n_local_blocks", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("lse_coarse_ratio", ctypes.c_int32)]
 
 
 class CTensor(ctypes.Structure):
@@ -55,6 +56,7 @@ class Params:
     n_init_blocks: int = 1
     n_local_blocks: int = 2
     softmax_scale: float = None
+    lse_coarse_ratio: int = 1      # rho of the approximate log-sum-exp (prefill selection); 1 = exact
 
     def __post_init__(self):
         if self.softmax_scale is None:
@@ -63,7 +65,7 @@ class Params:
     def c(self):
         return CParams(self.head_dim, self.n_q_heads, self.n_kv_heads, self.block_size,
                        self.kernel_size, self.kernel_stride, self.topk, self.n_init_blocks,
-                       self.n_local_blocks, self.softmax_scale)
+                       self.n_local_blocks, self.softmax_scale, self.lse_coarse_ratio)
 
 
 class InfLLMv2Error(RuntimeError):

@@ -23,6 +23,14 @@ int32_t check_params(const infllmv2_params *p) {
     const int g = p->n_q_heads / p->n_kv_heads;
     if (!(g == 1 || g == 2 || g == 4 || g == 8 || g == 16)) return INFLLMV2_ERR_UNSUPPORTED;
     if (p->topk > kMaxTopk) return INFLLMV2_ERR_UNSUPPORTED;
+    if (p->lse_coarse_ratio < 0) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    if (p->lse_coarse_ratio > 1) {                       // approximate log-sum-exp
+        const int rho = p->lse_coarse_ratio;
+        if (!(rho == 2 || rho == 4) || g != 16) return INFLLMV2_ERR_UNSUPPORTED;
+        // a query that has candidate blocks must see at least one coarse kernel
+        if ((p->n_init_blocks + p->n_local_blocks) * p->block_size < 2 * rho * p->kernel_stride)
+            return INFLLMV2_ERR_UNSUPPORTED;
+    }
     return INFLLMV2_OK;
 }
 
@@ -51,6 +59,7 @@ Dims make_dims(const infllmv2_params *p, int32_t batch, int32_t max_seqlen) {
     d.batch = batch;
     d.max_seqlen = max_seqlen;
     d.scale_log2 = p->softmax_scale * kLog2e;
+    d.rho = p->lse_coarse_ratio > 1 ? p->lse_coarse_ratio : 1;
     return d;
 }
 
@@ -196,6 +205,7 @@ int32_t infllmv2_select_blocks(const infllmv2_params *prm, int32_t mode, const i
     RETURN_IF_ERR(check_tensor(ck));
     if (!seqlens || !block_idx) return INFLLMV2_ERR_INVALID_ARGUMENT;
     if (mode == INFLLMV2_MODE_DECODE && max_seqlen > kMaxDecodeSeqlen) return INFLLMV2_ERR_UNSUPPORTED;
+    if (mode == INFLLMV2_MODE_DECODE && prm->lse_coarse_ratio > 1) return INFLLMV2_ERR_UNSUPPORTED;
     const Dims dm = make_dims(prm, batch, max_seqlen);
     const size_t need = mode == INFLLMV2_MODE_PREFILL ? select_prefill_ws_bytes(dm) : select_decode_ws_bytes(dm);
     if (need > 0 && (!workspace || workspace_bytes < need ||

@@ -20,6 +20,7 @@ constexpr int kMaxTopk = 64;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kScoreFloor = 7.888609052210118e-31f;  // 2^-100, floor of a relevance score
+constexpr float kScoreCeil = 1.2676506002282294e30f;   // 2^100, ceiling (only the approximate LSE can reach it)
 
 // Host+device view of the call: everything a kernel needs besides its own buffers.
 struct Dims {
@@ -27,6 +28,7 @@ struct Dims {
     int32_t topk, n_init, n_local;
     int32_t batch, max_seqlen;
     float scale_log2;   // softmax_scale * log2(e)
+    int32_t rho;        // coarse / fine kernel stride of the approximate log-sum-exp; 1 = exact
 };
 
 struct Tensor {          // strides in elements
@@ -37,6 +39,26 @@ struct Tensor {          // strides in elements
 // Number of complete semantic kernels of a sequence of l tokens (p=32, s=16).
 __host__ __device__ inline int32_t num_kernels(int32_t l) {
     return l < kKernel ? 0 : (l - kKernel) / kStride + 1;
+}
+
+// Number of coarse kernels (ratio rho) all of whose fine kernels rho*c + 2r, r < rho, lie among the
+// first n fine kernels ("Efficient Top-K Implementation": coarse-grained semantic kernels).
+__host__ __device__ inline int32_t num_coarse(int32_t n, int32_t rho) {
+    return n < 2 * rho - 1 ? 0 : (n - (2 * rho - 1)) / rho + 1;
+}
+
+// fp64 -> bf16, round to nearest even with a single rounding: first round-to-odd to fp32
+// (24 bits keep a sticky bit), then nearest-even to 8 bits.
+__device__ inline uint16_t f64_to_bf16_rne(double x) {
+    float f = (float)x;
+    uint32_t u = __float_as_uint(f);
+    double fd = (double)f;
+    if (fd != x) {
+        if (fabs(fd) > fabs(x)) u -= 1u;   // back to the truncated magnitude
+        u |= 1u;                           // inexact: make the last bit odd
+    }
+    uint32_t r = u + 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(r >> 16);
 }
 
 // 16x16x32 bf16 MFMA, D = A*B + C.

@@ -5,20 +5,6 @@
 
 namespace infllmv2 {
 
-// fp64 -> bf16, round to nearest even with a single rounding: first round-to-odd to fp32
-// (24 bits keep a sticky bit), then nearest-even to 8 bits.
-__device__ inline uint16_t f64_to_bf16_rne(double x) {
-    float f = (float)x;
-    uint32_t u = __float_as_uint(f);
-    double fd = (double)f;
-    if (fd != x) {
-        if (fabs(fd) > fabs(x)) u -= 1u;   // back to the truncated magnitude
-        u |= 1u;                           // inexact: make the last bit odd
-    }
-    uint32_t r = u + 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(r >> 16);
-}
-
 // One thread = 8 channels of one semantic kernel; 16 threads cover a 128-wide row, so a
 // 256-thread workgroup produces 16 kernels.  The sum runs in fp64 in token order: for bf16
 // inputs it is exact, so the result is the correctly rounded mean.

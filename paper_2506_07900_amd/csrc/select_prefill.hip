@@ -224,7 +224,7 @@ __global__ __launch_bounds__(256) void select_score_kernel(Dims dm, Tensor q, Te
                     const int tloc = wave * C::kTokPerWave + mt * C::kTokPerTile + (4 * g + tl * RL) / G;
                     const bool writer = ((4 * g + tl * RL) % G) == 0;
                     if (writer) {
-                        float r = fmaxf(vsum * (1.f / G), kScoreFloor);
+                        float r = fminf(fmaxf(vsum * (1.f / G), kScoreFloor), kScoreCeil);
                         if (jh >= n_visible(t0 + tloc)) r = -INFINITY;
                         rs[tloc][1 + 16 * nt + n] = r;
                     }

@@ -23,6 +23,11 @@ constexpr float kRescaleSlack = 60.f;  // pass 1 re-bases its exponent only when
                                        // reference by 2^60: sums stay far from fp32 overflow
 
 __device__ inline int n_visible16(int i) { return num_kernels(i + 1); }
+// kernels of pass 1: the fine ones, or the coarse ones of the approximate log-sum-exp
+__device__ inline int n_visible_lse(int i, int rho) {
+    const int nf = num_kernels(i + 1);
+    return rho > 1 ? num_coarse(nf, rho) : nf;
+}
 
 // DPP helpers on floats (row = 16 lanes).  Lanes whose source falls outside the row keep `old`.
 template <int kCtrl>
@@ -47,6 +52,40 @@ __global__ __launch_bounds__(256) void pack_ck_kernel(Dims dm, Tensor ck, const 
     if (16 * t + n < n_c)
         x = *reinterpret_cast<const uint4 *>(ck.ptr + b * ck.sb + h * ck.sh + (int64_t)(16 * t + n) * ck.st +
                                              32 * ks + 8 * g);
+    ckp[(((int64_t)b * dm.Hkv + h) * nt_cap + t) * 256 + c] = x;
+}
+
+// Coarse kernels of the approximate log-sum-exp ("Efficient Top-K Implementation", last
+// paragraph), built from the fine representations and stored fragment-major like them:
+// CKc[c] = bf16(mean_r CK[rho*c + 2r]), r < rho.  The sum of rho bf16 values is exact in fp64, so
+// the result is the correctly rounded mean.
+__global__ __launch_bounds__(256) void pack_ck_coarse_kernel(Dims dm, Tensor ck, const int32_t *__restrict__ seqlens,
+                                                              uint4 *__restrict__ ckp, int32_t nt_cap) {
+    const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    int32_t L = seqlens[b];
+    L = L < 0 ? 0 : (L > dm.max_seqlen ? dm.max_seqlen : L);
+    const int n_cc = num_coarse(num_kernels(L), dm.rho);
+    if (16 * t >= n_cc) return;
+    const int c = threadIdx.x, ks = c >> 6, lane = c & 63, n = lane & 15, g = lane >> 4;
+    uint4 x = {0u, 0u, 0u, 0u};
+    const int cc = 16 * t + n;
+    if (cc < n_cc) {
+        double acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.0;
+        for (int r = 0; r < dm.rho; ++r) {
+            const bf16x8 v = load8(ck.ptr + b * ck.sb + h * ck.sh + (int64_t)(dm.rho * cc + 2 * r) * ck.st +
+                                   32 * ks + 8 * g);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += (double)(float)v[e];
+        }
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            w[e] = (uint32_t)f64_to_bf16_rne(acc[2 * e] / (double)dm.rho) |
+                   ((uint32_t)f64_to_bf16_rne(acc[2 * e + 1] / (double)dm.rho) << 16);
+        x = uint4{w[0], w[1], w[2], w[3]};
+    }
     ckp[(((int64_t)b * dm.Hkv + h) * nt_cap + t) * 256 + c] = x;
 }
 
@@ -125,7 +164,7 @@ __global__ __launch_bounds__(256, 2) void select_lse16_kernel(Dims dm, Tensor q,
         s_run[mt] = 0.f;
     }
     const int last_tok = min(t0 + kMT, (int)L) - 1;
-    const int nvis_hi = n_visible16(last_tok), nvis_lo = n_visible16(t0);
+    const int nvis_hi = n_visible_lse(last_tok, dm.rho), nvis_lo = n_visible_lse(t0, dm.rho);
     const int nt_full = nvis_lo >> 4;                    // tiles wholly visible to every token here
     const int nt_all = (nvis_hi + 15) >> 4;
     const uint4 *ckp_head = ckp + ((int64_t)b * dm.Hkv + h) * nt_cap * 256;
@@ -196,7 +235,7 @@ __global__ __launch_bounds__(256, 2) void select_lse16_kernel(Dims dm, Tensor q,
             mfma_half<true>(fr, qf, half * kHalf, zA);
 #pragma unroll
             for (int u = 0; u < kHalf; ++u) {
-                const int nv = n_visible16(t0 + half * kHalf + u);
+                const int nv = n_visible_lse(t0 + half * kHalf + u, dm.rho);
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     if (16 * t + 4 * g + j >= nv) zA[u][j] = -INFINITY;
@@ -211,7 +250,11 @@ __global__ __launch_bounds__(256, 2) void select_lse16_kernel(Dims dm, Tensor q,
         const float m_use = M == -INFINITY ? 0.f : M;
         const float S = xgroup_sum(s_run[mt] * fast_exp2(m_lane - m_use));
         const int tok = t0 + mt;
-        if (g == 0 && tok < L) lse2[((int64_t)b * dm.max_seqlen + tok) * dm.Hq + h * 16 + n] = M + fast_log2(S);
+        float lse = M + fast_log2(S);
+        // approximate mode: rho times fewer kernels were summed (log2 rho is an integer); a query
+        // that sees no coarse kernel yet gets 0 (it has no candidate blocks to rank)
+        if (dm.rho > 1) lse = M == -INFINITY ? 0.f : lse + (float)(31 - __clz(dm.rho));
+        if (g == 0 && tok < L) lse2[((int64_t)b * dm.max_seqlen + tok) * dm.Hq + h * 16 + n] = lse;
     }
 }
 
@@ -289,7 +332,7 @@ __global__ __launch_bounds__(256, 2) void select_score16_kernel(Dims dm, Tensor 
         const float s23 = __uint_as_float(p23[0]) + __uint_as_float(p23[1]);
         const v2u pq = __builtin_amdgcn_permlane32_swap(__float_as_uint(s01), __float_as_uint(s23), false, false);
         float v = __uint_as_float(pq[0]) + __uint_as_float(pq[1]);
-        v = fmaxf(v * (1.f / 16.f), kScoreFloor);
+        v = fminf(fmaxf(v * (1.f / 16.f), kScoreFloor), kScoreCeil);
         if (t >= nt_pipe && 16 * t + n >= nvis_tok[i]) v = -INFINITY;         // kernel not visible to this token
         const float a = fmaxf(v, dpp_f32<kRowShl1>(v, v));
         const float bq = fmaxf(a, dpp_f32<kRowShl2>(a, a));
@@ -326,13 +369,21 @@ __global__ __launch_bounds__(256, 2) void select_score16_kernel(Dims dm, Tensor 
     finish(zB, 1, nt_all - 1);
 }
 
+static int32_t coarse_tiles_cap(const Dims &dm) {
+    return dm.rho > 1 ? (num_coarse(num_kernels(dm.max_seqlen), dm.rho) + 15) / 16 : 0;
+}
+static size_t coarse_tiles_bytes(const Dims &dm) {
+    const size_t b = (size_t)dm.batch * dm.Hkv * coarse_tiles_cap(dm) * 256 * sizeof(uint4);
+    return (b + 255) / 256 * 256;
+}
+
 size_t select_prefill16_ws_bytes(const Dims &dm) {
     size_t lse = (size_t)dm.batch * dm.max_seqlen * dm.Hq * sizeof(float);
     lse = (lse + 255) / 256 * 256;
     const size_t nt_cap = ((size_t)num_kernels(dm.max_seqlen) + 15) / 16;
     size_t ckp = (size_t)dm.batch * dm.Hkv * nt_cap * 256 * sizeof(uint4);
     ckp = (ckp + 255) / 256 * 256;
-    return lse + ckp + select_scores_bytes(dm);
+    return lse + ckp + coarse_tiles_bytes(dm) + select_scores_bytes(dm);
 }
 
 int launch_select_prefill16(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens, int32_t *block_idx,
@@ -344,7 +395,9 @@ int launch_select_prefill16(const Dims &dm, Tensor q, Tensor ck, const int32_t *
     ckp_bytes = (ckp_bytes + 255) / 256 * 256;
     float *lse2 = reinterpret_cast<float *>(ws);
     uint4 *ckp = reinterpret_cast<uint4 *>(reinterpret_cast<char *>(ws) + lse_bytes);
-    float *R = reinterpret_cast<float *>(reinterpret_cast<char *>(ws) + lse_bytes + ckp_bytes);
+    uint4 *ckp_c = reinterpret_cast<uint4 *>(reinterpret_cast<char *>(ws) + lse_bytes + ckp_bytes);
+    const int32_t ntc_cap = coarse_tiles_cap(dm);
+    float *R = reinterpret_cast<float *>(reinterpret_cast<char *>(ws) + lse_bytes + ckp_bytes + coarse_tiles_bytes(dm));
     const int32_t nb_cap = select_scores_pitch(dm);
     const int32_t n_tiles = (dm.max_seqlen + kTokPerWg16 - 1) / kTokPerWg16;
     const int64_t n_wg = (int64_t)n_tiles * dm.Hkv * dm.batch;
@@ -354,9 +407,15 @@ int launch_select_prefill16(const Dims &dm, Tensor q, Tensor ck, const int32_t *
         hipLaunchKernelGGL(pack_ck_kernel, dim3(nt_cap, dm.Hkv, dm.batch), dim3(256), 0, stream, dm, ck, seqlens,
                            ckp, nt_cap);
         timing_end(stream);
+        if (dm.rho > 1 && ntc_cap > 0) {                 // pass 1 runs over the coarse kernels
+            timing_begin("pack_ck_coarse_kernel", stream);
+            hipLaunchKernelGGL(pack_ck_coarse_kernel, dim3(ntc_cap, dm.Hkv, dm.batch), dim3(256), 0, stream, dm, ck,
+                               seqlens, ckp_c, ntc_cap);
+            timing_end(stream);
+        }
         timing_begin("select_lse16_kernel", stream);
-        hipLaunchKernelGGL(select_lse16_kernel, dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, ckp, nt_cap,
-                           seqlens, lse2, n_tiles);
+        hipLaunchKernelGGL(select_lse16_kernel, dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q,
+                           dm.rho > 1 ? ckp_c : ckp, dm.rho > 1 ? ntc_cap : nt_cap, seqlens, lse2, n_tiles);
         timing_end(stream);
         timing_begin("select_score16_kernel", stream);
         hipLaunchKernelGGL(select_score16_kernel, dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, ckp, nt_cap,

@@ -30,7 +30,7 @@ def test_header_symbols_are_exported(lib):
 
 
 def test_struct_layout_matches_header():
-    assert ctypes.sizeof(CParams) == 40 and ctypes.sizeof(CTensor) == 32
+    assert ctypes.sizeof(CParams) == 44 and ctypes.sizeof(CTensor) == 32      # 10 int32 + 1 float; 1 pointer + 3 int64
 
 
 def good_params(**kw):
@@ -71,6 +71,13 @@ def test_parameter_validation(lib):
     assert call_compress(lib, good_params(kernel_size=16)) == UNSUPPORTED
     assert call_compress(lib, good_params(n_q_heads=64, n_kv_heads=2)) == UNSUPPORTED  # G = 32
     assert call_compress(lib, good_params(topk=65)) == UNSUPPORTED
+    # approximate log-sum-exp: ratios 2 and 4, G = 16, and a visible coarse kernel for every query
+    # that has candidate blocks
+    assert call_compress(lib, good_params(lse_coarse_ratio=-1)) == INVALID
+    assert call_compress(lib, good_params(lse_coarse_ratio=3)) == UNSUPPORTED
+    assert call_compress(lib, good_params(lse_coarse_ratio=8)) == UNSUPPORTED
+    assert call_compress(lib, good_params(lse_coarse_ratio=2, n_q_heads=16, n_kv_heads=2)) == UNSUPPORTED   # G = 8
+    assert call_compress(lib, good_params(lse_coarse_ratio=4, n_init_blocks=0, n_local_blocks=1, topk=4)) == UNSUPPORTED
     assert call_compress(lib, good_params(), seqlens=None) == INVALID
     assert call_compress(lib, good_params(), k=tensor(ptr=None)) == INVALID
     assert call_compress(lib, good_params(), k=tensor(ptr=FAKE + 2)) == INVALID        # misaligned

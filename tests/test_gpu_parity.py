@@ -151,6 +151,45 @@ def test_sparse_attn_prefill(seqlens, Hq, Hkv, topk, planted):
         assert np.all(o[b, l:] == 3.0) and np.all(ls[b, l:] == 5.0)     # padding rows untouched
 
 
+@pytest.mark.parametrize("rho", [2, 4])
+@pytest.mark.parametrize("seqlens,Hq,Hkv,topk,planted,heavy", [([1077, 333], 32, 2, 16, 6, ()),
+                                                               ([2500], 16, 1, 8, 5, ()),
+                                                               ([1900, 130, 127, 64], 32, 2, 6, 3, (0,))])
+def test_select_blocks_prefill_approximate_lse(seqlens, Hq, Hkv, topk, planted, heavy, rho):
+    # the approximate log-sum-exp from coarse semantic kernels: same parity bar against the
+    # oracle's definition of it; the recall against the exact selection is printed
+    print("case approximate lse", seqlens, Hq, Hkv, topk, "rho", rho, flush=True)
+    prm = binding.Params(Hq, Hkv, topk=topk, lse_coarse_ratio=rho)
+    oprm = oracle_params(prm)
+    exact = binding.Params(Hq, Hkv, topk=topk)
+    q, k, v, T = make_batch(51, seqlens, Hq, Hkv, n_planted=planted, heavy=heavy)
+    qd, kd, sl = to_dev(q), to_dev(k), dev_i32(seqlens)
+    ck = binding.compress_keys(prm, kd, sl, T)
+    idx = binding.select_blocks(prm, binding.MODE_PREFILL, qd, ck, sl, T).cpu().numpy()
+    idx_exact = binding.select_blocks(exact, binding.MODE_PREFILL, qd, ck, sl, T).cpu().numpy()
+    ckb = to_bits(ck)
+    tot = ex = near = 0
+    same = picks = 0
+    for b, l in enumerate(seqlens):
+        n_c = ref.num_kernels(l, 32, 16)
+        pos = np.arange(l, dtype=np.int32)
+        want, margins, R = ref.select_blocks(q[b, :l], ckb[b, :, :n_c], pos, oprm, want_scores=True)
+        n, e, nt, hard = compare_selection(idx[b, :, :l], want, margins, R)
+        assert not hard, hard[:3]
+        tot, ex, near = tot + n, ex + e, near + nt
+        for h in range(Hkv):
+            for t in range(l):
+                a = set(idx[b, h, t].tolist()) - {-1}
+                same += len(a & (set(idx_exact[b, h, t].tolist()) - {-1}))
+                picks += len(a)
+    print("rows %d exact %d near-tie %d; blocks shared with the exact selection: %.4f" %
+          (tot, ex, near, same / max(1, picks)), flush=True)
+    assert near <= max(2, tot // 100)
+    assert same / max(1, picks) > 0.9
+    with pytest.raises(binding.InfLLMv2Error):          # decode keeps the exact log-sum-exp only
+        binding.select_blocks(prm, binding.MODE_DECODE, qd[:, :1], ck, sl, T)
+
+
 def test_exact_ties_go_to_the_lower_block_index():
     # zero queries: every visible kernel gets the same probability, so every block score of a
     # row is the same number on both sides; the selection is decided by the tie rule alone

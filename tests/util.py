@@ -37,7 +37,7 @@ def to_bits(t):
 def oracle_params(prm):
     return ref.Params(prm.n_q_heads, prm.n_kv_heads, prm.head_dim, prm.block_size, prm.kernel_size,
                       prm.kernel_stride, prm.topk, prm.n_init_blocks, prm.n_local_blocks,
-                      prm.softmax_scale)
+                      prm.softmax_scale, prm.lse_coarse_ratio)
 
 
 def compare_selection(idx_gpu, idx_ref, margins, R):

@@ -21,12 +21,12 @@ def sample_rows(l, n_random, seed):
     return np.array(sorted(rows), np.int32)
 
 
-def run_prefill_config(cfg_index, n_random):
+def run_prefill_config(cfg_index, n_random, rho=1):
     cfg = synth.CONFIGS[cfg_index]
     print("workload", cfg.name, flush=True)
     x = synth.make_prefill(cfg)
     l, Hq, Hkv = cfg.seqlen, cfg.n_q_heads, cfg.n_kv_heads
-    prm = binding.Params(Hq, Hkv, topk=cfg.topk)
+    prm = binding.Params(Hq, Hkv, topk=cfg.topk, lse_coarse_ratio=rho)
     oprm = oracle_params(prm)
     q, k, v = to_dev(x.q)[None], to_dev(x.k)[None], to_dev(x.v)[None]
     sl = torch.tensor([l], dtype=torch.int32, device="cuda")
@@ -85,6 +85,12 @@ def run_prefill_config(cfg_index, n_random):
 @pytest.mark.timeout(300)
 def test_prefill_32k_sampled_rows():
     run_prefill_config(1, 150)
+
+
+@pytest.mark.timeout(300)
+def test_prefill_32k_sampled_rows_approximate_lse():
+    # selection with the approximate log-sum-exp (coarse kernels of ratio 4) at the stated size
+    run_prefill_config(1, 100, rho=4)
 
 
 @pytest.mark.timeout(600)

@@ -80,7 +80,7 @@ typedef struct infllmv2_params {
     float softmax_scale;     /* multiplies q.k in both the relevance softmax and the attention */
     int32_t lse_coarse_ratio; /* rho = s_c / s of the approximate log-sum-exp of the relevance softmax
                                 ("Efficient Top-K Implementation", last paragraph); 0 or 1 = exact.
-                                rho = 2 or 4: prefill selection only, G = 16, and
+                                rho = 2 or 4 needs G = 16 and
                                 (n_init_blocks + n_local_blocks) * m >= 2 * rho * s.  A coarse kernel is
                                 the bf16-rounded mean of the rho disjoint semantic kernels
                                 rho*c, rho*c+2, .., that tile tokens [rho*s*c, rho*s*(c+2)); the

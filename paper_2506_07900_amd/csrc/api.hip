@@ -205,7 +205,6 @@ int32_t infllmv2_select_blocks(const infllmv2_params *prm, int32_t mode, const i
     RETURN_IF_ERR(check_tensor(ck));
     if (!seqlens || !block_idx) return INFLLMV2_ERR_INVALID_ARGUMENT;
     if (mode == INFLLMV2_MODE_DECODE && max_seqlen > kMaxDecodeSeqlen) return INFLLMV2_ERR_UNSUPPORTED;
-    if (mode == INFLLMV2_MODE_DECODE && prm->lse_coarse_ratio > 1) return INFLLMV2_ERR_UNSUPPORTED;
     const Dims dm = make_dims(prm, batch, max_seqlen);
     const size_t need = mode == INFLLMV2_MODE_PREFILL ? select_prefill_ws_bytes(dm) : select_decode_ws_bytes(dm);
     if (need > 0 && (!workspace || workspace_bytes < need ||

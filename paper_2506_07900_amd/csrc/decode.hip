@@ -27,9 +27,11 @@ __device__ inline int clamp_len(int32_t L, int32_t cap) { return L < 0 ? 0 : (L 
 __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, Tensor ck,
                                                              const int32_t *__restrict__ seqlens,
                                                              float *__restrict__ zbuf,
-                                                             float2 *__restrict__ part, int32_t n_c_cap,
+                                                             float2 *__restrict__ part,
+                                                             float2 *__restrict__ part_c, int32_t n_c_cap,
                                                              int32_t n_part) {
     __shared__ float2 wpart[4][16];
+    __shared__ float2 wpart_c[2][16];
     const int b = blockIdx.z, h = blockIdx.y;
     const int L = clamp_len(seqlens[b], dm.max_seqlen);
     const int n_vis = num_kernels(L);                 // the query sits at L-1: n_c((L-1)+1)
@@ -81,6 +83,65 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, T
         for (int w = 0; w < 4; ++w) S += wpart[w][threadIdx.x].y * fast_exp2(wpart[w][threadIdx.x].x - mu);
         part[(((int64_t)b * dm.Hkv + h) * G + threadIdx.x) * n_part + blockIdx.x] = float2{M, S};
     }
+    // Approximate log-sum-exp ("Efficient Top-K Implementation", last paragraph): the same
+    // partial (max, sum) over the coarse kernels 64/rho * bx .. of this chunk, each the bf16 mean
+    // of its rho fine kernels rho*c + 2r (exact sum in fp64, one rounding).
+    if (dm.rho > 1) {                                 // uniform over the launch
+        const int tiles_c = 4 / dm.rho;               // 16-kernel tiles of coarse kernels per workgroup
+        const int n_vis_c = num_coarse(n_vis, dm.rho);
+        if (wave < tiles_c) {
+            const int c0 = blockIdx.x * (64 / dm.rho) + wave * 16, cc = c0 + n;
+            bf16x8 ac[4];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                ac[ks] = zero8();
+                if (cc < n_vis_c) {
+                    double acc[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[e] = 0.0;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        if (r >= dm.rho) break;
+                        const bf16x8 v = load8(ck.ptr + b * ck.sb + h * ck.sh +
+                                               (int64_t)(dm.rho * cc + 2 * r) * ck.st + 32 * ks + 8 * g);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) acc[e] += (double)(float)v[e];
+                    }
+                    uint32_t w[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        w[e] = (uint32_t)f64_to_bf16_rne(acc[2 * e] / (double)dm.rho) |
+                               ((uint32_t)f64_to_bf16_rne(acc[2 * e + 1] / (double)dm.rho) << 16);
+                    ac[ks] = __builtin_bit_cast(bf16x8, uint4{w[0], w[1], w[2], w[3]});
+                }
+            }
+            f32x4 zc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) zc = mfma16(ac[ks], bq[ks], zc);
+            float mc = -INFINITY, xc[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                xc[j] = c0 + 4 * g + j < n_vis_c ? zc[j] * dm.scale_log2 : -INFINITY;
+                mc = fmaxf(mc, xc[j]);
+            }
+            mc = xgroup_max(mc);
+            const float mcu = mc == -INFINITY ? 0.f : mc;
+            float sc = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sc += fast_exp2(xc[j] - mcu);
+            sc = xgroup_sum(sc);
+            if (g == 0) wpart_c[wave][n] = float2{mc, sc};
+        }
+        __syncthreads();
+        if (threadIdx.x < 16 && (int)threadIdx.x < G) {
+            float M = -INFINITY;
+            for (int w = 0; w < tiles_c; ++w) M = fmaxf(M, wpart_c[w][threadIdx.x].x);
+            const float mu = M == -INFINITY ? 0.f : M;
+            float S = 0.f;
+            for (int w = 0; w < tiles_c; ++w) S += wpart_c[w][threadIdx.x].y * fast_exp2(wpart_c[w][threadIdx.x].x - mu);
+            part_c[(((int64_t)b * dm.Hkv + h) * G + threadIdx.x) * n_part + blockIdx.x] = float2{M, S};
+        }
+    }
 }
 
 // ---- selection, part 2 ------------------------------------------------------------------------
@@ -123,7 +184,9 @@ __global__ __launch_bounds__(320) void decode_scores_kernel(Dims dm, const int32
         for (int i = 0; i < kMaxParts / 16; ++i) s += v[i].y * fast_exp2(v[i].x - mu);
 #pragma unroll
         for (int o = 1; o < 16; o <<= 1) s += __shfl_xor(s, o);
-        if (sub == 0) lse_h[head] = m + fast_log2(s);
+        if (sub == 0)      // approximate mode: rho times fewer kernels were summed; 0 when none is visible
+            lse_h[head] = dm.rho > 1 ? (m == -INFINITY ? 0.f : m + fast_log2(s) + (float)(31 - __clz(dm.rho)))
+                                     : m + fast_log2(s);
     }
     // logits of this thread's kernel, all heads (independent loads, in flight during the reduction)
     const int jh = base - 1 + tid;
@@ -140,7 +203,7 @@ __global__ __launch_bounds__(320) void decode_scores_kernel(Dims dm, const int32
 #pragma unroll
         for (int gq = 0; gq < 16; ++gq)
             if (gq < G) acc += fast_exp2(zz[gq] - lse_h[gq]);
-        rs[tid] = have ? fmaxf(acc * (1.f / G), kScoreFloor) : -INFINITY;
+        rs[tid] = have ? fminf(fmaxf(acc * (1.f / G), kScoreFloor), kScoreCeil) : -INFINITY;
     }
     __syncthreads();
     if (tid < 64) {
@@ -441,7 +504,7 @@ static DecodeSelLayout decode_sel_layout(const Dims &dm) {
 
 size_t select_decode_ws_bytes(const Dims &dm) {
     DecodeSelLayout l = decode_sel_layout(dm);
-    return l.z_bytes + l.part_bytes + l.r_bytes;
+    return l.z_bytes + 2 * l.part_bytes + l.r_bytes;
 }
 
 int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
@@ -451,14 +514,15 @@ int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seq
     if (l.n_part > kMaxParts) return (int)hipErrorInvalidValue;      // rejected earlier by the C ABI
     float *zbuf = reinterpret_cast<float *>(ws);
     float2 *part = reinterpret_cast<float2 *>(reinterpret_cast<char *>(ws) + l.z_bytes);
-    float *R = reinterpret_cast<float *>(reinterpret_cast<char *>(ws) + l.z_bytes + l.part_bytes);
+    float2 *part_c = reinterpret_cast<float2 *>(reinterpret_cast<char *>(ws) + l.z_bytes + l.part_bytes);
+    float *R = reinterpret_cast<float *>(reinterpret_cast<char *>(ws) + l.z_bytes + 2 * l.part_bytes);
     timing_begin("decode_logits_kernel", stream);
     hipLaunchKernelGGL(decode_logits_kernel, dim3(l.n_c_cap / 64, dm.Hkv, dm.batch), dim3(256), 0,
-                       stream, dm, q, ck, seqlens, zbuf, part, l.n_c_cap, l.n_part);
+                       stream, dm, q, ck, seqlens, zbuf, part, part_c, l.n_c_cap, l.n_part);
     timing_end(stream);
     timing_begin("decode_scores_kernel", stream);
     hipLaunchKernelGGL(decode_scores_kernel, dim3(l.n_c_cap / 256, dm.Hkv, dm.batch), dim3(320), 0, stream,
-                       dm, seqlens, zbuf, part, l.n_c_cap, l.n_part, R, l.nb_cap);
+                       dm, seqlens, zbuf, dm.rho > 1 ? part_c : part, l.n_c_cap, l.n_part, R, l.nb_cap);
     timing_end(stream);
     const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
     if (n_blocks > kPickThreads * kPickMaxVPT) return (int)hipErrorInvalidValue;   // rejected earlier by the C ABI

@@ -186,8 +186,12 @@ def test_select_blocks_prefill_approximate_lse(seqlens, Hq, Hkv, topk, planted, 
           (tot, ex, near, same / max(1, picks)), flush=True)
     assert near <= max(2, tot // 100)
     assert same / max(1, picks) > 0.9
-    with pytest.raises(binding.InfLLMv2Error):          # decode keeps the exact log-sum-exp only
-        binding.select_blocks(prm, binding.MODE_DECODE, qd[:, :1], ck, sl, T)
+    # decode with the same approximation: the row of the last token, bit for bit
+    last = [max(l - 1, 0) for l in seqlens]
+    q1 = np.stack([q[b, last[b]] for b in range(len(seqlens))])[:, None]
+    idx_dec = binding.select_blocks(prm, binding.MODE_DECODE, to_dev(q1), ck, sl, T).cpu().numpy()
+    for b, l in enumerate(seqlens):
+        assert np.array_equal(idx_dec[b, :, 0], idx[b, :, l - 1]), b
 
 
 def test_exact_ties_go_to_the_lower_block_index():

@@ -40,6 +40,13 @@
  *     rho times fewer coarse kernels); 0 when no coarse kernel is visible (no selection
  *     depends on it when (n_init + n_local) * m >= 2 * s_c);
  *   - scores exp(z - LSE_approx) are no longer bounded by 1: they are clamped above at 2^100.
+ * Reading for tree-style draft verification (section 4.1, "InfLLM v2 for Target Model"; the
+ * report says only that the local mask of the last n x n region is bit-packed in uint64 --
+ * parity unpinned for the reading, the arithmetic is pinned):
+ *   - the n <= 64 drafted tokens are already in the cache at positions l_ctx .. l_ctx+n-1 in
+ *     draft order; draft token t selects blocks as a query at position l_ctx+t would (the
+ *     selection does not look at the tree); only the attention's causal test inside the last
+ *     n x n region is replaced by "bit j of tree_mask[t]".
  */
 #include <math.h>
 #include <stdint.h>
@@ -389,10 +396,11 @@ void oracle_select_blocks_coarse(const uint16_t *q_bits, const uint16_t *ck_bits
  *   block_idx  [Hkv, Tq, topk], -1 entries ignored
  *   out        [Tq, Hq, d] fp64,  lse [Tq, Hq] fp64 (natural log)
  *   probs_sum  [Tq, Hq] fp64 (may be NULL): sum of the softmax weights, for the row-sum pin */
-void oracle_sparse_attn(const uint16_t *q_bits, const uint16_t *k_bits, const uint16_t *v_bits,
+static void attend_rows(const uint16_t *q_bits, const uint16_t *k_bits, const uint16_t *v_bits,
                         const int32_t *pos, const int32_t *block_idx, int32_t Tq, int32_t Hq,
                         int32_t Hkv, int32_t d, int32_t l, int32_t m, int32_t topk, double scale,
-                        double *out, double *lse, double *probs_sum) {
+                        double *out, double *lse, double *probs_sum, int32_t l_ctx,
+                        const uint64_t *tree_mask) {
     int32_t G = Hq / Hkv;
 #pragma omp parallel
     {
@@ -408,8 +416,13 @@ void oracle_sparse_attn(const uint16_t *q_bits, const uint16_t *k_bits, const ui
                 int32_t n = 0;
                 for (int32_t c = 0; c < topk; ++c) {
                     if (sel[c] < 0) continue;
-                    for (int32_t u = sel[c] * m; u < (sel[c] + 1) * m; ++u)
-                        if (u <= i && u < l) tok[n++] = u;      /* causal, inside the cache */
+                    for (int32_t u = sel[c] * m; u < (sel[c] + 1) * m; ++u) {
+                        int allowed;
+                        if (!tree_mask) allowed = u <= i;       /* causal */
+                        else allowed = u < l_ctx ||             /* context, or a draft token the mask lets through */
+                                       (u - l_ctx < 64 && ((tree_mask[t] >> (u - l_ctx)) & 1u));
+                        if (allowed && u < l) tok[n++] = u;     /* inside the cache */
+                    }
                 }
                 double zmax = -INFINITY;
                 for (int32_t a = 0; a < n; ++a) {
@@ -435,6 +448,31 @@ void oracle_sparse_attn(const uint16_t *q_bits, const uint16_t *k_bits, const ui
             }
         free(z); free(tok);
     }
+}
+
+void oracle_sparse_attn(const uint16_t *q_bits, const uint16_t *k_bits, const uint16_t *v_bits,
+                        const int32_t *pos, const int32_t *block_idx, int32_t Tq, int32_t Hq,
+                        int32_t Hkv, int32_t d, int32_t l, int32_t m, int32_t topk, double scale,
+                        double *out, double *lse, double *probs_sum) {
+    attend_rows(q_bits, k_bits, v_bits, pos, block_idx, Tq, Hq, Hkv, d, l, m, topk, scale, out, lse,
+                probs_sum, 0, NULL);
+}
+
+/* Tree-style draft verification (section 4.1, "InfLLM v2 for Target Model"): the Tq = n <= 64
+ * drafted tokens occupy cache positions l_ctx .. l_ctx+n-1, query t is draft token t, and inside
+ * that last n x n region the causal triangle is replaced by a mask: query t attends draft token j
+ * iff bit j of tree_mask[t] is set.  Context tokens (< l_ctx) of the selected blocks are always
+ * attended.  Everything else (block selection per token by position, scale, LSE) is unchanged;
+ * a lower-triangular mask gives back oracle_sparse_attn. */
+void oracle_sparse_attn_tree(const uint16_t *q_bits, const uint16_t *k_bits, const uint16_t *v_bits,
+                             const int32_t *block_idx, const uint64_t *tree_mask, int32_t n, int32_t l_ctx,
+                             int32_t Hq, int32_t Hkv, int32_t d, int32_t l, int32_t m, int32_t topk,
+                             double scale, double *out, double *lse) {
+    int32_t *pos = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    for (int32_t t = 0; t < n; ++t) pos[t] = l_ctx + t;
+    attend_rows(q_bits, k_bits, v_bits, pos, block_idx, n, Hq, Hkv, d, l, m, topk, scale, out, lse, NULL,
+                l_ctx, tree_mask);
+    free(pos);
 }
 
 /* Rounding helper exported for tests of the bf16 conversion itself. */

@@ -57,6 +57,8 @@ def _load():
         lib.oracle_select_blocks_coarse.argtypes = [vp, vp, vp, vp] + [i32] * 13 + [f64, vp, vp, vp, i32]
         lib.oracle_sparse_attn.restype = None
         lib.oracle_sparse_attn.argtypes = [vp, vp, vp, vp, vp] + [i32] * 7 + [f64, vp, vp, vp]
+        lib.oracle_sparse_attn_tree.restype = None
+        lib.oracle_sparse_attn_tree.argtypes = [vp, vp, vp, vp, vp] + [i32] * 8 + [f64, vp, vp]
         lib.oracle_f64_to_bf16.restype = ctypes.c_uint16
         lib.oracle_f64_to_bf16.argtypes = [f64]
         lib.oracle_bf16_to_f64.restype = f64
@@ -214,3 +216,25 @@ def sparse_attn(q, k, v, pos, block_idx, prm, want_probs_sum=False):
                            l, prm.block_size, topk, float(prm.softmax_scale),
                            _ptr(out), _ptr(lse), _ptr(ps))
     return (out, lse, ps) if want_probs_sum else (out, lse)
+
+
+def sparse_attn_tree(q, k, v, block_idx, tree_mask, l_ctx, prm):
+    """Tree-style draft verification: q uint16 [n, Hq, d] are the n <= 64 drafted tokens at cache
+    positions l_ctx .. l_ctx+n-1, tree_mask uint64 [n] (bit j of word t: query t attends draft j),
+    block_idx int32 [Hkv, n, topk] -> out fp64 [n, Hq, d], lse fp64 [n, Hq]."""
+    lib = _load()
+    q = _u16(q)
+    k = _u16(k)
+    v = _u16(v)
+    block_idx = np.ascontiguousarray(block_idx, np.int32)
+    tree_mask = np.ascontiguousarray(tree_mask, np.uint64)
+    n, Hq, d = q.shape
+    Hkv, l, _ = k.shape
+    topk = block_idx.shape[-1]
+    assert v.shape == k.shape and block_idx.shape == (Hkv, n, topk) and tree_mask.shape == (n,) and n <= 64
+    out = np.zeros((n, Hq, d), np.float64)
+    lse = np.zeros((n, Hq), np.float64)
+    lib.oracle_sparse_attn_tree(_ptr(q), _ptr(k), _ptr(v), _ptr(block_idx), _ptr(tree_mask), n, int(l_ctx),
+                                Hq, Hkv, d, l, prm.block_size, topk, float(prm.softmax_scale),
+                                _ptr(out), _ptr(lse))
+    return out, lse

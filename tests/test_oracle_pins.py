@@ -495,3 +495,64 @@ def test_coarse_lse_closed_form_and_clamps():
     _, ckb2 = ref.compress_keys(k2, prm)
     r2 = ref.kernel_scores(q2, ckb2, np.array([299], np.int32), prm)
     assert r2[0, 0, 4] == 2.0 ** 100 and r2[0, 0, 8] == 2.0 ** -100
+
+
+# ------------------------------------------------------------------ tree-style draft verification
+# (section 4.1, "InfLLM v2 for Target Model": a bit-packed local mask for the last n x n region)
+
+def _tree_case(l_ctx, n, Hq, Hkv, topk, seed, d=16, m=8, p=4, s=2):
+    rng = np.random.default_rng(seed)
+    l = l_ctx + n
+    q = synth.f32_to_bf16_bits(rng.standard_normal((l, Hq, d), dtype=np.float32))
+    k = synth.f32_to_bf16_bits(rng.standard_normal((Hkv, l, d), dtype=np.float32))
+    v = synth.f32_to_bf16_bits(rng.standard_normal((Hkv, l, d), dtype=np.float32))
+    prm = ref.Params(Hq, Hkv, head_dim=d, block_size=m, kernel_size=p, kernel_stride=s, topk=topk)
+    _, ckb = ref.compress_keys(k, prm)
+    pos = np.arange(l_ctx, l, dtype=np.int32)
+    idx, _ = ref.select_blocks(q[pos], ckb, pos, prm)
+    return q, k, v, prm, pos, idx
+
+
+def test_tree_attention_with_chain_mask_is_causal_attention():
+    l_ctx, n = 70, 13
+    q, k, v, prm, pos, idx = _tree_case(l_ctx, n, 4, 2, 5, 11)
+    chain = np.array([(1 << (t + 1)) - 1 for t in range(n)], np.uint64)
+    o_t, l_t = ref.sparse_attn_tree(q[pos], k, v, idx, chain, l_ctx, prm)
+    o_c, l_c = ref.sparse_attn(q[pos], k, v, pos, idx, prm)
+    assert np.array_equal(o_t, o_c) and np.array_equal(l_t, l_c)
+
+
+def test_tree_attention_against_library_masked_attention():
+    l_ctx, n, Hq, Hkv, m = 90, 17, 6, 2, 8
+    q, k, v, prm, pos, idx = _tree_case(l_ctx, n, Hq, Hkv, 6, 13, m=m)
+    rng = np.random.default_rng(3)
+    parent = [-1] + [int(rng.integers(0, t)) for t in range(1, n)]          # a random tree, node 0 the root
+    words = []
+    for t in range(n):
+        w, a = 0, t
+        while a >= 0:
+            w |= 1 << a
+            a = parent[a]
+        words.append(w)
+    mask_words = np.array(words, np.uint64)
+    o, lse = ref.sparse_attn_tree(q[pos], k, v, idx, mask_words, l_ctx, prm)
+    l, G = l_ctx + n, Hq // Hkv
+    allowed = np.zeros((Hkv, n, l), bool)
+    for h in range(Hkv):
+        for t in range(n):
+            for j in idx[h, t]:
+                if j >= 0:
+                    allowed[h, t, j * m:(j + 1) * m] = True
+            allowed[h, t, l_ctx:] &= np.array([(words[t] >> u) & 1 for u in range(n)], bool)
+    qt = torch.from_numpy(synth.bf16_bits_to_f32(q[pos]).astype(np.float64)).permute(1, 0, 2)     # [Hq, n, d]
+    kt = torch.from_numpy(synth.bf16_bits_to_f32(k).astype(np.float64)).repeat_interleave(G, 0)
+    vt = torch.from_numpy(synth.bf16_bits_to_f32(v).astype(np.float64)).repeat_interleave(G, 0)
+    mt = torch.from_numpy(allowed).repeat_interleave(G, 0)
+    want = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, attn_mask=mt).permute(1, 0, 2).numpy()
+    assert np.abs(o - want).max() < 1e-12
+    # siblings do not see each other; every node sees itself and the root
+    for t in range(1, n):
+        assert words[t] & 1 and (words[t] >> t) & 1
+    z = (qt @ kt.transpose(1, 2)) * prm.softmax_scale
+    z = z.masked_fill(~mt, -np.inf)
+    assert np.abs(lse - torch.logsumexp(z, -1).T.numpy()).max() < 1e-12

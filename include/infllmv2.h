@@ -10,7 +10,8 @@
  *                                   the always-selected initial and local-window blocks
  *   3. infllmv2_sparse_attn_prefill / infllmv2_sparse_attn_decode
  *                                   exact softmax attention over the selected blocks only
- * plus infllmv2_append_kv, the cache append that opens a decode step.
+ * plus infllmv2_append_kv, the cache append that opens a decode step, and the *_verify
+ * variants of the decode step for the n drafted tokens of speculative decoding (section 4.1).
  *
  * Conventions for every entry point
  *   - Returns 0 (INFLLMV2_OK) or a negative INFLLMV2_ERR_* code; never throws, never
@@ -61,6 +62,9 @@ extern "C" {
 #define INFLLMV2_OP_SELECT_DECODE 2
 #define INFLLMV2_OP_ATTN_PREFILL 3
 #define INFLLMV2_OP_ATTN_DECODE 4
+/* Stage selector for infllmv2_verify_workspace_bytes. */
+#define INFLLMV2_OP_SELECT_VERIFY 5
+#define INFLLMV2_OP_ATTN_VERIFY 6
 
 /* Query layout selector for infllmv2_select_blocks. */
 #define INFLLMV2_MODE_PREFILL 0 /* one query per cached token: query t sits at position t        */
@@ -202,6 +206,52 @@ int32_t infllmv2_append_kv(const infllmv2_params *prm, const infllmv2_tensor *k_
                            const infllmv2_tensor *v_new, const infllmv2_tensor *k,
                            const infllmv2_tensor *v, const infllmv2_tensor *ck,
                            const int32_t *seqlens, int32_t batch, int32_t max_seqlen, void *stream);
+
+/*
+ * Draft verification (section 4.1, "InfLLM v2 for Target Model": the target model checks n drafted
+ * tokens in one step; inside the last n x n region of the attention the causal triangle is replaced
+ * by a tree mask, bit-packed in uint64).  The three calls below are the decode step for n_draft
+ * query tokens per sequence, 1 <= n_draft <= 64, batch * n_draft <= 65535:
+ *   - the drafted tokens occupy the LAST n_draft cache rows of each sequence, in draft order:
+ *     draft token t sits at position seqlens[b] - n_draft + t (seqlens counts them);
+ *   - draft token t selects blocks exactly as a query at that position does in
+ *     infllmv2_select_blocks (the selection does not look at the tree);
+ *   - it attends, inside its selected blocks, every context token (position < seqlens[b] - n_draft)
+ *     and draft token j iff bit j of tree_mask[b * n_draft + t] is set (j may exceed t only inside
+ *     selected blocks; bits >= n_draft are ignored).  tree_mask == NULL means the causal chain
+ *     (bit j set iff j <= t), which makes the step equal to n_draft prefill rows.
+ *   A sequence with seqlens[b] < n_draft is skipped as a whole: block_idx -1, out 0, lse -inf,
+ *   nothing appended.  A query whose mask hides every key of its selected blocks gets out 0, lse -inf.
+ *
+ * infllmv2_append_kv_verify     k_new, v_new bf16 [batch, Hkv, n_draft, d] -> cache rows
+ *                               seqlens[b]-n_draft .. seqlens[b]-1; with ck != NULL a second launch
+ *                               writes the semantic kernels those rows complete
+ *                               (= infllmv2_compress_keys with n_new_tokens = n_draft).
+ * infllmv2_select_blocks_verify q bf16 [batch, n_draft, Hq, d]; block_idx out int32
+ *                               [batch, Hkv, n_draft, topk], ascending, padded with -1.
+ * infllmv2_sparse_attn_verify   q, out bf16 [batch, n_draft, Hq, d]; tree_mask DEVICE uint64
+ *                               [batch, n_draft] or NULL; lse out fp32 [batch, n_draft, Hq];
+ *                               arithmetic as in infllmv2_sparse_attn_decode.
+ * Workspaces: infllmv2_verify_workspace_bytes(INFLLMV2_OP_SELECT_VERIFY / _ATTN_VERIFY, ...)
+ * (0 if the arguments are invalid), 256-byte aligned.
+ */
+size_t infllmv2_verify_workspace_bytes(int32_t op, const infllmv2_params *prm, int32_t batch,
+                                       int32_t max_seqlen, int32_t n_draft);
+int32_t infllmv2_append_kv_verify(const infllmv2_params *prm, const infllmv2_tensor *k_new,
+                                  const infllmv2_tensor *v_new, const infllmv2_tensor *k,
+                                  const infllmv2_tensor *v, const infllmv2_tensor *ck,
+                                  const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
+                                  int32_t n_draft, void *stream);
+int32_t infllmv2_select_blocks_verify(const infllmv2_params *prm, const infllmv2_tensor *q,
+                                      const infllmv2_tensor *ck, const int32_t *seqlens, int32_t batch,
+                                      int32_t max_seqlen, int32_t n_draft, int32_t *block_idx,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+int32_t infllmv2_sparse_attn_verify(const infllmv2_params *prm, const infllmv2_tensor *q,
+                                    const infllmv2_tensor *k, const infllmv2_tensor *v,
+                                    const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
+                                    int32_t n_draft, const uint64_t *tree_mask, const int32_t *block_idx,
+                                    const infllmv2_tensor *out, float *lse, void *workspace,
+                                    size_t workspace_bytes, void *stream);
 
 /*
  * Measured practical peaks for the benchmark's rooflines (not part of the method).  Launches two

@@ -7,7 +7,7 @@ A missing library is an error: there is no fallback path.
 
 Tensor layouts (bf16, CUDA/HIP device, head_dim contiguous):
   caches k, v, ck   [B, Hkv, T, d]
-  queries, outputs  [B, T, Hq, d]   (decode: T = 1)
+  queries, outputs  [B, T, Hq, d]   (decode: T = 1; draft verification: T = n_draft)
   seqlens           int32 [B]
   block_idx         int32 [B, Hkv, Tq, topk]
 """
@@ -22,11 +22,14 @@ LIB_PATH = os.path.join(_HERE, "libinfllmv2.so")
 
 OK = 0
 OP_SELECT_PREFILL, OP_SELECT_DECODE, OP_ATTN_PREFILL, OP_ATTN_DECODE = 1, 2, 3, 4
+OP_SELECT_VERIFY, OP_ATTN_VERIFY = 5, 6
 MODE_PREFILL, MODE_DECODE = 0, 1
 
 EXPORTS = ["infllmv2_status_string", "infllmv2_workspace_bytes", "infllmv2_compress_keys",
            "infllmv2_select_blocks", "infllmv2_sparse_attn_prefill", "infllmv2_sparse_attn_decode",
-           "infllmv2_append_kv", "infllmv2_probe_peaks", "infllmv2_timing_enable", "infllmv2_timing_read"]
+           "infllmv2_append_kv", "infllmv2_verify_workspace_bytes", "infllmv2_append_kv_verify",
+           "infllmv2_select_blocks_verify", "infllmv2_sparse_attn_verify",
+           "infllmv2_probe_peaks", "infllmv2_timing_enable", "infllmv2_timing_read"]
 
 
 class CParams(ctypes.Structure):
@@ -100,6 +103,14 @@ def load_library(path=None):
     lib.infllmv2_sparse_attn_decode.argtypes = [P, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
     lib.infllmv2_append_kv.restype = i32
     lib.infllmv2_append_kv.argtypes = [P, T, T, T, T, T, vp, i32, i32, vp]
+    lib.infllmv2_verify_workspace_bytes.restype = sz
+    lib.infllmv2_verify_workspace_bytes.argtypes = [i32, P, i32, i32, i32]
+    lib.infllmv2_append_kv_verify.restype = i32
+    lib.infllmv2_append_kv_verify.argtypes = [P, T, T, T, T, T, vp, i32, i32, i32, vp]
+    lib.infllmv2_select_blocks_verify.restype = i32
+    lib.infllmv2_select_blocks_verify.argtypes = [P, T, T, vp, i32, i32, i32, vp, vp, sz, vp]
+    lib.infllmv2_sparse_attn_verify.restype = i32
+    lib.infllmv2_sparse_attn_verify.argtypes = [P, T, T, T, vp, i32, i32, i32, vp, vp, T, vp, vp, sz, vp]
     lib.infllmv2_probe_peaks.restype = i32
     lib.infllmv2_probe_peaks.argtypes = [vp, sz, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp]
     lib.infllmv2_timing_enable.restype = i32
@@ -263,4 +274,70 @@ def sparse_attn_decode(prm, q, k, v, seqlens, max_seqlen, block_idx, out=None, l
                                            max_seqlen, _i32(block_idx, "block_idx").data_ptr(),
                                            ctypes.byref(d[3]), lse.data_ptr(), workspace.data_ptr(),
                                            ws_bytes, _stream()), "infllmv2_sparse_attn_decode")
+    return out, lse
+
+
+# ---- draft verification (section 4.1, "InfLLM v2 for Target Model") ---------------------------------
+
+def verify_workspace_bytes(op, prm, batch, max_seqlen, n_draft):
+    return int(load_library().infllmv2_verify_workspace_bytes(op, ctypes.byref(prm.c()), batch, max_seqlen, n_draft))
+
+
+def _verify_workspace(op, prm, batch, max_seqlen, n_draft, workspace, device):
+    need = verify_workspace_bytes(op, prm, batch, max_seqlen, n_draft)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def append_kv_verify(prm, k_new, v_new, k, v, seqlens, max_seqlen, ck=None):
+    """k_new, v_new [B, Hkv, n_draft, d] are written at cache rows seqlens[b]-n_draft .. seqlens[b]-1;
+    with ck the compressed keys those rows complete are written too."""
+    lib = load_library()
+    d = [_cache_desc(k_new, "k_new"), _cache_desc(v_new, "v_new"), _cache_desc(k, "k"), _cache_desc(v, "v")]
+    ckd = ctypes.byref(_cache_desc(ck, "ck")) if ck is not None else None
+    _check(lib.infllmv2_append_kv_verify(ctypes.byref(prm.c()), ctypes.byref(d[0]), ctypes.byref(d[1]),
+                                         ctypes.byref(d[2]), ctypes.byref(d[3]), ckd,
+                                         _i32(seqlens, "seqlens").data_ptr(), k.shape[0], max_seqlen,
+                                         k_new.shape[2], _stream()), "infllmv2_append_kv_verify")
+
+
+def select_blocks_verify(prm, q, ck, seqlens, max_seqlen, block_idx=None, workspace=None):
+    """q [B, n_draft, Hq, d] -> block_idx int32 [B, Hkv, n_draft, topk]."""
+    lib = load_library()
+    B, n = q.shape[0], q.shape[1]
+    if block_idx is None:
+        block_idx = torch.full((B, prm.n_kv_heads, n, prm.topk), -1, dtype=torch.int32, device=q.device)
+    workspace, ws_bytes = _verify_workspace(OP_SELECT_VERIFY, prm, B, max_seqlen, n, workspace, q.device)
+    qd, cd = _query_desc(q, "q"), _cache_desc(ck, "ck")
+    _check(lib.infllmv2_select_blocks_verify(ctypes.byref(prm.c()), ctypes.byref(qd), ctypes.byref(cd),
+                                             _i32(seqlens, "seqlens").data_ptr(), B, max_seqlen, n,
+                                             _i32(block_idx, "block_idx").data_ptr(), workspace.data_ptr(),
+                                             ws_bytes, _stream()), "infllmv2_select_blocks_verify")
+    return block_idx
+
+
+def sparse_attn_verify(prm, q, k, v, seqlens, max_seqlen, block_idx, tree_mask=None, out=None, lse=None,
+                       workspace=None):
+    """q [B, n_draft, Hq, d]; tree_mask int64 device tensor [B, n_draft] holding the uint64 mask words
+    (None = causal chain) -> out bf16 [B, n_draft, Hq, d], lse fp32 [B, n_draft, Hq]."""
+    lib = load_library()
+    B, n = q.shape[0], q.shape[1]
+    if out is None:
+        out = torch.zeros_like(q)
+    if lse is None:
+        lse = torch.zeros((B, n, prm.n_q_heads), dtype=torch.float32, device=q.device)
+    mask_ptr = None
+    if tree_mask is not None:
+        if not (tree_mask.is_cuda and tree_mask.dtype == torch.int64 and tree_mask.is_contiguous()
+                and tuple(tree_mask.shape) == (B, n)):
+            raise InfLLMv2Error("tree_mask must be a contiguous int64 device tensor [B, n_draft]")
+        mask_ptr = tree_mask.data_ptr()
+    workspace, ws_bytes = _verify_workspace(OP_ATTN_VERIFY, prm, B, max_seqlen, n, workspace, q.device)
+    d = [_query_desc(q, "q"), _cache_desc(k, "k"), _cache_desc(v, "v"), _query_desc(out, "out")]
+    _check(lib.infllmv2_sparse_attn_verify(ctypes.byref(prm.c()), ctypes.byref(d[0]), ctypes.byref(d[1]),
+                                           ctypes.byref(d[2]), _i32(seqlens, "seqlens").data_ptr(), B,
+                                           max_seqlen, n, mask_ptr, _i32(block_idx, "block_idx").data_ptr(),
+                                           ctypes.byref(d[3]), lse.data_ptr(), workspace.data_ptr(),
+                                           ws_bytes, _stream()), "infllmv2_sparse_attn_verify")
     return out, lse

@@ -7,6 +7,7 @@ using namespace infllmv2;
 namespace {
 
 constexpr int32_t kMaxDecodeSeqlen = 262144;   // decode selection: at most 256 log-sum-exp partials per head
+constexpr int32_t kMaxDraft = 64;              // one uint64 mask word per drafted token
 
 int32_t check_params(const infllmv2_params *p) {
     if (!p) return INFLLMV2_ERR_INVALID_ARGUMENT;
@@ -40,6 +41,13 @@ int32_t check_sizes(int32_t batch, int32_t max_seqlen) {
     return INFLLMV2_OK;
 }
 
+// query rows of a verification step: one grid-z slot each
+int32_t check_draft(int32_t batch, int32_t n_draft) {
+    if (n_draft < 1) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    if (n_draft > kMaxDraft || (int64_t)batch * n_draft > 65535) return INFLLMV2_ERR_UNSUPPORTED;
+    return INFLLMV2_OK;
+}
+
 int32_t check_tensor(const infllmv2_tensor *t) {
     if (!t || !t->ptr) return INFLLMV2_ERR_INVALID_ARGUMENT;
     if ((reinterpret_cast<uintptr_t>(t->ptr) & 15u) != 0) return INFLLMV2_ERR_INVALID_ARGUMENT;
@@ -48,7 +56,7 @@ int32_t check_tensor(const infllmv2_tensor *t) {
     return INFLLMV2_OK;
 }
 
-Dims make_dims(const infllmv2_params *p, int32_t batch, int32_t max_seqlen) {
+Dims make_dims(const infllmv2_params *p, int32_t batch, int32_t max_seqlen, int32_t n_q = 1) {
     Dims d;
     d.Hq = p->n_q_heads;
     d.Hkv = p->n_kv_heads;
@@ -60,6 +68,7 @@ Dims make_dims(const infllmv2_params *p, int32_t batch, int32_t max_seqlen) {
     d.max_seqlen = max_seqlen;
     d.scale_log2 = p->softmax_scale * kLog2e;
     d.rho = p->lse_coarse_ratio > 1 ? p->lse_coarse_ratio : 1;
+    d.n_q = n_q;
     return d;
 }
 
@@ -161,6 +170,19 @@ size_t infllmv2_workspace_bytes(int32_t op, const infllmv2_params *prm, int32_t 
     return 0;
 }
 
+size_t infllmv2_verify_workspace_bytes(int32_t op, const infllmv2_params *prm, int32_t batch,
+                                       int32_t max_seqlen, int32_t n_draft) {
+    if (check_params(prm) != INFLLMV2_OK || check_sizes(batch, max_seqlen) != INFLLMV2_OK ||
+        check_draft(batch, n_draft) != INFLLMV2_OK)
+        return 0;
+    const Dims dm = make_dims(prm, batch, max_seqlen, n_draft);
+    switch (op) {
+        case INFLLMV2_OP_SELECT_VERIFY: return max_seqlen > kMaxDecodeSeqlen ? 0 : select_decode_ws_bytes(dm);
+        case INFLLMV2_OP_ATTN_VERIFY: return attn_decode_ws_bytes(dm);
+    }
+    return 0;
+}
+
 int32_t infllmv2_compress_keys(const infllmv2_params *prm, const infllmv2_tensor *k,
                                const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
                                int32_t n_new_tokens, const infllmv2_tensor *ck, void *stream) {
@@ -192,6 +214,72 @@ int32_t infllmv2_append_kv(const infllmv2_params *prm, const infllmv2_tensor *k_
     return hip_status(launch_append_kv(dm, make_tensor(k_new), make_tensor(v_new), make_tensor(k),
                                        make_tensor(v), ck ? &ckt : nullptr, seqlens,
                                        reinterpret_cast<hipStream_t>(stream)));
+}
+
+int32_t infllmv2_append_kv_verify(const infllmv2_params *prm, const infllmv2_tensor *k_new,
+                                  const infllmv2_tensor *v_new, const infllmv2_tensor *k,
+                                  const infllmv2_tensor *v, const infllmv2_tensor *ck, const int32_t *seqlens,
+                                  int32_t batch, int32_t max_seqlen, int32_t n_draft, void *stream) {
+    RETURN_IF_ERR(check_params(prm));
+    RETURN_IF_ERR(check_sizes(batch, max_seqlen));
+    RETURN_IF_ERR(check_draft(batch, n_draft));
+    RETURN_IF_ERR(check_tensor(k_new));
+    RETURN_IF_ERR(check_tensor(v_new));
+    RETURN_IF_ERR(check_tensor(k));
+    RETURN_IF_ERR(check_tensor(v));
+    if (ck) RETURN_IF_ERR(check_tensor(ck));
+    if (!seqlens) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    const Dims dm = make_dims(prm, batch, max_seqlen, n_draft);
+    Tensor ckt;
+    if (ck) ckt = make_tensor(ck);
+    return hip_status(launch_append_kv(dm, make_tensor(k_new), make_tensor(v_new), make_tensor(k),
+                                       make_tensor(v), ck ? &ckt : nullptr, seqlens,
+                                       reinterpret_cast<hipStream_t>(stream)));
+}
+
+int32_t infllmv2_select_blocks_verify(const infllmv2_params *prm, const infllmv2_tensor *q,
+                                      const infllmv2_tensor *ck, const int32_t *seqlens, int32_t batch,
+                                      int32_t max_seqlen, int32_t n_draft, int32_t *block_idx,
+                                      void *workspace, size_t workspace_bytes, void *stream) {
+    RETURN_IF_ERR(check_params(prm));
+    RETURN_IF_ERR(check_sizes(batch, max_seqlen));
+    RETURN_IF_ERR(check_draft(batch, n_draft));
+    RETURN_IF_ERR(check_tensor(q));
+    RETURN_IF_ERR(check_tensor(ck));
+    if (!seqlens || !block_idx) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    if (max_seqlen > kMaxDecodeSeqlen) return INFLLMV2_ERR_UNSUPPORTED;
+    const Dims dm = make_dims(prm, batch, max_seqlen, n_draft);
+    const size_t need = select_decode_ws_bytes(dm);
+    if (need > 0 && (!workspace || workspace_bytes < need ||
+                     (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0))
+        return INFLLMV2_ERR_WORKSPACE;
+    return hip_status(launch_select_decode(dm, make_tensor(q), make_tensor(ck), seqlens, block_idx,
+                                           workspace, reinterpret_cast<hipStream_t>(stream)));
+}
+
+int32_t infllmv2_sparse_attn_verify(const infllmv2_params *prm, const infllmv2_tensor *q,
+                                    const infllmv2_tensor *k, const infllmv2_tensor *v,
+                                    const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
+                                    int32_t n_draft, const uint64_t *tree_mask, const int32_t *block_idx,
+                                    const infllmv2_tensor *out, float *lse, void *workspace,
+                                    size_t workspace_bytes, void *stream) {
+    RETURN_IF_ERR(check_params(prm));
+    RETURN_IF_ERR(check_sizes(batch, max_seqlen));
+    RETURN_IF_ERR(check_draft(batch, n_draft));
+    RETURN_IF_ERR(check_tensor(q));
+    RETURN_IF_ERR(check_tensor(k));
+    RETURN_IF_ERR(check_tensor(v));
+    RETURN_IF_ERR(check_tensor(out));
+    if (!seqlens || !block_idx || !lse) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    if (tree_mask && (reinterpret_cast<uintptr_t>(tree_mask) & 7u) != 0) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    const Dims dm = make_dims(prm, batch, max_seqlen, n_draft);
+    const size_t need = attn_decode_ws_bytes(dm);
+    if (need > 0 && (!workspace || workspace_bytes < need ||
+                     (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0))
+        return INFLLMV2_ERR_WORKSPACE;
+    return hip_status(launch_attn_decode(dm, make_tensor(q), make_tensor(k), make_tensor(v), seqlens,
+                                         block_idx, tree_mask, make_tensor(out), lse, workspace,
+                                         reinterpret_cast<hipStream_t>(stream)));
 }
 
 int32_t infllmv2_select_blocks(const infllmv2_params *prm, int32_t mode, const infllmv2_tensor *q,
@@ -258,7 +346,7 @@ int32_t infllmv2_sparse_attn_decode(const infllmv2_params *prm, const infllmv2_t
                      (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0))
         return INFLLMV2_ERR_WORKSPACE;
     return hip_status(launch_attn_decode(dm, make_tensor(q), make_tensor(k), make_tensor(v), seqlens,
-                                         block_idx, make_tensor(out), lse, workspace,
+                                         block_idx, nullptr, make_tensor(out), lse, workspace,
                                          reinterpret_cast<hipStream_t>(stream)));
 }
 

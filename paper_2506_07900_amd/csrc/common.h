@@ -29,6 +29,7 @@ struct Dims {
     int32_t batch, max_seqlen;
     float scale_log2;   // softmax_scale * log2(e)
     int32_t rho;        // coarse / fine kernel stride of the approximate log-sum-exp; 1 = exact
+    int32_t n_q;        // decode-side kernels: query tokens per sequence (1 = plain decode, n = draft verification)
 };
 
 struct Tensor {          // strides in elements
@@ -120,7 +121,7 @@ void timing_end(hipStream_t stream);
 int launch_compress_keys(const Dims &dm, Tensor k, Tensor ck, const int32_t *seqlens,
                          int32_t n_new_tokens, hipStream_t stream);
 int launch_append_kv(const Dims &dm, Tensor k_new, Tensor v_new, Tensor k, Tensor v, const Tensor *ck,
-                     const int32_t *seqlens, hipStream_t stream);
+                     const int32_t *seqlens, hipStream_t stream);   // dm.n_q rows per sequence
 int launch_select_prefill(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
                           int32_t *block_idx, void *ws, hipStream_t stream);
 size_t select_prefill_ws_bytes(const Dims &dm);
@@ -138,7 +139,7 @@ int launch_attn_prefill(const Dims &dm, Tensor q, Tensor k, Tensor v, const int3
                         const int32_t *block_idx, Tensor out, float *lse, void *ws, hipStream_t stream);
 size_t attn_prefill_ws_bytes(const Dims &dm);
 int launch_attn_decode(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32_t *seqlens,
-                       const int32_t *block_idx, Tensor out, float *lse, void *ws,
+                       const int32_t *block_idx, const uint64_t *tree_mask, Tensor out, float *lse, void *ws,
                        hipStream_t stream);
 size_t attn_decode_ws_bytes(const Dims &dm);
 int launch_probes(void *buf, size_t buf_bytes, double *mfma_flops, double *stream_bytes, hipStream_t stream);

@@ -59,22 +59,24 @@ int launch_compress_keys(const Dims &dm, Tensor k, Tensor ck, const int32_t *seq
     return (int)hipGetLastError();
 }
 
-// Decode-step append: copy the new key / value row of every (sequence, key-value head) to
-// cache position seqlens[b]-1.  One 16-lane group per row.  With kWithCk the same launch also
+// Decode-step append: copy the new key / value rows of every (sequence, key-value head) to
+// cache positions seqlens[b]-n_q .. seqlens[b]-1 (n_q = 1 in plain decode; the drafted tokens of a
+// verification step otherwise).  One 16-lane group per row.  With kWithCk (n_q = 1 only) the same launch also
 // writes the semantic-kernel representation that the new token completes (it ends kernel
 // jh = (L-32)/16 when L >= 32 and L-32 is a multiple of 16): its 31 older rows come from the
 // cache, the newest from k_new, summed in fp64 like compress_keys_kernel (exact for bf16 inputs).
 template <bool kWithCk>
 __global__ __launch_bounds__(256) void append_kv_kernel(Dims dm, Tensor k_new, Tensor v_new, Tensor k,
                                                          Tensor v, Tensor ck, const int32_t *__restrict__ seqlens) {
-    const int row = blockIdx.x * 16 + (threadIdx.x >> 4);   // (b, h) pair
-    if (row >= dm.batch * dm.Hkv) return;
-    const int b = row / dm.Hkv, h = row % dm.Hkv;
-    const int32_t L = seqlens[b];
-    if (L < 1 || L > dm.max_seqlen) return;
+    const int row = blockIdx.x * 16 + (threadIdx.x >> 4);   // (b, h, new token) triple
+    if (row >= dm.batch * dm.Hkv * dm.n_q) return;
+    const int bh = row / dm.n_q, qi = row - bh * dm.n_q;
+    const int b = bh / dm.Hkv, h = bh % dm.Hkv;
+    const int32_t L = seqlens[b] - (dm.n_q - 1 - qi);       // cache rows up to and including this token
+    if (L < 1 + qi || seqlens[b] > dm.max_seqlen) return;   // a sequence shorter than n_q is skipped as a whole
     const int c = (threadIdx.x & 15) * 8;
     const int64_t dst = (int64_t)(L - 1);
-    const uint4 kn = *reinterpret_cast<const uint4 *>(k_new.ptr + b * k_new.sb + h * k_new.sh + c);
+    const uint4 kn = *reinterpret_cast<const uint4 *>(k_new.ptr + b * k_new.sb + h * k_new.sh + qi * k_new.st + c);
     const __bf16 *kb = k.ptr + b * k.sb + h * k.sh + c;
     const bool closes = kWithCk && L >= kKernel && (L - kKernel) % kStride == 0;
     bf16x8 old[kKernel - 1];
@@ -84,7 +86,7 @@ __global__ __launch_bounds__(256) void append_kv_kernel(Dims dm, Tensor k_new, T
     }
     *reinterpret_cast<uint4 *>(k.ptr + b * k.sb + h * k.sh + dst * k.st + c) = kn;
     *reinterpret_cast<uint4 *>(v.ptr + b * v.sb + h * v.sh + dst * v.st + c) =
-        *reinterpret_cast<const uint4 *>(v_new.ptr + b * v_new.sb + h * v_new.sh + c);
+        *reinterpret_cast<const uint4 *>(v_new.ptr + b * v_new.sb + h * v_new.sh + qi * v_new.st + c);
     if (closes) {
         const bf16x8 newest = __builtin_bit_cast(bf16x8, kn);
         double acc[8];
@@ -109,16 +111,21 @@ __global__ __launch_bounds__(256) void append_kv_kernel(Dims dm, Tensor k_new, T
 
 int launch_append_kv(const Dims &dm, Tensor k_new, Tensor v_new, Tensor k, Tensor v, const Tensor *ck,
                      const int32_t *seqlens, hipStream_t stream) {
-    int rows = dm.batch * dm.Hkv;
+    int rows = dm.batch * dm.Hkv * dm.n_q;
     if (rows <= 0) return 0;
     timing_begin("append_kv_kernel", stream);
-    if (ck)
+    if (ck && dm.n_q == 1)
         hipLaunchKernelGGL(append_kv_kernel<true>, dim3((rows + 15) / 16), dim3(256), 0, stream, dm, k_new,
                            v_new, k, v, *ck, seqlens);
     else
         hipLaunchKernelGGL(append_kv_kernel<false>, dim3((rows + 15) / 16), dim3(256), 0, stream, dm, k_new,
                            v_new, k, v, k, seqlens);
     timing_end(stream);
+    if (ck && dm.n_q > 1) {      // several new rows: the kernels they complete, after the rows are in the cache
+        const int e = (int)hipGetLastError();
+        if (e) return e;
+        return launch_compress_keys(dm, k, *ck, seqlens, dm.n_q, stream);
+    }
     return (int)hipGetLastError();
 }
 

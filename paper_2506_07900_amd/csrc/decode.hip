@@ -1,7 +1,10 @@
 // Decode step, stages 2 and 3 for ONE query token per sequence at position seqlens[b]-1
 // (section 2.1.3 "Different Granularity for Query and Key-Value Tokens": token-level queries
 // keep the method usable in decoding; section 5.4: per step the attended blocks stay constant
-// and only the semantic-kernel representations grow).
+// and only the semantic-kernel representations grow), and for the n drafted tokens of a
+// speculative-verification step (section 4.1, "InfLLM v2 for Target Model"): the same kernels
+// over n query rows per sequence, with the causal test of the last n x n region replaced by a
+// bit-packed tree mask.
 //
 // A decode step moves a few megabytes, so it is bound by launch and memory latency, not by
 // bandwidth: every kernel below spreads its reads over many workgroups and issues all the loads
@@ -21,6 +24,23 @@ namespace infllmv2 {
 
 __device__ inline int clamp_len(int32_t L, int32_t cap) { return L < 0 ? 0 : (L > cap ? cap : L); }
 
+// Every kernel below works on "query rows": row bv = b * n_q + qi is query token qi of sequence b.
+// Plain decode has n_q = 1.  Draft verification (section 4.1, "InfLLM v2 for Target Model") has the
+// n_q drafted tokens in the last n_q cache rows; token qi sits at position seqlens[b] - n_q + qi and
+// selects blocks like any query at that position.  Returns the number of cache rows up to and
+// including the query (0: the row is skipped; a sequence shorter than n_q is skipped as a whole).
+__device__ inline int query_row(const Dims &dm, const int32_t *__restrict__ seqlens, int bv, int &b, int &qi) {
+    if (dm.n_q == 1) {
+        b = bv;
+        qi = 0;
+        return clamp_len(seqlens[b], dm.max_seqlen);
+    }
+    b = bv / dm.n_q;
+    qi = bv - b * dm.n_q;
+    const int L_all = clamp_len(seqlens[b], dm.max_seqlen);
+    return L_all < dm.n_q ? 0 : L_all - (dm.n_q - 1 - qi);
+}
+
 // ---- selection, part 1 ------------------------------------------------------------------------
 // grid (n_c_cap/64, Hkv, B); wave w of a workgroup owns kernels 64*bx + 16*w .. +15.
 // Z^T = CK . Q^T: lane = query head, 4 accumulator entries = 4 consecutive kernels.
@@ -32,8 +52,9 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, T
                                                              int32_t n_part) {
     __shared__ float2 wpart[4][16];
     __shared__ float2 wpart_c[2][16];
-    const int b = blockIdx.z, h = blockIdx.y;
-    const int L = clamp_len(seqlens[b], dm.max_seqlen);
+    const int bv = blockIdx.z, h = blockIdx.y;
+    int b, qi;
+    const int L = query_row(dm, seqlens, bv, b, qi);
     const int n_vis = num_kernels(L);                 // the query sits at L-1: n_c((L-1)+1)
     if ((int)blockIdx.x * 64 >= n_vis) return;        // uniform over the workgroup
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -42,7 +63,7 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, T
     const int G = dm.G;
     f32x4 z = {0.f, 0.f, 0.f, 0.f};
     const __bf16 *ckr = ck.ptr + b * ck.sb + h * ck.sh + (int64_t)(jh0 + n) * ck.st + 8 * g;
-    const __bf16 *qr = q.ptr + b * q.sb + (int64_t)(h * G + n) * q.sh + 8 * g;
+    const __bf16 *qr = q.ptr + b * q.sb + qi * q.st + (int64_t)(h * G + n) * q.sh + 8 * g;
     bf16x8 a[4], bq[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -68,7 +89,7 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, T
     for (int j = 0; j < 4; ++j) s += fast_exp2(x[j] - m_use);
     s = xgroup_sum(s);
     if (n < G && jh0 < n_vis) {
-        float *zr = zbuf + (((int64_t)b * dm.Hkv + h) * G + n) * n_c_cap + jh0 + 4 * g;
+        float *zr = zbuf + (((int64_t)bv * dm.Hkv + h) * G + n) * n_c_cap + jh0 + 4 * g;
         *reinterpret_cast<float4 *>(zr) = float4{x[0], x[1], x[2], x[3]};
     }
     if (g == 0) wpart[wave][n] = float2{mx, s};
@@ -81,7 +102,7 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, T
         float S = 0.f;
 #pragma unroll
         for (int w = 0; w < 4; ++w) S += wpart[w][threadIdx.x].y * fast_exp2(wpart[w][threadIdx.x].x - mu);
-        part[(((int64_t)b * dm.Hkv + h) * G + threadIdx.x) * n_part + blockIdx.x] = float2{M, S};
+        part[(((int64_t)bv * dm.Hkv + h) * G + threadIdx.x) * n_part + blockIdx.x] = float2{M, S};
     }
     // Approximate log-sum-exp ("Efficient Top-K Implementation", last paragraph): the same
     // partial (max, sum) over the coarse kernels 64/rho * bx .. of this chunk, each the bf16 mean
@@ -139,7 +160,7 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, T
             const float mu = M == -INFINITY ? 0.f : M;
             float S = 0.f;
             for (int w = 0; w < tiles_c; ++w) S += wpart_c[w][threadIdx.x].y * fast_exp2(wpart_c[w][threadIdx.x].x - mu);
-            part_c[(((int64_t)b * dm.Hkv + h) * G + threadIdx.x) * n_part + blockIdx.x] = float2{M, S};
+            part_c[(((int64_t)bv * dm.Hkv + h) * G + threadIdx.x) * n_part + blockIdx.x] = float2{M, S};
         }
     }
 }
@@ -155,10 +176,11 @@ __global__ __launch_bounds__(320) void decode_scores_kernel(Dims dm, const int32
                                                              float *__restrict__ R, int32_t nb_cap) {
     __shared__ float lse_h[16];
     __shared__ float rs[260];
-    const int h = blockIdx.y, b = blockIdx.z;
+    const int h = blockIdx.y, bv = blockIdx.z;
     const int tid = threadIdx.x;
     const int G = dm.G;
-    const int L = clamp_len(seqlens[b], dm.max_seqlen);
+    int b, qi;
+    const int L = query_row(dm, seqlens, bv, b, qi);
     const int n_vis = num_kernels(L);
     const int base = blockIdx.x * 256;
     if (L < 1 || (int)blockIdx.x * 64 > (L - 1) / kBlock) return;            // no block of this chunk exists
@@ -171,7 +193,7 @@ __global__ __launch_bounds__(320) void decode_scores_kernel(Dims dm, const int32
         for (int i = 0; i < kMaxParts / 16; ++i) {
             const int p = sub + 16 * i;
             v[i] = float2{-INFINITY, 0.f};
-            if (head < G && p < np) v[i] = part[(((int64_t)b * dm.Hkv + h) * G + head) * n_part + p];
+            if (head < G && p < np) v[i] = part[(((int64_t)bv * dm.Hkv + h) * G + head) * n_part + p];
         }
         float m = -INFINITY;
 #pragma unroll
@@ -195,7 +217,7 @@ __global__ __launch_bounds__(320) void decode_scores_kernel(Dims dm, const int32
 #pragma unroll
     for (int gq = 0; gq < 16; ++gq) {
         zz[gq] = -INFINITY;
-        if (have && gq < G) zz[gq] = zbuf[(((int64_t)b * dm.Hkv + h) * G + gq) * n_c_cap + jh];
+        if (have && gq < G) zz[gq] = zbuf[(((int64_t)bv * dm.Hkv + h) * G + gq) * n_c_cap + jh];
     }
     __syncthreads();
     if (tid <= 256) {
@@ -212,13 +234,13 @@ __global__ __launch_bounds__(320) void decode_scores_kernel(Dims dm, const int32
             float v = rs[4 * tid];
 #pragma unroll
             for (int x = 1; x < 5; ++x) v = fmaxf(v, rs[4 * tid + x]);
-            R[((int64_t)b * dm.Hkv + h) * nb_cap + j] = v;
+            R[((int64_t)bv * dm.Hkv + h) * nb_cap + j] = v;
         }
     }
 }
 
 // ---- selection, part 3: top-k of one row of block scores ----------------------------------------
-// grid (B*Hkv), 256 threads.  Candidates are the blocks n_init .. b_own - n_local; the forced ones
+// grid (B*n_q*Hkv), 256 threads.  Candidates are the blocks n_init .. b_own - n_local; the forced ones
 // are added afterwards (section 2.1.2 "Top-K Blocks Sharing": initial and local blocks are always
 // attended).  Scores are positive floats, so their bit patterns order like unsigned integers.
 // An element is the 64-bit word  key << 32 | ~block  with key = bits of the score (1 for a block
@@ -246,14 +268,15 @@ __global__ __launch_bounds__(kPickThreads) void decode_pick_kernel(Dims dm, cons
     __shared__ uint64_t tau_s;
     __shared__ int n_cand_s;
     __shared__ int picked[kMaxTopk];
-    const int row = blockIdx.x, b = row / dm.Hkv;
+    const int row = blockIdx.x, bv = row / dm.Hkv, h = row - bv * dm.Hkv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *Rr = R + (int64_t)row * nb_cap;
     float r[kVPT];                                        // every load issued before any use
 #pragma unroll
     for (int s = 0; s < kVPT; ++s) r[s] = Rr[min(tid + kPickThreads * s, nb_cap - 1)];
-    const int L = clamp_len(seqlens[b], dm.max_seqlen);
-    int32_t *o = block_idx + (int64_t)row * dm.topk;
+    int b, qi;
+    const int L = query_row(dm, seqlens, bv, b, qi);
+    int32_t *o = block_idx + (((int64_t)b * dm.Hkv + h) * dm.n_q + qi) * dm.topk;
     if (L < 1) {
         if (tid < dm.topk) o[tid] = -1;
         return;
@@ -337,22 +360,28 @@ constexpr int kVsPitch = kHeadDim + 4;               // bf16 elements per LDS va
 __global__ __launch_bounds__(256) void decode_attn_partial_kernel(Dims dm, Tensor q, Tensor k, Tensor v,
                                                                    const int32_t *__restrict__ seqlens,
                                                                    const int32_t *__restrict__ block_idx,
+                                                                   const uint64_t *__restrict__ tree_mask,
                                                                    float *__restrict__ o_part,
                                                                    float2 *__restrict__ ml_part) {
     __shared__ __align__(16) uint16_t Vs[kBlock * kVsPitch];
     __shared__ float Ps[kBlock][17];
     __shared__ float wmax[4][16], wsum[4][16];
-    const int cidx = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int cidx = blockIdx.x, h = blockIdx.y, bv = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, g = lane >> 4;
     const int G = dm.G;
-    const int L = clamp_len(seqlens[b], dm.max_seqlen);
-    const int blk = block_idx[((int64_t)b * dm.Hkv + h) * dm.topk + cidx];
-    const bool valid = L >= 1 && blk >= 0 && (int64_t)blk * kBlock < L;
+    int b, qi;
+    const int L = query_row(dm, seqlens, bv, b, qi);
+    const int L_all = L + (dm.n_q - 1 - qi);             // cache rows of the sequence (when L >= 1)
+    const int blk = block_idx[(((int64_t)b * dm.Hkv + h) * dm.n_q + qi) * dm.topk + cidx];
+    uint64_t mask_word = 0ull;
+    if (tree_mask) mask_word = tree_mask[bv];
+    // a tree mask may let a query attend drafted tokens that lie after it in the cache
+    const bool valid = L >= 1 && blk >= 0 && (int64_t)blk * kBlock < (tree_mask ? L_all : L);
     if (!valid) {                                        // uniform over the workgroup
         const int head = tid & 15, chunk = tid >> 4;
         if (head < G) {
-            const int64_t pbase = (((int64_t)b * dm.Hq + h * G + head) * dm.topk + cidx);
+            const int64_t pbase = (((int64_t)bv * dm.Hq + h * G + head) * dm.topk + cidx);
             if (chunk == 0) ml_part[pbase] = float2{-INFINITY, 0.f};
             float4 zf = {0.f, 0.f, 0.f, 0.f};
             float4 *op = reinterpret_cast<float4 *>(o_part + pbase * kHeadDim + 8 * chunk);
@@ -362,8 +391,7 @@ __global__ __launch_bounds__(256) void decode_attn_partial_kernel(Dims dm, Tenso
         return;
     }
     const int key0 = blk * kBlock;
-    const int pos = L - 1;                               // key0 <= pos
-    const int last_row = dm.max_seqlen - 1;              // rows past pos are read (in bounds) and masked
+    const int last_row = dm.max_seqlen - 1;              // rows the query may not see are read (in bounds) and masked
     // ---- all loads --------------------------------------------------------------------------------
     const int c8 = tid & 15, vr = tid >> 4;
     uint4 vrow[4];
@@ -377,19 +405,33 @@ __global__ __launch_bounds__(256) void decode_attn_partial_kernel(Dims dm, Tenso
     {
         const int key = min(key0 + 16 * wave + n, last_row);
         const __bf16 *kr = k.ptr + b * k.sb + h * k.sh + (int64_t)key * k.st + 8 * g;
-        const __bf16 *qr = q.ptr + b * q.sb + (int64_t)(h * G + min(n, G - 1)) * q.sh + 8 * g;
+        const __bf16 *qr = q.ptr + b * q.sb + qi * q.st + (int64_t)(h * G + min(n, G - 1)) * q.sh + 8 * g;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             a[ks] = load8(kr + 32 * ks);
             bq[ks] = load8(qr + 32 * ks);
         }
     }
-    // ---- value tile to LDS (rows past the query position as zeros: 0 * garbage must stay 0) -------
+    // ---- which of the block's 64 keys the query attends: bit r = key key0 + r ------------------------
+    // Causal: keys up to the query's own position.  Tree mask: every context key (before the drafted
+    // tokens), and drafted token j iff bit j of the query's mask word is set.
+    uint64_t allow;
+    if (!tree_mask) {
+        const int nv = L - key0;                         // >= 1
+        allow = nv >= 64 ? ~0ull : (1ull << nv) - 1ull;
+    } else {
+        const int l_ctx = L_all - dm.n_q;                // >= 0
+        const uint64_t mw = dm.n_q >= 64 ? mask_word : mask_word & ((1ull << dm.n_q) - 1ull);
+        const int sh = key0 - l_ctx;                     // block offset of the first drafted token, negated
+        if (sh >= 0) allow = sh < 64 ? mw >> sh : 0ull;
+        else allow = sh > -64 ? (mw << -sh) | ((1ull << -sh) - 1ull) : ~0ull;
+    }
+    // ---- value tile to LDS (masked rows as zeros: 0 * garbage must stay 0) ----------------------------
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int r = vr + 16 * i;
         uint4 x = vrow[i];
-        if (key0 + r > pos) x = uint4{0u, 0u, 0u, 0u};
+        if (!((allow >> r) & 1ull)) x = uint4{0u, 0u, 0u, 0u};
         *reinterpret_cast<uint2 *>(&Vs[r * kVsPitch + 8 * c8]) = uint2{x.x, x.y};
         *reinterpret_cast<uint2 *>(&Vs[r * kVsPitch + 8 * c8 + 4]) = uint2{x.z, x.w};
     }
@@ -400,17 +442,18 @@ __global__ __launch_bounds__(256) void decode_attn_partial_kernel(Dims dm, Tenso
     float x[4], mx = -INFINITY;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        x[j] = (key0 + 16 * wave + 4 * g + j <= pos) ? s[j] * dm.scale_log2 : -INFINITY;
+        x[j] = ((allow >> (16 * wave + 4 * g + j)) & 1ull) ? s[j] * dm.scale_log2 : -INFINITY;
         mx = fmaxf(mx, x[j]);
     }
     mx = xgroup_max(mx);
     if (g == 0) wmax[wave][n] = mx;
     __syncthreads();
-    const float m = fmaxf(fmaxf(wmax[0][n], wmax[1][n]), fmaxf(wmax[2][n], wmax[3][n]));   // finite: key0 <= pos
+    const float m = fmaxf(fmaxf(wmax[0][n], wmax[1][n]), fmaxf(wmax[2][n], wmax[3][n]));
+    const float m_sub = m == -INFINITY ? 0.f : m;       // -inf only when a tree mask hides the whole block
     float ps = 0.f;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const float p = fast_exp2(x[j] - m);
+        const float p = fast_exp2(x[j] - m_sub);
         ps += p;
         Ps[16 * wave + 4 * g + j][n] = p;
     }
@@ -437,7 +480,7 @@ __global__ __launch_bounds__(256) void decode_attn_partial_kernel(Dims dm, Tenso
         }
     }
     if (n < G) {                                         // lane: head n, channels 32w + 16ct + 4g .. +3
-        const int64_t pbase = (((int64_t)b * dm.Hq + h * G + n) * dm.topk + cidx);
+        const int64_t pbase = (((int64_t)bv * dm.Hq + h * G + n) * dm.topk + cidx);
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct)
             *reinterpret_cast<float4 *>(o_part + pbase * kHeadDim + 32 * wave + 16 * ct + 4 * g) =
@@ -448,12 +491,13 @@ __global__ __launch_bounds__(256) void decode_attn_partial_kernel(Dims dm, Tenso
 }
 
 // ---- attention, part 2: merge the k partials of every query head ---------------------------------
-// grid (Hq, B), 128 threads: thread = channel.  All partial loads are issued before the merge.
+// grid (Hq, B*n_q), 128 threads: thread = channel.  All partial loads are issued before the merge.
 __global__ __launch_bounds__(128) void decode_merge_kernel(Dims dm, const float *__restrict__ o_part,
                                                             const float2 *__restrict__ ml_part, Tensor out,
                                                             float *__restrict__ lse) {
-    const int hq = blockIdx.x, b = blockIdx.y, cch = threadIdx.x;
-    const int64_t pbase = ((int64_t)b * dm.Hq + hq) * dm.topk;
+    const int hq = blockIdx.x, bv = blockIdx.y, cch = threadIdx.x;
+    const int b = bv / dm.n_q, qi = bv - b * dm.n_q;
+    const int64_t pbase = ((int64_t)bv * dm.Hq + hq) * dm.topk;
     float2 ml[kMaxTopk];
     float ov[kMaxTopk];
 #pragma unroll
@@ -478,8 +522,8 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(Dims dm, const float 
         }
     }
     const float o = den > 0.f ? num / den : 0.f;
-    out.ptr[b * out.sb + (int64_t)hq * out.sh + cch] = (__bf16)o;
-    if (cch == 0) lse[(int64_t)b * dm.Hq + hq] = den > 0.f ? (M + fast_log2(den)) * kLn2 : -INFINITY;
+    out.ptr[b * out.sb + qi * out.st + (int64_t)hq * out.sh + cch] = (__bf16)o;
+    if (cch == 0) lse[(int64_t)bv * dm.Hq + hq] = den > 0.f ? (M + fast_log2(den)) * kLn2 : -INFINITY;
 }
 
 // ---- host side -------------------------------------------------------------------------------------
@@ -496,9 +540,10 @@ static DecodeSelLayout decode_sel_layout(const Dims &dm) {
     if (l.n_c_cap < 256) l.n_c_cap = 256;
     l.n_part = l.n_c_cap / 64;
     l.nb_cap = ((dm.max_seqlen + kBlock - 1) / kBlock + 63) / 64 * 64;
-    l.z_bytes = align256((size_t)dm.batch * dm.Hq * l.n_c_cap * sizeof(float));
-    l.part_bytes = align256((size_t)dm.batch * dm.Hq * l.n_part * sizeof(float2));
-    l.r_bytes = align256((size_t)dm.batch * dm.Hkv * l.nb_cap * sizeof(float));
+    const size_t rows = (size_t)dm.batch * dm.n_q;
+    l.z_bytes = align256(rows * dm.Hq * l.n_c_cap * sizeof(float));
+    l.part_bytes = align256(rows * dm.Hq * l.n_part * sizeof(float2));
+    l.r_bytes = align256(rows * dm.Hkv * l.nb_cap * sizeof(float));
     return l;
 }
 
@@ -517,16 +562,17 @@ int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seq
     float2 *part_c = reinterpret_cast<float2 *>(reinterpret_cast<char *>(ws) + l.z_bytes + l.part_bytes);
     float *R = reinterpret_cast<float *>(reinterpret_cast<char *>(ws) + l.z_bytes + 2 * l.part_bytes);
     timing_begin("decode_logits_kernel", stream);
-    hipLaunchKernelGGL(decode_logits_kernel, dim3(l.n_c_cap / 64, dm.Hkv, dm.batch), dim3(256), 0,
+    const int rows = dm.batch * dm.n_q;                              // <= 65535, checked by the C ABI
+    hipLaunchKernelGGL(decode_logits_kernel, dim3(l.n_c_cap / 64, dm.Hkv, rows), dim3(256), 0,
                        stream, dm, q, ck, seqlens, zbuf, part, part_c, l.n_c_cap, l.n_part);
     timing_end(stream);
     timing_begin("decode_scores_kernel", stream);
-    hipLaunchKernelGGL(decode_scores_kernel, dim3(l.n_c_cap / 256, dm.Hkv, dm.batch), dim3(320), 0, stream,
+    hipLaunchKernelGGL(decode_scores_kernel, dim3(l.n_c_cap / 256, dm.Hkv, rows), dim3(320), 0, stream,
                        dm, seqlens, zbuf, dm.rho > 1 ? part_c : part, l.n_c_cap, l.n_part, R, l.nb_cap);
     timing_end(stream);
     const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
     if (n_blocks > kPickThreads * kPickMaxVPT) return (int)hipErrorInvalidValue;   // rejected earlier by the C ABI
-    const dim3 grid(dm.batch * dm.Hkv), block(kPickThreads);
+    const dim3 grid(rows * dm.Hkv), block(kPickThreads);
     timing_begin("decode_pick_kernel", stream);
     if (n_blocks <= kPickThreads * 4)
         hipLaunchKernelGGL(decode_pick_kernel<4>, grid, block, 0, stream, dm, seqlens, R, l.nb_cap, block_idx);
@@ -541,23 +587,25 @@ int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seq
 }
 
 size_t attn_decode_ws_bytes(const Dims &dm) {
-    const size_t o = align256((size_t)dm.batch * dm.Hq * dm.topk * kHeadDim * sizeof(float));
-    const size_t ml = align256((size_t)dm.batch * dm.Hq * dm.topk * sizeof(float2));
+    const size_t o = align256((size_t)dm.batch * dm.n_q * dm.Hq * dm.topk * kHeadDim * sizeof(float));
+    const size_t ml = align256((size_t)dm.batch * dm.n_q * dm.Hq * dm.topk * sizeof(float2));
     return o + ml;
 }
 
 int launch_attn_decode(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32_t *seqlens,
-                       const int32_t *block_idx, Tensor out, float *lse, void *ws, hipStream_t stream) {
+                       const int32_t *block_idx, const uint64_t *tree_mask, Tensor out, float *lse, void *ws,
+                       hipStream_t stream) {
     if (dm.batch <= 0) return 0;
-    const size_t o_bytes = align256((size_t)dm.batch * dm.Hq * dm.topk * kHeadDim * sizeof(float));
+    const int rows = dm.batch * dm.n_q;
+    const size_t o_bytes = align256((size_t)rows * dm.Hq * dm.topk * kHeadDim * sizeof(float));
     float *o_part = reinterpret_cast<float *>(ws);
     float2 *ml_part = reinterpret_cast<float2 *>(reinterpret_cast<char *>(ws) + o_bytes);
     timing_begin("decode_attn_partial_kernel", stream);
-    hipLaunchKernelGGL(decode_attn_partial_kernel, dim3(dm.topk, dm.Hkv, dm.batch), dim3(256), 0, stream,
-                       dm, q, k, v, seqlens, block_idx, o_part, ml_part);
+    hipLaunchKernelGGL(decode_attn_partial_kernel, dim3(dm.topk, dm.Hkv, rows), dim3(256), 0, stream,
+                       dm, q, k, v, seqlens, block_idx, tree_mask, o_part, ml_part);
     timing_end(stream);
     timing_begin("decode_merge_kernel", stream);
-    hipLaunchKernelGGL(decode_merge_kernel, dim3(dm.Hq, dm.batch), dim3(128), 0, stream, dm, o_part,
+    hipLaunchKernelGGL(decode_merge_kernel, dim3(dm.Hq, rows), dim3(128), 0, stream, dm, o_part,
                        ml_part, out, lse);
     timing_end(stream);
     return (int)hipGetLastError();

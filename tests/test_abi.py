@@ -123,6 +123,29 @@ def test_append_kv_validation(lib):
     assert lib.infllmv2_append_kv(P, T, T, T, T, None, FAKE, 0, 4096, None) == 0         # empty batch: nothing to do
 
 
+def test_verify_validation(lib):
+    prm, t = good_params(), tensor()
+    P, T = ctypes.byref(prm), ctypes.byref(t)
+    ws = lib.infllmv2_verify_workspace_bytes
+    assert ws(binding.OP_SELECT_VERIFY, P, 2, 4096, 8) == 8 * lib.infllmv2_workspace_bytes(binding.OP_SELECT_DECODE, P, 2, 4096)
+    assert ws(binding.OP_ATTN_VERIFY, P, 1, 4096, 1) == lib.infllmv2_workspace_bytes(binding.OP_ATTN_DECODE, P, 1, 4096)
+    assert ws(binding.OP_ATTN_VERIFY, P, 1, 4096, 0) == 0 and ws(binding.OP_ATTN_VERIFY, P, 1, 4096, 65) == 0
+    assert ws(binding.OP_SELECT_DECODE, P, 1, 4096, 4) == 0                              # not a verify stage
+    sel = lambda n, w=FAKE, wb=1 << 40: lib.infllmv2_select_blocks_verify(P, T, T, FAKE, 1, 4096, n, FAKE, w, wb, None)
+    assert sel(0) == INVALID and sel(-3) == INVALID
+    assert sel(65) == UNSUPPORTED                                                        # one uint64 word per token
+    assert sel(8, None, 0) == WORKSPACE
+    assert lib.infllmv2_select_blocks_verify(P, T, T, FAKE, 16384, 4096, 4, FAKE, FAKE, 1 << 40, None) == UNSUPPORTED
+    att = lambda n, mask=None, w=FAKE, wb=1 << 40: lib.infllmv2_sparse_attn_verify(
+        P, T, T, T, FAKE, 1, 4096, n, mask, FAKE, T, FAKE, w, wb, None)
+    assert att(0) == INVALID and att(65) == UNSUPPORTED
+    assert att(4, FAKE + 4) == INVALID                                                   # mask words 8-byte aligned
+    assert att(4, None, None, 0) == WORKSPACE
+    app = lambda n, sl=FAKE: lib.infllmv2_append_kv_verify(P, T, T, T, T, None, sl, 1, 4096, n, None)
+    assert app(0) == INVALID and app(65) == UNSUPPORTED and app(4, None) == INVALID
+    assert lib.infllmv2_append_kv_verify(P, T, T, T, T, None, FAKE, 0, 4096, 4, None) == 0
+
+
 def test_binding_fails_loudly_without_library(tmp_path):
     with pytest.raises(binding.InfLLMv2Error):
         binding.load_library(str(tmp_path / "missing.so"))

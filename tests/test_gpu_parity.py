@@ -336,3 +336,127 @@ def test_decode_steps_with_append_and_incremental_compress(fused):
                 assert np.abs(out[0].double().cpu().numpy() - wo).max() <= OUT_TOL
                 assert lse_err(lse[0].double().cpu().numpy(), wl[0]) <= 1.0
     assert torch.equal(kd.view(torch.int16).cpu(), torch.from_numpy(k_np.view(np.int16)))
+
+
+# ------------------------------------------------------------------ draft verification (section 4.1)
+
+def tree_masks(rng, n, kind):
+    """uint64 mask words of n drafted tokens: 'chain', a random 'tree' (node 0 the root, each word
+    the node's ancestors and itself) or 'holes' (a tree with some words emptied or cut down)."""
+    if kind == "chain":
+        return np.array([(1 << (t + 1)) - 1 for t in range(n)], np.uint64)
+    parent = [-1] + [int(rng.integers(0, t)) for t in range(1, n)]
+    words = []
+    for t in range(n):
+        w, a = 0, t
+        while a >= 0:
+            w |= 1 << a
+            a = parent[a]
+        words.append(w)
+    if kind == "holes":
+        for t in range(0, n, 3):
+            words[t] = 0 if t % 2 else words[t] & ~(1 << t)          # nothing / no self bit
+        words[n - 1] |= 1 << (n - 1)
+        if n > 2:
+            words[1] |= 1 << (n - 1)                                  # a later draft token: allowed inside selected blocks
+    return np.array(words, np.uint64)
+
+
+def dev_masks(m):
+    return torch.from_numpy(np.ascontiguousarray(m).view(np.int64)).cuda()
+
+
+@pytest.mark.parametrize("seqlens,n,Hq,Hkv,topk,kind", [
+    ([1500, 700, 69, 8, 3, 0], 8, 32, 2, 16, "chain"),
+    ([2100, 16, 130, 1029], 16, 32, 2, 16, "tree"),
+    ([900, 64, 100, 4160], 64, 16, 2, 8, "tree"),
+    ([333, 1], 1, 8, 2, 4, "tree"),
+    ([1300, 40, 24, 200], 24, 32, 2, 16, "holes"),
+    ([520, 513], 5, 4, 1, 6, "holes"),
+])
+def test_verify_select_and_attn(seqlens, n, Hq, Hkv, topk, kind):
+    print("case verify", seqlens, n, Hq, Hkv, topk, kind, flush=True)
+    prm = binding.Params(Hq, Hkv, topk=topk)
+    oprm = oracle_params(prm)
+    q, k, v, T = make_batch(41, seqlens, Hq, Hkv, n_planted=4, heavy=(1,))
+    B = len(seqlens)
+    rng = np.random.default_rng(5)
+    qn = np.zeros((B, n, Hq, 128), np.uint16)
+    masks = np.zeros((B, n), np.uint64)
+    for b, l in enumerate(seqlens):
+        masks[b] = tree_masks(rng, n, kind)
+        if l >= n:
+            qn[b] = q[b, l - n:l]
+    qd, kd, vd, sl = to_dev(qn), to_dev(k), to_dev(v), dev_i32(seqlens)
+    ck = binding.compress_keys(prm, kd, sl, T)
+    idx = binding.select_blocks_verify(prm, qd, ck, sl, T)
+    torch.cuda.synchronize()
+    idx_np = idx.cpu().numpy()
+    assert idx_np.shape == (B, Hkv, n, topk)
+    ckb = to_bits(ck)
+    idx_ref = np.full((B, Hkv, n, topk), -1, np.int32)
+    want = [None] * B
+    for b, l in enumerate(seqlens):
+        if l < n:                                                     # skipped as a whole
+            assert np.all(idx_np[b] == -1)
+            continue
+        pos = np.arange(l - n, l, dtype=np.int32)
+        n_c = ref.num_kernels(l, 32, 16)
+        ib, margins, R = ref.select_blocks(qn[b], ckb[b, :, :n_c], pos, oprm, want_scores=True)
+        rows, e, nt, hard = compare_selection(idx_np[b], ib, margins, R)
+        assert not hard, (b, hard)
+        idx_ref[b] = ib
+        want[b] = ref.sparse_attn_tree(qn[b], k[b, :, :l], v[b, :, :l], ib, masks[b], l - n, oprm)
+        if kind == "chain":                                           # the chain is the causal prefill rows
+            wc = ref.sparse_attn(qn[b], k[b, :, :l], v[b, :, :l], pos, ib, oprm)
+            assert np.array_equal(want[b][0], wc[0]) and np.array_equal(want[b][1], wc[1])
+    idx_d = torch.from_numpy(idx_ref).cuda()
+    out, lse = binding.sparse_attn_verify(prm, qd, kd, vd, sl, T, idx_d, tree_mask=dev_masks(masks))
+    torch.cuda.synchronize()
+    if kind == "chain":                                               # no mask = the chain, bit for bit
+        out2, lse2 = binding.sparse_attn_verify(prm, qd, kd, vd, sl, T, idx_d)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), out2.view(torch.int16)) and torch.equal(lse, lse2)
+    for b, l in enumerate(seqlens):
+        o, ls = out[b].double().cpu().numpy(), lse[b].double().cpu().numpy()
+        if l < n:
+            assert np.all(o == 0) and np.all(np.isneginf(ls))
+            continue
+        wo, wl = want[b]
+        empty = np.isneginf(wl)
+        assert np.array_equal(np.isneginf(ls), empty)                 # rows whose mask hides every key
+        assert np.all(o[empty] == 0)
+        eo = np.abs(o - wo).max()
+        el = lse_err(ls[~empty], wl[~empty])
+        print("seq %d len %d: max|dO| %.3e LSE err/tol %.3f, %d empty rows" % (b, l, eo, el, int(empty.sum())),
+              flush=True)
+        assert eo <= OUT_TOL and el <= 1.0
+
+
+def test_verify_append_writes_rows_and_completed_kernels():
+    print("case verify append", flush=True)
+    Hkv, n = 2, 12
+    prm = binding.Params(32, Hkv)
+    seqlens = [1000, 44, 32, 12, 7, 0]                                # 7 and 0: shorter than n, untouched
+    q, k, v, T = make_batch(43, seqlens, 32, Hkv)
+    B = len(seqlens)
+    k0, v0 = k.copy(), v.copy()
+    kn = np.zeros((B, Hkv, n, 128), np.uint16)
+    vn = np.zeros((B, Hkv, n, 128), np.uint16)
+    for b, l in enumerate(seqlens):
+        if l >= n:
+            kn[b], vn[b] = k[b, :, l - n:l], v[b, :, l - n:l]
+            k0[b, :, l - n:l] = 0
+            v0[b, :, l - n:l] = 0
+    kd, vd = to_dev(k0), to_dev(v0)
+    before = dev_i32([max(l - n, 0) if l >= n else l for l in seqlens])
+    n_cap = binding.num_kernels(T, prm) + 2
+    ck = torch.full((B, Hkv, n_cap, 128), 7.0, dtype=torch.bfloat16, device="cuda")
+    binding.compress_keys(prm, kd, before, T, ck=ck)
+    binding.append_kv_verify(prm, to_dev(kn), to_dev(vn), kd, vd, dev_i32(seqlens), T, ck=ck)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(kd), k) and np.array_equal(to_bits(vd), v)
+    got = to_bits(ck)
+    for b, l in enumerate(seqlens):
+        _, w = ref.compress_keys(k[b, :, :l], oracle_params(prm))
+        assert np.array_equal(got[b, :, :w.shape[1]], w), (b, l)

@@ -239,6 +239,89 @@ def bench_decode(cfg_index, steps):
             "contexts_at_end": [int(v) for v in sl.cpu().numpy()], "launch": launch}
 
 
+def bench_verify(cfg_index, n_draft, steps):
+    """Draft-verification workload (section 4.1): per step, n_draft drafted tokens are appended
+    (+ the semantic kernels they complete), each selects its blocks, and all attend under a random
+    tree mask; the context grows by n_draft per step (every draft accepted)."""
+    import torch
+    from paper_2506_07900_amd import binding, synth
+
+    cfg = synth.CONFIGS[cfg_index]
+    n = n_draft
+    log("[bench] generating %s inputs for draft verification (%d steps of %d tokens)" % (cfg.name, steps, n))
+    x = synth.make_decode(cfg, steps=2 * steps * n)        # the graph is replayed once untimed
+    prm = binding.Params(cfg.n_q_heads, cfg.n_kv_heads, topk=cfg.topk)
+    Hq, Hkv, d, m, B = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.block_size, cfg.batch
+
+    def dev(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+    cap = x.capacity
+    kc, vc = dev(x.k_cache), dev(x.v_cache)
+    S = steps
+    qs = dev(x.q_steps[:S * n].reshape(S, n, B, Hq, d).transpose(0, 2, 1, 3, 4))        # [S, B, n, Hq, d]
+    ks = dev(x.k_steps[:S * n].reshape(S, n, B, Hkv, d).transpose(0, 2, 3, 1, 4))       # [S, B, Hkv, n, d]
+    vs = dev(x.v_steps[:S * n].reshape(S, n, B, Hkv, d).transpose(0, 2, 3, 1, 4))
+    rng = np.random.Generator(np.random.PCG64(cfg.seed + 77))
+    words = np.zeros((S, B, n), np.uint64)
+    for s_ in range(S):
+        for b in range(B):
+            parent = [-1] + [int(rng.integers(0, t)) for t in range(1, n)]
+            for t in range(n):
+                w, a = 0, t
+                while a >= 0:
+                    w |= 1 << a
+                    a = parent[a]
+                words[s_, b, t] = w
+    masks = torch.from_numpy(words.view(np.int64)).cuda()
+    sl0 = torch.tensor(x.seqlens0, dtype=torch.int32, device="cuda")
+    ck = torch.zeros((B, Hkv, binding.num_kernels(cap, prm), d), dtype=torch.bfloat16, device="cuda")
+    binding.compress_keys(prm, kc, sl0, cap, ck=ck)
+    idx = torch.full((B, Hkv, n, cfg.topk), -1, dtype=torch.int32, device="cuda")
+    out = torch.zeros((B, n, Hq, d), dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros((B, n, Hq), dtype=torch.float32, device="cuda")
+    ws_sel = torch.empty(binding.verify_workspace_bytes(binding.OP_SELECT_VERIFY, prm, B, cap, n), dtype=torch.uint8, device="cuda")
+    ws_att = torch.empty(binding.verify_workspace_bytes(binding.OP_ATTN_VERIFY, prm, B, cap, n), dtype=torch.uint8, device="cuda")
+
+    def step(s_, sl):
+        binding.append_kv_verify(prm, ks[s_], vs[s_], kc, vc, sl, cap, ck=ck)
+        binding.select_blocks_verify(prm, qs[s_], ck, sl, cap, block_idx=idx, workspace=ws_sel)
+        binding.sparse_attn_verify(prm, qs[s_], kc, vc, sl, cap, idx, tree_mask=masks[s_], out=out, lse=lse,
+                                   workspace=ws_att)
+
+    # lengths per captured step, advanced by S*n at the end of the graph
+    sl_tab = (sl0[None, :] + n * torch.arange(1, S + 1, dtype=torch.int32, device="cuda")[:, None]).contiguous()
+    step(0, sl_tab[0])                                       # eager warm-up of the three entry points
+    torch.cuda.synchronize()
+    binding.timing_enable(True)                              # per-kernel durations of one eager step
+    step(0, sl_tab[0])
+    kernels_us = {}
+    for name, ms in binding.timing_read():
+        kernels_us[name] = kernels_us.get(name, 0.0) + ms * 1e3
+    binding.timing_enable(False)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(S):
+                step(i, sl_tab[i])
+            sl_tab.add_(S * n)
+    torch.cuda.synchronize()
+    graph.replay()                                           # untimed: contexts L0 .. L0 + S*n
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    graph.replay()                                           # timed: contexts L0 + S*n .. L0 + 2*S*n
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    us = (t1 - t0) * 1e6 / S
+    return {"workload": cfg.name, "batch": B, "n_draft": n, "steps": S, "us_per_step": us,
+            "us_per_draft_token": us / (B * n), "kernels_us_eager": kernels_us,
+            "tree": "random tree per step, node 0 the root",
+            "contexts_at_end": [int(v) for v in (sl_tab[0] - n).cpu().numpy()],
+            "launch": "HIP graph of %d consecutive verification steps, replayed once untimed and once timed" % S}
+
+
 def measured_peaks():
     """What this machine sustains on the two roofline resources, measured with the library's probe
     kernels: dense bf16 MFMA rate and HBM read rate over a 2 GiB buffer (best of 5 launches)."""
@@ -303,6 +386,8 @@ def main():
                          "(ratio s_c/s); 1 = the exact two-pass selection the headline metric is quoted on")
     ap.add_argument("--decode-steps", type=int, default=1000)
     ap.add_argument("--ragged-steps", type=int, default=200)
+    ap.add_argument("--verify-draft", type=int, default=16, help="drafted tokens per verification step (0: skip the leg)")
+    ap.add_argument("--verify-steps", type=int, default=50)
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=32768)
@@ -364,6 +449,10 @@ def main():
             line["decode_ragged_b8"] = bench_decode(4, args.ragged_steps)
             line["decode_ragged_b8"]["frac_measured_hbm_algorithmic"] = (
                 line["decode_ragged_b8"]["algorithmic_GBs"] / mp["hbm_read_GBs"])
+        if args.verify_draft > 0:
+            line["verify"] = bench_verify(3, args.verify_draft, args.verify_steps)
+            line["verify"]["speedup_per_token_vs_decode"] = (
+                line["decode"]["us_per_token"] / line["verify"]["us_per_draft_token"])
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a sample")
         line["cpu_baseline"] = cpu_baseline(x, cfg, args.cpu_rows if args.workload == "prefill_32k" else min(args.cpu_rows, 8192),

@@ -11,10 +11,11 @@
 // of a thread before using any of them.
 //
 // Selection (the softmax needs the log-sum-exp over ALL visible kernels before any score exists):
-//   decode_logits_kernel   64 kernels per workgroup: MFMA logits -> scratch, one partial
-//                          (max, sum) per head and workgroup
-//   decode_scores_kernel   256 kernels (64 blocks) per workgroup: merges the partials into the
-//                          log-sum-exp, group-mean scores, 5/4 max-pool -> block scores
+//   decode_logits_kernel   64 kernels per workgroup: MFMA logits, one partial (max, sum) per head
+//                          and workgroup
+//   decode_scores_*kernel  merges the partials into the log-sum-exp, group-mean scores, 5/4 max-pool
+//                          -> block scores; the logits come from scratch (plain decode) or are
+//                          computed again on the matrix cores (verification)
 //   decode_pick_kernel     two-level top-k of the block-score row
 // Attention: one workgroup per selected block (split-KV) writes an unnormalised partial
 // (o, max, sum); decode_merge_kernel combines the k partials per query head.
@@ -41,82 +42,160 @@ __device__ inline int query_row(const Dims &dm, const int32_t *__restrict__ seql
     return L_all < dm.n_q ? 0 : L_all - (dm.n_q - 1 - qi);
 }
 
-// ---- selection, part 1 ------------------------------------------------------------------------
-// grid (n_c_cap/64, Hkv, B); wave w of a workgroup owns kernels 64*bx + 16*w .. +15.
+// Query operands of parts 1 and 2.  MFMA operand layout: lane (n, g) holds head n, channels
+// 32*ks + 8*g .. +7.  One query per workgroup: straight from memory.  Several (verification): every
+// wave needs the same rows and every workgroup of the launch the same few cache lines, so the
+// workgroup fetches them once into LDS (row pitch 272 bytes: conflict-free 16-byte reads).
+constexpr int kQsPitch = kHeadDim + 8;
+template <int kQT>
+__device__ inline void load_query_operands(const Dims &dm, const Tensor &q, int b, int h, int qi0, uint16_t *qs,
+                                           bf16x8 (&bq)[kQT][4]) {
+    const int lane = threadIdx.x & 63, n = lane & 15, g = lane >> 4;
+    const int G = dm.G;
+    if constexpr (kQT == 1) {
+        const __bf16 *qr = q.ptr + b * q.sb + min(qi0, dm.n_q - 1) * q.st + (int64_t)(h * G + min(n, G - 1)) * q.sh + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) bq[0][ks] = load8(qr + 32 * ks);
+    } else {
+        const int row = threadIdx.x >> 4, c16 = threadIdx.x & 15;     // 256 threads: 16 heads x 16 chunks of 16 bytes
+        uint4 x[kQT];
+#pragma unroll
+        for (int t = 0; t < kQT; ++t)
+            x[t] = *reinterpret_cast<const uint4 *>(q.ptr + b * q.sb + min(qi0 + t, dm.n_q - 1) * q.st +
+                                                    (int64_t)(h * G + min(row, G - 1)) * q.sh + 8 * c16);
+#pragma unroll
+        for (int t = 0; t < kQT; ++t) *reinterpret_cast<uint4 *>(&qs[(t * 16 + row) * kQsPitch + 8 * c16]) = x[t];
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < kQT; ++t)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                bq[t][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&qs[(t * 16 + n) * kQsPitch + 32 * ks + 8 * g]));
+    }
+}
+
+// ---- selection, parts 1 and 2 -------------------------------------------------------------------
+// Both parts score semantic kernels against kQT consecutive query tokens of one sequence on the
+// matrix cores.  kQT = 1 is plain decode; verification uses kQT = kVerifyQT.  A workgroup of part 1
+// covers tiles_per_wave tiles of 16 kernels per wave, one of part 2 tiles_per_wave2 (plus one halo
+// tile): one tile per wave keeps a lone decode step spread over many workgroups; two amortise the
+// query rows and the partials that every workgroup of a verification step has to fetch (measured at
+// 128K context: one, two and four tiles per wave differ by under 10 % for 4 to 64 drafted tokens).
+constexpr int kVerifyQT = 4;
+__host__ __device__ constexpr int tiles_per_wave(int qt) { return qt == 1 ? 1 : 2; }    // part 1
+__host__ __device__ constexpr int tiles_per_wave2(int qt) { return qt == 1 ? 1 : 2; }   // part 2
+
+// length of the cache up to and including query token qi of sequence b (0: no such row)
+__device__ inline int row_len(const Dims &dm, int L_all, int qi) {
+    return (L_all < dm.n_q || qi >= dm.n_q) ? 0 : L_all - (dm.n_q - 1 - qi);
+}
+
+// ---- part 1: partial (max, sum) of the relevance softmax ---------------------------------------------
+// grid (n_c_cap / (64*kTW), Hkv, B * ceil(n_q/kQT)); wave w owns kernels chunk + 16*kTW*w .. +16*kTW-1.
 // Z^T = CK . Q^T: lane = query head, 4 accumulator entries = 4 consecutive kernels.
+template <int kQT>
 __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, Tensor ck,
                                                              const int32_t *__restrict__ seqlens,
-                                                             float *__restrict__ zbuf,
+                                                             float *__restrict__ zbuf, int32_t n_c_cap,
                                                              float2 *__restrict__ part,
-                                                             float2 *__restrict__ part_c, int32_t n_c_cap,
-                                                             int32_t n_part) {
-    __shared__ float2 wpart[4][16];
-    __shared__ float2 wpart_c[2][16];
-    const int bv = blockIdx.z, h = blockIdx.y;
-    int b, qi;
-    const int L = query_row(dm, seqlens, bv, b, qi);
-    const int n_vis = num_kernels(L);                 // the query sits at L-1: n_c((L-1)+1)
-    if ((int)blockIdx.x * 64 >= n_vis) return;        // uniform over the workgroup
+                                                             float2 *__restrict__ part_c, int32_t n_part) {
+    constexpr int kTW = tiles_per_wave(kQT), kChunk = 64 * kTW;
+    __shared__ float2 wpart[kQT][4][16];
+    __shared__ float2 wpart_c[kQT][4][16];
+    __shared__ __align__(16) uint16_t qs[kQT > 1 ? kQT * 16 * kQsPitch : 8];
+    const int h = blockIdx.y;
+    const int n_qt = (dm.n_q + kQT - 1) / kQT;        // query tiles per sequence
+    const int b = kQT == 1 ? blockIdx.z : blockIdx.z / n_qt;   // kQT = 1 is only launched with n_q = 1
+    const int qi0 = (blockIdx.z - b * n_qt) * kQT;
+    const int L_all = clamp_len(seqlens[b], dm.max_seqlen);
+    int n_vis[kQT], n_vis_max = 0;                    // query slot t sits at L-1: n_c((L-1)+1); 0 = no such row
+#pragma unroll
+    for (int t = 0; t < kQT; ++t) {
+        n_vis[t] = num_kernels(row_len(dm, L_all, qi0 + t));
+        n_vis_max = max(n_vis_max, n_vis[t]);
+    }
+    if ((int)blockIdx.x * kChunk >= n_vis_max) return;    // uniform over the workgroup
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, g = lane >> 4;
-    const int jh0 = blockIdx.x * 64 + wave * 16;
+    const int jw = blockIdx.x * kChunk + wave * 16 * kTW; // first kernel of this wave
     const int G = dm.G;
-    f32x4 z = {0.f, 0.f, 0.f, 0.f};
-    const __bf16 *ckr = ck.ptr + b * ck.sb + h * ck.sh + (int64_t)(jh0 + n) * ck.st + 8 * g;
-    const __bf16 *qr = q.ptr + b * q.sb + qi * q.st + (int64_t)(h * G + n) * q.sh + 8 * g;
-    bf16x8 a[4], bq[4];
+    bf16x8 a[kTW][4], bq[kQT][4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        a[ks] = zero8();
-        bq[ks] = zero8();
-        if (jh0 + n < n_vis) a[ks] = load8(ckr + 32 * ks);
-        if (n < G) bq[ks] = load8(qr + 32 * ks);
+    for (int i = 0; i < kTW; ++i) {
+        const __bf16 *ckr = ck.ptr + b * ck.sb + h * ck.sh + (int64_t)(jw + 16 * i + n) * ck.st + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            a[i][ks] = zero8();
+            if (jw + 16 * i + n < n_vis_max) a[i][ks] = load8(ckr + 32 * ks);
+        }
     }
+    load_query_operands<kQT>(dm, q, b, h, qi0, qs, bq);   // heads >= G repeat head G-1: their columns are never used
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) z = mfma16(a[ks], bq[ks], z);
-    float mx = -INFINITY;
-    float x[4];
+    for (int t = 0; t < kQT; ++t) {
+        float x[kTW][4], mx = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        x[j] = z[j] * dm.scale_log2;
-        if (jh0 + 4 * g + j >= n_vis) x[j] = -INFINITY;
-        mx = fmaxf(mx, x[j]);
+        for (int i = 0; i < kTW; ++i) {
+            f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) z = mfma16(a[i][ks], bq[t][ks], z);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                x[i][j] = z[j] * dm.scale_log2;
+                if (jw + 16 * i + 4 * g + j >= n_vis[t]) x[i][j] = -INFINITY;
+                mx = fmaxf(mx, x[i][j]);
+            }
+        }
+        mx = xgroup_max(mx);
+        const float m_use = mx == -INFINITY ? 0.f : mx;
+        float sm = 0.f;
+#pragma unroll
+        for (int i = 0; i < kTW; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sm += fast_exp2(x[i][j] - m_use);
+        sm = xgroup_sum(sm);
+        if (g == 0) wpart[t][wave][n] = float2{mx, sm};
+        if constexpr (kQT == 1) {                     // plain decode keeps the logits for part 2
+#pragma unroll
+            for (int i = 0; i < kTW; ++i)
+                if (n < G && jw + 16 * i < n_vis[0])
+                    *reinterpret_cast<float4 *>(zbuf + (((int64_t)b * dm.Hkv + h) * G + n) * n_c_cap + jw + 16 * i + 4 * g) =
+                        float4{x[i][0], x[i][1], x[i][2], x[i][3]};
+        }
     }
-    mx = xgroup_max(mx);
-    const float m_use = mx == -INFINITY ? 0.f : mx;
-    float s = 0.f;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) s += fast_exp2(x[j] - m_use);
-    s = xgroup_sum(s);
-    if (n < G && jh0 < n_vis) {
-        float *zr = zbuf + (((int64_t)bv * dm.Hkv + h) * G + n) * n_c_cap + jh0 + 4 * g;
-        *reinterpret_cast<float4 *>(zr) = float4{x[0], x[1], x[2], x[3]};
-    }
-    if (g == 0) wpart[wave][n] = float2{mx, s};
     __syncthreads();
-    if (threadIdx.x < 16 && (int)threadIdx.x < G) {   // merge the four waves: one partial per head
-        float M = -INFINITY;
+    if (threadIdx.x < 16 * kQT) {                     // merge the four waves: one partial per head and query
+        const int t = threadIdx.x >> 4, head = threadIdx.x & 15;
+        if (head < G && qi0 + t < dm.n_q) {
+            float M = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) M = fmaxf(M, wpart[w][threadIdx.x].x);
-        const float mu = M == -INFINITY ? 0.f : M;
-        float S = 0.f;
+            for (int w = 0; w < 4; ++w) M = fmaxf(M, wpart[t][w][head].x);
+            const float mu = M == -INFINITY ? 0.f : M;
+            float S = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) S += wpart[w][threadIdx.x].y * fast_exp2(wpart[w][threadIdx.x].x - mu);
-        part[(((int64_t)bv * dm.Hkv + h) * G + threadIdx.x) * n_part + blockIdx.x] = float2{M, S};
+            for (int w = 0; w < 4; ++w) S += wpart[t][w][head].y * fast_exp2(wpart[t][w][head].x - mu);
+            const int64_t bv = (int64_t)b * dm.n_q + qi0 + t;
+            part[((bv * dm.Hkv + h) * G + head) * n_part + blockIdx.x] = float2{M, S};
+        }
     }
     // Approximate log-sum-exp ("Efficient Top-K Implementation", last paragraph): the same
-    // partial (max, sum) over the coarse kernels 64/rho * bx .. of this chunk, each the bf16 mean
+    // partial (max, sum) over the coarse kernels kChunk/rho * bx .. of this chunk, each the bf16 mean
     // of its rho fine kernels rho*c + 2r (exact sum in fp64, one rounding).
     if (dm.rho > 1) {                                 // uniform over the launch
-        const int tiles_c = 4 / dm.rho;               // 16-kernel tiles of coarse kernels per workgroup
-        const int n_vis_c = num_coarse(n_vis, dm.rho);
-        if (wave < tiles_c) {
-            const int c0 = blockIdx.x * (64 / dm.rho) + wave * 16, cc = c0 + n;
+        const int tiles_c = 4 * kTW / dm.rho;         // 16-kernel tiles of coarse kernels per workgroup
+        const int n_vis_c_max = num_coarse(n_vis_max, dm.rho);
+        float Mc[kQT], Sc[kQT];                       // running partial of this wave, reduced over the wave
+#pragma unroll
+        for (int t = 0; t < kQT; ++t) {
+            Mc[t] = -INFINITY;
+            Sc[t] = 0.f;
+        }
+        for (int tc = wave; tc < tiles_c; tc += 4) {
+            const int c0 = blockIdx.x * (kChunk / dm.rho) + tc * 16, cc = c0 + n;
             bf16x8 ac[4];
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 ac[ks] = zero8();
-                if (cc < n_vis_c) {
+                if (cc < n_vis_c_max) {
                     double acc[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) acc[e] = 0.0;
@@ -136,40 +215,178 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, T
                     ac[ks] = __builtin_bit_cast(bf16x8, uint4{w[0], w[1], w[2], w[3]});
                 }
             }
-            f32x4 zc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) zc = mfma16(ac[ks], bq[ks], zc);
-            float mc = -INFINITY, xc[4];
+            for (int t = 0; t < kQT; ++t) {
+                const int n_vis_c = num_coarse(n_vis[t], dm.rho);
+                f32x4 zc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                xc[j] = c0 + 4 * g + j < n_vis_c ? zc[j] * dm.scale_log2 : -INFINITY;
-                mc = fmaxf(mc, xc[j]);
+                for (int ks = 0; ks < 4; ++ks) zc = mfma16(ac[ks], bq[t][ks], zc);
+                float mc = -INFINITY, xc[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    xc[j] = c0 + 4 * g + j < n_vis_c ? zc[j] * dm.scale_log2 : -INFINITY;
+                    mc = fmaxf(mc, xc[j]);
+                }
+                mc = xgroup_max(mc);
+                const float Mn = fmaxf(Mc[t], mc), mu = Mn == -INFINITY ? 0.f : Mn;
+                float sc = 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sc += fast_exp2(xc[j] - mu);
+                sc = xgroup_sum(sc);
+                Sc[t] = Sc[t] * fast_exp2(Mc[t] - mu) + sc;
+                Mc[t] = Mn;
             }
-            mc = xgroup_max(mc);
-            const float mcu = mc == -INFINITY ? 0.f : mc;
-            float sc = 0.f;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) sc += fast_exp2(xc[j] - mcu);
-            sc = xgroup_sum(sc);
-            if (g == 0) wpart_c[wave][n] = float2{mc, sc};
         }
+#pragma unroll
+        for (int t = 0; t < kQT; ++t)
+            if (g == 0) wpart_c[t][wave][n] = float2{Mc[t], Sc[t]};
         __syncthreads();
-        if (threadIdx.x < 16 && (int)threadIdx.x < G) {
-            float M = -INFINITY;
-            for (int w = 0; w < tiles_c; ++w) M = fmaxf(M, wpart_c[w][threadIdx.x].x);
-            const float mu = M == -INFINITY ? 0.f : M;
-            float S = 0.f;
-            for (int w = 0; w < tiles_c; ++w) S += wpart_c[w][threadIdx.x].y * fast_exp2(wpart_c[w][threadIdx.x].x - mu);
-            part_c[(((int64_t)bv * dm.Hkv + h) * G + threadIdx.x) * n_part + blockIdx.x] = float2{M, S};
+        if (threadIdx.x < 16 * kQT) {
+            const int t = threadIdx.x >> 4, head = threadIdx.x & 15;
+            if (head < G && qi0 + t < dm.n_q) {
+                float M = -INFINITY;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) M = fmaxf(M, wpart_c[t][w][head].x);
+                const float mu = M == -INFINITY ? 0.f : M;
+                float S = 0.f;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) S += wpart_c[t][w][head].y * fast_exp2(wpart_c[t][w][head].x - mu);
+                const int64_t bv = (int64_t)b * dm.n_q + qi0 + t;
+                part_c[((bv * dm.Hkv + h) * G + head) * n_part + blockIdx.x] = float2{M, S};
+            }
         }
     }
 }
 
-// ---- selection, part 2 ------------------------------------------------------------------------
-// grid (ceil(n_c_cap/256), Hkv, B), 320 threads.  Thread t <= 256 scores kernel 256*bx - 1 + t
+// ---- part 2, several queries per sequence: block scores ----------------------------------------------
+// grid (nb_cap / (16*kTW), Hkv, B * ceil(n_q/kQT)), 256 threads (every block has a workgroup, also a
+// last one too short to hold a complete kernel).  Workgroup bx pools blocks
+// 16*kTW*bx .. +16*kTW-1 of kQT consecutive query tokens; block j needs kernels 4j-1 .. 4j+3, so the
+// workgroup scores 4*kTW+1 tiles of 16 kernels starting one tile before its chunk (of that halo tile
+// only the last kernel is used).  The logits are computed again rather than kept from part 1: a
+// kernel's output has to reach memory before the next kernel starts, and megabytes of logits per
+// query cost more than the matrix-core work to redo them.
+// Z = Q . CK^T: lane = kernel (column), 4 accumulator entries = 4 consecutive heads.  A lane adds its 4
+// heads; the four 16-lane groups leave their sums side by side in LDS and the pooling adds them, so
+// no cross-lane traffic sits between the matrix cores and the scores.
+template <int kQT>
+__global__ __launch_bounds__(256) void decode_scores_kernel(Dims dm, Tensor q, Tensor ck,
+                                                             const int32_t *__restrict__ seqlens,
+                                                             const float2 *__restrict__ part, int32_t n_part,
+                                                             float *__restrict__ R, int32_t nb_cap) {
+    constexpr int kTW = tiles_per_wave2(kQT), kChunk = 64 * kTW, kTiles = 4 * kTW + 1;
+    constexpr int kChunk1 = 64 * tiles_per_wave(kQT);  // kernels per partial of part 1
+    constexpr int kLanesPerPair = 256 / (16 * kQT);   // lanes that merge the partials of one (query, head)
+    constexpr int kMaxPartsPerLane = 16384 / kChunk1 / kLanesPerPair;   // contexts up to 262144 tokens
+    __shared__ __align__(16) float lse_h[kQT][16];
+    __shared__ float rs[kQT][4][kTiles * 16];         // per 16-lane group: head sums of kernels chunk-16 .. chunk+kChunk-1
+    __shared__ __align__(16) uint16_t qs[kQT > 1 ? kQT * 16 * kQsPitch : 8];
+    const int h = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, g = lane >> 4;
+    const int G = dm.G;
+    const int n_qt = (dm.n_q + kQT - 1) / kQT;
+    const int b = kQT == 1 ? blockIdx.z : blockIdx.z / n_qt;   // kQT = 1 is only launched with n_q = 1
+    const int qi0 = (blockIdx.z - b * n_qt) * kQT;
+    const int L_all = clamp_len(seqlens[b], dm.max_seqlen);
+    int L_max = 0;
+#pragma unroll
+    for (int t = 0; t < kQT; ++t) L_max = max(L_max, row_len(dm, L_all, qi0 + t));
+    if (L_max < 1 || (int)blockIdx.x * 16 * kTW > (L_max - 1) / kBlock) return;    // no block of this chunk exists
+    const int n_vis_max = num_kernels(L_max);
+    const int first = (int)blockIdx.x * kChunk - 16;  // kernel of rs[.][.][0]
+    // ---- operand loads: this wave's kernel tiles (tile 0 is the halo, taken by wave 3), the query rows ----
+    bf16x8 aq[kQT][4], bk[kTW + 1][4];
+#pragma unroll
+    for (int i = 0; i <= kTW; ++i) {
+        const int tile = i < kTW ? 1 + wave * kTW + i : 0;
+        const int jh = first + 16 * tile + n;
+        const bool have = (i < kTW || wave == 3) && jh >= 0 && jh < n_vis_max;
+        const __bf16 *ckr = ck.ptr + b * ck.sb + h * ck.sh + (int64_t)jh * ck.st + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bk[i][ks] = zero8();
+            if (have) bk[i][ks] = load8(ckr + 32 * ks);
+        }
+    }
+    // ---- log-sum-exp per (query, head): kLanesPerPair lanes each, all loads of a lane issued together ----
+    {
+        const int pair = tid / kLanesPerPair, sub = tid % kLanesPerPair;
+        const int t = pair >> 4, head = pair & 15;
+        const int np = (num_kernels(row_len(dm, L_all, qi0 + t)) + kChunk1 - 1) / kChunk1;   // valid partials
+        const int64_t bv = (int64_t)b * dm.n_q + min(qi0 + t, dm.n_q - 1);
+        const float2 *pr = part + ((bv * dm.Hkv + h) * G + min(head, G - 1)) * n_part;
+        float2 v[kMaxPartsPerLane];
+#pragma unroll
+        for (int i = 0; i < kMaxPartsPerLane; ++i) {
+            const int p = sub + kLanesPerPair * i;
+            v[i] = float2{-INFINITY, 0.f};
+            if (p < np) v[i] = pr[p];
+        }
+        float m = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < kMaxPartsPerLane; ++i) m = fmaxf(m, v[i].x);
+#pragma unroll
+        for (int o = 1; o < kLanesPerPair; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
+        const float mu = m == -INFINITY ? 0.f : m;
+        float sm = 0.f;
+#pragma unroll
+        for (int i = 0; i < kMaxPartsPerLane; ++i) sm += v[i].y * fast_exp2(v[i].x - mu);
+#pragma unroll
+        for (int o = 1; o < kLanesPerPair; o <<= 1) sm += __shfl_xor(sm, o);
+        if (sub == 0)      // approximate mode: rho times fewer kernels were summed; 0 when none is visible
+            lse_h[t][head] = dm.rho > 1 ? (m == -INFINITY ? 0.f : m + fast_log2(sm) + (float)(31 - __clz(dm.rho)))
+                                        : m + fast_log2(sm);
+    }
+    load_query_operands<kQT>(dm, q, b, h, qi0, qs, aq);     // (a barrier inside when kQT > 1)
+    __syncthreads();
+    // ---- head sums of exp(z - lse) ------------------------------------------------------------------------
+#pragma unroll
+    for (int t = 0; t < kQT; ++t) {
+        const float4 l4 = *reinterpret_cast<const float4 *>(&lse_h[t][4 * g]);
+        const float lh[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+        for (int i = 0; i <= kTW; ++i) {
+            if (i == kTW && wave != 3) break;         // uniform over the wave
+            const int tile = i < kTW ? 1 + wave * kTW + i : 0;
+            f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) z = mfma16(aq[t][ks], bk[i][ks], z);
+            float acc = 0.f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (4 * g + r < G) acc += fast_exp2(z[r] * dm.scale_log2 - lh[r]);
+            rs[t][g][16 * tile + n] = acc;
+        }
+    }
+    __syncthreads();
+    // ---- group mean, clamps, 5/4 max-pool: thread (t, jl) takes kernels 4j-1 .. 4j+3 = rs[..][4*jl+15 .. +19] ----
+    if (tid < kQT * 16 * kTW) {
+        const int t = tid / (16 * kTW), jl = tid % (16 * kTW);
+        const int j = blockIdx.x * 16 * kTW + jl;
+        const int L = row_len(dm, L_all, qi0 + t);
+        if (L >= 1 && j <= (L - 1) / kBlock) {
+            const int n_vis = num_kernels(L);
+            float v = -INFINITY;
+#pragma unroll
+            for (int x = 0; x < 5; ++x) {
+                const int c = 4 * jl + 15 + x, jh = first + c;
+                const float sum = (rs[t][0][c] + rs[t][1][c]) + (rs[t][2][c] + rs[t][3][c]);
+                if (jh >= 0 && jh < n_vis) v = fmaxf(v, fminf(fmaxf(sum * (1.f / G), kScoreFloor), kScoreCeil));
+            }
+            const int64_t bv = (int64_t)b * dm.n_q + qi0 + t;
+            R[(bv * dm.Hkv + h) * nb_cap + j] = v;
+        }
+    }
+}
+
+// ---- part 2, plain decode: block scores from the logits part 1 kept ---------------------------------
+// (One query per sequence: its logits are a quarter of the bytes of the compressed keys, so reading
+// them back is cheaper than computing them again; with several queries per sequence the balance tips.)
+// grid (nb_cap/64, Hkv, B), 320 threads.  Thread t <= 256 scores kernel 256*bx - 1 + t
 // (one halo kernel to the left); threads 0..63 then pool blocks 64*bx + t.
 constexpr int kMaxParts = 256;                        // partials per head: contexts up to 262144 tokens
-__global__ __launch_bounds__(320) void decode_scores_kernel(Dims dm, const int32_t *__restrict__ seqlens,
+__global__ __launch_bounds__(320) void decode_scores_z_kernel(Dims dm, const int32_t *__restrict__ seqlens,
                                                              const float *__restrict__ zbuf,
                                                              const float2 *__restrict__ part,
                                                              int32_t n_c_cap, int32_t n_part,
@@ -531,17 +748,17 @@ static inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct DecodeSelLayout {
     int32_t n_c_cap, n_part, nb_cap;
-    size_t z_bytes, part_bytes, r_bytes;
+    size_t z_bytes, part_bytes, r_bytes;              // z: logits, plain decode only
 };
 static DecodeSelLayout decode_sel_layout(const Dims &dm) {
     DecodeSelLayout l;
     int32_t n_c = num_kernels(dm.max_seqlen);
     l.n_c_cap = (n_c + 255) / 256 * 256;
     if (l.n_c_cap < 256) l.n_c_cap = 256;
-    l.n_part = l.n_c_cap / 64;
+    l.n_part = l.n_c_cap / (64 * tiles_per_wave(dm.n_q == 1 ? 1 : kVerifyQT));
     l.nb_cap = ((dm.max_seqlen + kBlock - 1) / kBlock + 63) / 64 * 64;
     const size_t rows = (size_t)dm.batch * dm.n_q;
-    l.z_bytes = align256(rows * dm.Hq * l.n_c_cap * sizeof(float));
+    l.z_bytes = dm.n_q == 1 ? align256(rows * dm.Hq * l.n_c_cap * sizeof(float)) : 0;
     l.part_bytes = align256(rows * dm.Hq * l.n_part * sizeof(float2));
     l.r_bytes = align256(rows * dm.Hkv * l.nb_cap * sizeof(float));
     return l;
@@ -556,19 +773,31 @@ int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seq
                          int32_t *block_idx, void *ws, hipStream_t stream) {
     if (dm.batch <= 0) return 0;
     DecodeSelLayout l = decode_sel_layout(dm);
-    if (l.n_part > kMaxParts) return (int)hipErrorInvalidValue;      // rejected earlier by the C ABI
-    float *zbuf = reinterpret_cast<float *>(ws);
-    float2 *part = reinterpret_cast<float2 *>(reinterpret_cast<char *>(ws) + l.z_bytes);
-    float2 *part_c = reinterpret_cast<float2 *>(reinterpret_cast<char *>(ws) + l.z_bytes + l.part_bytes);
-    float *R = reinterpret_cast<float *>(reinterpret_cast<char *>(ws) + l.z_bytes + 2 * l.part_bytes);
-    timing_begin("decode_logits_kernel", stream);
+    if (l.n_c_cap > 16384) return (int)hipErrorInvalidValue;         // rejected earlier by the C ABI
+    char *wsb = reinterpret_cast<char *>(ws);
+    float *zbuf = reinterpret_cast<float *>(wsb);
+    float2 *part = reinterpret_cast<float2 *>(wsb + l.z_bytes);
+    float2 *part_c = reinterpret_cast<float2 *>(wsb + l.z_bytes + l.part_bytes);
+    float *R = reinterpret_cast<float *>(wsb + l.z_bytes + 2 * l.part_bytes);
     const int rows = dm.batch * dm.n_q;                              // <= 65535, checked by the C ABI
-    hipLaunchKernelGGL(decode_logits_kernel, dim3(l.n_c_cap / 64, dm.Hkv, rows), dim3(256), 0,
-                       stream, dm, q, ck, seqlens, zbuf, part, part_c, l.n_c_cap, l.n_part);
+    const int n_qt = (dm.n_q + kVerifyQT - 1) / kVerifyQT;
+    const float2 *part_lse = dm.rho > 1 ? part_c : part;
+    timing_begin("decode_logits_kernel", stream);
+    if (dm.n_q == 1)
+        hipLaunchKernelGGL(decode_logits_kernel<1>, dim3(l.n_part, dm.Hkv, dm.batch), dim3(256), 0, stream,
+                           dm, q, ck, seqlens, zbuf, l.n_c_cap, part, part_c, l.n_part);
+    else
+        hipLaunchKernelGGL(decode_logits_kernel<kVerifyQT>, dim3(l.n_part, dm.Hkv, dm.batch * n_qt), dim3(256),
+                           0, stream, dm, q, ck, seqlens, nullptr, 0, part, part_c, l.n_part);
     timing_end(stream);
     timing_begin("decode_scores_kernel", stream);
-    hipLaunchKernelGGL(decode_scores_kernel, dim3(l.n_c_cap / 256, dm.Hkv, rows), dim3(320), 0, stream,
-                       dm, seqlens, zbuf, dm.rho > 1 ? part_c : part, l.n_c_cap, l.n_part, R, l.nb_cap);
+    if (dm.n_q == 1)
+        hipLaunchKernelGGL(decode_scores_z_kernel, dim3(l.nb_cap / 64, dm.Hkv, dm.batch), dim3(320), 0, stream,
+                           dm, seqlens, zbuf, part_lse, l.n_c_cap, l.n_part, R, l.nb_cap);
+    else
+        hipLaunchKernelGGL(decode_scores_kernel<kVerifyQT>,
+                           dim3(l.nb_cap / (16 * tiles_per_wave2(kVerifyQT)), dm.Hkv, dm.batch * n_qt), dim3(256), 0,
+                           stream, dm, q, ck, seqlens, part_lse, l.n_part, R, l.nb_cap);
     timing_end(stream);
     const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
     if (n_blocks > kPickThreads * kPickMaxVPT) return (int)hipErrorInvalidValue;   // rejected earlier by the C ABI

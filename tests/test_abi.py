@@ -127,7 +127,8 @@ def test_verify_validation(lib):
     prm, t = good_params(), tensor()
     P, T = ctypes.byref(prm), ctypes.byref(t)
     ws = lib.infllmv2_verify_workspace_bytes
-    assert ws(binding.OP_SELECT_VERIFY, P, 2, 4096, 8) == 8 * lib.infllmv2_workspace_bytes(binding.OP_SELECT_DECODE, P, 2, 4096)
+    # 16 query rows: two (max, sum) partial sets of 2 chunks x 32 heads + fp32 scores of 64 blocks x 2 kv heads
+    assert ws(binding.OP_SELECT_VERIFY, P, 2, 4096, 8) == 2 * 16 * 32 * 2 * 8 + 16 * 2 * 64 * 4
     assert ws(binding.OP_ATTN_VERIFY, P, 1, 4096, 1) == lib.infllmv2_workspace_bytes(binding.OP_ATTN_DECODE, P, 1, 4096)
     assert ws(binding.OP_ATTN_VERIFY, P, 1, 4096, 0) == 0 and ws(binding.OP_ATTN_VERIFY, P, 1, 4096, 65) == 0
     assert ws(binding.OP_SELECT_DECODE, P, 1, 4096, 4) == 0                              # not a verify stage

@@ -254,13 +254,16 @@ def test_prefill_end_to_end_dense_degrade():
 
 # ------------------------------------------------------------------ decode
 
-@pytest.mark.parametrize("seqlens,Hq,Hkv,topk", [([3000, 1077, 64, 33, 31, 1], 32, 2, 16),
-                                                 ([2048, 129], 4, 1, 8), ([777], 16, 2, 6),
-                                                 ([9000, 4500, 200], 32, 2, 64),
-                                                 ([4100, 4097, 20], 32, 2, 16)])      # 65 blocks, 255 kernels
-def test_decode_select_and_attn(seqlens, Hq, Hkv, topk):
-    print("case decode", seqlens, Hq, Hkv, topk, flush=True)
-    prm = binding.Params(Hq, Hkv, topk=topk)
+@pytest.mark.parametrize("seqlens,Hq,Hkv,topk,forced", [
+    ([3000, 1077, 64, 33, 31, 1], 32, 2, 16, (1, 2)),
+    ([2048, 129], 4, 1, 8, (1, 2)), ([777], 16, 2, 6, (1, 2)),
+    ([9000, 4500, 200], 32, 2, 64, (1, 2)),
+    ([4100, 4097, 20], 32, 2, 16, (1, 2)),                  # 65 blocks, 255 kernels
+    ([4100, 4097, 4128, 20, 70], 32, 2, 16, (0, 0)),        # nothing forced: the query's own (short) block competes
+])
+def test_decode_select_and_attn(seqlens, Hq, Hkv, topk, forced):
+    print("case decode", seqlens, Hq, Hkv, topk, forced, flush=True)
+    prm = binding.Params(Hq, Hkv, topk=topk, n_init_blocks=forced[0], n_local_blocks=forced[1])
     oprm = oracle_params(prm)
     q, k, v, T = make_batch(31, seqlens, Hq, Hkv, n_planted=4, heavy=(1,))
     B = len(seqlens)

@@ -85,8 +85,8 @@ PREFILL_CASES = [
 ]
 
 
-def run_prefill(seqlens, Hq, Hkv, topk, planted, seed=21):
-    prm = binding.Params(Hq, Hkv, topk=topk)
+def run_prefill(seqlens, Hq, Hkv, topk, planted, seed=21, forced=(1, 2)):
+    prm = binding.Params(Hq, Hkv, topk=topk, n_init_blocks=forced[0], n_local_blocks=forced[1])
     q, k, v, T = make_batch(seed, seqlens, Hq, Hkv, n_planted=planted)
     qd, kd, vd, sl = to_dev(q), to_dev(k), to_dev(v), dev_i32(seqlens)
     ck = binding.compress_keys(prm, kd, sl, T)
@@ -113,6 +113,27 @@ def test_select_blocks_prefill(seqlens, Hq, Hkv, topk, planted):
         assert not hard, hard[:3]
         tot, exact, near = tot + n, exact + e, near + nt
     print("rows %d exact %d near-tie %d" % (tot, exact, near), flush=True)
+    assert near <= max(2, tot // 200)
+
+
+@pytest.mark.parametrize("forced", [(0, 0), (0, 1), (3, 0), (2, 4)])
+@pytest.mark.parametrize("seqlens,Hq,Hkv,topk", [([1100, 333, 70], 32, 2, 8), ([700, 65], 4, 1, 6)])
+def test_select_blocks_prefill_other_forced_counts(seqlens, Hq, Hkv, topk, forced):
+    # with no local block forced, the query's own block competes on its score, also while it is too
+    # short to hold a visible kernel (score -inf)
+    print("case select prefill forced", seqlens, Hq, Hkv, topk, forced, flush=True)
+    prm, (q, k, v, T), dev, ck, idx = run_prefill(seqlens, Hq, Hkv, topk, 3, forced=forced)
+    oprm = oracle_params(prm)
+    idx = idx.cpu().numpy()
+    ckb = to_bits(ck)
+    tot = near = 0
+    for b, l in enumerate(seqlens):
+        n_c = ref.num_kernels(l, 32, 16)
+        pos = np.arange(l, dtype=np.int32)
+        want, margins, R = ref.select_blocks(q[b, :l], ckb[b, :, :n_c], pos, oprm, want_scores=True)
+        n, e, nt, hard = compare_selection(idx[b, :, :l], want, margins, R)
+        assert not hard, hard[:3]
+        tot, near = tot + n, near + nt
     assert near <= max(2, tot // 200)
 
 

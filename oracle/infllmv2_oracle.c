@@ -40,6 +40,9 @@
  *     rho times fewer coarse kernels); 0 when no coarse kernel is visible (no selection
  *     depends on it when (n_init + n_local) * m >= 2 * s_c);
  *   - scores exp(z - LSE_approx) are no longer bounded by 1: they are clamped above at 2^100.
+ * Reading for the backward pass (section 2.1 calls the attention trainable and gives no backward
+ * formulas -- parity unpinned for the reading, the arithmetic is pinned against automatic
+ * differentiation): gradients flow to q, k, v through the stage-3 attention only, block sets fixed.
  * Reading for tree-style draft verification (section 4.1, "InfLLM v2 for Target Model"; the
  * report says only that the local mask of the last n x n region is bit-packed in uint64 --
  * parity unpinned for the reading, the arithmetic is pinned):
@@ -473,6 +476,86 @@ void oracle_sparse_attn_tree(const uint16_t *q_bits, const uint16_t *k_bits, con
     attend_rows(q_bits, k_bits, v_bits, pos, block_idx, n, Hq, Hkv, d, l, m, topk, scale, out, lse, NULL,
                 l_ctx, tree_mask);
     free(pos);
+}
+
+/* ---- O5: backward of the sparse attention ------------------------------------------------ */
+
+/* Gradients of oracle_sparse_attn's output with respect to q, k and v for a given upstream
+ * gradient dout, the block sets held fixed (section 2.1: the sparse attention is trainable; the
+ * selection is a discrete choice and the mean-pooled kernels have no parameters, so the
+ * gradient reaches q, k, v through the attention only.  The report prints no backward formulas;
+ * these are the derivatives of the forward definition):
+ *     p[t]   = softmax over T_i of z[t],  z[t] = scale <q_i, k_t>
+ *     dv_t  += p[t] dout_i                       dp[t] = <dout_i, v_t>
+ *     ds[t]  = p[t] (dp[t] - sum_u p[u] dp[u])
+ *     dq_i   = scale sum_t ds[t] k_t             dk_t += scale ds[t] q_i
+ * summed over the query heads of a group for dk, dv.
+ *   dout_bits [Tq, Hq, d] bf16;  dq [Tq, Hq, d], dk, dv [Hkv, l, d] fp64 out (overwritten). */
+void oracle_sparse_attn_bwd(const uint16_t *q_bits, const uint16_t *k_bits, const uint16_t *v_bits,
+                            const uint16_t *dout_bits, const int32_t *pos, const int32_t *block_idx,
+                            int32_t Tq, int32_t Hq, int32_t Hkv, int32_t d, int32_t l, int32_t m,
+                            int32_t topk, double scale, double *dq, double *dk, double *dv) {
+    int32_t G = Hq / Hkv;
+    size_t kv_elems = (size_t)Hkv * l * d;
+    for (size_t x = 0; x < kv_elems; ++x) dk[x] = dv[x] = 0.0;
+#pragma omp parallel
+    {
+        double *p = (double *)malloc(sizeof(double) * (size_t)topk * m);
+        double *dp = (double *)malloc(sizeof(double) * (size_t)topk * m);
+        int32_t *tok = (int32_t *)malloc(sizeof(int32_t) * (size_t)topk * m);
+        double *dk_own = (double *)calloc(kv_elems, sizeof(double));   /* this thread's share of the sums */
+        double *dv_own = (double *)calloc(kv_elems, sizeof(double));
+#pragma omp for schedule(dynamic, 4)
+        for (int32_t t = 0; t < Tq; ++t)
+            for (int32_t hq = 0; hq < Hq; ++hq) {
+                int32_t h = hq / G;
+                int32_t i = pos[t];
+                const uint16_t *q = q_bits + ((size_t)t * Hq + hq) * d;
+                const uint16_t *go = dout_bits + ((size_t)t * Hq + hq) * d;
+                const int32_t *sel = block_idx + ((size_t)h * Tq + t) * topk;
+                int32_t n = 0;
+                for (int32_t c = 0; c < topk; ++c) {
+                    if (sel[c] < 0) continue;
+                    for (int32_t u = sel[c] * m; u < (sel[c] + 1) * m; ++u)
+                        if (u <= i && u < l) tok[n++] = u;
+                }
+                double zmax = -INFINITY, denom = 0.0, pdp = 0.0;
+                for (int32_t a = 0; a < n; ++a) {
+                    const uint16_t *kr = k_bits + ((size_t)h * l + tok[a]) * d;
+                    const uint16_t *vr = v_bits + ((size_t)h * l + tok[a]) * d;
+                    double dot = 0.0, gv = 0.0;
+                    for (int32_t c = 0; c < d; ++c) {
+                        dot += bf16_to_f64(q[c]) * bf16_to_f64(kr[c]);
+                        gv += bf16_to_f64(go[c]) * bf16_to_f64(vr[c]);
+                    }
+                    p[a] = scale * dot;
+                    dp[a] = gv;
+                    if (p[a] > zmax) zmax = p[a];
+                }
+                for (int32_t a = 0; a < n; ++a) denom += exp(p[a] - zmax);
+                for (int32_t a = 0; a < n; ++a) {
+                    p[a] = exp(p[a] - zmax) / denom;
+                    pdp += p[a] * dp[a];
+                }
+                double *gq = dq + ((size_t)t * Hq + hq) * d;
+                for (int32_t c = 0; c < d; ++c) gq[c] = 0.0;
+                for (int32_t a = 0; a < n; ++a) {
+                    double ds = p[a] * (dp[a] - pdp);
+                    size_t row = ((size_t)h * l + tok[a]) * d;
+                    for (int32_t c = 0; c < d; ++c) {
+                        gq[c] += scale * ds * bf16_to_f64(k_bits[row + c]);
+                        dk_own[row + c] += scale * ds * bf16_to_f64(q[c]);
+                        dv_own[row + c] += p[a] * bf16_to_f64(go[c]);
+                    }
+                }
+            }
+#pragma omp critical
+        for (size_t x = 0; x < kv_elems; ++x) {
+            dk[x] += dk_own[x];
+            dv[x] += dv_own[x];
+        }
+        free(p); free(dp); free(tok); free(dk_own); free(dv_own);
+    }
 }
 
 /* Rounding helper exported for tests of the bf16 conversion itself. */

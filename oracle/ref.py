@@ -57,6 +57,8 @@ def _load():
         lib.oracle_select_blocks_coarse.argtypes = [vp, vp, vp, vp] + [i32] * 13 + [f64, vp, vp, vp, i32]
         lib.oracle_sparse_attn.restype = None
         lib.oracle_sparse_attn.argtypes = [vp, vp, vp, vp, vp] + [i32] * 7 + [f64, vp, vp, vp]
+        lib.oracle_sparse_attn_bwd.restype = None
+        lib.oracle_sparse_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp] + [i32] * 7 + [f64, vp, vp, vp]
         lib.oracle_sparse_attn_tree.restype = None
         lib.oracle_sparse_attn_tree.argtypes = [vp, vp, vp, vp, vp] + [i32] * 8 + [f64, vp, vp]
         lib.oracle_f64_to_bf16.restype = ctypes.c_uint16
@@ -238,3 +240,22 @@ def sparse_attn_tree(q, k, v, block_idx, tree_mask, l_ctx, prm):
                                 Hq, Hkv, d, l, prm.block_size, topk, float(prm.softmax_scale),
                                 _ptr(out), _ptr(lse))
     return out, lse
+
+
+def sparse_attn_bwd(q, k, v, dout, pos, block_idx, prm):
+    """Gradients of sparse_attn's output for the upstream gradient dout (uint16 bf16 bits [Tq, Hq, d]),
+    block sets fixed -> dq fp64 [Tq, Hq, d], dk, dv fp64 [Hkv, l, d]."""
+    lib = _load()
+    q, k, v, dout = _u16(q), _u16(k), _u16(v), _u16(dout)
+    pos = np.ascontiguousarray(pos, np.int32)
+    block_idx = np.ascontiguousarray(block_idx, np.int32)
+    Tq, Hq, d = q.shape
+    Hkv, l, _ = k.shape
+    topk = block_idx.shape[-1]
+    assert dout.shape == q.shape and v.shape == k.shape and block_idx.shape == (Hkv, Tq, topk)
+    dq = np.zeros((Tq, Hq, d), np.float64)
+    dk = np.zeros((Hkv, l, d), np.float64)
+    dv = np.zeros((Hkv, l, d), np.float64)
+    lib.oracle_sparse_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(pos), _ptr(block_idx), Tq, Hq, Hkv, d,
+                               l, prm.block_size, topk, float(prm.softmax_scale), _ptr(dq), _ptr(dk), _ptr(dv))
+    return dq, dk, dv

@@ -556,3 +556,65 @@ def test_tree_attention_against_library_masked_attention():
     z = (qt @ kt.transpose(1, 2)) * prm.softmax_scale
     z = z.masked_fill(~mt, -np.inf)
     assert np.abs(lse - torch.logsumexp(z, -1).T.numpy()).max() < 1e-12
+
+
+# ------------------------------------------------------------------ backward of the sparse attention
+# (section 2.1: the attention is trainable; gradients through stage 3 with the block sets fixed)
+
+def _bwd_case(l, Hq, Hkv, topk, seed, d=16, m=8, p=4, s=2):
+    rng = np.random.default_rng(seed)
+    q = synth.f32_to_bf16_bits(rng.standard_normal((l, Hq, d), dtype=np.float32))
+    k = synth.f32_to_bf16_bits(rng.standard_normal((Hkv, l, d), dtype=np.float32))
+    v = synth.f32_to_bf16_bits(rng.standard_normal((Hkv, l, d), dtype=np.float32))
+    do = synth.f32_to_bf16_bits(rng.standard_normal((l, Hq, d), dtype=np.float32))
+    prm = ref.Params(Hq, Hkv, head_dim=d, block_size=m, kernel_size=p, kernel_stride=s, topk=topk)
+    _, ckb = ref.compress_keys(k, prm)
+    pos = np.arange(l, dtype=np.int32)
+    idx, _ = ref.select_blocks(q, ckb, pos, prm)
+    return q, k, v, do, prm, pos, idx
+
+
+def test_attention_backward_against_automatic_differentiation():
+    l, Hq, Hkv, m = 150, 6, 2, 8
+    q, k, v, do, prm, pos, idx = _bwd_case(l, Hq, Hkv, 5, 17, m=m)
+    dq, dk, dv = ref.sparse_attn_bwd(q, k, v, do, pos, idx, prm)
+    G = Hq // Hkv
+    allowed = np.zeros((Hkv, l, l), bool)
+    for h in range(Hkv):
+        for t in range(l):
+            for j in idx[h, t]:
+                if j >= 0:
+                    allowed[h, t, j * m:(j + 1) * m] = True
+            allowed[h, t, t + 1:] = False
+    f = lambda b: torch.from_numpy(synth.bf16_bits_to_f32(b).astype(np.float64))
+    qt = f(q).permute(1, 0, 2).clone().requires_grad_(True)                     # [Hq, l, d]
+    kt, vt = f(k).clone().requires_grad_(True), f(v).clone().requires_grad_(True)
+    mt = torch.from_numpy(allowed).repeat_interleave(G, 0)
+    out = torch.nn.functional.scaled_dot_product_attention(qt, kt.repeat_interleave(G, 0), vt.repeat_interleave(G, 0),
+                                                           attn_mask=mt)
+    out.backward(f(do).permute(1, 0, 2))
+    assert np.abs(dq - qt.grad.permute(1, 0, 2).numpy()).max() < 1e-12
+    assert np.abs(dk - kt.grad.numpy()).max() < 1e-12
+    assert np.abs(dv - vt.grad.numpy()).max() < 1e-12
+    assert np.abs(dq).max() > 1e-3 and np.abs(dk).max() > 1e-3 and np.abs(dv).max() > 1e-3
+    assert (~allowed[:, :, :l - 1].all(axis=1)).any()                           # the mask is really sparse
+
+
+def test_attention_backward_by_finite_differences_and_invariants():
+    l, Hq, Hkv = 40, 4, 2
+    q, k, v, do, prm, pos, idx = _bwd_case(l, Hq, Hkv, 3, 19)
+    dq, dk, dv = ref.sparse_attn_bwd(q, k, v, do, pos, idx, prm)
+    g = synth.bf16_bits_to_f32(do).astype(np.float64)
+    # dv is linear in the probabilities: sum over keys of dv = sum over (token, head of the group) of dout
+    G = Hq // Hkv
+    for h in range(Hkv):
+        assert np.allclose(dv[h].sum(0), g[:, h * G:(h + 1) * G].sum((0, 1)), atol=1e-10)
+    # the loss <out, dout> is linear in v: a central difference with a bf16-exact step is the gradient exactly
+    vf = synth.bf16_bits_to_f32(v).astype(np.float64)
+    loss = lambda vb: float((ref.sparse_attn(q, k, vb, pos, idx, prm)[0] * g).sum())
+    for (h, t, c) in [(0, 3, 1), (1, 17, 5), (0, 39, 0)]:
+        e = np.zeros_like(vf)
+        e[h, t, c] = 0.5                                                        # stays exactly representable
+        vp = synth.f32_to_bf16_bits((vf + e).astype(np.float32))
+        vm = synth.f32_to_bf16_bits((vf - e).astype(np.float32))
+        assert abs((loss(vp) - loss(vm)) - dv[h, t, c]) < 1e-9

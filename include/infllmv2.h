@@ -62,6 +62,7 @@ extern "C" {
 #define INFLLMV2_OP_SELECT_DECODE 2
 #define INFLLMV2_OP_ATTN_PREFILL 3
 #define INFLLMV2_OP_ATTN_DECODE 4
+#define INFLLMV2_OP_ATTN_BWD 7
 /* Stage selector for infllmv2_verify_workspace_bytes. */
 #define INFLLMV2_OP_SELECT_VERIFY 5
 #define INFLLMV2_OP_ATTN_VERIFY 6
@@ -171,6 +172,34 @@ int32_t infllmv2_sparse_attn_prefill(const infllmv2_params *prm, const infllmv2_
                                      const int32_t *block_idx, const infllmv2_tensor *out,
                                      float *lse, void *workspace, size_t workspace_bytes,
                                      void *stream);
+
+/*
+ * Stage 3, backward -- gradients of infllmv2_sparse_attn_prefill's output with respect to q, k and v
+ * for an upstream gradient dout, the block sets held fixed (section 2.1: the sparse attention is
+ * trainable; the selection is a discrete choice and the mean-pooled semantic kernels have no
+ * parameters, so nothing flows through stage 2).  With p = exp(softmax_scale <q_i, k_t> - lse) over
+ * T_i and D = <dout_i, out_i> per (token, head):
+ *     dv_t = sum p dout_i        ds = p (<dout_i, v_t> - D)
+ *     dq_i = softmax_scale sum_t ds k_t        dk_t = softmax_scale sum ds q_i
+ * (sums for dk, dv over the tokens that selected t's block and the query heads of the group).
+ * bf16 products accumulated in fp32; p and ds are rounded to bf16 before the second products;
+ * dk, dv are merged with fp32 atomic adds (the last bits depend on the order).
+ *   q, out, dout  in   [batch, max_seqlen, Hq, d] bf16: the forward's input, output and its gradient
+ *   k, v          in   bf16 caches [batch, Hkv, >=max_seqlen, d]
+ *   lse           in   fp32 [batch, max_seqlen, Hq], the forward's log-sum-exp
+ *   block_idx     in   int32 [batch, Hkv, max_seqlen, topk], as given to the forward
+ *   dq            out  [batch, max_seqlen, Hq, d] bf16 (rows t >= seqlens[b] not written)
+ *   dk, dv        out  [batch, Hkv, >=max_seqlen, d] bf16 (rows t >= seqlens[b] not written)
+ *   workspace     device scratch of infllmv2_workspace_bytes(INFLLMV2_OP_ATTN_BWD, ...) bytes: packed
+ *                 copies of K, V, q and dout, D, a block x token membership bitmap, fp32 dk / dv
+ */
+int32_t infllmv2_sparse_attn_bwd(const infllmv2_params *prm, const infllmv2_tensor *q,
+                                 const infllmv2_tensor *k, const infllmv2_tensor *v,
+                                 const infllmv2_tensor *out, const infllmv2_tensor *dout, const float *lse,
+                                 const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
+                                 const int32_t *block_idx, const infllmv2_tensor *dq,
+                                 const infllmv2_tensor *dk, const infllmv2_tensor *dv, void *workspace,
+                                 size_t workspace_bytes, void *stream);
 
 /*
  * Stage 3, decode -- the same attention for the single query at position seqlens[b]-1

@@ -490,21 +490,35 @@ void oracle_sparse_attn_tree(const uint16_t *q_bits, const uint16_t *k_bits, con
  *     ds[t]  = p[t] (dp[t] - sum_u p[u] dp[u])
  *     dq_i   = scale sum_t ds[t] k_t             dk_t += scale ds[t] q_i
  * summed over the query heads of a group for dk, dv.
- *   dout_bits [Tq, Hq, d] bf16;  dq [Tq, Hq, d], dk, dv [Hkv, l, d] fp64 out (overwritten). */
+ *   dout_bits [Tq, Hq, d] bf16;  dq [Tq, Hq, d], dk, dv [Hkv, l, d] fp64 out (overwritten).
+ * Optional (all three or none, NULL to skip): the size of the terms behind every gradient
+ * element, the scale a rounding-error tolerance has to be measured in.  An implementation that
+ * takes D = <dout_i, out_i> from a rounded copy of the output perturbs every ds[t] by p[t] dD,
+ * with |dD| <= eps * A_i,  A_i = sum_t p[t] <|dout_i|, |v_t|>:
+ *     dq_mag_i = scale sum_t (|ds[t]| + p[t] A_i) |k_t|
+ *     dk_mag_t = scale sum   (|ds[t]| + p[t] A_i) |q_i|
+ *     dv_mag_t =       sum    p[t] |dout_i| */
 void oracle_sparse_attn_bwd(const uint16_t *q_bits, const uint16_t *k_bits, const uint16_t *v_bits,
                             const uint16_t *dout_bits, const int32_t *pos, const int32_t *block_idx,
                             int32_t Tq, int32_t Hq, int32_t Hkv, int32_t d, int32_t l, int32_t m,
-                            int32_t topk, double scale, double *dq, double *dk, double *dv) {
+                            int32_t topk, double scale, double *dq, double *dk, double *dv,
+                            double *dq_mag, double *dk_mag, double *dv_mag) {
     int32_t G = Hq / Hkv;
     size_t kv_elems = (size_t)Hkv * l * d;
+    int want_mag = dq_mag && dk_mag && dv_mag;
     for (size_t x = 0; x < kv_elems; ++x) dk[x] = dv[x] = 0.0;
+    if (want_mag)
+        for (size_t x = 0; x < kv_elems; ++x) dk_mag[x] = dv_mag[x] = 0.0;
 #pragma omp parallel
     {
         double *p = (double *)malloc(sizeof(double) * (size_t)topk * m);
         double *dp = (double *)malloc(sizeof(double) * (size_t)topk * m);
+        double *dpa = (double *)malloc(sizeof(double) * (size_t)topk * m);
         int32_t *tok = (int32_t *)malloc(sizeof(int32_t) * (size_t)topk * m);
         double *dk_own = (double *)calloc(kv_elems, sizeof(double));   /* this thread's share of the sums */
         double *dv_own = (double *)calloc(kv_elems, sizeof(double));
+        double *dkm_own = want_mag ? (double *)calloc(kv_elems, sizeof(double)) : NULL;
+        double *dvm_own = want_mag ? (double *)calloc(kv_elems, sizeof(double)) : NULL;
 #pragma omp for schedule(dynamic, 4)
         for (int32_t t = 0; t < Tq; ++t)
             for (int32_t hq = 0; hq < Hq; ++hq) {
@@ -523,22 +537,39 @@ void oracle_sparse_attn_bwd(const uint16_t *q_bits, const uint16_t *k_bits, cons
                 for (int32_t a = 0; a < n; ++a) {
                     const uint16_t *kr = k_bits + ((size_t)h * l + tok[a]) * d;
                     const uint16_t *vr = v_bits + ((size_t)h * l + tok[a]) * d;
-                    double dot = 0.0, gv = 0.0;
+                    double dot = 0.0, gv = 0.0, gva = 0.0;
                     for (int32_t c = 0; c < d; ++c) {
                         dot += bf16_to_f64(q[c]) * bf16_to_f64(kr[c]);
                         gv += bf16_to_f64(go[c]) * bf16_to_f64(vr[c]);
+                        gva += fabs(bf16_to_f64(go[c]) * bf16_to_f64(vr[c]));
                     }
                     p[a] = scale * dot;
                     dp[a] = gv;
+                    dpa[a] = gva;
                     if (p[a] > zmax) zmax = p[a];
                 }
                 for (int32_t a = 0; a < n; ++a) denom += exp(p[a] - zmax);
+                double A = 0.0;
                 for (int32_t a = 0; a < n; ++a) {
                     p[a] = exp(p[a] - zmax) / denom;
                     pdp += p[a] * dp[a];
+                    A += p[a] * dpa[a];
                 }
                 double *gq = dq + ((size_t)t * Hq + hq) * d;
                 for (int32_t c = 0; c < d; ++c) gq[c] = 0.0;
+                if (want_mag) {
+                    double *gm = dq_mag + ((size_t)t * Hq + hq) * d;
+                    for (int32_t c = 0; c < d; ++c) gm[c] = 0.0;
+                    for (int32_t a = 0; a < n; ++a) {
+                        double w = fabs(p[a] * (dp[a] - pdp)) + p[a] * A;
+                        size_t row = ((size_t)h * l + tok[a]) * d;
+                        for (int32_t c = 0; c < d; ++c) {
+                            gm[c] += scale * w * fabs(bf16_to_f64(k_bits[row + c]));
+                            dkm_own[row + c] += scale * w * fabs(bf16_to_f64(q[c]));
+                            dvm_own[row + c] += p[a] * fabs(bf16_to_f64(go[c]));
+                        }
+                    }
+                }
                 for (int32_t a = 0; a < n; ++a) {
                     double ds = p[a] * (dp[a] - pdp);
                     size_t row = ((size_t)h * l + tok[a]) * d;
@@ -553,8 +584,12 @@ void oracle_sparse_attn_bwd(const uint16_t *q_bits, const uint16_t *k_bits, cons
         for (size_t x = 0; x < kv_elems; ++x) {
             dk[x] += dk_own[x];
             dv[x] += dv_own[x];
+            if (want_mag) {
+                dk_mag[x] += dkm_own[x];
+                dv_mag[x] += dvm_own[x];
+            }
         }
-        free(p); free(dp); free(tok); free(dk_own); free(dv_own);
+        free(p); free(dp); free(dpa); free(tok); free(dk_own); free(dv_own); free(dkm_own); free(dvm_own);
     }
 }
 

@@ -58,7 +58,7 @@ def _load():
         lib.oracle_sparse_attn.restype = None
         lib.oracle_sparse_attn.argtypes = [vp, vp, vp, vp, vp] + [i32] * 7 + [f64, vp, vp, vp]
         lib.oracle_sparse_attn_bwd.restype = None
-        lib.oracle_sparse_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp] + [i32] * 7 + [f64, vp, vp, vp]
+        lib.oracle_sparse_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp] + [i32] * 7 + [f64, vp, vp, vp, vp, vp, vp]
         lib.oracle_sparse_attn_tree.restype = None
         lib.oracle_sparse_attn_tree.argtypes = [vp, vp, vp, vp, vp] + [i32] * 8 + [f64, vp, vp]
         lib.oracle_f64_to_bf16.restype = ctypes.c_uint16
@@ -242,9 +242,10 @@ def sparse_attn_tree(q, k, v, block_idx, tree_mask, l_ctx, prm):
     return out, lse
 
 
-def sparse_attn_bwd(q, k, v, dout, pos, block_idx, prm):
+def sparse_attn_bwd(q, k, v, dout, pos, block_idx, prm, want_mag=False):
     """Gradients of sparse_attn's output for the upstream gradient dout (uint16 bf16 bits [Tq, Hq, d]),
-    block sets fixed -> dq fp64 [Tq, Hq, d], dk, dv fp64 [Hkv, l, d]."""
+    block sets fixed -> dq fp64 [Tq, Hq, d], dk, dv fp64 [Hkv, l, d]; with want_mag also the three
+    arrays of term magnitudes (the scale of a rounding-error tolerance)."""
     lib = _load()
     q, k, v, dout = _u16(q), _u16(k), _u16(v), _u16(dout)
     pos = np.ascontiguousarray(pos, np.int32)
@@ -256,6 +257,8 @@ def sparse_attn_bwd(q, k, v, dout, pos, block_idx, prm):
     dq = np.zeros((Tq, Hq, d), np.float64)
     dk = np.zeros((Hkv, l, d), np.float64)
     dv = np.zeros((Hkv, l, d), np.float64)
+    mags = [np.zeros_like(dq), np.zeros_like(dk), np.zeros_like(dv)] if want_mag else [None] * 3
     lib.oracle_sparse_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(pos), _ptr(block_idx), Tq, Hq, Hkv, d,
-                               l, prm.block_size, topk, float(prm.softmax_scale), _ptr(dq), _ptr(dk), _ptr(dv))
-    return dq, dk, dv
+                               l, prm.block_size, topk, float(prm.softmax_scale), _ptr(dq), _ptr(dk), _ptr(dv),
+                               *[_ptr(x) if x is not None else None for x in mags])
+    return (dq, dk, dv, *mags) if want_mag else (dq, dk, dv)

@@ -23,11 +23,12 @@ LIB_PATH = os.path.join(_HERE, "libinfllmv2.so")
 OK = 0
 OP_SELECT_PREFILL, OP_SELECT_DECODE, OP_ATTN_PREFILL, OP_ATTN_DECODE = 1, 2, 3, 4
 OP_SELECT_VERIFY, OP_ATTN_VERIFY = 5, 6
+OP_ATTN_BWD = 7
 MODE_PREFILL, MODE_DECODE = 0, 1
 
 EXPORTS = ["infllmv2_status_string", "infllmv2_workspace_bytes", "infllmv2_compress_keys",
            "infllmv2_select_blocks", "infllmv2_sparse_attn_prefill", "infllmv2_sparse_attn_decode",
-           "infllmv2_append_kv", "infllmv2_verify_workspace_bytes", "infllmv2_append_kv_verify",
+           "infllmv2_sparse_attn_bwd", "infllmv2_append_kv", "infllmv2_verify_workspace_bytes", "infllmv2_append_kv_verify",
            "infllmv2_select_blocks_verify", "infllmv2_sparse_attn_verify",
            "infllmv2_probe_peaks", "infllmv2_timing_enable", "infllmv2_timing_read"]
 
@@ -101,6 +102,8 @@ def load_library(path=None):
     lib.infllmv2_sparse_attn_prefill.argtypes = [P, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
     lib.infllmv2_sparse_attn_decode.restype = i32
     lib.infllmv2_sparse_attn_decode.argtypes = [P, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
+    lib.infllmv2_sparse_attn_bwd.restype = i32
+    lib.infllmv2_sparse_attn_bwd.argtypes = [P, T, T, T, T, T, vp, vp, i32, i32, vp, T, T, T, vp, sz, vp]
     lib.infllmv2_append_kv.restype = i32
     lib.infllmv2_append_kv.argtypes = [P, T, T, T, T, T, vp, i32, i32, vp]
     lib.infllmv2_verify_workspace_bytes.restype = sz
@@ -341,3 +344,23 @@ def sparse_attn_verify(prm, q, k, v, seqlens, max_seqlen, block_idx, tree_mask=N
                                            ctypes.byref(d[3]), lse.data_ptr(), workspace.data_ptr(),
                                            ws_bytes, _stream()), "infllmv2_sparse_attn_verify")
     return out, lse
+
+
+def sparse_attn_bwd(prm, q, k, v, out, dout, lse, seqlens, max_seqlen, block_idx, dq=None, dk=None, dv=None,
+                    workspace=None):
+    """Backward of sparse_attn_prefill with the block sets fixed -> dq [B, T, Hq, d], dk, dv [B, Hkv, T, d] (bf16)."""
+    lib = load_library()
+    B = q.shape[0]
+    dq = torch.zeros_like(q) if dq is None else dq
+    dk = torch.zeros_like(k) if dk is None else dk
+    dv = torch.zeros_like(v) if dv is None else dv
+    workspace, ws_bytes = _workspace(OP_ATTN_BWD, prm, B, max_seqlen, workspace, q.device)
+    d = [_query_desc(q, "q"), _cache_desc(k, "k"), _cache_desc(v, "v"), _query_desc(out, "out"),
+         _query_desc(dout, "dout"), _query_desc(dq, "dq"), _cache_desc(dk, "dk"), _cache_desc(dv, "dv")]
+    if not (lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous()):
+        raise InfLLMv2Error("lse must be a contiguous fp32 device tensor")
+    _check(lib.infllmv2_sparse_attn_bwd(ctypes.byref(prm.c()), *[ctypes.byref(x) for x in d[:5]], lse.data_ptr(),
+                                        _i32(seqlens, "seqlens").data_ptr(), B, max_seqlen,
+                                        _i32(block_idx, "block_idx").data_ptr(), *[ctypes.byref(x) for x in d[5:]],
+                                        workspace.data_ptr(), ws_bytes, _stream()), "infllmv2_sparse_attn_bwd")
+    return dq, dk, dv

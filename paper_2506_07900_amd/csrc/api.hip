@@ -166,6 +166,7 @@ size_t infllmv2_workspace_bytes(int32_t op, const infllmv2_params *prm, int32_t 
         case INFLLMV2_OP_SELECT_DECODE: return max_seqlen > kMaxDecodeSeqlen ? 0 : select_decode_ws_bytes(dm);
         case INFLLMV2_OP_ATTN_PREFILL: return attn_prefill_ws_bytes(dm);
         case INFLLMV2_OP_ATTN_DECODE: return attn_decode_ws_bytes(dm);
+        case INFLLMV2_OP_ATTN_BWD: return attn_bwd_ws_bytes(dm);
     }
     return 0;
 }
@@ -326,6 +327,28 @@ int32_t infllmv2_sparse_attn_prefill(const infllmv2_params *prm, const infllmv2_
     return hip_status(launch_attn_prefill(dm, make_tensor(q), make_tensor(k), make_tensor(v), seqlens,
                                           block_idx, make_tensor(out), lse, workspace,
                                           reinterpret_cast<hipStream_t>(stream)));
+}
+
+int32_t infllmv2_sparse_attn_bwd(const infllmv2_params *prm, const infllmv2_tensor *q,
+                                 const infllmv2_tensor *k, const infllmv2_tensor *v,
+                                 const infllmv2_tensor *out, const infllmv2_tensor *dout, const float *lse,
+                                 const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
+                                 const int32_t *block_idx, const infllmv2_tensor *dq,
+                                 const infllmv2_tensor *dk, const infllmv2_tensor *dv, void *workspace,
+                                 size_t workspace_bytes, void *stream) {
+    RETURN_IF_ERR(check_params(prm));
+    RETURN_IF_ERR(check_sizes(batch, max_seqlen));
+    const infllmv2_tensor *ts[8] = {q, k, v, out, dout, dq, dk, dv};
+    for (int i = 0; i < 8; ++i) RETURN_IF_ERR(check_tensor(ts[i]));
+    if (!seqlens || !block_idx || !lse) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    const Dims dm = make_dims(prm, batch, max_seqlen);
+    const size_t need = attn_bwd_ws_bytes(dm);
+    if (need > 0 && (!workspace || workspace_bytes < need ||
+                     (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0))
+        return INFLLMV2_ERR_WORKSPACE;
+    return hip_status(launch_attn_bwd(dm, make_tensor(q), make_tensor(k), make_tensor(v), make_tensor(out),
+                                      make_tensor(dout), lse, seqlens, block_idx, make_tensor(dq), make_tensor(dk),
+                                      make_tensor(dv), workspace, reinterpret_cast<hipStream_t>(stream)));
 }
 
 int32_t infllmv2_sparse_attn_decode(const infllmv2_params *prm, const infllmv2_tensor *q,

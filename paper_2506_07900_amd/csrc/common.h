@@ -142,6 +142,10 @@ int launch_attn_decode(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32
                        const int32_t *block_idx, const uint64_t *tree_mask, Tensor out, float *lse, void *ws,
                        hipStream_t stream);
 size_t attn_decode_ws_bytes(const Dims &dm);
+int launch_attn_bwd(const Dims &dm, Tensor q, Tensor k, Tensor v, Tensor out, Tensor dout, const float *lse,
+                    const int32_t *seqlens, const int32_t *block_idx, Tensor dq, Tensor dk, Tensor dv, void *ws,
+                    hipStream_t stream);
+size_t attn_bwd_ws_bytes(const Dims &dm);
 int launch_probes(void *buf, size_t buf_bytes, double *mfma_flops, double *stream_bytes, hipStream_t stream);
 
 }  // namespace infllmv2

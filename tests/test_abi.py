@@ -147,6 +147,18 @@ def test_verify_validation(lib):
     assert lib.infllmv2_append_kv_verify(P, T, T, T, T, None, FAKE, 0, 4096, 4, None) == 0
 
 
+def test_backward_validation(lib):
+    prm, t = good_params(), tensor()
+    P, T = ctypes.byref(prm), ctypes.byref(t)
+    need = lib.infllmv2_workspace_bytes(binding.OP_ATTN_BWD, P, 1, 4096)
+    assert need > 2 * 64 * 3 * 16384                                                    # at least the packed blocks
+    call = lambda lse=FAKE, idx=FAKE, w=FAKE, wb=1 << 40, dq=T: lib.infllmv2_sparse_attn_bwd(
+        P, T, T, T, T, T, lse, FAKE, 1, 4096, idx, dq, T, T, w, wb, None)
+    assert call(lse=None) == INVALID and call(idx=None) == INVALID and call(dq=None) == INVALID
+    assert call(w=None, wb=0) == WORKSPACE and call(wb=need - 1) == WORKSPACE and call(w=FAKE + 16) == WORKSPACE
+    assert lib.infllmv2_sparse_attn_bwd(P, T, T, T, T, T, FAKE, FAKE, 0, 4096, FAKE, T, T, T, FAKE, 1 << 40, None) == 0
+
+
 def test_binding_fails_loudly_without_library(tmp_path):
     with pytest.raises(binding.InfLLMv2Error):
         binding.load_library(str(tmp_path / "missing.so"))

@@ -484,3 +484,72 @@ def test_verify_append_writes_rows_and_completed_kernels():
     for b, l in enumerate(seqlens):
         _, w = ref.compress_keys(k[b, :, :l], oracle_params(prm))
         assert np.array_equal(got[b, :, :w.shape[1]], w), (b, l)
+
+
+# ------------------------------------------------------------------ backward of the sparse attention
+
+GRAD_EPS = 2.0 ** -8          # unit roundoff of bf16 (8 significant bits, round to nearest)
+
+
+def grad_err(got, want, mag):
+    """Largest error of a gradient tensor in units of its tolerance (<= 1 passes).  `mag` is the
+    oracle's sum of the absolute values of the terms behind each element, including the terms by
+    which D = <dout, out> moves when `out` is a bf16-rounded copy.  Every term carries relative
+    rounding errors of up to 2^-8 (probabilities and their derivatives go to the second contraction
+    in bf16, `out` is bf16) and the result one more.  A value gradient has exactly one rounding per
+    term plus its own, so |error| <= 2^-8 (mag + |dv|) holds strictly; for dq and dk the terms carry
+    up to three roundings, which aligned would add up to 3 * 2^-8 * mag and in practice add like a
+    random walk: the same bound is used (observed: a third of it)."""
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    if want.size == 0:
+        return 0.0
+    tol = GRAD_EPS * (mag + np.abs(want)) + 1e-30
+    return float(np.max(np.abs(got - want) / tol))
+
+
+@pytest.mark.parametrize("seqlens,Hq,Hkv,topk,planted", [
+    ([1077, 333], 32, 2, 16, 6),     # G = 16, ragged tails, two sequences
+    ([700], 16, 2, 6, 3),            # G = 8
+    ([300, 64, 63, 1, 0], 4, 2, 4, 0),  # G = 2, tiny and empty sequences
+    ([450], 2, 2, 5, 2),             # G = 1
+    ([1500], 16, 1, 32, 5),          # everything selected: dense causal attention
+    ([2500], 32, 2, 8, 4),           # two 2048-token segments per block row
+])
+def test_sparse_attn_backward(seqlens, Hq, Hkv, topk, planted):
+    print("case attn backward", seqlens, Hq, Hkv, topk, flush=True)
+    prm = binding.Params(Hq, Hkv, topk=topk)
+    oprm = oracle_params(prm)
+    q, k, v, T = make_batch(51, seqlens, Hq, Hkv, n_planted=planted)
+    B = len(seqlens)
+    rng = np.random.default_rng(9)
+    do = synth.f32_to_bf16_bits(rng.standard_normal((B, T, Hq, 128), dtype=np.float32))
+    idx_ref = np.full((B, Hkv, T, topk), -1, np.int32)
+    want = [None] * B
+    for b, l in enumerate(seqlens):
+        if l == 0:
+            continue
+        _, ckb = ref.compress_keys(k[b, :, :l], oprm)
+        pos = np.arange(l, dtype=np.int32)
+        ib, _ = ref.select_blocks(q[b, :l], ckb, pos, oprm)
+        idx_ref[b, :, :l] = ib
+        want[b] = ref.sparse_attn_bwd(q[b, :l], k[b, :, :l], v[b, :, :l], do[b, :l], pos, ib, oprm, want_mag=True)
+    qd, kd, vd, dod, sl = to_dev(q), to_dev(k), to_dev(v), to_dev(do), dev_i32(seqlens)
+    idx_d = torch.from_numpy(idx_ref).cuda()
+    out, lse = binding.sparse_attn_prefill(prm, qd, kd, vd, sl, T, idx_d)
+    sentinel = 3.0
+    dq = torch.full_like(qd, sentinel)
+    dk = torch.full_like(kd, sentinel)
+    dv = torch.full_like(vd, sentinel)
+    binding.sparse_attn_bwd(prm, qd, kd, vd, out, dod, lse, sl, T, idx_d, dq=dq, dk=dk, dv=dv)
+    torch.cuda.synchronize()
+    dq, dk, dv = dq.double().cpu().numpy(), dk.double().cpu().numpy(), dv.double().cpu().numpy()
+    for b, l in enumerate(seqlens):
+        assert np.all(dq[b, l:] == sentinel) and np.all(dk[b, :, l:] == sentinel) and np.all(dv[b, :, l:] == sentinel)
+        if l == 0:
+            continue
+        wq, wk, wv, mq, mk, mv = want[b]
+        eq, ek, ev = grad_err(dq[b, :l], wq, mq), grad_err(dk[b, :, :l], wk, mk), grad_err(dv[b, :, :l], wv, mv)
+        print("seq %d len %d: err/tol dq %.3f dk %.3f dv %.3f   (max|dq| %.2e max|dk| %.2e max|dv| %.2e)"
+              % (b, l, eq, ek, ev, np.abs(wq).max(), np.abs(wk).max(), np.abs(wv).max()), flush=True)
+        assert eq <= 1.0 and ek <= 1.0 and ev <= 1.0

@@ -618,3 +618,18 @@ def test_attention_backward_by_finite_differences_and_invariants():
         vp = synth.f32_to_bf16_bits((vf + e).astype(np.float32))
         vm = synth.f32_to_bf16_bits((vf - e).astype(np.float32))
         assert abs((loss(vp) - loss(vm)) - dv[h, t, c]) < 1e-9
+
+
+def test_attention_backward_term_magnitudes():
+    # the magnitude arrays bound the gradients they belong to, and with non-negative inputs the
+    # value gradient equals its own magnitude
+    l, Hq, Hkv = 60, 4, 2
+    q, k, v, do, prm, pos, idx = _bwd_case(l, Hq, Hkv, 4, 23)
+    dq, dk, dv, mq, mk, mv = ref.sparse_attn_bwd(q, k, v, do, pos, idx, prm, want_mag=True)
+    assert np.all(np.abs(dq) <= mq + 1e-12) and np.all(np.abs(dk) <= mk + 1e-12) and np.all(np.abs(dv) <= mv + 1e-12)
+    dq2, dk2, dv2 = ref.sparse_attn_bwd(q, k, v, do, pos, idx, prm)
+    # (dk, dv are sums over threads in whatever order they finish: equal up to fp64 rounding)
+    assert np.array_equal(dq, dq2) and np.allclose(dk, dk2, rtol=0, atol=1e-12) and np.allclose(dv, dv2, rtol=0, atol=1e-12)
+    do_abs = do & np.uint16(0x7fff)
+    _, _, dv3, _, _, mv3 = ref.sparse_attn_bwd(q, k, v, do_abs, pos, idx, prm, want_mag=True)
+    assert np.allclose(dv3, mv3, rtol=0, atol=1e-12) and np.allclose(mv3, mv, rtol=0, atol=1e-12)

@@ -9,7 +9,7 @@
 // scatter (a block collects from every token that selected it).  The scatter is turned around with
 // a membership bitmap (block x token) built from the block lists, so both big kernels accumulate
 // in registers:
-//   bwd_prep_kernel     D, transposed MFMA fragments of q and dout per token, membership bits
+//   bwd_prep_kernel     D and the membership bits of every token
 //   pack_bwd_kernel     fragment-major copies of every block: K rows, V rows, K transposed
 //   attn_bwd_dq_kernel  wavefront = 2 tokens, walks the union of their block lists:
 //                       S^T = K.Q^T, dP^T = V.dO^T, dQ^T += K^T.dS^T
@@ -19,7 +19,7 @@
 //   bwd_finish_kernel   fp32 accumulators -> bf16 dk (times scale), dv
 // As in the forward, every second contraction takes its B operand straight from the accumulator
 // layout of the first (lane = column, 4 consecutive rows per 16-lane group), with the contraction
-// index of the packed A fragments permuted to match.
+// index of the A fragments permuted to match.
 #include "common.h"
 
 namespace infllmv2 {
@@ -30,12 +30,13 @@ typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kBwdBlockU4 = 3 * 16 * 64;              // uint4 per packed block: K rows, V rows, K^T (48 KiB)
 constexpr int kSegTokens = 2048;                      // member tokens of one dk/dv workgroup come from one segment
 constexpr int kSegWords = kSegTokens / 32;
+static_assert(kSegWords <= 64 && kSegTokens % 32 == 0, "the member list is compacted by one wavefront, one word per lane");
 constexpr int kBwdNone = 0x7fffffff;
 constexpr int kBwdBlkBits = 27, kBwdBlkMask = (1 << kBwdBlkBits) - 1;
 
 struct BwdLayout {
     int32_t nb_cap, words;                            // blocks per sequence; bitmap words per block row (multiple of 64)
-    size_t kvb, qt, dot, delta, bitmap, acc_dk, acc_dv, total;   // byte offsets into the workspace
+    size_t kvb, delta, bitmap, acc_dk, acc_dv, total; // byte offsets into the workspace
     size_t zero_begin, zero_bytes;                    // the part that has to start at zero (bitmap and accumulators)
 };
 static inline size_t al256(size_t x) { return (x + 255) / 256 * 256; }
@@ -46,8 +47,6 @@ static BwdLayout bwd_layout(const Dims &dm) {
     l.words = ((dm.max_seqlen + kSegTokens - 1) / kSegTokens) * kSegWords;
     size_t o = 0;
     l.kvb = o;    o += al256(BH * l.nb_cap * kBwdBlockU4 * sizeof(uint4));
-    l.qt = o;     o += al256(BH * T * 8 * 64 * sizeof(uint2));
-    l.dot = o;    o += al256(BH * T * 8 * 64 * sizeof(uint2));
     l.delta = o;  o += al256((size_t)dm.batch * T * dm.Hq * sizeof(float));
     l.zero_begin = o;
     l.bitmap = o; o += al256(BH * l.nb_cap * l.words * sizeof(uint32_t));
@@ -70,62 +69,42 @@ __global__ __launch_bounds__(256) void bwd_zero_kernel(uint4 *__restrict__ p, si
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = z;
 }
 
-// ---- per token: D, transposed fragments, membership bits ------------------------------------------
+// ---- per token: D and membership bits -----------------------------------------------------------------
 // grid (ceil(T/4), Hkv, B); wave w handles token 4*bx + w for key-value head h.
-// Transposed fragment dt of a token, lane (g, m):  X[head 4g .. 4g+3][channel 16dt + m]  (8 bytes).
-__global__ __launch_bounds__(256) void bwd_prep_kernel(Dims dm, Tensor q, Tensor out, Tensor dout,
+__global__ __launch_bounds__(256) void bwd_prep_kernel(Dims dm, Tensor out, Tensor dout,
                                                         const int32_t *__restrict__ seqlens,
                                                         const int32_t *__restrict__ block_idx,
-                                                        uint2 *__restrict__ qt, uint2 *__restrict__ dot,
                                                         float *__restrict__ delta, uint32_t *__restrict__ bitmap,
                                                         int32_t nb_cap, int32_t words) {
-    __shared__ __align__(16) uint16_t Qs[4][16 * 136];
-    __shared__ __align__(16) uint16_t Gs[4][16 * 136];
     const int h = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int tok = blockIdx.x * 4 + wave;
     const int L = seq_len(dm, seqlens, b);
-    if (tok >= L) return;                                 // per wave; no barriers below
+    if (tok >= L) return;
     const int G = dm.G;
     const int row = lane >> 2, quarter = lane & 3;        // head of the group, 32 channels
-    const int64_t qoff = b * q.sb + (int64_t)tok * q.st + (int64_t)(h * G + min(row, G - 1)) * q.sh + 32 * quarter;
     const int64_t ooff = b * out.sb + (int64_t)tok * out.st + (int64_t)(h * G + min(row, G - 1)) * out.sh + 32 * quarter;
     const int64_t goff = b * dout.sb + (int64_t)tok * dout.st + (int64_t)(h * G + min(row, G - 1)) * dout.sh + 32 * quarter;
-    uint4 xq[4], xo[4], xg[4];
+    uint4 xo[4], xg[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        xq[i] = *reinterpret_cast<const uint4 *>(q.ptr + qoff + 8 * i);
         xo[i] = *reinterpret_cast<const uint4 *>(out.ptr + ooff + 8 * i);
         xg[i] = *reinterpret_cast<const uint4 *>(dout.ptr + goff + 8 * i);
     }
     int blk = -1;
     if (lane < dm.topk) blk = block_idx[(((int64_t)b * dm.Hkv + h) * dm.max_seqlen + tok) * dm.topk + lane];
-    const bool live = row < G;                            // heads past the group are zero rows
     float dsum = 0.f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        if (!live) xq[i] = xg[i] = uint4{0u, 0u, 0u, 0u};
         const bf16x8 o8 = __builtin_bit_cast(bf16x8, xo[i]), g8 = __builtin_bit_cast(bf16x8, xg[i]);
 #pragma unroll
         for (int e = 0; e < 8; ++e) dsum += (float)o8[e] * (float)g8[e];
-        *reinterpret_cast<uint4 *>(&Qs[wave][row * 136 + 32 * quarter + 8 * i]) = xq[i];
-        *reinterpret_cast<uint4 *>(&Gs[wave][row * 136 + 32 * quarter + 8 * i]) = xg[i];
     }
     dsum += __shfl_xor(dsum, 1);
     dsum += __shfl_xor(dsum, 2);
-    if (quarter == 0 && live) delta[((int64_t)b * dm.max_seqlen + tok) * dm.Hq + h * G + row] = dsum;
+    if (quarter == 0 && row < G) delta[((int64_t)b * dm.max_seqlen + tok) * dm.Hq + h * G + row] = dsum;
     if (blk >= 0 && blk <= tok / kBlock)
         atomicOr(&bitmap[(((int64_t)b * dm.Hkv + h) * nb_cap + blk) * words + (tok >> 5)], 1u << (tok & 31));
-    // same wavefront wrote the tiles: LDS keeps the order
-    const int m = lane & 15, g = lane >> 4;
-    const int64_t frag0 = ((((int64_t)b * dm.Hkv + h) * dm.max_seqlen + tok) * 8) * 64 + lane;
-#pragma unroll
-    for (int dt = 0; dt < 8; ++dt) {
-        const uint16_t *qc = &Qs[wave][(4 * g) * 136 + 16 * dt + m];
-        const uint16_t *gc = &Gs[wave][(4 * g) * 136 + 16 * dt + m];
-        qt[frag0 + dt * 64] = uint2{(uint32_t)qc[0] | ((uint32_t)qc[136] << 16), (uint32_t)qc[272] | ((uint32_t)qc[408] << 16)};
-        dot[frag0 + dt * 64] = uint2{(uint32_t)gc[0] | ((uint32_t)gc[136] << 16), (uint32_t)gc[272] | ((uint32_t)gc[408] << 16)};
-    }
 }
 
 // ---- re-layout of one 64-token block per workgroup ---------------------------------------------------
@@ -376,47 +355,60 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(Dims dm, Tensor q, 
 
 // ---- dk, dv: a wavefront owns 16 keys of a block ---------------------------------------------------------
 // grid (nb_cap, n_seg, B*Hkv), 256 threads: workgroup (j, seg) handles the member tokens of block j
-// that lie in tokens [2048 seg, 2048 seg + 2047]; wave w the keys 64j + 16w .. +15.  The four waves
-// work independently (no barriers): each compacts the segment's membership bits into its own list
-// in LDS and walks it two tokens at a time.
+// that lie in tokens [2048 seg, 2048 seg + 2047]; wave w the keys 64j + 16w .. +15.  The member
+// tokens are compacted from the bitmap into a list and walked two at a time.  All four waves need
+// the same 16 KiB of q and dout rows per pair, so the workgroup fetches each pair once: every
+// thread keeps its 1/256 of the next three pairs in registers (memory latency is several times the
+// arithmetic of a pair) and drops a pair into one of two LDS buffers one step before it is used.
 //   S  [head, key] = Q[tok] . K^T        A = q rows of the token (lane = head), B = K rows (registers)
 //   dP [head, key] = dO[tok] . V^T
-//   dV^T[c, key]  += dO^T[c, (tok, head)] . P[(tok, head), key]      A = transposed fragments of the
-//   dK^T[c, key]  += Q^T [c, (tok, head)] . dS[(tok, head), key]     two tokens, B = P / dS as they sit
+//   dV^T[c, key]  += dO^T[c, (tok, head)] . P[(tok, head), key]      A = columns of the staged rows
+//   dK^T[c, key]  += Q^T [c, (tok, head)] . dS[(tok, head), key]     (2-byte LDS reads), B = P / dS
+// as they sit in the accumulators of the first two products.
+constexpr int kRowPitch = kHeadDim + 8;               // bf16 per staged row: conflict-free column reads
+constexpr int kPairRows = 2 * 2 * 16;                 // q rows of two tokens, dout rows of two tokens
+constexpr int kDepth = 3;                             // pairs in flight per thread
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q, Tensor dout, const uint4 *__restrict__ kvb,
-                                                                int32_t nb_cap, const uint2 *__restrict__ qt,
-                                                                const uint2 *__restrict__ dot,
-                                                                const int32_t *__restrict__ seqlens,
+                                                                int32_t nb_cap, const int32_t *__restrict__ seqlens,
                                                                 const float *__restrict__ lse,
                                                                 const float *__restrict__ delta,
                                                                 const uint32_t *__restrict__ bitmap, int32_t words,
                                                                 float *__restrict__ acc_dk, float *__restrict__ acc_dv) {
-    __shared__ int list[4][kSegTokens];
+    __shared__ int list[kSegTokens];
+    __shared__ __align__(16) uint16_t stage[2][kPairRows * kRowPitch];   // [buffer][(q | dout, token, head)][channel]
+    __shared__ __align__(16) float ld[2][2][2][16];       // [buffer][lse | D][token of the pair][head]
+    __shared__ int total_s;
     const int j = blockIdx.x, seg = blockIdx.y;
     const int b = blockIdx.z / dm.Hkv, h = blockIdx.z - b * dm.Hkv;
     const int L = seq_len(dm, seqlens, b);
     if ((seg + 1) * kSegTokens <= j * kBlock || seg * kSegTokens >= L || j * kBlock >= L) return;   // no member can be here
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, g = lane >> 4;
     const int G = dm.G;
     const float c = dm.scale_log2;
-    // ---- member tokens of this segment, ascending ------------------------------------------------------
     const int64_t bh = (int64_t)b * dm.Hkv + h;
-    uint32_t word = bitmap[(bh * nb_cap + j) * words + seg * kSegWords + lane];
-    int before = __popc(word);
+    // ---- member tokens of this segment, ascending (wave 0) ----------------------------------------------
+    if (wave == 0) {
+        uint32_t word = 0u;                               // one bitmap word per lane: a segment has at most 64 words
+        if (lane < kSegWords) word = bitmap[(bh * nb_cap + j) * words + seg * kSegWords + lane];
+        int before = __popc(word);
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int x = __shfl_up(before, o);
-        if (lane >= o) before += x;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int x = __shfl_up(before, o);
+            if (lane >= o) before += x;
+        }
+        if (lane == 63) total_s = before;
+        before -= __popc(word);
+        while (word) {
+            const int bit = __ffs(word) - 1;
+            word &= word - 1;
+            list[before++] = seg * kSegTokens + lane * 32 + bit;
+        }
     }
-    const int total = __builtin_amdgcn_readlane(before, 63);
-    if (total == 0) return;
-    before -= __popc(word);
-    while (word) {
-        const int bit = __ffs(word) - 1;
-        word &= word - 1;
-        list[wave][before++] = seg * kSegTokens + lane * 32 + bit;
-    }
+    __syncthreads();
+    const int total = total_s;
+    if (total == 0) return;                               // uniform
+    const int n_pairs = (total + 1) >> 1;
     // ---- this wave's keys as B operands: lane (n, g) = key 16w + n, channels 32ks + 8g .. +7 -----------
     const u32x4 *blk_lane = reinterpret_cast<const u32x4 *>(kvb) + (bh * nb_cap + j) * kBwdBlockU4 + lane;
     bf16x8 kB[4], vB[4];
@@ -429,58 +421,96 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) dkT[dt] = dvT[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     const int key = j * kBlock + 16 * wave + n;           // this lane's key (column of S)
-    const int hd = min(4 * g, G - 1);                     // first of this lane's four heads (rows of S)
-    for (int p = 0; p < total; p += 2) {
-        int tk[2];
-        tk[0] = __builtin_amdgcn_readfirstlane(list[wave][p]);      // uniform: keeps the addresses scalar
-        const bool two = p + 1 < total;
-        tk[1] = two ? __builtin_amdgcn_readfirstlane(list[wave][p + 1]) : tk[0];
-        bf16x8 ps, dss;                                   // B operands of the second contractions
-        u32x2 qT[2][8], gT[2][8];
+
+    // this thread's share of a pair: 16 bytes of each of the four 16-row tiles, one scalar.
+    // tile = tid>>6: q of token a, q of token b, dout of token a, dout of token b; row = (tid>>2)&15,
+    // and the thread's 16-byte pieces are channels 8*(tid&3) + 32*i .. +7, i = 0..3
+    const int f_tile = tid >> 6, f_row = (tid >> 2) & 15, f_c = 8 * (tid & 3);
+    const Tensor &src = (f_tile & 2) ? dout : q;
+    const __bf16 *f_base = src.ptr + b * src.sb + (int64_t)(h * G + min(f_row, G - 1)) * src.sh + f_c;
+    u32x4 r[kDepth][4];                                   // (ext vectors: arrays of HIP's uint4 struct end up in scratch)
+    float rf[kDepth];
+    auto fetch = [&](int p, int st) __attribute__((always_inline)) {
+        const int ta = list[min(2 * p, total - 1)], tb = list[min(2 * p + 1, total - 1)];
+        const int tok = (f_tile & 1) ? tb : ta;
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int tok = tk[u];
-            const int64_t row = (int64_t)(h * G + min(n, G - 1));
-            bf16x8 qa[4], ga[4];
+        for (int i = 0; i < 4; ++i) r[st][i] = *reinterpret_cast<const u32x4 *>(f_base + (int64_t)tok * src.st + 32 * i);
+        rf[st] = 0.f;
+        if (tid < 64) {
+            const int t2 = ((tid >> 4) & 1) ? tb : ta;
+            const int64_t o = ((int64_t)b * dm.max_seqlen + t2) * dm.Hq + h * G + min(tid & 15, G - 1);
+            rf[st] = (tid >> 5) ? delta[o] : lse[o];
+        }
+    };
+    auto stash = [&](int buf, int st) __attribute__((always_inline)) {
+        uint16_t *dst = &stage[buf][(f_tile * 16 + f_row) * kRowPitch + f_c];
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                qa[ks] = load8(q.ptr + b * q.sb + (int64_t)tok * q.st + row * q.sh + 32 * ks + 8 * g);
-                ga[ks] = load8(dout.ptr + b * dout.sb + (int64_t)tok * dout.st + row * dout.sh + 32 * ks + 8 * g);
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(dst + 32 * i) = r[st][i];
+        if (tid < 64) ld[buf][tid >> 5][(tid >> 4) & 1][tid & 15] = rf[st];
+    };
+
+    // pairs past the end are fetched as copies of the last one and never used
+#pragma unroll
+    for (int st = 0; st < kDepth; ++st) fetch(st, st);
+    stash(0, 0);
+    fetch(kDepth, 0);
+    __syncthreads();
+    for (int p0 = 0; p0 < n_pairs; p0 += kDepth) {
+#pragma unroll
+        for (int kk = 0; kk < kDepth; ++kk) {
+            const int p = p0 + kk;
+            if (p >= n_pairs) break;                      // uniform
+            const int cur = p & 1;
+            const bool two = 2 * p + 1 < total;
+            const int tk0 = list[2 * p], tk1 = two ? list[2 * p + 1] : tk0;
+            const uint16_t *sq = stage[cur];
+            bf16x8 ps, dss;                               // B operands of the second contractions
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int tok = u ? tk1 : tk0;
+                f32x4 sacc = {0.f, 0.f, 0.f, 0.f}, dp = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const bf16x8 qa = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&sq[(u * 16 + n) * kRowPitch + 32 * ks + 8 * g]));
+                    const bf16x8 ga = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&sq[((2 + u) * 16 + n) * kRowPitch + 32 * ks + 8 * g]));
+                    sacc = mfma16(qa, kB[ks], sacc);
+                    dp = mfma16(ga, vB[ks], dp);
+                }
+                const float4 l4 = *reinterpret_cast<const float4 *>(&ld[cur][0][u][4 * g]);
+                const float4 d4 = *reinterpret_cast<const float4 *>(&ld[cur][1][u][4 * g]);
+                const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
+                const bool dead = (u == 1 && !two) || key > tok;   // padding of an odd tail; causal inside the own block
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    float pr = fast_exp2(__builtin_fmaf(sacc[rr], c, -ls[rr] * kLog2e));
+                    if (dead || 4 * g + rr >= G || !(ls[rr] > -INFINITY)) pr = 0.f;
+                    ps[4 * u + rr] = (__bf16)pr;
+                    dss[4 * u + rr] = (__bf16)(pr * (dp[rr] - dl[rr]));
+                }
             }
-            const int64_t f0 = ((bh * dm.max_seqlen + tok) * 8) * 64 + lane;
+            // A operands of the second products: lane (n = channel, g), element 4u + e = (token u, head 4g + e)
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) {
-                qT[u][dt] = *reinterpret_cast<const u32x2 *>(qt + f0 + dt * 64);
-                gT[u][dt] = *reinterpret_cast<const u32x2 *>(dot + f0 + dt * 64);
-            }
-            float ls[4], dl[4];
+                uint32_t wq[4], wg[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int64_t o = ((int64_t)b * dm.max_seqlen + tok) * dm.Hq + h * G + min(hd + r, G - 1);
-                ls[r] = lse[o];
-                dl[r] = delta[o];
+                for (int u = 0; u < 2; ++u) {
+                    const uint16_t *cq = &sq[(u * 16 + 4 * g) * kRowPitch + 16 * dt + n];
+                    const uint16_t *cg = &sq[((2 + u) * 16 + 4 * g) * kRowPitch + 16 * dt + n];
+                    wq[2 * u] = (uint32_t)cq[0] | ((uint32_t)cq[kRowPitch] << 16);
+                    wq[2 * u + 1] = (uint32_t)cq[2 * kRowPitch] | ((uint32_t)cq[3 * kRowPitch] << 16);
+                    wg[2 * u] = (uint32_t)cg[0] | ((uint32_t)cg[kRowPitch] << 16);
+                    wg[2 * u + 1] = (uint32_t)cg[2 * kRowPitch] | ((uint32_t)cg[3 * kRowPitch] << 16);
+                }
+                const u32x4 aq = {wq[0], wq[1], wq[2], wq[3]}, ag = {wg[0], wg[1], wg[2], wg[3]};
+                dvT[dt] = mfma16(__builtin_bit_cast(bf16x8, ag), ps, dvT[dt]);
+                dkT[dt] = mfma16(__builtin_bit_cast(bf16x8, aq), dss, dkT[dt]);
             }
-            f32x4 s = {0.f, 0.f, 0.f, 0.f}, dp = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                s = mfma16(qa[ks], kB[ks], s);
-                dp = mfma16(ga[ks], vB[ks], dp);
-            }
-            const bool dead = (u == 1 && !two) || key > tok;   // padding of an odd tail; causal inside the own block
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                float pr = fast_exp2(__builtin_fmaf(s[r], c, -ls[r] * kLog2e));
-                if (dead || 4 * g + r >= G || !(ls[r] > -INFINITY)) pr = 0.f;
-                ps[4 * u + r] = (__bf16)pr;
-                dss[4 * u + r] = (__bf16)(pr * (dp[r] - dl[r]));
-            }
-        }
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-            const u32x4 aq = {qT[0][dt].x, qT[0][dt].y, qT[1][dt].x, qT[1][dt].y};
-            const u32x4 ag = {gT[0][dt].x, gT[0][dt].y, gT[1][dt].x, gT[1][dt].y};
-            dvT[dt] = mfma16(__builtin_bit_cast(bf16x8, ag), ps, dvT[dt]);
-            dkT[dt] = mfma16(__builtin_bit_cast(bf16x8, aq), dss, dkT[dt]);
+            // pair p+1 goes to the other buffer (last read one step ago), its registers take pair p+1+kDepth
+            constexpr int kD = kDepth;
+            const int st = (kk + 1) % kD;
+            stash(cur ^ 1, st);
+            fetch(p + 1 + kD, st);
+            __syncthreads();
         }
     }
     // ---- merge: lane holds channels 16*dt + 4*g .. +3 of its key --------------------------------------------
@@ -490,9 +520,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                unsafeAtomicAdd(pk + 16 * dt + r, dkT[dt][r]);
-                unsafeAtomicAdd(pv + 16 * dt + r, dvT[dt][r]);
+            for (int rr = 0; rr < 4; ++rr) {
+                unsafeAtomicAdd(pk + 16 * dt + rr, dkT[dt][rr]);
+                unsafeAtomicAdd(pv + 16 * dt + rr, dvT[dt][rr]);
             }
     }
 }
@@ -528,7 +558,6 @@ int launch_attn_bwd(const Dims &dm, Tensor q, Tensor k, Tensor v, Tensor out, Te
     const BwdLayout l = bwd_layout(dm);
     char *base = reinterpret_cast<char *>(ws);
     uint4 *kvb = reinterpret_cast<uint4 *>(base + l.kvb);
-    uint2 *qt = reinterpret_cast<uint2 *>(base + l.qt), *dot = reinterpret_cast<uint2 *>(base + l.dot);
     float *delta = reinterpret_cast<float *>(base + l.delta);
     uint32_t *bitmap = reinterpret_cast<uint32_t *>(base + l.bitmap);
     float *acc_dk = reinterpret_cast<float *>(base + l.acc_dk), *acc_dv = reinterpret_cast<float *>(base + l.acc_dv);
@@ -538,8 +567,8 @@ int launch_attn_bwd(const Dims &dm, Tensor q, Tensor k, Tensor v, Tensor out, Te
                        l.zero_bytes / sizeof(uint4));
     timing_end(stream);
     timing_begin("bwd_prep_kernel", stream);
-    hipLaunchKernelGGL(bwd_prep_kernel, dim3((T + 3) / 4, dm.Hkv, dm.batch), dim3(256), 0, stream, dm, q, out, dout,
-                       seqlens, block_idx, qt, dot, delta, bitmap, l.nb_cap, l.words);
+    hipLaunchKernelGGL(bwd_prep_kernel, dim3((T + 3) / 4, dm.Hkv, dm.batch), dim3(256), 0, stream, dm, out, dout,
+                       seqlens, block_idx, delta, bitmap, l.nb_cap, l.words);
     timing_end(stream);
     timing_begin("pack_bwd_kernel", stream);
     hipLaunchKernelGGL(pack_bwd_kernel, dim3(l.nb_cap, dm.Hkv, dm.batch), dim3(256), 0, stream, dm, k, v, seqlens, kvb,
@@ -552,7 +581,7 @@ int launch_attn_bwd(const Dims &dm, Tensor q, Tensor k, Tensor v, Tensor out, Te
     timing_end(stream);
     timing_begin("attn_bwd_dkdv_kernel", stream);
     hipLaunchKernelGGL(attn_bwd_dkdv_kernel, dim3(l.nb_cap, l.words / kSegWords, dm.batch * dm.Hkv), dim3(256), 0, stream,
-                       dm, q, dout, kvb, l.nb_cap, qt, dot, seqlens, lse, delta, bitmap, l.words, acc_dk, acc_dv);
+                       dm, q, dout, kvb, l.nb_cap, seqlens, lse, delta, bitmap, l.words, acc_dk, acc_dv);
     timing_end(stream);
     timing_begin("bwd_finish_kernel", stream);
     hipLaunchKernelGGL(bwd_finish_kernel, dim3((T + 15) / 16, dm.Hkv, dm.batch), dim3(256), 0, stream, dm, seqlens,

@@ -359,13 +359,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(Dims dm, Tensor q, 
 // tokens are compacted from the bitmap into a list and walked two at a time.  All four waves need
 // the same 16 KiB of q and dout rows per pair, so the workgroup fetches each pair once: every
 // thread keeps its 1/256 of the next three pairs in registers (memory latency is several times the
-// arithmetic of a pair) and drops a pair into one of two LDS buffers one step before it is used.
+// arithmetic of a pair) and drops a pair into one of two LDS buffers one step before it is used,
+// as rows and, transposed in registers, as columns.
 //   S  [head, key] = Q[tok] . K^T        A = q rows of the token (lane = head), B = K rows (registers)
 //   dP [head, key] = dO[tok] . V^T
-//   dV^T[c, key]  += dO^T[c, (tok, head)] . P[(tok, head), key]      A = columns of the staged rows
-//   dK^T[c, key]  += Q^T [c, (tok, head)] . dS[(tok, head), key]     (2-byte LDS reads), B = P / dS
+//   dV^T[c, key]  += dO^T[c, (tok, head)] . P[(tok, head), key]      A = the staged columns,
+//   dK^T[c, key]  += Q^T [c, (tok, head)] . dS[(tok, head), key]     B = P / dS
 // as they sit in the accumulators of the first two products.
-constexpr int kRowPitch = kHeadDim + 8;               // bf16 per staged row: conflict-free column reads
+constexpr int kRowPitch = kHeadDim + 8;               // bf16 per staged row (272 bytes: rows start 4 banks apart)
 constexpr int kPairRows = 2 * 2 * 16;                 // q rows of two tokens, dout rows of two tokens
 constexpr int kDepth = 3;                             // pairs in flight per thread
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q, Tensor dout, const uint4 *__restrict__ kvb,
@@ -376,6 +377,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
                                                                 float *__restrict__ acc_dk, float *__restrict__ acc_dv) {
     __shared__ int list[kSegTokens];
     __shared__ __align__(16) uint16_t stage[2][kPairRows * kRowPitch];   // [buffer][(q | dout, token, head)][channel]
+    __shared__ __align__(16) uint16_t stageT[2][4 * 8 * 64 * 4];         // [buffer][(tile, dt, lane)][4 heads]
     __shared__ __align__(16) float ld[2][2][2][16];       // [buffer][lse | D][token of the pair][head]
     __shared__ int total_s;
     const int j = blockIdx.x, seg = blockIdx.y;
@@ -422,30 +424,51 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
     for (int dt = 0; dt < 8; ++dt) dkT[dt] = dvT[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     const int key = j * kBlock + 16 * wave + n;           // this lane's key (column of S)
 
-    // this thread's share of a pair: 16 bytes of each of the four 16-row tiles, one scalar.
-    // tile = tid>>6: q of token a, q of token b, dout of token a, dout of token b; row = (tid>>2)&15,
-    // and the thread's 16-byte pieces are channels 8*(tid&3) + 32*i .. +7, i = 0..3
-    const int f_tile = tid >> 6, f_row = (tid >> 2) & 15, f_c = 8 * (tid & 3);
+    // this thread's share of a pair: a 4-head x 8-channel patch of one of the four 16-row tiles
+    // (tile = tid>>6: q of token a, q of token b, dout of token a, dout of token b; heads 4*f_g .. +3,
+    // channels 8*f_pc .. +7), one scalar.  The patch goes to LDS twice: as rows (A operands of the
+    // first products, 16 bytes per head) and transposed (A operands of the second products: lane
+    // (n = channel, g) reads heads 4g .. 4g+3 of its channel as 8 bytes).
+    const int f_tile = tid >> 6, f_g = (tid >> 4) & 3, f_pc = tid & 15;
     const Tensor &src = (f_tile & 2) ? dout : q;
-    const __bf16 *f_base = src.ptr + b * src.sb + (int64_t)(h * G + min(f_row, G - 1)) * src.sh + f_c;
+    const __bf16 *f_base[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        f_base[e] = src.ptr + b * src.sb + (int64_t)(h * G + min(4 * f_g + e, G - 1)) * src.sh + 8 * f_pc;
     u32x4 r[kDepth][4];                                   // (ext vectors: arrays of HIP's uint4 struct end up in scratch)
     float rf[kDepth];
     auto fetch = [&](int p, int st) __attribute__((always_inline)) {
         const int ta = list[min(2 * p, total - 1)], tb = list[min(2 * p + 1, total - 1)];
         const int tok = (f_tile & 1) ? tb : ta;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) r[st][i] = *reinterpret_cast<const u32x4 *>(f_base + (int64_t)tok * src.st + 32 * i);
-        rf[st] = 0.f;
-        if (tid < 64) {
+        for (int e = 0; e < 4; ++e) r[st][e] = *reinterpret_cast<const u32x4 *>(f_base[e] + (int64_t)tok * src.st);
+        {   // every thread loads (a fixed number of loads per step keeps the wait counts exact); 64 values are kept
             const int t2 = ((tid >> 4) & 1) ? tb : ta;
             const int64_t o = ((int64_t)b * dm.max_seqlen + t2) * dm.Hq + h * G + min(tid & 15, G - 1);
-            rf[st] = (tid >> 5) ? delta[o] : lse[o];
+            rf[st] = ((tid >> 5) & 1 ? delta : lse)[o];
         }
     };
     auto stash = [&](int buf, int st) __attribute__((always_inline)) {
-        uint16_t *dst = &stage[buf][(f_tile * 16 + f_row) * kRowPitch + f_c];
+        uint16_t *dst = &stage[buf][(f_tile * 16 + 4 * f_g) * kRowPitch + 8 * f_pc];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(dst + 32 * i) = r[st][i];
+        for (int e = 0; e < 4; ++e) {
+            u32x4 x = r[st][e];
+            if (4 * f_g + e >= G) x = u32x4{0u, 0u, 0u, 0u};        // heads past the group are zero rows
+            *reinterpret_cast<u32x4 *>(dst + e * kRowPitch) = x;
+        }
+        // transposed: channel 8*f_pc + cc -> fragment dt = f_pc/2, lane (f_g, m = 8*(f_pc&1) + cc): heads 4f_g .. +3
+        u32x4 *tdst = reinterpret_cast<u32x4 *>(&stageT[buf][((f_tile * 8 + (f_pc >> 1)) * 64 + f_g * 16 + 8 * (f_pc & 1)) * 4]);
+#pragma unroll
+        for (int c2 = 0; c2 < 4; ++c2) {                  // channels 2*c2, 2*c2+1 sit in word c2 of every head's piece
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w[e] = (4 * f_g + e < G) ? r[st][e][c2] : 0u;
+            const uint32_t lo01 = __builtin_amdgcn_perm(w[1], w[0], 0x05040100u);   // low halves of heads 0, 1
+            const uint32_t lo23 = __builtin_amdgcn_perm(w[3], w[2], 0x05040100u);
+            const uint32_t hi01 = __builtin_amdgcn_perm(w[1], w[0], 0x07060302u);   // high halves
+            const uint32_t hi23 = __builtin_amdgcn_perm(w[3], w[2], 0x07060302u);
+            tdst[c2] = u32x4{lo01, lo23, hi01, hi23};     // channel 2*c2 (8 bytes), channel 2*c2+1 (8 bytes)
+        }
         if (tid < 64) ld[buf][tid >> 5][(tid >> 4) & 1][tid & 15] = rf[st];
     };
 
@@ -471,8 +494,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
                 f32x4 sacc = {0.f, 0.f, 0.f, 0.f}, dp = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {
-                    const bf16x8 qa = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&sq[(u * 16 + n) * kRowPitch + 32 * ks + 8 * g]));
-                    const bf16x8 ga = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&sq[((2 + u) * 16 + n) * kRowPitch + 32 * ks + 8 * g]));
+                    const bf16x8 qa = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&sq[(u * 16 + n) * kRowPitch + 32 * ks + 8 * g]));
+                    const bf16x8 ga = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&sq[((2 + u) * 16 + n) * kRowPitch + 32 * ks + 8 * g]));
                     sacc = mfma16(qa, kB[ks], sacc);
                     dp = mfma16(ga, vB[ks], dp);
                 }
@@ -489,25 +512,19 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
                 }
             }
             // A operands of the second products: lane (n = channel, g), element 4u + e = (token u, head 4g + e)
+            const u32x2 *tq = reinterpret_cast<const u32x2 *>(stageT[cur]);
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) {
-                uint32_t wq[4], wg[4];
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const uint16_t *cq = &sq[(u * 16 + 4 * g) * kRowPitch + 16 * dt + n];
-                    const uint16_t *cg = &sq[((2 + u) * 16 + 4 * g) * kRowPitch + 16 * dt + n];
-                    wq[2 * u] = (uint32_t)cq[0] | ((uint32_t)cq[kRowPitch] << 16);
-                    wq[2 * u + 1] = (uint32_t)cq[2 * kRowPitch] | ((uint32_t)cq[3 * kRowPitch] << 16);
-                    wg[2 * u] = (uint32_t)cg[0] | ((uint32_t)cg[kRowPitch] << 16);
-                    wg[2 * u + 1] = (uint32_t)cg[2 * kRowPitch] | ((uint32_t)cg[3 * kRowPitch] << 16);
-                }
-                const u32x4 aq = {wq[0], wq[1], wq[2], wq[3]}, ag = {wg[0], wg[1], wg[2], wg[3]};
+                const u32x2 q0 = tq[(0 * 8 + dt) * 64 + lane], q1 = tq[(1 * 8 + dt) * 64 + lane];
+                const u32x2 g0 = tq[(2 * 8 + dt) * 64 + lane], g1 = tq[(3 * 8 + dt) * 64 + lane];
+                const u32x4 aq = {q0.x, q0.y, q1.x, q1.y}, ag = {g0.x, g0.y, g1.x, g1.y};
                 dvT[dt] = mfma16(__builtin_bit_cast(bf16x8, ag), ps, dvT[dt]);
                 dkT[dt] = mfma16(__builtin_bit_cast(bf16x8, aq), dss, dkT[dt]);
             }
             // pair p+1 goes to the other buffer (last read one step ago), its registers take pair p+1+kDepth
             constexpr int kD = kDepth;
             const int st = (kk + 1) % kD;
+            __builtin_amdgcn_sched_barrier(0);            // keep the wait for this pair's registers behind the arithmetic
             stash(cur ^ 1, st);
             fetch(p + 1 + kD, st);
             __syncthreads();

@@ -173,7 +173,7 @@ __device__ inline uint32_t bwd_xcd_contiguous_id(uint32_t bid, uint32_t n) {
 //   K rows of key tile 2hs, of key tile 2hs+1      -> S^T  = K . Q^T
 //   V rows of key tile 2hs, of key tile 2hs+1      -> dP^T = V . dO^T
 //   K^T of the half for channel tiles 0..3, 4..7   -> dQ^T += K^T . dS^T
-constexpr int kDqTok = 2, kDqRing = 4, kDqUnits = 12;
+constexpr int kDqTok = 2, kDqRing = 3, kDqUnits = 12;
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(Dims dm, Tensor q, Tensor dout, const uint4 *__restrict__ kvb,
                                                               int32_t nb_cap, const int32_t *__restrict__ seqlens,
                                                               const int32_t *__restrict__ block_idx,

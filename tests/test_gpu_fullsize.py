@@ -201,3 +201,59 @@ def test_decode_graph_replays_match_eager():
         assert torch.equal(g_st["out"].view(torch.int16), e_st["out"].view(torch.int16)), r
         assert torch.equal(g_st["lse"], e_st["lse"]), r
         assert torch.equal(g_st["ck"].view(torch.int16), e_st["ck"].view(torch.int16)), r
+
+
+@pytest.mark.timeout(600)
+def test_backward_32k_sampled_rows_and_identities():
+    # backward of the attention at the benchmark's size and launch configuration: dq on sampled
+    # rows and dk, dv on the last two blocks (which only the last 128 tokens attend) against the
+    # oracle; two identities that hold at any size on the whole tensors
+    from util import grad_err
+    cfg = synth.CONFIGS[1]
+    print("workload", cfg.name, "backward", flush=True)
+    x = synth.make_prefill(cfg)
+    l, Hq, Hkv = cfg.seqlen, cfg.n_q_heads, cfg.n_kv_heads
+    G = Hq // Hkv
+    prm = binding.Params(Hq, Hkv, topk=cfg.topk)
+    oprm = oracle_params(prm)
+    q, k, v = to_dev(x.q)[None], to_dev(x.k)[None], to_dev(x.v)[None]
+    sl = torch.tensor([l], dtype=torch.int32, device="cuda")
+    ck = binding.compress_keys(prm, k, sl, l)
+    idx = binding.select_blocks(prm, binding.MODE_PREFILL, q, ck, sl, l)
+    out, lse = binding.sparse_attn_prefill(prm, q, k, v, sl, l, idx)
+    gen = torch.Generator(device="cuda").manual_seed(77)
+    do = torch.randn(q.shape, device="cuda", generator=gen).bfloat16()
+    dq, dk, dv = binding.sparse_attn_bwd(prm, q, k, v, out, do, lse, sl, l, idx)
+    torch.cuda.synchronize()
+    print("gpu path done", flush=True)
+    assert bool(torch.isfinite(dq.float()).all()) and bool(torch.isfinite(dk.float()).all()) and bool(torch.isfinite(dv.float()).all())
+    do_bits = to_bits(do)[0]
+    idx_np = idx[0].cpu().numpy()
+    # dq of sampled rows
+    rows = sample_rows(l, 24, 4242)
+    wq, _, _, mq, _, _ = ref.sparse_attn_bwd(np.ascontiguousarray(x.q[rows]), x.k, x.v, np.ascontiguousarray(do_bits[rows]),
+                                             rows, np.ascontiguousarray(idx_np[:, rows]), oprm, want_mag=True)
+    ri = torch.from_numpy(rows).long().cuda()
+    eq = grad_err(dq[0, ri].double().cpu().numpy(), wq, mq)
+    print("dq on %d sampled rows: err/tol %.3f" % (len(rows), eq), flush=True)
+    assert eq <= 1.0
+    # dk, dv of the last two blocks: only the last 128 tokens attend them
+    tail = np.arange(l - 128, l, dtype=np.int32)
+    _, wk, wv, _, mk, mv = ref.sparse_attn_bwd(np.ascontiguousarray(x.q[tail]), x.k, x.v, np.ascontiguousarray(do_bits[tail]),
+                                               tail, np.ascontiguousarray(idx_np[:, tail]), oprm, want_mag=True)
+    ek = grad_err(dk[0, :, l - 128:].double().cpu().numpy(), wk[:, l - 128:], mk[:, l - 128:])
+    ev = grad_err(dv[0, :, l - 128:].double().cpu().numpy(), wv[:, l - 128:], mv[:, l - 128:])
+    print("dk, dv on the last 128 keys: err/tol %.3f %.3f" % (ek, ev), flush=True)
+    assert ek <= 1.0 and ev <= 1.0
+    # probabilities of a row sum to one: the value gradients of a head add up to the output gradients of its group
+    dvs = dv[0].double().sum(1)                                                   # [Hkv, d]
+    dos = do[0].double().view(l, Hkv, G, -1).sum((0, 2))
+    scale = do[0].double().abs().view(l, Hkv, G, -1).sum((0, 2))
+    e1 = float(((dvs - dos).abs() / scale).max())
+    # sum_t <dk_t, k_t> = sum_i <dq_i, q_i> (both are scale * sum ds z / scale), per key-value head
+    a = (dk[0].double() * k[0].double()).sum((1, 2))
+    bq = (dq[0].double() * q[0].double()).view(l, Hkv, G, -1).sum((0, 2, 3))
+    sa = (dk[0].double() * k[0].double()).abs().sum((1, 2))
+    e2 = float(((a - bq).abs() / sa).max())
+    print("identities: sum dv vs sum dout %.2e of the term sizes, <dk,k> vs <dq,q> %.2e" % (e1, e2), flush=True)
+    assert e1 < 2.0 ** -8 and e2 < 2.0 ** -8

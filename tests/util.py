@@ -13,6 +13,26 @@ LSE_TOL = 1e-5
 NEAR_TIE = 1e-3
 
 
+GRAD_EPS = 2.0 ** -8          # unit roundoff of bf16 (8 significant bits, round to nearest)
+
+
+def grad_err(got, want, mag):
+    """Largest error of a gradient tensor in units of its tolerance (<= 1 passes).  `mag` is the
+    oracle's sum of the absolute values of the terms behind each element, including the terms by
+    which D = <dout, out> moves when `out` is a bf16-rounded copy.  Every term carries relative
+    rounding errors of up to 2^-8 (probabilities and their derivatives go to the second contraction
+    in bf16, `out` is bf16) and the result one more.  A value gradient has exactly one rounding per
+    term plus its own, so |error| <= 2^-8 (mag + |dv|) holds strictly; for dq and dk the terms carry
+    up to three roundings, which aligned would add up to 3 * 2^-8 * mag and in practice add like a
+    random walk: the same bound is used (observed: a third of it)."""
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    if want.size == 0:
+        return 0.0
+    tol = GRAD_EPS * (mag + np.abs(want)) + 1e-30
+    return float(np.max(np.abs(got - want) / tol))
+
+
 def lse_err(got, want):
     """Largest log-sum-exp error in units of its tolerance (<= 1 passes).  The tolerance is the
     stated 1e-5 absolute, widened to 2^-20 * |LSE| (16 fp32 ulps) where |LSE| is so large that

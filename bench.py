@@ -142,6 +142,36 @@ def bench_prefill(args):
         "kernels_ms": kern_ms, "attended_flops": attended_flops, "scoring_flops_per_pass": score_flops,
         "attn_only_tflops": attended_flops / (kern_ms["attn_prefill_kernel"] * 1e-3) / 1e12,
     }
+    if not args.no_backward:
+        # backward of the attention (training): gradients to q, k, v for a random upstream gradient
+        gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+        dout = torch.randn(q.shape, device="cuda", generator=gen).bfloat16()
+        dq, dk, dv = torch.zeros_like(q), torch.zeros_like(k), torch.zeros_like(v)
+        ws_b = torch.empty(binding.workspace_bytes(binding.OP_ATTN_BWD, prm, 1, l), dtype=torch.uint8, device="cuda")
+        bwd = lambda: binding.sparse_attn_bwd(prm, q, k, v, out, dout, lse, sl, l, idx, dq=dq, dk=dk, dv=dv, workspace=ws_b)
+        for _ in range(max(1, args.warmup)):
+            bwd()
+        torch.cuda.synchronize()
+        binding.timing_enable(True)
+        n_b = max(1, min(args.steps, 10))
+        t0 = time.perf_counter()
+        for _ in range(n_b):
+            bwd()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        per_b = {}
+        for name, ms in binding.timing_read():
+            per_b.setdefault(name, []).append(ms)
+        binding.timing_enable(False)
+        ms_b = (t1 - t0) * 1e3 / n_b
+        bflops = attended_flops * 2.5                  # five contractions of the forward's two
+        res["backward"] = {"ms_per_pass": ms_b, "passes": n_b, "useful_flops": bflops,
+                           "tflops": bflops / (ms_b * 1e-3) / 1e12,
+                           "frac_bf16_peak": bflops / (ms_b * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                           "kernels_ms": {n: float(np.mean(v_)) for n, v_ in per_b.items()},
+                           "executed_flops_note": "dq recomputes S and dP (3 contractions), dk/dv recomputes them "
+                                                  "again (4): 3.5x the forward's matrix work is executed, 2.5x counted"}
+        del dq, dk, dv, dout, ws_b
     return res, (x, idx, out, lse, prm, cfg)
 
 
@@ -389,6 +419,7 @@ def main():
     ap.add_argument("--verify-draft", type=int, default=16, help="drafted tokens per verification step (0: skip the leg)")
     ap.add_argument("--verify-steps", type=int, default=50)
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-backward", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=32768)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -435,6 +466,8 @@ def main():
         "scoring_flops_per_pass": res["scoring_flops_per_pass"],
         "roofline": res["roofline"],
     }
+    if "backward" in res:
+        line["backward"] = res["backward"]
     mp = measured_peaks()
     line["measured_peaks"] = mp
     rf = line["roofline"]

@@ -457,7 +457,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
             *reinterpret_cast<u32x4 *>(dst + e * kRowPitch) = x;
         }
         // transposed: channel 8*f_pc + cc -> fragment dt = f_pc/2, lane (f_g, m = 8*(f_pc&1) + cc): heads 4f_g .. +3
-        u32x4 *tdst = reinterpret_cast<u32x4 *>(&stageT[buf][((f_tile * 8 + (f_pc >> 1)) * 64 + f_g * 16 + 8 * (f_pc & 1)) * 4]);
+        // (the 16-byte chunks of a fragment are XOR-swizzled with its index dt so that the 16 lanes of a
+        // write, which differ in dt, spread over all banks; a read has dt fixed and stays contiguous)
+        const int t_dt = f_pc >> 1, t_swz = (t_dt & 3) | ((t_dt >> 2) << 3);
+        u32x4 *trow = reinterpret_cast<u32x4 *>(&stageT[buf][(f_tile * 8 + t_dt) * 64 * 4]);
+        const int t_chunk = f_g * 8 + 4 * (f_pc & 1);
 #pragma unroll
         for (int c2 = 0; c2 < 4; ++c2) {                  // channels 2*c2, 2*c2+1 sit in word c2 of every head's piece
             uint32_t w[4];
@@ -467,7 +471,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
             const uint32_t lo23 = __builtin_amdgcn_perm(w[3], w[2], 0x05040100u);
             const uint32_t hi01 = __builtin_amdgcn_perm(w[1], w[0], 0x07060302u);   // high halves
             const uint32_t hi23 = __builtin_amdgcn_perm(w[3], w[2], 0x07060302u);
-            tdst[c2] = u32x4{lo01, lo23, hi01, hi23};     // channel 2*c2 (8 bytes), channel 2*c2+1 (8 bytes)
+            trow[(t_chunk + c2) ^ t_swz] = u32x4{lo01, lo23, hi01, hi23};   // channel 2*c2 (8 bytes), channel 2*c2+1 (8 bytes)
         }
         if (tid < 64) ld[buf][tid >> 5][(tid >> 4) & 1][tid & 15] = rf[st];
     };
@@ -478,14 +482,16 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
     stash(0, 0);
     fetch(kDepth, 0);
     __syncthreads();
+    // The trip count is rounded up to a multiple of kDepth and the steps past the end work on copies of
+    // the last pair with every probability forced to zero: one loop exit, so the compiler's count of
+    // loads still in flight is the same on every path into a step and its waits stay exact.
     for (int p0 = 0; p0 < n_pairs; p0 += kDepth) {
 #pragma unroll
         for (int kk = 0; kk < kDepth; ++kk) {
             const int p = p0 + kk;
-            if (p >= n_pairs) break;                      // uniform
             const int cur = p & 1;
-            const bool two = 2 * p + 1 < total;
-            const int tk0 = list[2 * p], tk1 = two ? list[2 * p + 1] : tk0;
+            const bool one = 2 * p < total, two = 2 * p + 1 < total;
+            const int tk0 = list[min(2 * p, total - 1)], tk1 = list[min(2 * p + 1, total - 1)];
             const uint16_t *sq = stage[cur];
             bf16x8 ps, dss;                               // B operands of the second contractions
 #pragma unroll
@@ -502,7 +508,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
                 const float4 l4 = *reinterpret_cast<const float4 *>(&ld[cur][0][u][4 * g]);
                 const float4 d4 = *reinterpret_cast<const float4 *>(&ld[cur][1][u][4 * g]);
                 const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
-                const bool dead = (u == 1 && !two) || key > tok;   // padding of an odd tail; causal inside the own block
+                const bool dead = !(u ? two : one) || key > tok;   // padding past the end of the list; causal inside the own block
 #pragma unroll
                 for (int rr = 0; rr < 4; ++rr) {
                     float pr = fast_exp2(__builtin_fmaf(sacc[rr], c, -ls[rr] * kLog2e));
@@ -515,8 +521,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
             const u32x2 *tq = reinterpret_cast<const u32x2 *>(stageT[cur]);
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) {
-                const u32x2 q0 = tq[(0 * 8 + dt) * 64 + lane], q1 = tq[(1 * 8 + dt) * 64 + lane];
-                const u32x2 g0 = tq[(2 * 8 + dt) * 64 + lane], g1 = tq[(3 * 8 + dt) * 64 + lane];
+                const int sl = ((((lane >> 1) ^ ((dt & 3) | ((dt >> 2) << 3))) << 1) | (lane & 1));   // swizzled slot of this lane
+                const u32x2 q0 = tq[(0 * 8 + dt) * 64 + sl], q1 = tq[(1 * 8 + dt) * 64 + sl];
+                const u32x2 g0 = tq[(2 * 8 + dt) * 64 + sl], g1 = tq[(3 * 8 + dt) * 64 + sl];
                 const u32x4 aq = {q0.x, q0.y, q1.x, q1.y}, ag = {g0.x, g0.y, g1.x, g1.y};
                 dvT[dt] = mfma16(__builtin_bit_cast(bf16x8, ag), ps, dvT[dt]);
                 dkT[dt] = mfma16(__builtin_bit_cast(bf16x8, aq), dss, dkT[dt]);

@@ -377,7 +377,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
                                                                 float *__restrict__ acc_dk, float *__restrict__ acc_dv) {
     __shared__ int list[kSegTokens];
     __shared__ __align__(16) uint16_t stage[2][kPairRows * kRowPitch];   // [buffer][(q | dout, token, head)][channel]
-    __shared__ __align__(16) uint16_t stageT[2][4 * 8 * 64 * 4];         // [buffer][(tile, dt, lane)][4 heads]
+    __shared__ __align__(16) uint16_t stageT[2][2 * 8 * 64 * 8];         // [buffer][(q | dout, dt, lane)][token][4 heads]
     __shared__ __align__(16) float ld[2][2][2][16];       // [buffer][lse | D][token of the pair][head]
     __shared__ int total_s;
     const int j = blockIdx.x, seg = blockIdx.y;
@@ -456,12 +456,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
             if (4 * f_g + e >= G) x = u32x4{0u, 0u, 0u, 0u};        // heads past the group are zero rows
             *reinterpret_cast<u32x4 *>(dst + e * kRowPitch) = x;
         }
-        // transposed: channel 8*f_pc + cc -> fragment dt = f_pc/2, lane (f_g, m = 8*(f_pc&1) + cc): heads 4f_g .. +3
-        // (the 16-byte chunks of a fragment are XOR-swizzled with its index dt so that the 16 lanes of a
-        // write, which differ in dt, spread over all banks; a read has dt fixed and stays contiguous)
-        const int t_dt = f_pc >> 1, t_swz = (t_dt & 3) | ((t_dt >> 2) << 3);
-        u32x4 *trow = reinterpret_cast<u32x4 *>(&stageT[buf][(f_tile * 8 + t_dt) * 64 * 4]);
-        const int t_chunk = f_g * 8 + 4 * (f_pc & 1);
+        // transposed: channel 8*f_pc + cc -> fragment dt = f_pc/2, lane (f_g, m = 8*(f_pc&1) + cc): heads 4f_g .. +3.
+        // Layout [q | dout][dt][lane][token of the pair][4 heads]: a lane finds the 16 bytes of one A operand
+        // in one piece.  The 16-byte slots of a fragment are XOR-swizzled with dt & 7 so that the 16 lanes of
+        // a store, which differ in dt, spread over all banks; a load has dt fixed and stays a permutation.
+        const int t_dt = f_pc >> 1;
+        u32x2 *trow = reinterpret_cast<u32x2 *>(&stageT[buf][(((f_tile >> 1) * 8 + t_dt) * 64) * 8]) + (f_tile & 1);
+        const int t_lane = f_g * 16 + 8 * (f_pc & 1);
 #pragma unroll
         for (int c2 = 0; c2 < 4; ++c2) {                  // channels 2*c2, 2*c2+1 sit in word c2 of every head's piece
             uint32_t w[4];
@@ -471,7 +472,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
             const uint32_t lo23 = __builtin_amdgcn_perm(w[3], w[2], 0x05040100u);
             const uint32_t hi01 = __builtin_amdgcn_perm(w[1], w[0], 0x07060302u);   // high halves
             const uint32_t hi23 = __builtin_amdgcn_perm(w[3], w[2], 0x07060302u);
-            trow[(t_chunk + c2) ^ t_swz] = u32x4{lo01, lo23, hi01, hi23};   // channel 2*c2 (8 bytes), channel 2*c2+1 (8 bytes)
+            trow[2 * ((t_lane + 2 * c2) ^ (t_dt & 7))] = u32x2{lo01, lo23};         // channel 2*c2
+            trow[2 * ((t_lane + 2 * c2 + 1) ^ (t_dt & 7))] = u32x2{hi01, hi23};     // channel 2*c2 + 1
         }
         if (tid < 64) ld[buf][tid >> 5][(tid >> 4) & 1][tid & 15] = rf[st];
     };
@@ -518,13 +520,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
                 }
             }
             // A operands of the second products: lane (n = channel, g), element 4u + e = (token u, head 4g + e)
-            const u32x2 *tq = reinterpret_cast<const u32x2 *>(stageT[cur]);
+            const u32x4 *tq = reinterpret_cast<const u32x4 *>(stageT[cur]);
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) {
-                const int sl = ((((lane >> 1) ^ ((dt & 3) | ((dt >> 2) << 3))) << 1) | (lane & 1));   // swizzled slot of this lane
-                const u32x2 q0 = tq[(0 * 8 + dt) * 64 + sl], q1 = tq[(1 * 8 + dt) * 64 + sl];
-                const u32x2 g0 = tq[(2 * 8 + dt) * 64 + sl], g1 = tq[(3 * 8 + dt) * 64 + sl];
-                const u32x4 aq = {q0.x, q0.y, q1.x, q1.y}, ag = {g0.x, g0.y, g1.x, g1.y};
+                const u32x4 aq = tq[dt * 64 + (lane ^ (dt & 7))];
+                const u32x4 ag = tq[(8 + dt) * 64 + (lane ^ (dt & 7))];
                 dvT[dt] = mfma16(__builtin_bit_cast(bf16x8, ag), ps, dvT[dt]);
                 dkT[dt] = mfma16(__builtin_bit_cast(bf16x8, aq), dss, dkT[dt]);
             }

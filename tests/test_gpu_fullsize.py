@@ -257,3 +257,99 @@ def test_backward_32k_sampled_rows_and_identities():
     e2 = float(((a - bq).abs() / sa).max())
     print("identities: sum dv vs sum dout %.2e of the term sizes, <dk,k> vs <dq,q> %.2e" % (e1, e2), flush=True)
     assert e1 < 2.0 ** -8 and e2 < 2.0 ** -8
+
+
+def test_verify_and_backward_graph_replays_match_eager():
+    # captured verification steps and a captured backward pass give the eager result on every
+    # replay, with eager work and synchronisations in between (the backward clears its
+    # accumulators with a kernel, not a memset node)
+    cfg = synth.CONFIGS[3]
+    n, chunk, reps, L0 = 6, 3, 3, 2500
+    x = synth.make_decode(cfg, steps=n * (chunk * reps + 1), seqlen=L0)
+    Hq, Hkv, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    prm = binding.Params(Hq, Hkv, topk=cfg.topk)
+    cap = x.capacity
+    S = chunk * reps + 1
+    qs = to_dev(x.q_steps[:S * n].reshape(S, n, 1, Hq, d).transpose(0, 2, 1, 3, 4))
+    ks = to_dev(x.k_steps[:S * n].reshape(S, n, 1, Hkv, d).transpose(0, 2, 3, 1, 4))
+    vs = to_dev(x.v_steps[:S * n].reshape(S, n, 1, Hkv, d).transpose(0, 2, 3, 1, 4))
+    rng = np.random.default_rng(4)
+    words = np.zeros((S, 1, n), np.uint64)
+    for s in range(S):
+        parent = [-1] + [int(rng.integers(0, t)) for t in range(1, n)]
+        for t in range(n):
+            a = t
+            while a >= 0:
+                words[s, 0, t] |= np.uint64(1 << a)
+                a = parent[a]
+    masks = torch.from_numpy(words.view(np.int64)).cuda()
+
+    def make_state():
+        st = dict(kc=to_dev(x.k_cache), vc=to_dev(x.v_cache),
+                  sl=torch.tensor(x.seqlens0, dtype=torch.int32, device="cuda"),
+                  idx=torch.full((1, Hkv, n, cfg.topk), -1, dtype=torch.int32, device="cuda"),
+                  out=torch.zeros((1, n, Hq, d), dtype=torch.bfloat16, device="cuda"),
+                  lse=torch.zeros((1, n, Hq), dtype=torch.float32, device="cuda"),
+                  ws1=torch.empty(binding.verify_workspace_bytes(binding.OP_SELECT_VERIFY, prm, 1, cap, n), dtype=torch.uint8, device="cuda"),
+                  ws2=torch.empty(binding.verify_workspace_bytes(binding.OP_ATTN_VERIFY, prm, 1, cap, n), dtype=torch.uint8, device="cuda"))
+        st["ck"] = binding.compress_keys(prm, st["kc"], st["sl"], cap)
+        return st
+
+    def step(st, s):
+        st["sl"].add_(n)
+        binding.append_kv_verify(prm, ks[s], vs[s], st["kc"], st["vc"], st["sl"], cap, ck=st["ck"])
+        binding.select_blocks_verify(prm, qs[s], st["ck"], st["sl"], cap, block_idx=st["idx"], workspace=st["ws1"])
+        binding.sparse_attn_verify(prm, qs[s], st["kc"], st["vc"], st["sl"], cap, st["idx"], tree_mask=masks[s],
+                                   out=st["out"], lse=st["lse"], workspace=st["ws2"])
+
+    g_st, e_st = make_state(), make_state()
+    for st in (g_st, e_st):
+        step(st, 0)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for s in range(1, 1 + chunk):
+                step(g_st, s)
+    torch.cuda.synchronize()
+    for r in range(reps):
+        graph.replay()
+        for s in range(1, 1 + chunk):
+            step(e_st, s)
+        torch.cuda.synchronize()
+        for key in ("sl", "idx", "lse"):
+            assert torch.equal(g_st[key], e_st[key]), (r, key)
+        for key in ("out", "ck", "kc"):
+            assert torch.equal(g_st[key].view(torch.int16), e_st[key].view(torch.int16)), (r, key)
+
+    # backward of a small prefill, captured once
+    l = 1500
+    xs = synth.make_sequence(91, l, Hq, Hkv, n_planted=3)
+    q, k, v = to_dev(xs.q)[None], to_dev(xs.k)[None], to_dev(xs.v)[None]
+    sl = torch.tensor([l], dtype=torch.int32, device="cuda")
+    ck = binding.compress_keys(prm, k, sl, l)
+    idx = binding.select_blocks(prm, binding.MODE_PREFILL, q, ck, sl, l)
+    out, lse = binding.sparse_attn_prefill(prm, q, k, v, sl, l, idx)
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    do = torch.randn(q.shape, device="cuda", generator=gen).bfloat16()
+    ws = torch.empty(binding.workspace_bytes(binding.OP_ATTN_BWD, prm, 1, l), dtype=torch.uint8, device="cuda")
+    eager = binding.sparse_attn_bwd(prm, q, k, v, out, do, lse, sl, l, idx, workspace=ws)
+    torch.cuda.synchronize()
+    got = [torch.zeros_like(t) for t in eager]
+    side.wait_stream(torch.cuda.current_stream())
+    g2 = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g2, stream=side):
+            binding.sparse_attn_bwd(prm, q, k, v, out, do, lse, sl, l, idx, dq=got[0], dk=got[1], dv=got[2], workspace=ws)
+    torch.cuda.synchronize()
+    for r in range(reps):
+        for t in got:
+            t.fill_(7.0)                                  # eager work between the replays
+        g2.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(got[0].view(torch.int16), eager[0].view(torch.int16)), r      # dq: no atomics
+        for a, b_ in zip(got[1:], eager[1:]):             # dk, dv: fp32 atomics, then one bf16 rounding
+            diff = (a.float() - b_.float()).abs()
+            assert bool((diff <= 2.0 ** -7 * b_.float().abs() + 1e-6).all()), r

@@ -136,7 +136,43 @@ def bench_prefill(args):
         hit = ((a[:, :, None] == e[:, None, :]) & (a[:, :, None] >= 0)).any(-1).sum().item()
         overlap = hit / max(1, int((a >= 0).sum().item()))
         del exact
+    # selection statistics that govern the attainable attention throughput
+    nb = (l + m - 1) // m
+    t_idx = torch.arange(l, device="cuda")
+    own = (t_idx // m)[None, :, None]
+    ii = idx[0]
+    valid = ii >= 0
+    scored = valid & (ii != 0) & (ii < own - 1)                       # not the initial block, not the two local ones
+    is_planted = torch.zeros((Hkv, nb), dtype=torch.bool, device="cuda")
+    for h in range(Hkv):
+        pl = [int(pb) for pb in x.planted[h] if pb < nb]
+        if pl:
+            is_planted[h, torch.tensor(pl, device="cuda")] = True
+    hit = torch.gather(is_planted[:, None, :].expand(Hkv, l, nb), 2, ii.clamp(min=0).long()) & scored
+    n_tiles64 = l // m
+    member = torch.zeros((Hkv, n_tiles64, nb + 1), dtype=torch.bool, device="cuda")
+    tile_of = (t_idx[: n_tiles64 * m] // m)[None, :, None].expand(Hkv, n_tiles64 * m, cfg.topk)
+    jj = torch.where(valid[:, : n_tiles64 * m], ii[:, : n_tiles64 * m].long(), torch.full_like(ii[:, : n_tiles64 * m], nb).long())
+    member[torch.arange(Hkv, device="cuda")[:, None, None].expand_as(jj), tile_of, jj] = True
+    union = member[:, :, :nb].sum(-1).float()
+    listed = valid[:, : n_tiles64 * m].reshape(Hkv, n_tiles64, -1).sum(-1).float()
+    sel_stats = {"planted_fraction_of_scored_picks": float(hit.sum().item()) / max(1, int(scored.sum().item())),
+                 "mean_union_blocks_per_64_token_tile": float(union.mean().item()),
+                 "mean_reuse_factor_per_64_token_tile": float((listed / union.clamp(min=1)).mean().item())}
+    # one step with cold caches: a 1 GiB fill runs right before it (events around the step only)
+    thrash = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    cold = []
+    for _ in range(3):
+        thrash.fill_(1.0)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        step()
+        e1.record()
+        torch.cuda.synchronize()
+        cold.append(e0.elapsed_time(e1))
+    del thrash
     res = {
+        "selection_stats": sel_stats, "ms_per_step_after_cache_thrash": float(np.median(cold)),
         "selection_overlap_with_exact": overlap,
         "ms_per_step": ms_per_step, "value": value, "roofline": roofline,
         "kernels_ms": kern_ms, "attended_flops": attended_flops, "scoring_flops_per_pass": score_flops,
@@ -215,6 +251,23 @@ def bench_decode(cfg_index, steps):
         sl.add_(1)
         step(s, sl)
     torch.cuda.synchronize()
+    extra = {}
+    # distribution over single steps (eager launches, HIP events around each step; the graph figure
+    # below is the throughput, this is the spread): the same steps the graph will run, on a scratch copy
+    # of the lengths so that the caches are written with the same rows again later
+    n_eager = min(100, steps - n_warm)
+    if n_eager >= 10:
+        sl_e = sl.clone()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_eager)]
+        for i in range(n_eager):
+            sl_e.add_(1)
+            evs[i][0].record()
+            step(n_warm + i, sl_e)
+            evs[i][1].record()
+        torch.cuda.synchronize()
+        ts = np.array([a.elapsed_time(b_) * 1e3 for a, b_ in evs])
+        extra["eager_step_us"] = {"mean": float(ts.mean()), "p50": float(np.percentile(ts, 50)),
+                                  "p99": float(np.percentile(ts, 99)), "steps": n_eager}
     timed = steps - n_warm
     launch = "eager launches"
     chunk = min(100, timed)
@@ -247,6 +300,25 @@ def bench_decode(cfg_index, steps):
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         launch = "HIP graph of %d consecutive steps replayed %d times (step inputs repeat per replay, the context keeps growing)" % (chunk, reps)
+        # the floor of this launch shape: the same number of empty launches per step, in a graph of the same length
+        tiny = torch.zeros(64, dtype=torch.float32, device="cuda")
+        n_launch = 6
+        side.wait_stream(torch.cuda.current_stream())
+        floor_graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(floor_graph, stream=side):
+                for _ in range(chunk * n_launch):
+                    tiny.add_(1.0)
+        torch.cuda.synchronize()
+        floor_graph.replay()
+        torch.cuda.synchronize()
+        tf0 = time.perf_counter()
+        for _ in range(reps):
+            floor_graph.replay()
+        torch.cuda.synchronize()
+        floor_us = (time.perf_counter() - tf0) * 1e6 / (reps * chunk)
+        extra["launch_floor_us_per_step"] = floor_us
+        extra["launch_floor_note"] = "%d dependent 64-element kernels per step in the same kind of graph" % n_launch
     else:
         t0 = time.perf_counter()
         for s in range(n_warm, steps):
@@ -266,7 +338,7 @@ def bench_decode(cfg_index, steps):
             "gathered_GBs": gathered / us / 1e3, "algorithmic_GBs": algorithmic / us / 1e3,
             "frac_hbm_gathered": gathered / us / 1e3 / PEAK_HBM_GBS,
             "frac_hbm_algorithmic": algorithmic / us / 1e3 / PEAK_HBM_GBS,
-            "contexts_at_end": [int(v) for v in sl.cpu().numpy()], "launch": launch}
+            "contexts_at_end": [int(v) for v in sl.cpu().numpy()], "launch": launch, **extra}
 
 
 def bench_verify(cfg_index, n_draft, steps):
@@ -458,6 +530,8 @@ def main():
                    "step": "compress_keys + select_blocks + sparse_attn_prefill",
                    "lse": "exact" if args.lse_ratio <= 1 else "approximate, coarse kernels of ratio %d" % args.lse_ratio},
         "selection_overlap_with_exact": res["selection_overlap_with_exact"],
+        "selection_stats": res["selection_stats"],
+        "ms_per_step_after_cache_thrash": res["ms_per_step_after_cache_thrash"],
         "frac_bf16_peak_whole_step": res["value"] / PEAK_BF16_TFLOPS,
         "attn_only_tflops": res["attn_only_tflops"],
         "frac_bf16_peak_attn_only": res["attn_only_tflops"] / PEAK_BF16_TFLOPS,

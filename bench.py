@@ -237,14 +237,13 @@ def bench_decode(cfg_index, steps):
     idx = torch.full((B, Hkv, 1, cfg.topk), -1, dtype=torch.int32, device="cuda")
     out = torch.zeros((B, 1, Hq, d), dtype=torch.bfloat16, device="cuda")
     lse = torch.zeros((B, Hq), dtype=torch.float32, device="cuda")
-    ws_sel = torch.empty(binding.workspace_bytes(binding.OP_SELECT_DECODE, prm, B, cap), dtype=torch.uint8, device="cuda")
-    ws_att = torch.empty(binding.workspace_bytes(binding.OP_ATTN_DECODE, prm, B, cap), dtype=torch.uint8, device="cuda")
+    ws_step = torch.empty(binding.workspace_bytes(binding.OP_DECODE_STEP, prm, B, cap), dtype=torch.uint8, device="cuda")
 
     def step(s, sl):
-        """One decoded token; sl holds the sequence lengths INCLUDING the new token."""
-        binding.append_kv(prm, ks[s], vs[s], kc, vc, sl, cap, ck=ck)      # append + incremental compression
-        binding.select_blocks(prm, binding.MODE_DECODE, qs[s], ck, sl, cap, block_idx=idx, workspace=ws_sel)
-        binding.sparse_attn_decode(prm, qs[s], kc, vc, sl, cap, idx, out=out, lse=lse, workspace=ws_att)
+        """One decoded token; sl holds the sequence lengths INCLUDING the new token.  One call: cache
+        append + incremental compression (inside the first selection kernel), select, attend."""
+        binding.decode_step(prm, qs[s], ks[s], vs[s], kc, vc, ck, sl, cap, block_idx=idx, out=out, lse=lse,
+                            workspace=ws_step)
 
     n_warm = min(20, max(1, steps // 10))
     for s in range(n_warm):
@@ -302,7 +301,7 @@ def bench_decode(cfg_index, steps):
         launch = "HIP graph of %d consecutive steps replayed %d times (step inputs repeat per replay, the context keeps growing)" % (chunk, reps)
         # the floor of this launch shape: the same number of empty launches per step, in a graph of the same length
         tiny = torch.zeros(64, dtype=torch.float32, device="cuda")
-        n_launch = 6
+        n_launch = 5
         side.wait_stream(torch.cuda.current_stream())
         floor_graph = torch.cuda.CUDAGraph()
         with torch.cuda.stream(side):

@@ -63,6 +63,7 @@ extern "C" {
 #define INFLLMV2_OP_ATTN_PREFILL 3
 #define INFLLMV2_OP_ATTN_DECODE 4
 #define INFLLMV2_OP_ATTN_BWD 7
+#define INFLLMV2_OP_DECODE_STEP 8
 /* Stage selector for infllmv2_verify_workspace_bytes. */
 #define INFLLMV2_OP_SELECT_VERIFY 5
 #define INFLLMV2_OP_ATTN_VERIFY 6
@@ -235,6 +236,23 @@ int32_t infllmv2_append_kv(const infllmv2_params *prm, const infllmv2_tensor *k_
                            const infllmv2_tensor *v_new, const infllmv2_tensor *k,
                            const infllmv2_tensor *v, const infllmv2_tensor *ck,
                            const int32_t *seqlens, int32_t batch, int32_t max_seqlen, void *stream);
+
+/*
+ * One decode step in one call (section 5.4: per step only the semantic-kernel representations grow):
+ * infllmv2_append_kv (with ck) + infllmv2_select_blocks(INFLLMV2_MODE_DECODE) +
+ * infllmv2_sparse_attn_decode, with the append folded into the first selection kernel: five launches
+ * instead of six, the same caches, ck, block_idx, out and lse bit for bit.
+ *   q, out        [batch, 1, Hq, d] bf16;  k_new, v_new  [batch, Hkv, 1, d] bf16
+ *   k, v, ck      the caches (updated in place);  seqlens counts the new token
+ *   block_idx     out  int32 [batch, Hkv, 1, topk];  lse  out  fp32 [batch, Hq]
+ *   workspace     infllmv2_workspace_bytes(INFLLMV2_OP_DECODE_STEP, ...) bytes
+ */
+int32_t infllmv2_decode_step(const infllmv2_params *prm, const infllmv2_tensor *q,
+                             const infllmv2_tensor *k_new, const infllmv2_tensor *v_new,
+                             const infllmv2_tensor *k, const infllmv2_tensor *v, const infllmv2_tensor *ck,
+                             const int32_t *seqlens, int32_t batch, int32_t max_seqlen, int32_t *block_idx,
+                             const infllmv2_tensor *out, float *lse, void *workspace, size_t workspace_bytes,
+                             void *stream);
 
 /*
  * Draft verification (section 4.1, "InfLLM v2 for Target Model": the target model checks n drafted

@@ -24,11 +24,12 @@ OK = 0
 OP_SELECT_PREFILL, OP_SELECT_DECODE, OP_ATTN_PREFILL, OP_ATTN_DECODE = 1, 2, 3, 4
 OP_SELECT_VERIFY, OP_ATTN_VERIFY = 5, 6
 OP_ATTN_BWD = 7
+OP_DECODE_STEP = 8
 MODE_PREFILL, MODE_DECODE = 0, 1
 
 EXPORTS = ["infllmv2_status_string", "infllmv2_workspace_bytes", "infllmv2_compress_keys",
            "infllmv2_select_blocks", "infllmv2_sparse_attn_prefill", "infllmv2_sparse_attn_decode",
-           "infllmv2_sparse_attn_bwd", "infllmv2_append_kv", "infllmv2_verify_workspace_bytes", "infllmv2_append_kv_verify",
+           "infllmv2_sparse_attn_bwd", "infllmv2_append_kv", "infllmv2_decode_step", "infllmv2_verify_workspace_bytes", "infllmv2_append_kv_verify",
            "infllmv2_select_blocks_verify", "infllmv2_sparse_attn_verify",
            "infllmv2_probe_peaks", "infllmv2_timing_enable", "infllmv2_timing_read"]
 
@@ -104,6 +105,8 @@ def load_library(path=None):
     lib.infllmv2_sparse_attn_decode.argtypes = [P, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
     lib.infllmv2_sparse_attn_bwd.restype = i32
     lib.infllmv2_sparse_attn_bwd.argtypes = [P, T, T, T, T, T, vp, vp, i32, i32, vp, T, T, T, vp, sz, vp]
+    lib.infllmv2_decode_step.restype = i32
+    lib.infllmv2_decode_step.argtypes = [P, T, T, T, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
     lib.infllmv2_append_kv.restype = i32
     lib.infllmv2_append_kv.argtypes = [P, T, T, T, T, T, vp, i32, i32, vp]
     lib.infllmv2_verify_workspace_bytes.restype = sz
@@ -364,3 +367,25 @@ def sparse_attn_bwd(prm, q, k, v, out, dout, lse, seqlens, max_seqlen, block_idx
                                         _i32(block_idx, "block_idx").data_ptr(), *[ctypes.byref(x) for x in d[5:]],
                                         workspace.data_ptr(), ws_bytes, _stream()), "infllmv2_sparse_attn_bwd")
     return dq, dk, dv
+
+
+def decode_step(prm, q, k_new, v_new, k, v, ck, seqlens, max_seqlen, block_idx=None, out=None, lse=None,
+                workspace=None):
+    """append_kv (with ck) + select_blocks(MODE_DECODE) + sparse_attn_decode in one call, five launches.
+    -> block_idx [B, Hkv, 1, topk], out [B, 1, Hq, d], lse [B, Hq]."""
+    lib = load_library()
+    B = q.shape[0]
+    if block_idx is None:
+        block_idx = torch.full((B, prm.n_kv_heads, 1, prm.topk), -1, dtype=torch.int32, device=q.device)
+    if out is None:
+        out = torch.zeros_like(q)
+    if lse is None:
+        lse = torch.zeros((B, prm.n_q_heads), dtype=torch.float32, device=q.device)
+    workspace, ws_bytes = _workspace(OP_DECODE_STEP, prm, B, max_seqlen, workspace, q.device)
+    d = [_query_desc(q, "q"), _cache_desc(k_new, "k_new"), _cache_desc(v_new, "v_new"), _cache_desc(k, "k"),
+         _cache_desc(v, "v"), _cache_desc(ck, "ck"), _query_desc(out, "out")]
+    _check(lib.infllmv2_decode_step(ctypes.byref(prm.c()), *[ctypes.byref(x) for x in d[:6]],
+                                    _i32(seqlens, "seqlens").data_ptr(), B, max_seqlen,
+                                    _i32(block_idx, "block_idx").data_ptr(), ctypes.byref(d[6]), lse.data_ptr(),
+                                    workspace.data_ptr(), ws_bytes, _stream()), "infllmv2_decode_step")
+    return block_idx, out, lse

@@ -167,6 +167,8 @@ size_t infllmv2_workspace_bytes(int32_t op, const infllmv2_params *prm, int32_t 
         case INFLLMV2_OP_ATTN_PREFILL: return attn_prefill_ws_bytes(dm);
         case INFLLMV2_OP_ATTN_DECODE: return attn_decode_ws_bytes(dm);
         case INFLLMV2_OP_ATTN_BWD: return attn_bwd_ws_bytes(dm);
+        case INFLLMV2_OP_DECODE_STEP:
+            return max_seqlen > kMaxDecodeSeqlen ? 0 : select_decode_ws_bytes(dm) + attn_decode_ws_bytes(dm);
     }
     return 0;
 }
@@ -281,6 +283,32 @@ int32_t infllmv2_sparse_attn_verify(const infllmv2_params *prm, const infllmv2_t
     return hip_status(launch_attn_decode(dm, make_tensor(q), make_tensor(k), make_tensor(v), seqlens,
                                          block_idx, tree_mask, make_tensor(out), lse, workspace,
                                          reinterpret_cast<hipStream_t>(stream)));
+}
+
+int32_t infllmv2_decode_step(const infllmv2_params *prm, const infllmv2_tensor *q,
+                             const infllmv2_tensor *k_new, const infllmv2_tensor *v_new,
+                             const infllmv2_tensor *k, const infllmv2_tensor *v, const infllmv2_tensor *ck,
+                             const int32_t *seqlens, int32_t batch, int32_t max_seqlen, int32_t *block_idx,
+                             const infllmv2_tensor *out, float *lse, void *workspace, size_t workspace_bytes,
+                             void *stream) {
+    RETURN_IF_ERR(check_params(prm));
+    RETURN_IF_ERR(check_sizes(batch, max_seqlen));
+    const infllmv2_tensor *ts[7] = {q, k_new, v_new, k, v, ck, out};
+    for (int i = 0; i < 7; ++i) RETURN_IF_ERR(check_tensor(ts[i]));
+    if (!seqlens || !block_idx || !lse) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    if (max_seqlen > kMaxDecodeSeqlen) return INFLLMV2_ERR_UNSUPPORTED;
+    const Dims dm = make_dims(prm, batch, max_seqlen);
+    const size_t sel = select_decode_ws_bytes(dm), need = sel + attn_decode_ws_bytes(dm);
+    if (need > 0 && (!workspace || workspace_bytes < need ||
+                     (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0))
+        return INFLLMV2_ERR_WORKSPACE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const AppendArgs ap = {make_tensor(k_new), make_tensor(v_new), make_tensor(k), make_tensor(v)};
+    RETURN_IF_ERR(hip_status(launch_select_decode(dm, make_tensor(q), make_tensor(ck), seqlens, block_idx,
+                                                  workspace, st, &ap)));
+    return hip_status(launch_attn_decode(dm, make_tensor(q), make_tensor(k), make_tensor(v), seqlens, block_idx,
+                                         nullptr, make_tensor(out), lse, reinterpret_cast<char *>(workspace) + sel,
+                                         st));
 }
 
 int32_t infllmv2_select_blocks(const infllmv2_params *prm, int32_t mode, const infllmv2_tensor *q,

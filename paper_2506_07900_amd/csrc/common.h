@@ -37,6 +37,10 @@ struct Tensor {          // strides in elements
     int64_t sb, sh, st;
 };
 
+struct AppendArgs {      // the cache append folded into the first kernel of a fused decode step
+    Tensor k_new, v_new, k, v;
+};
+
 // Number of complete semantic kernels of a sequence of l tokens (p=32, s=16).
 __host__ __device__ inline int32_t num_kernels(int32_t l) {
     return l < kKernel ? 0 : (l - kKernel) / kStride + 1;
@@ -133,7 +137,7 @@ size_t select_scores_bytes(const Dims &dm);
 int launch_select_pick(const Dims &dm, const int32_t *seqlens, const float *R, int32_t nb_cap,
                        int32_t *block_idx, hipStream_t stream);
 int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
-                         int32_t *block_idx, void *ws, hipStream_t stream);
+                         int32_t *block_idx, void *ws, hipStream_t stream, const AppendArgs *append = nullptr);
 size_t select_decode_ws_bytes(const Dims &dm);
 int launch_attn_prefill(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32_t *seqlens,
                         const int32_t *block_idx, Tensor out, float *lse, void *ws, hipStream_t stream);

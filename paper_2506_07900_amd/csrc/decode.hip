@@ -93,21 +93,42 @@ __device__ inline int row_len(const Dims &dm, int L_all, int qi) {
 // ---- part 1: partial (max, sum) of the relevance softmax ---------------------------------------------
 // grid (n_c_cap / (64*kTW), Hkv, B * ceil(n_q/kQT)); wave w owns kernels chunk + 16*kTW*w .. +16*kTW-1.
 // Z^T = CK . Q^T: lane = query head, 4 accumulator entries = 4 consecutive kernels.
-template <int kQT>
+// With kAppend (plain decode, the fused step) the kernel also opens the step: the workgroups of chunk 0
+// copy the new token's key and value rows into the caches (nothing before the attention kernel reads
+// them), and the wave that owns the semantic kernel the new token completes builds its representation
+// itself -- 31 cached rows and the new one, fp64 sum in token order, one rounding, the same bits as
+// compress_keys_kernel -- uses it, and stores it for the steps to come.
+template <int kQT, bool kAppend>
 __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, Tensor ck,
                                                              const int32_t *__restrict__ seqlens,
                                                              float *__restrict__ zbuf, int32_t n_c_cap,
                                                              float2 *__restrict__ part,
-                                                             float2 *__restrict__ part_c, int32_t n_part) {
+                                                             float2 *__restrict__ part_c, int32_t n_part,
+                                                             AppendArgs ap) {
+    static_assert(!kAppend || kQT == 1, "the fused append is for one query per sequence");
     constexpr int kTW = tiles_per_wave(kQT), kChunk = 64 * kTW;
     __shared__ float2 wpart[kQT][4][16];
     __shared__ float2 wpart_c[kQT][4][16];
     __shared__ __align__(16) uint16_t qs[kQT > 1 ? kQT * 16 * kQsPitch : 8];
+    __shared__ __align__(16) uint32_t newrow[kAppend ? 64 : 1];
     const int h = blockIdx.y;
     const int n_qt = (dm.n_q + kQT - 1) / kQT;        // query tiles per sequence
     const int b = kQT == 1 ? blockIdx.z : blockIdx.z / n_qt;   // kQT = 1 is only launched with n_q = 1
     const int qi0 = (blockIdx.z - b * n_qt) * kQT;
     const int L_all = clamp_len(seqlens[b], dm.max_seqlen);
+    bool closes = false;                              // the new token completes semantic kernel n_vis - 1
+    if constexpr (kAppend) {
+        const int32_t L_raw = seqlens[b];
+        const bool live = L_raw >= 1 && L_raw <= dm.max_seqlen;       // as the stand-alone append: others are skipped
+        if (live && blockIdx.x == 0 && threadIdx.x < 32) {
+            const int c8 = (threadIdx.x & 15) * 8;
+            const Tensor &src = threadIdx.x < 16 ? ap.k_new : ap.v_new;
+            const Tensor &dst = threadIdx.x < 16 ? ap.k : ap.v;
+            *reinterpret_cast<uint4 *>(dst.ptr + b * dst.sb + h * dst.sh + (int64_t)(L_raw - 1) * dst.st + c8) =
+                *reinterpret_cast<const uint4 *>(src.ptr + b * src.sb + h * src.sh + c8);
+        }
+        closes = live && L_raw >= kKernel && (L_raw - kKernel) % kStride == 0;
+    }
     int n_vis[kQT], n_vis_max = 0;                    // query slot t sits at L-1: n_c((L-1)+1); 0 = no such row
 #pragma unroll
     for (int t = 0; t < kQT; ++t) {
@@ -130,6 +151,35 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, T
         }
     }
     load_query_operands<kQT>(dm, q, b, h, qi0, qs, bq);   // heads >= G repeat head G-1: their columns are never used
+    if constexpr (kAppend) {
+        const int jh_new = n_vis_max - 1;             // = (L - p) / s when the new token closes a kernel
+        if (closes && jh_new >= jw && jh_new < jw + 16) {             // uniform over the wave (kTW = 1)
+            // lane = channels 2*lane, 2*lane+1: rows L-32 .. L-2 from the cache, row L-1 from k_new
+            const int L = L_all;
+            const __bf16 *kc = ap.k.ptr + b * ap.k.sb + h * ap.k.sh + 2 * lane;
+            uint32_t rowv[kKernel];
+#pragma unroll
+            for (int t = 0; t < kKernel - 1; ++t)
+                rowv[t] = *reinterpret_cast<const uint32_t *>(kc + (int64_t)(L - kKernel + t) * ap.k.st);
+            rowv[kKernel - 1] = *reinterpret_cast<const uint32_t *>(ap.k_new.ptr + b * ap.k_new.sb + h * ap.k_new.sh + 2 * lane);
+            double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+            for (int t = 0; t < kKernel; ++t) {
+                s0 += (double)__uint_as_float(rowv[t] << 16);
+                s1 += (double)__uint_as_float(rowv[t] & 0xffff0000u);
+            }
+            const uint32_t packed = (uint32_t)f64_to_bf16_rne(s0 / (double)kKernel) |
+                                    ((uint32_t)f64_to_bf16_rne(s1 / (double)kKernel) << 16);
+            newrow[lane] = packed;
+            *reinterpret_cast<uint32_t *>(ck.ptr + b * ck.sb + h * ck.sh + (int64_t)jh_new * ck.st + 2 * lane) = packed;
+            // same wavefront wrote newrow: LDS keeps the order.  The lanes whose operand row it is take it from there.
+            if (jw + n == jh_new) {
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    a[0][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&newrow[16 * ks + 4 * g]));
+            }
+        }
+    }
 #pragma unroll
     for (int t = 0; t < kQT; ++t) {
         float x[kTW][4], mx = -INFINITY;
@@ -770,7 +820,7 @@ size_t select_decode_ws_bytes(const Dims &dm) {
 }
 
 int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
-                         int32_t *block_idx, void *ws, hipStream_t stream) {
+                         int32_t *block_idx, void *ws, hipStream_t stream, const AppendArgs *append) {
     if (dm.batch <= 0) return 0;
     DecodeSelLayout l = decode_sel_layout(dm);
     if (l.n_c_cap > 16384) return (int)hipErrorInvalidValue;         // rejected earlier by the C ABI
@@ -783,12 +833,16 @@ int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seq
     const int n_qt = (dm.n_q + kVerifyQT - 1) / kVerifyQT;
     const float2 *part_lse = dm.rho > 1 ? part_c : part;
     timing_begin("decode_logits_kernel", stream);
-    if (dm.n_q == 1)
-        hipLaunchKernelGGL(decode_logits_kernel<1>, dim3(l.n_part, dm.Hkv, dm.batch), dim3(256), 0, stream,
-                           dm, q, ck, seqlens, zbuf, l.n_c_cap, part, part_c, l.n_part);
+    const AppendArgs no_append = {q, q, q, q};                       // unused placeholders
+    if (dm.n_q == 1 && append)
+        hipLaunchKernelGGL((decode_logits_kernel<1, true>), dim3(l.n_part, dm.Hkv, dm.batch), dim3(256), 0, stream,
+                           dm, q, ck, seqlens, zbuf, l.n_c_cap, part, part_c, l.n_part, *append);
+    else if (dm.n_q == 1)
+        hipLaunchKernelGGL((decode_logits_kernel<1, false>), dim3(l.n_part, dm.Hkv, dm.batch), dim3(256), 0, stream,
+                           dm, q, ck, seqlens, zbuf, l.n_c_cap, part, part_c, l.n_part, no_append);
     else
-        hipLaunchKernelGGL(decode_logits_kernel<kVerifyQT>, dim3(l.n_part, dm.Hkv, dm.batch * n_qt), dim3(256),
-                           0, stream, dm, q, ck, seqlens, nullptr, 0, part, part_c, l.n_part);
+        hipLaunchKernelGGL((decode_logits_kernel<kVerifyQT, false>), dim3(l.n_part, dm.Hkv, dm.batch * n_qt), dim3(256),
+                           0, stream, dm, q, ck, seqlens, nullptr, 0, part, part_c, l.n_part, no_append);
     timing_end(stream);
     timing_begin("decode_scores_kernel", stream);
     if (dm.n_q == 1)

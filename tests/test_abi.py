@@ -159,6 +159,20 @@ def test_backward_validation(lib):
     assert lib.infllmv2_sparse_attn_bwd(P, T, T, T, T, T, FAKE, FAKE, 0, 4096, FAKE, T, T, T, FAKE, 1 << 40, None) == 0
 
 
+def test_decode_step_validation(lib):
+    prm, t = good_params(), tensor()
+    P, T = ctypes.byref(prm), ctypes.byref(t)
+    need = lib.infllmv2_workspace_bytes(binding.OP_DECODE_STEP, P, 2, 4096)
+    assert need == (lib.infllmv2_workspace_bytes(binding.OP_SELECT_DECODE, P, 2, 4096) +
+                    lib.infllmv2_workspace_bytes(binding.OP_ATTN_DECODE, P, 2, 4096))
+    call = lambda q=T, sl=FAKE, w=FAKE, wb=1 << 40, ms=4096: lib.infllmv2_decode_step(
+        P, q, T, T, T, T, T, sl, 2, ms, FAKE, T, FAKE, w, wb, None)
+    assert call(q=None) == INVALID and call(sl=None) == INVALID
+    assert call(w=None, wb=0) == WORKSPACE and call(wb=need - 1) == WORKSPACE
+    assert call(ms=1 << 20) == UNSUPPORTED                                               # decode context cap
+    assert lib.infllmv2_decode_step(P, T, T, T, T, T, T, FAKE, 0, 4096, FAKE, T, FAKE, FAKE, 1 << 40, None) == 0
+
+
 def test_binding_fails_loudly_without_library(tmp_path):
     with pytest.raises(binding.InfLLMv2Error):
         binding.load_library(str(tmp_path / "missing.so"))

@@ -103,7 +103,7 @@ def test_decode_ragged_batch8_steps():
     # the ragged decode workload: 8 sequences of different cached lengths, four with heavy-tailed
     # key norms; a few real decode steps, every sequence checked against the oracle
     cfg = synth.CONFIGS[4]
-    steps = 6
+    steps = 20                                            # every sequence completes a semantic kernel at least once
     print("workload", cfg.name, flush=True)
     x = synth.make_decode(cfg, steps=steps)
     B, Hq, Hkv = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads
@@ -121,15 +121,19 @@ def test_decode_ragged_batch8_steps():
         lens = lens + 1
         sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
         qd = to_dev(x.q_steps[s][:, None])
-        binding.append_kv(prm, to_dev(x.k_steps[s][:, :, None]), to_dev(x.v_steps[s][:, :, None]), kd, vd, sl, cap)
-        binding.compress_keys(prm, kd, sl, cap, ck=ck, n_new_tokens=1)
-        idx = binding.select_blocks(prm, binding.MODE_DECODE, qd, ck, sl, cap)
-        out, lse = binding.sparse_attn_decode(prm, qd, kd, vd, sl, cap, idx)
+        kn, vn = to_dev(x.k_steps[s][:, :, None]), to_dev(x.v_steps[s][:, :, None])
+        if s % 2:                                         # the benchmark's configuration: the whole step in one call
+            idx, out, lse = binding.decode_step(prm, qd, kn, vn, kd, vd, ck, sl, cap)
+        else:
+            binding.append_kv(prm, kn, vn, kd, vd, sl, cap)
+            binding.compress_keys(prm, kd, sl, cap, ck=ck, n_new_tokens=1)
+            idx = binding.select_blocks(prm, binding.MODE_DECODE, qd, ck, sl, cap)
+            out, lse = binding.sparse_attn_decode(prm, qd, kd, vd, sl, cap, idx)
         torch.cuda.synchronize()
         for b in range(B):
             k_np[b, :, lens[b] - 1] = x.k_steps[s][b]
             v_np[b, :, lens[b] - 1] = x.v_steps[s][b]
-        if s in (0, steps - 1):
+        if s in (0, 1, steps - 1):
             ckb = to_bits(ck)
             idx_np = idx.cpu().numpy()
             for b in range(B):
@@ -169,12 +173,17 @@ def test_decode_graph_replays_match_eager():
                   out=torch.zeros((1, 1, Hq, d), dtype=torch.bfloat16, device="cuda"),
                   lse=torch.zeros((1, Hq), dtype=torch.float32, device="cuda"),
                   ws1=torch.empty(binding.workspace_bytes(binding.OP_SELECT_DECODE, prm, 1, cap), dtype=torch.uint8, device="cuda"),
-                  ws2=torch.empty(binding.workspace_bytes(binding.OP_ATTN_DECODE, prm, 1, cap), dtype=torch.uint8, device="cuda"))
+                  ws2=torch.empty(binding.workspace_bytes(binding.OP_ATTN_DECODE, prm, 1, cap), dtype=torch.uint8, device="cuda"),
+                  ws3=torch.empty(binding.workspace_bytes(binding.OP_DECODE_STEP, prm, 1, cap), dtype=torch.uint8, device="cuda"))
         st["ck"] = binding.compress_keys(prm, st["kc"], st["sl"], cap)
         return st
 
-    def step(st, s):
+    def step(st, s, one_call=False):
         st["sl"].add_(1)
+        if one_call:
+            binding.decode_step(prm, qs[s], ks[s], vs[s], st["kc"], st["vc"], st["ck"], st["sl"], cap,
+                                block_idx=st["idx"], out=st["out"], lse=st["lse"], workspace=st["ws3"])
+            return
         binding.append_kv(prm, ks[s], vs[s], st["kc"], st["vc"], st["sl"], cap, ck=st["ck"])
         binding.select_blocks(prm, binding.MODE_DECODE, qs[s], st["ck"], st["sl"], cap, block_idx=st["idx"], workspace=st["ws1"])
         binding.sparse_attn_decode(prm, qs[s], st["kc"], st["vc"], st["sl"], cap, st["idx"], out=st["out"], lse=st["lse"], workspace=st["ws2"])
@@ -189,7 +198,7 @@ def test_decode_graph_replays_match_eager():
     with torch.cuda.stream(side):
         with torch.cuda.graph(graph, stream=side):
             for s in range(1, 1 + chunk):
-                step(g_st, s)
+                step(g_st, s, one_call=True)     # the graph holds the one-call step, the eager twin the three calls
     torch.cuda.synchronize()
     for r in range(reps):
         graph.replay()

@@ -315,7 +315,7 @@ def test_decode_select_and_attn(seqlens, Hq, Hkv, topk, forced):
         assert eo <= OUT_TOL and el <= 1.0
 
 
-@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("fused", [False, True, "one call"])
 def test_decode_steps_with_append_and_incremental_compress(fused):
     # a short run of real decode steps: append, incremental compression (its own launch, or
     # inside the append), select, attend; every step equals the oracle on the cache as it stands
@@ -337,13 +337,16 @@ def test_decode_steps_with_append_and_incremental_compress(fused):
         kn = to_dev(x.k_steps[s][:, :, None])
         vn = to_dev(x.v_steps[s][:, :, None])
         qd = to_dev(x.q_steps[s][:, None])
-        if fused:
-            binding.append_kv(prm, kn, vn, kd, vd, sl, cap, ck=ck)
+        if fused == "one call":                               # the whole step behind one entry point, five launches
+            idx, out, lse = binding.decode_step(prm, qd, kn, vn, kd, vd, ck, sl, cap)
         else:
-            binding.append_kv(prm, kn, vn, kd, vd, sl, cap)
-            binding.compress_keys(prm, kd, sl, cap, ck=ck, n_new_tokens=1)
-        idx = binding.select_blocks(prm, binding.MODE_DECODE, qd, ck, sl, cap)
-        out, lse = binding.sparse_attn_decode(prm, qd, kd, vd, sl, cap, idx)
+            if fused:
+                binding.append_kv(prm, kn, vn, kd, vd, sl, cap, ck=ck)
+            else:
+                binding.append_kv(prm, kn, vn, kd, vd, sl, cap)
+                binding.compress_keys(prm, kd, sl, cap, ck=ck, n_new_tokens=1)
+            idx = binding.select_blocks(prm, binding.MODE_DECODE, qd, ck, sl, cap)
+            out, lse = binding.sparse_attn_decode(prm, qd, kd, vd, sl, cap, idx)
         torch.cuda.synchronize()
         l = int(lens[0])
         k_np[0, :, l - 1] = x.k_steps[s][0]

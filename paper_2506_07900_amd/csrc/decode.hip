@@ -446,22 +446,30 @@ __global__ __launch_bounds__(320) void decode_scores_z_kernel(Dims dm, const int
     const int h = blockIdx.y, bv = blockIdx.z;
     const int tid = threadIdx.x;
     const int G = dm.G;
+    const int base = blockIdx.x * 256;
+    // Everything this thread reads lies in the workspace at places that do not depend on the sequence
+    // length, so the loads go out before the length is known (one memory round trip less on the
+    // critical path of the step); what turns out to be past the end is masked afterwards.
+    const int head = min(tid >> 4, G - 1), sub = tid & 15;
+    float2 v[kMaxParts / 16];
+#pragma unroll
+    for (int i = 0; i < kMaxParts / 16; ++i)
+        v[i] = part[(((int64_t)bv * dm.Hkv + h) * G + head) * n_part + min(sub + 16 * i, n_part - 1)];
+    const int jh = base - 1 + tid;
+    const int jh_c = min(max(jh, 0), n_c_cap - 1);
+    float zz[16];
+#pragma unroll
+    for (int gq = 0; gq < 16; ++gq) zz[gq] = zbuf[(((int64_t)bv * dm.Hkv + h) * G + min(gq, G - 1)) * n_c_cap + jh_c];
     int b, qi;
     const int L = query_row(dm, seqlens, bv, b, qi);
     const int n_vis = num_kernels(L);
-    const int base = blockIdx.x * 256;
     if (L < 1 || (int)blockIdx.x * 64 > (L - 1) / kBlock) return;            // no block of this chunk exists
     const int np = (n_vis + 63) >> 6;                 // valid partials
-    // log-sum-exp per head: 16 lanes per head, all loads of a lane issued together
+    // log-sum-exp per head: 16 lanes per head
     if (tid < 256) {
-        const int head = tid >> 4, sub = tid & 15;
-        float2 v[kMaxParts / 16];
 #pragma unroll
-        for (int i = 0; i < kMaxParts / 16; ++i) {
-            const int p = sub + 16 * i;
-            v[i] = float2{-INFINITY, 0.f};
-            if (head < G && p < np) v[i] = part[(((int64_t)bv * dm.Hkv + h) * G + head) * n_part + p];
-        }
+        for (int i = 0; i < kMaxParts / 16; ++i)
+            if (sub + 16 * i >= np) v[i] = float2{-INFINITY, 0.f};
         float m = -INFINITY;
 #pragma unroll
         for (int i = 0; i < kMaxParts / 16; ++i) m = fmaxf(m, v[i].x);
@@ -473,19 +481,12 @@ __global__ __launch_bounds__(320) void decode_scores_z_kernel(Dims dm, const int
         for (int i = 0; i < kMaxParts / 16; ++i) s += v[i].y * fast_exp2(v[i].x - mu);
 #pragma unroll
         for (int o = 1; o < 16; o <<= 1) s += __shfl_xor(s, o);
-        if (sub == 0)      // approximate mode: rho times fewer kernels were summed; 0 when none is visible
-            lse_h[head] = dm.rho > 1 ? (m == -INFINITY ? 0.f : m + fast_log2(s) + (float)(31 - __clz(dm.rho)))
-                                     : m + fast_log2(s);
+        if (sub == 0 && (tid >> 4) < G)   // approximate mode: rho times fewer kernels were summed; 0 when none is visible
+            lse_h[tid >> 4] = dm.rho > 1 ? (m == -INFINITY ? 0.f : m + fast_log2(s) + (float)(31 - __clz(dm.rho)))
+                                         : m + fast_log2(s);
     }
-    // logits of this thread's kernel, all heads (independent loads, in flight during the reduction)
-    const int jh = base - 1 + tid;
+    // logits of this thread's kernel, all heads
     const bool have = tid <= 256 && jh >= 0 && jh < n_vis;
-    float zz[16];
-#pragma unroll
-    for (int gq = 0; gq < 16; ++gq) {
-        zz[gq] = -INFINITY;
-        if (have && gq < G) zz[gq] = zbuf[(((int64_t)bv * dm.Hkv + h) * G + gq) * n_c_cap + jh];
-    }
     __syncthreads();
     if (tid <= 256) {
         float acc = 0.f;

@@ -271,9 +271,9 @@ int32_t infllmv2_decode_step(const infllmv2_params *prm, const infllmv2_tensor *
  *   nothing appended.  A query whose mask hides every key of its selected blocks gets out 0, lse -inf.
  *
  * infllmv2_append_kv_verify     k_new, v_new bf16 [batch, Hkv, n_draft, d] -> cache rows
- *                               seqlens[b]-n_draft .. seqlens[b]-1; with ck != NULL a second launch
- *                               writes the semantic kernels those rows complete
- *                               (= infllmv2_compress_keys with n_new_tokens = n_draft).
+ *                               seqlens[b]-n_draft .. seqlens[b]-1; with ck != NULL the same launch
+ *                               writes the semantic kernels those rows complete (the bits
+ *                               infllmv2_compress_keys with n_new_tokens = n_draft writes afterwards).
  * infllmv2_select_blocks_verify q bf16 [batch, n_draft, Hq, d]; block_idx out int32
  *                               [batch, Hkv, n_draft, topk], ascending, padded with -1.
  * infllmv2_sparse_attn_verify   q, out bf16 [batch, n_draft, Hq, d]; tree_mask DEVICE uint64

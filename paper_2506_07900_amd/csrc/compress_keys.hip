@@ -109,8 +109,64 @@ __global__ __launch_bounds__(256) void append_kv_kernel(Dims dm, Tensor k_new, T
     }
 }
 
+// Verification-step append in one launch: workgroups 0 .. n_copy-1 of a (sequence, head) copy the
+// n_q new rows into the caches, the others write the semantic kernels those rows complete, reading
+// the rows that are new from k_new and the older ones from the cache (fp64 sum in token order, one
+// rounding: the bits compress_keys_kernel produces once the rows are in the cache).
+__global__ __launch_bounds__(256) void append_compress_kernel(Dims dm, Tensor k_new, Tensor v_new, Tensor k, Tensor v,
+                                                              Tensor ck, const int32_t *__restrict__ seqlens,
+                                                              int32_t n_copy) {
+    const int b = blockIdx.z, h = blockIdx.y;
+    const int32_t L = seqlens[b];
+    if (L < dm.n_q || L > dm.max_seqlen) return;          // a sequence shorter than n_q is skipped as a whole
+    const int c = (threadIdx.x & 15) * 8, sub = threadIdx.x >> 4;
+    const int32_t first_new = L - dm.n_q;
+    if ((int)blockIdx.x < n_copy) {
+        const int qi = blockIdx.x * 16 + sub;
+        if (qi >= dm.n_q) return;
+        const int64_t dst = first_new + qi;
+        *reinterpret_cast<uint4 *>(k.ptr + b * k.sb + h * k.sh + dst * k.st + c) =
+            *reinterpret_cast<const uint4 *>(k_new.ptr + b * k_new.sb + h * k_new.sh + qi * k_new.st + c);
+        *reinterpret_cast<uint4 *>(v.ptr + b * v.sb + h * v.sh + dst * v.st + c) =
+            *reinterpret_cast<const uint4 *>(v_new.ptr + b * v_new.sb + h * v_new.sh + qi * v_new.st + c);
+        return;
+    }
+    const int32_t jh = num_kernels(first_new) + ((int)blockIdx.x - n_copy) * 16 + sub;
+    if (jh >= num_kernels(L)) return;
+    const __bf16 *kb = k.ptr + b * k.sb + h * k.sh + c;
+    const __bf16 *nb = k_new.ptr + b * k_new.sb + h * k_new.sh + c;
+    bf16x8 x[kKernel];
+#pragma unroll
+    for (int t = 0; t < kKernel; ++t) {
+        const int32_t r = jh * kStride + t;
+        x[t] = r >= first_new ? load8(nb + (int64_t)(r - first_new) * k_new.st) : load8(kb + (int64_t)r * k.st);
+    }
+    double acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.0;
+#pragma unroll
+    for (int t = 0; t < kKernel; ++t)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += (double)(float)x[t][e];
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        w[e] = (uint32_t)f64_to_bf16_rne(acc[2 * e] / (double)kKernel) |
+               ((uint32_t)f64_to_bf16_rne(acc[2 * e + 1] / (double)kKernel) << 16);
+    *reinterpret_cast<uint4 *>(ck.ptr + b * ck.sb + h * ck.sh + (int64_t)jh * ck.st + c) = uint4{w[0], w[1], w[2], w[3]};
+}
+
 int launch_append_kv(const Dims &dm, Tensor k_new, Tensor v_new, Tensor k, Tensor v, const Tensor *ck,
                      const int32_t *seqlens, hipStream_t stream) {
+    if (ck && dm.n_q > 1) {
+        if (dm.batch <= 0) return 0;
+        const int n_copy = (dm.n_q + 15) / 16, n_comp = (dm.n_q / kStride + 1 + 15) / 16;
+        timing_begin("append_compress_kernel", stream);
+        hipLaunchKernelGGL(append_compress_kernel, dim3(n_copy + n_comp, dm.Hkv, dm.batch), dim3(256), 0, stream, dm,
+                           k_new, v_new, k, v, *ck, seqlens, n_copy);
+        timing_end(stream);
+        return (int)hipGetLastError();
+    }
     int rows = dm.batch * dm.Hkv * dm.n_q;
     if (rows <= 0) return 0;
     timing_begin("append_kv_kernel", stream);
@@ -121,11 +177,6 @@ int launch_append_kv(const Dims &dm, Tensor k_new, Tensor v_new, Tensor k, Tenso
         hipLaunchKernelGGL(append_kv_kernel<false>, dim3((rows + 15) / 16), dim3(256), 0, stream, dm, k_new,
                            v_new, k, v, k, seqlens);
     timing_end(stream);
-    if (ck && dm.n_q > 1) {      // several new rows: the kernels they complete, after the rows are in the cache
-        const int e = (int)hipGetLastError();
-        if (e) return e;
-        return launch_compress_keys(dm, k, *ck, seqlens, dm.n_q, stream);
-    }
     return (int)hipGetLastError();
 }
 

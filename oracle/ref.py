@@ -262,3 +262,51 @@ def sparse_attn_bwd(q, k, v, dout, pos, block_idx, prm, want_mag=False):
                                l, prm.block_size, topk, float(prm.softmax_scale), _ptr(dq), _ptr(dk), _ptr(dv),
                                *[_ptr(x) if x is not None else None for x in mags])
     return (dq, dk, dv, *mags) if want_mag else (dq, dk, dv)
+
+
+def select_blocks_shared(q, ck, prm, want_scores=False):
+    """Query-block-shared selection -- NOT the report's method (section 2.1.3 argues for token-level
+    queries); a comparison variant in which the m tokens of a query block attend one common block set.
+    Query block I (tokens m*I .. m*I+m-1 of a sequence of l = len(q) tokens) scores key-value block j by
+    the mean over its tokens of their per-token block relevance (Eq. 1 of section 2.1.2, as computed by
+    select_blocks); the first n_init blocks and the last n_local blocks up to I are forced, and the
+    min(topk, I+1) best are taken, ties to the lower index.  All candidates n_init <= j <= I - n_local
+    are wholly visible to every token of the query block.
+    -> block_idx int32 [Hkv, n_qb, topk] ascending, padded with -1, margins fp64 [Hkv, n_qb, 2]
+       (score of the last pick, best score not picked; nan if none) (, Rq fp64 [Hkv, n_qb, nb])."""
+    q = _u16(q)
+    l = q.shape[0]
+    m = prm.block_size
+    Hkv = prm.n_kv_heads
+    pos = np.arange(l, dtype=np.int32)
+    _, _, R = select_blocks(q, ck, pos, prm, want_scores=True)
+    n_qb = (l + m - 1) // m
+    idx = np.full((Hkv, n_qb, prm.topk), -1, np.int32)
+    margins = np.full((Hkv, n_qb, 2), np.nan)
+    Rq = np.full((Hkv, n_qb, n_qb), -np.inf)
+    for h in range(Hkv):
+        for I in range(n_qb):
+            toks = range(I * m, min((I + 1) * m, l))
+            n_init = min(prm.n_init_blocks, I + 1)
+            lo_local = max(n_init, I - prm.n_local_blocks + 1)
+            forced = list(range(n_init)) + list(range(lo_local, I + 1))
+            cand = list(range(n_init, lo_local))
+            score = {}
+            for j in cand:
+                total = 0.0
+                for t in toks:
+                    total += R[h, t, j]
+                score[j] = total / len(toks)
+                Rq[h, I, j] = score[j]
+            for j in forced:
+                Rq[h, I, j] = np.inf
+            n_pick = min(prm.topk, I + 1) - len(forced)
+            order = sorted(cand, key=lambda j: (-score[j], j))
+            picks = order[:n_pick]
+            if picks:
+                margins[h, I, 0] = score[picks[-1]]
+            if len(order) > n_pick and n_pick >= 0:
+                margins[h, I, 1] = score[order[n_pick]]
+            sel = sorted(forced + picks)
+            idx[h, I, :len(sel)] = sel
+    return (idx, margins, Rq) if want_scores else (idx, margins)

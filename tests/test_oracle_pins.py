@@ -633,3 +633,43 @@ def test_attention_backward_term_magnitudes():
     do_abs = do & np.uint16(0x7fff)
     _, _, dv3, _, _, mv3 = ref.sparse_attn_bwd(q, k, v, do_abs, pos, idx, prm, want_mag=True)
     assert np.allclose(dv3, mv3, rtol=0, atol=1e-12) and np.allclose(mv3, mv, rtol=0, atol=1e-12)
+
+
+# ------------------------------------------------------------------ query-block-shared selection
+# (a comparison variant, not the report's method: one block set per query block of m tokens)
+
+def test_shared_selection_invariants_and_single_head_special_case():
+    rng = np.random.default_rng(31)
+    l, d, m = 150, 16, 8
+    # G = 1 and the same query in every token of a query block: a token's block scores are exp(z[j]) / Z_i,
+    # so all tokens of a query block rank the candidates alike and the shared set is the last token's set
+    Hq = Hkv = 2
+    qb = rng.standard_normal(((l + m - 1) // m, Hq, d), dtype=np.float32)
+    q = synth.f32_to_bf16_bits(np.repeat(qb, m, axis=0)[:l])
+    k = synth.f32_to_bf16_bits(rng.standard_normal((Hkv, l, d), dtype=np.float32))
+    prm = ref.Params(Hq, Hkv, head_dim=d, block_size=m, kernel_size=4, kernel_stride=2, topk=5)
+    _, ckb = ref.compress_keys(k, prm)
+    idx_s, _ = ref.select_blocks_shared(q, ckb, prm)
+    idx_t, _ = ref.select_blocks(q, ckb, np.arange(l, dtype=np.int32), prm)
+    for I in range(idx_s.shape[1]):
+        last = min((I + 1) * m, l) - 1
+        assert np.array_equal(idx_s[:, I], idx_t[:, last]), I
+    # general case: forced blocks, counts, order, nestedness in k
+    Hq, Hkv = 8, 2
+    q = synth.f32_to_bf16_bits(rng.standard_normal((l, Hq, d), dtype=np.float32))
+    prev = None
+    for topk in (3, 4, 6, 9):
+        prm = ref.Params(Hq, Hkv, head_dim=d, block_size=m, kernel_size=4, kernel_stride=2, topk=topk)
+        idx, margins, Rq = ref.select_blocks_shared(q, ckb, prm, want_scores=True)
+        for h in range(Hkv):
+            for I in range(idx.shape[1]):
+                sel = idx[h, I][idx[h, I] >= 0]
+                assert len(sel) == min(topk, I + 1) and np.all(np.diff(sel) > 0) and sel.max() <= I
+                assert 0 in sel and I in sel and (I < 1 or I - 1 in sel)
+                scored = [j for j in sel if np.isfinite(Rq[h, I, j])]
+                rest = [j for j in range(I + 1) if j not in sel]
+                if scored and rest:
+                    assert min(Rq[h, I, j] for j in scored) >= max(Rq[h, I, j] for j in rest)
+                if prev is not None:
+                    assert set(prev[h, I][prev[h, I] >= 0].tolist()) <= set(sel.tolist())
+        prev = idx

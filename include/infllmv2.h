@@ -64,6 +64,7 @@ extern "C" {
 #define INFLLMV2_OP_ATTN_DECODE 4
 #define INFLLMV2_OP_ATTN_BWD 7
 #define INFLLMV2_OP_DECODE_STEP 8
+#define INFLLMV2_OP_SELECT_SHARED 9
 /* Stage selector for infllmv2_verify_workspace_bytes. */
 #define INFLLMV2_OP_SELECT_VERIFY 5
 #define INFLLMV2_OP_ATTN_VERIFY 6
@@ -151,6 +152,22 @@ int32_t infllmv2_select_blocks(const infllmv2_params *prm, int32_t mode, const i
                                const infllmv2_tensor *ck, const int32_t *seqlens, int32_t batch,
                                int32_t max_seqlen, int32_t *block_idx, void *workspace,
                                size_t workspace_bytes, void *stream);
+
+/*
+ * Query-block-shared selection -- a COMPARISON VARIANT, not the report's method (section 2.1.3 argues
+ * for token-level queries; infllmv2_select_blocks is the method).  The m = 64 tokens of query block I
+ * attend one common block set: block j is scored by the mean over the tokens of I of their per-token
+ * block relevance R[j] (as in infllmv2_select_blocks), the first n_init_blocks blocks and the last
+ * n_local_blocks blocks up to I are forced, the min(topk, I+1) best are taken, ties to the lower index.
+ *   q          [batch, max_seqlen, Hq, d]
+ *   block_idx  out  int32 [batch, Hkv, ceil(max_seqlen/64), topk], ascending, padded with -1; rows of
+ *              query blocks that start at or after seqlens[b] are not written
+ *   workspace  infllmv2_workspace_bytes(INFLLMV2_OP_SELECT_SHARED, ...) bytes
+ */
+int32_t infllmv2_select_blocks_shared(const infllmv2_params *prm, const infllmv2_tensor *q,
+                                      const infllmv2_tensor *ck, const int32_t *seqlens, int32_t batch,
+                                      int32_t max_seqlen, int32_t *block_idx, void *workspace,
+                                      size_t workspace_bytes, void *stream);
 
 /*
  * Stage 3, prefill -- attention over the selected blocks (section 2.1.1, second stage):

@@ -25,11 +25,12 @@ OP_SELECT_PREFILL, OP_SELECT_DECODE, OP_ATTN_PREFILL, OP_ATTN_DECODE = 1, 2, 3, 
 OP_SELECT_VERIFY, OP_ATTN_VERIFY = 5, 6
 OP_ATTN_BWD = 7
 OP_DECODE_STEP = 8
+OP_SELECT_SHARED = 9
 MODE_PREFILL, MODE_DECODE = 0, 1
 
 EXPORTS = ["infllmv2_status_string", "infllmv2_workspace_bytes", "infllmv2_compress_keys",
            "infllmv2_select_blocks", "infllmv2_sparse_attn_prefill", "infllmv2_sparse_attn_decode",
-           "infllmv2_sparse_attn_bwd", "infllmv2_append_kv", "infllmv2_decode_step", "infllmv2_verify_workspace_bytes", "infllmv2_append_kv_verify",
+           "infllmv2_sparse_attn_bwd", "infllmv2_append_kv", "infllmv2_decode_step", "infllmv2_select_blocks_shared", "infllmv2_verify_workspace_bytes", "infllmv2_append_kv_verify",
            "infllmv2_select_blocks_verify", "infllmv2_sparse_attn_verify",
            "infllmv2_probe_peaks", "infllmv2_timing_enable", "infllmv2_timing_read"]
 
@@ -107,6 +108,8 @@ def load_library(path=None):
     lib.infllmv2_sparse_attn_bwd.argtypes = [P, T, T, T, T, T, vp, vp, i32, i32, vp, T, T, T, vp, sz, vp]
     lib.infllmv2_decode_step.restype = i32
     lib.infllmv2_decode_step.argtypes = [P, T, T, T, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
+    lib.infllmv2_select_blocks_shared.restype = i32
+    lib.infllmv2_select_blocks_shared.argtypes = [P, T, T, vp, i32, i32, vp, vp, sz, vp]
     lib.infllmv2_append_kv.restype = i32
     lib.infllmv2_append_kv.argtypes = [P, T, T, T, T, T, vp, i32, i32, vp]
     lib.infllmv2_verify_workspace_bytes.restype = sz
@@ -389,3 +392,20 @@ def decode_step(prm, q, k_new, v_new, k, v, ck, seqlens, max_seqlen, block_idx=N
                                     _i32(block_idx, "block_idx").data_ptr(), ctypes.byref(d[6]), lse.data_ptr(),
                                     workspace.data_ptr(), ws_bytes, _stream()), "infllmv2_decode_step")
     return block_idx, out, lse
+
+
+def select_blocks_shared(prm, q, ck, seqlens, max_seqlen, block_idx=None, workspace=None):
+    """Query-block-shared selection (comparison variant, not the report's method)
+    -> block_idx int32 [B, Hkv, ceil(max_seqlen / 64), topk]."""
+    lib = load_library()
+    B = q.shape[0]
+    n_qb = (max_seqlen + prm.block_size - 1) // prm.block_size
+    if block_idx is None:
+        block_idx = torch.full((B, prm.n_kv_heads, n_qb, prm.topk), -1, dtype=torch.int32, device=q.device)
+    workspace, ws_bytes = _workspace(OP_SELECT_SHARED, prm, B, max_seqlen, workspace, q.device)
+    qd, cd = _query_desc(q, "q"), _cache_desc(ck, "ck")
+    _check(lib.infllmv2_select_blocks_shared(ctypes.byref(prm.c()), ctypes.byref(qd), ctypes.byref(cd),
+                                             _i32(seqlens, "seqlens").data_ptr(), B, max_seqlen,
+                                             _i32(block_idx, "block_idx").data_ptr(), workspace.data_ptr(),
+                                             ws_bytes, _stream()), "infllmv2_select_blocks_shared")
+    return block_idx

@@ -69,6 +69,7 @@ Dims make_dims(const infllmv2_params *p, int32_t batch, int32_t max_seqlen, int3
     d.scale_log2 = p->softmax_scale * kLog2e;
     d.rho = p->lse_coarse_ratio > 1 ? p->lse_coarse_ratio : 1;
     d.n_q = n_q;
+    d.shared_q = 0;
     return d;
 }
 
@@ -167,6 +168,11 @@ size_t infllmv2_workspace_bytes(int32_t op, const infllmv2_params *prm, int32_t 
         case INFLLMV2_OP_ATTN_PREFILL: return attn_prefill_ws_bytes(dm);
         case INFLLMV2_OP_ATTN_DECODE: return attn_decode_ws_bytes(dm);
         case INFLLMV2_OP_ATTN_BWD: return attn_bwd_ws_bytes(dm);
+        case INFLLMV2_OP_SELECT_SHARED: {
+            Dims ds = dm;
+            ds.shared_q = 1;
+            return select_prefill_ws_bytes(ds);
+        }
         case INFLLMV2_OP_DECODE_STEP:
             return max_seqlen > kMaxDecodeSeqlen ? 0 : select_decode_ws_bytes(dm) + attn_decode_ws_bytes(dm);
     }
@@ -333,6 +339,25 @@ int32_t infllmv2_select_blocks(const infllmv2_params *prm, int32_t mode, const i
                                                 workspace, st));
     return hip_status(launch_select_decode(dm, make_tensor(q), make_tensor(ck), seqlens, block_idx,
                                            workspace, st));
+}
+
+int32_t infllmv2_select_blocks_shared(const infllmv2_params *prm, const infllmv2_tensor *q,
+                                      const infllmv2_tensor *ck, const int32_t *seqlens, int32_t batch,
+                                      int32_t max_seqlen, int32_t *block_idx, void *workspace,
+                                      size_t workspace_bytes, void *stream) {
+    RETURN_IF_ERR(check_params(prm));
+    RETURN_IF_ERR(check_sizes(batch, max_seqlen));
+    RETURN_IF_ERR(check_tensor(q));
+    RETURN_IF_ERR(check_tensor(ck));
+    if (!seqlens || !block_idx) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    Dims dm = make_dims(prm, batch, max_seqlen);
+    dm.shared_q = 1;
+    const size_t need = select_prefill_ws_bytes(dm);
+    if (need > 0 && (!workspace || workspace_bytes < need ||
+                     (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0))
+        return INFLLMV2_ERR_WORKSPACE;
+    return hip_status(launch_select_prefill(dm, make_tensor(q), make_tensor(ck), seqlens, block_idx, workspace,
+                                            reinterpret_cast<hipStream_t>(stream)));
 }
 
 int32_t infllmv2_sparse_attn_prefill(const infllmv2_params *prm, const infllmv2_tensor *q,

@@ -30,6 +30,7 @@ struct Dims {
     float scale_log2;   // softmax_scale * log2(e)
     int32_t rho;        // coarse / fine kernel stride of the approximate log-sum-exp; 1 = exact
     int32_t n_q;        // decode-side kernels: query tokens per sequence (1 = plain decode, n = draft verification)
+    int32_t shared_q;   // prefill selection: 1 = one block set per 64-token query block (comparison variant)
 };
 
 struct Tensor {          // strides in elements
@@ -134,6 +135,7 @@ int launch_select_prefill16(const Dims &dm, Tensor q, Tensor ck, const int32_t *
 size_t select_prefill16_ws_bytes(const Dims &dm);
 int32_t select_scores_pitch(const Dims &dm);
 size_t select_scores_bytes(const Dims &dm);
+size_t select_shared_scores_bytes(const Dims &dm);
 int launch_select_pick(const Dims &dm, const int32_t *seqlens, const float *R, int32_t nb_cap,
                        int32_t *block_idx, hipStream_t stream);
 int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,

@@ -271,25 +271,29 @@ __host__ __device__ inline int pick_cand_cap(int topk, int vpl) { return (topk *
 template <int VPL>
 __global__ __launch_bounds__(256) void select_pick_kernel(Dims dm, const int32_t *__restrict__ seqlens,
                                                            const float *__restrict__ R, int32_t nb_cap,
-                                                           int32_t *__restrict__ block_idx) {
+                                                           int32_t *__restrict__ block_idx, int32_t row_tokens) {
     extern __shared__ __align__(16) unsigned char pick_smem[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int cand_cap = pick_cand_cap(dm.topk, VPL);
     uint64_t *tmax = reinterpret_cast<uint64_t *>(pick_smem) + (size_t)wave * (64 + cand_cap);
     uint64_t *cand = tmax + 64;
     int *picked = reinterpret_cast<int *>(tmax);                              // reused once the ranks are known
+    // a row is one query token, or (row_tokens = 64, the query-block-shared variant) one query block,
+    // which selects like its last token
+    const int rows_per_seq = (dm.max_seqlen + row_tokens - 1) / row_tokens;
     const int64_t row = (int64_t)blockIdx.x * kPickRowsPerWg + wave;
-    const int64_t rows = (int64_t)dm.batch * dm.Hkv * dm.max_seqlen;
+    const int64_t rows = (int64_t)dm.batch * dm.Hkv * rows_per_seq;
     if (row >= rows) return;
-    const int b = row / ((int64_t)dm.max_seqlen * dm.Hkv);
+    const int b = row / ((int64_t)rows_per_seq * dm.Hkv);
     const float *Rr = R + row * nb_cap;
     float r[VPL];                                                             // every load issued before any use
 #pragma unroll
     for (int s = 0; s < VPL; ++s) r[s] = Rr[min(lane + 64 * s, nb_cap - 1)];
     int32_t L = seqlens[b];
     L = L < 0 ? 0 : (L > dm.max_seqlen ? dm.max_seqlen : L);
-    const int tok = row % dm.max_seqlen;
-    if (tok >= L) return;
+    const int tok0 = (int)(row % rows_per_seq) * row_tokens;
+    if (tok0 >= L) return;
+    const int tok = min(tok0 + row_tokens - 1, L - 1);
     const int b_own = tok / kBlock, n_blk = b_own + 1;
     const int n_sel = dm.topk < n_blk ? dm.topk : n_blk;
     const int n_init = dm.n_init < n_blk ? dm.n_init : n_blk;                 // forced leading blocks
@@ -355,16 +359,18 @@ __global__ __launch_bounds__(256) void select_pick_kernel(Dims dm, const int32_t
 // Fallback for rows longer than 64*32 blocks: scans the row in memory once per pick.
 __global__ __launch_bounds__(256) void select_pick_scan_kernel(Dims dm, const int32_t *__restrict__ seqlens,
                                                                 const float *__restrict__ R, int32_t nb_cap,
-                                                                int32_t *__restrict__ block_idx) {
+                                                                int32_t *__restrict__ block_idx, int32_t row_tokens) {
     const int lane = threadIdx.x & 63;
+    const int rows_per_seq = (dm.max_seqlen + row_tokens - 1) / row_tokens;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int64_t rows = (int64_t)dm.batch * dm.Hkv * dm.max_seqlen;
+    const int64_t rows = (int64_t)dm.batch * dm.Hkv * rows_per_seq;
     if (row >= rows) return;
-    const int tok = row % dm.max_seqlen;
-    const int b = row / ((int64_t)dm.max_seqlen * dm.Hkv);
+    const int b = row / ((int64_t)rows_per_seq * dm.Hkv);
     int32_t L = seqlens[b];
     L = L < 0 ? 0 : (L > dm.max_seqlen ? dm.max_seqlen : L);
-    if (tok >= L) return;
+    const int tok0 = (int)(row % rows_per_seq) * row_tokens;
+    if (tok0 >= L) return;
+    const int tok = min(tok0 + row_tokens - 1, L - 1);
     const int b_own = tok / kBlock, n_blk = b_own + 1;
     const int n_sel = dm.topk < n_blk ? dm.topk : n_blk;
     const float *Rr = R + row * nb_cap;
@@ -408,10 +414,47 @@ int32_t select_scores_pitch(const Dims &dm) {
 size_t select_scores_bytes(const Dims &dm) {
     return (size_t)dm.batch * dm.Hkv * dm.max_seqlen * select_scores_pitch(dm) * sizeof(float);
 }
+size_t select_shared_scores_bytes(const Dims &dm) {     // per-query-block scores of the shared variant, behind the per-token ones
+    if (!dm.shared_q) return 0;
+    return (size_t)dm.batch * dm.Hkv * ((dm.max_seqlen + kBlock - 1) / kBlock) * select_scores_pitch(dm) * sizeof(float);
+}
+
+// Query-block-shared variant (not the report's method; section 2.1.3 argues for token-level queries):
+// the block scores of the 64 tokens of a query block are averaged, one row per query block.
+// grid (n_qb, Hkv, B), 256 threads over the candidate blocks.
+__global__ __launch_bounds__(256) void reduce_scores_kernel(Dims dm, const int32_t *__restrict__ seqlens,
+                                                             const float *__restrict__ R, int32_t nb_cap,
+                                                             float *__restrict__ Rq, int32_t n_qb) {
+    const int I = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    int32_t L = seqlens[b];
+    L = L < 0 ? 0 : (L > dm.max_seqlen ? dm.max_seqlen : L);
+    const int t0 = I * kBlock, n_tok = min(kBlock, L - t0);
+    if (n_tok <= 0) return;
+    const int64_t bh = (int64_t)b * dm.Hkv + h;
+    const int j_hi = I - dm.n_local;                      // candidates n_init .. I - n_local: wholly visible to every token
+    for (int j = dm.n_init + threadIdx.x; j <= j_hi; j += 256) {
+        float acc = 0.f;
+        for (int t = 0; t < n_tok; ++t) acc += R[(bh * dm.max_seqlen + t0 + t) * nb_cap + j];
+        Rq[(bh * n_qb + I) * nb_cap + j] = acc / (float)n_tok;
+    }
+}
 
 int launch_select_pick(const Dims &dm, const int32_t *seqlens, const float *R, int32_t nb_cap,
                        int32_t *block_idx, hipStream_t stream) {
-    const int64_t rows = (int64_t)dm.batch * dm.Hkv * dm.max_seqlen;
+    int32_t row_tokens = 1;
+    if (dm.shared_q) {                                    // average over the query blocks first; Rq sits behind R
+        const int32_t n_qb = (dm.max_seqlen + kBlock - 1) / kBlock;
+        if (n_qb <= 0 || dm.batch <= 0) return 0;
+        float *Rq = const_cast<float *>(R) + select_scores_bytes(dm) / sizeof(float);
+        timing_begin("reduce_scores_kernel", stream);
+        hipLaunchKernelGGL(reduce_scores_kernel, dim3(n_qb, dm.Hkv, dm.batch), dim3(256), 0, stream, dm, seqlens, R,
+                           nb_cap, Rq, n_qb);
+        timing_end(stream);
+        R = Rq;
+        row_tokens = kBlock;
+    }
+    const int rows_per_seq = (dm.max_seqlen + row_tokens - 1) / row_tokens;
+    const int64_t rows = (int64_t)dm.batch * dm.Hkv * rows_per_seq;
     if (rows <= 0) return 0;
     const dim3 grid((uint32_t)((rows + 3) / 4));
     const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
@@ -419,15 +462,15 @@ int launch_select_pick(const Dims &dm, const int32_t *seqlens, const float *R, i
     const size_t lds = (size_t)kPickRowsPerWg * (64 + pick_cand_cap(dm.topk, vpl)) * sizeof(uint64_t);
     timing_begin("select_pick_kernel", stream);
     if (n_blocks > 64 * 32 || lds > 64 * 1024)           // very long rows or very wide top-k: generic scan
-        hipLaunchKernelGGL(select_pick_scan_kernel, grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx);
+        hipLaunchKernelGGL(select_pick_scan_kernel, grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx, row_tokens);
     else if (vpl == 4)
-        hipLaunchKernelGGL((select_pick_kernel<4>), grid, dim3(256), lds, stream, dm, seqlens, R, nb_cap, block_idx);
+        hipLaunchKernelGGL((select_pick_kernel<4>), grid, dim3(256), lds, stream, dm, seqlens, R, nb_cap, block_idx, row_tokens);
     else if (vpl == 8)
-        hipLaunchKernelGGL((select_pick_kernel<8>), grid, dim3(256), lds, stream, dm, seqlens, R, nb_cap, block_idx);
+        hipLaunchKernelGGL((select_pick_kernel<8>), grid, dim3(256), lds, stream, dm, seqlens, R, nb_cap, block_idx, row_tokens);
     else if (vpl == 16)
-        hipLaunchKernelGGL((select_pick_kernel<16>), grid, dim3(256), lds, stream, dm, seqlens, R, nb_cap, block_idx);
+        hipLaunchKernelGGL((select_pick_kernel<16>), grid, dim3(256), lds, stream, dm, seqlens, R, nb_cap, block_idx, row_tokens);
     else
-        hipLaunchKernelGGL((select_pick_kernel<32>), grid, dim3(256), lds, stream, dm, seqlens, R, nb_cap, block_idx);
+        hipLaunchKernelGGL((select_pick_kernel<32>), grid, dim3(256), lds, stream, dm, seqlens, R, nb_cap, block_idx, row_tokens);
     timing_end(stream);
     return (int)hipGetLastError();
 }
@@ -436,7 +479,7 @@ size_t select_prefill_ws_bytes(const Dims &dm) {
     if (dm.G == 16) return select_prefill16_ws_bytes(dm);
     size_t lse = (size_t)dm.batch * dm.max_seqlen * dm.Hq * sizeof(float);
     lse = (lse + 255) / 256 * 256;
-    return lse + select_scores_bytes(dm);
+    return lse + select_scores_bytes(dm) + select_shared_scores_bytes(dm);
 }
 
 template <int G>

@@ -383,7 +383,7 @@ size_t select_prefill16_ws_bytes(const Dims &dm) {
     const size_t nt_cap = ((size_t)num_kernels(dm.max_seqlen) + 15) / 16;
     size_t ckp = (size_t)dm.batch * dm.Hkv * nt_cap * 256 * sizeof(uint4);
     ckp = (ckp + 255) / 256 * 256;
-    return lse + ckp + coarse_tiles_bytes(dm) + select_scores_bytes(dm);
+    return lse + ckp + coarse_tiles_bytes(dm) + select_scores_bytes(dm) + select_shared_scores_bytes(dm);
 }
 
 int launch_select_prefill16(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens, int32_t *block_idx,

@@ -536,3 +536,30 @@ def test_sparse_attn_backward(seqlens, Hq, Hkv, topk, planted):
         print("seq %d len %d: err/tol dq %.3f dk %.3f dv %.3f   (max|dq| %.2e max|dk| %.2e max|dv| %.2e)"
               % (b, l, eq, ek, ev, np.abs(wq).max(), np.abs(wk).max(), np.abs(wv).max()), flush=True)
         assert eq <= 1.0 and ek <= 1.0 and ev <= 1.0
+
+
+# ------------------------------------------------------------------ query-block-shared selection (comparison variant)
+
+@pytest.mark.parametrize("seqlens,Hq,Hkv,topk,planted", [([1077, 333, 64, 1], 32, 2, 8, 5), ([700], 16, 2, 6, 3),
+                                                          ([2500], 4, 1, 16, 4)])
+def test_select_blocks_shared(seqlens, Hq, Hkv, topk, planted):
+    print("case select shared", seqlens, Hq, Hkv, topk, flush=True)
+    prm = binding.Params(Hq, Hkv, topk=topk)
+    oprm = oracle_params(prm)
+    q, k, v, T = make_batch(61, seqlens, Hq, Hkv, n_planted=planted)
+    qd, kd, sl = to_dev(q), to_dev(k), dev_i32(seqlens)
+    ck = binding.compress_keys(prm, kd, sl, T)
+    idx = binding.select_blocks_shared(prm, qd, ck, sl, T)
+    torch.cuda.synchronize()
+    idx = idx.cpu().numpy()
+    ckb = to_bits(ck)
+    tot = near = 0
+    for b, l in enumerate(seqlens):
+        n_c = ref.num_kernels(l, 32, 16)
+        want, margins, Rq = ref.select_blocks_shared(q[b, :l], ckb[b, :, :n_c], oprm, want_scores=True)
+        n_qb = want.shape[1]
+        n, e, nt, hard = compare_selection(idx[b, :, :n_qb], want, margins, Rq)
+        assert not hard, hard[:3]
+        assert np.all(idx[b, :, n_qb:] == -1)                          # query blocks past the end are not written
+        tot, near = tot + n, near + nt
+    assert near <= max(2, tot // 100)

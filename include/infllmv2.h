@@ -170,6 +170,20 @@ int32_t infllmv2_select_blocks_shared(const infllmv2_params *prm, const infllmv2
                                       size_t workspace_bytes, void *stream);
 
 /*
+ * The attention for block sets shared by the 64 tokens of a query block (the same COMPARISON VARIANT):
+ * out and lse as infllmv2_sparse_attn_prefill computes them when every token of query block I is given
+ * row I of block_idx.
+ *   block_idx  in   int32 [batch, Hkv, ceil(max_seqlen/64), topk]; entries < 0 or > I are skipped; each
+ *              row must be duplicate-free
+ *   workspace  infllmv2_workspace_bytes(INFLLMV2_OP_ATTN_PREFILL, ...) bytes
+ */
+int32_t infllmv2_sparse_attn_prefill_shared(const infllmv2_params *prm, const infllmv2_tensor *q,
+                                            const infllmv2_tensor *k, const infllmv2_tensor *v,
+                                            const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
+                                            const int32_t *block_idx, const infllmv2_tensor *out, float *lse,
+                                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Stage 3, prefill -- attention over the selected blocks (section 2.1.1, second stage):
  *     T_i = { t <= i : floor(t/m) in block_idx[b, h, i, :] }
  *     out[b, i, hq, :] = sum_{t in T_i} softmax_t(softmax_scale * <q_i, k_t>) v_t

@@ -30,7 +30,7 @@ MODE_PREFILL, MODE_DECODE = 0, 1
 
 EXPORTS = ["infllmv2_status_string", "infllmv2_workspace_bytes", "infllmv2_compress_keys",
            "infllmv2_select_blocks", "infllmv2_sparse_attn_prefill", "infllmv2_sparse_attn_decode",
-           "infllmv2_sparse_attn_bwd", "infllmv2_append_kv", "infllmv2_decode_step", "infllmv2_select_blocks_shared", "infllmv2_verify_workspace_bytes", "infllmv2_append_kv_verify",
+           "infllmv2_sparse_attn_bwd", "infllmv2_append_kv", "infllmv2_decode_step", "infllmv2_select_blocks_shared", "infllmv2_sparse_attn_prefill_shared", "infllmv2_verify_workspace_bytes", "infllmv2_append_kv_verify",
            "infllmv2_select_blocks_verify", "infllmv2_sparse_attn_verify",
            "infllmv2_probe_peaks", "infllmv2_timing_enable", "infllmv2_timing_read"]
 
@@ -110,6 +110,8 @@ def load_library(path=None):
     lib.infllmv2_decode_step.argtypes = [P, T, T, T, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
     lib.infllmv2_select_blocks_shared.restype = i32
     lib.infllmv2_select_blocks_shared.argtypes = [P, T, T, vp, i32, i32, vp, vp, sz, vp]
+    lib.infllmv2_sparse_attn_prefill_shared.restype = i32
+    lib.infllmv2_sparse_attn_prefill_shared.argtypes = [P, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
     lib.infllmv2_append_kv.restype = i32
     lib.infllmv2_append_kv.argtypes = [P, T, T, T, T, T, vp, i32, i32, vp]
     lib.infllmv2_verify_workspace_bytes.restype = sz
@@ -409,3 +411,22 @@ def select_blocks_shared(prm, q, ck, seqlens, max_seqlen, block_idx=None, worksp
                                              _i32(block_idx, "block_idx").data_ptr(), workspace.data_ptr(),
                                              ws_bytes, _stream()), "infllmv2_select_blocks_shared")
     return block_idx
+
+
+def sparse_attn_prefill_shared(prm, q, k, v, seqlens, max_seqlen, block_idx, out=None, lse=None, workspace=None):
+    """Attention for block sets shared per 64-token query block (comparison variant); block_idx
+    [B, Hkv, ceil(T/64), topk] -> out bf16 [B, T, Hq, d], lse fp32 [B, T, Hq]."""
+    lib = load_library()
+    B = q.shape[0]
+    if out is None:
+        out = torch.zeros_like(q)
+    if lse is None:
+        lse = torch.zeros((B, max_seqlen, prm.n_q_heads), dtype=torch.float32, device=q.device)
+    workspace, ws_bytes = _workspace(OP_ATTN_PREFILL, prm, B, max_seqlen, workspace, q.device)
+    d = [_query_desc(q, "q"), _cache_desc(k, "k"), _cache_desc(v, "v"), _query_desc(out, "out")]
+    _check(lib.infllmv2_sparse_attn_prefill_shared(ctypes.byref(prm.c()), ctypes.byref(d[0]), ctypes.byref(d[1]),
+                                                   ctypes.byref(d[2]), _i32(seqlens, "seqlens").data_ptr(), B,
+                                                   max_seqlen, _i32(block_idx, "block_idx").data_ptr(),
+                                                   ctypes.byref(d[3]), lse.data_ptr(), workspace.data_ptr(),
+                                                   ws_bytes, _stream()), "infllmv2_sparse_attn_prefill_shared")
+    return out, lse

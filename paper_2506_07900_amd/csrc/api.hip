@@ -382,6 +382,29 @@ int32_t infllmv2_sparse_attn_prefill(const infllmv2_params *prm, const infllmv2_
                                           reinterpret_cast<hipStream_t>(stream)));
 }
 
+int32_t infllmv2_sparse_attn_prefill_shared(const infllmv2_params *prm, const infllmv2_tensor *q,
+                                            const infllmv2_tensor *k, const infllmv2_tensor *v,
+                                            const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
+                                            const int32_t *block_idx, const infllmv2_tensor *out, float *lse,
+                                            void *workspace, size_t workspace_bytes, void *stream) {
+    RETURN_IF_ERR(check_params(prm));
+    RETURN_IF_ERR(check_sizes(batch, max_seqlen));
+    RETURN_IF_ERR(check_tensor(q));
+    RETURN_IF_ERR(check_tensor(k));
+    RETURN_IF_ERR(check_tensor(v));
+    RETURN_IF_ERR(check_tensor(out));
+    if (!seqlens || !block_idx || !lse) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    Dims dm = make_dims(prm, batch, max_seqlen);
+    dm.shared_q = 1;
+    const size_t need = attn_prefill_ws_bytes(dm);
+    if (need > 0 && (!workspace || workspace_bytes < need ||
+                     (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0))
+        return INFLLMV2_ERR_WORKSPACE;
+    return hip_status(launch_attn_prefill(dm, make_tensor(q), make_tensor(k), make_tensor(v), seqlens,
+                                          block_idx, make_tensor(out), lse, workspace,
+                                          reinterpret_cast<hipStream_t>(stream)));
+}
+
 int32_t infllmv2_sparse_attn_bwd(const infllmv2_params *prm, const infllmv2_tensor *q,
                                  const infllmv2_tensor *k, const infllmv2_tensor *v,
                                  const infllmv2_tensor *out, const infllmv2_tensor *dout, const float *lse,

@@ -360,6 +360,170 @@ __global__ __launch_bounds__(256, kWavesPerSimd) void attn_prefill_kernel(Dims d
     }
 }
 
+// ---- attention with one block set per query block (comparison variant) ------------------------------------
+// Not the report's method (section 2.1.3: token-level queries); it shows what the same arithmetic
+// reaches when the 64 tokens of a query block attend one common block list.  A workgroup takes 8
+// consecutive tokens of a query block (a wavefront 2, as above) and walks the shared list in step:
+// every packed block is fetched once per workgroup -- each thread carries 1/256 of the next block in
+// registers while the current one is consumed -- and all four wavefronts read their operand
+// fragments from LDS, which delivers several times what the L2 path does.  Only the query block's
+// own key-value block needs the causal mask.
+constexpr int kShTok = 2;                                // tokens per wavefront
+__global__ __launch_bounds__(256, 2) void attn_prefill_shared_kernel(Dims dm, Tensor q, const uint4 *__restrict__ kvp,
+                                                                      int32_t nb_cap, const int32_t *__restrict__ seqlens,
+                                                                      const int32_t *__restrict__ block_idx,
+                                                                      Tensor out, float *__restrict__ lse,
+                                                                      int32_t n_tiles) {
+    __shared__ __align__(16) u32x4 stage[2][kPackedBlockU4];
+    const uint32_t vid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    const int tile = vid % n_tiles;                      // 8 tokens
+    const int h = (vid / n_tiles) % dm.Hkv;
+    const int b = vid / (n_tiles * dm.Hkv);
+    int32_t L = seqlens[b];
+    L = L < 0 ? 0 : (L > dm.max_seqlen ? dm.max_seqlen : L);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tile * 8 >= L) return;                           // uniform over the workgroup
+    const int t0 = tile * 8 + wave * kShTok;             // this wavefront's first token (may lie past the end)
+    const int I = (tile * 8) / kBlock;                   // the query block, and its own key-value block
+    const int n_qb = (dm.max_seqlen + kBlock - 1) / kBlock;
+    const int n = lane & 15, g = lane >> 4;
+    const int G = dm.G;
+    const float c = dm.scale_log2;
+
+    // the shared list, compacted: entries < 0 or above the own block are dropped (each wavefront keeps its own copy)
+    __shared__ int blist[4][64];
+    int entry = kNone;
+    if (lane < dm.topk) {
+        const int x = block_idx[(((int64_t)b * dm.Hkv + h) * n_qb + I) * dm.topk + lane];
+        if (x >= 0 && x <= I) entry = x;
+    }
+    const uint64_t have = __ballot(entry != kNone);
+    const int cnt = __popcll(have);
+    if (entry != kNone) blist[wave][__popcll(have & ((1ull << lane) - 1ull))] = entry;   // same wavefront reads it back
+    bf16x8 qf[kShTok][4];
+    f32x4 o[kShTok][8];
+    float neg_m[kShTok], l_run[kShTok];
+#pragma unroll
+    for (int u = 0; u < kShTok; ++u) {
+        const int tok = min(t0 + u, L - 1);              // rows past the end compute on a copy and are not written
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            qf[u][ks] = load8(q.ptr + b * q.sb + (int64_t)tok * q.st + (int64_t)(h * G + min(n, G - 1)) * q.sh + 32 * ks + 8 * g);
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) o[u][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        neg_m[u] = __builtin_nanf("");
+        l_run[u] = 0.f;
+    }
+    auto softmax = [&](f32x4 (&s)[2], int u, bf16x8 &pf) __attribute__((always_inline)) {
+        float ps = half_probs(s, c, neg_m[u], pf);
+        if (__any(!(ps <= kPsumLimit))) {                 // rare: too large, inf, or NaN (no reference yet)
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) tmax = fmaxf(tmax, s[t][j]);
+            tmax = xgroup_max(tmax) * c;
+            const float old = neg_m[u];
+            const float m_new = (old != old) ? tmax : fmaxf(-old, tmax);
+            if (m_new > -INFINITY) {
+                const float f = (old != old) ? 0.f : fast_exp2(-old - m_new);
+                l_run[u] *= f;
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) o[u][dt] *= f;
+                neg_m[u] = -m_new;
+                ps = half_probs(s, c, -m_new, pf);
+            } else {
+                ps = 0.f;
+                pf = zero8();
+            }
+        }
+        l_run[u] += ps;
+    };
+
+    const u32x4 *kv_head = reinterpret_cast<const u32x4 *>(kvp) + ((int64_t)b * dm.Hkv + h) * nb_cap * kPackedBlockU4;
+    u32x4 r[8];                                          // this thread's 1/256 of a packed block
+    auto fetch = [&](int ci) __attribute__((always_inline)) {
+        const int blk = blist[wave][min(ci, cnt - 1)];
+        const u32x4 *bp = kv_head + (int64_t)blk * kPackedBlockU4 + tid;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] = bp[256 * i];
+    };
+    auto stash = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) stage[buf][tid + 256 * i] = r[i];
+    };
+    if (cnt == 0) return;                                // (cannot happen for a live query block: its own block is forced)
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    for (int ci = 0; ci < cnt; ++ci) {
+        const int cur = ci & 1;
+        fetch(ci + 1);                                   // (a copy of the last block at the end, never used)
+        const int blk = blist[wave][ci];
+        const int key0 = blk * kBlock;
+        const bool edge = blk == I;
+        const u32x4 *sb = stage[cur] + lane;
+#pragma unroll
+        for (int hs = 0; hs < 2; ++hs) {
+            f32x4 s[kShTok][2];
+#pragma unroll
+            for (int rr = 0; rr < 2; ++rr) {
+                const int mt = 2 * hs + rr;
+                u32x4 kf[4];
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) kf[ks] = sb[(ks * 4 + mt) * 64];
+#pragma unroll
+                for (int u = 0; u < kShTok; ++u) {
+                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) acc = mfma16(__builtin_bit_cast(bf16x8, kf[ks]), qf[u][ks], acc);
+                    s[u][rr] = acc;
+                }
+            }
+            bf16x8 pf[kShTok];
+#pragma unroll
+            for (int u = 0; u < kShTok; ++u) {
+                if (edge) {
+                    const int tok = t0 + u;
+#pragma unroll
+                    for (int t = 0; t < 2; ++t)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (key0 + 32 * hs + 16 * t + 4 * g + j > tok) s[u][t][j] = -INFINITY;
+                }
+                softmax(s[u], u, pf[u]);
+            }
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+                const u32x4 vf = sb[(kFragsPerOperand + dt * 2 + hs) * 64];
+#pragma unroll
+                for (int u = 0; u < kShTok; ++u) o[u][dt] = mfma16(__builtin_bit_cast(bf16x8, vf), pf[u], o[u][dt]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        stash(cur ^ 1);
+        __syncthreads();
+    }
+#pragma unroll
+    for (int u = 0; u < kShTok; ++u) {
+        const int tok = t0 + u;
+        if (tok >= L || n >= G) continue;
+        const float l_tot = xgroup_sum(l_run[u]);
+        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+        __bf16 *op = out.ptr + b * out.sb + (int64_t)tok * out.st + (int64_t)(h * G + n) * out.sh + 4 * g;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+            bf16x4 rr;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) rr[j] = (__bf16)(o[u][dt][j] * inv);
+            *reinterpret_cast<uint2 *>(op + 16 * dt) = __builtin_bit_cast(uint2, rr);
+        }
+        if (g == 0)
+            lse[((int64_t)b * dm.max_seqlen + tok) * dm.Hq + h * G + n] =
+                l_tot > 0.f ? (fast_log2(l_tot) - neg_m[u]) * kLn2 : -INFINITY;
+    }
+}
+
 size_t attn_prefill_ws_bytes(const Dims &dm) {
     const size_t nb_cap = ((size_t)dm.max_seqlen + kBlock - 1) / kBlock;
     return (size_t)dm.batch * dm.Hkv * nb_cap * kPackedBlockU4 * sizeof(uint4);
@@ -383,6 +547,14 @@ int launch_attn_prefill(const Dims &dm, Tensor q, Tensor k, Tensor v, const int3
     hipLaunchKernelGGL(pack_kv_kernel, dim3(nb_cap, dm.Hkv, dm.batch), dim3(256), 0, stream, dm, k, v,
                        seqlens, kvp, nb_cap);
     timing_end(stream);
+    if (dm.shared_q) {                                   // one block list per query block (comparison variant)
+        const int32_t n_tiles = (dm.max_seqlen + 7) / 8;
+        timing_begin("attn_prefill_shared_kernel", stream);
+        hipLaunchKernelGGL(attn_prefill_shared_kernel, dim3((uint32_t)((int64_t)n_tiles * dm.Hkv * dm.batch)), dim3(256),
+                           0, stream, dm, q, kvp, nb_cap, seqlens, block_idx, out, lse, n_tiles);
+        timing_end(stream);
+        return (int)hipGetLastError();
+    }
     // 2 tokens per wavefront, ring of 4 units, 2 wavefronts per SIMD: the configuration that keeps
     // the most loads in flight per compute unit within 256 registers per lane
     timing_begin("attn_prefill_kernel", stream);

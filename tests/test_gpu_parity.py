@@ -563,3 +563,36 @@ def test_select_blocks_shared(seqlens, Hq, Hkv, topk, planted):
         assert np.all(idx[b, :, n_qb:] == -1)                          # query blocks past the end are not written
         tot, near = tot + n, near + nt
     assert near <= max(2, tot // 100)
+
+
+@pytest.mark.parametrize("seqlens,Hq,Hkv,topk,planted", [([1077, 333, 64, 1, 0], 32, 2, 8, 5), ([700], 16, 2, 6, 3),
+                                                          ([450], 2, 2, 5, 2), ([1500], 16, 1, 32, 5)])
+def test_sparse_attn_prefill_shared(seqlens, Hq, Hkv, topk, planted):
+    # the attention for per-query-block sets equals the per-token attention given the expanded sets
+    print("case attn shared", seqlens, Hq, Hkv, topk, flush=True)
+    prm = binding.Params(Hq, Hkv, topk=topk)
+    oprm = oracle_params(prm)
+    q, k, v, T = make_batch(63, seqlens, Hq, Hkv, n_planted=planted)
+    B = len(seqlens)
+    n_qb = (T + 63) // 64
+    idx_s = np.full((B, Hkv, n_qb, topk), -1, np.int32)
+    want = [None] * B
+    for b, l in enumerate(seqlens):
+        if l == 0:
+            continue
+        _, ckb = ref.compress_keys(k[b, :, :l], oprm)
+        ib, _ = ref.select_blocks_shared(q[b, :l], ckb, oprm)
+        idx_s[b, :, :ib.shape[1]] = ib
+        per_token = np.repeat(ib, 64, axis=1)[:, :l]                    # token t uses row t // 64
+        want[b] = ref.sparse_attn(q[b, :l], k[b, :, :l], v[b, :, :l], np.arange(l, dtype=np.int32), per_token, oprm)
+    qd, kd, vd, sl = to_dev(q), to_dev(k), to_dev(v), dev_i32(seqlens)
+    out, lse = binding.sparse_attn_prefill_shared(prm, qd, kd, vd, sl, T, torch.from_numpy(idx_s).cuda())
+    torch.cuda.synchronize()
+    for b, l in enumerate(seqlens):
+        if l == 0:
+            continue
+        eo = np.abs(out[b, :l].double().cpu().numpy() - want[b][0]).max()
+        el = lse_err(lse[b, :l].double().cpu().numpy(), want[b][1])
+        print("seq %d len %d: max|dO| %.3e LSE err/tol %.3f" % (b, l, eo, el), flush=True)
+        assert eo <= OUT_TOL and el <= 1.0
+        assert bool((out[b, l:] == 0).all())

@@ -264,7 +264,7 @@ def sparse_attn_bwd(q, k, v, dout, pos, block_idx, prm, want_mag=False):
     return (dq, dk, dv, *mags) if want_mag else (dq, dk, dv)
 
 
-def select_blocks_shared(q, ck, prm, want_scores=False):
+def select_blocks_shared(q, ck, prm, want_scores=False, qblocks=None):
     """Query-block-shared selection -- NOT the report's method (section 2.1.3 argues for token-level
     queries); a comparison variant in which the m tokens of a query block attend one common block set.
     Query block I (tokens m*I .. m*I+m-1 of a sequence of l = len(q) tokens) scores key-value block j by
@@ -273,19 +273,24 @@ def select_blocks_shared(q, ck, prm, want_scores=False):
     min(topk, I+1) best are taken, ties to the lower index.  All candidates n_init <= j <= I - n_local
     are wholly visible to every token of the query block.
     -> block_idx int32 [Hkv, n_qb, topk] ascending, padded with -1, margins fp64 [Hkv, n_qb, 2]
-       (score of the last pick, best score not picked; nan if none) (, Rq fp64 [Hkv, n_qb, nb])."""
+       (score of the last pick, best score not picked; nan if none) (, Rq fp64 [Hkv, n_qb, nb]).
+    With qblocks (a list of query-block indices) only those rows are computed; the others stay -1."""
     q = _u16(q)
     l = q.shape[0]
     m = prm.block_size
     Hkv = prm.n_kv_heads
-    pos = np.arange(l, dtype=np.int32)
-    _, _, R = select_blocks(q, ck, pos, prm, want_scores=True)
     n_qb = (l + m - 1) // m
+    which = list(range(n_qb)) if qblocks is None else [int(I) for I in qblocks]
+    pos = np.concatenate([np.arange(I * m, min((I + 1) * m, l), dtype=np.int32) for I in which]) if which \
+        else np.zeros((0,), np.int32)
+    _, _, Rt = select_blocks(np.ascontiguousarray(q[pos]), ck, pos, prm, want_scores=True)
+    row_of = {int(t): a for a, t in enumerate(pos)}
     idx = np.full((Hkv, n_qb, prm.topk), -1, np.int32)
     margins = np.full((Hkv, n_qb, 2), np.nan)
     Rq = np.full((Hkv, n_qb, n_qb), -np.inf)
     for h in range(Hkv):
-        for I in range(n_qb):
+        R = {t: Rt[h, a] for t, a in row_of.items()}
+        for I in which:
             toks = range(I * m, min((I + 1) * m, l))
             n_init = min(prm.n_init_blocks, I + 1)
             lo_local = max(n_init, I - prm.n_local_blocks + 1)
@@ -295,7 +300,7 @@ def select_blocks_shared(q, ck, prm, want_scores=False):
             for j in cand:
                 total = 0.0
                 for t in toks:
-                    total += R[h, t, j]
+                    total += R[t][j]
                 score[j] = total / len(toks)
                 Rq[h, I, j] = score[j]
             for j in forced:

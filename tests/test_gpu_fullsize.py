@@ -362,3 +362,45 @@ def test_verify_and_backward_graph_replays_match_eager():
         for a, b_ in zip(got[1:], eager[1:]):             # dk, dv: fp32 atomics, then one bf16 rounding
             diff = (a.float() - b_.float()).abs()
             assert bool((diff <= 2.0 ** -7 * b_.float().abs() + 1e-6).all()), r
+
+
+@pytest.mark.timeout(600)
+def test_shared_variant_32k_sampled_query_blocks():
+    # the query-block-shared comparison variant at the benchmark's size: sampled query blocks against
+    # the oracle (selection and, in isolation, attention), properties on every row
+    cfg = synth.CONFIGS[1]
+    print("workload", cfg.name, "shared variant", flush=True)
+    x = synth.make_prefill(cfg)
+    l, Hq, Hkv, m = cfg.seqlen, cfg.n_q_heads, cfg.n_kv_heads, cfg.block_size
+    prm = binding.Params(Hq, Hkv, topk=cfg.topk)
+    oprm = oracle_params(prm)
+    q, k, v = to_dev(x.q)[None], to_dev(x.k)[None], to_dev(x.v)[None]
+    sl = torch.tensor([l], dtype=torch.int32, device="cuda")
+    ck = binding.compress_keys(prm, k, sl, l)
+    idx = binding.select_blocks_shared(prm, q, ck, sl, l)
+    out, lse = binding.sparse_attn_prefill_shared(prm, q, k, v, sl, l, idx)
+    torch.cuda.synchronize()
+    n_qb = l // m
+    ii = idx[0]
+    own = torch.arange(n_qb, device="cuda")[None, :, None]
+    valid = ii >= 0
+    assert torch.equal(valid.sum(-1), torch.minimum(own[..., 0] + 1, torch.tensor(cfg.topk, device="cuda")).expand(Hkv, n_qb))
+    assert bool(((ii <= own) | ~valid).all()) and bool((ii[..., 0] == 0).all())
+    assert bool(((ii == own) & valid).any(-1).all())
+    assert bool(torch.isfinite(lse).all()) and bool(torch.isfinite(out.float()).all())
+    rng = np.random.default_rng(99)
+    qbs = sorted(set([0, 1, 2, 3, n_qb - 1] + [int(t) for t in rng.integers(4, n_qb, 9)]))
+    _, ck_ref = ref.compress_keys(x.k, oprm)
+    want, margins, Rq = ref.select_blocks_shared(x.q, ck_ref, oprm, want_scores=True, qblocks=qbs)
+    got = ii.cpu().numpy()
+    n, e, nt, hard = compare_selection(got[:, qbs], want[:, qbs], margins[:, qbs], Rq[:, qbs])
+    print("shared selection: %d rows, %d exact, %d near-tie" % (n, e, nt), flush=True)
+    assert not hard, hard[:3]
+    rows = np.concatenate([np.arange(I * m, (I + 1) * m, dtype=np.int32) for I in qbs])
+    per_token = np.repeat(got[:, qbs], m, axis=1)
+    wo, wl = ref.sparse_attn(np.ascontiguousarray(x.q[rows]), x.k, x.v, rows, per_token, oprm)
+    ri = torch.from_numpy(rows).long().cuda()
+    eo = np.abs(out[0, ri].double().cpu().numpy() - wo).max()
+    el = lse_err(lse[0, ri].double().cpu().numpy(), wl)
+    print("shared attention: max|dO| %.3e LSE err/tol %.3f" % (eo, el), flush=True)
+    assert eo <= OUT_TOL and el <= 1.0

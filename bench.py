@@ -178,6 +178,46 @@ def bench_prefill(args):
         "kernels_ms": kern_ms, "attended_flops": attended_flops, "scoring_flops_per_pass": score_flops,
         "attn_only_tflops": attended_flops / (kern_ms["attn_prefill_kernel"] * 1e-3) / 1e12,
     }
+    if not args.no_shared:
+        # comparison variant, NOT the report's method: one block set per 64-token query block
+        ws_s = torch.empty(binding.workspace_bytes(binding.OP_SELECT_SHARED, prm, 1, l), dtype=torch.uint8, device="cuda")
+        idx_s = torch.full((1, Hkv, (l + m - 1) // m, cfg.topk), -1, dtype=torch.int32, device="cuda")
+        out_s, lse_s = torch.zeros_like(q), torch.zeros_like(lse)
+
+        def step_shared():
+            binding.compress_keys(prm, k, sl, l, ck=ck)
+            binding.select_blocks_shared(prm, q, ck, sl, l, block_idx=idx_s, workspace=ws_s)
+            binding.sparse_attn_prefill_shared(prm, q, k, v, sl, l, idx_s, out=out_s, lse=lse_s)
+
+        for _ in range(max(1, args.warmup)):
+            step_shared()
+        torch.cuda.synchronize()
+        binding.timing_enable(True)
+        n_s = max(1, min(args.steps, 10))
+        t0 = time.perf_counter()
+        for _ in range(n_s):
+            step_shared()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        per_s = {}
+        for name, ms in binding.timing_read():
+            per_s.setdefault(name, []).append(ms)
+        binding.timing_enable(False)
+        ms_s = (t1 - t0) * 1e3 / n_s
+        ii = idx_s[0]
+        own_b = torch.arange(ii.shape[1], device="cuda")[None, :, None]
+        full = ((ii >= 0) & (ii < own_b)).sum().item()
+        tail = l - (l // m) * m
+        own_pairs = (l // m) * (m * (m + 1) // 2) + tail * (tail + 1) // 2
+        fl_s = (full * m * m + Hkv * own_pairs) * (Hq // Hkv) * 4 * d
+        ta = float(np.mean(per_s["attn_prefill_shared_kernel"]))
+        res["shared_variant"] = {"note": "comparison only, not the report's method (section 2.1.3 argues for token-level "
+                                         "queries): the 64 tokens of a query block share one block set",
+                                 "ms_per_step": ms_s, "attended_flops": fl_s, "tflops": fl_s / (ms_s * 1e-3) / 1e12,
+                                 "attn_only_tflops": fl_s / (ta * 1e-3) / 1e12,
+                                 "frac_bf16_peak_attn_only": fl_s / (ta * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                                 "kernels_ms": {n: float(np.mean(v_)) for n, v_ in per_s.items()}}
+        del ws_s, idx_s, out_s, lse_s
     if not args.no_backward:
         # backward of the attention (training): gradients to q, k, v for a random upstream gradient
         gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
@@ -491,6 +531,7 @@ def main():
     ap.add_argument("--verify-steps", type=int, default=50)
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-backward", action="store_true")
+    ap.add_argument("--no-shared", action="store_true", help="skip the query-block-shared comparison variant")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=32768)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -541,6 +582,8 @@ def main():
     }
     if "backward" in res:
         line["backward"] = res["backward"]
+    if "shared_variant" in res:
+        line["shared_variant"] = res["shared_variant"]
     mp = measured_peaks()
     line["measured_peaks"] = mp
     rf = line["roofline"]

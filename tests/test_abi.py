@@ -173,6 +173,19 @@ def test_decode_step_validation(lib):
     assert lib.infllmv2_decode_step(P, T, T, T, T, T, T, FAKE, 0, 4096, FAKE, T, FAKE, FAKE, 1 << 40, None) == 0
 
 
+def test_shared_variant_validation(lib):
+    prm, t = good_params(), tensor()
+    P, T = ctypes.byref(prm), ctypes.byref(t)
+    need = lib.infllmv2_workspace_bytes(binding.OP_SELECT_SHARED, P, 1, 4096)
+    # the per-token selection's scratch plus fp32 scores of 64 query blocks x 64 blocks x 2 kv heads
+    assert need == lib.infllmv2_workspace_bytes(binding.OP_SELECT_PREFILL, P, 1, 4096) + 2 * 64 * 64 * 4
+    sel = lambda w=FAKE, wb=1 << 40, idx=FAKE: lib.infllmv2_select_blocks_shared(P, T, T, FAKE, 1, 4096, idx, w, wb, None)
+    assert sel(idx=None) == INVALID and sel(w=None, wb=0) == WORKSPACE and sel(wb=need - 1) == WORKSPACE
+    att = lambda w=FAKE, wb=1 << 40, idx=FAKE: lib.infllmv2_sparse_attn_prefill_shared(
+        P, T, T, T, FAKE, 1, 4096, idx, T, FAKE, w, wb, None)
+    assert att(idx=None) == INVALID and att(w=None, wb=0) == WORKSPACE
+
+
 def test_binding_fails_loudly_without_library(tmp_path):
     with pytest.raises(binding.InfLLMv2Error):
         binding.load_library(str(tmp_path / "missing.so"))

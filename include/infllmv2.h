@@ -10,8 +10,12 @@
  *                                   the always-selected initial and local-window blocks
  *   3. infllmv2_sparse_attn_prefill / infllmv2_sparse_attn_decode
  *                                   exact softmax attention over the selected blocks only
- * plus infllmv2_append_kv, the cache append that opens a decode step, and the *_verify
- * variants of the decode step for the n drafted tokens of speculative decoding (section 4.1).
+ * plus infllmv2_append_kv, the cache append that opens a decode step, and infllmv2_decode_step, the
+ * whole decode step in one call.  Built on top of the path: the approximate log-sum-exp of stage 2
+ * (infllmv2_params.lse_coarse_ratio), infllmv2_sparse_attn_bwd (the gradients of stage 3), the
+ * *_verify variants of the decode step for the n drafted tokens of speculative decoding (section
+ * 4.1), and, as a labelled comparison that is NOT the report's method, the *_shared variants with
+ * one block set per query block.
  *
  * Conventions for every entry point
  *   - Returns 0 (INFLLMV2_OK) or a negative INFLLMV2_ERR_* code; never throws, never
@@ -152,36 +156,6 @@ int32_t infllmv2_select_blocks(const infllmv2_params *prm, int32_t mode, const i
                                const infllmv2_tensor *ck, const int32_t *seqlens, int32_t batch,
                                int32_t max_seqlen, int32_t *block_idx, void *workspace,
                                size_t workspace_bytes, void *stream);
-
-/*
- * Query-block-shared selection -- a COMPARISON VARIANT, not the report's method (section 2.1.3 argues
- * for token-level queries; infllmv2_select_blocks is the method).  The m = 64 tokens of query block I
- * attend one common block set: block j is scored by the mean over the tokens of I of their per-token
- * block relevance R[j] (as in infllmv2_select_blocks), the first n_init_blocks blocks and the last
- * n_local_blocks blocks up to I are forced, the min(topk, I+1) best are taken, ties to the lower index.
- *   q          [batch, max_seqlen, Hq, d]
- *   block_idx  out  int32 [batch, Hkv, ceil(max_seqlen/64), topk], ascending, padded with -1; rows of
- *              query blocks that start at or after seqlens[b] are not written
- *   workspace  infllmv2_workspace_bytes(INFLLMV2_OP_SELECT_SHARED, ...) bytes
- */
-int32_t infllmv2_select_blocks_shared(const infllmv2_params *prm, const infllmv2_tensor *q,
-                                      const infllmv2_tensor *ck, const int32_t *seqlens, int32_t batch,
-                                      int32_t max_seqlen, int32_t *block_idx, void *workspace,
-                                      size_t workspace_bytes, void *stream);
-
-/*
- * The attention for block sets shared by the 64 tokens of a query block (the same COMPARISON VARIANT):
- * out and lse as infllmv2_sparse_attn_prefill computes them when every token of query block I is given
- * row I of block_idx.
- *   block_idx  in   int32 [batch, Hkv, ceil(max_seqlen/64), topk]; entries < 0 or > I are skipped; each
- *              row must be duplicate-free
- *   workspace  infllmv2_workspace_bytes(INFLLMV2_OP_ATTN_PREFILL, ...) bytes
- */
-int32_t infllmv2_sparse_attn_prefill_shared(const infllmv2_params *prm, const infllmv2_tensor *q,
-                                            const infllmv2_tensor *k, const infllmv2_tensor *v,
-                                            const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
-                                            const int32_t *block_idx, const infllmv2_tensor *out, float *lse,
-                                            void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Stage 3, prefill -- attention over the selected blocks (section 2.1.1, second stage):
@@ -330,6 +304,36 @@ int32_t infllmv2_sparse_attn_verify(const infllmv2_params *prm, const infllmv2_t
                                     int32_t n_draft, const uint64_t *tree_mask, const int32_t *block_idx,
                                     const infllmv2_tensor *out, float *lse, void *workspace,
                                     size_t workspace_bytes, void *stream);
+
+/*
+ * Query-block-shared selection -- a COMPARISON VARIANT, not the report's method (section 2.1.3 argues
+ * for token-level queries; infllmv2_select_blocks is the method).  The m = 64 tokens of query block I
+ * attend one common block set: block j is scored by the mean over the tokens of I of their per-token
+ * block relevance R[j] (as in infllmv2_select_blocks), the first n_init_blocks blocks and the last
+ * n_local_blocks blocks up to I are forced, the min(topk, I+1) best are taken, ties to the lower index.
+ *   q          [batch, max_seqlen, Hq, d]
+ *   block_idx  out  int32 [batch, Hkv, ceil(max_seqlen/64), topk], ascending, padded with -1; rows of
+ *              query blocks that start at or after seqlens[b] are not written
+ *   workspace  infllmv2_workspace_bytes(INFLLMV2_OP_SELECT_SHARED, ...) bytes
+ */
+int32_t infllmv2_select_blocks_shared(const infllmv2_params *prm, const infllmv2_tensor *q,
+                                      const infllmv2_tensor *ck, const int32_t *seqlens, int32_t batch,
+                                      int32_t max_seqlen, int32_t *block_idx, void *workspace,
+                                      size_t workspace_bytes, void *stream);
+
+/*
+ * The attention for block sets shared by the 64 tokens of a query block (the same COMPARISON VARIANT):
+ * out and lse as infllmv2_sparse_attn_prefill computes them when every token of query block I is given
+ * row I of block_idx.
+ *   block_idx  in   int32 [batch, Hkv, ceil(max_seqlen/64), topk]; entries < 0 or > I are skipped; each
+ *              row must be duplicate-free
+ *   workspace  infllmv2_workspace_bytes(INFLLMV2_OP_ATTN_PREFILL, ...) bytes
+ */
+int32_t infllmv2_sparse_attn_prefill_shared(const infllmv2_params *prm, const infllmv2_tensor *q,
+                                            const infllmv2_tensor *k, const infllmv2_tensor *v,
+                                            const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
+                                            const int32_t *block_idx, const infllmv2_tensor *out, float *lse,
+                                            void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Measured practical peaks for the benchmark's rooflines (not part of the method).  Launches two

@@ -7,7 +7,7 @@ import torch
 
 from oracle import ref
 from paper_2506_07900_amd import binding, synth
-from util import grad_err, OUT_TOL, compare_selection, lse_err, oracle_params, to_bits, to_dev
+from util import grad_err, out_err, OUT_TOL, compare_selection, lse_err, oracle_params, to_bits, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -596,3 +596,119 @@ def test_sparse_attn_prefill_shared(seqlens, Hq, Hkv, topk, planted):
         print("seq %d len %d: max|dO| %.3e LSE err/tol %.3f" % (b, l, eo, el), flush=True)
         assert eo <= OUT_TOL and el <= 1.0
         assert bool((out[b, l:] == 0).all())
+
+
+# ------------------------------------------------------------------ seeded random configurations, every entry point
+
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_random_configurations_all_entry_points(seed):
+    rng = np.random.default_rng(1000 + seed)
+    G = int(rng.choice([1, 2, 4, 8, 16]))
+    Hkv = int(rng.choice([1, 2, 3]))
+    Hq = G * Hkv
+    n_init, n_local = int(rng.integers(0, 3)), int(rng.integers(0, 4))
+    topk = int(rng.integers(max(1, n_init + n_local), 20))
+    B = int(rng.integers(1, 4))
+    seqlens = [int(rng.integers(1, 900)) for _ in range(B)]
+    if seed % 3 == 0:
+        seqlens[0] = int(rng.choice([31, 32, 63, 64, 65, 128, 129]))
+    rho = 1
+    if G == 16 and (n_init + n_local) * 64 >= 128 and seed % 2:
+        rho = int(rng.choice([2, 4])) if (n_init + n_local) * 64 >= 8 * 16 else 2
+    print("case random", seed, dict(G=G, Hkv=Hkv, topk=topk, n_init=n_init, n_local=n_local, seqlens=seqlens, rho=rho), flush=True)
+    prm = binding.Params(Hq, Hkv, topk=topk, n_init_blocks=n_init, n_local_blocks=n_local, lse_coarse_ratio=rho)
+    oprm = oracle_params(prm)
+    q, k, v, T = make_batch(200 + seed, seqlens, Hq, Hkv, n_planted=int(rng.integers(0, 4)), heavy=(0,) if seed % 4 == 0 else ())
+    qd, kd, vd, sl = to_dev(q), to_dev(k), to_dev(v), dev_i32(seqlens)
+    # prefill: compress, select, attend
+    ck = binding.compress_keys(prm, kd, sl, T)
+    idx = binding.select_blocks(prm, binding.MODE_PREFILL, qd, ck, sl, T)
+    torch.cuda.synchronize()
+    ckb, idx_np = to_bits(ck), idx.cpu().numpy()
+    idx_ref = np.full((B, Hkv, T, topk), -1, np.int32)
+    near = 0
+    for b, l in enumerate(seqlens):
+        _, ck_ref = ref.compress_keys(k[b, :, :l], oprm)
+        assert np.array_equal(ckb[b, :, :ck_ref.shape[1]], ck_ref)
+        want, margins, R = ref.select_blocks(q[b, :l], ck_ref, np.arange(l, dtype=np.int32), oprm, want_scores=True)
+        n, e, nt, hard = compare_selection(idx_np[b, :, :l], want, margins, R)
+        assert not hard, hard[:3]
+        near += nt
+        idx_ref[b, :, :l] = want
+    assert near <= 3
+    idx_d = torch.from_numpy(idx_ref).cuda()
+    out, lse = binding.sparse_attn_prefill(prm, qd, kd, vd, sl, T, idx_d)
+    do = synth.f32_to_bf16_bits(rng.standard_normal((B, T, Hq, 128), dtype=np.float32))
+    dq, dk, dv = binding.sparse_attn_bwd(prm, qd, kd, vd, out, to_dev(do), lse, sl, T, idx_d)
+    torch.cuda.synchronize()
+    for b, l in enumerate(seqlens):
+        pos = np.arange(l, dtype=np.int32)
+        wo, wl = ref.sparse_attn(q[b, :l], k[b, :, :l], v[b, :, :l], pos, idx_ref[b, :, :l], oprm)
+        assert out_err(out[b, :l].double().cpu().numpy(), wo) <= 1.0
+        assert lse_err(lse[b, :l].double().cpu().numpy(), wl) <= 1.0
+        wq, wk, wv, mq, mk, mv = ref.sparse_attn_bwd(q[b, :l], k[b, :, :l], v[b, :, :l], do[b, :l], pos, idx_ref[b, :, :l],
+                                                     oprm, want_mag=True)
+        assert grad_err(dq[b, :l].double().cpu().numpy(), wq, mq) <= 1.0
+        assert grad_err(dk[b, :, :l].double().cpu().numpy(), wk, mk) <= 1.0
+        assert grad_err(dv[b, :, :l].double().cpu().numpy(), wv, mv) <= 1.0
+    # one decode step in one call: the last token of every sequence taken out of the cache and appended again
+    last = np.array([l - 1 for l in seqlens])
+    kn = np.stack([k[b, :, last[b]] for b in range(B)])[:, :, None]
+    vn = np.stack([v[b, :, last[b]] for b in range(B)])[:, :, None]
+    q1 = np.stack([q[b, last[b]] for b in range(B)])[:, None]
+    k0, v0 = k.copy(), v.copy()
+    for b in range(B):
+        k0[b, :, last[b]] = 0
+        v0[b, :, last[b]] = 0
+    kc, vc = to_dev(k0), to_dev(v0)
+    ck1 = binding.compress_keys(prm, kc, dev_i32([l - 1 for l in seqlens]), T)
+    i1, o1, l1 = binding.decode_step(prm, to_dev(q1), to_dev(kn), to_dev(vn), kc, vc, ck1, sl, T)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(kc), k) and np.array_equal(to_bits(vc), v)
+    i1 = i1.cpu().numpy()
+    for b, l in enumerate(seqlens):
+        pos = np.array([l - 1], np.int32)
+        _, ck_ref = ref.compress_keys(k[b, :, :l], oprm)
+        assert np.array_equal(to_bits(ck1)[b, :, :ck_ref.shape[1]], ck_ref)
+        want, margins, R = ref.select_blocks(q1[b], ck_ref, pos, oprm, want_scores=True)
+        n, e, nt, hard = compare_selection(i1[b], want, margins, R)
+        assert not hard, (b, hard)
+        wo, wl = ref.sparse_attn(q1[b], k[b, :, :l], v[b, :, :l], pos, i1[b], oprm)
+        assert out_err(o1[b].double().cpu().numpy(), wo) <= 1.0
+        assert lse_err(l1[b].double().cpu().numpy(), wl[0]) <= 1.0
+    # verification of the last n tokens with a random tree, and the query-block-shared comparison variant
+    n = int(rng.integers(1, 9))
+    qn = np.zeros((B, n, Hq, 128), np.uint16)
+    masks = np.zeros((B, n), np.uint64)
+    for b, l in enumerate(seqlens):
+        masks[b] = tree_masks(rng, n, "tree")
+        if l >= n:
+            qn[b] = q[b, l - n:l]
+    iv = binding.select_blocks_verify(prm, to_dev(qn), ck, sl, T)
+    ov, lv = binding.sparse_attn_verify(prm, to_dev(qn), kd, vd, sl, T, iv, tree_mask=dev_masks(masks))
+    torch.cuda.synchronize()
+    iv = iv.cpu().numpy()
+    for b, l in enumerate(seqlens):
+        if l < n:
+            assert np.all(iv[b] == -1)
+            continue
+        pos = np.arange(l - n, l, dtype=np.int32)
+        want, margins, R = ref.select_blocks(qn[b], ckb[b, :, :ref.num_kernels(l, 32, 16)], pos, oprm, want_scores=True)
+        nn, e, nt, hard = compare_selection(iv[b], want, margins, R)
+        assert not hard, (b, hard)
+        wo, wl = ref.sparse_attn_tree(qn[b], k[b, :, :l], v[b, :, :l], iv[b], masks[b], l - n, oprm)
+        assert out_err(ov[b].double().cpu().numpy(), wo) <= 1.0
+        assert lse_err(lv[b].double().cpu().numpy(), wl) <= 1.0
+    if rho == 1:
+        isd = binding.select_blocks_shared(prm, qd, ck, sl, T)
+        osd, lsd = binding.sparse_attn_prefill_shared(prm, qd, kd, vd, sl, T, isd)
+        torch.cuda.synchronize()
+        isd = isd.cpu().numpy()
+        for b, l in enumerate(seqlens):
+            want, margins, Rq = ref.select_blocks_shared(q[b, :l], ckb[b, :, :ref.num_kernels(l, 32, 16)], oprm, want_scores=True)
+            nn, e, nt, hard = compare_selection(isd[b, :, :want.shape[1]], want, margins, Rq)
+            assert not hard, (b, hard)
+            per_token = np.repeat(isd[b, :, :want.shape[1]], 64, axis=1)[:, :l]
+            wo, wl = ref.sparse_attn(q[b, :l], k[b, :, :l], v[b, :, :l], np.arange(l, dtype=np.int32), per_token, oprm)
+            assert out_err(osd[b, :l].double().cpu().numpy(), wo) <= 1.0
+            assert lse_err(lsd[b, :l].double().cpu().numpy(), wl) <= 1.0

@@ -33,6 +33,17 @@ def grad_err(got, want, mag):
     return float(np.max(np.abs(got - want) / tol))
 
 
+def out_err(got, want):
+    """Largest output error in units of its tolerance (<= 1 passes): the stated 2e-2 absolute, widened
+    to 2^-7 * |want| where bf16 cannot hold 2e-2 (an output of magnitude 4 or more has an ulp of 2^-5;
+    heavy-tailed keys make the attention one-hot, so an output is a single value row and a |v| > 4 from
+    the tail of N(0,1) comes through undiluted; two roundings, of the probability and of the result)."""
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    tol = np.maximum(OUT_TOL, 2.0 ** -7 * np.abs(want))
+    return float(np.max(np.abs(got - want) / tol)) if want.size else 0.0
+
+
 def lse_err(got, want):
     """Largest log-sum-exp error in units of its tolerance (<= 1 passes).  The tolerance is the
     stated 1e-5 absolute, widened to 2^-20 * |LSE| (16 fp32 ulps) where |LSE| is so large that

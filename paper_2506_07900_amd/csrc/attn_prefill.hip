@@ -465,19 +465,18 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_shared_kernel(Dims dm, Te
         const u32x4 *sb = stage[cur] + lane;
 #pragma unroll
         for (int hs = 0; hs < 2; ++hs) {
+            // four independent accumulation chains (2 key tiles x 2 tokens) interleaved k-step by k-step: a
+            // dependent MFMA then issues three MFMAs after the one it waits for, which covers its latency
             f32x4 s[kShTok][2];
 #pragma unroll
-            for (int rr = 0; rr < 2; ++rr) {
-                const int mt = 2 * hs + rr;
-                u32x4 kf[4];
+            for (int u = 0; u < kShTok; ++u) s[u][0] = s[u][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) kf[ks] = sb[(ks * 4 + mt) * 64];
+            for (int ks = 0; ks < 4; ++ks) {
+                const u32x4 k0 = sb[(ks * 4 + 2 * hs) * 64], k1 = sb[(ks * 4 + 2 * hs + 1) * 64];
 #pragma unroll
                 for (int u = 0; u < kShTok; ++u) {
-                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int ks = 0; ks < 4; ++ks) acc = mfma16(__builtin_bit_cast(bf16x8, kf[ks]), qf[u][ks], acc);
-                    s[u][rr] = acc;
+                    s[u][0] = mfma16(__builtin_bit_cast(bf16x8, k0), qf[u][ks], s[u][0]);
+                    s[u][1] = mfma16(__builtin_bit_cast(bf16x8, k1), qf[u][ks], s[u][1]);
                 }
             }
             bf16x8 pf[kShTok];

@@ -600,22 +600,23 @@ def test_sparse_attn_prefill_shared(seqlens, Hq, Hkv, topk, planted):
 
 # ------------------------------------------------------------------ seeded random configurations, every entry point
 
-@pytest.mark.parametrize("seed", list(range(24)))
-def test_random_configurations_all_entry_points(seed):
-    rng = np.random.default_rng(1000 + seed)
+@pytest.mark.parametrize("seed,wide", [(s, False) for s in range(24)] + [(s, True) for s in range(6)])
+def test_random_configurations_all_entry_points(seed, wide):
+    # wide: the limits of the interface (top-k up to 64, up to 64 drafted tokens) and longer sequences
+    rng = np.random.default_rng((5000 if wide else 1000) + seed)
     G = int(rng.choice([1, 2, 4, 8, 16]))
     Hkv = int(rng.choice([1, 2, 3]))
     Hq = G * Hkv
-    n_init, n_local = int(rng.integers(0, 3)), int(rng.integers(0, 4))
-    topk = int(rng.integers(max(1, n_init + n_local), 20))
-    B = int(rng.integers(1, 4))
-    seqlens = [int(rng.integers(1, 900)) for _ in range(B)]
+    n_init, n_local = int(rng.integers(0, 5 if wide else 3)), int(rng.integers(0, 6 if wide else 4))
+    topk = int(rng.integers(max(1, n_init + n_local), 65 if wide else 20))
+    B = int(rng.integers(1, 6 if wide else 4))
+    seqlens = [int(rng.integers(1, 2600 if wide else 900)) for _ in range(B)]
     if seed % 3 == 0:
         seqlens[0] = int(rng.choice([31, 32, 63, 64, 65, 128, 129]))
     rho = 1
     if G == 16 and (n_init + n_local) * 64 >= 128 and seed % 2:
         rho = int(rng.choice([2, 4])) if (n_init + n_local) * 64 >= 8 * 16 else 2
-    print("case random", seed, dict(G=G, Hkv=Hkv, topk=topk, n_init=n_init, n_local=n_local, seqlens=seqlens, rho=rho), flush=True)
+    print("case random", seed, wide, dict(G=G, Hkv=Hkv, topk=topk, n_init=n_init, n_local=n_local, seqlens=seqlens, rho=rho), flush=True)
     prm = binding.Params(Hq, Hkv, topk=topk, n_init_blocks=n_init, n_local_blocks=n_local, lse_coarse_ratio=rho)
     oprm = oracle_params(prm)
     q, k, v, T = make_batch(200 + seed, seqlens, Hq, Hkv, n_planted=int(rng.integers(0, 4)), heavy=(0,) if seed % 4 == 0 else ())
@@ -677,7 +678,7 @@ def test_random_configurations_all_entry_points(seed):
         assert out_err(o1[b].double().cpu().numpy(), wo) <= 1.0
         assert lse_err(l1[b].double().cpu().numpy(), wl[0]) <= 1.0
     # verification of the last n tokens with a random tree, and the query-block-shared comparison variant
-    n = int(rng.integers(1, 9))
+    n = int(rng.integers(1, 65 if wide else 9))
     qn = np.zeros((B, n, Hq, 128), np.uint16)
     masks = np.zeros((B, n), np.uint64)
     for b, l in enumerate(seqlens):

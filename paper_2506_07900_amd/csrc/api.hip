@@ -310,11 +310,8 @@ int32_t infllmv2_decode_step(const infllmv2_params *prm, const infllmv2_tensor *
         return INFLLMV2_ERR_WORKSPACE;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const AppendArgs ap = {make_tensor(k_new), make_tensor(v_new), make_tensor(k), make_tensor(v)};
-    RETURN_IF_ERR(hip_status(launch_select_decode(dm, make_tensor(q), make_tensor(ck), seqlens, block_idx,
-                                                  workspace, st, &ap)));
-    return hip_status(launch_attn_decode(dm, make_tensor(q), make_tensor(k), make_tensor(v), seqlens, block_idx,
-                                         nullptr, make_tensor(out), lse, reinterpret_cast<char *>(workspace) + sel,
-                                         st));
+    return hip_status(launch_decode_step(dm, make_tensor(q), make_tensor(ck), ap, seqlens, block_idx, make_tensor(out),
+                                         lse, workspace, reinterpret_cast<char *>(workspace) + sel, st));
 }
 
 int32_t infllmv2_select_blocks(const infllmv2_params *prm, int32_t mode, const infllmv2_tensor *q,

@@ -41,6 +41,11 @@ struct Tensor {          // strides in elements
 struct AppendArgs {      // the cache append folded into the first kernel of a fused decode step
     Tensor k_new, v_new, k, v;
 };
+struct AttendArgs {      // the per-block attention folded into the top-k kernel of a fused decode step
+    Tensor k, v;
+    float *o_part;
+    float2 *ml_part;
+};
 
 // Number of complete semantic kernels of a sequence of l tokens (p=32, s=16).
 __host__ __device__ inline int32_t num_kernels(int32_t l) {
@@ -103,18 +108,28 @@ __device__ inline float xgroup_sum(float v) {
 // key << 32 | ~block: larger word = better element, ties go to the lower block index.
 constexpr uint64_t kPickValid = 1ull << 32;               // smallest word of a real candidate
 
-// number of words in w[0..n) (n a multiple of 4, 16-byte aligned) that are larger than x
+// number of words in w[0..n) (n a multiple of 4, 16-byte aligned) that are larger than x; sixteen
+// words per step, all loaded before any is compared (a step costs one LDS latency, not eight)
 __device__ inline int count_larger(const uint64_t *w, int n, uint64_t x) {
-    int c0 = 0, c1 = 0, c2 = 0, c3 = 0;
-    for (int j = 0; j < n; j += 4) {
+    int c0 = 0, c1 = 0;
+    int j = 0;
+    for (; j + 16 <= n; j += 16) {
+        ulonglong2 a[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a[i] = *reinterpret_cast<const ulonglong2 *>(w + j + 2 * i);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            c0 += a[i].x > x ? 1 : 0;
+            c1 += a[i].y > x ? 1 : 0;
+        }
+    }
+    for (; j < n; j += 4) {
         const ulonglong2 a = *reinterpret_cast<const ulonglong2 *>(w + j);
         const ulonglong2 bq = *reinterpret_cast<const ulonglong2 *>(w + j + 2);
-        c0 += a.x > x ? 1 : 0;
-        c1 += a.y > x ? 1 : 0;
-        c2 += bq.x > x ? 1 : 0;
-        c3 += bq.y > x ? 1 : 0;
+        c0 += (a.x > x ? 1 : 0) + (bq.x > x ? 1 : 0);
+        c1 += (a.y > x ? 1 : 0) + (bq.y > x ? 1 : 0);
     }
-    return (c0 + c1) + (c2 + c3);
+    return c0 + c1;
 }
 
 // Optional per-kernel timing (infllmv2_timing_enable): when on, every launch is bracketed by HIP
@@ -139,7 +154,11 @@ size_t select_shared_scores_bytes(const Dims &dm);
 int launch_select_pick(const Dims &dm, const int32_t *seqlens, const float *R, int32_t nb_cap,
                        int32_t *block_idx, hipStream_t stream);
 int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
-                         int32_t *block_idx, void *ws, hipStream_t stream, const AppendArgs *append = nullptr);
+                         int32_t *block_idx, void *ws, hipStream_t stream, const AppendArgs *append = nullptr,
+                         const AttendArgs *attend = nullptr);
+int launch_decode_step(const Dims &dm, Tensor q, Tensor ck, const AppendArgs &append, const int32_t *seqlens,
+                       int32_t *block_idx, Tensor out, float *lse, void *ws_select, void *ws_attn,
+                       hipStream_t stream);
 size_t select_decode_ws_bytes(const Dims &dm);
 int launch_attn_prefill(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32_t *seqlens,
                         const int32_t *block_idx, Tensor out, float *lse, void *ws, hipStream_t stream);

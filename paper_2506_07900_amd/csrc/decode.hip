@@ -524,20 +524,108 @@ __global__ __launch_bounds__(320) void decode_scores_z_kernel(Dims dm, const int
 //   1a. rank of `best` inside its wavefront; the n_pick best of each wavefront survive
 //   1b. rank of the survivors among all survivors = rank among all thread maxima; gives tau
 //   2.  the n_pick best threads publish their elements >= tau; rank by counting among those
-constexpr int kPickThreads = 256, kPickWaves = kPickThreads / 64, kPickMaxVPT = 16;
+constexpr int kPickThreads = 256, kPickMaxVPT = 16;
 constexpr int kPickMaxCand = kMaxTopk * kPickMaxVPT;
+template <int kThreads>
+struct PickShared {
+    uint64_t tmax[kThreads];
+    uint64_t surv[kThreads / 64 * kMaxTopk];
+    uint64_t cand[kPickMaxCand];
+    uint64_t tau;
+    int n_cand;
+    int picked[kMaxTopk];
+};
+
+// Top-k of one row of block scores for a query at cache row L - 1 (L >= 1), by a whole workgroup of
+// kThreads threads; thread t passes the scores of blocks t, t + kThreads, ... in r.  The selected
+// blocks, ascending, go to `o` (a row of the block_idx output, padded with -1; may be null) and to
+// `sel` (LDS, may be null).  Returns their number.  Contains barriers: every thread calls it.
+template <int kThreads, int kVPT>
+__device__ inline int pick_row(const Dims &dm, int L, const float (&r)[kVPT], PickShared<kThreads> &sh,
+                               int32_t *__restrict__ o, int *sel) {
+    constexpr int kWaves = kThreads / 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b_own = (L - 1) / kBlock, n_blk = b_own + 1;
+    const int n_sel = dm.topk < n_blk ? dm.topk : n_blk;
+    const int n_init = dm.n_init < n_blk ? dm.n_init : n_blk;                 // forced leading blocks
+    const int lo_local = max(n_init, b_own - dm.n_local + 1);                 // forced trailing: lo_local..b_own
+    const int jc_max = lo_local - 1;                                          // candidates: n_init..jc_max
+    const int n_pick = n_sel - (n_init + (b_own - lo_local + 1));
+    if (n_pick > 0) {                                                         // uniform over the workgroup
+        const int n_surv = (kWaves * n_pick + 3) & ~3;
+        const int cand_cap = n_pick * kVPT;
+        for (int i = tid; i < n_surv; i += kThreads) sh.surv[i] = 0ull;
+        for (int i = tid; i < cand_cap + 4; i += kThreads)
+            if (i < kPickMaxCand) sh.cand[i] = 0ull;
+        if (tid == 0) {
+            sh.tau = kPickValid;
+            sh.n_cand = 0;
+        }
+        uint64_t el[kVPT], best = 0ull;
+#pragma unroll
+        for (int s = 0; s < kVPT; ++s) {
+            const int j = tid + kThreads * s;
+            const uint32_t kj = r[s] == -INFINITY ? 1u : __float_as_uint(r[s]);
+            const uint32_t key = (j >= n_init && j <= jc_max) ? kj : 0u;
+            el[s] = ((uint64_t)key << 32) | (uint32_t)~j;
+            best = el[s] > best ? el[s] : best;
+        }
+        const bool real = best >= kPickValid;
+        sh.tmax[tid] = best;
+        __syncthreads();
+        // 1a. rank inside the wavefront
+        const int wrank = count_larger(sh.tmax + 64 * wave, 64, best);
+        const bool survivor = real && wrank < n_pick;
+        if (survivor) sh.surv[wave * n_pick + wrank] = best;
+        __syncthreads();
+        // 1b. rank among all thread maxima (a thread that did not survive has n_pick better ones)
+        int trank = n_pick;
+        if (survivor) trank = count_larger(sh.surv, n_surv, best);
+        if (trank == n_pick - 1) sh.tau = best;
+        __syncthreads();
+        // 2. publish the elements that can still make it, then rank them by counting
+        if (trank < n_pick) {
+            const uint64_t tau = sh.tau;
+#pragma unroll
+            for (int s = 0; s < kVPT; ++s)
+                if (el[s] >= tau) sh.cand[atomicAdd(&sh.n_cand, 1)] = el[s];
+        }
+        __syncthreads();
+        const int n_cand = sh.n_cand;                                         // n_pick <= n_cand <= cand_cap
+        for (int i = tid; i < n_cand; i += kThreads) {
+            const uint64_t e = sh.cand[i];
+            const int beaten = count_larger(sh.cand, (n_cand + 3) & ~3, e);
+            if (beaten < n_pick) sh.picked[beaten] = (int)~(uint32_t)e;
+        }
+        __syncthreads();
+    }
+    if (wave == 0) {
+        int mine = 0x7fffffff;
+        if (lane < n_pick) mine = sh.picked[lane];
+        else if (lane < n_sel) {
+            const int f = lane - n_pick;
+            mine = f < n_init ? f : lo_local + (f - n_init);
+        }
+        // ascending order: rank = number of selected blocks below mine
+        int rank = 0;
+        for (int e = 0; e < n_sel; ++e) rank += __builtin_amdgcn_readlane(mine, e) < mine ? 1 : 0;
+        if (lane < n_sel) {
+            if (o) o[rank] = mine;
+            if (sel) sel[rank] = mine;
+        } else if (o && lane < dm.topk) {
+            o[lane] = -1;
+        }
+    }
+    return n_sel;
+}
+
 template <int kVPT>
 __global__ __launch_bounds__(kPickThreads) void decode_pick_kernel(Dims dm, const int32_t *__restrict__ seqlens,
                                                                     const float *__restrict__ R, int32_t nb_cap,
                                                                     int32_t *__restrict__ block_idx) {
-    __shared__ __align__(16) uint64_t tmax[kPickThreads];
-    __shared__ __align__(16) uint64_t surv[kPickWaves * kMaxTopk];
-    __shared__ __align__(16) uint64_t cand[kPickMaxCand];
-    __shared__ uint64_t tau_s;
-    __shared__ int n_cand_s;
-    __shared__ int picked[kMaxTopk];
+    __shared__ __align__(16) PickShared<kPickThreads> sh;
     const int row = blockIdx.x, bv = row / dm.Hkv, h = row - bv * dm.Hkv;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     const float *Rr = R + (int64_t)row * nb_cap;
     float r[kVPT];                                        // every load issued before any use
 #pragma unroll
@@ -549,73 +637,7 @@ __global__ __launch_bounds__(kPickThreads) void decode_pick_kernel(Dims dm, cons
         if (tid < dm.topk) o[tid] = -1;
         return;
     }
-    const int b_own = (L - 1) / kBlock, n_blk = b_own + 1;
-    const int n_sel = dm.topk < n_blk ? dm.topk : n_blk;
-    const int n_init = dm.n_init < n_blk ? dm.n_init : n_blk;                 // forced leading blocks
-    const int lo_local = max(n_init, b_own - dm.n_local + 1);                 // forced trailing: lo_local..b_own
-    const int jc_max = lo_local - 1;                                          // candidates: n_init..jc_max
-    const int n_pick = n_sel - (n_init + (b_own - lo_local + 1));
-    if (n_pick > 0) {                                                         // uniform over the workgroup
-        const int n_surv = (kPickWaves * n_pick + 3) & ~3;
-        const int cand_cap = n_pick * kVPT;
-        for (int i = tid; i < n_surv; i += kPickThreads) surv[i] = 0ull;
-        for (int i = tid; i < cand_cap + 4; i += kPickThreads)
-            if (i < kPickMaxCand) cand[i] = 0ull;
-        if (tid == 0) {
-            tau_s = kPickValid;
-            n_cand_s = 0;
-        }
-        uint64_t el[kVPT], best = 0ull;
-#pragma unroll
-        for (int s = 0; s < kVPT; ++s) {
-            const int j = tid + kPickThreads * s;
-            const uint32_t kj = r[s] == -INFINITY ? 1u : __float_as_uint(r[s]);
-            const uint32_t key = (j >= n_init && j <= jc_max) ? kj : 0u;
-            el[s] = ((uint64_t)key << 32) | (uint32_t)~j;
-            best = el[s] > best ? el[s] : best;
-        }
-        const bool real = best >= kPickValid;
-        tmax[tid] = best;
-        __syncthreads();
-        // 1a. rank inside the wavefront
-        const int wrank = count_larger(tmax + 64 * wave, 64, best);
-        const bool survivor = real && wrank < n_pick;
-        if (survivor) surv[wave * n_pick + wrank] = best;
-        __syncthreads();
-        // 1b. rank among all thread maxima (a thread that did not survive has n_pick better ones)
-        int trank = n_pick;
-        if (survivor) trank = count_larger(surv, n_surv, best);
-        if (trank == n_pick - 1) tau_s = best;
-        __syncthreads();
-        // 2. publish the elements that can still make it, then rank them by counting
-        if (trank < n_pick) {
-            const uint64_t tau = tau_s;
-#pragma unroll
-            for (int s = 0; s < kVPT; ++s)
-                if (el[s] >= tau) cand[atomicAdd(&n_cand_s, 1)] = el[s];
-        }
-        __syncthreads();
-        const int n_cand = n_cand_s;                                          // n_pick <= n_cand <= cand_cap
-        for (int i = tid; i < n_cand; i += kPickThreads) {
-            const uint64_t e = cand[i];
-            const int beaten = count_larger(cand, (n_cand + 3) & ~3, e);
-            if (beaten < n_pick) picked[beaten] = (int)~(uint32_t)e;
-        }
-        __syncthreads();
-    }
-    if (wave == 0) {
-        int mine = 0x7fffffff;
-        if (lane < n_pick) mine = picked[lane];
-        else if (lane < n_sel) {
-            const int f = lane - n_pick;
-            mine = f < n_init ? f : lo_local + (f - n_init);
-        }
-        // ascending order: rank = number of selected blocks below mine
-        int rank = 0;
-        for (int e = 0; e < n_sel; ++e) rank += __builtin_amdgcn_readlane(mine, e) < mine ? 1 : 0;
-        if (lane < n_sel) o[rank] = mine;
-        else if (lane < dm.topk) o[lane] = -1;
-    }
+    pick_row<kPickThreads, kVPT>(dm, L, r, sh, o, nullptr);
 }
 
 // ---- attention, part 1: one workgroup per selected block --------------------------------------
@@ -625,23 +647,18 @@ __global__ __launch_bounds__(kPickThreads) void decode_pick_kernel(Dims dm, cons
 // 32w..32w+31 and computes O^T = V^T . P^T on the matrix cores, gathering the V^T fragments
 // (8 keys of one channel per lane) from the row-major value tile in LDS.
 constexpr int kVsPitch = kHeadDim + 4;               // bf16 elements per LDS value row: conflict-free column reads
-__global__ __launch_bounds__(256) void decode_attn_partial_kernel(Dims dm, Tensor q, Tensor k, Tensor v,
-                                                                   const int32_t *__restrict__ seqlens,
-                                                                   const int32_t *__restrict__ block_idx,
-                                                                   const uint64_t *__restrict__ tree_mask,
-                                                                   float *__restrict__ o_part,
-                                                                   float2 *__restrict__ ml_part) {
+// Partial attention of query row bv = (b, qi), L cache rows up to and including the query, over
+// selected block `blk` (entry cidx of the row's list; < 0: none).  Whole workgroup of 256 threads.
+__device__ inline void attend_block(const Dims &dm, const Tensor &q, const Tensor &k, const Tensor &v, int bv, int b,
+                                    int qi, int h, int cidx, int L, int blk, const uint64_t *__restrict__ tree_mask,
+                                    float *__restrict__ o_part, float2 *__restrict__ ml_part) {
     __shared__ __align__(16) uint16_t Vs[kBlock * kVsPitch];
     __shared__ float Ps[kBlock][17];
     __shared__ float wmax[4][16], wsum[4][16];
-    const int cidx = blockIdx.x, h = blockIdx.y, bv = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, g = lane >> 4;
     const int G = dm.G;
-    int b, qi;
-    const int L = query_row(dm, seqlens, bv, b, qi);
     const int L_all = L + (dm.n_q - 1 - qi);             // cache rows of the sequence (when L >= 1)
-    const int blk = block_idx[(((int64_t)b * dm.Hkv + h) * dm.n_q + qi) * dm.topk + cidx];
     uint64_t mask_word = 0ull;
     if (tree_mask) mask_word = tree_mask[bv];
     // a tree mask may let a query attend drafted tokens that lie after it in the cache
@@ -758,6 +775,52 @@ __global__ __launch_bounds__(256) void decode_attn_partial_kernel(Dims dm, Tenso
     }
 }
 
+__global__ __launch_bounds__(256) void decode_attn_partial_kernel(Dims dm, Tensor q, Tensor k, Tensor v,
+                                                                   const int32_t *__restrict__ seqlens,
+                                                                   const int32_t *__restrict__ block_idx,
+                                                                   const uint64_t *__restrict__ tree_mask,
+                                                                   float *__restrict__ o_part,
+                                                                   float2 *__restrict__ ml_part) {
+    const int cidx = blockIdx.x, h = blockIdx.y, bv = blockIdx.z;
+    int b, qi;
+    const int L = query_row(dm, seqlens, bv, b, qi);
+    const int blk = block_idx[(((int64_t)b * dm.Hkv + h) * dm.n_q + qi) * dm.topk + cidx];
+    attend_block(dm, q, k, v, bv, b, qi, h, cidx, L, blk, tree_mask, o_part, ml_part);
+}
+
+// Plain decode (one query per sequence), top-k and partial attention in one launch: a decode step is
+// a chain of dependent launches, each costing a launch gap and a memory round trip, and the block
+// list is the only thing the attention waits for.  Every one of the k workgroups of a (sequence,
+// key-value head) repeats the top-k on the same row of block scores (same result; workgroup 0 writes
+// it out) and goes on with its own entry of the list.
+template <int kVPT>
+__global__ __launch_bounds__(kPickThreads) void decode_pick_partial_kernel(Dims dm, Tensor q, Tensor k, Tensor v,
+                                                                            const int32_t *__restrict__ seqlens,
+                                                                            const float *__restrict__ R, int32_t nb_cap,
+                                                                            int32_t *__restrict__ block_idx,
+                                                                            float *__restrict__ o_part,
+                                                                            float2 *__restrict__ ml_part) {
+    __shared__ __align__(16) PickShared<kPickThreads> sh;
+    __shared__ int sel[kMaxTopk];
+    const int cidx = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x;
+    const float *Rr = R + ((int64_t)b * dm.Hkv + h) * nb_cap;
+    float r[kVPT];                                        // every load issued before any use
+#pragma unroll
+    for (int s = 0; s < kVPT; ++s) r[s] = Rr[min(tid + kPickThreads * s, nb_cap - 1)];
+    const int L = clamp_len(seqlens[b], dm.max_seqlen);
+    int32_t *orow = block_idx + ((int64_t)b * dm.Hkv + h) * dm.topk;
+    int blk = -1;
+    if (L < 1) {                                          // uniform over the workgroup
+        if (cidx == 0 && tid < dm.topk) orow[tid] = -1;
+    } else {
+        const int n_sel = pick_row<kPickThreads, kVPT>(dm, L, r, sh, cidx == 0 ? orow : nullptr, sel);
+        __syncthreads();
+        if (cidx < n_sel) blk = sel[cidx];
+    }
+    attend_block(dm, q, k, v, b, b, 0, h, cidx, L, blk, nullptr, o_part, ml_part);
+}
+
 // ---- attention, part 2: merge the k partials of every query head ---------------------------------
 // grid (Hq, B*n_q), 128 threads: thread = channel.  All partial loads are issued before the merge.
 __global__ __launch_bounds__(128) void decode_merge_kernel(Dims dm, const float *__restrict__ o_part,
@@ -821,7 +884,8 @@ size_t select_decode_ws_bytes(const Dims &dm) {
 }
 
 int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
-                         int32_t *block_idx, void *ws, hipStream_t stream, const AppendArgs *append) {
+                         int32_t *block_idx, void *ws, hipStream_t stream, const AppendArgs *append,
+                         const AttendArgs *attend) {
     if (dm.batch <= 0) return 0;
     DecodeSelLayout l = decode_sel_layout(dm);
     if (l.n_c_cap > 16384) return (int)hipErrorInvalidValue;         // rejected earlier by the C ABI
@@ -856,6 +920,20 @@ int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seq
     timing_end(stream);
     const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
     if (n_blocks > kPickThreads * kPickMaxVPT) return (int)hipErrorInvalidValue;   // rejected earlier by the C ABI
+    if (attend && dm.n_q == 1) {                                     // top-k and partial attention in one launch
+        const dim3 grid(dm.topk, dm.Hkv, dm.batch), block(kPickThreads);
+        timing_begin("decode_pick_partial_kernel", stream);
+#define INFLLMV2_PICK_PARTIAL(VPT)                                                                                  \
+    hipLaunchKernelGGL(decode_pick_partial_kernel<VPT>, grid, block, 0, stream, dm, q, attend->k, attend->v, seqlens, \
+                       R, l.nb_cap, block_idx, attend->o_part, attend->ml_part)
+        if (n_blocks <= kPickThreads * 4) INFLLMV2_PICK_PARTIAL(4);
+        else if (n_blocks <= kPickThreads * 8) INFLLMV2_PICK_PARTIAL(8);
+        else if (n_blocks <= kPickThreads * 12) INFLLMV2_PICK_PARTIAL(12);
+        else INFLLMV2_PICK_PARTIAL(16);
+#undef INFLLMV2_PICK_PARTIAL
+        timing_end(stream);
+        return (int)hipGetLastError();
+    }
     const dim3 grid(rows * dm.Hkv), block(kPickThreads);
     timing_begin("decode_pick_kernel", stream);
     if (n_blocks <= kPickThreads * 4)
@@ -876,23 +954,45 @@ size_t attn_decode_ws_bytes(const Dims &dm) {
     return o + ml;
 }
 
+static void attn_decode_ws(const Dims &dm, void *ws, float *&o_part, float2 *&ml_part) {
+    const size_t o_bytes = align256((size_t)dm.batch * dm.n_q * dm.Hq * dm.topk * kHeadDim * sizeof(float));
+    o_part = reinterpret_cast<float *>(ws);
+    ml_part = reinterpret_cast<float2 *>(reinterpret_cast<char *>(ws) + o_bytes);
+}
+
+static int launch_decode_merge(const Dims &dm, const float *o_part, const float2 *ml_part, Tensor out, float *lse,
+                               hipStream_t stream) {
+    timing_begin("decode_merge_kernel", stream);
+    hipLaunchKernelGGL(decode_merge_kernel, dim3(dm.Hq, dm.batch * dm.n_q), dim3(128), 0, stream, dm, o_part,
+                       ml_part, out, lse);
+    timing_end(stream);
+    return (int)hipGetLastError();
+}
+
 int launch_attn_decode(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32_t *seqlens,
                        const int32_t *block_idx, const uint64_t *tree_mask, Tensor out, float *lse, void *ws,
                        hipStream_t stream) {
     if (dm.batch <= 0) return 0;
-    const int rows = dm.batch * dm.n_q;
-    const size_t o_bytes = align256((size_t)rows * dm.Hq * dm.topk * kHeadDim * sizeof(float));
-    float *o_part = reinterpret_cast<float *>(ws);
-    float2 *ml_part = reinterpret_cast<float2 *>(reinterpret_cast<char *>(ws) + o_bytes);
+    float *o_part;
+    float2 *ml_part;
+    attn_decode_ws(dm, ws, o_part, ml_part);
     timing_begin("decode_attn_partial_kernel", stream);
-    hipLaunchKernelGGL(decode_attn_partial_kernel, dim3(dm.topk, dm.Hkv, rows), dim3(256), 0, stream,
+    hipLaunchKernelGGL(decode_attn_partial_kernel, dim3(dm.topk, dm.Hkv, dm.batch * dm.n_q), dim3(256), 0, stream,
                        dm, q, k, v, seqlens, block_idx, tree_mask, o_part, ml_part);
     timing_end(stream);
-    timing_begin("decode_merge_kernel", stream);
-    hipLaunchKernelGGL(decode_merge_kernel, dim3(dm.Hq, rows), dim3(128), 0, stream, dm, o_part,
-                       ml_part, out, lse);
-    timing_end(stream);
-    return (int)hipGetLastError();
+    return launch_decode_merge(dm, o_part, ml_part, out, lse, stream);
+}
+
+// One decode step for one query per sequence: cache append + selection + attention, four launches.
+int launch_decode_step(const Dims &dm, Tensor q, Tensor ck, const AppendArgs &append, const int32_t *seqlens,
+                       int32_t *block_idx, Tensor out, float *lse, void *ws_select, void *ws_attn,
+                       hipStream_t stream) {
+    if (dm.batch <= 0) return 0;
+    AttendArgs at = {append.k, append.v, nullptr, nullptr};
+    attn_decode_ws(dm, ws_attn, at.o_part, at.ml_part);
+    const int err = launch_select_decode(dm, q, ck, seqlens, block_idx, ws_select, stream, &append, &at);
+    if (err) return err;
+    return launch_decode_merge(dm, at.o_part, at.ml_part, out, lse, stream);
 }
 
 }  // namespace infllmv2

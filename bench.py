@@ -341,7 +341,7 @@ def bench_decode(cfg_index, steps):
         launch = "HIP graph of %d consecutive steps replayed %d times (step inputs repeat per replay, the context keeps growing)" % (chunk, reps)
         # the floor of this launch shape: the same number of empty launches per step, in a graph of the same length
         tiny = torch.zeros(64, dtype=torch.float32, device="cuda")
-        n_launch = 5
+        n_launch = 4                                   # logits (+append), scores, top-k + partial attention, merge
         side.wait_stream(torch.cuda.current_stream())
         floor_graph = torch.cuda.CUDAGraph()
         with torch.cuda.stream(side):

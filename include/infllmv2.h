@@ -245,8 +245,9 @@ int32_t infllmv2_append_kv(const infllmv2_params *prm, const infllmv2_tensor *k_
 /*
  * One decode step in one call (section 5.4: per step only the semantic-kernel representations grow):
  * infllmv2_append_kv (with ck) + infllmv2_select_blocks(INFLLMV2_MODE_DECODE) +
- * infllmv2_sparse_attn_decode, with the append folded into the first selection kernel: five launches
- * instead of six, the same caches, ck, block_idx, out and lse bit for bit.
+ * infllmv2_sparse_attn_decode, with the append folded into the first selection kernel and the top-k
+ * into the per-block attention kernel: four launches instead of six, the same caches, ck, block_idx,
+ * out and lse bit for bit.
  *   q, out        [batch, 1, Hq, d] bf16;  k_new, v_new  [batch, Hkv, 1, d] bf16
  *   k, v, ck      the caches (updated in place);  seqlens counts the new token
  *   block_idx     out  int32 [batch, Hkv, 1, topk];  lse  out  fp32 [batch, Hq]

@@ -189,7 +189,7 @@ def test_decode_graph_replays_match_eager():
         binding.sparse_attn_decode(prm, qs[s], st["kc"], st["vc"], st["sl"], cap, st["idx"], out=st["out"], lse=st["lse"], workspace=st["ws2"])
 
     # g: the one-call step in a graph; e: the same call, eager; t: the three separate calls, eager
-    # (other attention kernels: same block sets, outputs equal up to rounding)
+    # (two more launches, the same arithmetic: equal bit for bit)
     g_st, e_st, t_st = make_state(), make_state(), make_state()
     for st in (g_st, e_st, t_st):
         step(st, 0)
@@ -212,11 +212,8 @@ def test_decode_graph_replays_match_eager():
             assert torch.equal(g_st["sl"], st["sl"]), r
             assert torch.equal(g_st["idx"], st["idx"]), r
             assert torch.equal(g_st["ck"].view(torch.int16), st["ck"].view(torch.int16)), r
-        assert torch.equal(g_st["out"].view(torch.int16), e_st["out"].view(torch.int16)), r
-        assert torch.equal(g_st["lse"], e_st["lse"]), r
-        do = (g_st["out"].float() - t_st["out"].float()).abs().max().item()
-        dl = (g_st["lse"] - t_st["lse"]).abs().max().item()
-        assert do <= 2.0 ** -7 * t_st["out"].float().abs().max().item() and dl <= 1e-5 * max(1.0, t_st["lse"].abs().max().item()), (r, do, dl)
+            assert torch.equal(g_st["out"].view(torch.int16), st["out"].view(torch.int16)), r
+            assert torch.equal(g_st["lse"], st["lse"]), r
 
 
 @pytest.mark.timeout(600)

@@ -251,8 +251,10 @@ def bench_prefill(args):
     return res, (x, idx, out, lse, prm, cfg)
 
 
-def bench_decode(cfg_index, steps):
-    """Decode workload: append (+ incremental compression) -> select -> attend, per step."""
+def bench_decode(cfg_index, steps, replicate=1):
+    """Decode workload: append (+ incremental compression) -> select -> attend, per step.
+    replicate > 1: the batch is the workload's sequences `replicate` times over (separate caches in
+    memory, same contents), to show the same kernels where bandwidth, not latency, is the bound."""
     import torch
     from paper_2506_07900_amd import binding, synth
 
@@ -270,8 +272,12 @@ def bench_decode(cfg_index, steps):
     qs = dev(x.q_steps)[:, :, None].contiguous()         # [steps, B, 1, Hq, d]
     ks = dev(x.k_steps)[:, :, :, None].contiguous()      # [steps, B, Hkv, 1, d]
     vs = dev(x.v_steps)[:, :, :, None].contiguous()
-    B = cfg.batch
+    B = cfg.batch * replicate
     sl = torch.tensor(x.seqlens0, dtype=torch.int32, device="cuda")
+    if replicate > 1:
+        kc, vc = kc.repeat(replicate, 1, 1, 1), vc.repeat(replicate, 1, 1, 1)
+        qs, ks, vs = qs.repeat(1, replicate, 1, 1, 1), ks.repeat(1, replicate, 1, 1, 1), vs.repeat(1, replicate, 1, 1, 1)
+        sl = sl.repeat(replicate)
     ck = torch.zeros((B, Hkv, binding.num_kernels(cap, prm), d), dtype=torch.bfloat16, device="cuda")
     binding.compress_keys(prm, kc, sl, cap, ck=ck)
     idx = torch.full((B, Hkv, 1, cfg.topk), -1, dtype=torch.int32, device="cuda")
@@ -372,12 +378,13 @@ def bench_decode(cfg_index, steps):
     n_c = np.maximum((Ls - 32) // 16 + 1, 0)
     gathered = B * Hkv * cfg.topk * m * d * 2 * 2
     algorithmic = gathered + int(n_c.sum()) * Hkv * d * 2 + B * (2 * Hq * d * 2 + Hkv * cfg.topk * 4)
-    return {"workload": cfg.name, "batch": B, "steps": timed, "us_per_step": us, "us_per_token": us / B,
+    return {"workload": cfg.name if replicate == 1 else "%s x %d (replicated sequences)" % (cfg.name, replicate),
+            "batch": B, "steps": timed, "us_per_step": us, "us_per_token": us / B,
             "bytes_gathered": gathered, "bytes_algorithmic": algorithmic,
             "gathered_GBs": gathered / us / 1e3, "algorithmic_GBs": algorithmic / us / 1e3,
             "frac_hbm_gathered": gathered / us / 1e3 / PEAK_HBM_GBS,
             "frac_hbm_algorithmic": algorithmic / us / 1e3 / PEAK_HBM_GBS,
-            "contexts_at_end": [int(v) for v in sl.cpu().numpy()], "launch": launch, **extra}
+            "contexts_at_end": [int(v) for v in sl.cpu().numpy()[:8]], "launch": launch, **extra}
 
 
 def bench_verify(cfg_index, n_draft, steps):
@@ -527,6 +534,9 @@ def main():
                          "(ratio s_c/s); 1 = the exact two-pass selection the headline metric is quoted on")
     ap.add_argument("--decode-steps", type=int, default=1000)
     ap.add_argument("--ragged-steps", type=int, default=200)
+    ap.add_argument("--decode-batch", type=int, default=32,
+                    help="batch of the bandwidth-regime decode leg: the 128K decode workload replicated this many times (<= 1: skip)")
+    ap.add_argument("--decode-batch-steps", type=int, default=150)
     ap.add_argument("--verify-draft", type=int, default=16, help="drafted tokens per verification step (0: skip the leg)")
     ap.add_argument("--verify-steps", type=int, default=50)
     ap.add_argument("--no-decode", action="store_true")
@@ -598,6 +608,10 @@ def main():
             line["decode_ragged_b8"] = bench_decode(4, args.ragged_steps)
             line["decode_ragged_b8"]["frac_measured_hbm_algorithmic"] = (
                 line["decode_ragged_b8"]["algorithmic_GBs"] / mp["hbm_read_GBs"])
+        if args.decode_batch > 1:
+            line["decode_batched"] = bench_decode(3, args.decode_batch_steps, replicate=args.decode_batch)
+            line["decode_batched"]["frac_measured_hbm_algorithmic"] = (
+                line["decode_batched"]["algorithmic_GBs"] / mp["hbm_read_GBs"])
         if args.verify_draft > 0:
             line["verify"] = bench_verify(3, args.verify_draft, args.verify_steps)
             line["verify"]["speedup_per_token_vs_decode"] = (

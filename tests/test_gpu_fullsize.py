@@ -153,6 +153,63 @@ def test_decode_ragged_batch8_steps():
     print("ragged decode: %d rows, %d exact, %d near-tie" % (tot, exact, near), flush=True)
 
 
+@pytest.mark.timeout(600)
+def test_verify_128k_steps():
+    # draft verification in the benchmark's configuration: 128K tokens of context, 16 drafted tokens
+    # per step under a random tree; append (+ completed semantic kernels), selection per drafted
+    # token, tree-masked attention; every drafted token of every step against the oracle
+    cfg = synth.CONFIGS[3]
+    n, steps = 16, 3
+    x = synth.make_decode(cfg, steps=n * steps)
+    Hq, Hkv, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    prm = binding.Params(Hq, Hkv, topk=cfg.topk)
+    oprm = oracle_params(prm)
+    cap = x.capacity
+    kd, vd = to_dev(x.k_cache), to_dev(x.v_cache)
+    k_np, v_np = x.k_cache, x.v_cache
+    l = int(x.seqlens0[0])
+    sl = torch.tensor([l], dtype=torch.int32, device="cuda")
+    ck = binding.compress_keys(prm, kd, sl, cap)
+    rng = np.random.default_rng(11)
+    tot = exact = near = 0
+    for s in range(steps):
+        qn = x.q_steps[s * n:(s + 1) * n, 0]                                  # [n, Hq, d]
+        kn = x.k_steps[s * n:(s + 1) * n, 0].transpose(1, 0, 2)               # [Hkv, n, d]
+        vn = x.v_steps[s * n:(s + 1) * n, 0].transpose(1, 0, 2)
+        parent = [-1] + [int(rng.integers(0, t)) for t in range(1, n)]
+        words = np.zeros(n, np.uint64)
+        for t in range(n):
+            a = t
+            while a >= 0:
+                words[t] |= np.uint64(1 << a)
+                a = parent[a]
+        l += n
+        sl = torch.tensor([l], dtype=torch.int32, device="cuda")
+        binding.append_kv_verify(prm, to_dev(kn[None]), to_dev(vn[None]), kd, vd, sl, cap, ck=ck)
+        idx = binding.select_blocks_verify(prm, to_dev(qn[None]), ck, sl, cap)
+        masks = torch.from_numpy(words.view(np.int64)[None]).cuda()
+        out, lse = binding.sparse_attn_verify(prm, to_dev(qn[None]), kd, vd, sl, cap, idx, tree_mask=masks)
+        torch.cuda.synchronize()
+        k_np[0, :, l - n:l] = kn
+        v_np[0, :, l - n:l] = vn
+        assert np.array_equal(to_bits(kd)[0, :, l - n:l], kn) and np.array_equal(to_bits(vd)[0, :, l - n:l], vn)
+        _, ck_ref = ref.compress_keys(k_np[0, :, :l], oprm)
+        assert np.array_equal(to_bits(ck)[0, :, :ck_ref.shape[1]], ck_ref), s
+        pos = np.arange(l - n, l, dtype=np.int32)
+        ib, margins, R = ref.select_blocks(qn, ck_ref, pos, oprm, want_scores=True)
+        idx_np = idx.cpu().numpy()[0]
+        rows, e, nt, hard = compare_selection(idx_np, ib, margins, R)
+        assert not hard, (s, hard)
+        tot, exact, near = tot + rows, exact + e, near + nt
+        wo, wl = ref.sparse_attn_tree(qn, k_np[0, :, :l], v_np[0, :, :l], idx_np, words, l - n, oprm)
+        eo = np.abs(out[0].double().cpu().numpy() - wo).max()
+        el = lse_err(lse[0].double().cpu().numpy(), wl)
+        print("step %d context %d: max|dO| %.3e LSE err/tol %.3f" % (s, l, eo, el), flush=True)
+        assert eo <= OUT_TOL and el <= 1.0
+    print("verification at 128K: %d rows, %d exact, %d near-tie" % (tot, exact, near), flush=True)
+    assert near <= 2
+
+
 def test_decode_graph_replays_match_eager():
     # a captured decode step must give the eager result on every replay, with eager work and
     # synchronisations in between

@@ -154,6 +154,53 @@ def test_decode_ragged_batch8_steps():
 
 
 @pytest.mark.timeout(600)
+def test_decode_128k_steps():
+    # the decode workload itself: one sequence, 128K tokens of context, the whole step in one call
+    # (the benchmark's configuration); checked against the oracle on the first step, on the step that
+    # completes a semantic kernel and on the one after it
+    cfg = synth.CONFIGS[3]
+    steps = 18
+    x = synth.make_decode(cfg, steps=steps)
+    Hq, Hkv = cfg.n_q_heads, cfg.n_kv_heads
+    prm = binding.Params(Hq, Hkv, topk=cfg.topk)
+    oprm = oracle_params(prm)
+    cap = x.capacity
+    kd, vd = to_dev(x.k_cache), to_dev(x.v_cache)
+    k_np, v_np = x.k_cache, x.v_cache
+    l = int(x.seqlens0[0])
+    ck = binding.compress_keys(prm, kd, torch.tensor([l], dtype=torch.int32, device="cuda"), cap)
+    n_c0 = ref.num_kernels(l, 32, 16)
+    checked = 0
+    for s in range(steps):
+        l += 1
+        sl = torch.tensor([l], dtype=torch.int32, device="cuda")
+        idx, out, lse = binding.decode_step(prm, to_dev(x.q_steps[s][:, None]), to_dev(x.k_steps[s][:, :, None]),
+                                            to_dev(x.v_steps[s][:, :, None]), kd, vd, ck, sl, cap)
+        torch.cuda.synchronize()
+        k_np[0, :, l - 1] = x.k_steps[s][0]
+        v_np[0, :, l - 1] = x.v_steps[s][0]
+        grew = ref.num_kernels(l, 32, 16) > ref.num_kernels(l - 1, 32, 16)
+        if not (s == 0 or grew or ref.num_kernels(l - 1, 32, 16) > ref.num_kernels(l - 2, 32, 16)):
+            continue
+        checked += 1
+        _, ck_ref = ref.compress_keys(k_np[0, :, :l], oprm)
+        assert np.array_equal(to_bits(ck)[0, :, :ck_ref.shape[1]], ck_ref), s
+        pos = np.array([l - 1], np.int32)
+        q1 = x.q_steps[s][0][None]
+        ib, margins, R = ref.select_blocks(q1, ck_ref, pos, oprm, want_scores=True)
+        idx_np = idx.cpu().numpy()[0]
+        rows, e, nt, hard = compare_selection(idx_np, ib, margins, R)
+        assert not hard, (s, hard)
+        wo, wl = ref.sparse_attn(q1, k_np[0, :, :l], v_np[0, :, :l], pos, idx_np, oprm)
+        eo = np.abs(out[0].double().cpu().numpy() - wo).max()
+        el = lse_err(lse[0].double().cpu().numpy(), wl[0])
+        print("step %d context %d (%d kernels%s): max|dO| %.3e LSE err/tol %.3f, %d near-tie rows"
+              % (s, l, ck_ref.shape[1], ", one new" if grew else "", eo, el, nt), flush=True)
+        assert eo <= OUT_TOL and el <= 1.0
+    assert checked >= 3 and ref.num_kernels(l, 32, 16) > n_c0
+
+
+@pytest.mark.timeout(600)
 def test_verify_128k_steps():
     # draft verification in the benchmark's configuration: 128K tokens of context, 16 drafted tokens
     # per step under a random tree; append (+ completed semantic kernels), selection per drafted

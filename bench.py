@@ -428,18 +428,16 @@ def bench_verify(cfg_index, n_draft, steps):
     idx = torch.full((B, Hkv, n, cfg.topk), -1, dtype=torch.int32, device="cuda")
     out = torch.zeros((B, n, Hq, d), dtype=torch.bfloat16, device="cuda")
     lse = torch.zeros((B, n, Hq), dtype=torch.float32, device="cuda")
-    ws_sel = torch.empty(binding.verify_workspace_bytes(binding.OP_SELECT_VERIFY, prm, B, cap, n), dtype=torch.uint8, device="cuda")
-    ws_att = torch.empty(binding.verify_workspace_bytes(binding.OP_ATTN_VERIFY, prm, B, cap, n), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(binding.verify_workspace_bytes(binding.OP_VERIFY_STEP, prm, B, cap, n), dtype=torch.uint8, device="cuda")
 
     def step(s_, sl):
-        binding.append_kv_verify(prm, ks[s_], vs[s_], kc, vc, sl, cap, ck=ck)
-        binding.select_blocks_verify(prm, qs[s_], ck, sl, cap, block_idx=idx, workspace=ws_sel)
-        binding.sparse_attn_verify(prm, qs[s_], kc, vc, sl, cap, idx, tree_mask=masks[s_], out=out, lse=lse,
-                                   workspace=ws_att)
+        """One verification step in one call: append (+ completed semantic kernels), select, attend."""
+        binding.verify_step(prm, qs[s_], ks[s_], vs[s_], kc, vc, ck, sl, cap, tree_mask=masks[s_], block_idx=idx,
+                            out=out, lse=lse, workspace=ws)
 
     # lengths per captured step, advanced by S*n at the end of the graph
     sl_tab = (sl0[None, :] + n * torch.arange(1, S + 1, dtype=torch.int32, device="cuda")[:, None]).contiguous()
-    step(0, sl_tab[0])                                       # eager warm-up of the three entry points
+    step(0, sl_tab[0])                                       # eager warm-up
     torch.cuda.synchronize()
     binding.timing_enable(True)                              # per-kernel durations of one eager step
     step(0, sl_tab[0])

@@ -72,6 +72,7 @@ extern "C" {
 /* Stage selector for infllmv2_verify_workspace_bytes. */
 #define INFLLMV2_OP_SELECT_VERIFY 5
 #define INFLLMV2_OP_ATTN_VERIFY 6
+#define INFLLMV2_OP_VERIFY_STEP 10
 
 /* Query layout selector for infllmv2_select_blocks. */
 #define INFLLMV2_MODE_PREFILL 0 /* one query per cached token: query t sits at position t        */
@@ -285,8 +286,11 @@ int32_t infllmv2_decode_step(const infllmv2_params *prm, const infllmv2_tensor *
  * infllmv2_sparse_attn_verify   q, out bf16 [batch, n_draft, Hq, d]; tree_mask DEVICE uint64
  *                               [batch, n_draft] or NULL; lse out fp32 [batch, n_draft, Hq];
  *                               arithmetic as in infllmv2_sparse_attn_decode.
- * Workspaces: infllmv2_verify_workspace_bytes(INFLLMV2_OP_SELECT_VERIFY / _ATTN_VERIFY, ...)
- * (0 if the arguments are invalid), 256-byte aligned.
+ * infllmv2_verify_step          the three calls in one (ck required), five launches instead of six
+ *                               (the top-k is folded into the per-block attention kernel); the same
+ *                               caches, ck, block_idx, out and lse bit for bit.
+ * Workspaces: infllmv2_verify_workspace_bytes(INFLLMV2_OP_SELECT_VERIFY / _ATTN_VERIFY /
+ * _VERIFY_STEP, ...) (0 if the arguments are invalid), 256-byte aligned.
  */
 size_t infllmv2_verify_workspace_bytes(int32_t op, const infllmv2_params *prm, int32_t batch,
                                        int32_t max_seqlen, int32_t n_draft);
@@ -305,6 +309,12 @@ int32_t infllmv2_sparse_attn_verify(const infllmv2_params *prm, const infllmv2_t
                                     int32_t n_draft, const uint64_t *tree_mask, const int32_t *block_idx,
                                     const infllmv2_tensor *out, float *lse, void *workspace,
                                     size_t workspace_bytes, void *stream);
+int32_t infllmv2_verify_step(const infllmv2_params *prm, const infllmv2_tensor *q,
+                             const infllmv2_tensor *k_new, const infllmv2_tensor *v_new,
+                             const infllmv2_tensor *k, const infllmv2_tensor *v, const infllmv2_tensor *ck,
+                             const int32_t *seqlens, int32_t batch, int32_t max_seqlen, int32_t n_draft,
+                             const uint64_t *tree_mask, int32_t *block_idx, const infllmv2_tensor *out,
+                             float *lse, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Query-block-shared selection -- a COMPARISON VARIANT, not the report's method (section 2.1.3 argues

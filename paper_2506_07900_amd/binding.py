@@ -26,12 +26,13 @@ OP_SELECT_VERIFY, OP_ATTN_VERIFY = 5, 6
 OP_ATTN_BWD = 7
 OP_DECODE_STEP = 8
 OP_SELECT_SHARED = 9
+OP_VERIFY_STEP = 10
 MODE_PREFILL, MODE_DECODE = 0, 1
 
 EXPORTS = ["infllmv2_status_string", "infllmv2_workspace_bytes", "infllmv2_compress_keys",
            "infllmv2_select_blocks", "infllmv2_sparse_attn_prefill", "infllmv2_sparse_attn_decode",
            "infllmv2_sparse_attn_bwd", "infllmv2_append_kv", "infllmv2_decode_step", "infllmv2_select_blocks_shared", "infllmv2_sparse_attn_prefill_shared", "infllmv2_verify_workspace_bytes", "infllmv2_append_kv_verify",
-           "infllmv2_select_blocks_verify", "infllmv2_sparse_attn_verify",
+           "infllmv2_select_blocks_verify", "infllmv2_sparse_attn_verify", "infllmv2_verify_step",
            "infllmv2_probe_peaks", "infllmv2_timing_enable", "infllmv2_timing_read"]
 
 
@@ -120,6 +121,8 @@ def load_library(path=None):
     lib.infllmv2_append_kv_verify.argtypes = [P, T, T, T, T, T, vp, i32, i32, i32, vp]
     lib.infllmv2_select_blocks_verify.restype = i32
     lib.infllmv2_select_blocks_verify.argtypes = [P, T, T, vp, i32, i32, i32, vp, vp, sz, vp]
+    lib.infllmv2_verify_step.restype = i32
+    lib.infllmv2_verify_step.argtypes = [P, T, T, T, T, T, T, vp, i32, i32, i32, vp, vp, T, vp, vp, sz, vp]
     lib.infllmv2_sparse_attn_verify.restype = i32
     lib.infllmv2_sparse_attn_verify.argtypes = [P, T, T, T, vp, i32, i32, i32, vp, vp, T, vp, vp, sz, vp]
     lib.infllmv2_probe_peaks.restype = i32
@@ -352,6 +355,34 @@ def sparse_attn_verify(prm, q, k, v, seqlens, max_seqlen, block_idx, tree_mask=N
                                            ctypes.byref(d[3]), lse.data_ptr(), workspace.data_ptr(),
                                            ws_bytes, _stream()), "infllmv2_sparse_attn_verify")
     return out, lse
+
+
+def verify_step(prm, q, k_new, v_new, k, v, ck, seqlens, max_seqlen, tree_mask=None, block_idx=None, out=None,
+                lse=None, workspace=None):
+    """One verification step in one call: append_kv_verify (with ck) + select_blocks_verify + sparse_attn_verify.
+    q [B, n_draft, Hq, d]; k_new, v_new [B, Hkv, n_draft, d] -> block_idx [B, Hkv, n_draft, topk], out, lse."""
+    lib = load_library()
+    B, n = q.shape[0], q.shape[1]
+    if block_idx is None:
+        block_idx = torch.full((B, prm.n_kv_heads, n, prm.topk), -1, dtype=torch.int32, device=q.device)
+    if out is None:
+        out = torch.zeros_like(q)
+    if lse is None:
+        lse = torch.zeros((B, n, prm.n_q_heads), dtype=torch.float32, device=q.device)
+    mask_ptr = None
+    if tree_mask is not None:
+        if not (tree_mask.is_cuda and tree_mask.dtype == torch.int64 and tree_mask.is_contiguous()
+                and tuple(tree_mask.shape) == (B, n)):
+            raise InfLLMv2Error("tree_mask must be a contiguous int64 device tensor [B, n_draft]")
+        mask_ptr = tree_mask.data_ptr()
+    workspace, ws_bytes = _verify_workspace(OP_VERIFY_STEP, prm, B, max_seqlen, n, workspace, q.device)
+    d = [_query_desc(q, "q"), _cache_desc(k_new, "k_new"), _cache_desc(v_new, "v_new"), _cache_desc(k, "k"),
+         _cache_desc(v, "v"), _cache_desc(ck, "ck"), _query_desc(out, "out")]
+    _check(lib.infllmv2_verify_step(ctypes.byref(prm.c()), *[ctypes.byref(x) for x in d[:6]],
+                                    _i32(seqlens, "seqlens").data_ptr(), B, max_seqlen, n, mask_ptr,
+                                    _i32(block_idx, "block_idx").data_ptr(), ctypes.byref(d[6]), lse.data_ptr(),
+                                    workspace.data_ptr(), ws_bytes, _stream()), "infllmv2_verify_step")
+    return block_idx, out, lse
 
 
 def sparse_attn_bwd(prm, q, k, v, out, dout, lse, seqlens, max_seqlen, block_idx, dq=None, dk=None, dv=None,

@@ -188,6 +188,8 @@ size_t infllmv2_verify_workspace_bytes(int32_t op, const infllmv2_params *prm, i
     switch (op) {
         case INFLLMV2_OP_SELECT_VERIFY: return max_seqlen > kMaxDecodeSeqlen ? 0 : select_decode_ws_bytes(dm);
         case INFLLMV2_OP_ATTN_VERIFY: return attn_decode_ws_bytes(dm);
+        case INFLLMV2_OP_VERIFY_STEP:
+            return max_seqlen > kMaxDecodeSeqlen ? 0 : select_decode_ws_bytes(dm) + attn_decode_ws_bytes(dm);
     }
     return 0;
 }
@@ -288,6 +290,31 @@ int32_t infllmv2_sparse_attn_verify(const infllmv2_params *prm, const infllmv2_t
         return INFLLMV2_ERR_WORKSPACE;
     return hip_status(launch_attn_decode(dm, make_tensor(q), make_tensor(k), make_tensor(v), seqlens,
                                          block_idx, tree_mask, make_tensor(out), lse, workspace,
+                                         reinterpret_cast<hipStream_t>(stream)));
+}
+
+int32_t infllmv2_verify_step(const infllmv2_params *prm, const infllmv2_tensor *q,
+                             const infllmv2_tensor *k_new, const infllmv2_tensor *v_new,
+                             const infllmv2_tensor *k, const infllmv2_tensor *v, const infllmv2_tensor *ck,
+                             const int32_t *seqlens, int32_t batch, int32_t max_seqlen, int32_t n_draft,
+                             const uint64_t *tree_mask, int32_t *block_idx, const infllmv2_tensor *out,
+                             float *lse, void *workspace, size_t workspace_bytes, void *stream) {
+    RETURN_IF_ERR(check_params(prm));
+    RETURN_IF_ERR(check_sizes(batch, max_seqlen));
+    RETURN_IF_ERR(check_draft(batch, n_draft));
+    const infllmv2_tensor *ts[7] = {q, k_new, v_new, k, v, ck, out};
+    for (int i = 0; i < 7; ++i) RETURN_IF_ERR(check_tensor(ts[i]));
+    if (!seqlens || !block_idx || !lse) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    if (tree_mask && (reinterpret_cast<uintptr_t>(tree_mask) & 7u) != 0) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    if (max_seqlen > kMaxDecodeSeqlen) return INFLLMV2_ERR_UNSUPPORTED;
+    const Dims dm = make_dims(prm, batch, max_seqlen, n_draft);
+    const size_t sel = select_decode_ws_bytes(dm), need = sel + attn_decode_ws_bytes(dm);
+    if (need > 0 && (!workspace || workspace_bytes < need ||
+                     (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0))
+        return INFLLMV2_ERR_WORKSPACE;
+    const AppendArgs ap = {make_tensor(k_new), make_tensor(v_new), make_tensor(k), make_tensor(v)};
+    return hip_status(launch_verify_step(dm, make_tensor(q), make_tensor(ck), ap, seqlens, tree_mask, block_idx,
+                                         make_tensor(out), lse, workspace, reinterpret_cast<char *>(workspace) + sel,
                                          reinterpret_cast<hipStream_t>(stream)));
 }
 

@@ -43,6 +43,7 @@ struct AppendArgs {      // the cache append folded into the first kernel of a f
 };
 struct AttendArgs {      // the per-block attention folded into the top-k kernel of a fused decode step
     Tensor k, v;
+    const uint64_t *tree_mask;                        // verification only, else null
     float *o_part;
     float2 *ml_part;
 };
@@ -159,6 +160,9 @@ int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seq
 int launch_decode_step(const Dims &dm, Tensor q, Tensor ck, const AppendArgs &append, const int32_t *seqlens,
                        int32_t *block_idx, Tensor out, float *lse, void *ws_select, void *ws_attn,
                        hipStream_t stream);
+int launch_verify_step(const Dims &dm, Tensor q, Tensor ck, const AppendArgs &append, const int32_t *seqlens,
+                       const uint64_t *tree_mask, int32_t *block_idx, Tensor out, float *lse, void *ws_select,
+                       void *ws_attn, hipStream_t stream);
 size_t select_decode_ws_bytes(const Dims &dm);
 int launch_attn_prefill(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32_t *seqlens,
                         const int32_t *block_idx, Tensor out, float *lse, void *ws, hipStream_t stream);

@@ -788,28 +788,30 @@ __global__ __launch_bounds__(256) void decode_attn_partial_kernel(Dims dm, Tenso
     attend_block(dm, q, k, v, bv, b, qi, h, cidx, L, blk, tree_mask, o_part, ml_part);
 }
 
-// Plain decode (one query per sequence), top-k and partial attention in one launch: a decode step is
+// Top-k and partial attention in one launch (the one-call decode and verification steps): a step is
 // a chain of dependent launches, each costing a launch gap and a memory round trip, and the block
-// list is the only thing the attention waits for.  Every one of the k workgroups of a (sequence,
+// list is the only thing the attention waits for.  Every one of the k workgroups of a (query row,
 // key-value head) repeats the top-k on the same row of block scores (same result; workgroup 0 writes
 // it out) and goes on with its own entry of the list.
 template <int kVPT>
 __global__ __launch_bounds__(kPickThreads) void decode_pick_partial_kernel(Dims dm, Tensor q, Tensor k, Tensor v,
                                                                             const int32_t *__restrict__ seqlens,
                                                                             const float *__restrict__ R, int32_t nb_cap,
+                                                                            const uint64_t *__restrict__ tree_mask,
                                                                             int32_t *__restrict__ block_idx,
                                                                             float *__restrict__ o_part,
                                                                             float2 *__restrict__ ml_part) {
     __shared__ __align__(16) PickShared<kPickThreads> sh;
     __shared__ int sel[kMaxTopk];
-    const int cidx = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int cidx = blockIdx.x, h = blockIdx.y, bv = blockIdx.z;
     const int tid = threadIdx.x;
-    const float *Rr = R + ((int64_t)b * dm.Hkv + h) * nb_cap;
+    const float *Rr = R + ((int64_t)bv * dm.Hkv + h) * nb_cap;
     float r[kVPT];                                        // every load issued before any use
 #pragma unroll
     for (int s = 0; s < kVPT; ++s) r[s] = Rr[min(tid + kPickThreads * s, nb_cap - 1)];
-    const int L = clamp_len(seqlens[b], dm.max_seqlen);
-    int32_t *orow = block_idx + ((int64_t)b * dm.Hkv + h) * dm.topk;
+    int b, qi;
+    const int L = query_row(dm, seqlens, bv, b, qi);
+    int32_t *orow = block_idx + (((int64_t)b * dm.Hkv + h) * dm.n_q + qi) * dm.topk;
     int blk = -1;
     if (L < 1) {                                          // uniform over the workgroup
         if (cidx == 0 && tid < dm.topk) orow[tid] = -1;
@@ -818,7 +820,7 @@ __global__ __launch_bounds__(kPickThreads) void decode_pick_partial_kernel(Dims 
         __syncthreads();
         if (cidx < n_sel) blk = sel[cidx];
     }
-    attend_block(dm, q, k, v, b, b, 0, h, cidx, L, blk, nullptr, o_part, ml_part);
+    attend_block(dm, q, k, v, bv, b, qi, h, cidx, L, blk, tree_mask, o_part, ml_part);
 }
 
 // ---- attention, part 2: merge the k partials of every query head ---------------------------------
@@ -920,12 +922,12 @@ int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seq
     timing_end(stream);
     const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
     if (n_blocks > kPickThreads * kPickMaxVPT) return (int)hipErrorInvalidValue;   // rejected earlier by the C ABI
-    if (attend && dm.n_q == 1) {                                     // top-k and partial attention in one launch
-        const dim3 grid(dm.topk, dm.Hkv, dm.batch), block(kPickThreads);
+    if (attend) {                                                    // top-k and partial attention in one launch
+        const dim3 grid(dm.topk, dm.Hkv, rows), block(kPickThreads);
         timing_begin("decode_pick_partial_kernel", stream);
 #define INFLLMV2_PICK_PARTIAL(VPT)                                                                                  \
     hipLaunchKernelGGL(decode_pick_partial_kernel<VPT>, grid, block, 0, stream, dm, q, attend->k, attend->v, seqlens, \
-                       R, l.nb_cap, block_idx, attend->o_part, attend->ml_part)
+                       R, l.nb_cap, attend->tree_mask, block_idx, attend->o_part, attend->ml_part)
         if (n_blocks <= kPickThreads * 4) INFLLMV2_PICK_PARTIAL(4);
         else if (n_blocks <= kPickThreads * 8) INFLLMV2_PICK_PARTIAL(8);
         else if (n_blocks <= kPickThreads * 12) INFLLMV2_PICK_PARTIAL(12);
@@ -988,9 +990,24 @@ int launch_decode_step(const Dims &dm, Tensor q, Tensor ck, const AppendArgs &ap
                        int32_t *block_idx, Tensor out, float *lse, void *ws_select, void *ws_attn,
                        hipStream_t stream) {
     if (dm.batch <= 0) return 0;
-    AttendArgs at = {append.k, append.v, nullptr, nullptr};
+    AttendArgs at = {append.k, append.v, nullptr, nullptr, nullptr};
     attn_decode_ws(dm, ws_attn, at.o_part, at.ml_part);
     const int err = launch_select_decode(dm, q, ck, seqlens, block_idx, ws_select, stream, &append, &at);
+    if (err) return err;
+    return launch_decode_merge(dm, at.o_part, at.ml_part, out, lse, stream);
+}
+
+// One verification step for n_q drafted tokens per sequence: append (+ completed semantic kernels),
+// selection per drafted token, tree-masked attention; five launches.
+int launch_verify_step(const Dims &dm, Tensor q, Tensor ck, const AppendArgs &append, const int32_t *seqlens,
+                       const uint64_t *tree_mask, int32_t *block_idx, Tensor out, float *lse, void *ws_select,
+                       void *ws_attn, hipStream_t stream) {
+    if (dm.batch <= 0) return 0;
+    int err = launch_append_kv(dm, append.k_new, append.v_new, append.k, append.v, &ck, seqlens, stream);
+    if (err) return err;
+    AttendArgs at = {append.k, append.v, tree_mask, nullptr, nullptr};
+    attn_decode_ws(dm, ws_attn, at.o_part, at.ml_part);
+    err = launch_select_decode(dm, q, ck, seqlens, block_idx, ws_select, stream, nullptr, &at);
     if (err) return err;
     return launch_decode_merge(dm, at.o_part, at.ml_part, out, lse, stream);
 }

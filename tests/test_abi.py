@@ -173,6 +173,24 @@ def test_decode_step_validation(lib):
     assert lib.infllmv2_decode_step(P, T, T, T, T, T, T, FAKE, 0, 4096, FAKE, T, FAKE, FAKE, 1 << 40, None) == 0
 
 
+def test_verify_step_validation(lib):
+    prm, t = good_params(), tensor()
+    P, T = ctypes.byref(prm), ctypes.byref(t)
+    ws = lib.infllmv2_verify_workspace_bytes
+    need = ws(binding.OP_VERIFY_STEP, P, 2, 4096, 8)
+    assert need == ws(binding.OP_SELECT_VERIFY, P, 2, 4096, 8) + ws(binding.OP_ATTN_VERIFY, P, 2, 4096, 8) > 0
+    assert ws(binding.OP_VERIFY_STEP, P, 2, 4096, 65) == 0 and ws(binding.OP_VERIFY_STEP, P, 2, 1 << 20, 8) == 0
+    call = lambda n=8, q=T, ck=T, sl=FAKE, mask=None, w=FAKE, wb=1 << 40, ms=4096: lib.infllmv2_verify_step(
+        P, q, T, T, T, T, ck, sl, 2, ms, n, mask, FAKE, T, FAKE, w, wb, None)
+    assert call(n=0) == INVALID and call(n=65) == UNSUPPORTED
+    assert call(q=None) == INVALID and call(ck=None) == INVALID and call(sl=None) == INVALID
+    assert call(mask=FAKE + 4) == INVALID                                                # mask words 8-byte aligned
+    assert call(w=None, wb=0) == WORKSPACE and call(wb=need - 1) == WORKSPACE and call(w=FAKE + 16) == WORKSPACE
+    assert call(ms=1 << 20) == UNSUPPORTED                                               # decode context cap
+    assert lib.infllmv2_verify_step(P, T, T, T, T, T, T, FAKE, 0, 4096, 8, None, FAKE, T, FAKE, FAKE, 1 << 40,
+                                    None) == 0                                           # empty batch: nothing to do
+
+
 def test_shared_variant_validation(lib):
     prm, t = good_params(), tensor()
     P, T = ctypes.byref(prm), ctypes.byref(t)

@@ -232,10 +232,14 @@ def test_verify_128k_steps():
                 a = parent[a]
         l += n
         sl = torch.tensor([l], dtype=torch.int32, device="cuda")
-        binding.append_kv_verify(prm, to_dev(kn[None]), to_dev(vn[None]), kd, vd, sl, cap, ck=ck)
-        idx = binding.select_blocks_verify(prm, to_dev(qn[None]), ck, sl, cap)
         masks = torch.from_numpy(words.view(np.int64)[None]).cuda()
-        out, lse = binding.sparse_attn_verify(prm, to_dev(qn[None]), kd, vd, sl, cap, idx, tree_mask=masks)
+        if s % 2 == 0:                                    # the benchmark's configuration: the whole step in one call
+            idx, out, lse = binding.verify_step(prm, to_dev(qn[None]), to_dev(kn[None]), to_dev(vn[None]), kd, vd, ck,
+                                                sl, cap, tree_mask=masks)
+        else:
+            binding.append_kv_verify(prm, to_dev(kn[None]), to_dev(vn[None]), kd, vd, sl, cap, ck=ck)
+            idx = binding.select_blocks_verify(prm, to_dev(qn[None]), ck, sl, cap)
+            out, lse = binding.sparse_attn_verify(prm, to_dev(qn[None]), kd, vd, sl, cap, idx, tree_mask=masks)
         torch.cuda.synchronize()
         k_np[0, :, l - n:l] = kn
         v_np[0, :, l - n:l] = vn
@@ -408,12 +412,17 @@ def test_verify_and_backward_graph_replays_match_eager():
                   out=torch.zeros((1, n, Hq, d), dtype=torch.bfloat16, device="cuda"),
                   lse=torch.zeros((1, n, Hq), dtype=torch.float32, device="cuda"),
                   ws1=torch.empty(binding.verify_workspace_bytes(binding.OP_SELECT_VERIFY, prm, 1, cap, n), dtype=torch.uint8, device="cuda"),
-                  ws2=torch.empty(binding.verify_workspace_bytes(binding.OP_ATTN_VERIFY, prm, 1, cap, n), dtype=torch.uint8, device="cuda"))
+                  ws2=torch.empty(binding.verify_workspace_bytes(binding.OP_ATTN_VERIFY, prm, 1, cap, n), dtype=torch.uint8, device="cuda"),
+                  ws3=torch.empty(binding.verify_workspace_bytes(binding.OP_VERIFY_STEP, prm, 1, cap, n), dtype=torch.uint8, device="cuda"))
         st["ck"] = binding.compress_keys(prm, st["kc"], st["sl"], cap)
         return st
 
-    def step(st, s):
+    def step(st, s, one_call=False):
         st["sl"].add_(n)
+        if one_call:
+            binding.verify_step(prm, qs[s], ks[s], vs[s], st["kc"], st["vc"], st["ck"], st["sl"], cap, tree_mask=masks[s],
+                                block_idx=st["idx"], out=st["out"], lse=st["lse"], workspace=st["ws3"])
+            return
         binding.append_kv_verify(prm, ks[s], vs[s], st["kc"], st["vc"], st["sl"], cap, ck=st["ck"])
         binding.select_blocks_verify(prm, qs[s], st["ck"], st["sl"], cap, block_idx=st["idx"], workspace=st["ws1"])
         binding.sparse_attn_verify(prm, qs[s], st["kc"], st["vc"], st["sl"], cap, st["idx"], tree_mask=masks[s],
@@ -429,7 +438,7 @@ def test_verify_and_backward_graph_replays_match_eager():
     with torch.cuda.stream(side):
         with torch.cuda.graph(graph, stream=side):
             for s in range(1, 1 + chunk):
-                step(g_st, s)
+                step(g_st, s, one_call=True)         # the graph holds the one-call step, the eager twin the three calls
     torch.cuda.synchronize()
     for r in range(reps):
         graph.replay()

@@ -700,6 +700,22 @@ def test_random_configurations_all_entry_points(seed, wide):
         wo, wl = ref.sparse_attn_tree(qn[b], k[b, :, :l], v[b, :, :l], iv[b], masks[b], l - n, oprm)
         assert out_err(ov[b].double().cpu().numpy(), wo) <= 1.0
         assert lse_err(lv[b].double().cpu().numpy(), wl) <= 1.0
+    # the same verification step in one call, from the state before the drafts: equal bit for bit
+    k0, v0 = k.copy(), v.copy()
+    kn = np.zeros((B, Hkv, n, 128), np.uint16)
+    vn = np.zeros((B, Hkv, n, 128), np.uint16)
+    for b, l in enumerate(seqlens):
+        if l >= n:
+            kn[b], vn[b] = k[b, :, l - n:l], v[b, :, l - n:l]
+            k0[b, :, l - n:l] = 0
+            v0[b, :, l - n:l] = 0
+    kc, vc = to_dev(k0), to_dev(v0)
+    ckv = binding.compress_keys(prm, kc, dev_i32([l - n if l >= n else l for l in seqlens]), T)
+    i2, o2, l2 = binding.verify_step(prm, to_dev(qn), to_dev(kn), to_dev(vn), kc, vc, ckv, sl, T, tree_mask=dev_masks(masks))
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(kc), k) and np.array_equal(to_bits(vc), v) and np.array_equal(to_bits(ckv), ckb)
+    assert np.array_equal(i2.cpu().numpy(), iv)
+    assert torch.equal(o2.view(torch.int16), ov.view(torch.int16)) and torch.equal(l2, lv)
     if rho == 1:
         isd = binding.select_blocks_shared(prm, qd, ck, sl, T)
         osd, lsd = binding.sparse_attn_prefill_shared(prm, qd, kd, vd, sl, T, isd)

@@ -18,7 +18,8 @@
 //                          computed again on the matrix cores (verification)
 //   decode_pick_kernel     two-level top-k of the block-score row
 // Attention: one workgroup per selected block (split-KV) writes an unnormalised partial
-// (o, max, sum); decode_merge_kernel combines the k partials per query head.
+// (o, max, sum); decode_merge_kernel combines the k partials per query head.  The one-call steps
+// run the top-k inside the attention kernel (decode_pick_partial_kernel): one launch fewer.
 #include "common.h"
 
 namespace infllmv2 {

@@ -19,8 +19,6 @@ namespace infllmv2 {
 
 constexpr int kMT = 8;                 // tokens (= 16-row tiles) per wavefront
 constexpr int kTokPerWg16 = 4 * kMT;   // 4 independent wavefronts per workgroup
-constexpr float kRescaleSlack = 60.f;  // pass 1 re-bases its exponent only when a logit exceeds the
-                                       // reference by 2^60: sums stay far from fp32 overflow
 
 __device__ inline int n_visible16(int i) { return num_kernels(i + 1); }
 // kernels of pass 1: the fine ones, or the coarse ones of the approximate log-sum-exp

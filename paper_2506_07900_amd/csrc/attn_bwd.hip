@@ -28,9 +28,10 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBwdBlockU4 = 3 * 16 * 64;              // uint4 per packed block: K rows, V rows, K^T (48 KiB)
-constexpr int kSegTokens = 2048;                      // member tokens of one dk/dv workgroup come from one segment
-constexpr int kSegWords = kSegTokens / 32;
-static_assert(kSegWords <= 64 && kSegTokens % 32 == 0, "the member list is compacted by one wavefront, one word per lane");
+// Member tokens of one dk/dv workgroup come from one segment of the sequence.  Short segments give
+// more workgroups (better balance at 32K tokens), long ones fewer prologues and merges per block
+// (at 128K tokens most (block, segment) units hold a handful of members).
+static inline int bwd_seg_tokens(const Dims &dm) { return dm.max_seqlen > 65536 ? 4096 : 2048; }
 constexpr int kBwdNone = 0x7fffffff;
 constexpr int kBwdBlkBits = 27, kBwdBlkMask = (1 << kBwdBlkBits) - 1;
 
@@ -44,7 +45,8 @@ static BwdLayout bwd_layout(const Dims &dm) {
     BwdLayout l;
     const size_t T = (size_t)dm.max_seqlen, BH = (size_t)dm.batch * dm.Hkv;
     l.nb_cap = (dm.max_seqlen + kBlock - 1) / kBlock;
-    l.words = ((dm.max_seqlen + kSegTokens - 1) / kSegTokens) * kSegWords;
+    const int seg_tokens = bwd_seg_tokens(dm);
+    l.words = ((dm.max_seqlen + seg_tokens - 1) / seg_tokens) * (seg_tokens / 32);
     size_t o = 0;
     l.kvb = o;    o += al256(BH * l.nb_cap * kBwdBlockU4 * sizeof(uint4));
     l.delta = o;  o += al256((size_t)dm.batch * T * dm.Hq * sizeof(float));
@@ -369,13 +371,17 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(Dims dm, Tensor q, 
 constexpr int kRowPitch = kHeadDim + 8;               // bf16 per staged row (272 bytes: rows start 4 banks apart)
 constexpr int kPairRows = 2 * 2 * 16;                 // q rows of two tokens, dout rows of two tokens
 constexpr int kDepth = 3;                             // pairs in flight per thread
+template <int kSegTokens>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q, Tensor dout, const uint4 *__restrict__ kvb,
                                                                 int32_t nb_cap, const int32_t *__restrict__ seqlens,
                                                                 const float *__restrict__ lse,
                                                                 const float *__restrict__ delta,
                                                                 const uint32_t *__restrict__ bitmap, int32_t words,
                                                                 float *__restrict__ acc_dk, float *__restrict__ acc_dv) {
-    __shared__ int list[kSegTokens];
+    constexpr int kSegWords = kSegTokens / 32;
+    constexpr int kSegWordsPerLane = kSegWords / 64;      // the member list is compacted by one wavefront
+    static_assert(kSegWords % 64 == 0 && kSegTokens <= 65536, "whole words per lane; 16-bit offsets in the member list");
+    __shared__ uint16_t list[kSegTokens];                // member tokens as offsets into the segment
     __shared__ __align__(16) uint16_t stage[2][kPairRows * kRowPitch];   // [buffer][(q | dout, token, head)][channel]
     __shared__ __align__(16) uint16_t stageT[2][2 * 8 * 64 * 8];         // [buffer][(q | dout, dt, lane)][token][4 heads]
     __shared__ __align__(16) float ld[2][2][2][16];       // [buffer][lse | D][token of the pair][head]
@@ -391,20 +397,29 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
     const int64_t bh = (int64_t)b * dm.Hkv + h;
     // ---- member tokens of this segment, ascending (wave 0) ----------------------------------------------
     if (wave == 0) {
-        uint32_t word = 0u;                               // one bitmap word per lane: a segment has at most 64 words
-        if (lane < kSegWords) word = bitmap[(bh * nb_cap + j) * words + seg * kSegWords + lane];
-        int before = __popc(word);
+        uint32_t word[kSegWordsPerLane];                  // consecutive words per lane: the list comes out ascending
+        int mine = 0;
+#pragma unroll
+        for (int i = 0; i < kSegWordsPerLane; ++i) {
+            word[i] = bitmap[(bh * nb_cap + j) * words + seg * kSegWords + lane * kSegWordsPerLane + i];
+            mine += __popc(word[i]);
+        }
+        int before = mine;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
             const int x = __shfl_up(before, o);
             if (lane >= o) before += x;
         }
         if (lane == 63) total_s = before;
-        before -= __popc(word);
-        while (word) {
-            const int bit = __ffs(word) - 1;
-            word &= word - 1;
-            list[before++] = seg * kSegTokens + lane * 32 + bit;
+        before -= mine;
+#pragma unroll
+        for (int i = 0; i < kSegWordsPerLane; ++i) {
+            uint32_t w = word[i];
+            while (w) {
+                const int bit = __ffs(w) - 1;
+                w &= w - 1;
+                list[before++] = (uint16_t)((lane * kSegWordsPerLane + i) * 32 + bit);
+            }
         }
     }
     __syncthreads();
@@ -438,7 +453,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
     u32x4 r[kDepth][4];                                   // (ext vectors: arrays of HIP's uint4 struct end up in scratch)
     float rf[kDepth];
     auto fetch = [&](int p, int st) __attribute__((always_inline)) {
-        const int ta = list[min(2 * p, total - 1)], tb = list[min(2 * p + 1, total - 1)];
+        const int ta = seg * kSegTokens + list[min(2 * p, total - 1)], tb = seg * kSegTokens + list[min(2 * p + 1, total - 1)];
         const int tok = (f_tile & 1) ? tb : ta;
 #pragma unroll
         for (int e = 0; e < 4; ++e) r[st][e] = *reinterpret_cast<const u32x4 *>(f_base[e] + (int64_t)tok * src.st);
@@ -493,7 +508,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
             const int p = p0 + kk;
             const int cur = p & 1;
             const bool one = 2 * p < total, two = 2 * p + 1 < total;
-            const int tk0 = list[min(2 * p, total - 1)], tk1 = list[min(2 * p + 1, total - 1)];
+            const int tk0 = seg * kSegTokens + list[min(2 * p, total - 1)], tk1 = seg * kSegTokens + list[min(2 * p + 1, total - 1)];
             const uint16_t *sq = stage[cur];
             bf16x8 ps, dss;                               // B operands of the second contractions
 #pragma unroll
@@ -604,8 +619,12 @@ int launch_attn_bwd(const Dims &dm, Tensor q, Tensor k, Tensor v, Tensor out, Te
                        dm, q, dout, kvb, l.nb_cap, seqlens, block_idx, lse, delta, dq, n_tiles);
     timing_end(stream);
     timing_begin("attn_bwd_dkdv_kernel", stream);
-    hipLaunchKernelGGL(attn_bwd_dkdv_kernel, dim3(l.nb_cap, l.words / kSegWords, dm.batch * dm.Hkv), dim3(256), 0, stream,
-                       dm, q, dout, kvb, l.nb_cap, seqlens, lse, delta, bitmap, l.words, acc_dk, acc_dv);
+    if (bwd_seg_tokens(dm) == 4096)
+        hipLaunchKernelGGL(attn_bwd_dkdv_kernel<4096>, dim3(l.nb_cap, l.words / 128, dm.batch * dm.Hkv), dim3(256), 0,
+                           stream, dm, q, dout, kvb, l.nb_cap, seqlens, lse, delta, bitmap, l.words, acc_dk, acc_dv);
+    else
+        hipLaunchKernelGGL(attn_bwd_dkdv_kernel<2048>, dim3(l.nb_cap, l.words / 64, dm.batch * dm.Hkv), dim3(256), 0,
+                           stream, dm, q, dout, kvb, l.nb_cap, seqlens, lse, delta, bitmap, l.words, acc_dk, acc_dv);
     timing_end(stream);
     timing_begin("bwd_finish_kernel", stream);
     hipLaunchKernelGGL(bwd_finish_kernel, dim3((T + 15) / 16, dm.Hkv, dm.batch), dim3(256), 0, stream, dm, seqlens,

@@ -538,6 +538,47 @@ def test_sparse_attn_backward(seqlens, Hq, Hkv, topk, planted):
         assert eq <= 1.0 and ek <= 1.0 and ev <= 1.0
 
 
+def test_sparse_attn_backward_long_capacity():
+    # buffers sized for more than 65536 tokens make the dk/dv kernel work on 4096-token segments
+    # (2048 below that); sequences that cross a segment boundary, the rest of the capacity unused
+    seqlens, Hq, Hkv, topk, cap = [5000, 4200], 16, 1, 8, 66000
+    prm = binding.Params(Hq, Hkv, topk=topk)
+    oprm = oracle_params(prm)
+    q, k, v, T = make_batch(57, seqlens, Hq, Hkv, n_planted=4)
+    B = len(seqlens)
+    rng = np.random.default_rng(10)
+    do = synth.f32_to_bf16_bits(rng.standard_normal((B, T, Hq, 128), dtype=np.float32))
+
+    def padded(x, axis):                                   # device copy with `cap` rows along the token axis
+        shape = list(x.shape)
+        shape[axis] = cap
+        t = torch.zeros(shape, dtype=torch.bfloat16, device="cuda")
+        t.narrow(axis, 0, x.shape[axis]).copy_(to_dev(x))
+        return t
+
+    qd, kd, vd, dod = padded(q, 1), padded(k, 2), padded(v, 2), padded(do, 1)
+    sl = dev_i32(seqlens)
+    idx = torch.full((B, Hkv, cap, topk), -1, dtype=torch.int32, device="cuda")
+    want = [None] * B
+    for b, l in enumerate(seqlens):
+        _, ckb = ref.compress_keys(k[b, :, :l], oprm)
+        pos = np.arange(l, dtype=np.int32)
+        ib, _ = ref.select_blocks(q[b, :l], ckb, pos, oprm)
+        idx[b, :, :l] = torch.from_numpy(ib).cuda()
+        want[b] = ref.sparse_attn_bwd(q[b, :l], k[b, :, :l], v[b, :, :l], do[b, :l], pos, ib, oprm, want_mag=True)
+    out, lse = binding.sparse_attn_prefill(prm, qd, kd, vd, sl, cap, idx)
+    dq, dk, dv = binding.sparse_attn_bwd(prm, qd, kd, vd, out, dod, lse, sl, cap, idx)
+    torch.cuda.synchronize()
+    for b, l in enumerate(seqlens):
+        wq, wk, wv, mq, mk, mv = want[b]
+        eq = grad_err(dq[b, :l].double().cpu().numpy(), wq, mq)
+        ek = grad_err(dk[b, :, :l].double().cpu().numpy(), wk, mk)
+        ev = grad_err(dv[b, :, :l].double().cpu().numpy(), wv, mv)
+        print("seq %d len %d: err/tol dq %.3f dk %.3f dv %.3f" % (b, l, eq, ek, ev), flush=True)
+        assert eq <= 1.0 and ek <= 1.0 and ev <= 1.0
+        assert bool((dq[b, l:] == 0).all()) and bool((dk[b, :, l:] == 0).all()) and bool((dv[b, :, l:] == 0).all())
+
+
 # ------------------------------------------------------------------ query-block-shared selection (comparison variant)
 
 @pytest.mark.parametrize("seqlens,Hq,Hkv,topk,planted", [([1077, 333, 64, 1], 32, 2, 8, 5), ([700], 16, 2, 6, 3),

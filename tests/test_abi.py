@@ -29,6 +29,19 @@ def test_header_symbols_are_exported(lib):
         assert hasattr(lib, name), name
 
 
+def test_header_is_plain_c():
+    # the boundary is a C ABI: the header has to compile as strict C99 (and as C++) on its own
+    import shutil
+    import subprocess
+    hdr = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "infllmv2.h")
+    if shutil.which("gcc") is None:
+        pytest.skip("no host C compiler")
+    for lang, std in (("c", "-std=c99"), ("c++", "-std=c++17")):
+        r = subprocess.run(["gcc", "-x", lang, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", hdr],
+                           capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+
+
 def test_struct_layout_matches_header():
     assert ctypes.sizeof(CParams) == 44 and ctypes.sizeof(CTensor) == 32      # 10 int32 + 1 float; 1 pointer + 3 int64
 

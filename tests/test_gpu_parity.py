@@ -1,6 +1,8 @@
 """GPU parity: the HIP path, called through the C ABI, against the fp64 oracle element by
 element on the same seeded inputs.  Sizes span several tiles and ragged tails; the largest
 stated workloads are checked on sampled rows."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -29,6 +31,19 @@ def make_batch(seed, seqlens, Hq, Hkv, n_planted=0, heavy=()):
         s = synth.make_sequence(seed * 100 + b, l, Hq, Hkv, n_planted=n_planted, heavy_tail=b in heavy)
         q[b, :l], k[b, :, :l], v[b, :, :l] = s.q, s.k, s.v
     return q, k, v, T
+
+
+# ------------------------------------------------------------------ the boundary from plain C
+
+def test_c_client_of_the_abi():
+    # a C99 program (no Python, no torch: HIP runtime + include/infllmv2.h) runs the three stages on a
+    # small dense-degrade case and checks them against loops of its own; exit status 0 = all checks passed
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_client", "abi_client")
+    assert os.path.exists(exe), "tests/c_client/abi_client is not built (run __graft_entry__.build())"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    print(r.stdout, r.stderr, flush=True)
+    assert r.returncode == 0 and "abi_client ok" in r.stdout
 
 
 # ------------------------------------------------------------------ stage 1

@@ -78,12 +78,16 @@ __device__ inline void load_query_operands(const Dims &dm, const Tensor &q, int 
 // ---- selection, parts 1 and 2 -------------------------------------------------------------------
 // Both parts score semantic kernels against kQT consecutive query tokens of one sequence on the
 // matrix cores.  kQT = 1 is plain decode; verification uses kQT = kVerifyQT.  A workgroup of part 1
-// covers tiles_per_wave tiles of 16 kernels per wave, one of part 2 tiles_per_wave2 (plus one halo
-// tile): one tile per wave keeps a lone decode step spread over many workgroups; two amortise the
-// query rows and the partials that every workgroup of a verification step has to fetch (measured at
-// 128K context: one, two and four tiles per wave differ by under 10 % for 4 to 64 drafted tokens).
+// covers kTW tiles of 16 kernels per wave, one of part 2 tiles_per_wave2 (plus one halo tile).  More
+// tiles per wave mean fewer workgroups and fewer log-sum-exp partials for part 2 to merge (every
+// workgroup of part 2 reads all partials of its heads); fewer tiles spread a lone step over more compute
+// units.  Measured at 128K context, plain decode, 1 / 2 / 4 tiles: 21.6 / 21.1 / 21.6 us per step for
+// one sequence, 27.2 / 26.8 / 25.8 us for the ragged batch of 8, 73 / 62 / 61 us for 32 sequences;
+// verification (4 to 64 drafted tokens): under 10 % between them.
 constexpr int kVerifyQT = 4;
-__host__ __device__ constexpr int tiles_per_wave(int qt) { return qt == 1 ? 1 : 2; }    // part 1
+__host__ __device__ constexpr int tiles_per_wave(int qt) { return 2; }                   // part 1, verification
+// part 1, plain decode: by batch size
+static inline int decode_tiles_per_wave(const Dims &dm) { return dm.batch >= 4 ? 4 : 2; }
 __host__ __device__ constexpr int tiles_per_wave2(int qt) { return qt == 1 ? 1 : 2; }   // part 2
 
 // length of the cache up to and including query token qi of sequence b (0: no such row)
@@ -99,7 +103,7 @@ __device__ inline int row_len(const Dims &dm, int L_all, int qi) {
 // them), and the wave that owns the semantic kernel the new token completes builds its representation
 // itself -- 31 cached rows and the new one, fp64 sum in token order, one rounding, the same bits as
 // compress_keys_kernel -- uses it, and stores it for the steps to come.
-template <int kQT, bool kAppend>
+template <int kQT, bool kAppend, int kTW>
 __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, Tensor ck,
                                                              const int32_t *__restrict__ seqlens,
                                                              float *__restrict__ zbuf, int32_t n_c_cap,
@@ -107,7 +111,7 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, T
                                                              float2 *__restrict__ part_c, int32_t n_part,
                                                              AppendArgs ap) {
     static_assert(!kAppend || kQT == 1, "the fused append is for one query per sequence");
-    constexpr int kTW = tiles_per_wave(kQT), kChunk = 64 * kTW;
+    constexpr int kChunk = 64 * kTW;
     __shared__ float2 wpart[kQT][4][16];
     __shared__ float2 wpart_c[kQT][4][16];
     __shared__ __align__(16) uint16_t qs[kQT > 1 ? kQT * 16 * kQsPitch : 8];
@@ -154,7 +158,7 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, T
     load_query_operands<kQT>(dm, q, b, h, qi0, qs, bq);   // heads >= G repeat head G-1: their columns are never used
     if constexpr (kAppend) {
         const int jh_new = n_vis_max - 1;             // = (L - p) / s when the new token closes a kernel
-        if (closes && jh_new >= jw && jh_new < jw + 16) {             // uniform over the wave (kTW = 1)
+        if (closes && jh_new >= jw && jh_new < jw + 16 * kTW) {       // uniform over the wave
             // lane = channels 2*lane, 2*lane+1: rows L-32 .. L-2 from the cache, row L-1 from k_new
             const int L = L_all;
             const __bf16 *kc = ap.k.ptr + b * ap.k.sb + h * ap.k.sh + 2 * lane;
@@ -174,11 +178,13 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, T
             newrow[lane] = packed;
             *reinterpret_cast<uint32_t *>(ck.ptr + b * ck.sb + h * ck.sh + (int64_t)jh_new * ck.st + 2 * lane) = packed;
             // same wavefront wrote newrow: LDS keeps the order.  The lanes whose operand row it is take it from there.
-            if (jw + n == jh_new) {
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-                    a[0][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&newrow[16 * ks + 4 * g]));
-            }
+            for (int i = 0; i < kTW; ++i)
+                if (jw + 16 * i + n == jh_new) {
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)
+                        a[i][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&newrow[16 * ks + 4 * g]));
+                }
         }
     }
 #pragma unroll
@@ -436,11 +442,11 @@ __global__ __launch_bounds__(256) void decode_scores_kernel(Dims dm, Tensor q, T
 // them back is cheaper than computing them again; with several queries per sequence the balance tips.)
 // grid (nb_cap/64, Hkv, B), 320 threads.  Thread t <= 256 scores kernel 256*bx - 1 + t
 // (one halo kernel to the left); threads 0..63 then pool blocks 64*bx + t.
-constexpr int kMaxParts = 256;                        // partials per head: contexts up to 262144 tokens
+constexpr int kMaxParts = 128;                        // partials per head (of >= 128 kernels): contexts up to 262144 tokens
 __global__ __launch_bounds__(320) void decode_scores_z_kernel(Dims dm, const int32_t *__restrict__ seqlens,
                                                              const float *__restrict__ zbuf,
                                                              const float2 *__restrict__ part,
-                                                             int32_t n_c_cap, int32_t n_part,
+                                                             int32_t n_c_cap, int32_t n_part, int32_t part_kernels,
                                                              float *__restrict__ R, int32_t nb_cap) {
     __shared__ float lse_h[16];
     __shared__ float rs[260];
@@ -465,7 +471,7 @@ __global__ __launch_bounds__(320) void decode_scores_z_kernel(Dims dm, const int
     const int L = query_row(dm, seqlens, bv, b, qi);
     const int n_vis = num_kernels(L);
     if (L < 1 || (int)blockIdx.x * 64 > (L - 1) / kBlock) return;            // no block of this chunk exists
-    const int np = (n_vis + 63) >> 6;                 // valid partials
+    const int np = (n_vis + part_kernels - 1) / part_kernels;   // valid partials
     // log-sum-exp per head: 16 lanes per head
     if (tid < 256) {
 #pragma unroll
@@ -872,7 +878,7 @@ static DecodeSelLayout decode_sel_layout(const Dims &dm) {
     int32_t n_c = num_kernels(dm.max_seqlen);
     l.n_c_cap = (n_c + 255) / 256 * 256;
     if (l.n_c_cap < 256) l.n_c_cap = 256;
-    l.n_part = l.n_c_cap / (64 * tiles_per_wave(dm.n_q == 1 ? 1 : kVerifyQT));
+    l.n_part = l.n_c_cap / (64 * (dm.n_q == 1 ? decode_tiles_per_wave(dm) : tiles_per_wave(kVerifyQT)));
     l.nb_cap = ((dm.max_seqlen + kBlock - 1) / kBlock + 63) / 64 * 64;
     const size_t rows = (size_t)dm.batch * dm.n_q;
     l.z_bytes = dm.n_q == 1 ? align256(rows * dm.Hq * l.n_c_cap * sizeof(float)) : 0;
@@ -902,20 +908,28 @@ int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seq
     const float2 *part_lse = dm.rho > 1 ? part_c : part;
     timing_begin("decode_logits_kernel", stream);
     const AppendArgs no_append = {q, q, q, q};                       // unused placeholders
-    if (dm.n_q == 1 && append)
-        hipLaunchKernelGGL((decode_logits_kernel<1, true>), dim3(l.n_part, dm.Hkv, dm.batch), dim3(256), 0, stream,
-                           dm, q, ck, seqlens, zbuf, l.n_c_cap, part, part_c, l.n_part, *append);
-    else if (dm.n_q == 1)
-        hipLaunchKernelGGL((decode_logits_kernel<1, false>), dim3(l.n_part, dm.Hkv, dm.batch), dim3(256), 0, stream,
-                           dm, q, ck, seqlens, zbuf, l.n_c_cap, part, part_c, l.n_part, no_append);
-    else
-        hipLaunchKernelGGL((decode_logits_kernel<kVerifyQT, false>), dim3(l.n_part, dm.Hkv, dm.batch * n_qt), dim3(256),
-                           0, stream, dm, q, ck, seqlens, nullptr, 0, part, part_c, l.n_part, no_append);
+    const bool tw4 = decode_tiles_per_wave(dm) == 4;
+    const dim3 grid1(l.n_part, dm.Hkv, dm.batch);
+#define INFLLMV2_LOGITS(APPEND, TW, ARG)                                                                        \
+    hipLaunchKernelGGL((decode_logits_kernel<1, APPEND, TW>), grid1, dim3(256), 0, stream, dm, q, ck, seqlens, \
+                       zbuf, l.n_c_cap, part, part_c, l.n_part, ARG)
+    if (dm.n_q == 1 && append) {
+        if (tw4) INFLLMV2_LOGITS(true, 4, *append);
+        else INFLLMV2_LOGITS(true, 2, *append);
+    } else if (dm.n_q == 1) {
+        if (tw4) INFLLMV2_LOGITS(false, 4, no_append);
+        else INFLLMV2_LOGITS(false, 2, no_append);
+    } else {
+        hipLaunchKernelGGL((decode_logits_kernel<kVerifyQT, false, tiles_per_wave(kVerifyQT)>),
+                           dim3(l.n_part, dm.Hkv, dm.batch * n_qt), dim3(256), 0, stream, dm, q, ck, seqlens, nullptr, 0,
+                           part, part_c, l.n_part, no_append);
+    }
+#undef INFLLMV2_LOGITS
     timing_end(stream);
     timing_begin("decode_scores_kernel", stream);
     if (dm.n_q == 1)
         hipLaunchKernelGGL(decode_scores_z_kernel, dim3(l.nb_cap / 64, dm.Hkv, dm.batch), dim3(320), 0, stream,
-                           dm, seqlens, zbuf, part_lse, l.n_c_cap, l.n_part, R, l.nb_cap);
+                           dm, seqlens, zbuf, part_lse, l.n_c_cap, l.n_part, 64 * decode_tiles_per_wave(dm), R, l.nb_cap);
     else
         hipLaunchKernelGGL(decode_scores_kernel<kVerifyQT>,
                            dim3(l.nb_cap / (16 * tiles_per_wave2(kVerifyQT)), dm.Hkv, dm.batch * n_qt), dim3(256), 0,

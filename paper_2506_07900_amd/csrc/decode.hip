@@ -532,23 +532,43 @@ __global__ __launch_bounds__(320) void decode_scores_z_kernel(Dims dm, const int
 //   1b. rank of the survivors among all survivors = rank among all thread maxima; gives tau
 //   2.  the n_pick best threads publish their elements >= tau; rank by counting among those
 constexpr int kPickThreads = 256, kPickMaxVPT = 16;
-constexpr int kPickMaxCand = kMaxTopk * kPickMaxVPT;
+// LDS of the top-k, carved out of the kernel's dynamic shared memory (16-byte aligned) so that its size
+// follows the call's top-k instead of the largest one supported.
 template <int kThreads>
 struct PickShared {
-    uint64_t tmax[kThreads];
-    uint64_t surv[kThreads / 64 * kMaxTopk];
-    uint64_t cand[kPickMaxCand];
-    uint64_t tau;
-    int n_cand;
-    int picked[kMaxTopk];
+    uint64_t *tmax;                                       // [kThreads] thread maxima, 64 per wavefront
+    uint64_t *top;                                        // [kWaves * topk + 4] per wavefront: its n_pick best (0 = none)
+    uint64_t *cand;                                       // [kWaves][cand_cap] per wavefront: elements that can still make it
+    int *picked;                                          // [topk]
+    int cand_cap;
+    __device__ PickShared(unsigned char *smem, int topk, int vpt) {
+        tmax = reinterpret_cast<uint64_t *>(smem);
+        top = tmax + kThreads;
+        cand = top + ((kThreads / 64 * topk + 4 + 1) & ~1);
+        cand_cap = (topk * vpt + 3) & ~3;
+        picked = reinterpret_cast<int *>(cand + kThreads / 64 * cand_cap);
+    }
 };
+static inline size_t pick_shared_bytes(int threads, int topk, int vpt) {
+    const size_t words = (size_t)threads + (((size_t)threads / 64 * topk + 4 + 1) & ~(size_t)1) +
+                         (size_t)threads / 64 * (((size_t)topk * vpt + 3) & ~(size_t)3);
+    return words * sizeof(uint64_t) + (size_t)topk * sizeof(int);
+}
 
 // Top-k of one row of block scores for a query at cache row L - 1 (L >= 1), by a whole workgroup of
 // kThreads threads; thread t passes the scores of blocks t, t + kThreads, ... in r.  The selected
 // blocks, ascending, go to `o` (a row of the block_idx output, padded with -1; may be null) and to
 // `sel` (LDS, may be null).  Returns their number.  Contains barriers: every thread calls it.
+//
+// Two levels.  Every wavefront finds the n_pick best of its own share on its own, synchronising with
+// nobody: rank its 64 thread maxima by counting; an element of its top n_pick can only sit in a
+// thread whose maximum is among the n_pick largest, and is at least tau, the n_pick-th largest
+// maximum; those threads publish their elements >= tau (a handful) and the wavefront ranks them by
+// counting.  After one workgroup barrier the (at most) kWaves * n_pick finalists are ranked the same
+// way.  A step that waits for the slowest wavefront costs more here than the arithmetic between two
+// of them, hence as few of those as possible.
 template <int kThreads, int kVPT>
-__device__ inline int pick_row(const Dims &dm, int L, const float (&r)[kVPT], PickShared<kThreads> &sh,
+__device__ inline int pick_row(const Dims &dm, int L, const float (&r)[kVPT], const PickShared<kThreads> &sh,
                                int32_t *__restrict__ o, int *sel) {
     constexpr int kWaves = kThreads / 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -559,15 +579,10 @@ __device__ inline int pick_row(const Dims &dm, int L, const float (&r)[kVPT], Pi
     const int jc_max = lo_local - 1;                                          // candidates: n_init..jc_max
     const int n_pick = n_sel - (n_init + (b_own - lo_local + 1));
     if (n_pick > 0) {                                                         // uniform over the workgroup
-        const int n_surv = (kWaves * n_pick + 3) & ~3;
-        const int cand_cap = n_pick * kVPT;
-        for (int i = tid; i < n_surv; i += kThreads) sh.surv[i] = 0ull;
-        for (int i = tid; i < cand_cap + 4; i += kThreads)
-            if (i < kPickMaxCand) sh.cand[i] = 0ull;
-        if (tid == 0) {
-            sh.tau = kPickValid;
-            sh.n_cand = 0;
-        }
+        const int n_top = (kWaves * n_pick + 3) & ~3;
+        uint64_t *wtop = sh.top + wave * n_pick, *wcand = sh.cand + wave * sh.cand_cap, *wmax = sh.tmax + 64 * wave;
+        if (lane < n_pick) wtop[lane] = 0ull;
+        if (wave == kWaves - 1 && lane < n_top - kWaves * n_pick) sh.top[kWaves * n_pick + lane] = 0ull;
         uint64_t el[kVPT], best = 0ull;
 #pragma unroll
         for (int s = 0; s < kVPT; ++s) {
@@ -578,31 +593,41 @@ __device__ inline int pick_row(const Dims &dm, int L, const float (&r)[kVPT], Pi
             best = el[s] > best ? el[s] : best;
         }
         const bool real = best >= kPickValid;
-        sh.tmax[tid] = best;
-        __syncthreads();
-        // 1a. rank inside the wavefront
-        const int wrank = count_larger(sh.tmax + 64 * wave, 64, best);
-        const bool survivor = real && wrank < n_pick;
-        if (survivor) sh.surv[wave * n_pick + wrank] = best;
-        __syncthreads();
-        // 1b. rank among all thread maxima (a thread that did not survive has n_pick better ones)
-        int trank = n_pick;
-        if (survivor) trank = count_larger(sh.surv, n_surv, best);
-        if (trank == n_pick - 1) sh.tau = best;
-        __syncthreads();
-        // 2. publish the elements that can still make it, then rank them by counting
-        if (trank < n_pick) {
-            const uint64_t tau = sh.tau;
+        wmax[lane] = best;
+        __builtin_amdgcn_wave_barrier();                  // same wavefront: LDS keeps the order
+        const int lrank = count_larger(wmax, 64, best);
+        const bool finalist = real && lrank < n_pick;
+        uint64_t tau = kPickValid;                        // the n_pick-th largest maximum, if there are that many real ones
+        const uint64_t who = __ballot(real && lrank == n_pick - 1);
+        if (who) {
+            const int src = __builtin_ctzll(who);
+            tau = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(best >> 32), src) << 32) |
+                  (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)best, src);
+        }
+        int n_cand = 0;                                   // <= n_pick * kVPT <= cand_cap
+        const uint64_t below = (1ull << lane) - 1ull;
 #pragma unroll
-            for (int s = 0; s < kVPT; ++s)
-                if (el[s] >= tau) sh.cand[atomicAdd(&sh.n_cand, 1)] = el[s];
+        for (int s = 0; s < kVPT; ++s) {
+            const bool pub = finalist && el[s] >= tau;
+            const uint64_t m = __ballot(pub);
+            if (pub) wcand[n_cand + __popcll(m & below)] = el[s];
+            n_cand += __popcll(m);
+        }
+        const int n_cand4 = (n_cand + 3) & ~3;
+        if (lane < n_cand4 - n_cand) wcand[n_cand + lane] = 0ull;
+        __builtin_amdgcn_wave_barrier();
+        for (int i = lane; i < n_cand; i += 64) {
+            const uint64_t e = wcand[i];
+            const int beaten = count_larger(wcand, n_cand4, e);
+            if (beaten < n_pick) wtop[beaten] = e;
         }
         __syncthreads();
-        const int n_cand = sh.n_cand;                                         // n_pick <= n_cand <= cand_cap
-        for (int i = tid; i < n_cand; i += kThreads) {
-            const uint64_t e = sh.cand[i];
-            const int beaten = count_larger(sh.cand, (n_cand + 3) & ~3, e);
-            if (beaten < n_pick) sh.picked[beaten] = (int)~(uint32_t)e;
+        if (tid < kWaves * n_pick) {                      // kWaves * n_pick <= kThreads: n_pick <= 64
+            const uint64_t e = sh.top[tid];
+            if (e >= kPickValid) {
+                const int beaten = count_larger(sh.top, n_top, e);
+                if (beaten < n_pick) sh.picked[beaten] = (int)~(uint32_t)e;
+            }
         }
         __syncthreads();
     }
@@ -630,7 +655,8 @@ template <int kVPT>
 __global__ __launch_bounds__(kPickThreads) void decode_pick_kernel(Dims dm, const int32_t *__restrict__ seqlens,
                                                                     const float *__restrict__ R, int32_t nb_cap,
                                                                     int32_t *__restrict__ block_idx) {
-    __shared__ __align__(16) PickShared<kPickThreads> sh;
+    extern __shared__ __align__(16) unsigned char pick_smem[];
+    const PickShared<kPickThreads> sh(pick_smem, dm.topk, kVPT);
     const int row = blockIdx.x, bv = row / dm.Hkv, h = row - bv * dm.Hkv;
     const int tid = threadIdx.x;
     const float *Rr = R + (int64_t)row * nb_cap;
@@ -808,7 +834,8 @@ __global__ __launch_bounds__(kPickThreads) void decode_pick_partial_kernel(Dims 
                                                                             int32_t *__restrict__ block_idx,
                                                                             float *__restrict__ o_part,
                                                                             float2 *__restrict__ ml_part) {
-    __shared__ __align__(16) PickShared<kPickThreads> sh;
+    extern __shared__ __align__(16) unsigned char pick_smem[];
+    const PickShared<kPickThreads> sh(pick_smem, dm.topk, kVPT);
     __shared__ int sel[kMaxTopk];
     const int cidx = blockIdx.x, h = blockIdx.y, bv = blockIdx.z;
     const int tid = threadIdx.x;
@@ -941,8 +968,9 @@ int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seq
         const dim3 grid(dm.topk, dm.Hkv, rows), block(kPickThreads);
         timing_begin("decode_pick_partial_kernel", stream);
 #define INFLLMV2_PICK_PARTIAL(VPT)                                                                                  \
-    hipLaunchKernelGGL(decode_pick_partial_kernel<VPT>, grid, block, 0, stream, dm, q, attend->k, attend->v, seqlens, \
-                       R, l.nb_cap, attend->tree_mask, block_idx, attend->o_part, attend->ml_part)
+    hipLaunchKernelGGL(decode_pick_partial_kernel<VPT>, grid, block, pick_shared_bytes(kPickThreads, dm.topk, VPT), \
+                       stream, dm, q, attend->k, attend->v, seqlens, R, l.nb_cap, attend->tree_mask, block_idx,     \
+                       attend->o_part, attend->ml_part)
         if (n_blocks <= kPickThreads * 4) INFLLMV2_PICK_PARTIAL(4);
         else if (n_blocks <= kPickThreads * 8) INFLLMV2_PICK_PARTIAL(8);
         else if (n_blocks <= kPickThreads * 12) INFLLMV2_PICK_PARTIAL(12);
@@ -954,13 +982,17 @@ int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seq
     const dim3 grid(rows * dm.Hkv), block(kPickThreads);
     timing_begin("decode_pick_kernel", stream);
     if (n_blocks <= kPickThreads * 4)
-        hipLaunchKernelGGL(decode_pick_kernel<4>, grid, block, 0, stream, dm, seqlens, R, l.nb_cap, block_idx);
+        hipLaunchKernelGGL(decode_pick_kernel<4>, grid, block, pick_shared_bytes(kPickThreads, dm.topk, 4), stream, dm,
+                           seqlens, R, l.nb_cap, block_idx);
     else if (n_blocks <= kPickThreads * 8)
-        hipLaunchKernelGGL(decode_pick_kernel<8>, grid, block, 0, stream, dm, seqlens, R, l.nb_cap, block_idx);
+        hipLaunchKernelGGL(decode_pick_kernel<8>, grid, block, pick_shared_bytes(kPickThreads, dm.topk, 8), stream, dm,
+                           seqlens, R, l.nb_cap, block_idx);
     else if (n_blocks <= kPickThreads * 12)
-        hipLaunchKernelGGL(decode_pick_kernel<12>, grid, block, 0, stream, dm, seqlens, R, l.nb_cap, block_idx);
+        hipLaunchKernelGGL(decode_pick_kernel<12>, grid, block, pick_shared_bytes(kPickThreads, dm.topk, 12), stream, dm,
+                           seqlens, R, l.nb_cap, block_idx);
     else
-        hipLaunchKernelGGL(decode_pick_kernel<16>, grid, block, 0, stream, dm, seqlens, R, l.nb_cap, block_idx);
+        hipLaunchKernelGGL(decode_pick_kernel<16>, grid, block, pick_shared_bytes(kPickThreads, dm.topk, 16), stream, dm,
+                           seqlens, R, l.nb_cap, block_idx);
     timing_end(stream);
     return (int)hipGetLastError();
 }

@@ -245,11 +245,16 @@ __global__ __launch_bounds__(256) void select_score_kernel(Dims dm, Tensor q, Te
         __syncthreads();
         for (int i = tid; i < C::kTokPerWg; i += 256) rs[i][0] = rs[i][kChunk];
     }
-    // blocks past the last scored chunk (only the local ones can be): no visible kernel
+    // Blocks past the last scored chunk (only the last ones of a token can be).  Of their kernels only
+    // the left neighbour of the first one, 4*j_done - 1 = the last kernel of the last chunk, can be
+    // visible: its score sits in the halo slot.  It decides when the token's own block is a candidate
+    // (no forced local blocks).
+    __syncthreads();
     const int j_done = ((nvis_wg + kChunk - 1) / kChunk) * 16;
     for (int i = tid; i < C::kTokPerWg * 4; i += 256) {
         const int tloc = i >> 2, tok = t0 + tloc, j = j_done + (i & 3);
-        if (tok < L && j <= tok / kBlock) R[(((int64_t)b * dm.Hkv + h) * dm.max_seqlen + tok) * nb_cap + j] = -INFINITY;
+        if (tok < L && j <= tok / kBlock)
+            R[(((int64_t)b * dm.Hkv + h) * dm.max_seqlen + tok) * nb_cap + j] = (i & 3) == 0 ? rs[tloc][0] : -INFINITY;
     }
 }
 

@@ -367,6 +367,11 @@ __global__ __launch_bounds__(256, 2) void select_score16_kernel(Dims dm, Tensor 
     finish(zB, 1, nt_all - 1);
 }
 
+// Tiles of 16 fine kernels in the fragment-major copy: those that hold a kernel of the longest sequence,
+// plus one.  A token's last candidate block can lie one tile past the last kernel of its sequence (none
+// of that tile's kernels is visible, but the block's left-neighbour kernel in the tile before can be), and
+// pass 2 walks that tile like any other: its loads have to stay inside the buffer, whatever they return.
+static int32_t fine_tiles_cap(const Dims &dm) { return (num_kernels(dm.max_seqlen) + 15) / 16 + 1; }
 static int32_t coarse_tiles_cap(const Dims &dm) {
     return dm.rho > 1 ? (num_coarse(num_kernels(dm.max_seqlen), dm.rho) + 15) / 16 : 0;
 }
@@ -378,7 +383,7 @@ static size_t coarse_tiles_bytes(const Dims &dm) {
 size_t select_prefill16_ws_bytes(const Dims &dm) {
     size_t lse = (size_t)dm.batch * dm.max_seqlen * dm.Hq * sizeof(float);
     lse = (lse + 255) / 256 * 256;
-    const size_t nt_cap = ((size_t)num_kernels(dm.max_seqlen) + 15) / 16;
+    const size_t nt_cap = (size_t)fine_tiles_cap(dm);
     size_t ckp = (size_t)dm.batch * dm.Hkv * nt_cap * 256 * sizeof(uint4);
     ckp = (ckp + 255) / 256 * 256;
     return lse + ckp + coarse_tiles_bytes(dm) + select_scores_bytes(dm) + select_shared_scores_bytes(dm);
@@ -388,7 +393,7 @@ int launch_select_prefill16(const Dims &dm, Tensor q, Tensor ck, const int32_t *
                             void *ws, hipStream_t stream) {
     size_t lse_bytes = (size_t)dm.batch * dm.max_seqlen * dm.Hq * sizeof(float);
     lse_bytes = (lse_bytes + 255) / 256 * 256;
-    const int32_t nt_cap = (num_kernels(dm.max_seqlen) + 15) / 16;
+    const int32_t nt_cap = fine_tiles_cap(dm);
     size_t ckp_bytes = (size_t)dm.batch * dm.Hkv * nt_cap * 256 * sizeof(uint4);
     ckp_bytes = (ckp_bytes + 255) / 256 * 256;
     float *lse2 = reinterpret_cast<float *>(ws);

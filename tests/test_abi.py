@@ -103,8 +103,9 @@ def test_workspace_validation(lib):
     prm = good_params()
     need = lib.infllmv2_workspace_bytes(binding.OP_SELECT_PREFILL, ctypes.byref(prm), 1, 4096)
     # fp32 log-sum-exp per (token, head) + fragment-major copy of the compressed keys (4 KiB per
-    # 16 kernels) + fp32 block scores per (token, kv head, block)
-    assert need == 4096 * 32 * 4 + 2 * 16 * 4096 + 2 * 4096 * 64 * 4
+    # 16 kernels: 254 kernels = 16 tiles, plus the tile a last candidate block may reach into) + fp32
+    # block scores per (token, kv head, block)
+    assert need == 4096 * 32 * 4 + 2 * 17 * 4096 + 2 * 4096 * 64 * 4
     assert lib.infllmv2_workspace_bytes(binding.OP_ATTN_PREFILL, ctypes.byref(prm), 1, 4096) == 2 * 64 * 32768
     assert lib.infllmv2_workspace_bytes(binding.OP_ATTN_DECODE, ctypes.byref(prm), 2, 4096) > 0
     assert lib.infllmv2_workspace_bytes(99, ctypes.byref(prm), 1, 4096) == 0

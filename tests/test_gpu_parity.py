@@ -152,6 +152,35 @@ def test_select_blocks_prefill_other_forced_counts(seqlens, Hq, Hkv, topk, force
     assert near <= max(2, tot // 200)
 
 
+@pytest.mark.parametrize("fill", [0, 255])
+@pytest.mark.parametrize("topk", [6, 30])
+@pytest.mark.parametrize("Hq,Hkv", [(32, 2), (8, 1), (2, 2)])
+def test_select_blocks_prefill_own_block_is_a_candidate(Hq, Hkv, topk, fill):
+    # no forced local blocks: a token's own block is ranked like any other, on the one kernel that
+    # reaches into it from the left (if the token sees it yet).  Lengths just past a multiple of 256
+    # put that block one 16-kernel tile (one 64-kernel chunk) past the last kernel of the sequence.
+    # The workspace starts as all zeros / all ones: a score the kernels leave unwritten shows up.
+    seqlens = [542, 282, 2072, 40, 257]
+    prm = binding.Params(Hq, Hkv, topk=topk, n_init_blocks=1, n_local_blocks=0)
+    oprm = oracle_params(prm)
+    q, k, v, T = make_batch(71, seqlens, Hq, Hkv, n_planted=3)
+    qd, kd, sl = to_dev(q), to_dev(k), dev_i32(seqlens)
+    ck = binding.compress_keys(prm, kd, sl, T)
+    ws = torch.full((binding.workspace_bytes(binding.OP_SELECT_PREFILL, prm, len(seqlens), T),), fill, dtype=torch.uint8,
+                    device="cuda")
+    idx = binding.select_blocks(prm, binding.MODE_PREFILL, qd, ck, sl, T, workspace=ws)
+    torch.cuda.synchronize()
+    ckb, idx_np = to_bits(ck), idx.cpu().numpy()
+    near = 0
+    for b, l in enumerate(seqlens):
+        want, margins, R = ref.select_blocks(q[b, :l], ckb[b, :, :ref.num_kernels(l, 32, 16)], np.arange(l, dtype=np.int32),
+                                             oprm, want_scores=True)
+        n, e, nt, hard = compare_selection(idx_np[b, :, :l], want, margins, R)
+        assert not hard, (b, hard[:3])
+        near += nt
+    assert near <= 2
+
+
 @pytest.mark.parametrize("seqlens,Hq,Hkv,topk,planted", PREFILL_CASES)
 def test_sparse_attn_prefill(seqlens, Hq, Hkv, topk, planted):
     print("case attn prefill", seqlens, Hq, Hkv, topk, flush=True)

@@ -9,7 +9,7 @@ import torch
 
 from oracle import ref
 from paper_2506_07900_amd import binding, synth
-from util import grad_err, out_err, OUT_TOL, compare_selection, lse_err, oracle_params, to_bits, to_dev
+from util import grad_err, logit_mag, out_err, OUT_TOL, compare_selection, lse_err, oracle_params, to_bits, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -698,6 +698,8 @@ def test_random_configurations_all_entry_points(seed, wide):
     seqlens = [int(rng.integers(1, 2600 if wide else 900)) for _ in range(B)]
     if seed % 3 == 0:
         seqlens[0] = int(rng.choice([31, 32, 63, 64, 65, 128, 129]))
+    if seed % 3 == 1:                                                 # around tile (256) and kernel (16) boundaries
+        seqlens[-1] = int(rng.choice([255, 256, 257, 271, 272, 287, 288, 513, 527, 528, 543]))
     rho = 1
     if G == 16 and (n_init + n_local) * 64 >= 128 and seed % 2:
         rho = int(rng.choice([2, 4])) if (n_init + n_local) * 64 >= 8 * 16 else 2
@@ -731,7 +733,7 @@ def test_random_configurations_all_entry_points(seed, wide):
         pos = np.arange(l, dtype=np.int32)
         wo, wl = ref.sparse_attn(q[b, :l], k[b, :, :l], v[b, :, :l], pos, idx_ref[b, :, :l], oprm)
         assert out_err(out[b, :l].double().cpu().numpy(), wo) <= 1.0
-        assert lse_err(lse[b, :l].double().cpu().numpy(), wl) <= 1.0
+        assert lse_err(lse[b, :l].double().cpu().numpy(), wl, logit_mag(q[b, :l], k[b, :, :l], prm.softmax_scale)) <= 1.0
         wq, wk, wv, mq, mk, mv = ref.sparse_attn_bwd(q[b, :l], k[b, :, :l], v[b, :, :l], do[b, :l], pos, idx_ref[b, :, :l],
                                                      oprm, want_mag=True)
         assert grad_err(dq[b, :l].double().cpu().numpy(), wq, mq) <= 1.0
@@ -761,7 +763,7 @@ def test_random_configurations_all_entry_points(seed, wide):
         assert not hard, (b, hard)
         wo, wl = ref.sparse_attn(q1[b], k[b, :, :l], v[b, :, :l], pos, i1[b], oprm)
         assert out_err(o1[b].double().cpu().numpy(), wo) <= 1.0
-        assert lse_err(l1[b].double().cpu().numpy(), wl[0]) <= 1.0
+        assert lse_err(l1[b].double().cpu().numpy(), wl[0], logit_mag(q1[b], k[b, :, :l], prm.softmax_scale)[0]) <= 1.0
     # verification of the last n tokens with a random tree, and the query-block-shared comparison variant
     n = int(rng.integers(1, 65 if wide else 9))
     qn = np.zeros((B, n, Hq, 128), np.uint16)
@@ -784,7 +786,7 @@ def test_random_configurations_all_entry_points(seed, wide):
         assert not hard, (b, hard)
         wo, wl = ref.sparse_attn_tree(qn[b], k[b, :, :l], v[b, :, :l], iv[b], masks[b], l - n, oprm)
         assert out_err(ov[b].double().cpu().numpy(), wo) <= 1.0
-        assert lse_err(lv[b].double().cpu().numpy(), wl) <= 1.0
+        assert lse_err(lv[b].double().cpu().numpy(), wl, logit_mag(qn[b], k[b, :, :l], prm.softmax_scale)) <= 1.0
     # the same verification step in one call, from the state before the drafts: equal bit for bit
     k0, v0 = k.copy(), v.copy()
     kn = np.zeros((B, Hkv, n, 128), np.uint16)
@@ -813,4 +815,4 @@ def test_random_configurations_all_entry_points(seed, wide):
             per_token = np.repeat(isd[b, :, :want.shape[1]], 64, axis=1)[:, :l]
             wo, wl = ref.sparse_attn(q[b, :l], k[b, :, :l], v[b, :, :l], np.arange(l, dtype=np.int32), per_token, oprm)
             assert out_err(osd[b, :l].double().cpu().numpy(), wo) <= 1.0
-            assert lse_err(lsd[b, :l].double().cpu().numpy(), wl) <= 1.0
+            assert lse_err(lsd[b, :l].double().cpu().numpy(), wl, logit_mag(q[b, :l], k[b, :, :l], prm.softmax_scale)) <= 1.0

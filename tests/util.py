@@ -44,15 +44,31 @@ def out_err(got, want):
     return float(np.max(np.abs(got - want) / tol)) if want.size else 0.0
 
 
-def lse_err(got, want):
+def lse_err(got, want, mag=None):
     """Largest log-sum-exp error in units of its tolerance (<= 1 passes).  The tolerance is the
     stated 1e-5 absolute, widened to 2^-20 * |LSE| (16 fp32 ulps) where |LSE| is so large that
     fp32 cannot hold 1e-5: heavy-tailed keys give |LSE| in the hundreds, whose ulp alone is
-    1.5e-5, and the dominant logit is a 128-term fp32 sum (rounding grows like sqrt(128) ulps)."""
+    1.5e-5, and the dominant logit is a 128-term fp32 sum (rounding grows like sqrt(128) ulps).
+    `mag` (see logit_mag) widens it further to 2^-20 * mag: the rounding of that sum scales with the
+    size of its terms, not of its result, and with heavy-tailed keys the terms cancel."""
     got = np.asarray(got, np.float64)
     want = np.asarray(want, np.float64)
     tol = np.maximum(LSE_TOL, 2.0 ** -20 * np.abs(want))
+    if mag is not None:
+        tol = np.maximum(tol, 2.0 ** -20 * np.asarray(mag, np.float64))
     return float(np.max(np.abs(got - want) / tol)) if want.size else 0.0
+
+
+def logit_mag(q_bits, k_bits, scale):
+    """Bound on the size of the terms of any attention logit of a query row: scale * |q| * max_t |k_t|
+    (Cauchy-Schwarz over the head dimension).  q_bits [n, Hq, d], k_bits [Hkv, l, d] (bf16 bit
+    patterns) -> [n, Hq].  About 11 for N(0,1) data with d = 128 (2^-20 * 11 = 1e-5: no change there)."""
+    from paper_2506_07900_amd import synth
+    q = synth.bf16_bits_to_f32(q_bits).astype(np.float64)
+    k = synth.bf16_bits_to_f32(k_bits).astype(np.float64)
+    G = q.shape[1] // k.shape[0]
+    kmax = np.sqrt((k * k).sum(-1)).max(-1)                       # [Hkv]
+    return scale * np.sqrt((q * q).sum(-1)) * np.repeat(kmax, G)[None, :]
 
 
 def to_dev(bits):

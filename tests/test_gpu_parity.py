@@ -707,6 +707,12 @@ def test_random_configurations_all_entry_points(seed, wide):
     prm = binding.Params(Hq, Hkv, topk=topk, n_init_blocks=n_init, n_local_blocks=n_local, lse_coarse_ratio=rho)
     oprm = oracle_params(prm)
     q, k, v, T = make_batch(200 + seed, seqlens, Hq, Hkv, n_planted=int(rng.integers(0, 4)), heavy=(0,) if seed % 4 == 0 else ())
+    if seed % 5 == 0:                                                 # buffers larger than every sequence
+        extra = int(rng.integers(1, 400))
+        q = np.concatenate([q, np.zeros((B, extra, Hq, 128), np.uint16)], axis=1)
+        k = np.concatenate([k, np.zeros((B, Hkv, extra, 128), np.uint16)], axis=2)
+        v = np.concatenate([v, np.zeros((B, Hkv, extra, 128), np.uint16)], axis=2)
+        T += extra
     qd, kd, vd, sl = to_dev(q), to_dev(k), to_dev(v), dev_i32(seqlens)
     # prefill: compress, select, attend
     ck = binding.compress_keys(prm, kd, sl, T)

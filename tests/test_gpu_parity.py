@@ -713,7 +713,10 @@ def test_random_configurations_all_entry_points(seed, wide):
         k = np.concatenate([k, np.zeros((B, Hkv, extra, 128), np.uint16)], axis=2)
         v = np.concatenate([v, np.zeros((B, Hkv, extra, 128), np.uint16)], axis=2)
         T += extra
-    qd, kd, vd, sl = to_dev(q), to_dev(k), to_dev(v), dev_i32(seqlens)
+    # every seventh case: caches stored token-major and queries head-major (the ABI takes any strides with
+    # a contiguous head_dim axis)
+    lay = (lambda x: x.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)) if seed % 7 == 3 else (lambda x: x)
+    qd, kd, vd, sl = lay(to_dev(q)), lay(to_dev(k)), lay(to_dev(v)), dev_i32(seqlens)
     # prefill: compress, select, attend
     ck = binding.compress_keys(prm, kd, sl, T)
     idx = binding.select_blocks(prm, binding.MODE_PREFILL, qd, ck, sl, T)
@@ -733,7 +736,7 @@ def test_random_configurations_all_entry_points(seed, wide):
     idx_d = torch.from_numpy(idx_ref).cuda()
     out, lse = binding.sparse_attn_prefill(prm, qd, kd, vd, sl, T, idx_d)
     do = synth.f32_to_bf16_bits(rng.standard_normal((B, T, Hq, 128), dtype=np.float32))
-    dq, dk, dv = binding.sparse_attn_bwd(prm, qd, kd, vd, out, to_dev(do), lse, sl, T, idx_d)
+    dq, dk, dv = binding.sparse_attn_bwd(prm, qd, kd, vd, out, lay(to_dev(do)), lse, sl, T, idx_d)
     torch.cuda.synchronize()
     for b, l in enumerate(seqlens):
         pos = np.arange(l, dtype=np.int32)
@@ -754,7 +757,7 @@ def test_random_configurations_all_entry_points(seed, wide):
     for b in range(B):
         k0[b, :, last[b]] = 0
         v0[b, :, last[b]] = 0
-    kc, vc = to_dev(k0), to_dev(v0)
+    kc, vc = lay(to_dev(k0)), lay(to_dev(v0))
     ck1 = binding.compress_keys(prm, kc, dev_i32([l - 1 for l in seqlens]), T)
     i1, o1, l1 = binding.decode_step(prm, to_dev(q1), to_dev(kn), to_dev(vn), kc, vc, ck1, sl, T)
     torch.cuda.synchronize()
@@ -802,7 +805,7 @@ def test_random_configurations_all_entry_points(seed, wide):
             kn[b], vn[b] = k[b, :, l - n:l], v[b, :, l - n:l]
             k0[b, :, l - n:l] = 0
             v0[b, :, l - n:l] = 0
-    kc, vc = to_dev(k0), to_dev(v0)
+    kc, vc = lay(to_dev(k0)), lay(to_dev(v0))
     ckv = binding.compress_keys(prm, kc, dev_i32([l - n if l >= n else l for l in seqlens]), T)
     i2, o2, l2 = binding.verify_step(prm, to_dev(qn), to_dev(kn), to_dev(vn), kc, vc, ckv, sl, T, tree_mask=dev_masks(masks))
     torch.cuda.synchronize()

@@ -683,6 +683,69 @@ def test_sparse_attn_prefill_shared(seqlens, Hq, Hkv, topk, planted):
         assert bool((out[b, l:] == 0).all())
 
 
+# ------------------------------------------------------------------ lengths outside [0, max_seqlen]
+
+def test_out_of_range_lengths_are_clamped():
+    # the interface clamps every entry of seqlens to [0, max_seqlen]; a decode step appends nothing for
+    # an entry outside [1, max_seqlen]
+    Hq, Hkv, topk = 32, 2, 8
+    true_len = [0, 0, 700, 300]
+    prm = binding.Params(Hq, Hkv, topk=topk)
+    oprm = oracle_params(prm)
+    q, k, v, T = make_batch(91, true_len, Hq, Hkv, n_planted=3)          # T = 700
+    B = len(true_len)
+    given = dev_i32([-3, 0, T + 50, 300])
+    qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+    ck = binding.compress_keys(prm, kd, given, T)
+    idx = binding.select_blocks(prm, binding.MODE_PREFILL, qd, ck, given, T)
+    out, lse = binding.sparse_attn_prefill(prm, qd, kd, vd, given, T, idx)
+    rng = np.random.default_rng(12)
+    do = synth.f32_to_bf16_bits(rng.standard_normal((B, T, Hq, 128), dtype=np.float32))
+    dq, dk, dv = binding.sparse_attn_bwd(prm, qd, kd, vd, out, to_dev(do), lse, given, T, idx)
+    torch.cuda.synchronize()
+    ckb, idx_np = to_bits(ck), idx.cpu().numpy()
+    for b, l in enumerate(true_len):
+        assert bool((out[b, l:] == 0).all()) and bool((dq[b, l:] == 0).all()) and bool((dk[b, :, l:] == 0).all())
+        assert np.all(idx_np[b, :, l:] == -1)
+        if l == 0:
+            assert not ckb[b].any()
+            continue
+        pos = np.arange(l, dtype=np.int32)
+        _, ck_ref = ref.compress_keys(k[b, :, :l], oprm)
+        assert np.array_equal(ckb[b, :, :ck_ref.shape[1]], ck_ref) and not ckb[b, :, ck_ref.shape[1]:].any()
+        want, margins, R = ref.select_blocks(q[b, :l], ck_ref, pos, oprm, want_scores=True)
+        n, e, nt, hard = compare_selection(idx_np[b, :, :l], want, margins, R)
+        assert not hard, (b, hard[:3])
+        wo, wl = ref.sparse_attn(q[b, :l], k[b, :, :l], v[b, :, :l], pos, idx_np[b, :, :l], oprm)
+        assert out_err(out[b, :l].double().cpu().numpy(), wo) <= 1.0 and lse_err(lse[b, :l].double().cpu().numpy(), wl) <= 1.0
+        wq, wk, wv, mq, mk, mv = ref.sparse_attn_bwd(q[b, :l], k[b, :, :l], v[b, :, :l], do[b, :l], pos, idx_np[b, :, :l], oprm,
+                                                     want_mag=True)
+        assert grad_err(dq[b, :l].double().cpu().numpy(), wq, mq) <= 1.0
+        assert grad_err(dk[b, :, :l].double().cpu().numpy(), wk, mk) <= 1.0
+        assert grad_err(dv[b, :, :l].double().cpu().numpy(), wv, mv) <= 1.0
+    # one decode step with the same lengths: sequences 0-2 append nothing (2 decodes at position T - 1 on
+    # the cache as it is), sequence 3 appends its row 299 again
+    q1 = np.stack([q[b, max(l, 1) - 1] for b, l in enumerate(true_len)])[:, None]
+    kn = np.stack([k[b, :, max(l, 1) - 1] for b, l in enumerate(true_len)])[:, :, None]
+    vn = np.stack([v[b, :, max(l, 1) - 1] for b, l in enumerate(true_len)])[:, :, None]
+    kn[2], vn[2] = 0x3F80, 0x3F80                                         # would be visible if it were appended
+    kc, vc = to_dev(k), to_dev(v)
+    i1, o1, l1 = binding.decode_step(prm, to_dev(q1), to_dev(kn), to_dev(vn), kc, vc, ck, given, T)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(kc), k) and np.array_equal(to_bits(vc), v) and np.array_equal(to_bits(ck), ckb)
+    i1 = i1.cpu().numpy()
+    for b, l in enumerate(true_len):
+        if l == 0:
+            assert np.all(i1[b] == -1) and bool((o1[b] == 0).all()) and bool(torch.isneginf(l1[b]).all())
+            continue
+        pos = np.array([l - 1], np.int32)
+        want, margins, R = ref.select_blocks(q1[b], ckb[b, :, :ref.num_kernels(l, 32, 16)], pos, oprm, want_scores=True)
+        n, e, nt, hard = compare_selection(i1[b], want, margins, R)
+        assert not hard, (b, hard)
+        wo, wl = ref.sparse_attn(q1[b], k[b, :, :l], v[b, :, :l], pos, i1[b], oprm)
+        assert out_err(o1[b].double().cpu().numpy(), wo) <= 1.0 and lse_err(l1[b].double().cpu().numpy(), wl[0]) <= 1.0
+
+
 # ------------------------------------------------------------------ seeded random configurations, every entry point
 
 @pytest.mark.parametrize("seed,wide", [(s, False) for s in range(24)] + [(s, True) for s in range(6)])

@@ -8,7 +8,7 @@ import torch
 
 from oracle import ref
 from paper_2506_07900_amd import binding, synth
-from util import OUT_TOL, compare_selection, lse_err, oracle_params, to_bits, to_dev
+from util import OUT_TOL, compare_selection, logit_mag, lse_err, oracle_params, out_err, to_bits, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -259,6 +259,112 @@ def test_verify_128k_steps():
         assert eo <= OUT_TOL and el <= 1.0
     print("verification at 128K: %d rows, %d exact, %d near-tie" % (tot, exact, near), flush=True)
     assert near <= 2
+
+
+def long_context_case(rng, seed):
+    """Random shape, forced counts, top-k and cached lengths of 1000 to 140000 tokens (half of them a few
+    tokens around a power of two), caches of random keys (heavy-tailed for every fourth seed)."""
+    G, Hkv = int(rng.choice([1, 2, 4, 8, 16])), int(rng.choice([1, 2]))
+    Hq = G * Hkv
+    n_init, n_local = int(rng.integers(0, 3)), int(rng.integers(0, 4))
+    topk = int(rng.integers(max(1, n_init + n_local), 65 if seed % 3 == 0 else 20))
+    B = int(rng.integers(1, 5))
+    lens = []
+    for b in range(B):
+        l = int(rng.integers(1000, 140000))
+        if rng.random() < 0.5:
+            l = int(rng.choice([256, 4096, 16384, 65536, 131072])) + int(rng.choice([-17, -16, -1, 0, 1, 15, 16, 17, 31, 32, 33, 63, 64, 65]))
+        lens.append(max(l, 1))
+    rho = 1
+    if G == 16 and (n_init + n_local) * 64 >= 128 and seed % 2:
+        rho = int(rng.choice([2, 4]))
+    cap = max(lens) + int(rng.integers(0, 300))
+    print("case long", seed, dict(G=G, Hkv=Hkv, topk=topk, n_init=n_init, n_local=n_local, lens=lens, cap=cap, rho=rho), flush=True)
+    prm = binding.Params(Hq, Hkv, topk=topk, n_init_blocks=n_init, n_local_blocks=n_local, lse_coarse_ratio=rho)
+    oprm = oracle_params(prm)
+    k = np.zeros((B, Hkv, cap, 128), np.uint16)
+    v = np.zeros_like(k)
+    for b, l in enumerate(lens):
+        kk = rng.standard_normal((Hkv, l, 128), dtype=np.float32)
+        if seed % 4 == 0 and b == 0:
+            kk *= np.exp(rng.standard_normal((Hkv, l, 1), dtype=np.float32))
+        k[b, :, :l] = synth.f32_to_bf16_bits(kk)
+        v[b, :, :l] = synth.f32_to_bf16_bits(rng.standard_normal((Hkv, l, 128), dtype=np.float32))
+    return prm, oprm, B, Hq, Hkv, lens, cap, k, v
+
+
+@pytest.mark.parametrize("seed", list(range(8)))
+def test_decode_step_long_contexts_random(seed):
+    # one decode step in one call on random long contexts (other top-k dispatch widths, boundary lengths,
+    # forced counts including none, approximate LSE) against the oracle
+    rng = np.random.default_rng(70000 + seed)
+    prm, oprm, B, Hq, Hkv, lens, cap, k, v = long_context_case(rng, seed)
+    q1 = synth.f32_to_bf16_bits(rng.standard_normal((B, 1, Hq, 128), dtype=np.float32))
+    kn = np.stack([k[b, :, l - 1] for b, l in enumerate(lens)])[:, :, None]
+    vn = np.stack([v[b, :, l - 1] for b, l in enumerate(lens)])[:, :, None]
+    k0, v0 = k.copy(), v.copy()
+    for b, l in enumerate(lens):
+        k0[b, :, l - 1] = 0
+        v0[b, :, l - 1] = 0
+    kc, vc = to_dev(k0), to_dev(v0)
+    sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    ck = binding.compress_keys(prm, kc, sl - 1, cap)
+    i1, o1, l1 = binding.decode_step(prm, to_dev(q1), to_dev(kn), to_dev(vn), kc, vc, ck, sl, cap)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(kc), k) and np.array_equal(to_bits(vc), v)
+    i1, ckb = i1.cpu().numpy(), to_bits(ck)
+    for b, l in enumerate(lens):
+        pos = np.array([l - 1], np.int32)
+        _, ck_ref = ref.compress_keys(k[b, :, :l], oprm)
+        assert np.array_equal(ckb[b, :, :ck_ref.shape[1]], ck_ref), "ck"
+        want, margins, R = ref.select_blocks(q1[b], ck_ref, pos, oprm, want_scores=True)
+        n, e, nt, hard = compare_selection(i1[b], want, margins, R)
+        assert not hard, (b, hard)
+        wo, wl = ref.sparse_attn(q1[b], k[b, :, :l], v[b, :, :l], pos, i1[b], oprm)
+        assert out_err(o1[b].double().cpu().numpy(), wo) <= 1.0, "out"
+        assert lse_err(l1[b].double().cpu().numpy(), wl[0], logit_mag(q1[b], k[b, :, :l], prm.softmax_scale)[0]) <= 1.0, "lse"
+
+
+@pytest.mark.parametrize("seed", list(range(6)))
+def test_verify_step_long_contexts_random(seed):
+    # one verification step in one call (1 to 64 drafted tokens, random tree) on random long contexts
+    rng = np.random.default_rng(90000 + seed)
+    prm, oprm, B, Hq, Hkv, lens, cap, k, v = long_context_case(rng, seed)
+    n = int(rng.integers(1, 65))
+    lens = [max(l, n) for l in lens]
+    qn = synth.f32_to_bf16_bits(rng.standard_normal((B, n, Hq, 128), dtype=np.float32))
+    masks = np.zeros((B, n), np.uint64)
+    for b in range(B):
+        parent = [-1] + [int(rng.integers(0, t)) for t in range(1, n)]
+        for t in range(n):
+            a = t
+            while a >= 0:
+                masks[b, t] |= np.uint64(1) << np.uint64(a)
+                a = parent[a]
+    kn = np.stack([k[b, :, l - n:l] for b, l in enumerate(lens)])
+    vn = np.stack([v[b, :, l - n:l] for b, l in enumerate(lens)])
+    k0, v0 = k.copy(), v.copy()
+    for b, l in enumerate(lens):
+        k0[b, :, l - n:l] = 0
+        v0[b, :, l - n:l] = 0
+    kc, vc = to_dev(k0), to_dev(v0)
+    sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    ck = binding.compress_keys(prm, kc, sl - n, cap)
+    md = torch.from_numpy(masks.view(np.int64)).cuda()
+    i1, o1, l1 = binding.verify_step(prm, to_dev(qn), to_dev(kn), to_dev(vn), kc, vc, ck, sl, cap, tree_mask=md)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(kc), k) and np.array_equal(to_bits(vc), v)
+    i1, ckb = i1.cpu().numpy(), to_bits(ck)
+    for b, l in enumerate(lens):
+        pos = np.arange(l - n, l, dtype=np.int32)
+        _, ck_ref = ref.compress_keys(k[b, :, :l], oprm)
+        assert np.array_equal(ckb[b, :, :ck_ref.shape[1]], ck_ref), "ck"
+        want, margins, R = ref.select_blocks(qn[b], ck_ref, pos, oprm, want_scores=True)
+        nn, e, nt, hard = compare_selection(i1[b], want, margins, R)
+        assert not hard, (b, hard[:2])
+        wo, wl = ref.sparse_attn_tree(qn[b], k[b, :, :l], v[b, :, :l], i1[b], masks[b], l - n, oprm)
+        assert out_err(o1[b].double().cpu().numpy(), wo) <= 1.0, "out"
+        assert lse_err(l1[b].double().cpu().numpy(), wl, logit_mag(qn[b], k[b, :, :l], prm.softmax_scale)) <= 1.0, "lse"
 
 
 def test_decode_graph_replays_match_eager():

@@ -279,6 +279,8 @@ def long_context_case(rng, seed):
     if G == 16 and (n_init + n_local) * 64 >= 128 and seed % 2:
         rho = int(rng.choice([2, 4]))
     cap = max(lens) + int(rng.integers(0, 300))
+    if seed >= 1000:                                  # the largest buffers the decode entry points take
+        cap = 262144
     print("case long", seed, dict(G=G, Hkv=Hkv, topk=topk, n_init=n_init, n_local=n_local, lens=lens, cap=cap, rho=rho), flush=True)
     prm = binding.Params(Hq, Hkv, topk=topk, n_init_blocks=n_init, n_local_blocks=n_local, lse_coarse_ratio=rho)
     oprm = oracle_params(prm)
@@ -293,7 +295,7 @@ def long_context_case(rng, seed):
     return prm, oprm, B, Hq, Hkv, lens, cap, k, v
 
 
-@pytest.mark.parametrize("seed", list(range(8)))
+@pytest.mark.parametrize("seed", list(range(8)) + [1000, 1001])
 def test_decode_step_long_contexts_random(seed):
     # one decode step in one call on random long contexts (other top-k dispatch widths, boundary lengths,
     # forced counts including none, approximate LSE) against the oracle
@@ -325,7 +327,7 @@ def test_decode_step_long_contexts_random(seed):
         assert lse_err(l1[b].double().cpu().numpy(), wl[0], logit_mag(q1[b], k[b, :, :l], prm.softmax_scale)[0]) <= 1.0, "lse"
 
 
-@pytest.mark.parametrize("seed", list(range(6)))
+@pytest.mark.parametrize("seed", list(range(6)) + [1000])
 def test_verify_step_long_contexts_random(seed):
     # one verification step in one call (1 to 64 drafted tokens, random tree) on random long contexts
     rng = np.random.default_rng(90000 + seed)

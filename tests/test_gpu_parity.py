@@ -181,6 +181,37 @@ def test_select_blocks_prefill_own_block_is_a_candidate(Hq, Hkv, topk, fill):
     assert near <= 2
 
 
+@pytest.mark.parametrize("cap", [20000, 40000, 70000, 132000])
+@pytest.mark.parametrize("Hq,Hkv,n_local", [(16, 1, 2), (16, 1, 0), (4, 1, 1)])
+def test_select_blocks_prefill_long_capacity(Hq, Hkv, n_local, cap):
+    # the top-k kernel is chosen by the capacity of the buffers (blocks per lane: 8 up to 32768 tokens, 16 up
+    # to 65536, 32 up to 131072, above that a generic scan); short sequences in long buffers reach every one
+    seqlens, topk = [5000, 257], 16
+    prm = binding.Params(Hq, Hkv, topk=topk, n_init_blocks=1, n_local_blocks=n_local)
+    oprm = oracle_params(prm)
+    q, k, v, T = make_batch(83, seqlens, Hq, Hkv, n_planted=5)
+    B = len(seqlens)
+    qd = torch.zeros((B, cap, Hq, 128), dtype=torch.bfloat16, device="cuda")
+    kd = torch.zeros((B, Hkv, cap, 128), dtype=torch.bfloat16, device="cuda")
+    qd[:, :T].copy_(to_dev(q))
+    kd[:, :, :T].copy_(to_dev(k))
+    sl = dev_i32(seqlens)
+    ck = binding.compress_keys(prm, kd, sl, cap)
+    idx = binding.select_blocks(prm, binding.MODE_PREFILL, qd, ck, sl, cap)
+    torch.cuda.synchronize()
+    ckb = to_bits(ck)
+    near = 0
+    for b, l in enumerate(seqlens):
+        idx_b = idx[b, :, :l].cpu().numpy()
+        assert bool((idx[b, :, l:] == -1).all())
+        want, margins, R = ref.select_blocks(q[b, :l], ckb[b, :, :ref.num_kernels(l, 32, 16)], np.arange(l, dtype=np.int32),
+                                             oprm, want_scores=True)
+        n, e, nt, hard = compare_selection(idx_b, want, margins, R)
+        assert not hard, (b, hard[:3])
+        near += nt
+    assert near <= 2
+
+
 @pytest.mark.parametrize("seqlens,Hq,Hkv,topk,planted", PREFILL_CASES)
 def test_sparse_attn_prefill(seqlens, Hq, Hkv, topk, planted):
     print("case attn prefill", seqlens, Hq, Hkv, topk, flush=True)

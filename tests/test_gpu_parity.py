@@ -182,11 +182,12 @@ def test_select_blocks_prefill_own_block_is_a_candidate(Hq, Hkv, topk, fill):
 
 
 @pytest.mark.parametrize("cap", [20000, 40000, 70000, 132000])
-@pytest.mark.parametrize("Hq,Hkv,n_local", [(16, 1, 2), (16, 1, 0), (4, 1, 1)])
-def test_select_blocks_prefill_long_capacity(Hq, Hkv, n_local, cap):
+@pytest.mark.parametrize("Hq,Hkv,n_local,topk", [(16, 1, 2, 16), (16, 1, 0, 16), (4, 1, 1, 16), (16, 1, 1, 48), (16, 1, 1, 64)])
+def test_select_blocks_prefill_long_capacity(Hq, Hkv, n_local, topk, cap):
     # the top-k kernel is chosen by the capacity of the buffers (blocks per lane: 8 up to 32768 tokens, 16 up
-    # to 65536, 32 up to 131072, above that a generic scan); short sequences in long buffers reach every one
-    seqlens, topk = [5000, 257], 16
+    # to 65536, 32 up to 131072, above that, or when top-k times blocks per lane needs more than 64 KB of LDS,
+    # a generic scan); short sequences in long buffers reach every one
+    seqlens = [5000, 257]
     prm = binding.Params(Hq, Hkv, topk=topk, n_init_blocks=1, n_local_blocks=n_local)
     oprm = oracle_params(prm)
     q, k, v, T = make_batch(83, seqlens, Hq, Hkv, n_planted=5)

@@ -82,7 +82,8 @@ __device__ inline void load_query_operands(const Dims &dm, const Tensor &q, int 
 // tiles per wave mean fewer workgroups and fewer log-sum-exp partials for part 2 to merge (every
 // workgroup of part 2 reads all partials of its heads); fewer tiles spread a lone step over more compute
 // units.  Measured at 128K context, plain decode, 1 / 2 / 4 tiles: 21.6 / 21.1 / 21.6 us per step for
-// one sequence, 27.2 / 26.8 / 25.8 us for the ragged batch of 8, 73 / 62 / 61 us for 32 sequences;
+// one sequence, 27.2 / 26.8 / 25.8 us for the ragged batch of 8, 73 / 62 / 61 us for 32 sequences (eight
+// tiles: 63 us);
 // verification (4 to 64 drafted tokens): under 10 % between them.
 constexpr int kVerifyQT = 4;
 __host__ __device__ constexpr int tiles_per_wave(int qt) { return 2; }                   // part 1, verification

@@ -715,6 +715,41 @@ def test_sparse_attn_prefill_shared(seqlens, Hq, Hkv, topk, planted):
         assert bool((out[b, l:] == 0).all())
 
 
+@pytest.mark.parametrize("B", [4, 17])
+def test_decode_step_many_sequences(B):
+    # the decode selection covers more kernels per workgroup from 4 and from 16 sequences on: one step on
+    # a ragged batch, every sequence against the oracle (lengths include steps that complete a kernel)
+    Hq, Hkv, topk = 32, 2, 8
+    prm = binding.Params(Hq, Hkv, topk=topk)
+    oprm = oracle_params(prm)
+    rng = np.random.default_rng(77)
+    lens = [int(rng.integers(40, 5000)) for _ in range(B)]
+    lens[0], lens[1], lens[2] = 4128, 48, 1025                              # 4128 and 48 complete a kernel
+    q, k, v, T = make_batch(97, lens, Hq, Hkv, n_planted=3)
+    q1 = np.stack([q[b, l - 1] for b, l in enumerate(lens)])[:, None]
+    kn = np.stack([k[b, :, l - 1] for b, l in enumerate(lens)])[:, :, None]
+    vn = np.stack([v[b, :, l - 1] for b, l in enumerate(lens)])[:, :, None]
+    k0, v0 = k.copy(), v.copy()
+    for b, l in enumerate(lens):
+        k0[b, :, l - 1] = 0
+        v0[b, :, l - 1] = 0
+    kc, vc, sl = to_dev(k0), to_dev(v0), dev_i32(lens)
+    ck = binding.compress_keys(prm, kc, sl - 1, T)
+    i1, o1, l1 = binding.decode_step(prm, to_dev(q1), to_dev(kn), to_dev(vn), kc, vc, ck, sl, T)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(kc), k) and np.array_equal(to_bits(vc), v)
+    i1, ckb = i1.cpu().numpy(), to_bits(ck)
+    for b, l in enumerate(lens):
+        pos = np.array([l - 1], np.int32)
+        _, ck_ref = ref.compress_keys(k[b, :, :l], oprm)
+        assert np.array_equal(ckb[b, :, :ck_ref.shape[1]], ck_ref), b
+        want, margins, R = ref.select_blocks(q1[b], ck_ref, pos, oprm, want_scores=True)
+        n, e, nt, hard = compare_selection(i1[b], want, margins, R)
+        assert not hard, (b, hard)
+        wo, wl = ref.sparse_attn(q1[b], k[b, :, :l], v[b, :, :l], pos, i1[b], oprm)
+        assert out_err(o1[b].double().cpu().numpy(), wo) <= 1.0 and lse_err(l1[b].double().cpu().numpy(), wl[0]) <= 1.0
+
+
 # ------------------------------------------------------------------ lengths outside [0, max_seqlen]
 
 def test_out_of_range_lengths_are_clamped():

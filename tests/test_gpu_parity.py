@@ -717,8 +717,8 @@ def test_sparse_attn_prefill_shared(seqlens, Hq, Hkv, topk, planted):
 
 @pytest.mark.parametrize("B", [4, 17])
 def test_decode_step_many_sequences(B):
-    # the decode selection covers more kernels per workgroup from 4 and from 16 sequences on: one step on
-    # a ragged batch, every sequence against the oracle (lengths include steps that complete a kernel)
+    # the decode selection covers more kernels per workgroup from 4 sequences on: one step on a ragged
+    # batch, every sequence against the oracle (lengths include steps that complete a kernel)
     Hq, Hkv, topk = 32, 2, 8
     prm = binding.Params(Hq, Hkv, topk=topk)
     oprm = oracle_params(prm)

@@ -44,6 +44,7 @@ struct AppendArgs {      // the cache append folded into the first kernel of a f
 struct AttendArgs {      // the per-block attention folded into the top-k kernel of a fused decode step
     Tensor k, v;
     const uint64_t *tree_mask;                        // verification only, else null
+    bool fused;                                       // out: false = only the top-k ran (too many rows to repeat it per block)
     float *o_part;
     float2 *ml_part;
 };
@@ -156,7 +157,7 @@ int launch_select_pick(const Dims &dm, const int32_t *seqlens, const float *R, i
                        int32_t *block_idx, hipStream_t stream);
 int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
                          int32_t *block_idx, void *ws, hipStream_t stream, const AppendArgs *append = nullptr,
-                         const AttendArgs *attend = nullptr);
+                         AttendArgs *attend = nullptr);
 int launch_decode_step(const Dims &dm, Tensor q, Tensor ck, const AppendArgs &append, const int32_t *seqlens,
                        int32_t *block_idx, Tensor out, float *lse, void *ws_select, void *ws_attn,
                        hipStream_t stream);

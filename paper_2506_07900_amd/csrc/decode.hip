@@ -922,7 +922,7 @@ size_t select_decode_ws_bytes(const Dims &dm) {
 
 int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
                          int32_t *block_idx, void *ws, hipStream_t stream, const AppendArgs *append,
-                         const AttendArgs *attend) {
+                         AttendArgs *attend) {
     if (dm.batch <= 0) return 0;
     DecodeSelLayout l = decode_sel_layout(dm);
     if (l.n_c_cap > 16384) return (int)hipErrorInvalidValue;         // rejected earlier by the C ABI
@@ -965,7 +965,11 @@ int launch_select_decode(const Dims &dm, Tensor q, Tensor ck, const int32_t *seq
     timing_end(stream);
     const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
     if (n_blocks > kPickThreads * kPickMaxVPT) return (int)hipErrorInvalidValue;   // rejected earlier by the C ABI
-    if (attend) {                                                    // top-k and partial attention in one launch
+    // Top-k and partial attention in one launch: every workgroup of the attention repeats the top-k of its
+    // row, which is free while compute units idle and costs throughput once the launch fills the machine.
+    constexpr int64_t kMaxFusedUnits = 1024;                         // (row, key-value head, block) workgroups
+    if (attend) attend->fused = (int64_t)rows * dm.Hkv * dm.topk <= kMaxFusedUnits;
+    if (attend && attend->fused) {
         const dim3 grid(dm.topk, dm.Hkv, rows), block(kPickThreads);
         timing_begin("decode_pick_partial_kernel", stream);
 #define INFLLMV2_PICK_PARTIAL(VPT)                                                                                  \
@@ -1010,6 +1014,15 @@ static void attn_decode_ws(const Dims &dm, void *ws, float *&o_part, float2 *&ml
     ml_part = reinterpret_cast<float2 *>(reinterpret_cast<char *>(ws) + o_bytes);
 }
 
+static void launch_decode_partial(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32_t *seqlens,
+                                  const int32_t *block_idx, const uint64_t *tree_mask, float *o_part, float2 *ml_part,
+                                  hipStream_t stream) {
+    timing_begin("decode_attn_partial_kernel", stream);
+    hipLaunchKernelGGL(decode_attn_partial_kernel, dim3(dm.topk, dm.Hkv, dm.batch * dm.n_q), dim3(256), 0, stream,
+                       dm, q, k, v, seqlens, block_idx, tree_mask, o_part, ml_part);
+    timing_end(stream);
+}
+
 static int launch_decode_merge(const Dims &dm, const float *o_part, const float2 *ml_part, Tensor out, float *lse,
                                hipStream_t stream) {
     timing_begin("decode_merge_kernel", stream);
@@ -1026,10 +1039,7 @@ int launch_attn_decode(const Dims &dm, Tensor q, Tensor k, Tensor v, const int32
     float *o_part;
     float2 *ml_part;
     attn_decode_ws(dm, ws, o_part, ml_part);
-    timing_begin("decode_attn_partial_kernel", stream);
-    hipLaunchKernelGGL(decode_attn_partial_kernel, dim3(dm.topk, dm.Hkv, dm.batch * dm.n_q), dim3(256), 0, stream,
-                       dm, q, k, v, seqlens, block_idx, tree_mask, o_part, ml_part);
-    timing_end(stream);
+    launch_decode_partial(dm, q, k, v, seqlens, block_idx, tree_mask, o_part, ml_part, stream);
     return launch_decode_merge(dm, o_part, ml_part, out, lse, stream);
 }
 
@@ -1038,10 +1048,11 @@ int launch_decode_step(const Dims &dm, Tensor q, Tensor ck, const AppendArgs &ap
                        int32_t *block_idx, Tensor out, float *lse, void *ws_select, void *ws_attn,
                        hipStream_t stream) {
     if (dm.batch <= 0) return 0;
-    AttendArgs at = {append.k, append.v, nullptr, nullptr, nullptr};
+    AttendArgs at = {append.k, append.v, nullptr, false, nullptr, nullptr};
     attn_decode_ws(dm, ws_attn, at.o_part, at.ml_part);
     const int err = launch_select_decode(dm, q, ck, seqlens, block_idx, ws_select, stream, &append, &at);
     if (err) return err;
+    if (!at.fused) launch_decode_partial(dm, q, append.k, append.v, seqlens, block_idx, nullptr, at.o_part, at.ml_part, stream);
     return launch_decode_merge(dm, at.o_part, at.ml_part, out, lse, stream);
 }
 
@@ -1053,10 +1064,11 @@ int launch_verify_step(const Dims &dm, Tensor q, Tensor ck, const AppendArgs &ap
     if (dm.batch <= 0) return 0;
     int err = launch_append_kv(dm, append.k_new, append.v_new, append.k, append.v, &ck, seqlens, stream);
     if (err) return err;
-    AttendArgs at = {append.k, append.v, tree_mask, nullptr, nullptr};
+    AttendArgs at = {append.k, append.v, tree_mask, false, nullptr, nullptr};
     attn_decode_ws(dm, ws_attn, at.o_part, at.ml_part);
     err = launch_select_decode(dm, q, ck, seqlens, block_idx, ws_select, stream, nullptr, &at);
     if (err) return err;
+    if (!at.fused) launch_decode_partial(dm, q, append.k, append.v, seqlens, block_idx, tree_mask, at.o_part, at.ml_part, stream);
     return launch_decode_merge(dm, at.o_part, at.ml_part, out, lse, stream);
 }
 

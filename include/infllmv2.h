@@ -247,8 +247,9 @@ int32_t infllmv2_append_kv(const infllmv2_params *prm, const infllmv2_tensor *k_
  * One decode step in one call (section 5.4: per step only the semantic-kernel representations grow):
  * infllmv2_append_kv (with ck) + infllmv2_select_blocks(INFLLMV2_MODE_DECODE) +
  * infllmv2_sparse_attn_decode, with the append folded into the first selection kernel and the top-k
- * into the per-block attention kernel: four launches instead of six, the same caches, ck, block_idx,
- * out and lse bit for bit.
+ * into the per-block attention kernel: four launches instead of six (five when batch * Hkv * topk
+ * exceeds 1024: the top-k then runs once per row in a launch of its own), the same caches, ck,
+ * block_idx, out and lse bit for bit.
  *   q, out        [batch, 1, Hq, d] bf16;  k_new, v_new  [batch, Hkv, 1, d] bf16
  *   k, v, ck      the caches (updated in place);  seqlens counts the new token
  *   block_idx     out  int32 [batch, Hkv, 1, topk];  lse  out  fp32 [batch, Hq]
@@ -287,8 +288,9 @@ int32_t infllmv2_decode_step(const infllmv2_params *prm, const infllmv2_tensor *
  *                               [batch, n_draft] or NULL; lse out fp32 [batch, n_draft, Hq];
  *                               arithmetic as in infllmv2_sparse_attn_decode.
  * infllmv2_verify_step          the three calls in one (ck required), five launches instead of six
- *                               (the top-k is folded into the per-block attention kernel); the same
- *                               caches, ck, block_idx, out and lse bit for bit.
+ *                               (the top-k is folded into the per-block attention kernel unless
+ *                               batch * n_draft * Hkv * topk exceeds 1024); the same caches, ck,
+ *                               block_idx, out and lse bit for bit.
  * Workspaces: infllmv2_verify_workspace_bytes(INFLLMV2_OP_SELECT_VERIFY / _ATTN_VERIFY /
  * _VERIFY_STEP, ...) (0 if the arguments are invalid), 256-byte aligned.
  */

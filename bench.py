@@ -482,10 +482,15 @@ def measured_peaks():
             best[name] = min(best.get(name, 1e30), ms)
     binding.timing_enable(False)
     del buf
+    m, v, both = best["probe_mix_mfma_kernel"], best["probe_mix_valu_kernel"], best["probe_mix_both_kernel"]
     return {"mfma_bf16_TFLOPs": flops / (best["probe_mfma_kernel"] * 1e-3) / 1e12,
             "hbm_read_GBs": nbytes / (best["probe_stream_kernel"] * 1e-3) / 1e9,
             "how": "probe_mfma_kernel: 8 independent 16x16x32 bf16 MFMA chains per wave, 8 waves per SIMD; "
-                   "probe_stream_kernel: one coalesced read of a 2 GiB buffer"}
+                   "probe_stream_kernel: one coalesced read of a 2 GiB buffer",
+            # do the matrix cores and the vector ALU of a SIMD work at the same time?  per loop step 16 MFMAs
+            # and / or 16 x (fma, exp2, add, fma), 4 waves per SIMD: 1.0 = not at all, max/sum = completely
+            "mfma_valu_overlap": {"mfma_ms": m, "valu_ms": v, "both_ms": both, "both_over_sum": both / (m + v),
+                                  "both_over_max": both / max(m, v)}}
 
 
 def cpu_baseline(x, cfg, n_rows, lse_ratio=1):

@@ -349,10 +349,13 @@ int32_t infllmv2_sparse_attn_prefill_shared(const infllmv2_params *prm, const in
                                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Measured practical peaks for the benchmark's rooflines (not part of the method).  Launches two
- * probe kernels on `stream`: a dense bf16 MFMA loop ("probe_mfma_kernel") and a read of every byte
- * of `buf` ("probe_stream_kernel"); their durations are obtained like any other kernel's, through
- * infllmv2_timing_enable / infllmv2_timing_read.
+ * Measured practical peaks for the benchmark's rooflines (not part of the method).  Launches
+ * probe kernels on `stream`: a dense bf16 MFMA loop ("probe_mfma_kernel"), a read of every byte
+ * of `buf` ("probe_stream_kernel"), and the instruction mix of a softmax kernel as matrix work
+ * alone, vector work alone and both together ("probe_mix_mfma_kernel", "probe_mix_valu_kernel",
+ * "probe_mix_both_kernel": the same loop count each, so their durations compare directly); the
+ * durations are obtained like any other kernel's, through infllmv2_timing_enable /
+ * infllmv2_timing_read.
  *   buf            in   DEVICE buffer, 256-byte aligned, at least 8 MiB, ZERO-FILLED by the caller
  *                       (it is only read; a size far above the cache sizes measures HBM)
  *   mfma_flops     out  HOST: floating-point operations the MFMA probe executes per launch

@@ -96,6 +96,29 @@ __device__ inline int row_len(const Dims &dm, int L_all, int qi) {
     return (L_all < dm.n_q || qi >= dm.n_q) ? 0 : L_all - (dm.n_q - 1 - qi);
 }
 
+// Channels c0 .. c0+7 of the semantic kernel that the token appended at position L-1 completes: rows
+// L-32 .. L-2 from the cache, row L-1 from the step's new key; fp64 sum in token order, one rounding
+// (the bits compress_keys_kernel produces once the row is in the cache).
+__device__ inline bf16x8 fresh_kernel_row8(const AppendArgs &ap, int b, int h, int L, int c0) {
+    const __bf16 *kc = ap.k.ptr + b * ap.k.sb + h * ap.k.sh + c0;
+    bf16x8 rows[kKernel];
+#pragma unroll
+    for (int t = 0; t < kKernel - 1; ++t) rows[t] = load8(kc + (int64_t)(L - kKernel + t) * ap.k.st);
+    rows[kKernel - 1] = load8(ap.k_new.ptr + b * ap.k_new.sb + h * ap.k_new.sh + c0);
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+        for (int t = 0; t < kKernel; ++t) {
+            s0 += (double)(float)rows[t][2 * e];
+            s1 += (double)(float)rows[t][2 * e + 1];
+        }
+        w[e] = (uint32_t)f64_to_bf16_rne(s0 / (double)kKernel) | ((uint32_t)f64_to_bf16_rne(s1 / (double)kKernel) << 16);
+    }
+    return __builtin_bit_cast(bf16x8, uint4{w[0], w[1], w[2], w[3]});
+}
+
 // ---- part 1: partial (max, sum) of the relevance softmax ---------------------------------------------
 // grid (n_c_cap / (64*kTW), Hkv, B * ceil(n_q/kQT)); wave w owns kernels chunk + 16*kTW*w .. +16*kTW-1.
 // Z^T = CK . Q^T: lane = query head, 4 accumulator entries = 4 consecutive kernels.
@@ -260,8 +283,14 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(Dims dm, Tensor q, T
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         if (r >= dm.rho) break;
-                        const bf16x8 v = load8(ck.ptr + b * ck.sb + h * ck.sh +
-                                               (int64_t)(dm.rho * cc + 2 * r) * ck.st + 32 * ks + 8 * g);
+                        const int jf = dm.rho * cc + 2 * r;
+                        bf16x8 v;
+                        if (kAppend && closes && jf == n_vis_max - 1)
+                            // the kernel this step completes: another workgroup may be storing it right now,
+                            // so its row is built here from the cache and the new key, never read back
+                            v = fresh_kernel_row8(ap, b, h, L_all, 32 * ks + 8 * g);
+                        else
+                            v = load8(ck.ptr + b * ck.sb + h * ck.sh + (int64_t)jf * ck.st + 32 * ks + 8 * g);
 #pragma unroll
                         for (int e = 0; e < 8; ++e) acc[e] += (double)(float)v[e];
                     }

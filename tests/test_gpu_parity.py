@@ -756,6 +756,47 @@ def test_decode_step_many_sequences(B):
         assert out_err(o1[b].double().cpu().numpy(), wo) <= 1.0 and lse_err(l1[b].double().cpu().numpy(), wl[0]) <= 1.0
 
 
+@pytest.mark.parametrize("B", [1, 4])
+@pytest.mark.parametrize("rho", [2, 4])
+def test_decode_step_approximate_lse_when_the_new_kernel_feeds_another_workgroup(rho, B):
+    # One-call decode steps with the approximate log-sum-exp at the lengths where the semantic kernel the
+    # new token completes is the last fine kernel of a coarse kernel that ANOTHER workgroup of the first
+    # selection kernel owns (128 or 256 kernels per workgroup: one or four sequences).  That workgroup
+    # must not read the row back from the compressed-key cache while it is being written: the row is
+    # pre-filled with large values here, so a stale read changes the scores.
+    Hq, Hkv, topk = 32, 2, 16
+    prm = binding.Params(Hq, Hkv, topk=topk, lse_coarse_ratio=rho)
+    oprm = oracle_params(prm)
+    chunk_tokens = 16 * (128 if B < 4 else 256)
+    base = 32 if rho == 2 else 64
+    lens = [chunk_tokens * (1 + b % 2) + base for b in range(B)]
+    q, k, v, T = make_batch(131 + rho, lens, Hq, Hkv, n_planted=3)
+    q1 = np.stack([q[b, l - 1] for b, l in enumerate(lens)])[:, None]
+    kn = np.stack([k[b, :, l - 1] for b, l in enumerate(lens)])[:, :, None]
+    vn = np.stack([v[b, :, l - 1] for b, l in enumerate(lens)])[:, :, None]
+    k0, v0 = k.copy(), v.copy()
+    for b, l in enumerate(lens):
+        k0[b, :, l - 1] = 0
+        v0[b, :, l - 1] = 0
+    kc, vc, sl = to_dev(k0), to_dev(v0), dev_i32(lens)
+    ck = binding.compress_keys(prm, kc, sl - 1, T)
+    for b, l in enumerate(lens):
+        ck[b, :, (l - 32) // 16] = 100.0                                    # the row this step is about to write
+    i1, o1, l1 = binding.decode_step(prm, to_dev(q1), to_dev(kn), to_dev(vn), kc, vc, ck, sl, T)
+    torch.cuda.synchronize()
+    i1, ckb = i1.cpu().numpy(), to_bits(ck)
+    for b, l in enumerate(lens):
+        print("case rho %d batch %d seq %d len %d" % (rho, B, b, l), flush=True)
+        pos = np.array([l - 1], np.int32)
+        _, ck_ref = ref.compress_keys(k[b, :, :l], oprm)
+        assert np.array_equal(ckb[b, :, :ck_ref.shape[1]], ck_ref), b
+        want, margins, R = ref.select_blocks(q1[b], ck_ref, pos, oprm, want_scores=True)
+        n, e, nt, hard = compare_selection(i1[b], want, margins, R)
+        assert not hard, (b, hard)
+        wo, wl = ref.sparse_attn(q1[b], k[b, :, :l], v[b, :, :l], pos, i1[b], oprm)
+        assert out_err(o1[b].double().cpu().numpy(), wo) <= 1.0 and lse_err(l1[b].double().cpu().numpy(), wl[0]) <= 1.0
+
+
 # ------------------------------------------------------------------ lengths outside [0, max_seqlen]
 
 def test_out_of_range_lengths_are_clamped():

@@ -226,6 +226,28 @@ int32_t infllmv2_sparse_attn_decode(const infllmv2_params *prm, const infllmv2_t
                                     void *stream);
 
 /*
+ * infllmv2_sparse_attn_decode for callers that cannot allocate device memory or carry a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments minus
+ * the workspace, same kernels, same out and lse bit for bit.  The per-block partial results live in a
+ * fixed array of INFLLMV2_NOALLOC_SCRATCH_BYTES in device memory that belongs to the library's code
+ * object: every GPU the library runs on holds its own copy until the process ends, looked up on the
+ * first call made with that GPU current (`stream` must belong to the current device).
+ *   Limit: batch * n_q_heads * topk * 520 bytes (rounded up to 256-byte multiples per array) must fit the
+ *   array, e.g. batch 7 at 32 query heads and top-k 32; beyond it INFLLMV2_ERR_UNSUPPORTED is returned
+ *   and nothing is launched.
+ *   All calls on one GPU share that GPU's array: calls that may overlap in time (different streams,
+ *   different threads) race on it and must be ordered by the caller.  Nothing needs clearing between
+ *   calls: every partial a call reads is written by that call first.
+ * Calls no hipMalloc / hipFree, directly or through a library.
+ */
+#define INFLLMV2_NOALLOC_SCRATCH_BYTES (4u << 20)
+int32_t infllmv2_sparse_attn_decode_noalloc(const infllmv2_params *prm, const infllmv2_tensor *q,
+                                            const infllmv2_tensor *k, const infllmv2_tensor *v,
+                                            const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
+                                            const int32_t *block_idx, const infllmv2_tensor *out,
+                                            float *lse, void *stream);
+
+/*
  * Decode-step cache append: writes the new token's key and value rows at position
  * seqlens[b]-1 of each sequence's cache (seqlens already counts the new token).
  *   k_new, v_new  in   bf16 [batch, Hkv, 1, d]  (stride_t unused)

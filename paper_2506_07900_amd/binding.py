@@ -30,7 +30,7 @@ OP_VERIFY_STEP = 10
 MODE_PREFILL, MODE_DECODE = 0, 1
 
 EXPORTS = ["infllmv2_status_string", "infllmv2_workspace_bytes", "infllmv2_compress_keys",
-           "infllmv2_select_blocks", "infllmv2_sparse_attn_prefill", "infllmv2_sparse_attn_decode",
+           "infllmv2_select_blocks", "infllmv2_sparse_attn_prefill", "infllmv2_sparse_attn_decode", "infllmv2_sparse_attn_decode_noalloc",
            "infllmv2_sparse_attn_bwd", "infllmv2_append_kv", "infllmv2_decode_step", "infllmv2_select_blocks_shared", "infllmv2_sparse_attn_prefill_shared", "infllmv2_verify_workspace_bytes", "infllmv2_append_kv_verify",
            "infllmv2_select_blocks_verify", "infllmv2_sparse_attn_verify", "infllmv2_verify_step",
            "infllmv2_probe_peaks", "infllmv2_timing_enable", "infllmv2_timing_read"]
@@ -105,6 +105,8 @@ def load_library(path=None):
     lib.infllmv2_sparse_attn_prefill.argtypes = [P, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
     lib.infllmv2_sparse_attn_decode.restype = i32
     lib.infllmv2_sparse_attn_decode.argtypes = [P, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
+    lib.infllmv2_sparse_attn_decode_noalloc.restype = i32
+    lib.infllmv2_sparse_attn_decode_noalloc.argtypes = [P, T, T, T, vp, i32, i32, vp, T, vp, vp]
     lib.infllmv2_sparse_attn_bwd.restype = i32
     lib.infllmv2_sparse_attn_bwd.argtypes = [P, T, T, T, T, T, vp, vp, i32, i32, vp, T, T, T, vp, sz, vp]
     lib.infllmv2_decode_step.restype = i32
@@ -288,6 +290,19 @@ def sparse_attn_decode(prm, q, k, v, seqlens, max_seqlen, block_idx, out=None, l
                                            max_seqlen, _i32(block_idx, "block_idx").data_ptr(),
                                            ctypes.byref(d[3]), lse.data_ptr(), workspace.data_ptr(),
                                            ws_bytes, _stream()), "infllmv2_sparse_attn_decode")
+    return out, lse
+
+
+def sparse_attn_decode_noalloc(prm, q, k, v, seqlens, max_seqlen, block_idx, out, lse):
+    """sparse_attn_decode on the library's fixed scratch array: no workspace, and this wrapper creates no
+    tensor either (out [B, 1, Hq, d] bf16 and lse [B, Hq] fp32 are the caller's)."""
+    lib = load_library()
+    d = [_query_desc(q, "q"), _cache_desc(k, "k"), _cache_desc(v, "v"), _query_desc(out, "out")]
+    _check(lib.infllmv2_sparse_attn_decode_noalloc(ctypes.byref(prm.c()), ctypes.byref(d[0]), ctypes.byref(d[1]),
+                                                   ctypes.byref(d[2]), _i32(seqlens, "seqlens").data_ptr(),
+                                                   q.shape[0], max_seqlen, _i32(block_idx, "block_idx").data_ptr(),
+                                                   ctypes.byref(d[3]), lse.data_ptr(), _stream()),
+           "infllmv2_sparse_attn_decode_noalloc")
     return out, lse
 
 

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libinfllmv2.so")
-SOURCES = ["api.hip", "compress_keys.hip", "select_prefill.hip", "select_prefill16.hip", "attn_prefill.hip", "attn_bwd.hip", "decode.hip", "probes.hip"]
+SOURCES = ["api.hip", "compress_keys.hip", "select_prefill.hip", "select_prefill16.hip", "attn_prefill.hip", "attn_bwd.hip", "decode.hip", "noalloc.hip", "probes.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed fp32 VALU forms are kept out of the generated code on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -115,6 +115,29 @@ void timing_end(hipStream_t stream) {
 }
 }  // namespace infllmv2
 
+namespace infllmv2 {
+// Host-side validation of the stage-3 decode arguments, shared by the entry points that differ only in
+// where their scratch memory comes from.
+int32_t validate_attn_decode(const infllmv2_params *prm, const infllmv2_tensor *q, const infllmv2_tensor *k,
+                             const infllmv2_tensor *v, const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
+                             const int32_t *block_idx, const infllmv2_tensor *out, const float *lse, Dims *dm,
+                             Tensor *tq, Tensor *tk, Tensor *tv, Tensor *tout) {
+    RETURN_IF_ERR(check_params(prm));
+    RETURN_IF_ERR(check_sizes(batch, max_seqlen));
+    RETURN_IF_ERR(check_tensor(q));
+    RETURN_IF_ERR(check_tensor(k));
+    RETURN_IF_ERR(check_tensor(v));
+    RETURN_IF_ERR(check_tensor(out));
+    if (!seqlens || !block_idx || !lse) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    *dm = make_dims(prm, batch, max_seqlen);
+    *tq = make_tensor(q);
+    *tk = make_tensor(k);
+    *tv = make_tensor(v);
+    *tout = make_tensor(out);
+    return INFLLMV2_OK;
+}
+}  // namespace infllmv2
+
 extern "C" {
 
 int32_t infllmv2_timing_enable(int32_t enable) {
@@ -456,20 +479,15 @@ int32_t infllmv2_sparse_attn_decode(const infllmv2_params *prm, const infllmv2_t
                                     const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
                                     const int32_t *block_idx, const infllmv2_tensor *out, float *lse,
                                     void *workspace, size_t workspace_bytes, void *stream) {
-    RETURN_IF_ERR(check_params(prm));
-    RETURN_IF_ERR(check_sizes(batch, max_seqlen));
-    RETURN_IF_ERR(check_tensor(q));
-    RETURN_IF_ERR(check_tensor(k));
-    RETURN_IF_ERR(check_tensor(v));
-    RETURN_IF_ERR(check_tensor(out));
-    if (!seqlens || !block_idx || !lse) return INFLLMV2_ERR_INVALID_ARGUMENT;
-    const Dims dm = make_dims(prm, batch, max_seqlen);
+    Dims dm;
+    Tensor tq, tk, tv, tout;
+    RETURN_IF_ERR(validate_attn_decode(prm, q, k, v, seqlens, batch, max_seqlen, block_idx, out, lse, &dm, &tq, &tk,
+                                       &tv, &tout));
     const size_t need = attn_decode_ws_bytes(dm);
     if (need > 0 && (!workspace || workspace_bytes < need ||
                      (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0))
         return INFLLMV2_ERR_WORKSPACE;
-    return hip_status(launch_attn_decode(dm, make_tensor(q), make_tensor(k), make_tensor(v), seqlens,
-                                         block_idx, nullptr, make_tensor(out), lse, workspace,
+    return hip_status(launch_attn_decode(dm, tq, tk, tv, seqlens, block_idx, nullptr, tout, lse, workspace,
                                          reinterpret_cast<hipStream_t>(stream)));
 }
 

@@ -176,6 +176,10 @@ int launch_attn_bwd(const Dims &dm, Tensor q, Tensor k, Tensor v, Tensor out, Te
                     const int32_t *seqlens, const int32_t *block_idx, Tensor dq, Tensor dk, Tensor dv, void *ws,
                     hipStream_t stream);
 size_t attn_bwd_ws_bytes(const Dims &dm);
+int32_t validate_attn_decode(const infllmv2_params *prm, const infllmv2_tensor *q, const infllmv2_tensor *k,
+                             const infllmv2_tensor *v, const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
+                             const int32_t *block_idx, const infllmv2_tensor *out, const float *lse, Dims *dm,
+                             Tensor *tq, Tensor *tk, Tensor *tv, Tensor *tout);
 int launch_probes(void *buf, size_t buf_bytes, double *mfma_flops, double *stream_bytes, hipStream_t stream);
 
 }  // namespace infllmv2

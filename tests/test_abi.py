@@ -127,6 +127,20 @@ def test_workspace_validation(lib):
                                             FAKE, 1, 4096, FAKE, ctypes.byref(o), FAKE, None, 0, None) == WORKSPACE
 
 
+def test_noalloc_decode_validation(lib):
+    # the fixed-scratch variant validates like the workspace one and refuses sizes beyond its array, all
+    # on the host before any HIP call
+    prm, q, o = good_params(), tensor(), tensor()
+    P, Q, O = ctypes.byref(prm), ctypes.byref(q), ctypes.byref(o)
+    f = lib.infllmv2_sparse_attn_decode_noalloc
+    assert f(P, Q, Q, Q, None, 1, 4096, FAKE, O, FAKE, None) == INVALID                  # no seqlens
+    assert f(P, Q, Q, Q, FAKE, 1, 4096, FAKE, O, None, None) == INVALID                  # no lse
+    assert f(P, Q, Q, Q, FAKE, -1, 4096, FAKE, O, FAKE, None) == INVALID
+    assert f(P, Q, Q, Q, FAKE, 17, 4096, FAKE, O, FAKE, None) == UNSUPPORTED             # 17*32*16*520 B > 4 MiB
+    bad = good_params(head_dim=64)
+    assert f(ctypes.byref(bad), Q, Q, Q, FAKE, 1, 4096, FAKE, O, FAKE, None) == UNSUPPORTED
+
+
 def test_append_kv_validation(lib):
     prm, t = good_params(), tensor()
     P, T = ctypes.byref(prm), ctypes.byref(t)

@@ -6,11 +6,16 @@ sparse_attn_prefill -- over the 32K-token workload (batch 1, 32 query heads : 2 
 heads, head_dim 128, block 64, kernel 32 / stride 16, top-k 16; seeded synthetic bf16 inputs
 with planted key blocks), inputs resident in HBM.  The headline value is attended TFLOP/s
 (sum over heads and query tokens of |T_i| * 4d, divided by the time of the WHOLE step).  The
-line also carries the per-kernel times, the roofline of the dominant kernel, the decode leg of
-the metric (128K context, microseconds per token and bytes moved per second) and the fp64 CPU
-oracle timed on a bounded sample of the same workload.
+same line carries, under "workloads", the same step on the 2K (4 query heads : 1) and the 128K
+workloads, each with its own roofline object and per-pass fractions; the decode legs of the
+metric (128K context, 1000 consecutive steps; ragged batch of 8; 32 replicated sequences) with
+per-kernel times; the fp64 CPU oracle timed on a bounded sample of the headline workload; and
+"parity": what the oracle says about the very outputs the timed kernels produced (block sets,
+outputs, log-sum-exps).
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--decode-steps N] [--no-cpu-baseline]
+  python bench.py --profile-leg prefill_32k|prefill_128k|decode|decode_ragged_b8|decode_batched|backward
+        runs only that leg a few times, untimed, for rocprofv3 (kernel trace or counters)
 """
 import argparse
 import json
@@ -48,29 +53,48 @@ def visible_pairs(l, p=32, s=16):
     return int(np.where(i + 1 >= p, (i + 1 - p) // s + 1, 0).sum())
 
 
-def measured_hbm_traffic(kernel):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary (scaled
-    FETCH_SIZE + WRITE_SIZE), or None when the summary has no row for it."""
-    path = os.path.join(ROOT, "profiles", "prefill_32k_hbm_traffic.md")
+def source_digest(*names):
+    """sha256 over the named files under csrc/: identifies the kernel code a stored counter reading belongs to."""
+    import hashlib
+    h = hashlib.sha256()
+    for n in names:
+        with open(os.path.join(ROOT, "paper_2506_07900_amd", "csrc", n), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_hbm_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` on `workload` (scaled FETCH_SIZE + WRITE_SIZE of a separate
+    rocprofv3 counter run, which cannot share a process with the timed run), taken from
+    profiles/hbm_traffic.md -- but only from a row recorded for the kernel sources as they are now
+    (the row carries their digest).  None when there is no such row: a stale reading is not reported."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.md")
     try:
+        digest = source_digest("attn_prefill.hip", "common.h")
         for line in open(path):
-            cells = [c.strip() for c in line.split("|")]
-            if len(cells) >= 7 and cells[1].strip("`").startswith(kernel):
-                return (float(cells[4]) + float(cells[5])) * 1e6
+            cells = [c.strip().strip("`") for c in line.split("|")]
+            if len(cells) >= 8 and cells[1].startswith(kernel) and cells[2] == workload and cells[6] == digest:
+                return (float(cells[3]) + float(cells[4])) * 1e6
     except (OSError, ValueError):
         pass
     return None
 
 
-def bench_prefill(args):
+WORKLOAD_INDEX = {"prefill_2k_g4": 0, "prefill_32k": 1, "prefill_128k": 2}
+
+
+def bench_prefill(args, workload, extras=True):
+    """Times the whole prefill step on one workload.  extras: also the cold-cache step, the comparison
+    variant, the backward (the headline workload only)."""
     import torch
     from paper_2506_07900_amd import binding, synth
 
-    cfg = synth.CONFIGS[{"prefill_32k": 1, "prefill_128k": 2}[args.workload]]
+    cfg = synth.CONFIGS[WORKLOAD_INDEX[workload]]
     log("[bench] generating %s inputs" % cfg.name)
     x = synth.make_prefill(cfg)
     l, Hq, Hkv, d, m = cfg.seqlen, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.block_size
-    prm = binding.Params(Hq, Hkv, topk=cfg.topk, lse_coarse_ratio=args.lse_ratio)
+    lse_ratio = args.lse_ratio if Hq // Hkv == 16 else 1
+    prm = binding.Params(Hq, Hkv, topk=cfg.topk, lse_coarse_ratio=lse_ratio)
 
     def dev(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
@@ -82,13 +106,20 @@ def bench_prefill(args):
     out = torch.zeros_like(q)
     lse = torch.zeros((1, l, Hq), dtype=torch.float32, device="cuda")
     ws_bytes = binding.workspace_bytes(binding.OP_SELECT_PREFILL, prm, 1, l)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    ws_a = torch.empty(max(binding.workspace_bytes(binding.OP_ATTN_PREFILL, prm, 1, l), 256), dtype=torch.uint8, device="cuda")
 
     def step():
         binding.compress_keys(prm, k, sl, l, ck=ck)
         binding.select_blocks(prm, binding.MODE_PREFILL, q, ck, sl, l, block_idx=idx, workspace=ws)
-        binding.sparse_attn_prefill(prm, q, k, v, sl, l, idx, out=out, lse=lse)
+        binding.sparse_attn_prefill(prm, q, k, v, sl, l, idx, out=out, lse=lse, workspace=ws_a)
 
+    if args.profile_leg:                              # untimed runs for rocprofv3
+        for _ in range(4):
+            step()
+        torch.cuda.synchronize()
+        return None, None
+    steps = args.steps if l >= 32768 else max(args.steps, 50)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -97,8 +128,8 @@ def bench_prefill(args):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     done = 0
-    while done < args.steps:                      # the event log holds 256 launches: read it in chunks
-        n = min(32, args.steps - done)
+    while done < steps:                           # the event log holds 256 launches: read it in chunks
+        n = min(32, steps - done)
         for _ in range(n):
             step()
         for name, ms in binding.timing_read():
@@ -107,7 +138,7 @@ def bench_prefill(args):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     binding.timing_enable(False)
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
     kern_ms = {n: float(np.mean(v)) for n, v in per_kernel.items()}
 
     pairs = sum(attended_pairs_per_head(idx[0, h], l, m) for h in range(Hkv)) * (Hq // Hkv)
@@ -118,18 +149,19 @@ def bench_prefill(args):
     flops_of = {"attn_prefill_kernel": attended_flops, "select_lse_kernel": score_flops,
                 "select_score_kernel": score_flops, "select_lse16_kernel": score_flops,
                 "select_score16_kernel": score_flops}
-    dominant = max(kern_ms, key=kern_ms.get)
-    if dominant in flops_of:
-        ach = flops_of[dominant] / (kern_ms[dominant] * 1e-3) / 1e12
-        roofline = {"kernel": dominant, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
-                    "traffic": measured_hbm_traffic(dominant) if args.workload == "prefill_32k" else None,
-                    "flops_per_launch": flops_of[dominant], "avg_launch_ms": kern_ms[dominant]}
-    else:
-        roofline = {"kernel": dominant, "bound": "hbm", "achieved": None, "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "frac": None, "traffic": None, "avg_launch_ms": kern_ms[dominant]}
+    # the roofline object is that of the stage-3 attention kernel, the kernel the metric is about (and the
+    # longest launch of the step); the two selection passes are reported beside it on their own FLOPs
+    dominant = "attn_prefill_kernel"
+    ach = flops_of[dominant] / (kern_ms[dominant] * 1e-3) / 1e12
+    roofline = {"kernel": dominant, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                "traffic": measured_hbm_traffic(dominant, workload),
+                "flops_per_launch": flops_of[dominant], "avg_launch_ms": kern_ms[dominant],
+                "longest_launch_of_the_step": max(kern_ms, key=kern_ms.get)}
+    passes = {n: {"ms": kern_ms[n], "frac_bf16_peak_on_own_flops": flops_of[n] / (kern_ms[n] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+              for n in kern_ms if n.startswith("select_") and n in flops_of}
     overlap = None
-    if args.lse_ratio > 1:                        # how much of the exact selection the approximation keeps
+    if lse_ratio > 1:                        # how much of the exact selection the approximation keeps
         exact = binding.select_blocks(binding.Params(Hq, Hkv, topk=cfg.topk), binding.MODE_PREFILL, q, ck, sl, l,
                                       workspace=ws)
         a, e = idx[0].reshape(-1, cfg.topk), exact[0].reshape(-1, cfg.topk)
@@ -172,12 +204,20 @@ def bench_prefill(args):
         cold.append(e0.elapsed_time(e1))
     del thrash
     res = {
+        "workload": "%s: batch 1, seq %d, %d q heads : %d kv heads, d 128, block 64, kernel 32/16, top-k %d "
+                    "(1 init + 2 local + %d scored), %d planted blocks/head"
+                    % (cfg.name, cfg.seqlen, Hq, Hkv, cfg.topk, cfg.topk - 3, cfg.n_planted),
+        "steps": steps, "lse": "exact" if lse_ratio <= 1 else "approximate, coarse kernels of ratio %d" % lse_ratio,
         "selection_stats": sel_stats, "ms_per_step_after_cache_thrash": float(np.median(cold)),
         "selection_overlap_with_exact": overlap,
-        "ms_per_step": ms_per_step, "value": value, "roofline": roofline,
+        "ms_per_step": ms_per_step, "value": value, "frac_bf16_peak_whole_step": value / PEAK_BF16_TFLOPS,
+        "roofline": roofline, "selection_passes": passes,
         "kernels_ms": kern_ms, "attended_flops": attended_flops, "scoring_flops_per_pass": score_flops,
         "attn_only_tflops": attended_flops / (kern_ms["attn_prefill_kernel"] * 1e-3) / 1e12,
+        "select_workspace_bytes": ws_bytes,
     }
+    if not extras:
+        return res, (x, idx, out, lse, prm, cfg)
     if not args.no_shared:
         # comparison variant, NOT the report's method: one block set per 64-token query block
         ws_s = torch.empty(binding.workspace_bytes(binding.OP_SELECT_SHARED, prm, 1, l), dtype=torch.uint8, device="cuda")
@@ -251,16 +291,46 @@ def bench_prefill(args):
     return res, (x, idx, out, lse, prm, cfg)
 
 
-def bench_decode(cfg_index, steps, replicate=1):
-    """Decode workload: append (+ incremental compression) -> select -> attend, per step.
-    replicate > 1: the batch is the workload's sequences `replicate` times over (separate caches in
-    memory, same contents), to show the same kernels where bandwidth, not latency, is the bound."""
+def decode_parity(x, cfg, prm, s, lens, k_np, v_np, idx, out, lse):
+    """What the oracle says about decode step s as the GPU left it (caches mirrored on the host)."""
+    from oracle import ref
+    oprm = ref.Params(cfg.n_q_heads, cfg.n_kv_heads, topk=cfg.topk)
+    st = {"rows": 0, "exact": 0, "near_tie": 0, "hard": 0, "max_abs_out": 0.0, "max_abs_lse": 0.0}
+    idx_np, out_np, lse_np = idx.cpu().numpy(), out.double().cpu().numpy(), lse.double().cpu().numpy()
+    for b in range(len(lens)):
+        l = int(lens[b])
+        pos = np.array([l - 1], np.int32)
+        _, ckb = ref.compress_keys(k_np[b, :, :l], oprm)
+        qb = x.q_steps[s][b][None]
+        want, margins = ref.select_blocks(qb, ckb, pos, oprm)
+        for h in range(cfg.n_kv_heads):
+            st["rows"] += 1
+            if np.array_equal(idx_np[b, h, 0], want[h, 0]):
+                st["exact"] += 1
+            else:
+                kth, nxt = margins[h, 0]
+                st["near_tie" if abs(kth - nxt) <= 1e-3 * abs(kth) else "hard"] += 1
+        wo, wl = ref.sparse_attn(qb, k_np[b, :, :l], v_np[b, :, :l], pos, idx_np[b], oprm)   # on the GPU's block sets
+        st["max_abs_out"] = max(st["max_abs_out"], float(np.abs(out_np[b, 0] - wo[0]).max()))
+        st["max_abs_lse"] = max(st["max_abs_lse"], float(np.abs(lse_np[b] - wl[0]).max()))
+    return st
+
+
+def bench_decode(cfg_index, steps, replicate=1, profile=False, check_steps=(0, 1, 7, 15)):
+    """Decode workload: append (+ incremental compression) -> select -> attend, per step; `steps` timed
+    steps after 20 untimed ones.  replicate > 1: the batch is the workload's sequences `replicate` times
+    over (separate caches in memory, same contents), to show the same kernels where bandwidth, not
+    latency, is the bound.  The untimed steps listed in check_steps are compared with the oracle."""
     import torch
     from paper_2506_07900_amd import binding, synth
 
     cfg = synth.CONFIGS[cfg_index]
-    log("[bench] generating %s inputs (%d steps)" % (cfg.name, steps))
-    x = synth.make_decode(cfg, steps=steps + 128)      # head-room: the graph is replayed once untimed
+    n_warm = 20
+    chunk = min(100, steps)
+    reps = max(1, steps // chunk)
+    timed = reps * chunk
+    log("[bench] generating %s inputs (%d timed steps)" % (cfg.name, timed))
+    x = synth.make_decode(cfg, steps=n_warm + chunk * (reps + 1) + 8)    # cache room: the graph is replayed once untimed
     prm = binding.Params(cfg.n_q_heads, cfg.n_kv_heads, topk=cfg.topk)
     Hq, Hkv, d, m = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.block_size
 
@@ -269,9 +339,10 @@ def bench_decode(cfg_index, steps, replicate=1):
 
     cap = x.capacity
     kc, vc = dev(x.k_cache), dev(x.v_cache)
-    qs = dev(x.q_steps)[:, :, None].contiguous()         # [steps, B, 1, Hq, d]
-    ks = dev(x.k_steps)[:, :, :, None].contiguous()      # [steps, B, Hkv, 1, d]
-    vs = dev(x.v_steps)[:, :, :, None].contiguous()
+    n_in = n_warm + chunk                                # step inputs: the replays repeat them
+    qs = dev(x.q_steps[:n_in])[:, :, None].contiguous()          # [steps, B, 1, Hq, d]
+    ks = dev(x.k_steps[:n_in])[:, :, :, None].contiguous()       # [steps, B, Hkv, 1, d]
+    vs = dev(x.v_steps[:n_in])[:, :, :, None].contiguous()
     B = cfg.batch * replicate
     sl = torch.tensor(x.seqlens0, dtype=torch.int32, device="cuda")
     if replicate > 1:
@@ -291,16 +362,51 @@ def bench_decode(cfg_index, steps, replicate=1):
         binding.decode_step(prm, qs[s], ks[s], vs[s], kc, vc, ck, sl, cap, block_idx=idx, out=out, lse=lse,
                             workspace=ws_step)
 
-    n_warm = min(20, max(1, steps // 10))
+    if profile:                                          # untimed runs for rocprofv3
+        for s in range(8):
+            sl.add_(1)
+            step(s, sl)
+        torch.cuda.synchronize()
+        return None
+    parity = None
+    k_np = v_np = None
+    if replicate == 1 and check_steps:
+        k_np, v_np = x.k_cache.copy(), x.v_cache.copy()
+        parity = {"rows": 0, "exact": 0, "near_tie": 0, "hard": 0, "max_abs_out": 0.0, "max_abs_lse": 0.0,
+                  "checked_steps": list(check_steps)}
     for s in range(n_warm):
         sl.add_(1)
         step(s, sl)
+        if k_np is not None:
+            lens = sl.cpu().numpy()
+            for b in range(B):
+                k_np[b, :, lens[b] - 1] = x.k_steps[s][b]
+                v_np[b, :, lens[b] - 1] = x.v_steps[s][b]
+            if s in check_steps:
+                st = decode_parity(x, cfg, prm, s, lens, k_np, v_np, idx, out, lse)
+                for key in ("rows", "exact", "near_tie", "hard"):
+                    parity[key] += st[key]
+                for key in ("max_abs_out", "max_abs_lse"):
+                    parity[key] = max(parity[key], st[key])
+    del k_np, v_np
     torch.cuda.synchronize()
     extra = {}
+    if parity is not None:
+        extra["parity"] = parity
+    # per-kernel durations of one eager step (HIP events around every launch)
+    sl_k = sl.clone()
+    sl_k.add_(1)
+    binding.timing_enable(True)
+    step(n_warm, sl_k)
+    kernels_us = {}
+    for name, ms in binding.timing_read():
+        kernels_us[name] = kernels_us.get(name, 0.0) + ms * 1e3
+    binding.timing_enable(False)
+    extra["kernels_us_eager"] = kernels_us
     # distribution over single steps (eager launches, HIP events around each step; the graph figure
     # below is the throughput, this is the spread): the same steps the graph will run, on a scratch copy
     # of the lengths so that the caches are written with the same rows again later
-    n_eager = min(100, steps - n_warm)
+    n_eager = min(100, chunk)
     if n_eager >= 10:
         sl_e = sl.clone()
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_eager)]
@@ -313,9 +419,7 @@ def bench_decode(cfg_index, steps, replicate=1):
         ts = np.array([a.elapsed_time(b_) * 1e3 for a, b_ in evs])
         extra["eager_step_us"] = {"mean": float(ts.mean()), "p50": float(np.percentile(ts, 50)),
                                   "p99": float(np.percentile(ts, 99)), "steps": n_eager}
-    timed = steps - n_warm
     launch = "eager launches"
-    chunk = min(100, timed)
     graph = None
     if chunk >= 10:
         try:                                  # one HIP graph of `chunk` consecutive steps, replayed
@@ -335,8 +439,6 @@ def bench_decode(cfg_index, steps, replicate=1):
             log("[bench] graph capture failed (%r); timing eager launches" % (exc,))
             graph = None
     if graph is not None:
-        reps = timed // chunk
-        timed = reps * chunk
         graph.replay()                        # warm the instantiated graph once
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -347,7 +449,7 @@ def bench_decode(cfg_index, steps, replicate=1):
         launch = "HIP graph of %d consecutive steps replayed %d times (step inputs repeat per replay, the context keeps growing)" % (chunk, reps)
         # the floor of this launch shape: the same number of empty launches per step, in a graph of the same length
         tiny = torch.zeros(64, dtype=torch.float32, device="cuda")
-        n_launch = 4                                   # logits (+append), scores, top-k + partial attention, merge
+        n_launch = len(kernels_us)
         side.wait_stream(torch.cuda.current_stream())
         floor_graph = torch.cuda.CUDAGraph()
         with torch.cuda.stream(side):
@@ -366,9 +468,9 @@ def bench_decode(cfg_index, steps, replicate=1):
         extra["launch_floor_note"] = "%d dependent 64-element kernels per step in the same kind of graph" % n_launch
     else:
         t0 = time.perf_counter()
-        for s in range(n_warm, steps):
+        for i in range(timed):
             sl.add_(1)
-            step(s, sl)
+            step(n_warm + i % chunk, sl)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
     us = (t1 - t0) * 1e6 / timed
@@ -493,36 +595,66 @@ def measured_peaks():
                                   "both_over_max": both / max(m, v)}}
 
 
-def cpu_baseline(x, cfg, n_rows, lse_ratio=1):
-    """The fp64 oracle, as it stands, on a stratified sample of query rows of the same workload."""
+def sample_rows(l, n_rows):
+    """Query rows the oracle is run on: all of them when n_rows >= l, else the first 2048, the last 2048
+    and an even stride over the rest (rows are independent, so every checked row is exact)."""
+    if n_rows >= l:
+        return np.arange(l, dtype=np.int32), "all %d query rows" % l
+    edge = min(2048, n_rows // 4)
+    mid = n_rows - 2 * edge
+    rows = np.unique(np.concatenate([np.arange(edge), np.arange(l - edge, l),
+                                     np.linspace(edge, l - edge - 1, mid).astype(np.int64)])).astype(np.int32)
+    return rows, "%d of %d query rows (first %d, last %d, even stride between)" % (len(rows), l, edge, edge)
+
+
+def cpu_baseline(x, cfg, n_rows, lse_ratio, gpu):
+    """The fp64 oracle, as it stands, timed on a sample of query rows of the same workload -- and compared,
+    outside the timing, with what the timed GPU kernels left behind (gpu = (ck, idx, out, lse) tensors):
+    block sets against the oracle's own selection (near-ties: relative gap of the k-th and (k+1)-th score
+    below 1e-3), outputs and log-sum-exps against the oracle's attention over the GPU's block sets."""
     from oracle import ref
     oprm = ref.Params(cfg.n_q_heads, cfg.n_kv_heads, topk=cfg.topk, lse_coarse_ratio=lse_ratio)
     l = cfg.seqlen
-    stride = max(1, l // n_rows)
-    pos = np.arange(stride - 1, l, stride, dtype=np.int32)[:n_rows]
+    pos, what = sample_rows(l, n_rows)
+    ck_gpu, idx_gpu, out_gpu, lse_gpu = gpu
     t0 = time.perf_counter()
     _, ckb = ref.compress_keys(x.k, oprm)
     t_comp = time.perf_counter() - t0
-    qs = np.ascontiguousarray(x.q[pos])
-    t0 = time.perf_counter()
-    idx, _ = ref.select_blocks(qs, ckb, pos, oprm)
-    t_sel = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    ref.sparse_attn(qs, x.k, x.v, pos, idx, oprm)
-    t_att = time.perf_counter() - t0
-    m = cfg.block_size
+    ck_bits = ck_gpu[0].view(__import__("torch").int16).cpu().numpy().view(np.uint16)
+    par = {"rows": int(len(pos)) * cfg.n_kv_heads, "exact": 0, "near_tie": 0, "hard": 0,
+           "max_abs_out": 0.0, "max_abs_lse": 0.0,
+           "compressed_keys_bit_exact": bool(np.array_equal(ck_bits[:, :ckb.shape[1]], ckb))}
+    t_sel = t_att = 0.0
     pairs = 0
-    for h in range(cfg.n_kv_heads):
-        for a, i in enumerate(pos):
-            for j in idx[h, a]:
-                if j >= 0:
-                    pairs += min(m, int(i) + 1 - int(j) * m)
+    m = cfg.block_size
+    for a in range(0, len(pos), 4096):                   # in chunks: the fp64 outputs of 32K rows are 1 GiB
+        pc = pos[a:a + 4096]
+        qs = np.ascontiguousarray(x.q[pc])
+        t0 = time.perf_counter()
+        idx_ref, margins = ref.select_blocks(qs, ckb, pc, oprm)
+        t_sel += time.perf_counter() - t0
+        pc_t = __import__("torch").from_numpy(pc.astype(np.int64)).cuda()
+        ig = idx_gpu[0][:, pc_t].cpu().numpy()
+        t0 = time.perf_counter()
+        o_ref, l_ref = ref.sparse_attn(qs, x.k, x.v, pc, ig, oprm)        # attention in isolation: the GPU's sets
+        t_att += time.perf_counter() - t0
+        same = (ig == idx_ref).all(axis=2)
+        par["exact"] += int(same.sum())
+        for h, r in zip(*np.nonzero(~same)):
+            kth, nxt = margins[h, r]
+            par["near_tie" if abs(kth - nxt) <= 1e-3 * abs(kth) else "hard"] += 1
+        par["max_abs_out"] = max(par["max_abs_out"], float(np.abs(out_gpu[0][pc_t].double().cpu().numpy() - o_ref).max()))
+        par["max_abs_lse"] = max(par["max_abs_lse"], float(np.abs(lse_gpu[0][pc_t].double().cpu().numpy() - l_ref).max()))
+        jj = ig.astype(np.int64)
+        pairs += int(np.where(jj >= 0, np.clip(pc[None, :, None].astype(np.int64) + 1 - jj * m, 0, m), 0).sum())
     flops = pairs * (cfg.n_q_heads // cfg.n_kv_heads) * 4 * cfg.head_dim
     secs = t_sel + t_att + t_comp * len(pos) / l
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": "%d of %d query rows (every %dth), all heads: select %.2fs + attend %.2fs + compress %.2fs x %d/%d"
-                      % (len(pos), l, stride, t_sel, t_att, t_comp, len(pos), l)}
+    base = {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": "%s, all heads: select %.2fs + attend %.2fs + compress %.2fs x %d/%d%s"
+                      % (what, t_sel, t_att, t_comp, len(pos), l,
+                         "" if len(pos) == l else "; the rate is attended FLOPs of the sampled rows over their time, i.e. extrapolated to the workload")}
+    return base, par
 
 
 def main():
@@ -530,8 +662,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=["prefill_32k", "prefill_128k"], default="prefill_32k",
-                    help="prefill workload of the timed step (the headline metric is quoted on prefill_32k)")
+    ap.add_argument("--workload", choices=list(WORKLOAD_INDEX), default="prefill_32k",
+                    help="prefill workload of the headline value (the metric is quoted on prefill_32k); the other "
+                         "prefill workloads are reported under \"workloads\"")
+    ap.add_argument("--no-other-workloads", action="store_true", help="time only the headline prefill workload")
     ap.add_argument("--lse-ratio", type=int, default=1, choices=[1, 2, 4],
                     help="prefill selection with the approximate log-sum-exp from coarse semantic kernels "
                          "(ratio s_c/s); 1 = the exact two-pass selection the headline metric is quoted on")
@@ -539,7 +673,7 @@ def main():
     ap.add_argument("--ragged-steps", type=int, default=200)
     ap.add_argument("--decode-batch", type=int, default=32,
                     help="batch of the bandwidth-regime decode leg: the 128K decode workload replicated this many times (<= 1: skip)")
-    ap.add_argument("--decode-batch-steps", type=int, default=150)
+    ap.add_argument("--decode-batch-steps", type=int, default=100)
     ap.add_argument("--verify-draft", type=int, default=16, help="drafted tokens per verification step (0: skip the leg)")
     ap.add_argument("--verify-steps", type=int, default=50)
     ap.add_argument("--no-decode", action="store_true")
@@ -550,6 +684,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 1 GiB read + 1 GiB write elementwise kernel, the known-size "
                          "reference the rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled by")
+    ap.add_argument("--profile-leg", default="",
+                    choices=["", "prefill_2k_g4", "prefill_32k", "prefill_128k", "decode", "decode_ragged_b8", "decode_batched"],
+                    help="run only this leg a few times, untimed, and print nothing: the program rocprofv3 wraps")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (multi-GPU sharding is design only)",
@@ -569,26 +706,31 @@ def main():
             torch.add(src, 1, out=dst)
         torch.cuda.synchronize()
         del src, dst
-    res, (x, idx, out, lse, prm, cfg) = bench_prefill(args)
+    if args.profile_leg:
+        if args.profile_leg in WORKLOAD_INDEX:
+            bench_prefill(args, args.profile_leg)
+        else:
+            leg = {"decode": (3, 1), "decode_ragged_b8": (4, 1), "decode_batched": (3, args.decode_batch)}[args.profile_leg]
+            bench_decode(leg[0], 100, replicate=leg[1], profile=True)
+        return
+    res, (x, idx, out, lse, prm, cfg) = bench_prefill(args, args.workload)
     line = {
         "metric": "sparse-attn prefill TFLOP/s (% bf16 MFMA peak); 128K decode us/token (% HBM BW)",
         "value": res["value"], "unit": "TFLOP/s (attended flops / whole-step time)",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "n_gpus": 1, "steps": res["steps"], "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "%s: batch 1, seq %d, %d q heads : %d kv heads, d 128, block 64, "
-                               "kernel 32/16, top-k %d (1 init + 2 local + %d scored), %d planted blocks/head"
-                               % (cfg.name, cfg.seqlen, cfg.n_q_heads, cfg.n_kv_heads, cfg.topk, cfg.topk - 3,
-                                  cfg.n_planted),
-                   "step": "compress_keys + select_blocks + sparse_attn_prefill",
-                   "lse": "exact" if args.lse_ratio <= 1 else "approximate, coarse kernels of ratio %d" % args.lse_ratio},
+        "config": {"workload": res["workload"],
+                   "step": "compress_keys + select_blocks + sparse_attn_prefill", "lse": res["lse"]},
         "selection_overlap_with_exact": res["selection_overlap_with_exact"],
         "selection_stats": res["selection_stats"],
         "ms_per_step_after_cache_thrash": res["ms_per_step_after_cache_thrash"],
-        "frac_bf16_peak_whole_step": res["value"] / PEAK_BF16_TFLOPS,
+        "frac_bf16_peak_whole_step": res["frac_bf16_peak_whole_step"],
         "attn_only_tflops": res["attn_only_tflops"],
         "frac_bf16_peak_attn_only": res["attn_only_tflops"] / PEAK_BF16_TFLOPS,
         "kernels_ms": res["kernels_ms"],
+        "selection_passes": res["selection_passes"],
+        "select_workspace_bytes": res["select_workspace_bytes"],
         "attended_flops": res["attended_flops"],
         "scoring_flops_per_pass": res["scoring_flops_per_pass"],
         "roofline": res["roofline"],
@@ -597,18 +739,46 @@ def main():
         line["backward"] = res["backward"]
     if "shared_variant" in res:
         line["shared_variant"] = res["shared_variant"]
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on %s and comparing it with the GPU's outputs" % cfg.name)
+        ck_g = binding.compress_keys(prm, torch.from_numpy(np.ascontiguousarray(x.k).view(np.int16)).cuda().view(torch.bfloat16)[None],
+                                     torch.tensor([cfg.seqlen], dtype=torch.int32, device="cuda"), cfg.seqlen)
+        n_rows = args.cpu_rows if cfg.seqlen <= 32768 else min(args.cpu_rows, 5120)
+        line["cpu_baseline"], line["parity"] = cpu_baseline(x, cfg, n_rows, args.lse_ratio if cfg.n_q_heads // cfg.n_kv_heads == 16 else 1,
+                                                            (ck_g, idx, out, lse))
+        del ck_g
+    del x, idx, out, lse
+    torch.cuda.empty_cache()
     mp = measured_peaks()
     line["measured_peaks"] = mp
-    rf = line["roofline"]
-    if rf.get("achieved") is not None and rf.get("bound") == "mfma":
-        rf["frac_of_measured_peak"] = rf["achieved"] / mp["mfma_bf16_TFLOPs"]
+    line["roofline"]["frac_of_measured_peak"] = line["roofline"]["achieved"] / mp["mfma_bf16_TFLOPs"]
     line["frac_measured_mfma_peak_whole_step"] = res["value"] / mp["mfma_bf16_TFLOPs"]
+    if not args.no_other_workloads:
+        line["workloads"] = {}
+        for wl in WORKLOAD_INDEX:
+            if wl == args.workload:
+                continue
+            r2, (x2, idx2, out2, lse2, prm2, cfg2) = bench_prefill(args, wl, extras=False)
+            entry = {k_: r2[k_] for k_ in ("workload", "steps", "lse", "ms_per_step", "value", "frac_bf16_peak_whole_step",
+                                           "roofline", "selection_passes", "kernels_ms", "attended_flops",
+                                           "scoring_flops_per_pass", "attn_only_tflops", "select_workspace_bytes",
+                                           "selection_stats", "ms_per_step_after_cache_thrash")}
+            entry["unit"] = "TFLOP/s (attended flops / whole-step time)"
+            if not args.no_cpu_baseline:
+                log("[bench] comparing the CPU oracle with the GPU's outputs on %s" % cfg2.name)
+                ck2 = binding.compress_keys(prm2, torch.from_numpy(np.ascontiguousarray(x2.k).view(np.int16)).cuda().view(torch.bfloat16)[None],
+                                            torch.tensor([cfg2.seqlen], dtype=torch.int32, device="cuda"), cfg2.seqlen)
+                n2 = cfg2.seqlen if cfg2.seqlen <= 32768 else 5120
+                entry["cpu_baseline"], entry["parity"] = cpu_baseline(x2, cfg2, n2, 1, (ck2, idx2, out2, lse2))
+                del ck2
+            line["workloads"][wl] = entry
+            del x2, idx2, out2, lse2
+            torch.cuda.empty_cache()
     if not args.no_decode:
-        del out, lse
         line["decode"] = bench_decode(3, args.decode_steps)
         line["decode"]["frac_measured_hbm_algorithmic"] = line["decode"]["algorithmic_GBs"] / mp["hbm_read_GBs"]
         if args.ragged_steps > 0:
-            line["decode_ragged_b8"] = bench_decode(4, args.ragged_steps)
+            line["decode_ragged_b8"] = bench_decode(4, args.ragged_steps, check_steps=(0, 15))
             line["decode_ragged_b8"]["frac_measured_hbm_algorithmic"] = (
                 line["decode_ragged_b8"]["algorithmic_GBs"] / mp["hbm_read_GBs"])
         if args.decode_batch > 1:
@@ -619,10 +789,6 @@ def main():
             line["verify"] = bench_verify(3, args.verify_draft, args.verify_steps)
             line["verify"]["speedup_per_token_vs_decode"] = (
                 line["decode"]["us_per_token"] / line["verify"]["us_per_draft_token"])
-    if not args.no_cpu_baseline:
-        log("[bench] timing the CPU oracle on a sample")
-        line["cpu_baseline"] = cpu_baseline(x, cfg, args.cpu_rows if args.workload == "prefill_32k" else min(args.cpu_rows, 8192),
-                                            args.lse_ratio)
     print(json.dumps(line), flush=True)
 
 

@@ -101,21 +101,26 @@ __device__ inline int row_len(const Dims &dm, int L_all, int qi) {
 // (the bits compress_keys_kernel produces once the row is in the cache).
 __device__ inline bf16x8 fresh_kernel_row8(const AppendArgs &ap, int b, int h, int L, int c0) {
     const __bf16 *kc = ap.k.ptr + b * ap.k.sb + h * ap.k.sh + c0;
-    bf16x8 rows[kKernel];
+    double acc[8];
 #pragma unroll
-    for (int t = 0; t < kKernel - 1; ++t) rows[t] = load8(kc + (int64_t)(L - kKernel + t) * ap.k.st);
-    rows[kKernel - 1] = load8(ap.k_new.ptr + b * ap.k_new.sb + h * ap.k_new.sh + c0);
+    for (int e = 0; e < 8; ++e) acc[e] = 0.0;
+#pragma unroll 1
+    for (int t0 = 0; t0 < kKernel; t0 += 8) {            // eight rows in flight at a time
+        bf16x8 rows[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            rows[i] = t0 + i < kKernel - 1 ? load8(kc + (int64_t)(L - kKernel + t0 + i) * ap.k.st)
+                                           : load8(ap.k_new.ptr + b * ap.k_new.sb + h * ap.k_new.sh + c0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += (double)(float)rows[i][e];
+    }
     uint32_t w[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        double s0 = 0.0, s1 = 0.0;
-#pragma unroll
-        for (int t = 0; t < kKernel; ++t) {
-            s0 += (double)(float)rows[t][2 * e];
-            s1 += (double)(float)rows[t][2 * e + 1];
-        }
-        w[e] = (uint32_t)f64_to_bf16_rne(s0 / (double)kKernel) | ((uint32_t)f64_to_bf16_rne(s1 / (double)kKernel) << 16);
-    }
+    for (int e = 0; e < 4; ++e)
+        w[e] = (uint32_t)f64_to_bf16_rne(acc[2 * e] / (double)kKernel) |
+               ((uint32_t)f64_to_bf16_rne(acc[2 * e + 1] / (double)kKernel) << 16);
     return __builtin_bit_cast(bf16x8, uint4{w[0], w[1], w[2], w[3]});
 }
 

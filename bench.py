@@ -117,6 +117,12 @@ def bench_prefill(args, workload, extras=True):
     if args.profile_leg:                              # untimed runs for rocprofv3
         for _ in range(4):
             step()
+        if args.profile_leg == "backward":
+            dout = torch.randn(q.shape, device="cuda", generator=torch.Generator(device="cuda").manual_seed(cfg.seed)).bfloat16()
+            dq, dk, dv = torch.zeros_like(q), torch.zeros_like(k), torch.zeros_like(v)
+            ws_b = torch.empty(binding.workspace_bytes(binding.OP_ATTN_BWD, prm, 1, l), dtype=torch.uint8, device="cuda")
+            for _ in range(3):
+                binding.sparse_attn_bwd(prm, q, k, v, out, dout, lse, sl, l, idx, dq=dq, dk=dk, dv=dv, workspace=ws_b)
         torch.cuda.synchronize()
         return None, None
     steps = args.steps if l >= 32768 else max(args.steps, 50)
@@ -685,7 +691,8 @@ def main():
                     help="also launch a plain 1 GiB read + 1 GiB write elementwise kernel, the known-size "
                          "reference the rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled by")
     ap.add_argument("--profile-leg", default="",
-                    choices=["", "prefill_2k_g4", "prefill_32k", "prefill_128k", "decode", "decode_ragged_b8", "decode_batched"],
+                    choices=["", "prefill_2k_g4", "prefill_32k", "prefill_128k", "backward", "decode", "decode_ragged_b8",
+                             "decode_batched"],
                     help="run only this leg a few times, untimed, and print nothing: the program rocprofv3 wraps")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -707,8 +714,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if args.profile_leg:
-        if args.profile_leg in WORKLOAD_INDEX:
-            bench_prefill(args, args.profile_leg)
+        if args.profile_leg in WORKLOAD_INDEX or args.profile_leg == "backward":
+            bench_prefill(args, "prefill_32k" if args.profile_leg == "backward" else args.profile_leg)
         else:
             leg = {"decode": (3, 1), "decode_ragged_b8": (4, 1), "decode_batched": (3, args.decode_batch)}[args.profile_leg]
             bench_decode(leg[0], 100, replicate=leg[1], profile=True)

@@ -151,7 +151,10 @@ int32_t infllmv2_compress_keys(const infllmv2_params *prm, const infllmv2_tensor
  *   block_idx  out  int32 [batch, Hkv, n_q, topk] contiguous: selected block indices in
  *              ascending order, padded with -1.  Prefill rows t >= seqlens[b] are not written.
  *   workspace  device scratch of infllmv2_workspace_bytes(INFLLMV2_OP_SELECT_*, ...) bytes,
- *              256-byte aligned; contents are undefined before and after the call.
+ *              256-byte aligned; contents are undefined before and after the call.  Prefill: the
+ *              log-sum-exps of pass 1 (4 bytes per query token and head) and a tiled copy of ck, so
+ *              linear in max_seqlen; the block scores are ranked inside pass 2, chunk by chunk in
+ *              on-chip memory, and are never stored.
  */
 int32_t infllmv2_select_blocks(const infllmv2_params *prm, int32_t mode, const infllmv2_tensor *q,
                                const infllmv2_tensor *ck, const int32_t *seqlens, int32_t batch,

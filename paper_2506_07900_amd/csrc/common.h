@@ -134,6 +134,81 @@ __device__ inline int count_larger(const uint64_t *w, int n, uint64_t x) {
     return c0 + c1;
 }
 
+// The word of block j with the given score: candidates are the blocks n_init .. jc_max; a candidate
+// without any visible kernel (-inf) gets key 1, below every real score (>= 2^-100) and above "none".
+__device__ inline uint64_t pick_element(float score, int j, int n_init, int jc_max) {
+    const uint32_t kj = score == -INFINITY ? 1u : __float_as_uint(score);
+    const uint32_t key = (j >= n_init && j <= jc_max) ? kj : 0u;
+    return ((uint64_t)key << 32) | (uint32_t)~j;
+}
+
+// Wavefront top-n of distinct 64-bit words, no serial rounds.  Lane l brings NE words; words below
+// kPickValid are not candidates.  Returns in lane c < n the c-th largest candidate (0 when there are
+// fewer than c + 1); n <= 64.  An element of the top n can only sit in a lane whose own maximum is
+// among the n largest lane maxima, and it is at least tau, the n-th largest lane maximum: rank the 64
+// lane maxima by counting, let the n best lanes publish their words >= tau (a handful), rank those by
+// counting.  lds: 64 + topk_cand_cap(n, NE) words that belong to this wavefront alone.
+__host__ __device__ inline int topk_cand_cap(int n, int ne) { return (n * ne + 3) & ~3; }
+
+template <int NE>
+__device__ inline uint64_t wave_topk(const uint64_t (&el)[NE], int n, uint64_t *lds, int lane) {
+    uint64_t *tmax = lds, *cand = lds + 64;
+    uint64_t best = 0ull;
+#pragma unroll
+    for (int s = 0; s < NE; ++s) best = el[s] > best ? el[s] : best;
+    tmax[lane] = best;
+    __builtin_amdgcn_wave_barrier();
+    const bool real = best >= kPickValid;
+    const int lrank = count_larger(tmax, 64, best);
+    const bool finalist = real && lrank < n;
+    uint64_t tau = kPickValid;                            // when fewer than n lanes hold a candidate
+    const uint64_t who = __ballot(real && lrank == n - 1);
+    if (who) {
+        const int src = __builtin_ctzll(who);
+        tau = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(best >> 32), src) << 32) |
+              (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)best, src);
+    }
+    int n_cand = 0;
+    const uint64_t below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int s = 0; s < NE; ++s) {
+        const bool pub = finalist && el[s] >= tau;
+        const uint64_t m = __ballot(pub);
+        if (pub) cand[n_cand + __popcll(m & below)] = el[s];
+        n_cand += __popcll(m);
+    }
+    const int n_cand4 = (n_cand + 3) & ~3;                // <= topk_cand_cap(n, NE)
+    if (lane < n_cand4 - n_cand) cand[n_cand + lane] = 0ull;
+    tmax[lane] = 0ull;                                    // the ranks are known: reuse as the result row
+    __builtin_amdgcn_wave_barrier();
+    for (int i = lane; i < n_cand; i += 64) {
+        const uint64_t e = cand[i];
+        const int beaten = count_larger(cand, n_cand4, e);
+        if (beaten < n) tmax[beaten] = e;
+    }
+    __builtin_amdgcn_wave_barrier();
+    const uint64_t res = lane < n ? tmax[lane] : 0ull;
+    __builtin_amdgcn_wave_barrier();
+    return res;
+}
+
+// The row of selected blocks of one query: lane c < n_pick brings a picked candidate block, the forced
+// blocks (the first n_init and lo_local .. b_own) are added, and the n_sel blocks are written in
+// ascending order, padded with -1 up to topk.
+__device__ inline void write_block_row(int picked, int n_pick, int n_sel, int n_init, int lo_local, int topk,
+                                       int32_t *__restrict__ o, int lane) {
+    int mine = 0x7fffffff;
+    if (lane < n_pick) mine = picked;
+    else if (lane < n_sel) {
+        const int f = lane - n_pick;
+        mine = f < n_init ? f : lo_local + (f - n_init);
+    }
+    int rank = 0;                                         // number of selected blocks below mine
+    for (int e = 0; e < n_sel; ++e) rank += __builtin_amdgcn_readlane(mine, e) < mine ? 1 : 0;
+    if (lane < n_sel) o[rank] = mine;
+    else if (lane < topk) o[lane] = -1;
+}
+
 // Optional per-kernel timing (infllmv2_timing_enable): when on, every launch is bracketed by HIP
 // events on the launch stream.  No-ops when off.
 void timing_begin(const char *kernel_name, hipStream_t stream);

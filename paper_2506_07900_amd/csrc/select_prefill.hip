@@ -148,17 +148,38 @@ __global__ __launch_bounds__(256) void select_lse_kernel(Dims dm, Tensor q, Tens
 // ---- pass 2: group-mean kernel scores, 5-wide / stride-4 max over kernels -> block scores ----
 // MFMA computes Z = Q . CK^T: lane = one kernel, its 4 accumulator entries are 4 consecutive
 // (token, head) rows, so the sum over a token's heads is 3 adds plus at most 2 cross-group adds.
-template <int G>
+//
+// kFused: the block scores stay in LDS, a chunk of kPickChunk blocks per token; when a chunk is complete
+// each wavefront merges it into the running top n_pick of its tokens (wave_topk over the chunk's scores
+// plus the carried picks), and after the last chunk adds the forced blocks and writes the rows.  No
+// score matrix, no separate ranking kernel.  !kFused: the scores R[token, j] go to memory (only the
+// query-block-shared comparison variant, which averages them over 64 tokens first, needs that).
+constexpr int kPickVpl = 4, kPickChunk = 64 * kPickVpl;           // blocks per chunk of the in-kernel top-k
+template <int G> struct ScoreLds {                                 // dynamic LDS of the fused variant
+    int carry_pitch, topk_words;
+    __host__ __device__ explicit ScoreLds(int topk)
+        : carry_pitch((topk + 1) & ~1), topk_words(64 + topk_cand_cap(topk, kPickVpl + 1)) {}
+    __host__ __device__ size_t bytes() const {
+        return (size_t)SelCfg<G>::kTokPerWg * kPickChunk * sizeof(float) +
+               ((size_t)SelCfg<G>::kTokPerWg * carry_pitch + 4 * (size_t)topk_words) * sizeof(uint64_t);
+    }
+};
+
+template <int G, bool kFused>
 __global__ __launch_bounds__(256) void select_score_kernel(Dims dm, Tensor q, Tensor ck,
                                                             const int32_t *__restrict__ seqlens,
                                                             const float *__restrict__ lse2,
                                                             float *__restrict__ R, int32_t nb_cap,
-                                                            int32_t n_tiles) {
+                                                            int32_t n_tiles, int32_t *__restrict__ block_idx) {
     using C = SelCfg<G>;
     constexpr int TL = (G >= 4) ? 1 : 4 / G;     // tokens held by one lane of a row tile
     constexpr int RL = (G >= 4) ? 4 : G;         // rows of one token held by one lane
     __shared__ __align__(16) __bf16 cks[kChunk * kCkPitch];
     __shared__ float rs[C::kTokPerWg][kChunk + 2];   // slot 0: kernel jh0-1 (halo), slot 1+x: jh0+x
+    extern __shared__ __align__(16) unsigned char score_smem[];
+    const ScoreLds<G> lay(dm.topk);
+    float *Rl = reinterpret_cast<float *>(score_smem);                                   // [kTokPerWg][kPickChunk]
+    uint64_t *carry = reinterpret_cast<uint64_t *>(Rl + C::kTokPerWg * kPickChunk);      // [kTokPerWg][carry_pitch]
     const int tile = blockIdx.x % n_tiles;
     const int h = (blockIdx.x / n_tiles) % dm.Hkv;
     const int b = blockIdx.x / (n_tiles * dm.Hkv);
@@ -187,6 +208,30 @@ __global__ __launch_bounds__(256) void select_score_kernel(Dims dm, Tensor q, Te
     const int n_valid = num_kernels(L);
     const __bf16 *ckb = ck.ptr + b * ck.sb + h * ck.sh;
     for (int i = tid; i < C::kTokPerWg; i += 256) rs[i][0] = -INFINITY;
+    // the tokens of a workgroup share their own block (kTokPerWg divides 64), hence the candidate range
+    const int b_own = t0 / kBlock, n_blk = b_own + 1;
+    const int n_sel = dm.topk < n_blk ? dm.topk : n_blk;
+    const int n_init = dm.n_init < n_blk ? dm.n_init : n_blk;                 // forced leading blocks
+    const int lo_local = max(n_init, b_own - dm.n_local + 1);                 // forced trailing: lo_local..b_own
+    const int jc_max = lo_local - 1;                                          // candidates: n_init..jc_max
+    const int n_pick = max(0, n_sel - (n_init + (b_own - lo_local + 1)));
+    uint64_t *tk_lds = carry + C::kTokPerWg * lay.carry_pitch + wave * lay.topk_words;
+    if (kFused)
+        for (int i = tid; i < C::kTokPerWg * lay.carry_pitch; i += 256) carry[i] = 0ull;
+    // merges the chunk of blocks j0 .. j0 + kPickChunk - 1 into the running picks of this wavefront's tokens
+    auto merge_chunk = [&](int j0) {
+        for (int u = 0; u < C::kTokPerWave; ++u) {
+            const int tloc = wave * C::kTokPerWave + u;
+            if (t0 + tloc >= L || n_pick <= 0) break;
+            uint64_t el[kPickVpl + 1];
+#pragma unroll
+            for (int s2 = 0; s2 < kPickVpl; ++s2)
+                el[s2] = pick_element(Rl[tloc * kPickChunk + lane + 64 * s2], j0 + lane + 64 * s2, n_init, jc_max);
+            el[kPickVpl] = lane < n_pick ? carry[tloc * lay.carry_pitch + lane] : 0ull;
+            const uint64_t res = wave_topk<kPickVpl + 1>(el, n_pick, tk_lds, lane);
+            if (lane < n_pick) carry[tloc * lay.carry_pitch + lane] = res;
+        }
+    };
 
     for (int jh0 = 0; jh0 < nvis_wg; jh0 += kChunk) {
         __syncthreads();
@@ -239,11 +284,15 @@ __global__ __launch_bounds__(256) void select_score_kernel(Dims dm, Tensor q, Te
                 float r = rs[tloc][4 * jb];
 #pragma unroll
                 for (int x = 1; x < 5; ++x) r = fmaxf(r, rs[tloc][4 * jb + x]);
-                R[(((int64_t)b * dm.Hkv + h) * dm.max_seqlen + tok) * nb_cap + j] = r;
+                if (kFused) Rl[tloc * kPickChunk + (j & (kPickChunk - 1))] = r;
+                else R[(((int64_t)b * dm.Hkv + h) * dm.max_seqlen + tok) * nb_cap + j] = r;
             }
         }
         __syncthreads();
         for (int i = tid; i < C::kTokPerWg; i += 256) rs[i][0] = rs[i][kChunk];
+        // a chunk of blocks is complete (the barrier that opens the next stage orders the merge before
+        // the next chunk's scores)
+        if (kFused && (((jh0 >> 2) + 16) & (kPickChunk - 1)) == 0) merge_chunk((jh0 >> 2) + 16 - kPickChunk);
     }
     // Blocks past the last scored chunk (only the last ones of a token can be).  Of their kernels only
     // the left neighbour of the first one, 4*j_done - 1 = the last kernel of the last chunk, can be
@@ -253,25 +302,34 @@ __global__ __launch_bounds__(256) void select_score_kernel(Dims dm, Tensor q, Te
     const int j_done = ((nvis_wg + kChunk - 1) / kChunk) * 16;
     for (int i = tid; i < C::kTokPerWg * 4; i += 256) {
         const int tloc = i >> 2, tok = t0 + tloc, j = j_done + (i & 3);
-        if (tok < L && j <= tok / kBlock)
-            R[(((int64_t)b * dm.Hkv + h) * dm.max_seqlen + tok) * nb_cap + j] = (i & 3) == 0 ? rs[tloc][0] : -INFINITY;
+        if (tok < L && j <= tok / kBlock) {
+            const float r = (i & 3) == 0 ? rs[tloc][0] : -INFINITY;
+            if (kFused) Rl[tloc * kPickChunk + (j & (kPickChunk - 1))] = r;
+            else R[(((int64_t)b * dm.Hkv + h) * dm.max_seqlen + tok) * nb_cap + j] = r;
+        }
+    }
+    if (kFused) {
+        __syncthreads();
+        merge_chunk(j_done & ~(kPickChunk - 1));             // the last, partial chunk: it holds block j_done
+        for (int u = 0; u < C::kTokPerWave; ++u) {
+            const int tloc = wave * C::kTokPerWave + u;
+            if (t0 + tloc >= L) break;
+            const int picked = lane < n_pick ? (int)~(uint32_t)carry[tloc * lay.carry_pitch + lane] : 0;
+            write_block_row(picked, n_pick, n_sel, n_init, lo_local, dm.topk,
+                            block_idx + (((int64_t)b * dm.Hkv + h) * dm.max_seqlen + t0 + tloc) * dm.topk, lane);
+        }
     }
 }
 
-// ---- top-k: one wavefront per (sequence, key-value head, token) row of block scores ------------
-// Candidates are the blocks n_init .. b_own - n_local; the forced ones are added afterwards.
-// Scores are positive floats, so their bit patterns order like unsigned integers.  An element is
-// the 64-bit word  key << 32 | ~block  with key = bits of the score (1 for a block without visible
-// kernel, -inf): larger word = better element, ties go to the lower block index, no two elements
-// are equal; words below 2^32 are "not a candidate".
-//
-// No serial rounds: lane l keeps blocks l, l+64, ... in registers and `best`, the largest of
-// them.  An element of the final top-k can only sit in a lane whose best is among the n_pick
-// largest lane maxima, and it is at least tau, the n_pick-th largest lane maximum.  So: rank the
-// 64 lane maxima by counting, let the n_pick best lanes publish their elements >= tau (a
-// handful), and rank those by counting.  All through the wavefront's own piece of LDS.
+// ---- top-k over stored block scores: one wavefront per row ---------------------------------------
+// Only the query-block-shared comparison variant still ranks a stored score matrix (its rows are
+// averages over 64 tokens); the method itself ranks inside pass 2.  Candidates are the blocks
+// n_init .. b_own - n_local; the forced ones are added afterwards.  Scores are positive floats, so
+// their bit patterns order like unsigned integers.  An element is the 64-bit word  key << 32 | ~block
+// with key = bits of the score (1 for a block without visible kernel, -inf): larger word = better
+// element, ties go to the lower block index, no two elements are equal; words below 2^32 are "not a
+// candidate".  Lane l keeps blocks l, l+64, ... in registers; wave_topk ranks them.
 constexpr int kPickRowsPerWg = 4;
-__host__ __device__ inline int pick_cand_cap(int topk, int vpl) { return (topk * vpl + 3) & ~3; }
 
 template <int VPL>
 __global__ __launch_bounds__(256) void select_pick_kernel(Dims dm, const int32_t *__restrict__ seqlens,
@@ -279,10 +337,7 @@ __global__ __launch_bounds__(256) void select_pick_kernel(Dims dm, const int32_t
                                                            int32_t *__restrict__ block_idx, int32_t row_tokens) {
     extern __shared__ __align__(16) unsigned char pick_smem[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int cand_cap = pick_cand_cap(dm.topk, VPL);
-    uint64_t *tmax = reinterpret_cast<uint64_t *>(pick_smem) + (size_t)wave * (64 + cand_cap);
-    uint64_t *cand = tmax + 64;
-    int *picked = reinterpret_cast<int *>(tmax);                              // reused once the ranks are known
+    uint64_t *lds = reinterpret_cast<uint64_t *>(pick_smem) + (size_t)wave * (64 + topk_cand_cap(dm.topk, VPL));
     // a row is one query token, or (row_tokens = 64, the query-block-shared variant) one query block,
     // which selects like its last token
     const int rows_per_seq = (dm.max_seqlen + row_tokens - 1) / row_tokens;
@@ -305,60 +360,14 @@ __global__ __launch_bounds__(256) void select_pick_kernel(Dims dm, const int32_t
     const int lo_local = max(n_init, b_own - dm.n_local + 1);                 // forced trailing: lo_local..b_own
     const int jc_max = lo_local - 1;                                          // candidates: n_init..jc_max
     const int n_pick = n_sel - (n_init + (b_own - lo_local + 1));
-    int mine = 0x7fffffff;                                                    // lane c keeps pick c
+    int picked = 0;
     if (n_pick > 0) {                                                         // uniform over the wavefront
-        uint64_t el[VPL], best = 0ull;
+        uint64_t el[VPL];
 #pragma unroll
-        for (int s = 0; s < VPL; ++s) {
-            const int j = lane + 64 * s;
-            const uint32_t kj = r[s] == -INFINITY ? 1u : __float_as_uint(r[s]);
-            const uint32_t key = (j >= n_init && j <= jc_max) ? kj : 0u;
-            el[s] = ((uint64_t)key << 32) | (uint32_t)~j;
-            best = el[s] > best ? el[s] : best;
-        }
-        tmax[lane] = best;
-        __builtin_amdgcn_wave_barrier();
-        const bool real = best >= kPickValid;
-        const int lrank = count_larger(tmax, 64, best);
-        const bool finalist = real && lrank < n_pick;
-        // tau = the n_pick-th largest lane maximum, if there are that many real ones
-        uint64_t tau = kPickValid;
-        const uint64_t who = __ballot(real && lrank == n_pick - 1);
-        if (who) {
-            const int src = __builtin_ctzll(who);
-            tau = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(best >> 32), src) << 32) |
-                  (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)best, src);
-        }
-        int n_cand = 0;
-        const uint64_t below = (1ull << lane) - 1ull;
-#pragma unroll
-        for (int s = 0; s < VPL; ++s) {
-            const bool pub = finalist && el[s] >= tau;
-            const uint64_t m = __ballot(pub);
-            if (pub) cand[n_cand + __popcll(m & below)] = el[s];
-            n_cand += __popcll(m);
-        }
-        const int n_cand4 = (n_cand + 3) & ~3;                                // <= cand_cap
-        if (lane < n_cand4 - n_cand) cand[n_cand + lane] = 0ull;
-        __builtin_amdgcn_wave_barrier();
-        for (int i = lane; i < n_cand; i += 64) {
-            const uint64_t e = cand[i];
-            const int beaten = count_larger(cand, n_cand4, e);
-            if (beaten < n_pick) picked[beaten] = (int)~(uint32_t)e;
-        }
-        __builtin_amdgcn_wave_barrier();
-        if (lane < n_pick) mine = picked[lane];
+        for (int s = 0; s < VPL; ++s) el[s] = pick_element(r[s], lane + 64 * s, n_init, jc_max);
+        picked = (int)~(uint32_t)wave_topk<VPL>(el, n_pick, lds, lane);
     }
-    if (lane >= n_pick && lane < n_sel) {
-        const int f = lane - n_pick;
-        mine = f < n_init ? f : lo_local + (f - n_init);
-    }
-    // ascending order: rank = number of selected blocks below mine
-    int rank = 0;
-    for (int e = 0; e < n_sel; ++e) rank += __builtin_amdgcn_readlane(mine, e) < mine ? 1 : 0;
-    int32_t *o = block_idx + row * dm.topk;
-    if (lane < n_sel) o[rank] = mine;
-    else if (lane < dm.topk) o[lane] = -1;
+    write_block_row(picked, n_pick, n_sel, n_init, lo_local, dm.topk, block_idx + row * dm.topk, lane);
 }
 
 // Fallback for rows longer than 64*32 blocks: scans the row in memory once per pick.
@@ -416,7 +425,8 @@ __global__ __launch_bounds__(256) void select_pick_scan_kernel(Dims dm, const in
 int32_t select_scores_pitch(const Dims &dm) {
     return (int32_t)(((size_t)(dm.max_seqlen + kBlock - 1) / kBlock + 15) / 16 * 16);
 }
-size_t select_scores_bytes(const Dims &dm) {
+size_t select_scores_bytes(const Dims &dm) {            // only the query-block-shared variant stores scores
+    if (!dm.shared_q) return 0;
     return (size_t)dm.batch * dm.Hkv * dm.max_seqlen * select_scores_pitch(dm) * sizeof(float);
 }
 size_t select_shared_scores_bytes(const Dims &dm) {     // per-query-block scores of the shared variant, behind the per-token ones
@@ -464,7 +474,7 @@ int launch_select_pick(const Dims &dm, const int32_t *seqlens, const float *R, i
     const dim3 grid((uint32_t)((rows + 3) / 4));
     const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
     const int vpl = n_blocks <= 64 * 4 ? 4 : n_blocks <= 64 * 8 ? 8 : n_blocks <= 64 * 16 ? 16 : 32;
-    const size_t lds = (size_t)kPickRowsPerWg * (64 + pick_cand_cap(dm.topk, vpl)) * sizeof(uint64_t);
+    const size_t lds = (size_t)kPickRowsPerWg * (64 + topk_cand_cap(dm.topk, vpl)) * sizeof(uint64_t);
     timing_begin("select_pick_kernel", stream);
     if (n_blocks > 64 * 32 || lds > 64 * 1024)           // very long rows or very wide top-k: generic scan
         hipLaunchKernelGGL(select_pick_scan_kernel, grid, dim3(256), 0, stream, dm, seqlens, R, nb_cap, block_idx, row_tokens);
@@ -504,10 +514,20 @@ static int launch_select_prefill_g(const Dims &dm, Tensor q, Tensor ck, const in
                        seqlens, lse2, n_tiles);
     timing_end(stream);
     timing_begin("select_score_kernel", stream);
-    hipLaunchKernelGGL(select_score_kernel<G>, dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, ck,
-                       seqlens, lse2, R, nb_cap, n_tiles);
+    if (dm.shared_q) {
+        hipLaunchKernelGGL((select_score_kernel<G, false>), dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, ck,
+                           seqlens, lse2, R, nb_cap, n_tiles, block_idx);
+        timing_end(stream);
+        return launch_select_pick(dm, seqlens, R, nb_cap, block_idx, stream);
+    }
+    const size_t lds = ScoreLds<G>(dm.topk).bytes();     // beside 26 to 34 KiB of static LDS
+    const hipError_t e = hipFuncSetAttribute((const void *)select_score_kernel<G, true>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return (int)e;
+    hipLaunchKernelGGL((select_score_kernel<G, true>), dim3((uint32_t)n_wg), dim3(256), lds, stream, dm, q, ck,
+                       seqlens, lse2, R, nb_cap, n_tiles, block_idx);
     timing_end(stream);
-    return launch_select_pick(dm, seqlens, R, nb_cap, block_idx, stream);
+    return (int)hipGetLastError();
 }
 
 int launch_select_prefill(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,

@@ -257,14 +257,35 @@ __global__ __launch_bounds__(256, 2) void select_lse16_kernel(Dims dm, Tensor q,
 }
 
 // ---- pass 2 ----------------------------------------------------------------------------------------
-// Lane = kernel n of the tile, accumulator entries = heads 4g..4g+3 of the token.  Writes the
-// block scores R[token, j] of the candidate blocks j in [n_init, b_own - n_local] (-inf when no
-// visible kernel intersects the block); select_pick_kernel ranks them.
+// Lane = kernel n of the tile, accumulator entries = heads 4g..4g+3 of the token.  The block scores
+// never leave the compute unit: the wavefront keeps the scores of its 8 tokens for a chunk of 64*VPL
+// key-value blocks in LDS, and at the end of a chunk merges them into each token's running top
+// n_pick (wave_topk over the chunk's scores plus the carried picks), so the selection costs no score
+// matrix and no second kernel.  After the last chunk the forced blocks are added and the row written.
+// VPL = 0: the scores R[token, j] of the candidate blocks go to memory instead (-inf when no visible
+// kernel intersects the block); only the query-block-shared comparison variant, which averages them
+// over 64 tokens before ranking, uses that.
+struct Score16Lds {                                      // layout of one wavefront's piece of LDS
+    int chunk_blocks, carry_words, topk_words;
+    __host__ __device__ Score16Lds(int vpl, int topk)
+        : chunk_blocks(64 * vpl), carry_words(kMT * ((topk + 1) & ~1)),
+          topk_words(64 + topk_cand_cap(topk, vpl + 1)) {}
+    __host__ __device__ size_t bytes() const {
+        return (size_t)kMT * chunk_blocks * sizeof(float) + (size_t)(carry_words + topk_words) * sizeof(uint64_t) +
+               kMT * 16 * sizeof(float);
+    }
+};
+
+template <int VPL>
 __global__ __launch_bounds__(256, 2) void select_score16_kernel(Dims dm, Tensor q, const uint4 *__restrict__ ckp,
                                                               int32_t nt_cap, const int32_t *__restrict__ seqlens,
                                                               const float *__restrict__ lse2,
                                                               float *__restrict__ R, int32_t nb_cap,
-                                                              int32_t n_tiles) {
+                                                              int32_t n_tiles, int32_t *__restrict__ block_idx) {
+    extern __shared__ __align__(16) unsigned char score_smem[];
+    constexpr bool kFused = VPL > 0;
+    constexpr int kChunkBlocks = 64 * VPL;
+    constexpr int kChunkTiles = kFused ? kChunkBlocks / 4 : (1 << 30);
     const int tile = n_tiles - 1 - (int)(blockIdx.x % n_tiles);
     const int h = (blockIdx.x / n_tiles) % dm.Hkv;
     const int b = blockIdx.x / (n_tiles * dm.Hkv);
@@ -276,95 +297,135 @@ __global__ __launch_bounds__(256, 2) void select_score16_kernel(Dims dm, Tensor 
     const int n = lane & 15, g = lane >> 4;
     const float c = dm.scale_log2;
 
-    // the 8 tokens share their own block (8 divides 64), hence the candidate range
+    // the 8 tokens share their own block (8 divides 64), hence the candidate range and the counts
     const int b_own = t0 / kBlock, n_blk = b_own + 1;
     const int n_init = dm.n_init < n_blk ? dm.n_init : n_blk;
-    const int jc_max = max(n_init, b_own - dm.n_local + 1) - 1;               // candidates: n_init..jc_max
+    const int lo_local = max(n_init, b_own - dm.n_local + 1);                 // forced trailing: lo_local..b_own
+    const int jc_max = lo_local - 1;                                          // candidates: n_init..jc_max
     const int n_sel = dm.topk < n_blk ? dm.topk : n_blk;
     const int n_pick = n_sel - (n_init + (b_own - jc_max));
-    if (n_pick <= 0 || jc_max < n_init) return;                               // forced blocks only
+    const int64_t row0 = ((int64_t)b * dm.Hkv + h) * dm.max_seqlen + t0;
+    const Score16Lds lay(VPL, dm.topk);
+    float *Rl = reinterpret_cast<float *>(score_smem + (size_t)wave * lay.bytes());   // [kMT][kChunkBlocks]
+    uint64_t *carry = reinterpret_cast<uint64_t *>(Rl + kMT * kChunkBlocks);          // [kMT][carry_words / kMT]
+    uint64_t *tk_lds = carry + lay.carry_words;
+    const int carry_pitch = lay.carry_words / kMT;
+    const int nt_all = (n_pick > 0 && jc_max >= n_init) ? min((4 * jc_max + 4 + 15) >> 4, nt_cap) : 0;
+    if (!kFused && nt_all <= 0) return;                                       // forced blocks only
 
-    bf16x8 qf[kMT][4];
-    load_q16(qf, q, b, h, t0, L, n, g);
-    float nlse[kMT][4];                                                       // -lse of heads 4g+j of token mt
+    if (nt_all > 0) {
+        bf16x8 qf[kMT][4];
+        load_q16(qf, q, b, h, t0, L, n, g);
+        float *nls = reinterpret_cast<float *>(tk_lds + lay.topk_words);    // [kMT][16]: -lse of head, token
+        for (int i = lane; i < kMT * 16; i += 64)
+            nls[i] = (t0 + (i >> 4) < L) ? -lse2[((int64_t)b * dm.max_seqlen + t0 + (i >> 4)) * dm.Hq + h * 16 + (i & 15)] : 0.f;
+        __builtin_amdgcn_wave_barrier();
+        const int nt_pipe = min(n_visible16(t0) >> 4, nt_all);                // tiles needing no mask
+        const uint4 *ckp_head = ckp + ((int64_t)b * dm.Hkv + h) * nt_cap * 256;
+        // packed per-token values: 16-lane group g of half i belongs to token 4i+g
+        float prev_v[2] = {-INFINITY, -INFINITY};
+        float *Rrow[2];
+        bool wr[2];
+        int nvis_tok[2];
 #pragma unroll
-    for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            nlse[mt][j] = (t0 + mt < L) ? -lse2[((int64_t)b * dm.max_seqlen + t0 + mt) * dm.Hq + h * 16 + 4 * g + j]
-                                         : 0.f;
-    const int nt_full = n_visible16(t0) >> 4;                                 // tiles needing no mask
-    const int nt_all = min((4 * jc_max + 4 + 15) >> 4, nt_cap);               // tiles that hold candidate kernels
-    if (nt_all <= 0) return;
-    const int nt_pipe = min(nt_full, nt_all);
-    const uint4 *ckp_head = ckp + ((int64_t)b * dm.Hkv + h) * nt_cap * 256;
-    // packed per-token values: 16-lane group g of half i belongs to token 4i+g
-    float prev_v[2] = {-INFINITY, -INFINITY};
-    float *Rrow[2];
-    bool wr[2];
-    int nvis_tok[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int tok = t0 + 4 * i + g;
-        Rrow[i] = R + (((int64_t)b * dm.Hkv + h) * dm.max_seqlen + tok) * nb_cap + (n >> 2);
-        wr[i] = ((n & 3) == 0) && tok < L;
-        nvis_tok[i] = n_visible16(tok);
-    }
-
-    // epilogue of tile t for half i: 2^(z*c - lse), sum over the 16 heads, mean, floor, causal mask,
-    // 5-wide / stride-4 max over kernels -> lanes n = 0,4,8,12 hold blocks 4t + n/4
-    auto finish = [&](const f32x4 (&z)[kHalf], int i, int t) {
-        float e[kHalf];
-#pragma unroll
-        for (int u = 0; u < kHalf; ++u) {
-            float a = 0.f;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) a += fast_exp2(__builtin_fmaf(z[u][j], c, nlse[kHalf * i + u][j]));
-            e[u] = a;
+        for (int i = 0; i < 2; ++i) {
+            const int tok = t0 + 4 * i + g;
+            Rrow[i] = kFused ? Rl + (4 * i + g) * kChunkBlocks + (n >> 2) : R + (row0 + 4 * i + g) * nb_cap + (n >> 2);
+            wr[i] = ((n & 3) == 0) && tok < L;
+            nvis_tok[i] = n_visible16(tok);
         }
-        // sum over the four 16-lane groups, leaving token u's total in group u (3 lane swaps)
-        typedef unsigned v2u __attribute__((ext_vector_type(2)));
-        const v2u p01 = __builtin_amdgcn_permlane16_swap(__float_as_uint(e[0]), __float_as_uint(e[1]), false, false);
-        const v2u p23 = __builtin_amdgcn_permlane16_swap(__float_as_uint(e[2]), __float_as_uint(e[3]), false, false);
-        const float s01 = __uint_as_float(p01[0]) + __uint_as_float(p01[1]);
-        const float s23 = __uint_as_float(p23[0]) + __uint_as_float(p23[1]);
-        const v2u pq = __builtin_amdgcn_permlane32_swap(__float_as_uint(s01), __float_as_uint(s23), false, false);
-        float v = __uint_as_float(pq[0]) + __uint_as_float(pq[1]);
-        v = fminf(fmaxf(v * (1.f / 16.f), kScoreFloor), kScoreCeil);
-        if (t >= nt_pipe && 16 * t + n >= nvis_tok[i]) v = -INFINITY;         // kernel not visible to this token
-        const float a = fmaxf(v, dpp_f32<kRowShl1>(v, v));
-        const float bq = fmaxf(a, dpp_f32<kRowShl2>(a, a));
-        const float halo0 = dpp_f32<kRowRor1>(prev_v[i], prev_v[i]);          // lane 0 <- previous tile's lane 15
-        const float halo = dpp_f32<kRowShr1>(halo0, v);                       // lane n <- v[n-1]
-        const float w = fmaxf(bq, halo);
-        prev_v[i] = v;
-        const int j = 4 * t + (n >> 2);
-        if (wr[i] && j >= n_init && j <= jc_max) Rrow[i][4 * t] = w;
-    };
+        if (kFused)
+            for (int i = lane; i < lay.carry_words; i += 64) carry[i] = 0ull;
 
-    f32x4 zA[kHalf], zB[kHalf];
-    // two fragment buffers that swap roles each tile (loop unrolled by two: no register copies)
-    Frag4 f0 = load_ck_tile(ckp_head, 0, lane);
-    Frag4 f1 = f0;
-    if (nt_all > 1) f1 = load_ck_tile(ckp_head, 1, lane);
-    mfma_half<false>(f0, qf, 0, zA);
-    mfma_half<false>(f0, qf, kHalf, zB);
-    finish(zA, 0, 0);
-    auto tile_step = [&](const Frag4 &f, int t) {
-        mfma_half<false>(f, qf, 0, zA);                  // matrix work on half A of tile t ...
-        finish(zB, 1, t - 1);                            // ... alternates with the epilogue of half B, tile t-1
-        mfma_half<false>(f, qf, kHalf, zB);
-        finish(zA, 0, t);
-    };
-    int t = 1;
-    for (; t + 1 < nt_all; t += 2) {
-        f0 = load_ck_tile(ckp_head, t + 1, lane);
-        tile_step(f1, t);
-        if (t + 2 < nt_all) f1 = load_ck_tile(ckp_head, t + 2, lane);
-        tile_step(f0, t + 1);
+        // epilogue of tile t for half i: 2^(z*c - lse), sum over the 16 heads, mean, floor, causal mask,
+        // 5-wide / stride-4 max over kernels -> lanes n = 0,4,8,12 hold blocks 4t + n/4
+        auto finish = [&](const f32x4 (&z)[kHalf], int i, int t) {
+            float e[kHalf];
+#pragma unroll
+            for (int u = 0; u < kHalf; ++u) {
+                float a = 0.f;
+                const f32x4 nl4 = *reinterpret_cast<const f32x4 *>(nls + (kHalf * i + u) * 16 + 4 * g);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) a += fast_exp2(__builtin_fmaf(z[u][j], c, nl4[j]));
+                e[u] = a;
+            }
+            // sum over the four 16-lane groups, leaving token u's total in group u (3 lane swaps)
+            typedef unsigned v2u __attribute__((ext_vector_type(2)));
+            const v2u p01 = __builtin_amdgcn_permlane16_swap(__float_as_uint(e[0]), __float_as_uint(e[1]), false, false);
+            const v2u p23 = __builtin_amdgcn_permlane16_swap(__float_as_uint(e[2]), __float_as_uint(e[3]), false, false);
+            const float s01 = __uint_as_float(p01[0]) + __uint_as_float(p01[1]);
+            const float s23 = __uint_as_float(p23[0]) + __uint_as_float(p23[1]);
+            const v2u pq = __builtin_amdgcn_permlane32_swap(__float_as_uint(s01), __float_as_uint(s23), false, false);
+            float v = __uint_as_float(pq[0]) + __uint_as_float(pq[1]);
+            v = fminf(fmaxf(v * (1.f / 16.f), kScoreFloor), kScoreCeil);
+            if (t >= nt_pipe && 16 * t + n >= nvis_tok[i]) v = -INFINITY;     // kernel not visible to this token
+            const float a = fmaxf(v, dpp_f32<kRowShl1>(v, v));
+            const float bq = fmaxf(a, dpp_f32<kRowShl2>(a, a));
+            const float halo0 = dpp_f32<kRowRor1>(prev_v[i], prev_v[i]);      // lane 0 <- previous tile's lane 15
+            const float halo = dpp_f32<kRowShr1>(halo0, v);                   // lane n <- v[n-1]
+            const float w = fmaxf(bq, halo);
+            prev_v[i] = v;
+            if (kFused) {
+                if (wr[i]) Rrow[i][(4 * t) & (kChunkBlocks - 1)] = w;
+            } else {
+                const int j = 4 * t + (n >> 2);
+                if (wr[i] && j >= n_init && j <= jc_max) Rrow[i][4 * t] = w;
+            }
+        };
+
+        // the tiles [ta, te) through the software pipeline
+        auto run_tiles = [&](int ta, int te) {
+            f32x4 zA[kHalf], zB[kHalf];
+            // two fragment buffers that swap roles each tile (loop unrolled by two: no register copies)
+            Frag4 f0 = load_ck_tile(ckp_head, ta, lane);
+            Frag4 f1 = f0;
+            if (ta + 1 < te) f1 = load_ck_tile(ckp_head, ta + 1, lane);
+            mfma_half<false>(f0, qf, 0, zA);
+            mfma_half<false>(f0, qf, kHalf, zB);
+            finish(zA, 0, ta);
+            auto tile_step = [&](const Frag4 &f, int t) {
+                mfma_half<false>(f, qf, 0, zA);              // matrix work on half A of tile t ...
+                finish(zB, 1, t - 1);                        // ... alternates with the epilogue of half B, tile t-1
+                mfma_half<false>(f, qf, kHalf, zB);
+                finish(zA, 0, t);
+            };
+            int t = ta + 1;
+            for (; t + 1 < te; t += 2) {
+                f0 = load_ck_tile(ckp_head, t + 1, lane);
+                tile_step(f1, t);
+                if (t + 2 < te) f1 = load_ck_tile(ckp_head, t + 2, lane);
+                tile_step(f0, t + 1);
+            }
+            if (t < te) tile_step(f1, t);
+            finish(zB, 1, te - 1);
+        };
+
+        for (int ta = 0; ta < nt_all; ta += kChunkTiles) {
+            run_tiles(ta, min(ta + kChunkTiles, nt_all));
+            if (kFused) {                                                     // merge the chunk into the running picks
+                __builtin_amdgcn_wave_barrier();
+                const int j0 = 4 * ta;
+                for (int u = 0; u < kMT && t0 + u < L; ++u) {
+                    constexpr int NE = kFused ? VPL + 1 : 1;
+                    uint64_t el[NE];
+#pragma unroll
+                    for (int s2 = 0; s2 < NE - 1; ++s2)
+                        el[s2] = pick_element(Rl[u * kChunkBlocks + lane + 64 * s2], j0 + lane + 64 * s2, n_init, jc_max);
+                    el[NE - 1] = lane < n_pick ? carry[u * carry_pitch + lane] : 0ull;
+                    const uint64_t res = wave_topk<NE>(el, n_pick, tk_lds, lane);
+                    if (lane < n_pick) carry[u * carry_pitch + lane] = res;
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
     }
-    if (t < nt_all) tile_step(f1, t);
-    finish(zB, 1, nt_all - 1);
+    if (kFused) {
+        for (int u = 0; u < kMT && t0 + u < L; ++u) {
+            const int picked = (nt_all > 0 && lane < n_pick) ? (int)~(uint32_t)carry[u * carry_pitch + lane] : 0;
+            write_block_row(picked, n_pick > 0 ? n_pick : 0, n_sel, n_init, lo_local, dm.topk,
+                            block_idx + (row0 + u) * dm.topk, lane);
+        }
+    }
 }
 
 // Tiles of 16 fine kernels in the fragment-major copy: those that hold a kernel of the longest sequence,
@@ -378,6 +439,15 @@ static int32_t coarse_tiles_cap(const Dims &dm) {
 static size_t coarse_tiles_bytes(const Dims &dm) {
     const size_t b = (size_t)dm.batch * dm.Hkv * coarse_tiles_cap(dm) * 256 * sizeof(uint4);
     return (b + 255) / 256 * 256;
+}
+
+// Key-value blocks per chunk of the in-kernel top-k, in units of 64: the whole row in one chunk when it
+// fits, and never more LDS than lets two workgroups share a compute unit.
+static int score16_vpl(const Dims &dm) {
+    const int n_blocks = (dm.max_seqlen + kBlock - 1) / kBlock;
+    int vpl = n_blocks <= 128 ? 2 : n_blocks <= 256 ? 4 : 8;
+    while (vpl > 2 && 4 * Score16Lds(vpl, dm.topk).bytes() > 80 * 1024) vpl /= 2;
+    return vpl;
 }
 
 size_t select_prefill16_ws_bytes(const Dims &dm) {
@@ -421,10 +491,33 @@ int launch_select_prefill16(const Dims &dm, Tensor q, Tensor ck, const int32_t *
                            dm.rho > 1 ? ckp_c : ckp, dm.rho > 1 ? ntc_cap : nt_cap, seqlens, lse2, n_tiles);
         timing_end(stream);
         timing_begin("select_score16_kernel", stream);
-        hipLaunchKernelGGL(select_score16_kernel, dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, ckp, nt_cap,
-                           seqlens, lse2, R, nb_cap, n_tiles);
+        if (dm.shared_q) {
+            hipLaunchKernelGGL(select_score16_kernel<0>, dim3((uint32_t)n_wg), dim3(256),
+                               4 * Score16Lds(0, dm.topk).bytes(), stream, dm, q, ckp, nt_cap, seqlens, lse2, R, nb_cap,
+                               n_tiles, block_idx);
+        } else {
+            const int vpl = score16_vpl(dm);
+            const size_t lds = 4 * Score16Lds(vpl, dm.topk).bytes();
+            const void *fn = vpl == 8 ? (const void *)select_score16_kernel<8>
+                             : vpl == 4 ? (const void *)select_score16_kernel<4>
+                                        : (const void *)select_score16_kernel<2>;
+            if (lds > 64 * 1024) {
+                const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                if (e != hipSuccess) return (int)e;
+            }
+            if (vpl == 8)
+                hipLaunchKernelGGL(select_score16_kernel<8>, dim3((uint32_t)n_wg), dim3(256), lds, stream, dm, q, ckp,
+                                   nt_cap, seqlens, lse2, R, nb_cap, n_tiles, block_idx);
+            else if (vpl == 4)
+                hipLaunchKernelGGL(select_score16_kernel<4>, dim3((uint32_t)n_wg), dim3(256), lds, stream, dm, q, ckp,
+                                   nt_cap, seqlens, lse2, R, nb_cap, n_tiles, block_idx);
+            else
+                hipLaunchKernelGGL(select_score16_kernel<2>, dim3((uint32_t)n_wg), dim3(256), lds, stream, dm, q, ckp,
+                                   nt_cap, seqlens, lse2, R, nb_cap, n_tiles, block_idx);
+        }
         timing_end(stream);
     }
+    if (!dm.shared_q) return (int)hipGetLastError();     // the rows were ranked and written inside pass 2
     return launch_select_pick(dm, seqlens, R, nb_cap, block_idx, stream);
 }
 

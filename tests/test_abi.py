@@ -103,9 +103,15 @@ def test_workspace_validation(lib):
     prm = good_params()
     need = lib.infllmv2_workspace_bytes(binding.OP_SELECT_PREFILL, ctypes.byref(prm), 1, 4096)
     # fp32 log-sum-exp per (token, head) + fragment-major copy of the compressed keys (4 KiB per
-    # 16 kernels: 254 kernels = 16 tiles, plus the tile a last candidate block may reach into) + fp32
-    # block scores per (token, kv head, block)
-    assert need == 4096 * 32 * 4 + 2 * 17 * 4096 + 2 * 4096 * 64 * 4
+    # 16 kernels: 254 kernels = 16 tiles, plus the tile a last candidate block may reach into); no
+    # score matrix: linear in max_seqlen
+    assert need == 4096 * 32 * 4 + 2 * 17 * 4096
+    need_long = lib.infllmv2_workspace_bytes(binding.OP_SELECT_PREFILL, ctypes.byref(prm), 1, 32 * 4096)
+    assert need_long <= 33 * need
+    # the query-block-shared comparison variant still stores fp32 block scores per (token, kv head, block)
+    # and per (query block, kv head, block)
+    need_shared = lib.infllmv2_workspace_bytes(binding.OP_SELECT_SHARED, ctypes.byref(prm), 1, 4096)
+    assert need_shared == need + 2 * 4096 * 64 * 4 + 2 * 64 * 64 * 4
     assert lib.infllmv2_workspace_bytes(binding.OP_ATTN_PREFILL, ctypes.byref(prm), 1, 4096) == 2 * 64 * 32768
     assert lib.infllmv2_workspace_bytes(binding.OP_ATTN_DECODE, ctypes.byref(prm), 2, 4096) > 0
     assert lib.infllmv2_workspace_bytes(99, ctypes.byref(prm), 1, 4096) == 0
@@ -223,8 +229,10 @@ def test_shared_variant_validation(lib):
     prm, t = good_params(), tensor()
     P, T = ctypes.byref(prm), ctypes.byref(t)
     need = lib.infllmv2_workspace_bytes(binding.OP_SELECT_SHARED, P, 1, 4096)
-    # the per-token selection's scratch plus fp32 scores of 64 query blocks x 64 blocks x 2 kv heads
-    assert need == lib.infllmv2_workspace_bytes(binding.OP_SELECT_PREFILL, P, 1, 4096) + 2 * 64 * 64 * 4
+    # the per-token selection's scratch plus fp32 scores of 4096 tokens x 64 blocks x 2 kv heads (this
+    # variant averages stored scores) and of 64 query blocks x 64 blocks x 2 kv heads
+    assert need == (lib.infllmv2_workspace_bytes(binding.OP_SELECT_PREFILL, P, 1, 4096) + 2 * 4096 * 64 * 4 +
+                    2 * 64 * 64 * 4)
     sel = lambda w=FAKE, wb=1 << 40, idx=FAKE: lib.infllmv2_select_blocks_shared(P, T, T, FAKE, 1, 4096, idx, w, wb, None)
     assert sel(idx=None) == INVALID and sel(w=None, wb=0) == WORKSPACE and sel(wb=need - 1) == WORKSPACE
     att = lambda w=FAKE, wb=1 << 40, idx=FAKE: lib.infllmv2_sparse_attn_prefill_shared(

@@ -190,9 +190,9 @@ def test_select_blocks_prefill_own_block_is_a_candidate(Hq, Hkv, topk, fill):
 @pytest.mark.parametrize("cap", [20000, 40000, 70000, 132000])
 @pytest.mark.parametrize("Hq,Hkv,n_local,topk", [(16, 1, 2, 16), (16, 1, 0, 16), (4, 1, 1, 16), (16, 1, 1, 48), (16, 1, 1, 64)])
 def test_select_blocks_prefill_long_capacity(Hq, Hkv, n_local, topk, cap):
-    # the top-k kernel is chosen by the capacity of the buffers (blocks per lane: 8 up to 32768 tokens, 16 up
-    # to 65536, 32 up to 131072, above that, or when top-k times blocks per lane needs more than 64 KB of LDS,
-    # a generic scan); short sequences in long buffers reach every one
+    # the chunk of blocks pass 2 ranks at a time is chosen by the capacity of the buffers and by top-k (128,
+    # 256 or 512 blocks; fewer when a wide top-k needs the on-chip memory); short sequences in long buffers
+    # reach every variant
     seqlens = [5000, 257]
     prm = binding.Params(Hq, Hkv, topk=topk, n_init_blocks=1, n_local_blocks=n_local)
     oprm = oracle_params(prm)
@@ -217,6 +217,36 @@ def test_select_blocks_prefill_long_capacity(Hq, Hkv, n_local, topk, cap):
         assert not hard, (b, hard[:3])
         near += nt
     assert near <= 2
+
+
+@pytest.mark.parametrize("l,Hq,Hkv,topk,n_local", [(40000, 16, 1, 16, 2),    # G = 16: chunks of 512 blocks, 2 chunks
+                                                   (20000, 16, 1, 64, 1),    # wide top-k: chunks of 256 blocks
+                                                   (36000, 4, 1, 16, 0),     # other group sizes: chunks of 256, 3 chunks
+                                                   (17000, 2, 2, 8, 1)])     # G = 1
+def test_select_blocks_prefill_rows_longer_than_one_chunk(l, Hq, Hkv, topk, n_local):
+    # pass 2 ranks the block scores chunk by chunk inside the kernel and carries the running picks from
+    # chunk to chunk: sequences long enough for several chunks, checked on sampled query rows (the rows
+    # around the positions where a new chunk starts, the last rows, and random ones)
+    print("case select prefill chunks", l, Hq, Hkv, topk, n_local, flush=True)
+    prm = binding.Params(Hq, Hkv, topk=topk, n_init_blocks=1, n_local_blocks=n_local)
+    oprm = oracle_params(prm)
+    q, k, v, T = make_batch(91, [l], Hq, Hkv, n_planted=40)
+    qd, kd, sl = to_dev(q), to_dev(k), dev_i32([l])
+    ck = binding.compress_keys(prm, kd, sl, T)
+    idx = binding.select_blocks(prm, binding.MODE_PREFILL, qd, ck, sl, T)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    pos = set(rng.integers(0, l, 150).tolist()) | set(range(l - 40, l))
+    for edge in (256 * 64, 512 * 64):
+        pos |= {p_ for p_ in range(edge - 70, edge + 200) if 0 <= p_ < l}
+    pos = np.array(sorted(pos), np.int32)
+    ckb = to_bits(ck)
+    idx_np = idx[0].cpu().numpy()
+    want, margins, R = ref.select_blocks(q[0, pos], ckb[0, :, :ref.num_kernels(l, 32, 16)], pos, oprm, want_scores=True)
+    n, e, nt, hard = compare_selection(idx_np[:, pos], want, margins, R)
+    print("rows %d exact %d near-tie %d" % (n, e, nt), flush=True)
+    assert not hard, hard[:3]
+    assert nt <= max(2, n // 200)
 
 
 @pytest.mark.parametrize("seqlens,Hq,Hkv,topk,planted", PREFILL_CASES)

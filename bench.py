@@ -704,7 +704,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     from paper_2506_07900_amd import binding
-    binding.load_library()          # fails loudly when the HIP library is missing
+    # the bench build of the library: same kernels and entry points, plus per-kernel event timing and the
+    # probe kernels; fails loudly when it has not been built
+    binding.load_bench_library()
 
     if args.calibrate_copy:
         src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")

@@ -93,7 +93,11 @@ typedef struct infllmv2_params {
     int32_t lse_coarse_ratio; /* rho = s_c / s of the approximate log-sum-exp of the relevance softmax
                                 ("Efficient Top-K Implementation", last paragraph); 0 or 1 = exact.
                                 rho = 2 or 4 needs G = 16 and
-                                (n_init_blocks + n_local_blocks) * m >= 2 * rho * s.  A coarse kernel is
+                                (n_init_blocks + n_local_blocks) * m >= 2 * rho * s (other group sizes
+                                return INFLLMV2_ERR_UNSUPPORTED: the coarse pass exists in the kernels
+                                specialised for G = 16, the group size of "Hyper-Parameter
+                                Recommendation", only; every other G runs the exact two passes, of which
+                                this is an optimisation).  A coarse kernel is
                                 the bf16-rounded mean of the rho disjoint semantic kernels
                                 rho*c, rho*c+2, .., that tile tokens [rho*s*c, rho*s*(c+2)); the
                                 softmax denominator of a query head becomes
@@ -160,6 +164,23 @@ int32_t infllmv2_select_blocks(const infllmv2_params *prm, int32_t mode, const i
                                const infllmv2_tensor *ck, const int32_t *seqlens, int32_t batch,
                                int32_t max_seqlen, int32_t *block_idx, void *workspace,
                                size_t workspace_bytes, void *stream);
+
+/*
+ * The block scores stage 2 ranks, for inspection and for checking the selection's arithmetic (not a
+ * step of the method: infllmv2_select_blocks ranks the same scores on chip and never stores them).
+ * Prefill queries only.  For every key-value head h, query token t < seqlens[b] and candidate block j
+ * (n_init_blocks <= j <= floor(t/m) - n_local_blocks):
+ *     block_scores[((b * Hkv + h) * max_seqlen + t) * scores_pitch + j] = R[j]   of Eq. 1 as stated above,
+ * fp32, -inf when no semantic kernel that intersects block j is visible to the query.  Entries of
+ * other blocks and of rows t >= seqlens[b] may or may not be written.
+ *   block_scores  out  fp32 device buffer of batch * Hkv * max_seqlen * scores_pitch elements
+ *   scores_pitch       row pitch in elements, >= ceil(max_seqlen / m)
+ *   workspace          as for infllmv2_select_blocks in prefill mode (INFLLMV2_OP_SELECT_PREFILL)
+ */
+int32_t infllmv2_block_scores(const infllmv2_params *prm, const infllmv2_tensor *q,
+                              const infllmv2_tensor *ck, const int32_t *seqlens, int32_t batch,
+                              int32_t max_seqlen, float *block_scores, int32_t scores_pitch,
+                              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Stage 3, prefill -- attention over the selected blocks (section 2.1.1, second stage):
@@ -372,37 +393,6 @@ int32_t infllmv2_sparse_attn_prefill_shared(const infllmv2_params *prm, const in
                                             const int32_t *seqlens, int32_t batch, int32_t max_seqlen,
                                             const int32_t *block_idx, const infllmv2_tensor *out, float *lse,
                                             void *workspace, size_t workspace_bytes, void *stream);
-
-/*
- * Measured practical peaks for the benchmark's rooflines (not part of the method).  Launches
- * probe kernels on `stream`: a dense bf16 MFMA loop ("probe_mfma_kernel"), a read of every byte
- * of `buf` ("probe_stream_kernel"), and the instruction mix of a softmax kernel as matrix work
- * alone, vector work alone and both together ("probe_mix_mfma_kernel", "probe_mix_valu_kernel",
- * "probe_mix_both_kernel": the same loop count each, so their durations compare directly); the
- * durations are obtained like any other kernel's, through infllmv2_timing_enable /
- * infllmv2_timing_read.
- *   buf            in   DEVICE buffer, 256-byte aligned, at least 8 MiB, ZERO-FILLED by the caller
- *                       (it is only read; a size far above the cache sizes measures HBM)
- *   mfma_flops     out  HOST: floating-point operations the MFMA probe executes per launch
- *   stream_bytes   out  HOST: bytes the stream probe reads per launch
- */
-int32_t infllmv2_probe_peaks(void *buf, size_t buf_bytes, double *mfma_flops, double *stream_bytes,
-                             void *stream);
-
-/*
- * Per-kernel timing for benchmarks (the measurement the roofline figures are built on).
- * While enabled, every kernel launched by the entry points above is bracketed by HIP events
- * recorded on the call's stream; at most 256 launches are kept between reads.  Process-wide
- * state, not thread-safe; leave it off in production (each launch costs two event records).
- *   infllmv2_timing_enable  enable != 0 creates the events on the current device on first use
- *                           and clears the log; 0 switches recording off.
- *   infllmv2_timing_read    waits for the recorded launches to finish, writes up to max_entries
- *                           (kernel name, milliseconds) pairs in launch order into the HOST
- *                           arrays names / ms, clears the log, and returns the count (>= 0) or
- *                           a negative status.
- */
-int32_t infllmv2_timing_enable(int32_t enable);
-int32_t infllmv2_timing_read(int32_t max_entries, const char **names, float *ms);
 
 #ifdef __cplusplus
 }

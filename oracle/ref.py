@@ -1,8 +1,10 @@
 """ctypes wrapper around the C oracle (`infllmv2_oracle.c`).
 
-TEST INFRASTRUCTURE ONLY.  Marshals numpy arrays to the C functions; holds no
-arithmetic of the method.  bf16 tensors are numpy uint16 arrays of bit patterns.
-One sequence per call.
+TEST INFRASTRUCTURE ONLY.  Marshals numpy arrays to the C functions, which hold the arithmetic
+of the method.  The one exception is select_blocks_shared, the query-block-shared comparison
+variant (not the report's method): it averages the per-token block scores the C oracle returns
+over each query block and ranks them here, in plain Python loops.  bf16 tensors are numpy uint16
+arrays of bit patterns.  One sequence per call.
 
 Layouts (C-contiguous):
   q      [Tq, Hq, d]    row t is the query token at position pos[t]
@@ -19,7 +21,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "infllmv2_oracle.c")
-_LIB = os.path.join(_HERE, "libinfllmv2_oracle.so")
+# INFLLMV2_ORACLE_SANITIZE=undefined: a second build with UndefinedBehaviorSanitizer (any report aborts),
+# so that the pins can be run once more over instrumented code (tests/test_sanitizers.py)
+_SANITIZE = os.environ.get("INFLLMV2_ORACLE_SANITIZE", "")
+_LIB = os.path.join(_HERE, "libinfllmv2_oracle%s.so" % ("_" + _SANITIZE if _SANITIZE else ""))
 _lib = None
 
 
@@ -27,8 +32,9 @@ def build(force=False):
     """Compile the C oracle with gcc (CPU only)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp%d" % os.getpid()
+        san = ["-g", "-fsanitize=" + _SANITIZE, "-fno-sanitize-recover=all"] if _SANITIZE else []
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
-                               "-ffp-contract=off", "-o", tmp, _SRC, "-lm"])
+                               "-ffp-contract=off"] + san + ["-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 

@@ -19,6 +19,7 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libinfllmv2.so")
+BENCH_LIB_PATH = os.path.join(_HERE, "libinfllmv2_bench.so")   # + per-kernel timing and probes (include/infllmv2_bench.h)
 
 OK = 0
 OP_SELECT_PREFILL, OP_SELECT_DECODE, OP_ATTN_PREFILL, OP_ATTN_DECODE = 1, 2, 3, 4
@@ -33,7 +34,8 @@ EXPORTS = ["infllmv2_status_string", "infllmv2_workspace_bytes", "infllmv2_compr
            "infllmv2_select_blocks", "infllmv2_sparse_attn_prefill", "infllmv2_sparse_attn_decode", "infllmv2_sparse_attn_decode_noalloc",
            "infllmv2_sparse_attn_bwd", "infllmv2_append_kv", "infllmv2_decode_step", "infllmv2_select_blocks_shared", "infllmv2_sparse_attn_prefill_shared", "infllmv2_verify_workspace_bytes", "infllmv2_append_kv_verify",
            "infllmv2_select_blocks_verify", "infllmv2_sparse_attn_verify", "infllmv2_verify_step",
-           "infllmv2_probe_peaks", "infllmv2_timing_enable", "infllmv2_timing_read"]
+           "infllmv2_block_scores"]
+BENCH_EXPORTS = ["infllmv2_probe_peaks", "infllmv2_timing_enable", "infllmv2_timing_read"]
 
 
 class CParams(ctypes.Structure):
@@ -101,6 +103,8 @@ def load_library(path=None):
     lib.infllmv2_compress_keys.argtypes = [P, T, vp, i32, i32, i32, T, vp]
     lib.infllmv2_select_blocks.restype = i32
     lib.infllmv2_select_blocks.argtypes = [P, i32, T, T, vp, i32, i32, vp, vp, sz, vp]
+    lib.infllmv2_block_scores.restype = i32
+    lib.infllmv2_block_scores.argtypes = [P, T, T, vp, i32, i32, vp, i32, vp, sz, vp]
     lib.infllmv2_sparse_attn_prefill.restype = i32
     lib.infllmv2_sparse_attn_prefill.argtypes = [P, T, T, T, vp, i32, i32, vp, T, vp, vp, sz, vp]
     lib.infllmv2_sparse_attn_decode.restype = i32
@@ -127,13 +131,27 @@ def load_library(path=None):
     lib.infllmv2_verify_step.argtypes = [P, T, T, T, T, T, T, vp, i32, i32, i32, vp, vp, T, vp, vp, sz, vp]
     lib.infllmv2_sparse_attn_verify.restype = i32
     lib.infllmv2_sparse_attn_verify.argtypes = [P, T, T, T, vp, i32, i32, i32, vp, vp, T, vp, vp, sz, vp]
-    lib.infllmv2_probe_peaks.restype = i32
-    lib.infllmv2_probe_peaks.argtypes = [vp, sz, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp]
-    lib.infllmv2_timing_enable.restype = i32
-    lib.infllmv2_timing_enable.argtypes = [i32]
-    lib.infllmv2_timing_read.restype = i32
-    lib.infllmv2_timing_read.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float)]
+    if hasattr(lib, "infllmv2_timing_enable"):            # the bench build
+        lib.infllmv2_probe_peaks.restype = i32
+        lib.infllmv2_probe_peaks.argtypes = [vp, sz, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp]
+        lib.infllmv2_timing_enable.restype = i32
+        lib.infllmv2_timing_enable.argtypes = [i32]
+        lib.infllmv2_timing_read.restype = i32
+        lib.infllmv2_timing_read.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float)]
     _lib = lib
+    return lib
+
+
+def load_bench_library():
+    """Make libinfllmv2_bench.so the library every call of this module goes through: the same entry points,
+    plus timing_enable / timing_read / probe_peaks.  For benchmarks; call it before anything else."""
+    return load_library(BENCH_LIB_PATH)
+
+
+def _bench_lib():
+    lib = load_library()
+    if not hasattr(lib, "infllmv2_timing_enable"):
+        raise InfLLMv2Error("per-kernel timing and the probes are in libinfllmv2_bench.so only: call load_bench_library() first")
     return lib
 
 
@@ -175,14 +193,14 @@ def _stream():
 
 
 def timing_enable(enable):
-    _check(load_library().infllmv2_timing_enable(1 if enable else 0), "infllmv2_timing_enable")
+    _check(_bench_lib().infllmv2_timing_enable(1 if enable else 0), "infllmv2_timing_enable")
 
 
 def timing_read(max_entries=256):
     """-> list of (kernel name, milliseconds) for the launches recorded since the last read."""
     names = (ctypes.c_char_p * max_entries)()
     ms = (ctypes.c_float * max_entries)()
-    n = load_library().infllmv2_timing_read(max_entries, names, ms)
+    n = _bench_lib().infllmv2_timing_read(max_entries, names, ms)
     if n < 0:
         _check(n, "infllmv2_timing_read")
     return [(names[i].decode(), float(ms[i])) for i in range(n)]
@@ -233,11 +251,28 @@ def append_kv(prm, k_new, v_new, k, v, seqlens, max_seqlen, ck=None):
 def probe_peaks(buf):
     """Launch the two probe kernels over the zero-filled uint8 device buffer `buf`;
     -> (flops of the MFMA probe, bytes of the stream probe).  Durations come from timing_read()."""
-    lib = load_library()
+    lib = _bench_lib()
     fl, by = ctypes.c_double(), ctypes.c_double()
     _check(lib.infllmv2_probe_peaks(buf.data_ptr(), buf.numel(), ctypes.byref(fl), ctypes.byref(by), _stream()),
            "infllmv2_probe_peaks")
     return fl.value, by.value
+
+
+def block_scores(prm, q, ck, seqlens, max_seqlen, scores=None, workspace=None):
+    """-> fp32 [B, Hkv, max_seqlen, n_blocks]: the block scores of the candidate blocks of every prefill
+    query (entries of other blocks keep the NaN the buffer is created with)."""
+    lib = load_library()
+    B = q.shape[0]
+    nb = (max_seqlen + prm.block_size - 1) // prm.block_size
+    if scores is None:
+        scores = torch.full((B, prm.n_kv_heads, max_seqlen, nb), float("nan"), dtype=torch.float32, device=q.device)
+    ws, ws_bytes = _workspace(OP_SELECT_PREFILL, prm, B, max_seqlen, workspace, q.device)
+    qd, ckd = _query_desc(q, "q"), _cache_desc(ck, "ck")
+    _check(lib.infllmv2_block_scores(ctypes.byref(prm.c()), ctypes.byref(qd), ctypes.byref(ckd),
+                                     _i32(seqlens, "seqlens").data_ptr(), B, max_seqlen, scores.data_ptr(),
+                                     scores.stride(2), ws.data_ptr(), ws_bytes, _stream()),
+           "infllmv2_block_scores")
+    return scores
 
 
 def select_blocks(prm, mode, q, ck, seqlens, max_seqlen, block_idx=None, workspace=None):

@@ -92,29 +92,6 @@ int32_t hip_status(int e) { return e == 0 ? INFLLMV2_OK : INFLLMV2_ERR_HIP; }
 
 }  // namespace
 
-// ---- per-kernel timing ---------------------------------------------------------------------------
-namespace {
-constexpr int kMaxTimed = 256;
-bool g_timing = false;
-int g_timed = 0;
-hipEvent_t g_ev[2 * kMaxTimed];
-bool g_ev_made = false;
-const char *g_names[kMaxTimed];
-}  // namespace
-
-namespace infllmv2 {
-void timing_begin(const char *kernel_name, hipStream_t stream) {
-    if (!g_timing || g_timed >= kMaxTimed) return;
-    g_names[g_timed] = kernel_name;
-    (void)hipEventRecord(g_ev[2 * g_timed], stream);
-}
-void timing_end(hipStream_t stream) {
-    if (!g_timing || g_timed >= kMaxTimed) return;
-    (void)hipEventRecord(g_ev[2 * g_timed + 1], stream);
-    ++g_timed;
-}
-}  // namespace infllmv2
-
 namespace infllmv2 {
 // Host-side validation of the stage-3 decode arguments, shared by the entry points that differ only in
 // where their scratch memory comes from.
@@ -139,36 +116,6 @@ int32_t validate_attn_decode(const infllmv2_params *prm, const infllmv2_tensor *
 }  // namespace infllmv2
 
 extern "C" {
-
-int32_t infllmv2_timing_enable(int32_t enable) {
-    if (enable && !g_ev_made) {
-        for (int i = 0; i < 2 * kMaxTimed; ++i)
-            if (hipEventCreate(&g_ev[i]) != hipSuccess) return INFLLMV2_ERR_HIP;
-        g_ev_made = true;
-    }
-    g_timing = enable != 0;
-    g_timed = 0;
-    return INFLLMV2_OK;
-}
-
-int32_t infllmv2_timing_read(int32_t max_entries, const char **names, float *ms) {
-    if (max_entries < 0 || (max_entries > 0 && (!names || !ms))) return INFLLMV2_ERR_INVALID_ARGUMENT;
-    const int n = g_timed < max_entries ? g_timed : max_entries;
-    for (int i = 0; i < n; ++i) {
-        if (hipEventSynchronize(g_ev[2 * i + 1]) != hipSuccess) return INFLLMV2_ERR_HIP;
-        if (hipEventElapsedTime(&ms[i], g_ev[2 * i], g_ev[2 * i + 1]) != hipSuccess) return INFLLMV2_ERR_HIP;
-        names[i] = g_names[i];
-    }
-    g_timed = 0;
-    return n;
-}
-
-int32_t infllmv2_probe_peaks(void *buf, size_t buf_bytes, double *mfma_flops, double *stream_bytes, void *stream) {
-    if (!buf || !mfma_flops || !stream_bytes || buf_bytes < (size_t)(8u << 20) ||
-        (reinterpret_cast<uintptr_t>(buf) & 255u) != 0)
-        return INFLLMV2_ERR_INVALID_ARGUMENT;
-    return hip_status(launch_probes(buf, buf_bytes, mfma_flops, stream_bytes, reinterpret_cast<hipStream_t>(stream)));
-}
 
 const char *infllmv2_status_string(int32_t status) {
     switch (status) {
@@ -386,6 +333,24 @@ int32_t infllmv2_select_blocks(const infllmv2_params *prm, int32_t mode, const i
                                                 workspace, st));
     return hip_status(launch_select_decode(dm, make_tensor(q), make_tensor(ck), seqlens, block_idx,
                                            workspace, st));
+}
+
+int32_t infllmv2_block_scores(const infllmv2_params *prm, const infllmv2_tensor *q, const infllmv2_tensor *ck,
+                              const int32_t *seqlens, int32_t batch, int32_t max_seqlen, float *block_scores,
+                              int32_t scores_pitch, void *workspace, size_t workspace_bytes, void *stream) {
+    RETURN_IF_ERR(check_params(prm));
+    RETURN_IF_ERR(check_sizes(batch, max_seqlen));
+    RETURN_IF_ERR(check_tensor(q));
+    RETURN_IF_ERR(check_tensor(ck));
+    if (!seqlens || !block_scores || scores_pitch < (max_seqlen + prm->block_size - 1) / prm->block_size)
+        return INFLLMV2_ERR_INVALID_ARGUMENT;
+    const Dims dm = make_dims(prm, batch, max_seqlen);
+    const size_t need = select_prefill_ws_bytes(dm);
+    if (need > 0 && (!workspace || workspace_bytes < need ||
+                     (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0))
+        return INFLLMV2_ERR_WORKSPACE;
+    return hip_status(launch_select_prefill(dm, make_tensor(q), make_tensor(ck), seqlens, nullptr, workspace,
+                                            reinterpret_cast<hipStream_t>(stream), block_scores, scores_pitch));
 }
 
 int32_t infllmv2_select_blocks_shared(const infllmv2_params *prm, const infllmv2_tensor *q,

@@ -224,12 +224,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(Dims dm, Tensor q, 
         own[u] = e;
     }
     // ascending union of the two block lists by counting (an entry's place = number of distinct smaller entries)
+    // (a block listed twice in one row, against the contract, counts once: the copy in the higher lane is dropped)
     int w[kDqTok];
-    w[0] = own[0];
-    {
+#pragma unroll
+    for (int u = 0; u < kDqTok; ++u) {
         bool dup = false;
-        for (int j = 0; j < dm.topk; ++j) dup |= __builtin_amdgcn_readlane(own[0], j) == own[1];
-        w[1] = dup ? kBwdNone : own[1];
+        for (int j = 0; j < dm.topk; ++j) dup |= j < lane && __builtin_amdgcn_readlane(own[u], j) == own[u];
+        if (u == 1)
+            for (int j = 0; j < dm.topk; ++j) dup |= __builtin_amdgcn_readlane(own[0], j) == own[1];
+        w[u] = dup ? kBwdNone : own[u];
     }
     int rank[kDqTok] = {0, 0}, bits[kDqTok] = {0, 0};
 #pragma unroll

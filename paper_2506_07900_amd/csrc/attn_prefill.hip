@@ -185,11 +185,13 @@ __global__ __launch_bounds__(256, kWavesPerSimd) void attn_prefill_kernel(Dims d
     // is the number of distinct smaller entries.  A token's own list holds no duplicates, so an
     // entry is a duplicate exactly when a lower-numbered token of the wavefront lists the same
     // block.  Entry i of the union ends up in lane i%64 of ul[i/64] as block | member bits << 27.
+    // (A caller's row that lists a block twice, against the contract, is attended once: the copy in the
+    // higher lane counts as a duplicate too, so every rank below is taken by exactly one entry.)
     int w[kTok];                                         // own[u] with duplicates removed
-    w[0] = own[0];
 #pragma unroll
-    for (int u = 1; u < kTok; ++u) {
+    for (int u = 0; u < kTok; ++u) {
         bool dup = false;
+        for (int j = 0; j < dm.topk; ++j) dup |= j < lane && __builtin_amdgcn_readlane(own[u], j) == own[u];
 #pragma unroll
         for (int u2 = 0; u2 < u; ++u2)
             for (int j = 0; j < dm.topk; ++j) dup |= __builtin_amdgcn_readlane(own[u2], j) == own[u];

@@ -209,10 +209,16 @@ __device__ inline void write_block_row(int picked, int n_pick, int n_sel, int n_
     else if (lane < topk) o[lane] = -1;
 }
 
-// Optional per-kernel timing (infllmv2_timing_enable): when on, every launch is bracketed by HIP
-// events on the launch stream.  No-ops when off.
+// Per-kernel timing of the bench-only build (INFLLMV2_TIMING, see timing.hip): every launch is bracketed
+// by HIP events on its stream while infllmv2_timing_enable is on.  The production build compiles the
+// hooks away.
+#ifdef INFLLMV2_TIMING
 void timing_begin(const char *kernel_name, hipStream_t stream);
 void timing_end(hipStream_t stream);
+#else
+inline void timing_begin(const char *, hipStream_t) {}
+inline void timing_end(hipStream_t) {}
+#endif
 
 // Launchers implemented in the .hip files; each returns a hipError_t as int.
 int launch_compress_keys(const Dims &dm, Tensor k, Tensor ck, const int32_t *seqlens,
@@ -220,10 +226,12 @@ int launch_compress_keys(const Dims &dm, Tensor k, Tensor ck, const int32_t *seq
 int launch_append_kv(const Dims &dm, Tensor k_new, Tensor v_new, Tensor k, Tensor v, const Tensor *ck,
                      const int32_t *seqlens, hipStream_t stream);   // dm.n_q rows per sequence
 int launch_select_prefill(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
-                          int32_t *block_idx, void *ws, hipStream_t stream);
+                          int32_t *block_idx, void *ws, hipStream_t stream, float *scores_out = nullptr,
+                          int32_t scores_pitch = 0);
 size_t select_prefill_ws_bytes(const Dims &dm);
 int launch_select_prefill16(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
-                            int32_t *block_idx, void *ws, hipStream_t stream);
+                            int32_t *block_idx, void *ws, hipStream_t stream, float *scores_out = nullptr,
+                            int32_t scores_pitch = 0);
 size_t select_prefill16_ws_bytes(const Dims &dm);
 int32_t select_scores_pitch(const Dims &dm);
 size_t select_scores_bytes(const Dims &dm);

@@ -499,13 +499,14 @@ size_t select_prefill_ws_bytes(const Dims &dm) {
 
 template <int G>
 static int launch_select_prefill_g(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
-                                   int32_t *block_idx, void *ws, hipStream_t stream) {
+                                   int32_t *block_idx, void *ws, hipStream_t stream, float *scores_out,
+                                   int32_t scores_pitch) {
     using C = SelCfg<G>;
-    const int32_t nb_cap = select_scores_pitch(dm);
+    const int32_t nb_cap = scores_out ? scores_pitch : select_scores_pitch(dm);
     size_t lse_bytes = (size_t)dm.batch * dm.max_seqlen * dm.Hq * sizeof(float);
     lse_bytes = (lse_bytes + 255) / 256 * 256;
     float *lse2 = reinterpret_cast<float *>(ws);
-    float *R = reinterpret_cast<float *>(reinterpret_cast<char *>(ws) + lse_bytes);
+    float *R = scores_out ? scores_out : reinterpret_cast<float *>(reinterpret_cast<char *>(ws) + lse_bytes);
     const int32_t n_tiles = (dm.max_seqlen + C::kTokPerWg - 1) / C::kTokPerWg;
     const int64_t n_wg = (int64_t)n_tiles * dm.Hkv * dm.batch;
     if (n_wg <= 0) return 0;
@@ -514,10 +515,11 @@ static int launch_select_prefill_g(const Dims &dm, Tensor q, Tensor ck, const in
                        seqlens, lse2, n_tiles);
     timing_end(stream);
     timing_begin("select_score_kernel", stream);
-    if (dm.shared_q) {
+    if (dm.shared_q || scores_out) {
         hipLaunchKernelGGL((select_score_kernel<G, false>), dim3((uint32_t)n_wg), dim3(256), 0, stream, dm, q, ck,
                            seqlens, lse2, R, nb_cap, n_tiles, block_idx);
         timing_end(stream);
+        if (scores_out) return (int)hipGetLastError();    // the caller wanted the scores, not the block sets
         return launch_select_pick(dm, seqlens, R, nb_cap, block_idx, stream);
     }
     const size_t lds = ScoreLds<G>(dm.topk).bytes();     // beside 26 to 34 KiB of static LDS
@@ -530,14 +532,17 @@ static int launch_select_prefill_g(const Dims &dm, Tensor q, Tensor ck, const in
     return (int)hipGetLastError();
 }
 
+// scores_out != null: stop after pass 2 and leave the block scores of the candidate blocks in
+// scores_out[((b * Hkv + h) * max_seqlen + t) * scores_pitch + j] instead of ranking them.
 int launch_select_prefill(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens,
-                          int32_t *block_idx, void *ws, hipStream_t stream) {
+                          int32_t *block_idx, void *ws, hipStream_t stream, float *scores_out,
+                          int32_t scores_pitch) {
     switch (dm.G) {
-        case 1: return launch_select_prefill_g<1>(dm, q, ck, seqlens, block_idx, ws, stream);
-        case 2: return launch_select_prefill_g<2>(dm, q, ck, seqlens, block_idx, ws, stream);
-        case 4: return launch_select_prefill_g<4>(dm, q, ck, seqlens, block_idx, ws, stream);
-        case 8: return launch_select_prefill_g<8>(dm, q, ck, seqlens, block_idx, ws, stream);
-        case 16: return launch_select_prefill16(dm, q, ck, seqlens, block_idx, ws, stream);
+        case 1: return launch_select_prefill_g<1>(dm, q, ck, seqlens, block_idx, ws, stream, scores_out, scores_pitch);
+        case 2: return launch_select_prefill_g<2>(dm, q, ck, seqlens, block_idx, ws, stream, scores_out, scores_pitch);
+        case 4: return launch_select_prefill_g<4>(dm, q, ck, seqlens, block_idx, ws, stream, scores_out, scores_pitch);
+        case 8: return launch_select_prefill_g<8>(dm, q, ck, seqlens, block_idx, ws, stream, scores_out, scores_pitch);
+        case 16: return launch_select_prefill16(dm, q, ck, seqlens, block_idx, ws, stream, scores_out, scores_pitch);
     }
     return (int)hipErrorInvalidValue;
 }

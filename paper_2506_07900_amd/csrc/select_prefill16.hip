@@ -460,7 +460,7 @@ size_t select_prefill16_ws_bytes(const Dims &dm) {
 }
 
 int launch_select_prefill16(const Dims &dm, Tensor q, Tensor ck, const int32_t *seqlens, int32_t *block_idx,
-                            void *ws, hipStream_t stream) {
+                            void *ws, hipStream_t stream, float *scores_out, int32_t scores_pitch) {
     size_t lse_bytes = (size_t)dm.batch * dm.max_seqlen * dm.Hq * sizeof(float);
     lse_bytes = (lse_bytes + 255) / 256 * 256;
     const int32_t nt_cap = fine_tiles_cap(dm);
@@ -470,8 +470,9 @@ int launch_select_prefill16(const Dims &dm, Tensor q, Tensor ck, const int32_t *
     uint4 *ckp = reinterpret_cast<uint4 *>(reinterpret_cast<char *>(ws) + lse_bytes);
     uint4 *ckp_c = reinterpret_cast<uint4 *>(reinterpret_cast<char *>(ws) + lse_bytes + ckp_bytes);
     const int32_t ntc_cap = coarse_tiles_cap(dm);
-    float *R = reinterpret_cast<float *>(reinterpret_cast<char *>(ws) + lse_bytes + ckp_bytes + coarse_tiles_bytes(dm));
-    const int32_t nb_cap = select_scores_pitch(dm);
+    float *R = scores_out ? scores_out
+                          : reinterpret_cast<float *>(reinterpret_cast<char *>(ws) + lse_bytes + ckp_bytes + coarse_tiles_bytes(dm));
+    const int32_t nb_cap = scores_out ? scores_pitch : select_scores_pitch(dm);
     const int32_t n_tiles = (dm.max_seqlen + kTokPerWg16 - 1) / kTokPerWg16;
     const int64_t n_wg = (int64_t)n_tiles * dm.Hkv * dm.batch;
     if (n_wg <= 0) return 0;
@@ -491,7 +492,7 @@ int launch_select_prefill16(const Dims &dm, Tensor q, Tensor ck, const int32_t *
                            dm.rho > 1 ? ckp_c : ckp, dm.rho > 1 ? ntc_cap : nt_cap, seqlens, lse2, n_tiles);
         timing_end(stream);
         timing_begin("select_score16_kernel", stream);
-        if (dm.shared_q) {
+        if (dm.shared_q || scores_out) {
             hipLaunchKernelGGL(select_score16_kernel<0>, dim3((uint32_t)n_wg), dim3(256),
                                4 * Score16Lds(0, dm.topk).bytes(), stream, dm, q, ckp, nt_cap, seqlens, lse2, R, nb_cap,
                                n_tiles, block_idx);
@@ -517,7 +518,7 @@ int launch_select_prefill16(const Dims &dm, Tensor q, Tensor ck, const int32_t *
         }
         timing_end(stream);
     }
-    if (!dm.shared_q) return (int)hipGetLastError();     // the rows were ranked and written inside pass 2
+    if (!dm.shared_q || scores_out) return (int)hipGetLastError();   // ranked inside pass 2, or scores wanted
     return launch_select_pick(dm, seqlens, R, nb_cap, block_idx, stream);
 }
 

@@ -183,6 +183,52 @@ int main(void) {
     printf("abi_client: compressed keys and block lists exact; attention max|dO| %.3e max|dLSE| %.3e\n", worst_o,
            worst_l);
     if (!(worst_o <= 2e-2) || !(worst_l <= 1e-5)) return 1;
+
+    /* decode: the last token once more, as the one query of a decode step over the same cache -- stage 2 in
+     * decode mode, then infllmv2_sparse_attn_decode; the same row as the prefill above, from other kernels */
+    {
+        static uint16_t out_d[HQ][D];
+        static float lse_d[HQ];
+        static int32_t idx_d[TOPK];
+        void *dout_d, *dlse_d, *didx_d, *dws_d = NULL;
+        size_t ws_ds = infllmv2_workspace_bytes(INFLLMV2_OP_SELECT_DECODE, &prm, 1, T);
+        size_t ws_da = infllmv2_workspace_bytes(INFLLMV2_OP_ATTN_DECODE, &prm, 1, T);
+        size_t ws_d = ws_ds > ws_da ? ws_ds : ws_da;
+        CHECK_HIP(hipMalloc(&dout_d, sizeof out_d));
+        CHECK_HIP(hipMalloc(&dlse_d, sizeof lse_d));
+        CHECK_HIP(hipMalloc(&didx_d, sizeof idx_d));
+        if (ws_d > 0) CHECK_HIP(hipMalloc(&dws_d, ws_d));
+        const infllmv2_tensor tq_d = {(uint16_t *)dq + (size_t)(T - 1) * HQ * D, (int64_t)HQ * D, D, (int64_t)HQ * D};
+        const infllmv2_tensor to_d = {dout_d, (int64_t)HQ * D, D, (int64_t)HQ * D};
+        CHECK_ABI(infllmv2_select_blocks(&prm, INFLLMV2_MODE_DECODE, &tq_d, &tck, (const int32_t *)dsl, 1, T,
+                                         (int32_t *)didx_d, dws_d, ws_d, NULL));
+        CHECK_ABI(infllmv2_sparse_attn_decode(&prm, &tq_d, &tk, &tv, (const int32_t *)dsl, 1, T,
+                                              (const int32_t *)didx_d, &to_d, (float *)dlse_d, dws_d, ws_d, NULL));
+        CHECK_HIP(hipDeviceSynchronize());
+        CHECK_HIP(hipMemcpy(idx_d, didx_d, sizeof idx_d, hipMemcpyDeviceToHost));
+        CHECK_HIP(hipMemcpy(out_d, dout_d, sizeof out_d, hipMemcpyDeviceToHost));
+        CHECK_HIP(hipMemcpy(lse_d, dlse_d, sizeof lse_d, hipMemcpyDeviceToHost));
+        for (int e = 0; e < TOPK; ++e)
+            if (idx_d[e] != idx[T - 1][e]) ++bad;
+        if (bad) {
+            fprintf(stderr, "decode block list differs from the prefill row\n");
+            return 1;
+        }
+        double wo = 0.0, wl = 0.0;
+        for (int h = 0; h < HQ; ++h) {
+            for (int c = 0; c < D; ++c) {
+                const double e = fabs((double)bf16_to_f32(out_d[h][c]) - (double)bf16_to_f32(out[T - 1][h][c]));
+                if (e > wo) wo = e;
+            }
+            const double el = fabs((double)lse_d[h] - (double)lse[T - 1][h]);
+            if (el > wl) wl = el;
+        }
+        printf("abi_client: decode of the last token vs its prefill row max|dO| %.3e max|dLSE| %.3e\n", wo, wl);
+        /* both sides are within 2e-2 / 1e-5 of the exact row (checked above for the prefill side) */
+        if (!(wo <= 2e-2) || !(wl <= 2e-5)) return 1;
+        (void)hipFree(dout_d); (void)hipFree(dlse_d); (void)hipFree(didx_d);
+        if (dws_d) (void)hipFree(dws_d);
+    }
     (void)hipFree(dq); (void)hipFree(dk); (void)hipFree(dv); (void)hipFree(dck); (void)hipFree(dout);
     (void)hipFree(dlse); (void)hipFree(didx); (void)hipFree(dsl);
     if (dws) (void)hipFree(dws);

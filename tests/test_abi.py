@@ -29,17 +29,35 @@ def test_header_symbols_are_exported(lib):
         assert hasattr(lib, name), name
 
 
+def test_measurement_entry_points_live_in_the_bench_library_only(lib):
+    # per-kernel timing (process-wide state, synchronises) and the probe kernels are not product code:
+    # they are declared in their own header and exported by libinfllmv2_bench.so, which also has
+    # every entry point of the library proper
+    text = open(os.path.join(ROOT, "include", "infllmv2_bench.h")).read()
+    declared = sorted(set(re.findall(r"\b(infllmv2_[a-z_]+)\s*\(", text)))
+    assert set(declared) == set(binding.BENCH_EXPORTS)
+    for name in declared:
+        assert not hasattr(lib, name), name
+    assert os.path.exists(binding.BENCH_LIB_PATH)
+    bench = ctypes.CDLL(binding.BENCH_LIB_PATH)
+    for name in binding.EXPORTS + binding.BENCH_EXPORTS:
+        assert hasattr(bench, name), name
+    with pytest.raises(binding.InfLLMv2Error):
+        binding.timing_enable(True)
+
+
 def test_header_is_plain_c():
-    # the boundary is a C ABI: the header has to compile as strict C99 (and as C++) on its own
+    # the boundary is a C ABI: the headers have to compile as strict C99 (and as C++) on their own
     import shutil
     import subprocess
-    hdr = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "infllmv2.h")
     if shutil.which("gcc") is None:
         pytest.skip("no host C compiler")
-    for lang, std in (("c", "-std=c99"), ("c++", "-std=c++17")):
-        r = subprocess.run(["gcc", "-x", lang, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", hdr],
-                           capture_output=True, text=True)
-        assert r.returncode == 0, r.stderr
+    for name in ("infllmv2.h", "infllmv2_bench.h"):
+        hdr = os.path.join(ROOT, "include", name)
+        for lang, std in (("c", "-std=c99"), ("c++", "-std=c++17")):
+            r = subprocess.run(["gcc", "-x", lang, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", hdr],
+                               capture_output=True, text=True)
+            assert r.returncode == 0, r.stderr
 
 
 def test_struct_layout_matches_header():

@@ -137,6 +137,37 @@ def test_select_blocks_prefill(seqlens, Hq, Hkv, topk, planted):
     assert near <= max(2, tot // 200)
 
 
+@pytest.mark.parametrize("seqlens,Hq,Hkv,topk", [([1077, 333], 32, 2, 16), ([700, 65], 4, 1, 6), ([450], 2, 2, 5)])
+def test_block_scores_against_the_oracle(seqlens, Hq, Hkv, topk):
+    # the scores the selection ranks (Eq. 1 after the group mean and the max over intersecting kernels),
+    # value by value: fp32 with hardware exp2 / log2 on one side, fp64 on the other
+    print("case block scores", seqlens, Hq, Hkv, topk, flush=True)
+    prm = binding.Params(Hq, Hkv, topk=topk)
+    oprm = oracle_params(prm)
+    q, k, v, T = make_batch(23, seqlens, Hq, Hkv, n_planted=4)
+    qd, kd, sl = to_dev(q), to_dev(k), dev_i32(seqlens)
+    ck = binding.compress_keys(prm, kd, sl, T)
+    got = binding.block_scores(prm, qd, ck, sl, T).cpu().numpy().astype(np.float64)
+    torch.cuda.synchronize()
+    ckb = to_bits(ck)
+    worst = 0.0
+    for b, l in enumerate(seqlens):
+        pos = np.arange(l, dtype=np.int32)
+        _, _, R = ref.select_blocks(q[b, :l], ckb[b, :, :ref.num_kernels(l, 32, 16)], pos, oprm, want_scores=True)
+        for t in range(l):
+            lo, hi = min(prm.n_init_blocks, t // 64 + 1), t // 64 - prm.n_local_blocks       # candidate blocks lo..hi
+            if hi < lo:
+                continue
+            w, g = R[:, t, lo:hi + 1], got[b, :, t, lo:hi + 1]
+            assert np.array_equal(np.isneginf(w), np.isneginf(g)), (b, t)
+            fin = np.isfinite(w)
+            assert np.all(np.isfinite(g[fin]))
+            if fin.any():
+                worst = max(worst, float(np.max(np.abs(g[fin] - w[fin]) / w[fin])))
+    print("largest relative error of a block score %.3e" % worst, flush=True)
+    assert worst <= 2e-5
+
+
 @pytest.mark.parametrize("forced", [(0, 0), (0, 1), (3, 0), (2, 4)])
 @pytest.mark.parametrize("seqlens,Hq,Hkv,topk", [([1100, 333, 70], 32, 2, 8), ([700, 65], 4, 1, 6)])
 def test_select_blocks_prefill_other_forced_counts(seqlens, Hq, Hkv, topk, forced):
@@ -282,6 +313,29 @@ def test_sparse_attn_prefill(seqlens, Hq, Hkv, topk, planted):
             print("seq %d len %d: max|dO| %.3e LSE err/tol %.3f" % (b, l, eo, el), flush=True)
             assert eo <= OUT_TOL and el <= 1.0
         assert np.all(o[b, l:] == 3.0) and np.all(ls[b, l:] == 5.0)     # padding rows untouched
+
+
+def test_sparse_attn_prefill_row_that_repeats_a_block():
+    # the contract asks for duplicate-free rows; a row that repeats a block all the same must stay inside
+    # the caches and attend that block once: same output as the clean row, bit for bit
+    print("case attn prefill duplicate entries", flush=True)
+    l, Hq, Hkv, topk = 700, 32, 2, 16
+    prm = binding.Params(Hq, Hkv, topk=topk)
+    q, k, v, T = make_batch(29, [l], Hq, Hkv, n_planted=3)
+    qd, kd, vd, sl = to_dev(q), to_dev(k), to_dev(v), dev_i32([l])
+    ck = binding.compress_keys(prm, kd, sl, T)
+    idx = binding.select_blocks(prm, binding.MODE_PREFILL, qd, ck, sl, T)
+    out0, lse0 = binding.sparse_attn_prefill(prm, qd, kd, vd, sl, T, idx)
+    dup = idx.clone()
+    n_valid = (dup >= 0).sum(-1)                           # at most 11 blocks exist: every row has padding
+    rows = n_valid < topk
+    first = dup[..., 0]
+    last_real = torch.gather(dup, -1, (n_valid - 1).clamp(min=0)[..., None].long())[..., 0]
+    dup[..., topk - 1] = torch.where(rows, first, dup[..., topk - 1])          # repeat the lowest block at the end
+    dup[..., topk - 2] = torch.where(rows & (n_valid < topk - 1), last_real, dup[..., topk - 2])   # and the highest
+    out1, lse1 = binding.sparse_attn_prefill(prm, qd, kd, vd, sl, T, dup)
+    torch.cuda.synchronize()
+    assert torch.equal(out0.view(torch.int16), out1.view(torch.int16)) and torch.equal(lse0, lse1)
 
 
 @pytest.mark.parametrize("rho", [2, 4])

@@ -297,11 +297,24 @@ def bench_prefill(args, workload, extras=True):
     return res, (x, idx, out, lse, prm, cfg)
 
 
+def lse_err_over_tol(got, want):
+    """Largest log-sum-exp error in units of the tolerance the parity tests apply: the stated 1e-5 absolute,
+    widened to 2^-20 * |LSE| (16 fp32 ulps) where |LSE| is so large that fp32 cannot hold 1e-5 (heavy-tailed
+    keys give |LSE| in the hundreds, whose ulp alone is 1.5e-5).  <= 1 passes."""
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    fin = np.isfinite(want)
+    if not fin.any():
+        return 0.0
+    tol = np.maximum(1e-5, 2.0 ** -20 * np.abs(want[fin]))
+    return float(np.max(np.abs(got[fin] - want[fin]) / tol))
+
+
 def decode_parity(x, cfg, prm, s, lens, k_np, v_np, idx, out, lse):
     """What the oracle says about decode step s as the GPU left it (caches mirrored on the host)."""
     from oracle import ref
     oprm = ref.Params(cfg.n_q_heads, cfg.n_kv_heads, topk=cfg.topk)
-    st = {"rows": 0, "exact": 0, "near_tie": 0, "hard": 0, "max_abs_out": 0.0, "max_abs_lse": 0.0}
+    st = {"rows": 0, "exact": 0, "near_tie": 0, "hard": 0, "max_abs_out": 0.0, "max_abs_lse": 0.0,
+          "max_lse_err_over_tol": 0.0}
     idx_np, out_np, lse_np = idx.cpu().numpy(), out.double().cpu().numpy(), lse.double().cpu().numpy()
     for b in range(len(lens)):
         l = int(lens[b])
@@ -319,6 +332,7 @@ def decode_parity(x, cfg, prm, s, lens, k_np, v_np, idx, out, lse):
         wo, wl = ref.sparse_attn(qb, k_np[b, :, :l], v_np[b, :, :l], pos, idx_np[b], oprm)   # on the GPU's block sets
         st["max_abs_out"] = max(st["max_abs_out"], float(np.abs(out_np[b, 0] - wo[0]).max()))
         st["max_abs_lse"] = max(st["max_abs_lse"], float(np.abs(lse_np[b] - wl[0]).max()))
+        st["max_lse_err_over_tol"] = max(st["max_lse_err_over_tol"], lse_err_over_tol(lse_np[b], wl[0]))
     return st
 
 
@@ -379,7 +393,8 @@ def bench_decode(cfg_index, steps, replicate=1, profile=False, check_steps=(0, 1
     if replicate == 1 and check_steps:
         k_np, v_np = x.k_cache.copy(), x.v_cache.copy()
         parity = {"rows": 0, "exact": 0, "near_tie": 0, "hard": 0, "max_abs_out": 0.0, "max_abs_lse": 0.0,
-                  "checked_steps": list(check_steps)}
+                  "max_lse_err_over_tol": 0.0, "checked_steps": list(check_steps),
+                  "lse_tol": "max(1e-5, 2^-20 |LSE|): 1e-5 wherever fp32 can hold it"}
     for s in range(n_warm):
         sl.add_(1)
         step(s, sl)
@@ -392,7 +407,7 @@ def bench_decode(cfg_index, steps, replicate=1, profile=False, check_steps=(0, 1
                 st = decode_parity(x, cfg, prm, s, lens, k_np, v_np, idx, out, lse)
                 for key in ("rows", "exact", "near_tie", "hard"):
                     parity[key] += st[key]
-                for key in ("max_abs_out", "max_abs_lse"):
+                for key in ("max_abs_out", "max_abs_lse", "max_lse_err_over_tol"):
                     parity[key] = max(parity[key], st[key])
     del k_np, v_np
     torch.cuda.synchronize()
@@ -628,7 +643,7 @@ def cpu_baseline(x, cfg, n_rows, lse_ratio, gpu):
     t_comp = time.perf_counter() - t0
     ck_bits = ck_gpu[0].view(__import__("torch").int16).cpu().numpy().view(np.uint16)
     par = {"rows": int(len(pos)) * cfg.n_kv_heads, "exact": 0, "near_tie": 0, "hard": 0,
-           "max_abs_out": 0.0, "max_abs_lse": 0.0,
+           "max_abs_out": 0.0, "max_abs_lse": 0.0, "max_lse_err_over_tol": 0.0,
            "compressed_keys_bit_exact": bool(np.array_equal(ck_bits[:, :ckb.shape[1]], ckb))}
     t_sel = t_att = 0.0
     pairs = 0
@@ -650,7 +665,9 @@ def cpu_baseline(x, cfg, n_rows, lse_ratio, gpu):
             kth, nxt = margins[h, r]
             par["near_tie" if abs(kth - nxt) <= 1e-3 * abs(kth) else "hard"] += 1
         par["max_abs_out"] = max(par["max_abs_out"], float(np.abs(out_gpu[0][pc_t].double().cpu().numpy() - o_ref).max()))
-        par["max_abs_lse"] = max(par["max_abs_lse"], float(np.abs(lse_gpu[0][pc_t].double().cpu().numpy() - l_ref).max()))
+        lg = lse_gpu[0][pc_t].double().cpu().numpy()
+        par["max_abs_lse"] = max(par["max_abs_lse"], float(np.abs(lg - l_ref).max()))
+        par["max_lse_err_over_tol"] = max(par["max_lse_err_over_tol"], lse_err_over_tol(lg, l_ref))
         jj = ig.astype(np.int64)
         pairs += int(np.where(jj >= 0, np.clip(pc[None, :, None].astype(np.int64) + 1 - jj * m, 0, m), 0).sum())
     flops = pairs * (cfg.n_q_heads // cfg.n_kv_heads) * 4 * cfg.head_dim
@@ -783,6 +800,21 @@ def main():
             line["workloads"][wl] = entry
             del x2, idx2, out2, lse2
             torch.cuda.empty_cache()
+    if not args.no_other_workloads and args.lse_ratio == 1 and args.workload == "prefill_32k":
+        # the report's own shortcut for pass 1 ("Efficient Top-K Implementation": log-sum-exp from coarse
+        # semantic kernels, here s_c / s = 4), beside the exact selection the headline value is quoted on:
+        # it selects different blocks, so it is reported separately together with how much of the exact
+        # selection it keeps
+        import copy
+        a4 = copy.copy(args)
+        a4.lse_ratio = 4
+        r4, keep = bench_prefill(a4, "prefill_32k", extras=False)
+        line["approximate_lse_ratio_4"] = {k_: r4[k_] for k_ in ("lse", "ms_per_step", "value", "selection_passes",
+                                                                 "kernels_ms", "selection_overlap_with_exact")}
+        line["approximate_lse_ratio_4"]["note"] = ("not the headline: same workload with pass 1 over coarse kernels; value is "
+                                                   "attended flops of ITS selection / its whole-step time")
+        del r4, keep
+        torch.cuda.empty_cache()
     if not args.no_decode:
         line["decode"] = bench_decode(3, args.decode_steps)
         line["decode"]["frac_measured_hbm_algorithmic"] = line["decode"]["algorithmic_GBs"] / mp["hbm_read_GBs"]

@@ -603,8 +603,29 @@ def measured_peaks():
         flops, nbytes = binding.probe_peaks(buf)
         for name, ms in binding.timing_read():
             best[name] = min(best.get(name, 1e30), ms)
+    for _ in range(3):
+        work = binding.probe_detail(buf)
+        for name, ms in binding.timing_read():
+            best[name] = min(best.get(name, 1e30), ms)
     binding.timing_enable(False)
     del buf
+    # issue cost of an instruction group, in units of one independent fp32 fma (4 cycles per wavefront
+    # instruction on a 16-lane SIMD), from full-chip loops at four wavefronts per SIMD
+    per = {n: best[n] / w for n, w in zip(("probe_issue_fma_kernel", "probe_issue_exp_kernel", "probe_issue_mfma_k0_kernel",
+                                           "probe_issue_mfma_k2_kernel", "probe_issue_mfma_k4_kernel"), work[:5])}
+    ns = {k_: v_ * 1e6 for k_, v_ in per.items()}
+    issue = {"ns_per_group_per_simd": {"fma": ns["probe_issue_fma_kernel"], "exp2": ns["probe_issue_exp_kernel"],
+                                       "mfma": ns["probe_issue_mfma_k0_kernel"],
+                                       "mfma_plus_2_fma": ns["probe_issue_mfma_k2_kernel"],
+                                       "mfma_plus_4_fma": ns["probe_issue_mfma_k4_kernel"]},
+             "note": "full-chip loops of independent instructions at four wavefronts per SIMD; a group is one fp32 fma, "
+                     "one v_exp_f32, or one 16x16x32 bf16 MFMA followed by 0 / 2 / 4 fma's.  The MFMA alone is bound by "
+                     "its pipe (16 cycles); what MFMA + K fma costs beyond max(mfma, K x fma) is issue-port time the "
+                     "MFMA takes from the vector instructions"}
+    frag = {"l2_hit_TBs": work[5] / (best["probe_fragment_l2_kernel"] * 1e-3) / 1e12,
+            "random_32KiB_blocks_TBs": work[6] / (best["probe_fragment_random_kernel"] * 1e-3) / 1e12,
+            "note": "1 KiB coalesced operand fragments, 32 per 32 KiB block, as the attention kernels fetch them: from a "
+                    "2 MiB window that stays in L2, and from pseudo-random blocks of a 2 GiB buffer"}
     m, v, both = best["probe_mix_mfma_kernel"], best["probe_mix_valu_kernel"], best["probe_mix_both_kernel"]
     return {"mfma_bf16_TFLOPs": flops / (best["probe_mfma_kernel"] * 1e-3) / 1e12,
             "hbm_read_GBs": nbytes / (best["probe_stream_kernel"] * 1e-3) / 1e9,
@@ -613,7 +634,8 @@ def measured_peaks():
             # do the matrix cores and the vector ALU of a SIMD work at the same time?  per loop step 16 MFMAs
             # and / or 16 x (fma, exp2, add, fma), 4 waves per SIMD: 1.0 = not at all, max/sum = completely
             "mfma_valu_overlap": {"mfma_ms": m, "valu_ms": v, "both_ms": both, "both_over_sum": both / (m + v),
-                                  "both_over_max": both / max(m, v)}}
+                                  "both_over_max": both / max(m, v)},
+            "issue_model": issue, "operand_fragment_reads": frag}
 
 
 def sample_rows(l, n_rows):

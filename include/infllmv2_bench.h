@@ -31,6 +31,20 @@ int32_t infllmv2_probe_peaks(void *buf, size_t buf_bytes, double *mfma_flops, do
                              void *stream);
 
 /*
+ * Finer probes behind the bounds the design notes argue with; durations through infllmv2_timing_read.
+ *   "probe_issue_fma_kernel", "probe_issue_exp_kernel", "probe_issue_mfma_k0 / k2 / k4_kernel": loops of
+ *       independent instructions at four wavefronts per SIMD -- fp32 fma; v_exp_f32; one 16x16x32 bf16 MFMA
+ *       followed by 0 / 2 / 4 fma's.  work[0..4] = instruction groups executed per SIMD (a group = one fma,
+ *       one exp2, or one MFMA with its fma's): duration / work[i] is the issue cost of a group.
+ *   "probe_fragment_l2_kernel", "probe_fragment_random_kernel": every wavefront fetches 32 KiB blocks as 32
+ *       coalesced 1 KiB fragments, from a 2 MiB window (L2 hits) or from pseudo-random blocks of the whole
+ *       buffer (misses).  work[5], work[6] = bytes fetched.
+ *   buf    in   DEVICE buffer as for infllmv2_probe_peaks (zero-filled, only read)
+ *   work   out  HOST array of 7 doubles
+ */
+int32_t infllmv2_probe_detail(void *buf, size_t buf_bytes, double *work, void *stream);
+
+/*
  * Per-kernel timing for benchmarks (the measurement the roofline figures are built on).
  * While enabled, every kernel launched by the entry points above is bracketed by HIP events
  * recorded on the call's stream; at most 256 launches are kept between reads.  Process-wide

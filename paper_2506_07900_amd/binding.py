@@ -35,7 +35,7 @@ EXPORTS = ["infllmv2_status_string", "infllmv2_workspace_bytes", "infllmv2_compr
            "infllmv2_sparse_attn_bwd", "infllmv2_append_kv", "infllmv2_decode_step", "infllmv2_select_blocks_shared", "infllmv2_sparse_attn_prefill_shared", "infllmv2_verify_workspace_bytes", "infllmv2_append_kv_verify",
            "infllmv2_select_blocks_verify", "infllmv2_sparse_attn_verify", "infllmv2_verify_step",
            "infllmv2_block_scores"]
-BENCH_EXPORTS = ["infllmv2_probe_peaks", "infllmv2_timing_enable", "infllmv2_timing_read"]
+BENCH_EXPORTS = ["infllmv2_probe_peaks", "infllmv2_probe_detail", "infllmv2_timing_enable", "infllmv2_timing_read"]
 
 
 class CParams(ctypes.Structure):
@@ -134,6 +134,8 @@ def load_library(path=None):
     if hasattr(lib, "infllmv2_timing_enable"):            # the bench build
         lib.infllmv2_probe_peaks.restype = i32
         lib.infllmv2_probe_peaks.argtypes = [vp, sz, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp]
+        lib.infllmv2_probe_detail.restype = i32
+        lib.infllmv2_probe_detail.argtypes = [vp, sz, ctypes.POINTER(ctypes.c_double), vp]
         lib.infllmv2_timing_enable.restype = i32
         lib.infllmv2_timing_enable.argtypes = [i32]
         lib.infllmv2_timing_read.restype = i32
@@ -273,6 +275,15 @@ def block_scores(prm, q, ck, seqlens, max_seqlen, scores=None, workspace=None):
                                      scores.stride(2), ws.data_ptr(), ws_bytes, _stream()),
            "infllmv2_block_scores")
     return scores
+
+
+def probe_detail(buf):
+    """Launch the issue and fragment probes over the zero-filled uint8 device buffer `buf` -> the 7 work
+    figures of infllmv2_probe_detail (groups per SIMD x 5, bytes x 2).  Durations come from timing_read()."""
+    lib = _bench_lib()
+    work = (ctypes.c_double * 7)()
+    _check(lib.infllmv2_probe_detail(buf.data_ptr(), buf.numel(), work, _stream()), "infllmv2_probe_detail")
+    return [float(w) for w in work]
 
 
 def select_blocks(prm, mode, q, ck, seqlens, max_seqlen, block_idx=None, workspace=None):

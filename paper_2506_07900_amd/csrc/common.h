@@ -264,5 +264,6 @@ int32_t validate_attn_decode(const infllmv2_params *prm, const infllmv2_tensor *
                              const int32_t *block_idx, const infllmv2_tensor *out, const float *lse, Dims *dm,
                              Tensor *tq, Tensor *tk, Tensor *tv, Tensor *tout);
 int launch_probes(void *buf, size_t buf_bytes, double *mfma_flops, double *stream_bytes, hipStream_t stream);
+int launch_probes_detail(void *buf, size_t buf_bytes, double *work, hipStream_t stream);
 
 }  // namespace infllmv2

@@ -64,4 +64,11 @@ int32_t infllmv2_probe_peaks(void *buf, size_t buf_bytes, double *mfma_flops, do
                ? INFLLMV2_OK : INFLLMV2_ERR_HIP;
 }
 
+int32_t infllmv2_probe_detail(void *buf, size_t buf_bytes, double *work, void *stream) {
+    if (!buf || !work || buf_bytes < (size_t)(8u << 20) || (reinterpret_cast<uintptr_t>(buf) & 255u) != 0)
+        return INFLLMV2_ERR_INVALID_ARGUMENT;
+    return infllmv2::launch_probes_detail(buf, buf_bytes, work, reinterpret_cast<hipStream_t>(stream)) == 0
+               ? INFLLMV2_OK : INFLLMV2_ERR_HIP;
+}
+
 }  // extern "C"

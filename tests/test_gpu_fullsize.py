@@ -55,6 +55,26 @@ def run_prefill_config(cfg_index, n_random, rho=1):
     assert bool(has(b_own).all()) and bool((has(b_own - 1) | (b_own[..., 0] < 1)).all())  # local blocks
     assert bool(torch.isfinite(lse).all()) and bool(torch.isfinite(out.float()).all())
 
+    if n_random is None:
+        # every row against the oracle, in chunks (the fp64 outputs of all rows at once are 1 GiB)
+        n = exact = near = 0
+        eo = el = 0.0
+        for a in range(0, l, 4096):
+            rows = np.arange(a, min(a + 4096, l), dtype=np.int32)
+            qs = np.ascontiguousarray(x.q[rows])
+            want_idx, margins, R = ref.select_blocks(qs, ck_ref, rows, oprm, want_scores=True)
+            ri = torch.from_numpy(rows).long().cuda()
+            got_idx = idx_all[:, ri].cpu().numpy()
+            n_, e_, nt_, hard = compare_selection(got_idx, want_idx, margins, R)
+            assert not hard, hard[:3]
+            n, exact, near = n + n_, exact + e_, near + nt_
+            want_o, want_l = ref.sparse_attn(qs, x.k, x.v, rows, got_idx, oprm)
+            eo = max(eo, float(np.abs(out[0, ri].double().cpu().numpy() - want_o).max()))
+            el = max(el, lse_err(lse[0, ri].double().cpu().numpy(), want_l))
+            print("rows %d..%d done" % (a, rows[-1]), flush=True)
+        print("every row: %d rows, %d exact, %d near-tie; max|dO| %.3e LSE err/tol %.3f" % (n, exact, near, eo, el), flush=True)
+        assert near <= max(2, n // 1000) and eo <= OUT_TOL and el <= 1.0
+        return
     # sampled rows against the oracle
     rows = sample_rows(l, n_random, 1000 + cfg_index)
     qs = np.ascontiguousarray(x.q[rows])
@@ -85,6 +105,14 @@ def run_prefill_config(cfg_index, n_random, rho=1):
 @pytest.mark.timeout(300)
 def test_prefill_32k_sampled_rows():
     run_prefill_config(1, 150)
+
+
+@pytest.mark.timeout(600)
+def test_prefill_32k_every_row():
+    # the headline workload in full: all 32768 query rows x all heads, block sets and attention (an indexing
+    # mistake confined to one tile position mid-sequence cannot hide between sampled rows); about 20 s of
+    # oracle time on 16 host cores
+    run_prefill_config(1, None)
 
 
 @pytest.mark.timeout(300)

@@ -253,7 +253,9 @@ def test_select_blocks_prefill_long_capacity(Hq, Hkv, n_local, topk, cap):
 @pytest.mark.parametrize("l,Hq,Hkv,topk,n_local", [(40000, 16, 1, 16, 2),    # G = 16: chunks of 512 blocks, 2 chunks
                                                    (20000, 16, 1, 64, 1),    # wide top-k: chunks of 256 blocks
                                                    (36000, 4, 1, 16, 0),     # other group sizes: chunks of 256, 3 chunks
-                                                   (17000, 2, 2, 8, 1)])     # G = 1
+                                                   (17000, 2, 2, 8, 1),      # G = 1
+                                                   (5000, 2, 2, 64, 1),      # G = 1, widest top-k: the most LDS a launch asks for
+                                                   (5000, 4, 2, 64, 0)])     # G = 2, widest top-k
 def test_select_blocks_prefill_rows_longer_than_one_chunk(l, Hq, Hkv, topk, n_local):
     # pass 2 ranks the block scores chunk by chunk inside the kernel and carries the running picks from
     # chunk to chunk: sequences long enough for several chunks, checked on sampled query rows (the rows

@@ -9,17 +9,17 @@
 // scatter (a block collects from every token that selected it).  The scatter is turned around with
 // a membership bitmap (block x token) built from the block lists, so both big kernels accumulate
 // in registers:
-//   bwd_prep_kernel     D and the membership bits of every token
+//   bwd_prep_kernel     D, the exponent offsets -lse log2(e), and the membership bits of every token
 //   pack_bwd_kernel     fragment-major copies of every block: K rows, V rows, K transposed
 //   attn_bwd_dq_kernel  wavefront = 2 tokens, walks the union of their block lists:
 //                       S^T = K.Q^T, dP^T = V.dO^T, dQ^T += K^T.dS^T
-//   attn_bwd_dkdv_kernel  wavefront = 16 keys of a block, walks the member tokens of one
-//                       2048-token segment in pairs: S = Q.K^T, dP = dO.V^T,
-//                       dV^T += dO^T.P, dK^T += Q^T.dS; fp32 atomics merge the segments
+//   attn_bwd_dkdv_kernel  wavefront = 32 keys x 64 channels of a block, walks the member tokens of one
+//                       segment in pairs: S = Q.K^T, dP = dO.V^T, dV^T += dO^T.P, dK^T += Q^T.dS
+//                       (32x32x16 MFMAs; q and dout rows copied from memory straight into LDS);
+//                       fp32 atomics merge the segments
 //   bwd_finish_kernel   fp32 accumulators -> bf16 dk (times scale), dv
 // As in the forward, every second contraction takes its B operand straight from the accumulator
-// layout of the first (lane = column, 4 consecutive rows per 16-lane group), with the contraction
-// index of the A fragments permuted to match.
+// layout of the first, with the contraction index of the A fragments permuted to match.
 #include "common.h"
 
 namespace infllmv2 {
@@ -37,7 +37,7 @@ constexpr int kBwdBlkBits = 27, kBwdBlkMask = (1 << kBwdBlkBits) - 1;
 
 struct BwdLayout {
     int32_t nb_cap, words;                            // blocks per sequence; bitmap words per block row (multiple of 64)
-    size_t kvb, delta, bitmap, acc_dk, acc_dv, total; // byte offsets into the workspace
+    size_t kvb, delta, rowc, bitmap, acc_dk, acc_dv, total; // byte offsets into the workspace
     size_t zero_begin, zero_bytes;                    // the part that has to start at zero (bitmap and accumulators)
 };
 static inline size_t al256(size_t x) { return (x + 255) / 256 * 256; }
@@ -50,6 +50,7 @@ static BwdLayout bwd_layout(const Dims &dm) {
     size_t o = 0;
     l.kvb = o;    o += al256(BH * l.nb_cap * kBwdBlockU4 * sizeof(uint4));
     l.delta = o;  o += al256((size_t)dm.batch * T * dm.Hq * sizeof(float));
+    l.rowc = o;   o += al256((size_t)dm.batch * T * dm.Hkv * 32 * sizeof(float));
     l.zero_begin = o;
     l.bitmap = o; o += al256(BH * l.nb_cap * l.words * sizeof(uint32_t));
     l.acc_dk = o; o += al256(BH * T * kHeadDim * sizeof(float));
@@ -76,7 +77,8 @@ __global__ __launch_bounds__(256) void bwd_zero_kernel(uint4 *__restrict__ p, si
 __global__ __launch_bounds__(256) void bwd_prep_kernel(Dims dm, Tensor out, Tensor dout,
                                                         const int32_t *__restrict__ seqlens,
                                                         const int32_t *__restrict__ block_idx,
-                                                        float *__restrict__ delta, uint32_t *__restrict__ bitmap,
+                                                        const float *__restrict__ lse, float *__restrict__ delta,
+                                                        float *__restrict__ rowc, uint32_t *__restrict__ bitmap,
                                                         int32_t nb_cap, int32_t words) {
     const int h = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -105,6 +107,19 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(Dims dm, Tensor out, Tens
     dsum += __shfl_xor(dsum, 1);
     dsum += __shfl_xor(dsum, 2);
     if (quarter == 0 && row < G) delta[((int64_t)b * dm.max_seqlen + tok) * dm.Hq + h * G + row] = dsum;
+    // the same per (token, key-value head) as one 128-byte record for the dk/dv kernel: the exponent offsets
+    // -lse log2(e) of the 16 head slots (-inf for slots past the group and for rows without a finite lse, whose
+    // probabilities are then zero), then D
+    if (quarter == 0) {
+        float *rec = rowc + (((int64_t)b * dm.max_seqlen + tok) * dm.Hkv + h) * 32;
+        float ne = -INFINITY;
+        if (row < G) {
+            const float ls = lse[((int64_t)b * dm.max_seqlen + tok) * dm.Hq + h * G + row];
+            if (ls > -INFINITY && ls < INFINITY) ne = -ls * kLog2e;
+        }
+        rec[row] = ne;
+        rec[16 + row] = row < G ? dsum : 0.f;
+    }
     if (blk >= 0 && blk <= tok / kBlock)
         atomicOr(&bitmap[(((int64_t)b * dm.Hkv + h) * nb_cap + blk) * words + (tok >> 5)], 1u << (tok & 31));
 }
@@ -358,56 +373,77 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(Dims dm, Tensor q, 
     }
 }
 
-// ---- dk, dv: a wavefront owns 16 keys of a block ---------------------------------------------------------
-// grid (nb_cap, n_seg, B*Hkv), 256 threads: workgroup (j, seg) handles the member tokens of block j
-// that lie in tokens [2048 seg, 2048 seg + 2047]; wave w the keys 64j + 16w .. +15.  The member
-// tokens are compacted from the bitmap into a list and walked two at a time.  All four waves need
-// the same 16 KiB of q and dout rows per pair, so the workgroup fetches each pair once: every
-// thread keeps its 1/256 of the next three pairs in registers (memory latency is several times the
-// arithmetic of a pair) and drops a pair into one of two LDS buffers one step before it is used,
-// as rows and, transposed in registers, as columns.
-//   S  [head, key] = Q[tok] . K^T        A = q rows of the token (lane = head), B = K rows (registers)
-//   dP [head, key] = dO[tok] . V^T
-//   dV^T[c, key]  += dO^T[c, (tok, head)] . P[(tok, head), key]      A = the staged columns,
-//   dK^T[c, key]  += Q^T [c, (tok, head)] . dS[(tok, head), key]     B = P / dS
-// as they sit in the accumulators of the first two products.
-constexpr int kRowPitch = kHeadDim + 8;               // bf16 per staged row (272 bytes: rows start 4 banks apart)
-constexpr int kPairRows = 2 * 2 * 16;                 // q rows of two tokens, dout rows of two tokens
-constexpr int kDepth = 3;                             // pairs in flight per thread
+// ---- dk, dv: a wavefront owns 32 keys of a block ---------------------------------------------------------
+// 256 threads: a workgroup handles member tokens of block j that lie in one segment of the sequence (all of
+// them, or one slice of the list when there are many).  The member tokens are compacted from the bitmap into a list
+// and walked in pairs, two pairs per step.  Wave w owns the keys 64j + 32(w&1) .. +31 and, of their
+// gradients, the channels 64(w>>1) .. +63: the two wavefronts of a key half both form S and dP of every
+// pair (a wavefront that owned all 128 channels of dk and dv would need 128 accumulator registers on top
+// of the 64 of its K and V operands, and spill).  With 32x32x16 MFMAs, rows = (token of the pair, head):
+//   S  [row, key] = Q . K^T         A = the pair's q rows from LDS, B = K rows of the wave's keys (registers)
+//   dP [row, key] = dO . V^T
+//   dV^T[c, key] += dO^T[c, row] . P[row, key]      A = the same staged rows read through the transposing
+//   dK^T[c, key] += Q^T [c, row] . dS[row, key]     LDS load, B = P / dS as they sit in the accumulators
+// Staging: the 16 KiB of q and dout rows of a pair go from memory straight into LDS (no registers, no vector
+// instructions), a step ahead of their use; two step buffers alternate.  They are two objects and the
+// loop is unrolled by two, so that the compiler's wait counts let a read of one buffer run under the
+// copies into the other.  A row is 256 bytes; its sixteen 16-byte pieces are stored XOR-swizzled with the
+// head's two bit pairs exchanged: an operand load of the first products takes one piece from each of 16
+// rows, a transposing load 32 bytes from each of 4 consecutive rows, and both then touch every bank once.
+constexpr int kBwdSlices = 4;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+struct __align__(16) BwdRows {
+    uint16_t rows[2][2][32][kHeadDim];                    // [pair of the step][q | dout][(token, head)][channel]: 32 KiB
+};
+struct __align__(16) BwdScalars {
+    float ld[2][64];                                      // [pair][exponent offset of token a, of b | D of token a, of b][head]
+};
+__device__ __forceinline__ int bwd_swizzle(int head) { return ((head & 3) << 2) | ((head >> 2) & 3); }
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+// 4 rows x 16 channels per 16-lane group, transposed: lane i of the group gets channel i of the four rows its
+// group addressed (source lane s: row s/4, channels 4(s%4) .. +3)
+__device__ __forceinline__ s16x4 lds_read_tr16(const char *p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
+}
+
 template <int kSegTokens>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q, Tensor dout, const uint4 *__restrict__ kvb,
                                                                 int32_t nb_cap, const int32_t *__restrict__ seqlens,
-                                                                const float *__restrict__ lse,
-                                                                const float *__restrict__ delta,
+                                                                const float *__restrict__ rowc,
                                                                 const uint32_t *__restrict__ bitmap, int32_t words,
                                                                 float *__restrict__ acc_dk, float *__restrict__ acc_dv) {
     constexpr int kSegWords = kSegTokens / 32;
     constexpr int kSegWordsPerLane = kSegWords / 64;      // the member list is compacted by one wavefront
     static_assert(kSegWords % 64 == 0 && kSegTokens <= 65536, "whole words per lane; 16-bit offsets in the member list");
-    __shared__ uint16_t list[kSegTokens];                // member tokens as offsets into the segment
-    __shared__ __align__(16) uint16_t stage[2][kPairRows * kRowPitch];   // [buffer][(q | dout, token, head)][channel]
-    __shared__ __align__(16) uint16_t stageT[2][2 * 8 * 64 * 8];         // [buffer][(q | dout, dt, lane)][token][4 heads]
-    __shared__ __align__(16) float ld[2][2][2][16];       // [buffer][lse | D][token of the pair][head]
+    __shared__ uint16_t list[kSegTokens / kBwdSlices];   // this workgroup's member tokens as offsets into the segment
+    __shared__ BwdRows rows_even, rows_odd;
+    __shared__ BwdScalars sc_even, sc_odd;
     __shared__ int total_s;
-    const int j = blockIdx.x, seg = blockIdx.y;
+    // grid (segments x slices, blocks, B*Hkv): the initial blocks, which every token lists, come first in the
+    // launch order; a (block, segment) unit with many members is shared by up to kBwdSlices workgroups, each
+    // taking kSliceTokens consecutive members (the time of the longest workgroup bounds the kernel otherwise)
+    constexpr int kSliceTokens = kSegTokens / kBwdSlices;
+    const int j = blockIdx.x, seg = blockIdx.y / kBwdSlices, slice = blockIdx.y - seg * kBwdSlices;
     const int b = blockIdx.z / dm.Hkv, h = blockIdx.z - b * dm.Hkv;
     const int L = seq_len(dm, seqlens, b);
     if ((seg + 1) * kSegTokens <= j * kBlock || seg * kSegTokens >= L || j * kBlock >= L) return;   // no member can be here
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n = lane & 15, g = lane >> 4;
     const int G = dm.G;
     const float c = dm.scale_log2;
     const int64_t bh = (int64_t)b * dm.Hkv + h;
     // ---- member tokens of this segment, ascending (wave 0) ----------------------------------------------
+    uint32_t word[kSegWordsPerLane];                      // consecutive words per lane: the list comes out ascending
+    int before = 0, mine = 0;
     if (wave == 0) {
-        uint32_t word[kSegWordsPerLane];                  // consecutive words per lane: the list comes out ascending
-        int mine = 0;
 #pragma unroll
         for (int i = 0; i < kSegWordsPerLane; ++i) {
             word[i] = bitmap[(bh * nb_cap + j) * words + seg * kSegWords + lane * kSegWordsPerLane + i];
             mine += __popc(word[i]);
         }
-        int before = mine;
+        before = mine;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
             const int x = __shfl_up(before, o);
@@ -415,157 +451,163 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
         }
         if (lane == 63) total_s = before;
         before -= mine;
+    }
+    __syncthreads();
+    const int first = slice * kSliceTokens;               // this workgroup's members: first .. first + total - 1 of the unit
+    const int total = min(total_s - first, kSliceTokens);
+    if (total <= 0) return;                               // uniform
+    if (wave == 0) {
 #pragma unroll
         for (int i = 0; i < kSegWordsPerLane; ++i) {
             uint32_t w = word[i];
             while (w) {
                 const int bit = __ffs(w) - 1;
                 w &= w - 1;
-                list[before++] = (uint16_t)((lane * kSegWordsPerLane + i) * 32 + bit);
+                const int at = before++ - first;
+                if (at >= 0 && at < kSliceTokens) list[at] = (uint16_t)((lane * kSegWordsPerLane + i) * 32 + bit);
             }
         }
     }
     __syncthreads();
-    const int total = total_s;
-    if (total == 0) return;                               // uniform
-    const int n_pairs = (total + 1) >> 1;
-    // ---- this wave's keys as B operands: lane (n, g) = key 16w + n, channels 32ks + 8g .. +7 -----------
-    const u32x4 *blk_lane = reinterpret_cast<const u32x4 *>(kvb) + (bh * nb_cap + j) * kBwdBlockU4 + lane;
-    bf16x8 kB[4], vB[4];
+    const int n_steps = (total + 3) >> 2;                 // four tokens per step
+    const int kh = wave & 1, chh = wave >> 1;             // key half; channel half of the gradients
+    const int c32 = lane & 31, hf = lane >> 5;
+    // ---- this wave's keys as B operands: lane (c32, hf) = key 32kh + c32, channels 16ks + 8hf .. +7, picked
+    // out of the 16-key fragments of the packed block ------------------------------------------------------
+    const u32x4 *blk = reinterpret_cast<const u32x4 *>(kvb) + (bh * nb_cap + j) * kBwdBlockU4;
+    bf16x8 kB[8], vB[8];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        kB[ks] = __builtin_bit_cast(bf16x8, blk_lane[(ks * 4 + wave) * 64]);
-        vB[ks] = __builtin_bit_cast(bf16x8, blk_lane[(16 + ks * 4 + wave) * 64]);
+    for (int ks = 0; ks < 8; ++ks) {
+        const int at = ((ks >> 1) * 4 + 2 * kh + (c32 >> 4)) * 64 + (2 * (ks & 1) + hf) * 16 + (c32 & 15);
+        kB[ks] = __builtin_bit_cast(bf16x8, blk[at]);
+        vB[ks] = __builtin_bit_cast(bf16x8, blk[1024 + at]);
     }
-    f32x4 dkT[8], dvT[8];
+    f32x16 dkT[2], dvT[2];
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt) dkT[dt] = dvT[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const int key = j * kBlock + 16 * wave + n;           // this lane's key (column of S)
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dkT[ct][v] = dvT[ct][v] = 0.f;
+    const int key = j * kBlock + 32 * kh + c32;           // this lane's key (column of S)
 
-    // this thread's share of a pair: a 4-head x 8-channel patch of one of the four 16-row tiles
-    // (tile = tid>>6: q of token a, q of token b, dout of token a, dout of token b; heads 4*f_g .. +3,
-    // channels 8*f_pc .. +7), one scalar.  The patch goes to LDS twice: as rows (A operands of the
-    // first products, 16 bytes per head) and transposed (A operands of the second products: lane
-    // (n = channel, g) reads heads 4g .. 4g+3 of its channel as 8 bytes).
-    const int f_tile = tid >> 6, f_g = (tid >> 4) & 3, f_pc = tid & 15;
-    const Tensor &src = (f_tile & 2) ? dout : q;
-    const __bf16 *f_base[4];
+    // staging: wave w copies heads 4w .. 4w+3 of both tokens of a pair, q and dout: four 1 KiB copies per pair,
+    // lane = (head 4w + lane/16, piece lane%16 of the LDS row = piece (lane%16) ^ head of the row in memory)
+    const int s_n = 4 * wave + (lane >> 4);
+    const int s_piece = (lane & 15) ^ bwd_swizzle(s_n);
+    const __bf16 *s_q = q.ptr + b * q.sb + (int64_t)(h * G + min(s_n, G - 1)) * q.sh + 8 * s_piece;
+    const __bf16 *s_g = dout.ptr + b * dout.sb + (int64_t)(h * G + min(s_n, G - 1)) * dout.sh + 8 * s_piece;
+    const float *s_f = rowc + ((int64_t)b * dm.max_seqlen * dm.Hkv + h) * 32 + 16 * (lane >> 5) + (lane & 15);   // + 32 Hkv tok
+    auto stage = [&](BwdRows &dst, BwdScalars &dsc, int s) __attribute__((always_inline)) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-        f_base[e] = src.ptr + b * src.sb + (int64_t)(h * G + min(4 * f_g + e, G - 1)) * src.sh + 8 * f_pc;
-    u32x4 r[kDepth][4];                                   // (ext vectors: arrays of HIP's uint4 struct end up in scratch)
-    float rf[kDepth];
-    auto fetch = [&](int p, int st) __attribute__((always_inline)) {
-        const int ta = seg * kSegTokens + list[min(2 * p, total - 1)], tb = seg * kSegTokens + list[min(2 * p + 1, total - 1)];
-        const int tok = (f_tile & 1) ? tb : ta;
+        for (int pr = 0; pr < 2; ++pr) {
+            const int p = 2 * s + pr;                     // pairs past the end are copies of the last token, never used
+            const int ta = seg * kSegTokens + list[min(2 * p, total - 1)], tb = seg * kSegTokens + list[min(2 * p + 1, total - 1)];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) r[st][e] = *reinterpret_cast<const u32x4 *>(f_base[e] + (int64_t)tok * src.st);
-        {   // every thread loads (a fixed number of loads per step keeps the wait counts exact); 64 values are kept
-            const int t2 = ((tid >> 4) & 1) ? tb : ta;
-            const int64_t o = ((int64_t)b * dm.max_seqlen + t2) * dm.Hq + h * G + min(tid & 15, G - 1);
-            rf[st] = ((tid >> 5) & 1 ? delta : lse)[o];
+            for (int k = 0; k < 4; ++k) {
+                const int part = k >> 1, u = k & 1;
+                const int tok = u ? tb : ta;
+                const __bf16 *src = part ? s_g + (int64_t)tok * dout.st : s_q + (int64_t)tok * q.st;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                                 (__attribute__((address_space(3))) void *)&dst.rows[pr][part][16 * u + 4 * wave][0],
+                                                 16, 0, 0);
+            }
+            if (wave == 0) {
+                const int tok = ((lane >> 4) & 1) ? tb : ta;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(s_f + (int64_t)tok * dm.Hkv * 32),
+                                                 (__attribute__((address_space(3))) void *)&dsc.ld[pr][0], 4, 0, 0);
+            }
         }
     };
-    auto stash = [&](int buf, int st) __attribute__((always_inline)) {
-        uint16_t *dst = &stage[buf][(f_tile * 16 + 4 * f_g) * kRowPitch + 8 * f_pc];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            u32x4 x = r[st][e];
-            if (4 * f_g + e >= G) x = u32x4{0u, 0u, 0u, 0u};        // heads past the group are zero rows
-            *reinterpret_cast<u32x4 *>(dst + e * kRowPitch) = x;
-        }
-        // transposed: channel 8*f_pc + cc -> fragment dt = f_pc/2, lane (f_g, m = 8*(f_pc&1) + cc): heads 4f_g .. +3.
-        // Layout [q | dout][dt][lane][token of the pair][4 heads]: a lane finds the 16 bytes of one A operand
-        // in one piece.  The 16-byte slots of a fragment are XOR-swizzled with dt & 7 so that the 16 lanes of
-        // a store, which differ in dt, spread over all banks; a load has dt fixed and stays a permutation.
-        const int t_dt = f_pc >> 1;
-        u32x2 *trow = reinterpret_cast<u32x2 *>(&stageT[buf][(((f_tile >> 1) * 8 + t_dt) * 64) * 8]) + (f_tile & 1);
-        const int t_lane = f_g * 16 + 8 * (f_pc & 1);
-#pragma unroll
-        for (int c2 = 0; c2 < 4; ++c2) {                  // channels 2*c2, 2*c2+1 sit in word c2 of every head's piece
-            uint32_t w[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) w[e] = (4 * f_g + e < G) ? r[st][e][c2] : 0u;
-            const uint32_t lo01 = __builtin_amdgcn_perm(w[1], w[0], 0x05040100u);   // low halves of heads 0, 1
-            const uint32_t lo23 = __builtin_amdgcn_perm(w[3], w[2], 0x05040100u);
-            const uint32_t hi01 = __builtin_amdgcn_perm(w[1], w[0], 0x07060302u);   // high halves
-            const uint32_t hi23 = __builtin_amdgcn_perm(w[3], w[2], 0x07060302u);
-            trow[2 * ((t_lane + 2 * c2) ^ (t_dt & 7))] = u32x2{lo01, lo23};         // channel 2*c2
-            trow[2 * ((t_lane + 2 * c2 + 1) ^ (t_dt & 7))] = u32x2{hi01, hi23};     // channel 2*c2 + 1
-        }
-        if (tid < 64) ld[buf][tid >> 5][(tid >> 4) & 1][tid & 15] = rf[st];
-    };
+    // LDS addresses of the operand loads, the parts that depend on the lane
+    const uint32_t a_row = (uint32_t)c32 * 256u + (uint32_t)((hf ^ bwd_swizzle(c32 & 15)) << 4);   // piece 2ks + hf of row c32: ^ (ks << 5)
+    const uint32_t t_r = 4u * hf + ((lane & 15) >> 2), t_c = 2u * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+    // (channel tile 2chh + ct starts at piece 8chh + 4ct; rows 8rd + t_r have swizzle 2rd ^ swizzle(t_r))
+    const uint32_t a_tr = t_r * 256u + ((t_c ^ (uint32_t)bwd_swizzle((int)t_r) ^ (8u * chh)) << 4) + 8u * (lane & 1);   // ^ ((4ct ^ 2rd) << 4), + (16 s2 + 8 rd) rows
 
-    // pairs past the end are fetched as copies of the last one and never used
+    auto compute = [&](const BwdRows &cur, const BwdScalars &csc, int s, int pp) __attribute__((always_inline)) {
+        const int p = 2 * s + pp;
+        const bool one = 2 * p < total, two = 2 * p + 1 < total;
+        const int tk0 = seg * kSegTokens + list[min(2 * p, total - 1)], tk1 = seg * kSegTokens + list[min(2 * p + 1, total - 1)];
+        const char *xq = reinterpret_cast<const char *>(&cur.rows[pp][0][0][0]);
+        const char *xg = reinterpret_cast<const char *>(&cur.rows[pp][1][0][0]);
+        f32x16 sacc, dp;
 #pragma unroll
-    for (int st = 0; st < kDepth; ++st) fetch(st, st);
-    stash(0, 0);
-    fetch(kDepth, 0);
-    __syncthreads();
-    // The trip count is rounded up to a multiple of kDepth and the steps past the end work on copies of
-    // the last pair with every probability forced to zero: one loop exit, so the compiler's count of
-    // loads still in flight is the same on every path into a step and its waits stay exact.
-    for (int p0 = 0; p0 < n_pairs; p0 += kDepth) {
+        for (int v = 0; v < 16; ++v) sacc[v] = dp[v] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < kDepth; ++kk) {
-            const int p = p0 + kk;
-            const int cur = p & 1;
-            const bool one = 2 * p < total, two = 2 * p + 1 < total;
-            const int tk0 = seg * kSegTokens + list[min(2 * p, total - 1)], tk1 = seg * kSegTokens + list[min(2 * p + 1, total - 1)];
-            const uint16_t *sq = stage[cur];
-            bf16x8 ps, dss;                               // B operands of the second contractions
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int tok = u ? tk1 : tk0;
-                f32x4 sacc = {0.f, 0.f, 0.f, 0.f}, dp = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    const bf16x8 qa = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&sq[(u * 16 + n) * kRowPitch + 32 * ks + 8 * g]));
-                    const bf16x8 ga = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&sq[((2 + u) * 16 + n) * kRowPitch + 32 * ks + 8 * g]));
-                    sacc = mfma16(qa, kB[ks], sacc);
-                    dp = mfma16(ga, vB[ks], dp);
-                }
-                const float4 l4 = *reinterpret_cast<const float4 *>(&ld[cur][0][u][4 * g]);
-                const float4 d4 = *reinterpret_cast<const float4 *>(&ld[cur][1][u][4 * g]);
-                const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
-                const bool dead = !(u ? two : one) || key > tok;   // padding past the end of the list; causal inside the own block
-#pragma unroll
-                for (int rr = 0; rr < 4; ++rr) {
-                    float pr = fast_exp2(__builtin_fmaf(sacc[rr], c, -ls[rr] * kLog2e));
-                    if (dead || 4 * g + rr >= G || !(ls[rr] > -INFINITY)) pr = 0.f;
-                    ps[4 * u + rr] = (__bf16)pr;
-                    dss[4 * u + rr] = (__bf16)(pr * (dp[rr] - dl[rr]));
-                }
-            }
-            // A operands of the second products: lane (n = channel, g), element 4u + e = (token u, head 4g + e)
-            const u32x4 *tq = reinterpret_cast<const u32x4 *>(stageT[cur]);
-#pragma unroll
-            for (int dt = 0; dt < 8; ++dt) {
-                const u32x4 aq = tq[dt * 64 + (lane ^ (dt & 7))];
-                const u32x4 ag = tq[(8 + dt) * 64 + (lane ^ (dt & 7))];
-                dvT[dt] = mfma16(__builtin_bit_cast(bf16x8, ag), ps, dvT[dt]);
-                dkT[dt] = mfma16(__builtin_bit_cast(bf16x8, aq), dss, dkT[dt]);
-            }
-            // pair p+1 goes to the other buffer (last read one step ago), its registers take pair p+1+kDepth
-            constexpr int kD = kDepth;
-            const int st = (kk + 1) % kD;
-            __builtin_amdgcn_sched_barrier(0);            // keep the wait for this pair's registers behind the arithmetic
-            stash(cur ^ 1, st);
-            fetch(p + 1 + kD, st);
-            __syncthreads();
+        for (int ks = 0; ks < 8; ++ks) {
+            const u32x4 qa = *reinterpret_cast<const u32x4 *>(xq + (a_row ^ (uint32_t)(ks << 5)));
+            const u32x4 ga = *reinterpret_cast<const u32x4 *>(xg + (a_row ^ (uint32_t)(ks << 5)));
+            sacc = mfma32(__builtin_bit_cast(bf16x8, qa), kB[ks], sacc);
+            dp = mfma32(__builtin_bit_cast(bf16x8, ga), vB[ks], dp);
         }
-    }
-    // ---- merge: lane holds channels 16*dt + 4*g .. +3 of its key --------------------------------------------
-    if (key < L) {
-        float *pk = acc_dk + (bh * dm.max_seqlen + key) * kHeadDim + 4 * g;
-        float *pv = acc_dv + (bh * dm.max_seqlen + key) * kHeadDim + 4 * g;
+        // accumulator entry v of a lane: row 8(v/4) + 4hf + v%4 = (token v/8, head 8((v/4)%2) + 4hf + v%4), column = key.
+        // Padding of the list and the causal edge inside the own block: the exponent's offset becomes -inf.
+        const float bias0 = (!one | (key > tk0)) ? -INFINITY : 0.f, bias1 = (!two | (key > tk1)) ? -INFINITY : 0.f;
+        bf16x8 ps[2], dss[2];                             // B operands of the second products, one k-step per token
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt)
+        for (int j4 = 0; j4 < 4; ++j4) {
+            const float4 n4 = *reinterpret_cast<const float4 *>(&csc.ld[pp][8 * j4 + 4 * hf]);
+            const float4 d4 = *reinterpret_cast<const float4 *>(&csc.ld[pp][32 + 8 * j4 + 4 * hf]);
+            const float nl[4] = {n4.x, n4.y, n4.z, n4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
+            const float bias = (j4 >> 1) ? bias1 : bias0;
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) {
-                unsafeAtomicAdd(pk + 16 * dt + rr, dkT[dt][rr]);
-                unsafeAtomicAdd(pv + 16 * dt + rr, dvT[dt][rr]);
+            for (int e = 0; e < 4; ++e) {
+                const int v = 4 * j4 + e;
+                const float pr = fast_exp2(__builtin_fmaf(sacc[v], c, nl[e] + bias));
+                ps[v >> 3][v & 7] = (__bf16)pr;
+                dss[v >> 3][v & 7] = (__bf16)(pr * (dp[v] - dl[e]));
             }
+        }
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const uint32_t o0 = (a_tr ^ (uint32_t)((4 * ct) << 4)) + (uint32_t)(16 * s2) * 256u;
+                const uint32_t o1 = (a_tr ^ (uint32_t)(((4 * ct) ^ 2) << 4)) + (uint32_t)(16 * s2 + 8) * 256u;
+                const s16x4 g0 = lds_read_tr16(xg + o0), g1 = lds_read_tr16(xg + o1);
+                const s16x4 q0 = lds_read_tr16(xq + o0), q1 = lds_read_tr16(xq + o1);
+                const bf16x8 ag = __builtin_bit_cast(bf16x8, __builtin_shufflevector(g0, g1, 0, 1, 2, 3, 4, 5, 6, 7));
+                const bf16x8 aq = __builtin_bit_cast(bf16x8, __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7));
+                dvT[ct] = mfma32(ag, ps[s2], dvT[ct]);
+                dkT[ct] = mfma32(aq, dss[s2], dkT[ct]);
+            }
+    };
+    auto step = [&](BwdRows &cur, BwdScalars &csc, BwdRows &nxt, BwdScalars &nsc, int s) __attribute__((always_inline)) {
+        __builtin_amdgcn_s_waitcnt(0);                    // this wavefront's copies for step s have landed
+        __syncthreads();                                  // everyone's have, and everyone is past its reads of step s - 1
+        if (s + 1 < n_steps) stage(nxt, nsc, s + 1);
+        compute(cur, csc, s, 0);
+        if (2 * (2 * s + 1) < total) compute(cur, csc, s, 1);   // (uniform)
+    };
+    stage(rows_even, sc_even, 0);
+    for (int s = 0; s < n_steps; s += 2) {
+        step(rows_even, sc_even, rows_odd, sc_odd, s);
+        if (s + 1 < n_steps) step(rows_odd, sc_odd, rows_even, sc_even, s + 1);
+    }
+    // ---- merge: a lane holds channels 64chh + 32ct + 8(v/4) + 4hf + v%4 of its key.  The tiles are turned through
+    // LDS (the staging buffers, 8 KiB per wavefront) so that one atomic instruction covers 64 consecutive
+    // channels of one key: two cache lines instead of 64. ------------------------------------------------------
+    __syncthreads();                                      // every wavefront is past its last read of the staging buffers
+    float *tile = reinterpret_cast<float *>(wave < 2 ? &rows_even.rows[0][0][0][0] : &rows_odd.rows[0][0][0][0]) + (wave & 1) * 2048;
+    const int key0 = j * kBlock + 32 * kh;
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+        float *acc = (which ? acc_dv : acc_dk) + (bh * dm.max_seqlen + key0) * kHeadDim + 64 * chh + lane;
+        // [key][16-byte piece ^ (key & 15)][4 channels]
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const f32x16 &t = which ? dvT[ct] : dkT[ct];
+                const int piece = 8 * ct + 2 * v4 + hf;   // channels 4 piece .. +3 of the wave's 64
+                *reinterpret_cast<float4 *>(tile + c32 * 64 + ((piece ^ (c32 & 15)) << 2)) =
+                    float4{t[4 * v4], t[4 * v4 + 1], t[4 * v4 + 2], t[4 * v4 + 3]};
+            }
+        // (same wavefront wrote and reads: LDS keeps the order)
+#pragma unroll 8
+        for (int k = 0; k < 32; ++k) {
+            const float x = tile[k * 64 + ((((lane >> 2) ^ (k & 15)) << 2) | (lane & 3))];
+            if (key0 + k < L) unsafeAtomicAdd(acc + (int64_t)k * kHeadDim, x);
+        }
     }
 }
 
@@ -601,6 +643,7 @@ int launch_attn_bwd(const Dims &dm, Tensor q, Tensor k, Tensor v, Tensor out, Te
     char *base = reinterpret_cast<char *>(ws);
     uint4 *kvb = reinterpret_cast<uint4 *>(base + l.kvb);
     float *delta = reinterpret_cast<float *>(base + l.delta);
+    float *rowc = reinterpret_cast<float *>(base + l.rowc);
     uint32_t *bitmap = reinterpret_cast<uint32_t *>(base + l.bitmap);
     float *acc_dk = reinterpret_cast<float *>(base + l.acc_dk), *acc_dv = reinterpret_cast<float *>(base + l.acc_dv);
     const int T = dm.max_seqlen;
@@ -610,7 +653,7 @@ int launch_attn_bwd(const Dims &dm, Tensor q, Tensor k, Tensor v, Tensor out, Te
     timing_end(stream);
     timing_begin("bwd_prep_kernel", stream);
     hipLaunchKernelGGL(bwd_prep_kernel, dim3((T + 3) / 4, dm.Hkv, dm.batch), dim3(256), 0, stream, dm, out, dout,
-                       seqlens, block_idx, delta, bitmap, l.nb_cap, l.words);
+                       seqlens, block_idx, lse, delta, rowc, bitmap, l.nb_cap, l.words);
     timing_end(stream);
     timing_begin("pack_bwd_kernel", stream);
     hipLaunchKernelGGL(pack_bwd_kernel, dim3(l.nb_cap, dm.Hkv, dm.batch), dim3(256), 0, stream, dm, k, v, seqlens, kvb,
@@ -623,11 +666,11 @@ int launch_attn_bwd(const Dims &dm, Tensor q, Tensor k, Tensor v, Tensor out, Te
     timing_end(stream);
     timing_begin("attn_bwd_dkdv_kernel", stream);
     if (bwd_seg_tokens(dm) == 4096)
-        hipLaunchKernelGGL(attn_bwd_dkdv_kernel<4096>, dim3(l.nb_cap, l.words / 128, dm.batch * dm.Hkv), dim3(256), 0,
-                           stream, dm, q, dout, kvb, l.nb_cap, seqlens, lse, delta, bitmap, l.words, acc_dk, acc_dv);
+        hipLaunchKernelGGL(attn_bwd_dkdv_kernel<4096>, dim3(l.nb_cap, l.words / 128 * kBwdSlices, dm.batch * dm.Hkv), dim3(256), 0,
+                           stream, dm, q, dout, kvb, l.nb_cap, seqlens, rowc, bitmap, l.words, acc_dk, acc_dv);
     else
-        hipLaunchKernelGGL(attn_bwd_dkdv_kernel<2048>, dim3(l.nb_cap, l.words / 64, dm.batch * dm.Hkv), dim3(256), 0,
-                           stream, dm, q, dout, kvb, l.nb_cap, seqlens, lse, delta, bitmap, l.words, acc_dk, acc_dv);
+        hipLaunchKernelGGL(attn_bwd_dkdv_kernel<2048>, dim3(l.nb_cap, l.words / 64 * kBwdSlices, dm.batch * dm.Hkv), dim3(256), 0,
+                           stream, dm, q, dout, kvb, l.nb_cap, seqlens, rowc, bitmap, l.words, acc_dk, acc_dv);
     timing_end(stream);
     timing_begin("bwd_finish_kernel", stream);
     hipLaunchKernelGGL(bwd_finish_kernel, dim3((T + 15) / 16, dm.Hkv, dm.batch), dim3(256), 0, stream, dm, seqlens,

@@ -373,31 +373,33 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(Dims dm, Tensor q, 
     }
 }
 
-// ---- dk, dv: a wavefront owns 32 keys of a block ---------------------------------------------------------
+// ---- dk, dv of one block from the tokens that selected it ------------------------------------------------------
 // 256 threads: a workgroup handles member tokens of block j that lie in one segment of the sequence (all of
-// them, or one slice of the list when there are many).  The member tokens are compacted from the bitmap into a list
-// and walked in pairs, two pairs per step.  Wave w owns the keys 64j + 32(w&1) .. +31 and, of their
-// gradients, the channels 64(w>>1) .. +63: the two wavefronts of a key half both form S and dP of every
-// pair (a wavefront that owned all 128 channels of dk and dv would need 128 accumulator registers on top
-// of the 64 of its K and V operands, and spill).  With 32x32x16 MFMAs, rows = (token of the pair, head):
-//   S  [row, key] = Q . K^T         A = the pair's q rows from LDS, B = K rows of the wave's keys (registers)
-//   dP [row, key] = dO . V^T
-//   dV^T[c, key] += dO^T[c, row] . P[row, key]      A = the same staged rows read through the transposing
-//   dK^T[c, key] += Q^T [c, row] . dS[row, key]     LDS load, B = P / dS as they sit in the accumulators
-// Staging: the 16 KiB of q and dout rows of a pair go from memory straight into LDS (no registers, no vector
-// instructions), a step ahead of their use; two step buffers alternate.  They are two objects and the
-// loop is unrolled by two, so that the compiler's wait counts let a read of one buffer run under the
-// copies into the other.  A row is 256 bytes; its sixteen 16-byte pieces are stored XOR-swizzled with the
-// head's two bit pairs exchanged: an operand load of the first products takes one piece from each of 16
-// rows, a transposing load 32 bytes from each of 4 consecutive rows, and both then touch every bank once.
+// them, or one slice of the list when there are many).  The member tokens are compacted from the bitmap into a
+// list and walked in pairs; rows = (token of the pair, head).  Every pair has two phases with a barrier between:
+//   phase 1, wave = (token u, key half kh), 16x16x32 MFMAs: S = Q.K^T and dP = dO.V^T for the token's 16 heads
+//            and the half's 32 keys (A = the token's q / dout rows from LDS, B = K / V rows of the keys, held
+//            in registers), then P = exp(S - lse) and dS = P (dP - D), left in LDS as bf16 in the layout of a
+//            32x32x16 B operand (lane = key, 8 heads of one token per lane);
+//   phase 2, wave = channel quarter cq, 32x32x16 MFMAs: dV^T[c, key] += dO^T[c, row] . P[row, key] and
+//            dK^T[c, key] += Q^T[c, row] . dS[row, key] for channels 32cq .. +31 and all 64 keys: A = the same
+//            staged rows read through the transposing LDS load (each fragment feeds both key halves), B = P / dS.
+// Nothing is computed twice, and a wavefront keeps 64 accumulator registers next to the 64 of its K and V operands.
+// Staging: the 16 KiB of q and dout rows of a pair (and its 64 scalars) go from memory straight into LDS (no
+// registers, no vector instructions) two pairs ahead; three slots rotate.  The slots are three objects and the
+// loop is unrolled by three, so that the compiler's wait counts let reads of one slot run under the copies into
+// another.  A row is 256 bytes; its sixteen 16-byte pieces are stored XOR-swizzled with the head's two bit
+// pairs exchanged: an operand load of phase 1 takes one piece from each of 16 rows, a transposing load 32 bytes
+// from each of 4 consecutive rows, and both then touch every bank once.
 constexpr int kBwdSlices = 4;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-struct __align__(16) BwdRows {
-    uint16_t rows[2][2][32][kHeadDim];                    // [pair of the step][q | dout][(token, head)][channel]: 32 KiB
+struct __align__(16) BwdSlot {
+    uint16_t rows[2][32][kHeadDim];                       // [q | dout][(token, head)][channel]: 16 KiB
+    float ld[64];                                         // [exponent offset of token a, of b | D of token a, of b][head]
 };
-struct __align__(16) BwdScalars {
-    float ld[2][64];                                      // [pair][exponent offset of token a, of b | D of token a, of b][head]
+struct __align__(16) BwdExchange {
+    uint4 frag[2][2][2][2][64];                           // [buffer][P | dS][token][key half][lane = (key, head group)]: 16 KiB
 };
 __device__ __forceinline__ int bwd_swizzle(int head) { return ((head & 3) << 2) | ((head >> 2) & 3); }
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
@@ -419,12 +421,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
     constexpr int kSegWordsPerLane = kSegWords / 64;      // the member list is compacted by one wavefront
     static_assert(kSegWords % 64 == 0 && kSegTokens <= 65536, "whole words per lane; 16-bit offsets in the member list");
     __shared__ uint16_t list[kSegTokens / kBwdSlices];   // this workgroup's member tokens as offsets into the segment
-    __shared__ BwdRows rows_even, rows_odd;
-    __shared__ BwdScalars sc_even, sc_odd;
+    __shared__ BwdSlot slot0, slot1, slot2;
+    __shared__ BwdExchange ex;
     __shared__ int total_s;
-    // grid (segments x slices, blocks, B*Hkv): the initial blocks, which every token lists, come first in the
-    // launch order; a (block, segment) unit with many members is shared by up to kBwdSlices workgroups, each
-    // taking kSliceTokens consecutive members (the time of the longest workgroup bounds the kernel otherwise)
+    // grid (blocks, segments x slices, B*Hkv): workgroups that run at the same time work on neighbouring blocks
+    // of one segment and find its tokens' rows in the caches; a (block, segment) unit with many members is
+    // shared by up to kBwdSlices workgroups, each taking kSliceTokens consecutive members
     constexpr int kSliceTokens = kSegTokens / kBwdSlices;
     const int j = blockIdx.x, seg = blockIdx.y / kBwdSlices, slice = blockIdx.y - seg * kBwdSlices;
     const int b = blockIdx.z / dm.Hkv, h = blockIdx.z - b * dm.Hkv;
@@ -469,144 +471,165 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
         }
     }
     __syncthreads();
-    const int n_steps = (total + 3) >> 2;                 // four tokens per step
-    const int kh = wave & 1, chh = wave >> 1;             // key half; channel half of the gradients
-    const int c32 = lane & 31, hf = lane >> 5;
-    // ---- this wave's keys as B operands: lane (c32, hf) = key 32kh + c32, channels 16ks + 8hf .. +7, picked
-    // out of the 16-key fragments of the packed block ------------------------------------------------------
-    const u32x4 *blk = reinterpret_cast<const u32x4 *>(kvb) + (bh * nb_cap + j) * kBwdBlockU4;
-    bf16x8 kB[8], vB[8];
+    const int n_pairs = (total + 1) >> 1;
+    const int n = lane & 15, g = lane >> 4;               // 16x16x32 roles: row / column, k group
+    const int c32 = lane & 31, hf = lane >> 5;            // 32x32x16 roles
+    const int u = wave >> 1, kh = wave & 1;               // phase 1: token of the pair, key half
+    const int cq = wave;                                  // phase 2: channel quarter
+    // ---- phase 1 B operands: K and V rows of keys 32kh + 16t + n, channels 32ks + 8g .. +7 ---------------------
+    const u32x4 *blk = reinterpret_cast<const u32x4 *>(kvb) + (bh * nb_cap + j) * kBwdBlockU4 + lane;
+    bf16x8 kB[2][4], vB[2][4];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        const int at = ((ks >> 1) * 4 + 2 * kh + (c32 >> 4)) * 64 + (2 * (ks & 1) + hf) * 16 + (c32 & 15);
-        kB[ks] = __builtin_bit_cast(bf16x8, blk[at]);
-        vB[ks] = __builtin_bit_cast(bf16x8, blk[1024 + at]);
-    }
-    f32x16 dkT[2], dvT[2];
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int ct = 0; ct < 2; ++ct)
+        for (int ks = 0; ks < 4; ++ks) {
+            kB[t][ks] = __builtin_bit_cast(bf16x8, blk[(ks * 4 + 2 * kh + t) * 64]);
+            vB[t][ks] = __builtin_bit_cast(bf16x8, blk[(16 + ks * 4 + 2 * kh + t) * 64]);
+        }
+    f32x16 dkT[2], dvT[2];                                // [key half]: channels 32cq .. +31 x 32 keys
 #pragma unroll
-        for (int v = 0; v < 16; ++v) dkT[ct][v] = dvT[ct][v] = 0.f;
-    const int key = j * kBlock + 32 * kh + c32;           // this lane's key (column of S)
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dkT[i][v] = dvT[i][v] = 0.f;
 
     // staging: wave w copies heads 4w .. 4w+3 of both tokens of a pair, q and dout: four 1 KiB copies per pair,
-    // lane = (head 4w + lane/16, piece lane%16 of the LDS row = piece (lane%16) ^ head of the row in memory)
+    // lane = (head 4w + lane/16, piece lane%16 of the LDS row = piece (lane%16) ^ swizzle(head) of the row in memory)
     const int s_n = 4 * wave + (lane >> 4);
     const int s_piece = (lane & 15) ^ bwd_swizzle(s_n);
     const __bf16 *s_q = q.ptr + b * q.sb + (int64_t)(h * G + min(s_n, G - 1)) * q.sh + 8 * s_piece;
     const __bf16 *s_g = dout.ptr + b * dout.sb + (int64_t)(h * G + min(s_n, G - 1)) * dout.sh + 8 * s_piece;
     const float *s_f = rowc + ((int64_t)b * dm.max_seqlen * dm.Hkv + h) * 32 + 16 * (lane >> 5) + (lane & 15);   // + 32 Hkv tok
-    auto stage = [&](BwdRows &dst, BwdScalars &dsc, int s) __attribute__((always_inline)) {
+    auto stage = [&](BwdSlot &dst, int p) __attribute__((always_inline)) {
+        const int ta = seg * kSegTokens + list[min(2 * p, total - 1)], tb = seg * kSegTokens + list[min(2 * p + 1, total - 1)];
 #pragma unroll
-        for (int pr = 0; pr < 2; ++pr) {
-            const int p = 2 * s + pr;                     // pairs past the end are copies of the last token, never used
-            const int ta = seg * kSegTokens + list[min(2 * p, total - 1)], tb = seg * kSegTokens + list[min(2 * p + 1, total - 1)];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int part = k >> 1, u = k & 1;
-                const int tok = u ? tb : ta;
-                const __bf16 *src = part ? s_g + (int64_t)tok * dout.st : s_q + (int64_t)tok * q.st;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                                 (__attribute__((address_space(3))) void *)&dst.rows[pr][part][16 * u + 4 * wave][0],
-                                                 16, 0, 0);
-            }
-            if (wave == 0) {
-                const int tok = ((lane >> 4) & 1) ? tb : ta;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(s_f + (int64_t)tok * dm.Hkv * 32),
-                                                 (__attribute__((address_space(3))) void *)&dsc.ld[pr][0], 4, 0, 0);
-            }
+        for (int k = 0; k < 4; ++k) {
+            const int part = k >> 1, tu = k & 1;
+            const int tok = tu ? tb : ta;
+            const __bf16 *src = part ? s_g + (int64_t)tok * dout.st : s_q + (int64_t)tok * q.st;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)&dst.rows[part][16 * tu + 4 * wave][0],
+                                             16, 0, 0);
+        }
+        if (wave == 0) {
+            const int tok = ((lane >> 4) & 1) ? tb : ta;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(s_f + (int64_t)tok * dm.Hkv * 32),
+                                             (__attribute__((address_space(3))) void *)&dst.ld[0], 4, 0, 0);
         }
     };
     // LDS addresses of the operand loads, the parts that depend on the lane
-    const uint32_t a_row = (uint32_t)c32 * 256u + (uint32_t)((hf ^ bwd_swizzle(c32 & 15)) << 4);   // piece 2ks + hf of row c32: ^ (ks << 5)
+    const uint32_t a_row = (uint32_t)(16 * u + n) * 256u + (uint32_t)((g ^ bwd_swizzle(n)) << 4);   // piece 4ks + g of the row: ^ (ks << 6)
     const uint32_t t_r = 4u * hf + ((lane & 15) >> 2), t_c = 2u * ((lane >> 4) & 1) + ((lane & 3) >> 1);
-    // (channel tile 2chh + ct starts at piece 8chh + 4ct; rows 8rd + t_r have swizzle 2rd ^ swizzle(t_r))
-    const uint32_t a_tr = t_r * 256u + ((t_c ^ (uint32_t)bwd_swizzle((int)t_r) ^ (8u * chh)) << 4) + 8u * (lane & 1);   // ^ ((4ct ^ 2rd) << 4), + (16 s2 + 8 rd) rows
+    // (channel quarter cq starts at piece 4cq; rows 8rd + t_r have swizzle 2rd ^ swizzle(t_r))
+    const uint32_t a_tr = t_r * 256u + ((t_c ^ (uint32_t)bwd_swizzle((int)t_r) ^ (4u * cq)) << 4) + 8u * (lane & 1);   // ^ (2rd << 4), + (16 s2 + 8 rd) rows
+    // where this lane's four probabilities of a key go in the exchange: consumer lane (key 16t + n, head group g & 1),
+    // elements 4 (g >> 1) .. +3
+    const uint32_t x_put = (uint32_t)((n + 32 * (g & 1)) * 16 + 8 * (g >> 1));   // + 256 t bytes
 
-    auto compute = [&](const BwdRows &cur, const BwdScalars &csc, int s, int pp) __attribute__((always_inline)) {
-        const int p = 2 * s + pp;
-        const bool one = 2 * p < total, two = 2 * p + 1 < total;
-        const int tk0 = seg * kSegTokens + list[min(2 * p, total - 1)], tk1 = seg * kSegTokens + list[min(2 * p + 1, total - 1)];
-        const char *xq = reinterpret_cast<const char *>(&cur.rows[pp][0][0][0]);
-        const char *xg = reinterpret_cast<const char *>(&cur.rows[pp][1][0][0]);
-        f32x16 sacc, dp;
+    auto phase1 = [&](const BwdSlot &cur, int p) __attribute__((always_inline)) {
+        const int tk = seg * kSegTokens + list[min(2 * p + u, total - 1)];
+        const bool valid = 2 * p + u < total;
+        const char *xq = reinterpret_cast<const char *>(&cur.rows[0][0][0]);
+        const char *xg = reinterpret_cast<const char *>(&cur.rows[1][0][0]);
+        f32x4 sacc[2], dp[2];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sacc[v] = dp[v] = 0.f;
+        for (int t = 0; t < 2; ++t) sacc[t] = dp[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const u32x4 qa = *reinterpret_cast<const u32x4 *>(xq + (a_row ^ (uint32_t)(ks << 5)));
-            const u32x4 ga = *reinterpret_cast<const u32x4 *>(xg + (a_row ^ (uint32_t)(ks << 5)));
-            sacc = mfma32(__builtin_bit_cast(bf16x8, qa), kB[ks], sacc);
-            dp = mfma32(__builtin_bit_cast(bf16x8, ga), vB[ks], dp);
-        }
-        // accumulator entry v of a lane: row 8(v/4) + 4hf + v%4 = (token v/8, head 8((v/4)%2) + 4hf + v%4), column = key.
-        // Padding of the list and the causal edge inside the own block: the exponent's offset becomes -inf.
-        const float bias0 = (!one | (key > tk0)) ? -INFINITY : 0.f, bias1 = (!two | (key > tk1)) ? -INFINITY : 0.f;
-        bf16x8 ps[2], dss[2];                             // B operands of the second products, one k-step per token
+        for (int ks = 0; ks < 4; ++ks) {
+            const bf16x8 qa = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(xq + (a_row ^ (uint32_t)(ks << 6))));
+            const bf16x8 ga = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(xg + (a_row ^ (uint32_t)(ks << 6))));
 #pragma unroll
-        for (int j4 = 0; j4 < 4; ++j4) {
-            const float4 n4 = *reinterpret_cast<const float4 *>(&csc.ld[pp][8 * j4 + 4 * hf]);
-            const float4 d4 = *reinterpret_cast<const float4 *>(&csc.ld[pp][32 + 8 * j4 + 4 * hf]);
-            const float nl[4] = {n4.x, n4.y, n4.z, n4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
-            const float bias = (j4 >> 1) ? bias1 : bias0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int v = 4 * j4 + e;
-                const float pr = fast_exp2(__builtin_fmaf(sacc[v], c, nl[e] + bias));
-                ps[v >> 3][v & 7] = (__bf16)pr;
-                dss[v >> 3][v & 7] = (__bf16)(pr * (dp[v] - dl[e]));
+            for (int t = 0; t < 2; ++t) {
+                sacc[t] = mfma16(qa, kB[t][ks], sacc[t]);
+                dp[t] = mfma16(ga, vB[t][ks], dp[t]);
             }
         }
+        // accumulator entry r of tile t: head 4g + r (row), key 32kh + 16t + n (column)
+        const float4 n4 = *reinterpret_cast<const float4 *>(&cur.ld[16 * u + 4 * g]);
+        const float4 d4 = *reinterpret_cast<const float4 *>(&cur.ld[32 + 16 * u + 4 * g]);
+        const float nl[4] = {n4.x, n4.y, n4.z, n4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
+        char *xp = reinterpret_cast<char *>(&ex.frag[p & 1][0][u][kh][0]) + x_put;
+        char *xs = reinterpret_cast<char *>(&ex.frag[p & 1][1][u][kh][0]) + x_put;
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
+        for (int t = 0; t < 2; ++t) {
+            // padding of the list and the causal edge inside the own block: the exponent's offset becomes -inf
+            const float bias = (!valid | (j * kBlock + 32 * kh + 16 * t + n > tk)) ? -INFINITY : 0.f;
+            bf16x4 pb, sb;
 #pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                const uint32_t o0 = (a_tr ^ (uint32_t)((4 * ct) << 4)) + (uint32_t)(16 * s2) * 256u;
-                const uint32_t o1 = (a_tr ^ (uint32_t)(((4 * ct) ^ 2) << 4)) + (uint32_t)(16 * s2 + 8) * 256u;
-                const s16x4 g0 = lds_read_tr16(xg + o0), g1 = lds_read_tr16(xg + o1);
-                const s16x4 q0 = lds_read_tr16(xq + o0), q1 = lds_read_tr16(xq + o1);
-                const bf16x8 ag = __builtin_bit_cast(bf16x8, __builtin_shufflevector(g0, g1, 0, 1, 2, 3, 4, 5, 6, 7));
-                const bf16x8 aq = __builtin_bit_cast(bf16x8, __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7));
-                dvT[ct] = mfma32(ag, ps[s2], dvT[ct]);
-                dkT[ct] = mfma32(aq, dss[s2], dkT[ct]);
+            for (int r = 0; r < 4; ++r) {
+                const float pr = fast_exp2(__builtin_fmaf(sacc[t][r], c, nl[r] + bias));
+                pb[r] = (__bf16)pr;
+                sb[r] = (__bf16)(pr * (dp[t][r] - dl[r]));
             }
+            *reinterpret_cast<uint2 *>(xp + 256 * t) = __builtin_bit_cast(uint2, pb);
+            *reinterpret_cast<uint2 *>(xs + 256 * t) = __builtin_bit_cast(uint2, sb);
+        }
     };
-    auto step = [&](BwdRows &cur, BwdScalars &csc, BwdRows &nxt, BwdScalars &nsc, int s) __attribute__((always_inline)) {
-        __builtin_amdgcn_s_waitcnt(0);                    // this wavefront's copies for step s have landed
-        __syncthreads();                                  // everyone's have, and everyone is past its reads of step s - 1
-        if (s + 1 < n_steps) stage(nxt, nsc, s + 1);
-        compute(cur, csc, s, 0);
-        if (2 * (2 * s + 1) < total) compute(cur, csc, s, 1);   // (uniform)
+    auto phase2 = [&](const BwdSlot &cur, int p) __attribute__((always_inline)) {
+        const char *xq = reinterpret_cast<const char *>(&cur.rows[0][0][0]);
+        const char *xg = reinterpret_cast<const char *>(&cur.rows[1][0][0]);
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const uint32_t o0 = a_tr + (uint32_t)(16 * s2) * 256u;
+            const uint32_t o1 = (a_tr ^ (uint32_t)(2 << 4)) + (uint32_t)(16 * s2 + 8) * 256u;
+            const s16x4 g0 = lds_read_tr16(xg + o0), g1 = lds_read_tr16(xg + o1);
+            const s16x4 q0 = lds_read_tr16(xq + o0), q1 = lds_read_tr16(xq + o1);
+            const bf16x8 ag = __builtin_bit_cast(bf16x8, __builtin_shufflevector(g0, g1, 0, 1, 2, 3, 4, 5, 6, 7));
+            const bf16x8 aq = __builtin_bit_cast(bf16x8, __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+            for (int k2 = 0; k2 < 2; ++k2) {
+                const bf16x8 pf = __builtin_bit_cast(bf16x8, ex.frag[p & 1][0][s2][k2][lane]);
+                const bf16x8 sf = __builtin_bit_cast(bf16x8, ex.frag[p & 1][1][s2][k2][lane]);
+                dvT[k2] = mfma32(ag, pf, dvT[k2]);
+                dkT[k2] = mfma32(aq, sf, dkT[k2]);
+            }
+        }
     };
-    stage(rows_even, sc_even, 0);
-    for (int s = 0; s < n_steps; s += 2) {
-        step(rows_even, sc_even, rows_odd, sc_odd, s);
-        if (s + 1 < n_steps) step(rows_odd, sc_odd, rows_even, sc_even, s + 1);
+    // pair p: phase 1, barrier, phase 2; the copies for pair p + 2 go out right after the barrier, into the slot
+    // whose last reads (phase 2 of pair p - 1) everyone has finished by then, and have a whole pair's time to land.
+    // The trip count is rounded up to a multiple of three and nothing in the loop is conditional (pairs past the
+    // end are copies of the last token with every probability zero): at a join of two paths the compiler would
+    // wait for every copy in flight.
+    auto pair_step = [&](const BwdSlot &cur, BwdSlot &third, int p) __attribute__((always_inline)) {
+        phase1(cur, p);
+        __builtin_amdgcn_s_waitcnt(0);                    // this wavefront's copies for pair p + 1 have landed
+        __syncthreads();                                  // everyone's have; P and dS of pair p are in place
+        stage(third, p + 2);
+        phase2(cur, p);
+    };
+    stage(slot0, 0);
+    stage(slot1, 1);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    for (int p = 0; p < n_pairs; p += 3) {
+        pair_step(slot0, slot2, p);
+        pair_step(slot1, slot0, p + 1);
+        pair_step(slot2, slot1, p + 2);
     }
-    // ---- merge: a lane holds channels 64chh + 32ct + 8(v/4) + 4hf + v%4 of its key.  The tiles are turned through
-    // LDS (the staging buffers, 8 KiB per wavefront) so that one atomic instruction covers 64 consecutive
-    // channels of one key: two cache lines instead of 64. ------------------------------------------------------
-    __syncthreads();                                      // every wavefront is past its last read of the staging buffers
-    float *tile = reinterpret_cast<float *>(wave < 2 ? &rows_even.rows[0][0][0][0] : &rows_odd.rows[0][0][0][0]) + (wave & 1) * 2048;
-    const int key0 = j * kBlock + 32 * kh;
+    __builtin_amdgcn_s_waitcnt(0);                        // the last copies (never used) have landed: the slots are reused below
+    // ---- merge: a lane holds channels 32cq + 8(v/4) + 4hf + v%4 of key 32kh' + c32.  The tiles are turned through
+    // LDS (the staging slots, 8 KiB per wavefront) so that one atomic instruction covers the 32 channels of two
+    // keys: two cache lines instead of 64. --------------------------------------------------------------------
+    __syncthreads();                                      // every wavefront is past its last read of the staging slots
+    float *tile = reinterpret_cast<float *>(wave < 2 ? &slot0.rows[0][0][0] : &slot1.rows[0][0][0]) + (wave & 1) * 2048;
 #pragma unroll
     for (int which = 0; which < 2; ++which) {
-        float *acc = (which ? acc_dv : acc_dk) + (bh * dm.max_seqlen + key0) * kHeadDim + 64 * chh + lane;
-        // [key][16-byte piece ^ (key & 15)][4 channels]
+        // [key 0 .. 63][16-byte piece ^ (key & 7)][4 channels]
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
+        for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4) {
-                const f32x16 &t = which ? dvT[ct] : dkT[ct];
-                const int piece = 8 * ct + 2 * v4 + hf;   // channels 4 piece .. +3 of the wave's 64
-                *reinterpret_cast<float4 *>(tile + c32 * 64 + ((piece ^ (c32 & 15)) << 2)) =
+                const f32x16 &t = which ? dvT[k2] : dkT[k2];
+                const int key = 32 * k2 + c32, piece = 2 * v4 + hf;   // channels 4 piece .. +3 of the wave's 32
+                *reinterpret_cast<float4 *>(tile + key * 32 + ((piece ^ (key & 7)) << 2)) =
                     float4{t[4 * v4], t[4 * v4 + 1], t[4 * v4 + 2], t[4 * v4 + 3]};
             }
         // (same wavefront wrote and reads: LDS keeps the order)
+        float *acc = (which ? acc_dv : acc_dk) + (bh * dm.max_seqlen + (int64_t)j * kBlock + hf) * kHeadDim + 32 * cq + c32;
 #pragma unroll 8
-        for (int k = 0; k < 32; ++k) {
-            const float x = tile[k * 64 + ((((lane >> 2) ^ (k & 15)) << 2) | (lane & 3))];
-            if (key0 + k < L) unsafeAtomicAdd(acc + (int64_t)k * kHeadDim, x);
+        for (int i = 0; i < 32; ++i) {
+            const int key = 2 * i + hf;
+            const float x = tile[key * 32 + ((((c32 >> 2) ^ (key & 7)) << 2) | (c32 & 3))];
+            if (j * kBlock + key < L) unsafeAtomicAdd(acc + (int64_t)(2 * i) * kHeadDim, x);
         }
     }
 }

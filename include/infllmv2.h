@@ -222,7 +222,8 @@ int32_t infllmv2_sparse_attn_prefill(const infllmv2_params *prm, const infllmv2_
  *   dq            out  [batch, max_seqlen, Hq, d] bf16 (rows t >= seqlens[b] not written)
  *   dk, dv        out  [batch, Hkv, >=max_seqlen, d] bf16 (rows t >= seqlens[b] not written)
  *   workspace     device scratch of infllmv2_workspace_bytes(INFLLMV2_OP_ATTN_BWD, ...) bytes: packed
- *                 copies of the K and V blocks, D, a block x token membership bitmap, fp32 dk / dv
+ *                 copies of the K and V blocks, D and the exponent offsets per (token, head), a block x token
+ *                 membership bitmap, fp32 dk / dv
  */
 int32_t infllmv2_sparse_attn_bwd(const infllmv2_params *prm, const infllmv2_tensor *q,
                                  const infllmv2_tensor *k, const infllmv2_tensor *v,

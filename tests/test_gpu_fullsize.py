@@ -463,8 +463,9 @@ def test_decode_graph_replays_match_eager():
 @pytest.mark.timeout(600)
 def test_backward_32k_sampled_rows_and_identities():
     # backward of the attention at the benchmark's size and launch configuration: dq on sampled
-    # rows and dk, dv on the last two blocks (which only the last 128 tokens attend) against the
-    # oracle; two identities that hold at any size on the whole tensors
+    # rows, dk, dv on the last two blocks (which only the last 128 tokens attend) and on three whole
+    # blocks in mid-sequence (from all their member tokens) against the oracle; two identities that
+    # hold at any size on the whole tensors
     from util import grad_err
     cfg = synth.CONFIGS[1]
     print("workload", cfg.name, "backward", flush=True)
@@ -502,6 +503,20 @@ def test_backward_32k_sampled_rows_and_identities():
     ev = grad_err(dv[0, :, l - 128:].double().cpu().numpy(), wv[:, l - 128:], mv[:, l - 128:])
     print("dk, dv on the last 128 keys: err/tol %.3f %.3f" % (ek, ev), flush=True)
     assert ek <= 1.0 and ev <= 1.0
+    # dk, dv of whole blocks in the middle of the sequence: a block collects from exactly the tokens that list it, so
+    # the oracle's gradients over those tokens are complete for the block's 64 keys.  The blocks lie in different
+    # segments of the member lists and the first one's members straddle a segment boundary.
+    for j in (127, 300, 449):
+        members = np.nonzero((idx_np == j).any(axis=(0, 2)))[0].astype(np.int32)
+        assert len(members) >= 128, (j, len(members))      # at least the tokens of the block and of the next one
+        _, wk, wv, _, mk, mv = ref.sparse_attn_bwd(np.ascontiguousarray(x.q[members]), x.k, x.v,
+                                                   np.ascontiguousarray(do_bits[members]), members,
+                                                   np.ascontiguousarray(idx_np[:, members]), oprm, want_mag=True)
+        ks = slice(64 * j, 64 * j + 64)
+        ek = grad_err(dk[0, :, ks].double().cpu().numpy(), wk[:, ks], mk[:, ks])
+        ev = grad_err(dv[0, :, ks].double().cpu().numpy(), wv[:, ks], mv[:, ks])
+        print("dk, dv of block %d from its %d member tokens: err/tol %.3f %.3f" % (j, len(members), ek, ev), flush=True)
+        assert ek <= 1.0 and ev <= 1.0
     # probabilities of a row sum to one: the value gradients of a head add up to the output gradients of its group
     dvs = dv[0].double().sum(1)                                                   # [Hkv, d]
     dos = do[0].double().view(l, Hkv, G, -1).sum((0, 2))

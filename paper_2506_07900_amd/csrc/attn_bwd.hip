@@ -492,27 +492,30 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(Dims dm, Tensor q
 #pragma unroll
         for (int v = 0; v < 16; ++v) dkT[i][v] = dvT[i][v] = 0.f;
 
-    // staging: wave w copies heads 4w .. 4w+3 of both tokens of a pair, q and dout: four 1 KiB copies per pair,
-    // lane = (head 4w + lane/16, piece lane%16 of the LDS row = piece (lane%16) ^ swizzle(head) of the row in memory)
-    const int s_n = 4 * wave + (lane >> 4);
-    const int s_piece = (lane & 15) ^ bwd_swizzle(s_n);
-    const __bf16 *s_q = q.ptr + b * q.sb + (int64_t)(h * G + min(s_n, G - 1)) * q.sh + 8 * s_piece;
-    const __bf16 *s_g = dout.ptr + b * dout.sb + (int64_t)(h * G + min(s_n, G - 1)) * dout.sh + 8 * s_piece;
+    // staging: wave w copies one token's 16 rows of one tensor (token w&1 of the pair, q for w < 2, dout else): four
+    // 1 KiB copies of four heads each, all from one token offset; lane = (head 4i + lane/16, piece lane%16 of the
+    // LDS row = piece (lane%16) ^ swizzle(head) of the row in memory)
+    const Tensor &s_t = wave < 2 ? q : dout;
+    const __bf16 *s_base = s_t.ptr + b * s_t.sb + (int64_t)(h * G) * s_t.sh;
+    int32_t s_off[4];                                     // elements from the token's first head of the group
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int head = 4 * i + (lane >> 4);
+        s_off[i] = (int32_t)(min(head, G - 1) * s_t.sh) + 8 * ((lane & 15) ^ bwd_swizzle(head));
+    }
     const float *s_f = rowc + ((int64_t)b * dm.max_seqlen * dm.Hkv + h) * 32 + 16 * (lane >> 5) + (lane & 15);   // + 32 Hkv tok
     auto stage = [&](BwdSlot &dst, int p) __attribute__((always_inline)) {
-        const int ta = seg * kSegTokens + list[min(2 * p, total - 1)], tb = seg * kSegTokens + list[min(2 * p + 1, total - 1)];
+        const int tok = seg * kSegTokens + list[min(2 * p + (wave & 1), total - 1)];
+        const __bf16 *src = s_base + (int64_t)tok * s_t.st;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int part = k >> 1, tu = k & 1;
-            const int tok = tu ? tb : ta;
-            const __bf16 *src = part ? s_g + (int64_t)tok * dout.st : s_q + (int64_t)tok * q.st;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                             (__attribute__((address_space(3))) void *)&dst.rows[part][16 * tu + 4 * wave][0],
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + s_off[i]),
+                                             (__attribute__((address_space(3))) void *)&dst.rows[wave >> 1][16 * (wave & 1) + 4 * i][0],
                                              16, 0, 0);
-        }
         if (wave == 0) {
-            const int tok = ((lane >> 4) & 1) ? tb : ta;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(s_f + (int64_t)tok * dm.Hkv * 32),
+            const int tb = seg * kSegTokens + list[min(2 * p + 1, total - 1)];
+            const int tk = ((lane >> 4) & 1) ? tb : tok;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(s_f + (int64_t)tk * dm.Hkv * 32),
                                              (__attribute__((address_space(3))) void *)&dst.ld[0], 4, 0, 0);
         }
     };

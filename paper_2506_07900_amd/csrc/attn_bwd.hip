@@ -31,7 +31,7 @@ constexpr int kBwdBlockU4 = 3 * 16 * 64;              // uint4 per packed block:
 // Member tokens of one dk/dv workgroup come from one segment of the sequence.  Short segments give
 // more workgroups (better balance at 32K tokens), long ones fewer prologues and merges per block
 // (at 128K tokens most (block, segment) units hold a handful of members).
-static inline int bwd_seg_tokens(const Dims &dm) { return dm.max_seqlen > 65536 ? 4096 : 2048; }
+static inline int bwd_seg_tokens(const Dims &dm) { return dm.max_seqlen > 65536 ? 8192 : 2048; }
 constexpr int kBwdNone = 0x7fffffff;
 constexpr int kBwdBlkBits = 27, kBwdBlkMask = (1 << kBwdBlkBits) - 1;
 
@@ -691,8 +691,8 @@ int launch_attn_bwd(const Dims &dm, Tensor q, Tensor k, Tensor v, Tensor out, Te
                        dm, q, dout, kvb, l.nb_cap, seqlens, block_idx, lse, delta, dq, n_tiles);
     timing_end(stream);
     timing_begin("attn_bwd_dkdv_kernel", stream);
-    if (bwd_seg_tokens(dm) == 4096)
-        hipLaunchKernelGGL(attn_bwd_dkdv_kernel<4096>, dim3(l.nb_cap, l.words / 128 * kBwdSlices, dm.batch * dm.Hkv), dim3(256), 0,
+    if (bwd_seg_tokens(dm) == 8192)
+        hipLaunchKernelGGL(attn_bwd_dkdv_kernel<8192>, dim3(l.nb_cap, l.words / 256 * kBwdSlices, dm.batch * dm.Hkv), dim3(256), 0,
                            stream, dm, q, dout, kvb, l.nb_cap, seqlens, rowc, bitmap, l.words, acc_dk, acc_dv);
     else
         hipLaunchKernelGGL(attn_bwd_dkdv_kernel<2048>, dim3(l.nb_cap, l.words / 64 * kBwdSlices, dm.batch * dm.Hkv), dim3(256), 0,

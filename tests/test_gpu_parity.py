@@ -707,9 +707,10 @@ def test_sparse_attn_backward(seqlens, Hq, Hkv, topk, planted):
 
 
 def test_sparse_attn_backward_long_capacity():
-    # buffers sized for more than 65536 tokens make the dk/dv kernel work on 4096-token segments
-    # (2048 below that); sequences that cross a segment boundary, the rest of the capacity unused
-    seqlens, Hq, Hkv, topk, cap = [5000, 4200], 16, 1, 8, 66000
+    # buffers sized for more than 65536 tokens make the dk/dv kernel work on 8192-token segments
+    # (2048 below that); a sequence that crosses a segment boundary and one that does not, the rest
+    # of the capacity unused
+    seqlens, Hq, Hkv, topk, cap = [9000, 4200], 16, 1, 8, 66000
     prm = binding.Params(Hq, Hkv, topk=topk)
     oprm = oracle_params(prm)
     q, k, v, T = make_batch(57, seqlens, Hq, Hkv, n_planted=4)

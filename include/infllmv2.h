@@ -216,6 +216,7 @@ int32_t infllmv2_sparse_attn_prefill(const infllmv2_params *prm, const infllmv2_
  * bf16 products accumulated in fp32; p and ds are rounded to bf16 before the second products;
  * dk, dv are merged with fp32 atomic adds (the last bits depend on the order).
  *   q, out, dout  in   [batch, max_seqlen, Hq, d] bf16: the forward's input, output and its gradient
+ *                      (q, dout: group size x head stride at most 2^30 elements, else INFLLMV2_ERR_UNSUPPORTED)
  *   k, v          in   bf16 caches [batch, Hkv, >=max_seqlen, d]
  *   lse           in   fp32 [batch, max_seqlen, Hq], the forward's log-sum-exp
  *   block_idx     in   int32 [batch, Hkv, max_seqlen, topk], as given to the forward

@@ -429,6 +429,9 @@ int32_t infllmv2_sparse_attn_bwd(const infllmv2_params *prm, const infllmv2_tens
     const infllmv2_tensor *ts[8] = {q, k, v, out, dout, dq, dk, dv};
     for (int i = 0; i < 8; ++i) RETURN_IF_ERR(check_tensor(ts[i]));
     if (!seqlens || !block_idx || !lse) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    // the dk/dv kernel addresses the heads of a group with 32-bit element offsets from the group's first head
+    const int64_t head_span = (int64_t)(prm->n_q_heads / prm->n_kv_heads) * (q->stride_h > dout->stride_h ? q->stride_h : dout->stride_h);
+    if (head_span > (int64_t)1 << 30) return INFLLMV2_ERR_UNSUPPORTED;
     const Dims dm = make_dims(prm, batch, max_seqlen);
     const size_t need = attn_bwd_ws_bytes(dm);
     if (need > 0 && (!workspace || workspace_bytes < need ||

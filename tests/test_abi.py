@@ -209,6 +209,10 @@ def test_backward_validation(lib):
     assert call(lse=None) == INVALID and call(idx=None) == INVALID and call(dq=None) == INVALID
     assert call(w=None, wb=0) == WORKSPACE and call(wb=need - 1) == WORKSPACE and call(w=FAKE + 16) == WORKSPACE
     assert lib.infllmv2_sparse_attn_bwd(P, T, T, T, T, T, FAKE, FAKE, 0, 4096, FAKE, T, T, T, FAKE, 1 << 40, None) == 0
+    far = tensor()                                                                      # heads of a group too far apart
+    far.stride_h = 1 << 28
+    assert lib.infllmv2_sparse_attn_bwd(P, ctypes.byref(far), T, T, T, T, FAKE, FAKE, 1, 4096, FAKE, T, T, T, FAKE, 1 << 40,
+                                        None) == UNSUPPORTED
 
 
 def test_decode_step_validation(lib):
